@@ -1,0 +1,227 @@
+"""TEST INFRASTRUCTURE -- slow float64 CPU oracle for forward + BPTT on a generalized RNN graph.
+
+This file is the checker, not the product: only tests, the smoke entry and the
+benchmark's CPU-baseline leg may import it.  It shares no code with the HIP path.
+
+It is the plain definition written out, frame by frame (no SCC analysis, no batching
+over frames, no reordering): the paper's Section 2.1 forward equations and Section 2.2
+training equations, evaluated for N independent streams at once (Section 3.2 says the
+multi-stream mode equals N independent copies with gradients summed), each stream
+being one row of an [N x dim] matrix.
+
+Readings where the paper is silent (all listed in the design notes of the repository):
+  * optional bias per additive node, added to the state s_k (a full edge from a constant-1
+    input would be the same thing inside the paper's model);
+  * a third weight kind "diagonal" besides "full" and "identity" (needed for peepholes);
+  * y_k = f_k(s_k) is applied to multiplicative nodes too (Section 2.2's delta equation
+    uses f_k' for any layer);
+  * activations before the window (frame index <= 0) are zero; error terms from frames
+    after the window are zero (truncation at the window edges, Section 2.2);
+  * E_total = sum over frames, streams and output nodes of -ln y_target (natural log,
+    no averaging); a target of -1 masks the frame;
+  * the functions return dE_total/dW (the paper's nabla W = -sum eps y^T with
+    eps = -dE/dz is exactly that).
+
+Parity pins (tests/, `-m "not gpu"`): a separately written textbook peephole LSTM and
+Elman net with hand-derived full BPTT, central finite differences of E_total,
+stream-independence, delay-line, unreachable-node and relabelling invariants.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+INPUT, ADD, MUL = 0, 1, 2
+LINEAR, SIGMOID, TANH, SOFTMAX = 0, 1, 2, 3
+FULL, DIAG, IDENTITY = 0, 1, 2
+
+
+def delay0_topological_order(nodes, edges):
+    """Any topological order of the graph restricted to its delay-0 edges (Section 3.1
+    requires that what remains after setting the delayed connections aside is a DAG).
+    Kahn's algorithm, smallest node id first.  Raises if a delay-0 cycle exists."""
+    K = len(nodes)
+    indeg = [0] * K
+    succ = [[] for _ in range(K)]
+    for e in edges:
+        if e["delay"] == 0:
+            indeg[e["dst"]] += 1
+            succ[e["src"]].append(e["dst"])
+    ready = sorted(k for k in range(K) if indeg[k] == 0)
+    order = []
+    while ready:
+        k = ready.pop(0)
+        order.append(k)
+        for v in succ[k]:
+            indeg[v] -= 1
+            if indeg[v] == 0:
+                ready.append(v)
+        ready.sort()
+    if len(order) != K:
+        raise ValueError("delay-0 edges form a cycle")
+    return order
+
+
+def _apply_weight(e, w, y):
+    """z = W y for one connection (Section 2.1, first equation); rows of y are streams."""
+    if e["wkind"] == FULL:
+        return y @ w.T
+    if e["wkind"] == DIAG:
+        return y * w
+    return y
+
+
+def _apply_weight_transposed(e, w, eps):
+    """W^T eps for one connection (matrix form of the delta equation, Section 2.2)."""
+    if e["wkind"] == FULL:
+        return eps @ w
+    if e["wkind"] == DIAG:
+        return eps * w
+    return eps
+
+
+def _activation(act, s):
+    if act == LINEAR:
+        return s
+    if act == SIGMOID:
+        return 1.0 / (1.0 + np.exp(-s))
+    if act == TANH:
+        return np.tanh(s)
+    if act == SOFTMAX:
+        m = s.max(axis=-1, keepdims=True)
+        ex = np.exp(s - m)
+        return ex / ex.sum(axis=-1, keepdims=True)
+    raise ValueError(act)
+
+
+def _activation_derivative(act, y):
+    if act == LINEAR:
+        return np.ones_like(y)
+    if act == SIGMOID:
+        return y * (1.0 - y)
+    if act == TANH:
+        return 1.0 - y * y
+    raise ValueError(act)
+
+
+def forward(nodes, edges, weights, biases, inputs, T, N):
+    """Forward pass over frames 1..T (stored at index 0..T-1).
+
+    weights[m]: float array [n_dst, n_src] (full), [dim] (diagonal) or None (identity).
+    biases[k]:  float array [dim] or None.   inputs[k]: [T, N, dim] for every input node.
+    Returns (y, z): y[k] is [T, N, dim] for every node; z[m] is [T, N, dim] for every edge
+    (the connection outputs, which the multiplicative layers' backward pass needs)."""
+    W = [None if w is None else np.asarray(w, dtype=np.float64) for w in weights]
+    B = [None if b is None else np.asarray(b, dtype=np.float64) for b in biases]
+    order = delay0_topological_order(nodes, edges)
+    anterior = [[] for _ in nodes]
+    for m, e in enumerate(edges):
+        anterior[e["dst"]].append(m)
+    y = [np.zeros((T, N, n["dim"])) for n in nodes]
+    z = [np.zeros((T, N, nodes[e["dst"]]["dim"])) for e in edges]
+    for k, n in enumerate(nodes):
+        if n["kind"] == INPUT:
+            y[k][:] = np.asarray(inputs[k], dtype=np.float64)
+    for t in range(T):
+        for k in order:
+            n = nodes[k]
+            if n["kind"] == INPUT:
+                continue
+            for m in anterior[k]:
+                e = edges[m]
+                tau = t - e["delay"]
+                if tau >= 0:
+                    z[m][t] = _apply_weight(e, W[m], y[e["src"]][tau])
+                # else: the source activation before the window is zero, so z stays zero
+            if n["kind"] == ADD:
+                s = np.zeros((N, n["dim"]))
+                for m in anterior[k]:
+                    s = s + z[m][t]
+                if B[k] is not None:
+                    s = s + B[k]
+            else:
+                s = np.ones((N, n["dim"]))
+                for m in anterior[k]:
+                    s = s * z[m][t]
+            y[k][t] = _activation(n["act"], s)
+    return y, z
+
+
+def loss(nodes, y, targets):
+    """E_total: cross-entropy summed over frames, streams and output nodes."""
+    total = 0.0
+    for k, n in enumerate(nodes):
+        if not n["is_output"]:
+            continue
+        tg = np.asarray(targets[k])
+        T, N = tg.shape
+        for t in range(T):
+            for s in range(N):
+                c = int(tg[t, s])
+                if c >= 0:
+                    total -= np.log(y[k][t, s, c])
+    return float(total)
+
+
+def bptt(nodes, edges, weights, biases, y, z, targets, T, N):
+    """Backward pass over frames T..1 in reverse delay-0 topological order.
+
+    Works in the paper's variables: delta_k(t) = -dE/ds_k(t), eps_m(t) = -dE/dz_m(t);
+    output nodes start from delta = d - y (softmax with cross-entropy).  Returns
+    (grad_w, grad_b, delta): grad_w[m] = -sum_t eps_m(t) y_src(t - d_m)^T summed over
+    streams (None for identity edges), grad_b[k] = -sum_t delta_k(t), and delta[k] as
+    [T, N, dim] for every non-input node."""
+    W = [None if w is None else np.asarray(w, dtype=np.float64) for w in weights]
+    order = delay0_topological_order(nodes, edges)
+    anterior = [[] for _ in nodes]
+    for m, e in enumerate(edges):
+        anterior[e["dst"]].append(m)
+    acc = [np.zeros((T, N, n["dim"])) for n in nodes]       # sum_n W_n^T eps_n(t + d_n)
+    delta = [np.zeros((T, N, n["dim"])) for n in nodes]
+    grad_w = [None if w is None else np.zeros_like(w) for w in W]
+    grad_b = [None if b is None else np.zeros(nodes[k]["dim"]) for k, b in enumerate(biases)]
+    for t in range(T - 1, -1, -1):
+        for k in reversed(order):
+            n = nodes[k]
+            if n["kind"] == INPUT:
+                continue
+            if n["is_output"]:
+                d = np.zeros((N, n["dim"]))
+                tg = np.asarray(targets[k])[t]
+                for s in range(N):
+                    c = int(tg[s])
+                    if c >= 0:
+                        d[s, c] = 1.0
+                        d[s] -= y[k][t, s]
+                delta[k][t] = d
+            else:
+                delta[k][t] = acc[k][t] * _activation_derivative(n["act"], y[k][t])
+            if grad_b[k] is not None:
+                grad_b[k] -= delta[k][t].sum(axis=0)
+            for m in anterior[k]:
+                e = edges[m]
+                if n["kind"] == ADD:
+                    eps = delta[k][t]
+                else:
+                    eps = delta[k][t].copy()
+                    for other in anterior[k]:
+                        if other != m:
+                            eps = eps * z[other][t]
+                tau = t - e["delay"]
+                if tau < 0:
+                    continue            # source frame lies before the window
+                ysrc = y[e["src"]][tau]
+                if e["wkind"] == FULL:
+                    grad_w[m] -= eps.T @ ysrc
+                elif e["wkind"] == DIAG:
+                    grad_w[m] -= (eps * ysrc).sum(axis=0)
+                if nodes[e["src"]]["kind"] != INPUT:
+                    acc[e["src"]][tau] += _apply_weight_transposed(e, W[m], eps)
+    return grad_w, grad_b, delta
+
+
+def forward_bptt(nodes, edges, weights, biases, inputs, targets, T, N):
+    """Convenience wrapper: one window of forward + BPTT.  Returns a dict."""
+    y, z = forward(nodes, edges, weights, biases, inputs, T, N)
+    E = loss(nodes, y, targets)
+    grad_w, grad_b, delta = bptt(nodes, edges, weights, biases, y, z, targets, T, N)
+    return dict(y=y, z=z, loss=E, grad_w=grad_w, grad_b=grad_b, delta=delta)

@@ -1,0 +1,296 @@
+"""Pins for the float64 graph oracle (CPU only).
+
+The paper prints no worked numerical example, so the oracle is pinned to what the paper and
+the mathematics fix: exact equivalence to textbook LSTM / Elman BPTT (Sections 1, 2, 4),
+delta / epsilon / nabla W being derivatives of E_total (Section 2.2) checked by central finite
+differences, and structural invariants (stream independence of Section 3.2, delay indexing
+of the first equation of Section 2.1, unreachable nodes, relabelling)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import graph_oracle as go
+from tests import textbook_nets as tb
+
+
+def run_oracle(w):
+    return go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+
+
+def find_edge(spec, src, dst, delay=None, wkind=None):
+    s, d = spec.node_by_name(src), spec.node_by_name(dst)
+    hits = [m for m, e in enumerate(spec.edges) if e["src"] == s and e["dst"] == d
+            and (delay is None or e["delay"] == delay) and (wkind is None or e["wkind"] == wkind)]
+    assert len(hits) == 1, (src, dst, hits)
+    return hits[0]
+
+
+def lstm_layer_params(w, tag, below, use_h=True):
+    """Pick the textbook parameter set of one LSTM layer out of the per-edge weight list."""
+    sp = w.spec
+    p = {}
+    for name, node in (("i", "i"), ("f", "f"), ("g", "g"), ("o", "o")):
+        p["Wx" + name] = w.weights[find_edge(sp, below, f"{tag}.{node}", 0)]
+        H = p["Wx" + name].shape[0]
+        p["Wh" + name] = w.weights[find_edge(sp, f"{tag}.h", f"{tag}.{node}", 1)] if use_h else np.zeros((H, H))
+        p["b" + name] = w.biases[sp.node_by_name(f"{tag}.{node}")]
+    p["wci"] = w.weights[find_edge(sp, f"{tag}.c", f"{tag}.i", 1)]
+    p["wcf"] = w.weights[find_edge(sp, f"{tag}.c", f"{tag}.f", 1)]
+    p["wco"] = w.weights[find_edge(sp, f"{tag}.c", f"{tag}.o", 0)]
+    return p
+
+
+def lstm_layer_edges(sp, tag, below, use_h=True):
+    """(textbook name -> edge index / node index) for the gradient comparison."""
+    em, bm = {}, {}
+    for name in "ifgo":
+        em["Wx" + name] = find_edge(sp, below, f"{tag}.{name}", 0)
+        if use_h:
+            em["Wh" + name] = find_edge(sp, f"{tag}.h", f"{tag}.{name}", 1)
+        bm["b" + name] = sp.node_by_name(f"{tag}.{name}")
+    em["wci"] = find_edge(sp, f"{tag}.c", f"{tag}.i", 1)
+    em["wcf"] = find_edge(sp, f"{tag}.c", f"{tag}.f", 1)
+    em["wco"] = find_edge(sp, f"{tag}.c", f"{tag}.o", 0)
+    return em, bm
+
+
+def relerr(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    den = np.abs(b).max()
+    return np.abs(a - b).max() / (den if den > 0 else 1.0)
+
+
+@pytest.mark.parametrize("hidden,use_h", [([6], True), ([5, 7], True), ([6], False), ([4, 3], False)])
+def test_textbook_peephole_lstm_equivalence(hidden, use_h):
+    """P1: the graph oracle on the Fig. 1 construction == textbook peephole LSTM with full BPTT."""
+    T, N = 9, 3
+    spec = wl.lstm_net(4, hidden, 5, output_recurrence=use_h)
+    w = wl.make_workload("lstm", spec, T, N, seed=11, scale=0.7, bias_scale=0.5, masked_fraction=0.2)
+    r = run_oracle(w)
+    (x,) = spec.input_nodes(); (out,) = spec.output_nodes()
+    tags = [f"L{l + 1}" for l in range(len(hidden))]
+    below = ["x"] + [f"{t}.h" for t in tags[:-1]]
+    params = [lstm_layer_params(w, t, b, use_h) for t, b in zip(tags, below)]
+    e_out = find_edge(spec, f"{tags[-1]}.h", "out")
+    tot_loss = 0.0
+    G_layers = [None] * len(hidden); GWy = 0.0; Gby = 0.0
+    for n in range(N):
+        loss, probs, grads, dWy, dby, hs = tb.lstm_stack_loss_and_grads(
+            params, w.weights[e_out], w.biases[out], w.inputs[x][:, n], w.targets[out][:, n], use_h)
+        tot_loss += loss
+        assert relerr(r["y"][out][:, n], probs) < 1e-12
+        for l, t in enumerate(tags):
+            assert relerr(r["y"][spec.node_by_name(f"{t}.h")][:, n], hs[l]) < 1e-12
+        for l in range(len(hidden)):
+            G_layers[l] = grads[l] if G_layers[l] is None else {k: G_layers[l][k] + grads[l][k] for k in grads[l]}
+        GWy = GWy + dWy; Gby = Gby + dby
+    assert abs(r["loss"] - tot_loss) < 1e-10 * max(1.0, abs(tot_loss))
+    assert relerr(r["grad_w"][e_out], GWy) < 1e-11
+    assert relerr(r["grad_b"][out], Gby) < 1e-11
+    for l, (t, b) in enumerate(zip(tags, below)):
+        em, bm = lstm_layer_edges(spec, t, b, use_h)
+        for name, m in em.items():
+            assert relerr(r["grad_w"][m], G_layers[l][name]) < 1e-10, (t, name)
+        for name, k in bm.items():
+            assert relerr(r["grad_b"][k], G_layers[l][name]) < 1e-10, (t, name)
+
+
+def test_textbook_elman_equivalence():
+    """P2: a singleton with a delay-1 full self-loop == textbook Elman net."""
+    T, N = 12, 2
+    spec = wl.elman_net(5, 7, 4)
+    w = wl.make_workload("elman", spec, T, N, seed=5, scale=0.6, bias_scale=0.4, masked_fraction=0.15)
+    r = run_oracle(w)
+    x, h, out = 0, 1, 2
+    tot = 0.0; G = None
+    for n in range(N):
+        loss, probs, g, hh = tb.elman_loss_and_grads(w.weights[0], w.weights[1], w.biases[h], w.weights[2],
+                                                     w.biases[out], w.inputs[x][:, n], w.targets[out][:, n])
+        tot += loss
+        assert relerr(r["y"][out][:, n], probs) < 1e-12
+        assert relerr(r["y"][h][:, n], hh) < 1e-12
+        G = g if G is None else {k: G[k] + g[k] for k in g}
+    assert abs(r["loss"] - tot) < 1e-11 * max(1.0, abs(tot))
+    for m, name in ((0, "Wx"), (1, "Wh"), (2, "Wy")):
+        assert relerr(r["grad_w"][m], G[name]) < 1e-11
+    assert relerr(r["grad_b"][h], G["bh"]) < 1e-11
+    assert relerr(r["grad_b"][out], G["by"]) < 1e-11
+
+
+def total_loss(w, weights, biases):
+    y, _ = go.forward(w.spec.nodes, w.spec.edges, weights, biases, w.inputs, w.T, w.N)
+    return go.loss(w.spec.nodes, y, w.targets)
+
+
+def check_finite_differences(w, n_probe=6, h=1e-5, tol=2e-6, seed=0):
+    r = run_oracle(w)
+    rng = np.random.default_rng(seed)
+    W64 = [None if a is None else a.astype(np.float64) for a in w.weights]
+    B64 = [None if a is None else a.astype(np.float64) for a in w.biases]
+    worst = 0.0
+    for group, grads, store in (("w", r["grad_w"], W64), ("b", r["grad_b"], B64)):
+        for idx, g in enumerate(grads):
+            if g is None:
+                continue
+            flat = store[idx].reshape(-1)
+            for j in rng.choice(flat.size, size=min(n_probe, flat.size), replace=False):
+                old = flat[j]
+                flat[j] = old + h; ep = total_loss(w, W64, B64)
+                flat[j] = old - h; em = total_loss(w, W64, B64)
+                flat[j] = old
+                fd = (ep - em) / (2 * h)
+                an = g.reshape(-1)[j]
+                err = abs(fd - an) / max(1e-3, abs(fd), abs(an))
+                worst = max(worst, err)
+                assert err < tol, (group, idx, j, fd, an)
+    return worst
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_finite_differences_random_graphs(seed):
+    """P3: every gradient formula (incl. the multiplicative-layer epsilon and window edges)."""
+    rng = np.random.default_rng(100 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3)
+    w = wl.make_workload("rand", spec, T=6, N=2, seed=seed, scale=0.8, bias_scale=0.5,
+                         masked_fraction=0.2 if seed % 2 else 0.0)
+    check_finite_differences(w, n_probe=4, seed=seed)
+
+
+def test_finite_differences_generalized_lstm():
+    """P3 on the generalized net (delay-2 edge, sigmoid-gated multiplicative inter-layer node)."""
+    spec = wl.generalized_net(3, 4, 2, 3)
+    w = wl.make_workload("gen", spec, T=6, N=2, seed=3, scale=0.8, bias_scale=0.5)
+    check_finite_differences(w, n_probe=3)
+
+
+def test_unreachable_node_has_zero_gradient():
+    """P4: a node with no path to any output receives no error; its in-edges get exactly 0."""
+    spec = wl.lstm_net(3, [4], 3)
+    dead = spec.add_node(wl.ADD, wl.TANH, 4, has_bias=True, name="dead")
+    e1 = spec.add_edge(spec.node_by_name("L1.h"), dead, wl.FULL, 0)
+    e2 = spec.add_edge(dead, dead, wl.FULL, 1)
+    e3 = spec.add_edge(spec.node_by_name("L1.c"), dead, wl.DIAG, 2)
+    w = wl.make_workload("dead", spec, T=7, N=2, seed=1)
+    r = run_oracle(w)
+    for m in (e1, e2, e3):
+        assert np.all(r["grad_w"][m] == 0.0)
+    assert np.all(r["grad_b"][dead] == 0.0)
+    assert np.abs(r["y"][dead]).max() > 0          # it does compute something forward
+    assert np.abs(r["grad_w"][0]).max() > 0         # the live part has gradients
+
+
+def test_stream_independence():
+    """P5: N streams == N independent single-stream runs, gradients summed (Section 3.2)."""
+    spec = wl.generalized_net(3, 4, 2, 3)
+    w = wl.make_workload("gen", spec, T=5, N=3, seed=9)
+    r = run_oracle(w)
+    gsum = None; lsum = 0.0
+    for n in range(w.N):
+        one = wl.Workload("one", spec, w.T, 1, w.weights, w.biases,
+                          {k: v[:, n:n + 1] for k, v in w.inputs.items()},
+                          {k: v[:, n:n + 1] for k, v in w.targets.items()})
+        r1 = run_oracle(one)
+        lsum += r1["loss"]
+        for k in range(len(spec.nodes)):
+            assert np.array_equal(r1["y"][k][:, 0], r["y"][k][:, n]) or relerr(r1["y"][k][:, 0], r["y"][k][:, n]) < 1e-14
+        g = [None if a is None else a.copy() for a in r1["grad_w"]]
+        gsum = g if gsum is None else [None if a is None else a + b for a, b in zip(gsum, g)]
+    assert abs(lsum - r["loss"]) < 1e-11 * abs(lsum)
+    for a, b in zip(gsum, r["grad_w"]):
+        if a is not None:
+            assert relerr(b, a) < 1e-11
+
+
+@pytest.mark.parametrize("d", [0, 1, 3])
+def test_pure_delay_line(d):
+    """P6: input -> identity edge with delay d -> linear node gives y(t) = x(t - d), zero before."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 3, name="x")
+    v = g.add_node(wl.ADD, wl.LINEAR, 3, name="v")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 3, has_bias=True, is_output=True, name="out")
+    g.add_edge(x, v, wl.IDENTITY, d)
+    g.add_edge(v, out, wl.FULL, 0)
+    w = wl.make_workload("dl", g, T=8, N=2, seed=2)
+    r = run_oracle(w)
+    exp = np.zeros((8, 2, 3))
+    exp[d:] = w.inputs[x][:8 - d]
+    assert np.array_equal(r["y"][v], exp)
+
+
+def test_feed_forward_graph_is_per_frame_mlp():
+    """P7: with no delayed edges every frame is an independent MLP evaluation."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 4, name="x")
+    a = g.add_node(wl.ADD, wl.TANH, 6, has_bias=True, name="a")
+    b = g.add_node(wl.ADD, wl.SIGMOID, 6, has_bias=True, name="b")
+    m = g.add_node(wl.MUL, wl.LINEAR, 6, name="m")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 3, has_bias=True, is_output=True, name="out")
+    ea = g.add_edge(x, a, wl.FULL); eb = g.add_edge(x, b, wl.FULL)
+    g.add_edge(a, m, wl.IDENTITY); ed = g.add_edge(b, m, wl.DIAG)
+    eo = g.add_edge(m, out, wl.FULL)
+    w = wl.make_workload("ff", g, T=5, N=2, seed=4)
+    r = run_oracle(w)
+    W = [None if q is None else q.astype(np.float64) for q in w.weights]
+    X = w.inputs[x].astype(np.float64)
+    A = np.tanh(X @ W[ea].T + w.biases[a]); Bv = 1 / (1 + np.exp(-(X @ W[eb].T + w.biases[b])))
+    M = A * (Bv * W[ed])
+    L = M @ W[eo].T + w.biases[out]
+    P = np.exp(L - L.max(-1, keepdims=True)); P /= P.sum(-1, keepdims=True)
+    assert relerr(r["y"][out], P) < 1e-13
+    # gradient of the output layer in closed form
+    D = P.copy()
+    tg = w.targets[out]
+    for t in range(5):
+        for n in range(2):
+            D[t, n, tg[t, n]] -= 1
+    assert relerr(r["grad_w"][eo], np.einsum("tni,tnj->ij", D, M)) < 1e-12
+    assert relerr(r["grad_b"][out], D.sum((0, 1))) < 1e-12
+
+
+def test_relabelling_invariance():
+    """P8: permuting node and edge ids permutes outputs and gradients accordingly."""
+    rng = np.random.default_rng(77)
+    spec = wl.generalized_net(3, 4, 2, 3)
+    w = wl.make_workload("gen", spec, T=5, N=2, seed=8)
+    r = run_oracle(w)
+    K, M = len(spec.nodes), len(spec.edges)
+    np_, ep = rng.permutation(K), rng.permutation(M)
+    spec2 = spec.permuted(np_, ep)
+    w2 = wl.Workload("perm", spec2, w.T, w.N,
+                     [w.weights[int(np.argsort(ep)[m])] for m in range(M)],
+                     [w.biases[int(np.argsort(np_)[k])] for k in range(K)],
+                     {int(np_[k]): v for k, v in w.inputs.items()},
+                     {int(np_[k]): v for k, v in w.targets.items()})
+    r2 = run_oracle(w2)
+    assert abs(r2["loss"] - r["loss"]) < 1e-12 * abs(r["loss"])
+    for k in range(K):
+        assert relerr(r2["y"][int(np_[k])], r["y"][k]) < 1e-13
+    for m in range(M):
+        if r["grad_w"][m] is not None:
+            assert relerr(r2["grad_w"][int(ep[m])], r["grad_w"][m]) < 1e-11
+
+
+def test_delta_is_negative_state_gradient():
+    """Section 2.2 defines delta_k(t) = -dE_total/ds_k(t): perturbing the bias of an additive
+    node shifts s_k at every frame, so -sum_t delta_k(t) must equal the bias gradient, and the
+    softmax output delta must be d - y."""
+    spec = wl.lstm_net(3, [4], 3)
+    w = wl.make_workload("l", spec, T=6, N=2, seed=6)
+    r = run_oracle(w)
+    (out,) = spec.output_nodes()
+    onehot = np.zeros_like(r["y"][out])
+    for t in range(w.T):
+        for n in range(w.N):
+            onehot[t, n, w.targets[out][t, n]] = 1
+    assert np.allclose(r["delta"][out], onehot - r["y"][out], atol=1e-15)
+    for k, nd in enumerate(spec.nodes):
+        if nd["has_bias"]:
+            assert relerr(r["grad_b"][k], -r["delta"][k].sum((0, 1))) < 1e-13
+
+
+def test_delay0_cycle_is_rejected():
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 2); a = g.add_node(wl.ADD, wl.TANH, 2); b = g.add_node(wl.ADD, wl.TANH, 2)
+    g.add_edge(x, a, wl.FULL); g.add_edge(a, b, wl.FULL); g.add_edge(b, a, wl.FULL, 0)
+    with pytest.raises(ValueError):
+        go.delay0_topological_order(g.nodes, g.edges)
