@@ -1,0 +1,145 @@
+/*
+ * rnngraph -- forward pass and backpropagation through time for generalized LSTM-like RNN
+ * graphs (Hwang & Sung, "Single Stream Parallelization of Generalized LSTM-Like RNNs on a
+ * GPU") on one AMD MI355X (gfx950).
+ *
+ * A network is a directed graph (paper Section 2.1): a node is a layer, an edge is a
+ * connection m with a weight W_m and a delay d_m >= 0 that carries the source layer's
+ * activation of frame t - d_m to the destination layer at frame t.  The library analyses the
+ * graph (Section 3.1: strongly connected components become sequentially stepped "recurrent
+ * nodes", everything else is worked on for all frames of the window at once) and runs the
+ * forward pass and BPTT (Section 2.2) for N weight-sharing streams (Section 3.2).
+ *
+ * Conventions
+ *  - Every function returns 0 on success or a negative rnn_status; rnn_last_error() gives a
+ *    thread-local message.  Nothing throws across this boundary.
+ *  - "d_" pointers are DEVICE pointers owned by the caller (weights, inputs, targets,
+ *    workspace, gradients).  All other pointers are HOST pointers.  The library owns only
+ *    host-side plan memory inside rnn_graph.
+ *  - Calls that take a stream are asynchronous on that HIP stream (hipStream_t passed as
+ *    void*; NULL = the default stream).
+ *  - Frames x streams x units tensors are time-major row-major: element (t, n, i) of a node of
+ *    width dim lives at ((t * N + n) * dim + i), t in [0, T), n in [0, N).
+ *  - Activations before the window are zero; error terms from frames after the window are zero.
+ *  - All arithmetic is fp32.  Gradients are dE_total/dW, summed (not averaged) over frames
+ *    and streams, E_total = sum over frames, streams and output nodes of -ln y_target.
+ */
+#ifndef RNNGRAPH_H
+#define RNNGRAPH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rnn_graph rnn_graph; /* opaque */
+
+enum rnn_status {
+    RNN_OK = 0,
+    RNN_ERR_INVALID_ARGUMENT = -1, /* NULL pointer, bad size, bad index */
+    RNN_ERR_INVALID_GRAPH = -2,    /* the node / edge list violates a rule listed at rnn_graph_create */
+    RNN_ERR_WORKSPACE = -3,        /* workspace NULL, misaligned or too small */
+    RNN_ERR_SEQUENCE = -4,         /* rnn_bptt before rnn_forward, rnn_grads before rnn_bptt */
+    RNN_ERR_DEVICE = -5,           /* a HIP call failed or a kernel reported a step-barrier time-out */
+    RNN_ERR_NO_MEMORY = -6
+};
+
+/* Node (layer) kinds: Section 2.1 defines additive layers (sum of the incoming connection
+ * outputs, then an activation function) and multiplicative layers (element-wise product). */
+enum { RNN_NODE_INPUT = 0, RNN_NODE_ADD = 1, RNN_NODE_MUL = 2 };
+/* Activation functions f_k; softmax is allowed on output nodes only and is paired with the
+ * cross-entropy criterion, the one case for which Section 2.2 gives the output delta. */
+enum { RNN_ACT_LINEAR = 0, RNN_ACT_SIGMOID = 1, RNN_ACT_TANH = 2, RNN_ACT_SOFTMAX = 3 };
+/* Weight kinds: full matrix [n_dst x n_src] (row-major, z = W y), diagonal (a vector, used for
+ * peepholes) and identity (no parameters), cf. the Fig. 1 caption. */
+enum { RNN_W_FULL = 0, RNN_W_DIAG = 1, RNN_W_IDENTITY = 2 };
+/* Edge classes of the intra-stream schedule (Section 3.1). */
+enum { RNN_EDGE_BATCHED = 0, RNN_EDGE_STEP_DELAYED = 1, RNN_EDGE_STEP_DELAY0 = 2 };
+
+typedef struct { int32_t kind, act, dim, has_bias, is_output; } rnn_node_desc;
+typedef struct { int32_t src, dst, delay, wkind; } rnn_edge_desc;
+
+/* Builds the schedule for a graph given as a node list and an edge list (Section 2.1).
+ * HOST arrays, copied.  *out receives a handle to be released with rnn_graph_destroy.
+ * RNN_ERR_INVALID_GRAPH if: a node id is out of range; dim <= 0; an unknown kind / act / wkind;
+ * an identity or diagonal edge joins nodes of different width; delay < 0; an edge enters an
+ * input node; a non-input node has no incoming edge; an input node has a bias, an activation or
+ * is an output; softmax on a non-output node or an output node that is not additive-softmax;
+ * an output node with outgoing edges; has_bias on a multiplicative node; there is no output
+ * node; or the delay-0 edges contain a cycle (Section 3.1 needs the per-step remainder to be a
+ * DAG). */
+int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes,
+                     const rnn_edge_desc* edges, int32_t n_edges, rnn_graph** out);
+void rnn_graph_destroy(rnn_graph* g);
+
+/* The intra-stream schedule of Section 3.1 in canonical form (HOST int32 arrays supplied by
+ * the caller; the first four have n_nodes entries, edge_class has n_edges; any may be NULL):
+ *   node_comp[v]      index of v's strongly connected component; components are numbered by
+ *                     increasing (comp_level, smallest node id in the component)
+ *   node_level[v]     level of v inside one time step of its recurrent node: 0 if v has no
+ *                     delay-0 in-edge from its own component, else 1 + max over those sources;
+ *                     0 for nodes outside recurrent components
+ *   comp_level[v]     longest-path level of v's component in the condensation DAG
+ *   comp_recurrent[v] 1 if v's component is a recurrent node (more than one node, or a self-loop)
+ *   edge_class[m]     RNN_EDGE_BATCHED (source and destination in different components: worked
+ *                     on for all frames at once), RNN_EDGE_STEP_DELAYED (same component,
+ *                     delay >= 1: computed first in each step), RNN_EDGE_STEP_DELAY0 (same
+ *                     component, delay 0: part of the per-step DAG)
+ *   *n_comps          number of components */
+int rnn_graph_schedule(const rnn_graph* g, int32_t* node_comp, int32_t* node_level,
+                       int32_t* comp_level, int32_t* comp_recurrent, int32_t* edge_class,
+                       int32_t* n_comps);
+
+/* Flat parameter layout shared by the weight and the gradient buffer.  rnn_param_count is the
+ * buffer length in floats (it includes alignment padding between blocks; padding entries are
+ * never read and receive zero gradient).  A full edge occupies len = n_dst * n_src floats at
+ * off, row-major [n_dst][n_src]; a diagonal edge len = dim; an identity edge len = 0; a bias
+ * len = dim (0 if the node has none). */
+int64_t rnn_param_count(const rnn_graph* g);
+int rnn_edge_param_offset(const rnn_graph* g, int32_t edge, int64_t* off, int64_t* len);
+int rnn_bias_param_offset(const rnn_graph* g, int32_t node, int64_t* off, int64_t* len);
+
+/* Bytes of DEVICE workspace needed for a window of T frames and N streams (activations and
+ * error terms of every node for every frame, the plan tables and step-barrier words).
+ * Negative rnn_status on error. */
+int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N);
+
+/* Forward pass over one window (Section 2.1 equations on the Section 3.1 schedule).
+ *   d_weights  DEVICE, rnn_param_count floats.
+ *   d_inputs   HOST array with one DEVICE pointer per input node, in increasing node id, each
+ *              a [T][N][dim] float tensor.  The tensors are read in place by rnn_forward,
+ *              rnn_bptt and rnn_grads and must stay unchanged until rnn_grads has completed.
+ *   d_workspace DEVICE, 256-byte aligned, at least rnn_workspace_bytes(g, T, N); it holds the
+ *              window's state between rnn_forward, rnn_bptt and rnn_grads.
+ * One graph handle serves one window at a time. */
+int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs,
+                int32_t T, int32_t N, void* d_workspace, int64_t ws_bytes, void* hip_stream);
+
+/* DEVICE view of node's activations y [T][N][dim] inside the workspace of the last rnn_forward
+ * (for an input node: the caller's own input tensor). */
+int rnn_output(const rnn_graph* g, int32_t node, const float** d_y);
+
+/* Backward pass (Section 2.2: output delta from softmax + cross-entropy, delta and epsilon
+ * back-propagated through the reversed schedule) for the window of the last rnn_forward.
+ *   d_targets  HOST array with one DEVICE pointer per output node, in increasing node id, each
+ *              an int32 [T][N] tensor of class indices; -1 means "no error at this frame".
+ * d_weights must hold the same values as in rnn_forward. */
+int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targets, void* hip_stream);
+
+/* DEVICE view of dE_total/ds_k [T][N][dim] (the paper's -delta_k) after rnn_bptt; not defined
+ * for input nodes. */
+int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds);
+
+/* Weight gradients (last equation of Section 2.2, summed over the N streams as in Section 3.2).
+ *   d_grads  DEVICE, rnn_param_count floats, overwritten with dE_total/dW in the parameter layout.
+ *   loss     HOST double or NULL; if given the call synchronises the stream and stores E_total. */
+int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream);
+
+/* Message for the last error on this thread (never NULL). */
+const char* rnn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNNGRAPH_H */

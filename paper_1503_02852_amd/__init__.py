@@ -1,0 +1,2 @@
+"""MI355X-native forward + BPTT for generalized LSTM-like RNN graphs (C-ABI library + binding)."""
+from .binding import Graph, RnnError, load_library, LIB_PATH, EXPORTS  # noqa: F401

@@ -1,0 +1,362 @@
+// C-ABI boundary (declared in include/rnngraph.h) and the executor that walks the plan.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/rnngraph.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace rnng;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string& msg) { g_last_error = msg; return code; }
+int fail_hip(hipError_t e, const char* what) {
+    return fail(RNN_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    int64_t table_off = 0, dims_off = 0, words_off = 0, blob_bytes = 0;
+    int64_t sync_off = 0;                 // 1 KiB of zero-initialised control words; the loss (double) sits at its start
+    std::vector<int64_t> buf_off;         // per buffer id, bytes; -1 = not in the workspace
+    int64_t total = 0;
+};
+constexpr int64_t SYNC_BYTES = 1024;
+
+Layout make_layout(const Plan& P, int T, int N) {
+    Layout L;
+    const int K = (int)P.xnodes.size();
+    int64_t cur = 0;
+    L.table_off = cur; cur += (int64_t)P.n_bufs * 8;
+    L.dims_off = cur; cur += (int64_t)P.n_bufs * 4;
+    cur = align_up(cur, 16);
+    L.words_off = cur; cur += (int64_t)P.words.size() * 4;
+    L.blob_bytes = cur;
+    cur = align_up(cur, 256);
+    L.sync_off = cur; cur += SYNC_BYTES;
+    L.buf_off.assign(P.n_bufs, -1);
+    const int64_t F = (int64_t)T * N;
+    for (int k = 0; k < K; ++k) {
+        if (P.xnodes[k].kind == NODE_INPUT) continue;
+        const int64_t dim = P.xnodes[k].dim;
+        L.buf_off[P.ybuf(k)] = cur; cur = align_up(cur + F * dim * 4, 256);
+        L.buf_off[P.dbuf(k)] = cur; cur = align_up(cur + F * dim * 4, 256);
+        L.buf_off[P.abuf(k)] = cur; cur = align_up(cur + (int64_t)N * dim * 4, 256);
+    }
+    L.total = cur;
+    return L;
+}
+
+}  // namespace
+
+struct rnn_graph {
+    Plan plan;
+    // state of the current window
+    int T = 0, N = 0;
+    char* ws = nullptr;
+    Layout layout;
+    std::vector<char> blob;               // host copy of the plan tables (kept alive for the async upload)
+    std::vector<const float*> inputs;     // per exec node id (input nodes only)
+    const float* weights = nullptr;
+    bool fwd_done = false, bptt_done = false;
+    PlanView view() const {
+        PlanView pv;
+        pv.buf_ptr = reinterpret_cast<float* const*>(ws + layout.table_off);
+        pv.buf_dim = reinterpret_cast<const int32_t*>(ws + layout.dims_off);
+        pv.words = reinterpret_cast<const int32_t*>(ws + layout.words_off);
+        return pv;
+    }
+    float* buf(int id) const {
+        if (layout.buf_off[id] >= 0) return reinterpret_cast<float*>(ws + layout.buf_off[id]);
+        if (id < (int)inputs.size() && inputs[id]) return const_cast<float*>(inputs[id]);
+        return nullptr;
+    }
+    double* loss_ptr() const { return reinterpret_cast<double*>(ws + layout.sync_off); }
+};
+
+namespace {
+
+// Launches the GEMM problems of one component and direction, grouped by up to
+// GEMM_MAX_PROBLEMS destinations per launch and GEMM_MAX_PAIRS products per destination.
+hipError_t run_gemms(const rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bool backward, hipStream_t s) {
+    const int64_t F = (int64_t)g->T * g->N;
+    size_t max_pairs = 0;
+    for (const auto& p : probs) max_pairs = p.pairs.size() > max_pairs ? p.pairs.size() : max_pairs;
+    for (size_t round = 0; round * GEMM_MAX_PAIRS < max_pairs; ++round) {
+        GemmGroup grp; std::memset(&grp, 0, sizeof(grp));
+        grp.split_k = 1; grp.accumulate = round > 0;
+        auto flush = [&]() -> hipError_t {
+            if (grp.n_problems == 0) return hipSuccess;
+            hipError_t e = launch_gemm_group(backward ? GEMM_NN : GEMM_NT, grp, s);
+            grp.n_problems = 0;
+            return e;
+        };
+        for (const auto& pp : probs) {
+            if (pp.pairs.size() <= round * GEMM_MAX_PAIRS) continue;
+            GemmProblem& gp = grp.p[grp.n_problems];
+            gp.C = g->buf(pp.c_buf); gp.ldc = pp.n; gp.M = (int)F; gp.N = pp.n; gp.n_pairs = 0;
+            for (size_t q = round * GEMM_MAX_PAIRS; q < pp.pairs.size() && gp.n_pairs < GEMM_MAX_PAIRS; ++q) {
+                const GemmPairPlan& pr = pp.pairs[q];
+                GemmPair& o = gp.pairs[gp.n_pairs++];
+                o.A = g->buf(pr.a_buf); o.B = g->weights + pr.b_w_off; o.K = pr.k_len; o.lda = pr.k_len;
+                o.ldb = backward ? pp.n : pr.k_len;
+                o.a_row_off = (backward ? pr.delay : -pr.delay) * g->N; o.a_rows = (int)F;
+            }
+            if (++grp.n_problems == GEMM_MAX_PROBLEMS) { hipError_t e = flush(); if (e != hipSuccess) return e; }
+        }
+        hipError_t e = flush();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t run_phases(const rnn_graph* g, const CompPlan& cp, bool backward, hipStream_t s) {
+    const PlanView pv = g->view();
+    const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
+    const int T = g->T, N = g->N;
+    if (!cp.recurrent) {
+        for (const PhasePlan& ph : phases) {
+            hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, 0, T, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    for (int step = 0; step < T; ++step) {
+        const int t = backward ? T - 1 - step : step;
+        for (const PhasePlan& ph : phases) {
+            if (ph.mv_off >= 0) {
+                hipError_t e = launch_step_matvec(pv, ph.mv_off, ph.n_mv_tasks, ph.mv_max_out, g->weights, T, N, t, s);
+                if (e != hipSuccess) return e;
+            }
+            hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, t, t + 1, s);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rnn_last_error(void) { return g_last_error.c_str(); }
+
+int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge_desc* edges, int32_t n_edges,
+                     rnn_graph** out) {
+    if (!out) return fail(RNN_ERR_INVALID_ARGUMENT, "out is NULL");
+    *out = nullptr;
+    if (!nodes || n_nodes <= 0 || n_edges < 0 || (n_edges > 0 && !edges))
+        return fail(RNN_ERR_INVALID_ARGUMENT, "node / edge list missing");
+    std::vector<GNode> ns(n_nodes); std::vector<GEdge> es(n_edges);
+    for (int i = 0; i < n_nodes; ++i) ns[i] = GNode{nodes[i].kind, nodes[i].act, nodes[i].dim, nodes[i].has_bias != 0, nodes[i].is_output != 0};
+    for (int i = 0; i < n_edges; ++i) es[i] = GEdge{edges[i].src, edges[i].dst, edges[i].delay, edges[i].wkind};
+    rnn_graph* g = new (std::nothrow) rnn_graph();
+    if (!g) return fail(RNN_ERR_NO_MEMORY, "out of host memory");
+    std::string err;
+    if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
+    *out = g;
+    return RNN_OK;
+}
+
+void rnn_graph_destroy(rnn_graph* g) { delete g; }
+
+int rnn_graph_schedule(const rnn_graph* g, int32_t* node_comp, int32_t* node_level, int32_t* comp_level,
+                       int32_t* comp_recurrent, int32_t* edge_class, int32_t* n_comps) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    const Schedule& S = g->plan.sched;
+    const int K = (int)g->plan.nodes.size(), M = (int)g->plan.edges.size();
+    for (int v = 0; v < K; ++v) {
+        if (node_comp) node_comp[v] = S.node_comp[v];
+        if (node_level) node_level[v] = S.node_level[v];
+        if (comp_level) comp_level[v] = S.comp_level[S.node_comp[v]];
+        if (comp_recurrent) comp_recurrent[v] = S.comp_recurrent[S.node_comp[v]];
+    }
+    if (edge_class) for (int m = 0; m < M; ++m) edge_class[m] = S.edge_class[m];
+    if (n_comps) *n_comps = S.n_comps;
+    return RNN_OK;
+}
+
+int64_t rnn_param_count(const rnn_graph* g) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    return g->plan.n_params;
+}
+
+int rnn_edge_param_offset(const rnn_graph* g, int32_t edge, int64_t* off, int64_t* len) {
+    if (!g || !off || !len) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (edge < 0 || edge >= (int)g->plan.edges.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "edge index out of range");
+    *off = g->plan.edge_off[edge]; *len = g->plan.edge_len[edge];
+    return RNN_OK;
+}
+
+int rnn_bias_param_offset(const rnn_graph* g, int32_t node, int64_t* off, int64_t* len) {
+    if (!g || !off || !len) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (node < 0 || node >= (int)g->plan.nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "node index out of range");
+    *off = g->plan.bias_off[node]; *len = g->plan.bias_len[node];
+    return RNN_OK;
+}
+
+int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
+    if ((int64_t)T * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
+    return make_layout(g->plan, T, N).total;
+}
+
+int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs, int32_t T, int32_t N,
+                void* d_workspace, int64_t ws_bytes, void* hip_stream) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    g->fwd_done = g->bptt_done = false;
+    if (!d_weights || !d_inputs) return fail(RNN_ERR_INVALID_ARGUMENT, "weights / inputs pointer is NULL");
+    if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
+    if ((int64_t)T * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
+    const Plan& P = g->plan;
+    for (size_t i = 0; i < P.input_nodes.size(); ++i)
+        if (!d_inputs[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
+    Layout L = make_layout(P, T, N);
+    if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (ws_bytes < L.total) return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(L.total) + " bytes");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    g->T = T; g->N = N; g->ws = static_cast<char*>(d_workspace); g->layout = L; g->weights = d_weights;
+    g->inputs.assign(P.xnodes.size(), nullptr);
+    for (size_t i = 0; i < P.input_nodes.size(); ++i) g->inputs[P.input_nodes[i]] = d_inputs[i];
+
+    // plan tables: buffer pointers, widths, program words
+    g->blob.assign(L.blob_bytes, 0);
+    for (int b = 0; b < P.n_bufs; ++b) {
+        float* p = g->buf(b);
+        std::memcpy(&g->blob[L.table_off + 8 * (int64_t)b], &p, 8);
+    }
+    std::memcpy(&g->blob[L.dims_off], P.buf_dim.data(), (size_t)P.n_bufs * 4);
+    if (!P.words.empty()) std::memcpy(&g->blob[L.words_off], P.words.data(), P.words.size() * 4);
+    hipError_t e = hipMemcpyAsync(g->ws, g->blob.data(), (size_t)L.blob_bytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return fail_hip(e, "plan table upload");
+    e = launch_fill(reinterpret_cast<float*>(g->ws + L.sync_off), SYNC_BYTES / 4, 0.0f, s);
+    if (e != hipSuccess) return fail_hip(e, "control word reset");
+
+    for (const CompPlan& cp : P.comps) {
+        if (!cp.has_fwd_program) continue;
+        e = run_gemms(g, cp.fwd_gemms, false, s);
+        if (e != hipSuccess) return fail_hip(e, "forward GEMM");
+        e = run_phases(g, cp, false, s);
+        if (e != hipSuccess) return fail_hip(e, "forward node program");
+        if (cp.softmax_node >= 0) {
+            e = launch_softmax_rows(g->buf(P.ybuf(cp.softmax_node)), (int64_t)T * N, P.xnodes[cp.softmax_node].dim, s);
+            if (e != hipSuccess) return fail_hip(e, "softmax");
+        }
+    }
+    g->fwd_done = true;
+    return RNN_OK;
+}
+
+int rnn_output(const rnn_graph* g, int32_t node, const float** d_y) {
+    if (!g || !d_y) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (node < 0 || node >= (int)g->plan.nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "node index out of range");
+    if (!g->fwd_done) return fail(RNN_ERR_SEQUENCE, "rnn_output before rnn_forward");
+    *d_y = g->buf(g->plan.ybuf(node));
+    return RNN_OK;
+}
+
+int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targets, void* hip_stream) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (!g->fwd_done) return fail(RNN_ERR_SEQUENCE, "rnn_bptt before rnn_forward");
+    g->bptt_done = false;
+    if (!d_weights || !d_targets) return fail(RNN_ERR_INVALID_ARGUMENT, "weights / targets pointer is NULL");
+    const Plan& P = g->plan;
+    for (size_t i = 0; i < P.output_nodes.size(); ++i)
+        if (!d_targets[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "a target tensor pointer is NULL");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    g->weights = d_weights;
+    const int T = g->T, N = g->N;
+    hipError_t e = launch_fill(reinterpret_cast<float*>(g->loss_ptr()), 2, 0.0f, s);
+    if (e != hipSuccess) return fail_hip(e, "loss reset");
+    for (int c = (int)P.comps.size() - 1; c >= 0; --c) {
+        const CompPlan& cp = P.comps[c];
+        if (cp.softmax_node >= 0) {
+            const int k = cp.softmax_node;
+            size_t oi = 0;
+            while (oi < P.output_nodes.size() && P.output_nodes[oi] != k) ++oi;
+            e = launch_softmax_ce_delta(g->buf(P.ybuf(k)), d_targets[oi], g->buf(P.dbuf(k)), g->loss_ptr(),
+                                        (int64_t)T * N, P.xnodes[k].dim, s);
+            if (e != hipSuccess) return fail_hip(e, "softmax / cross-entropy delta");
+            continue;
+        }
+        if (!cp.has_bwd_program) continue;
+        e = run_gemms(g, cp.bwd_gemms, true, s);
+        if (e != hipSuccess) return fail_hip(e, "backward GEMM");
+        e = run_phases(g, cp, true, s);
+        if (e != hipSuccess) return fail_hip(e, "backward node program");
+    }
+    g->bptt_done = true;
+    return RNN_OK;
+}
+
+int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds) {
+    if (!g || !d_ds) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (node < 0 || node >= (int)g->plan.nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "node index out of range");
+    if (g->plan.nodes[node].kind == NODE_INPUT) return fail(RNN_ERR_INVALID_ARGUMENT, "input nodes have no state gradient");
+    if (!g->bptt_done) return fail(RNN_ERR_SEQUENCE, "rnn_state_grad before rnn_bptt");
+    *d_ds = g->buf(g->plan.dbuf(node));
+    return RNN_OK;
+}
+
+int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (!g->bptt_done) return fail(RNN_ERR_SEQUENCE, "rnn_grads before rnn_bptt");
+    if (!d_grads) return fail(RNN_ERR_INVALID_ARGUMENT, "gradient pointer is NULL");
+    const Plan& P = g->plan;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int T = g->T, N = g->N;
+    const int64_t F = (int64_t)T * N;
+    hipError_t e = launch_fill(d_grads, P.n_params, 0.0f, s);
+    if (e != hipSuccess) return fail_hip(e, "gradient reset");
+
+    // Weight-gradient GEMMs: the contraction runs over frames, split over blockIdx.z.
+    GemmGroup grp; std::memset(&grp, 0, sizeof(grp));
+    int64_t tiles = 0;
+    auto flush = [&]() -> hipError_t {
+        if (grp.n_problems == 0) return hipSuccess;
+        int split = (int)((1024 + tiles - 1) / tiles);
+        const int max_split = (int)((F + 127) / 128);
+        if (split > max_split) split = max_split;
+        if (split < 1) split = 1;
+        // split_k > 1 adds atomically into the zeroed buffer; split_k == 1 must add too (accumulate)
+        grp.split_k = split; grp.accumulate = 1;
+        hipError_t r = launch_gemm_group(GEMM_TN, grp, s);
+        grp.n_problems = 0; tiles = 0;
+        return r;
+    };
+    for (const GradGemmPlan& gg : P.grad_gemms) {
+        const int64_t Kf = F - (int64_t)gg.delay * N;
+        if (Kf <= 0) continue;
+        GemmProblem& gp = grp.p[grp.n_problems];
+        gp.C = d_grads + gg.w_off; gp.ldc = gg.n_src; gp.M = gg.n_dst; gp.N = gg.n_src; gp.n_pairs = 1;
+        GemmPair& o = gp.pairs[0];
+        o.A = g->buf(gg.dst_buf) + (int64_t)gg.delay * N * gg.n_dst; o.lda = gg.n_dst;
+        o.B = g->buf(gg.src_buf); o.ldb = gg.n_src; o.K = (int)Kf; o.a_row_off = 0; o.a_rows = (int)Kf;
+        tiles += (int64_t)((gg.n_dst + 127) / 128) * ((gg.n_src + 127) / 128);
+        if (++grp.n_problems == GEMM_MAX_PROBLEMS) { e = flush(); if (e != hipSuccess) return fail_hip(e, "gradient GEMM"); }
+    }
+    e = flush();
+    if (e != hipSuccess) return fail_hip(e, "gradient GEMM");
+    e = launch_colsum(g->view(), P.colsum_off, P.n_colsum, P.colsum_max_dim, g->weights, d_grads, T, N, s);
+    if (e != hipSuccess) return fail_hip(e, "diagonal / bias gradient");
+    if (loss) {
+        e = hipMemcpyAsync(loss, g->loss_ptr(), sizeof(double), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return fail_hip(e, "loss read-back");
+    }
+    return RNN_OK;
+}
+
+}  // extern "C"

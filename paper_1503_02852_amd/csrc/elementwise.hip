@@ -1,0 +1,181 @@
+// Element-wise kernels: node programs over many frames (additive / multiplicative layers,
+// activation functions and their derivatives: paper Section 2.1 and the delta / epsilon
+// equations of Section 2.2), row softmax with the cross-entropy output delta (Section 2.2),
+// column sums for diagonal-weight and bias gradients, and fills.
+#include "interp.h"
+#include "kernels.h"
+
+namespace rnng {
+namespace {
+
+__global__ __launch_bounds__(256) void node_program_kernel(PlanView pv, int prog_off, int max_dim,
+                                                           const float* __restrict__ weights,
+                                                           int T, int N, int t0, long long total) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % max_dim);
+    const long long row = idx / max_dim;
+    const int t = t0 + (int)(row / N), n = (int)(row % N);
+    run_node_program(pv, pv.words + prog_off, weights, T, N, t, n, i);
+}
+
+// One wavefront per output unit u of a task; all streams n in a loop.
+__global__ __launch_bounds__(256) void step_matvec_kernel(PlanView pv, int mv_off, const float* __restrict__ weights,
+                                                          int T, int N, int t) {
+    const int32_t* w = pv.words + mv_off + 1;
+    for (int task = 0; task < (int)blockIdx.y; ++task) w += MV_HEADER_WORDS + w[MV_NEDGES] * MVE_WORDS;
+    const int n_out = w[MV_NOUT], n_edges = w[MV_NEDGES];
+    const int lane = threadIdx.x & 63;
+    const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (u >= n_out) return;
+    float* acc = pv.buf_ptr[w[MV_ACC_BUF]];
+    for (int n = 0; n < N; ++n) {
+        float s = 0.0f;
+        for (int e = 0; e < n_edges; ++e) {
+            const int32_t* ed = w + MV_HEADER_WORDS + e * MVE_WORDS;
+            const int frame = t + ed[MVE_FRAME_OFF];
+            if (frame < 0 || frame >= T) continue;
+            const int K = ed[MVE_KLEN];
+            const float* W = weights + ed[MVE_W_OFF];
+            const float* x = pv.buf_ptr[ed[MVE_SRC_BUF]] + ((size_t)frame * N + n) * K;
+            if (ed[MVE_TRANSPOSED]) { for (int k = lane; k < K; k += 64) s += W[(size_t)k * n_out + u] * x[k]; }
+            else { for (int k = lane; k < K; k += 64) s += W[(size_t)u * K + k] * x[k]; }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) acc[(size_t)n * n_out + u] = s;
+    }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// One wavefront per row, in place.
+__global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ y, long long rows, int dim) {
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int lane = threadIdx.x & 63;
+    float* p = y + row * dim;
+    float m = -INFINITY;
+    for (int i = lane; i < dim; i += 64) m = fmaxf(m, p[i]);
+    m = wave_max(m);
+    float s = 0.0f;
+    for (int i = lane; i < dim; i += 64) s += __expf(p[i] - m);
+    s = wave_sum(s);
+    const float inv = 1.0f / s;
+    for (int i = lane; i < dim; i += 64) p[i] = __expf(p[i] - m) * inv;
+}
+
+__global__ __launch_bounds__(256) void softmax_ce_delta_kernel(const float* __restrict__ y, const int32_t* __restrict__ targets,
+                                                               float* __restrict__ ds, double* loss, long long rows, int dim) {
+    __shared__ float wl[4];
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float l = 0.0f;
+    if (row < rows) {
+        const int tg = targets[row];
+        const float* p = y + row * dim;
+        float* d = ds + row * dim;
+        for (int i = lane; i < dim; i += 64) d[i] = tg >= 0 ? p[i] - (i == tg ? 1.0f : 0.0f) : 0.0f;
+        if (tg >= 0 && lane == 0) l = -__logf(p[tg]);
+    }
+    if (lane == 0) wl[wave] = l;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double s = (double)wl[0] + (double)wl[1] + (double)wl[2] + (double)wl[3];
+        if (s != 0.0) atomicAdd(loss, s);
+    }
+}
+
+// grid: (ceil(dim / 64), n_tasks, row splits); block (64, 4).
+__global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off, const float* __restrict__ weights,
+                                                     float* __restrict__ grads, int T, int N) {
+    __shared__ float part[4][64];
+    const int32_t* w = pv.words + tasks_off;
+    for (int task = 0; task < (int)blockIdx.y; ++task) w += CS_HEADER_WORDS + w[CS_NFACTORS] * FACTOR_WORDS;
+    const int dim = w[CS_DIM], nf = w[CS_NFACTORS];
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    const long long rows = (long long)T * N;
+    float s = 0.0f;
+    if (i < dim) {
+        for (long long r = (long long)blockIdx.z * 4 + threadIdx.y; r < rows; r += 4LL * gridDim.z) {
+            const int t = (int)(r / N), n = (int)(r % N);
+            float prod = 1.0f;
+            for (int j = 0; j < nf; ++j)
+                prod *= factor_value(pv, w + CS_HEADER_WORDS + j * FACTOR_WORDS, weights, nullptr, T, N, t, n, i);
+            s += prod;
+        }
+    }
+    part[threadIdx.y][threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.y == 0 && i < dim) {
+        const float tot = part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x];
+        unsafeAtomicAdd(&grads[w[CS_OUT_OFF] + i], tot);
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, long long n, float v) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += 256LL * gridDim.x) p[i] = v;
+}
+
+}  // namespace
+
+hipError_t launch_node_program(const PlanView& pv, int prog_off, int max_dim, const float* weights,
+                               int T, int N, int t0, int t1, hipStream_t stream) {
+    const long long total = (long long)(t1 - t0) * N * max_dim;
+    if (total <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(node_program_kernel, dim3(blocks), dim3(256), 0, stream, pv, prog_off, max_dim, weights, T, N, t0, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_step_matvec(const PlanView& pv, int mv_off, int n_tasks, int max_out, const float* weights,
+                              int T, int N, int t, hipStream_t stream) {
+    if (n_tasks <= 0 || max_out <= 0) return hipSuccess;
+    hipLaunchKernelGGL(step_matvec_kernel, dim3((max_out + 3) / 4, n_tasks), dim3(256), 0, stream, pv, mv_off, weights, T, N, t);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_rows(float* y, int64_t rows, int dim, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(softmax_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, y, (long long)rows, dim);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss,
+                                   int64_t rows, int dim, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(softmax_ce_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, y, targets, ds, loss,
+                       (long long)rows, dim);
+    return hipGetLastError();
+}
+
+hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
+                         int T, int N, hipStream_t stream) {
+    if (n_tasks <= 0 || max_dim <= 0) return hipSuccess;
+    const long long rows = (long long)T * N;
+    int splits = (int)((rows + 63) / 64);
+    if (splits > 128) splits = 128;
+    if (splits < 1) splits = 1;
+    hipLaunchKernelGGL(colsum_kernel, dim3((max_dim + 63) / 64, n_tasks, splits), dim3(64, 4), 0, stream, pv, tasks_off,
+                       weights, grads, T, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    long long blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, (long long)n, v);
+    return hipGetLastError();
+}
+
+}  // namespace rnng

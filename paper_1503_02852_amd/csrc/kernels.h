@@ -1,0 +1,59 @@
+// Launch wrappers of the HIP kernels (implemented in the .hip files).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "program.h"
+
+namespace rnng {
+
+// ---------------------------------------------------------------------------------------
+// Grouped fp32 MFMA GEMM:  C[M][N] (+)= sum over pairs  A_p(M x K_p) * B_p(K_p x N)
+// ---------------------------------------------------------------------------------------
+constexpr int GEMM_MAX_PAIRS = 4;
+constexpr int GEMM_MAX_PROBLEMS = 8;
+
+struct GemmPair {
+    const float* A;   // K-contiguous modes: element (m, k) at A[(m + a_row_off) * lda + k], zero if the
+                      // shifted row falls outside [0, a_rows);  M-contiguous mode: element (m, k) at A[k * lda + m]
+    const float* B;   // K-contiguous mode: element (k, n) at B[n * ldb + k];  N-contiguous: B[k * ldb + n]
+    int K, lda, ldb, a_row_off, a_rows;
+};
+struct GemmProblem {
+    float* C; int ldc, M, N, n_pairs;
+    GemmPair pairs[GEMM_MAX_PAIRS];
+};
+struct GemmGroup {
+    GemmProblem p[GEMM_MAX_PROBLEMS];
+    int n_problems;
+    int split_k;      // >1: K is split over blockIdx.z and results are added atomically (C must be pre-zeroed)
+    int accumulate;   // 1: C += result instead of C = result (ignored when split_k > 1)
+};
+enum GemmMode {
+    GEMM_NT = 0,   // A K-contiguous, B K-contiguous      (forward:  Y_dst = Y_src W^T)
+    GEMM_NN = 1,   // A K-contiguous, B N-contiguous      (backward: dY_src = dS_dst W)
+    GEMM_TN = 2    // A M-contiguous, B N-contiguous      (gradient: G = dS_dst^T Y_src)
+};
+hipError_t launch_gemm_group(GemmMode mode, const GemmGroup& g, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------
+// Element-wise node programs, step matrix-vector products, softmax, reductions
+// ---------------------------------------------------------------------------------------
+// Runs a node program for frames [t0, t1) and all streams.
+hipError_t launch_node_program(const PlanView& pv, int prog_off, int max_dim, const float* weights,
+                               int T, int N, int t0, int t1, hipStream_t stream);
+// Matrix-vector task list for frame t (per-step launch).
+hipError_t launch_step_matvec(const PlanView& pv, int mv_off, int n_tasks, int max_out, const float* weights,
+                              int T, int N, int t, hipStream_t stream);
+// In-place row softmax over `rows` rows of width dim.
+hipError_t launch_softmax_rows(float* y, int64_t rows, int dim, hipStream_t stream);
+// ds = y - onehot(target) (0 where target < 0); *loss += sum of -ln y[target].
+hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss,
+                                   int64_t rows, int dim, hipStream_t stream);
+// Column-sum tasks (diagonal-weight and bias gradients), atomically added into grads.
+hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
+                         int T, int N, hipStream_t stream);
+hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream);
+
+}  // namespace rnng

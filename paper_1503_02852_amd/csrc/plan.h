@@ -1,0 +1,75 @@
+// Execution plan built once per graph by the host planner.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "graph.h"
+#include "program.h"
+
+namespace rnng {
+
+// One A*B product that contributes to a GEMM destination.
+struct GemmPairPlan {
+    int a_buf;          // buffer id of A ([frames][k] tensor)
+    int b_buf;          // buffer id of B, or -1 if B is a weight block
+    int64_t b_w_off;    // weight offset of B (if b_buf < 0)
+    int k_len;          // contraction length (units); for weight-gradient GEMMs: unused (frames)
+    int delay;          // frame shift between the destination rows and A's rows
+};
+
+// Forward: C = y_dst [frames][n] = sum_p y_src_p(t - d_p) W_p^T.
+// Backward: C = dE/dy_src [frames][n] = sum_p ds_dst_p(t + d_p) W_p.
+struct GemmProblemPlan {
+    int c_buf;
+    int n;              // columns of C
+    std::vector<GemmPairPlan> pairs;
+};
+
+// Weight gradient of one full edge: G[n_dst][n_src] = sum_t ds_dst(t)^T y_src(t - d).
+struct GradGemmPlan {
+    int64_t w_off; int n_dst, n_src, dst_buf, src_buf, delay;
+};
+
+struct PhasePlan {
+    int mv_off = -1;     // word offset of the matrix-vector task list (-1: none)
+    int prog_off = -1;   // word offset of the node program
+    int max_dim = 0;
+    int mv_max_out = 0;  // largest n_out over the tasks
+    int n_mv_tasks = 0;
+};
+
+struct CompPlan {
+    bool recurrent = false;
+    int softmax_node = -1;                  // exec node id if this component is a softmax output node
+    std::vector<GemmProblemPlan> fwd_gemms, bwd_gemms;
+    std::vector<PhasePlan> fwd_phases, bwd_phases;   // bwd_phases already in execution order
+    bool has_fwd_program = false, has_bwd_program = false;
+};
+
+struct Plan {
+    // original graph and its canonical schedule (what rnn_graph_schedule exports)
+    std::vector<GNode> nodes; std::vector<GEdge> edges; Schedule sched;
+    // execution graph: full edges into multiplicative nodes are routed through a synthetic
+    // linear additive node, so that every full edge ends in an additive node
+    std::vector<GNode> xnodes; std::vector<GEdge> xedges; std::vector<int> xedge_param; Schedule xsched;
+    // parameter layout (original indexing)
+    std::vector<int64_t> edge_off, edge_len, bias_off, bias_len; int64_t n_params = 0;
+    // buffers: y of exec node k -> k; ds of k -> K + k; accumulator of k -> 2K + k
+    int n_bufs = 0;
+    std::vector<int> buf_dim;
+    std::vector<CompPlan> comps;
+    std::vector<GradGemmPlan> grad_gemms;
+    int colsum_off = -1, n_colsum = 0, colsum_max_dim = 0;
+    std::vector<int32_t> words;             // all programs
+    std::vector<int> input_nodes, output_nodes;   // original ids, increasing
+
+    int ybuf(int k) const { return k; }
+    int dbuf(int k) const { return (int)xnodes.size() + k; }
+    int abuf(int k) const { return 2 * (int)xnodes.size() + k; }
+};
+
+// Returns false and a reason on an invalid graph.
+bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges, Plan& plan, std::string& err);
+
+}  // namespace rnng

@@ -1,0 +1,93 @@
+"""Device-memory plumbing around the binding: torch tensors hold weights, inputs, targets,
+workspace and gradients; every computation happens inside librnngraph.so."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from .binding import Graph
+
+
+class Window:
+    """One graph + one window shape (T, N) with all device buffers allocated."""
+
+    def __init__(self, node_array, edge_array, T, N, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("rnngraph needs a GPU: there is no CPU path")
+        self.g = Graph(node_array, edge_array)
+        self.T, self.N = T, N
+        self.dev = torch.device(device)
+        self.ws_bytes = self.g.workspace_bytes(T, N)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.dev)
+        self.ws_ptr = (self.ws.data_ptr() + 255) // 256 * 256
+        self.n_params = self.g.param_count()
+        self.weights = torch.zeros(self.n_params, dtype=torch.float32, device=self.dev)
+        self.grads = torch.empty(self.n_params, dtype=torch.float32, device=self.dev)
+        self.inputs = {}
+        self.targets = {}
+
+    def set_params(self, weights, biases):
+        self.weights.copy_(torch.from_numpy(self.g.pack_params(weights, biases)))
+
+    def set_inputs(self, inputs):
+        for k in self.g.input_nodes:
+            a = np.ascontiguousarray(inputs[k], dtype=np.float32)
+            assert a.shape == (self.T, self.N, int(self.g.nodes[k, 2])), a.shape
+            self.inputs[k] = torch.from_numpy(a).to(self.dev)
+
+    def set_targets(self, targets):
+        for k in self.g.output_nodes:
+            a = np.ascontiguousarray(targets[k], dtype=np.int32)
+            assert a.shape == (self.T, self.N)
+            self.targets[k] = torch.from_numpy(a).to(self.dev)
+
+    def _stream(self):
+        return torch.cuda.current_stream(self.dev).cuda_stream
+
+    def forward(self):
+        self.g.forward(self.weights.data_ptr(), [self.inputs[k].data_ptr() for k in self.g.input_nodes],
+                       self.T, self.N, self.ws_ptr, self.ws_bytes, self._stream())
+
+    def bptt(self):
+        self.g.bptt(self.weights.data_ptr(), [self.targets[k].data_ptr() for k in self.g.output_nodes], self._stream())
+
+    def compute_grads(self, want_loss=False):
+        return self.g.grads(self.grads.data_ptr(), want_loss, self._stream())
+
+    def step(self):
+        """One pass of the whole hot path: forward, BPTT, weight gradients (asynchronous)."""
+        self.forward()
+        self.bptt()
+        self.compute_grads(False)
+
+    # ---- read-back helpers for tests ---------------------------------------------------
+    def _view(self, ptr, dim):
+        n = self.T * self.N * dim
+        if ptr >= self.ws.data_ptr() and ptr < self.ws.data_ptr() + self.ws.numel():
+            off = ptr - self.ws.data_ptr()
+            return self.ws[off:off + 4 * n].view(torch.float32).view(self.T, self.N, dim)
+        raise ValueError("pointer outside the workspace")
+
+    def node_output(self, k):
+        dim = int(self.g.nodes[k, 2])
+        if k in self.inputs:
+            return self.inputs[k].cpu().numpy()
+        torch.cuda.synchronize(self.dev)
+        return self._view(self.g.output_ptr(k), dim).cpu().numpy()
+
+    def node_state_grad(self, k):
+        dim = int(self.g.nodes[k, 2])
+        torch.cuda.synchronize(self.dev)
+        return self._view(self.g.state_grad_ptr(k), dim).cpu().numpy()
+
+    def grads_unpacked(self):
+        torch.cuda.synchronize(self.dev)
+        return self.g.unpack_params(self.grads.cpu().numpy())
+
+
+def window_for(workload, device="cuda:0"):
+    w = Window(workload.spec.node_array(), workload.spec.edge_array(), workload.T, workload.N, device)
+    w.set_params(workload.weights, workload.biases)
+    w.set_inputs(workload.inputs)
+    w.set_targets(workload.targets)
+    return w

@@ -1,0 +1,148 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 oracle, element by element,
+on the same seeded inputs.  Bars: outputs / activations within 1e-4, gradients (state gradients
+and weight gradients) within 1e-3, normwise per tensor: max|gpu - oracle| / max|oracle|; the loss
+within 1e-5 relative.  Schedule parity (bit-exact) is a CPU test in test_abi_host.py."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import graph_oracle as go
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL, GRAD_TOL = 1e-4, 1e-3
+
+
+def nerr(a, b):
+    a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
+    den = np.abs(b).max()
+    return np.abs(a - b).max() / den if den > 0 else np.abs(a).max()
+
+
+def run_both(w, check_all_nodes=True, label=""):
+    from paper_1503_02852_amd.runner import window_for
+    print(f"[parity] {label or w.name}: T={w.T} N={w.N} nodes={len(w.spec.nodes)} params={w.n_params()}", flush=True)
+    win = window_for(w)
+    win.forward()
+    win.bptt()
+    loss = win.compute_grads(want_loss=True)
+    ref = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+    worst_y = worst_d = worst_g = 0.0
+    nodes = range(len(w.spec.nodes)) if check_all_nodes else w.spec.output_nodes()
+    for k in nodes:
+        if w.spec.nodes[k]["kind"] == wl.INPUT:
+            continue
+        e = nerr(win.node_output(k), ref["y"][k])
+        worst_y = max(worst_y, e)
+        assert e < OUT_TOL, (label, "y", w.spec.nodes[k]["name"], e)
+        # library returns dE/ds = -delta
+        e = nerr(win.node_state_grad(k), -ref["delta"][k])
+        worst_d = max(worst_d, e)
+        assert e < GRAD_TOL, (label, "ds", w.spec.nodes[k]["name"], e)
+    gw, gb = win.grads_unpacked()
+    for m, g in enumerate(ref["grad_w"]):
+        if g is None:
+            continue
+        e = nerr(gw[m], g)
+        worst_g = max(worst_g, e)
+        assert e < GRAD_TOL, (label, "grad_w", m, w.spec.edges[m], e)
+    for k, g in enumerate(ref["grad_b"]):
+        if g is None:
+            continue
+        e = nerr(gb[k], g)
+        worst_g = max(worst_g, e)
+        assert e < GRAD_TOL, (label, "grad_b", w.spec.nodes[k]["name"], e)
+    assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"])), (label, loss, ref["loss"])
+    print(f"[parity] {label or w.name}: worst y {worst_y:.2e}  ds {worst_d:.2e}  grad {worst_g:.2e}  loss {loss:.6f}", flush=True)
+    return win, ref
+
+
+def test_tiny_config():
+    run_both(wl.make_config("tiny"))
+
+
+def test_tiny_config_with_biases_and_masked_targets():
+    spec = wl.lstm_net(8, [16], 4)
+    run_both(wl.make_workload("tiny_masked", spec, 20, 3, seed=1, scale=0.5, bias_scale=0.3, masked_fraction=0.3))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_graphs(seed):
+    rng = np.random.default_rng(100 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, n_inputs=1 + seed % 2)
+    run_both(wl.make_workload(f"rand{seed}", spec, T=7 + seed, N=1 + seed % 4, seed=seed, scale=0.8, bias_scale=0.5,
+                              masked_fraction=0.2 if seed % 2 else 0.0))
+
+
+def test_elman():
+    run_both(wl.make_workload("elman", wl.elman_net(20, 150, 11), T=33, N=5, seed=2, scale=0.15))
+
+
+def test_lstm_without_output_recurrence():
+    run_both(wl.make_workload("lm_lstm", wl.lstm_net(12, [70], 9, output_recurrence=False), T=40, N=3, seed=3, scale=0.3))
+
+
+def test_delay0_full_edge_inside_recurrent_node():
+    """A recurrent node whose per-step DAG contains a full (not element-wise) edge: h -> p (full,
+    delay 0), p -> h (full, delay 1) -- needs a second phase inside every step."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 6, name="x")
+    h = g.add_node(wl.ADD, wl.TANH, 40, has_bias=True, name="h")
+    p = g.add_node(wl.ADD, wl.SIGMOID, 17, has_bias=True, name="p")
+    m = g.add_node(wl.MUL, wl.LINEAR, 17, name="m")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 5, has_bias=True, is_output=True, name="out")
+    g.add_edge(x, h, wl.FULL, 0); g.add_edge(h, p, wl.FULL, 0); g.add_edge(p, h, wl.FULL, 1)
+    g.add_edge(p, m, wl.IDENTITY, 0); g.add_edge(h, m, wl.FULL, 2); g.add_edge(m, out, wl.FULL, 0)
+    g.add_edge(m, h, wl.FULL, 1)
+    run_both(wl.make_workload("two_phase", g, T=19, N=3, seed=4, scale=0.4, bias_scale=0.2))
+
+
+def test_widths_spanning_tiles_with_ragged_tails():
+    """2-layer LSTM with widths that are not multiples of the GEMM tile, the wavefront or 4."""
+    run_both(wl.make_workload("ragged", wl.lstm_net(37, [130, 67], 13), T=50, N=7, seed=5, scale=0.2, bias_scale=0.1))
+
+
+def test_generalized_small():
+    run_both(wl.make_workload("gen_small", wl.generalized_net(24, 96, 3, 10), T=24, N=5, seed=6, scale=0.15, bias_scale=0.1))
+
+
+def test_single_frame_window():
+    run_both(wl.make_workload("T1", wl.lstm_net(5, [8], 3), T=1, N=2, seed=7))
+    run_both(wl.make_workload("T2_gen", wl.generalized_net(5, 8, 2, 3), T=2, N=1, seed=8))
+
+
+def test_all_targets_masked_gives_zero_gradients():
+    from paper_1503_02852_amd.runner import window_for
+    w = wl.make_workload("masked", wl.lstm_net(5, [8], 3), T=6, N=2, seed=9, masked_fraction=1.1)
+    win = window_for(w)
+    win.forward(); win.bptt()
+    loss = win.compute_grads(want_loss=True)
+    assert loss == 0.0
+    assert float(win.grads.abs().max().item()) == 0.0
+
+
+def test_repeated_windows_reuse_the_workspace():
+    """Two different windows through one handle; the second (smaller inputs) must not see the first."""
+    from paper_1503_02852_amd.runner import window_for
+    w1 = wl.make_workload("a", wl.lstm_net(6, [20], 4), T=15, N=2, seed=10)
+    win, ref1 = run_both(w1)
+    w2 = wl.make_workload("b", w1.spec, T=15, N=2, seed=11)
+    win.set_params(w2.weights, w2.biases); win.set_inputs(w2.inputs); win.set_targets(w2.targets)
+    win.forward(); win.bptt(); loss = win.compute_grads(want_loss=True)
+    ref2 = go.forward_bptt(w2.spec.nodes, w2.spec.edges, w2.weights, w2.biases, w2.inputs, w2.targets, w2.T, w2.N)
+    gw, gb = win.grads_unpacked()
+    for m, g in enumerate(ref2["grad_w"]):
+        if g is not None:
+            assert nerr(gw[m], g) < GRAD_TOL
+    assert abs(loss - ref2["loss"]) <= 1e-5 * abs(ref2["loss"])
+
+
+@pytest.mark.parametrize("name", ["speech_n1", "charlm_n1", "charlm_n32"])
+def test_full_size_configs(name):
+    run_both(wl.make_config(name), label=name)
+
+
+def test_generalized_full_width_reduced_window():
+    """The generalized configuration at its full widths and stream count (3 x 1024, N = 64) over a
+    24-frame window, which the oracle finishes in seconds."""
+    run_both(wl.make_config("generalized_n64", T=24), check_all_nodes=True, label="generalized_n64_T24")
