@@ -136,6 +136,23 @@ int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds);
  *   loss     HOST double or NULL; if given the call synchronises the stream and stores E_total. */
 int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream);
 
+/* Kernel-class timing for benchmarks: HIP events are recorded on the call's stream around the
+ * launches of every class whose bit is set in class_mask (0 switches timing off; it is off by
+ * default and costs nothing then).  rnn_profile_read waits for the recorded events, stores the
+ * summed duration in milliseconds and the number of kernel launches of that class since the
+ * last read (HOST pointers, either may be NULL) and resets both. */
+enum {
+    RNN_PROF_STEP_FWD = 0,   /* recurrent-node forward step kernels (Section 3.1 sequential part) */
+    RNN_PROF_STEP_BWD = 1,   /* recurrent-node backward step kernels */
+    RNN_PROF_GEMM_FWD = 2,   /* batched forward edge products */
+    RNN_PROF_GEMM_BWD = 3,   /* batched backward edge products */
+    RNN_PROF_GEMM_GRAD = 4,  /* weight-gradient GEMMs */
+    RNN_PROF_OTHER = 5,      /* element-wise programs over all frames, softmax, reductions, fills */
+    RNN_PROF_CLASSES = 6
+};
+int rnn_profile_enable(rnn_graph* g, int32_t class_mask);
+int rnn_profile_read(rnn_graph* g, int32_t cls, double* ms, int64_t* launches);
+
 /* Message for the last error on this thread (never NULL). */
 const char* rnn_last_error(void);
 

@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "librnngraph.so")
 
 EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_param_count",
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
-           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_last_error"]
+           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_profile_enable", "rnn_profile_read",
+           "rnn_last_error"]
 
 _lib = None
 
@@ -61,6 +62,10 @@ def load_library(build_if_missing=True):
     lib.rnn_state_grad.restype = C.c_int
     lib.rnn_grads.argtypes = [vp, vp, C.POINTER(C.c_double), vp]
     lib.rnn_grads.restype = C.c_int
+    lib.rnn_profile_enable.argtypes = [vp, C.c_int32]
+    lib.rnn_profile_enable.restype = C.c_int
+    lib.rnn_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), i64p]
+    lib.rnn_profile_read.restype = C.c_int
     lib.rnn_last_error.argtypes = []
     lib.rnn_last_error.restype = C.c_char_p
     _lib = lib
@@ -176,6 +181,14 @@ class Graph:
         p = C.c_void_p()
         _check(self.lib.rnn_state_grad(self.handle, node, C.byref(p)))
         return p.value
+
+    def profile_enable(self, class_mask):
+        _check(self.lib.rnn_profile_enable(self.handle, class_mask))
+
+    def profile_read(self, cls):
+        ms, n = C.c_double(), C.c_int64()
+        _check(self.lib.rnn_profile_read(self.handle, cls, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def grads(self, d_grads, want_loss=False, stream=0):
         if want_loss:

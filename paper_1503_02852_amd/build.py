@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librnngraph.so")
-SOURCES = ["analyse.cpp", "plan.cpp", "api.cpp", "gemm.hip", "elementwise.hip"]
+SOURCES = ["analyse.cpp", "plan.cpp", "api.cpp", "gemm.hip", "elementwise.hip", "step.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

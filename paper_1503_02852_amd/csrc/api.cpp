@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -45,12 +46,11 @@ Layout make_layout(const Plan& P, int T, int N) {
     L.sync_off = cur; cur += SYNC_BYTES;
     L.buf_off.assign(P.n_bufs, -1);
     const int64_t F = (int64_t)T * N;
-    for (int k = 0; k < K; ++k) {
-        if (P.xnodes[k].kind == NODE_INPUT) continue;
-        const int64_t dim = P.xnodes[k].dim;
-        L.buf_off[P.ybuf(k)] = cur; cur = align_up(cur + F * dim * 4, 256);
-        L.buf_off[P.dbuf(k)] = cur; cur = align_up(cur + F * dim * 4, 256);
-        L.buf_off[P.abuf(k)] = cur; cur = align_up(cur + (int64_t)N * dim * 4, 256);
+    (void)K;
+    for (int b = 0; b < P.n_bufs; ++b) {
+        if (!P.buf_alloc[b]) continue;
+        const int64_t rows = P.buf_alloc[b] == 1 ? F : N;
+        L.buf_off[b] = cur; cur = align_up(cur + rows * P.buf_dim[b] * 4, 256);
     }
     L.total = cur;
     return L;
@@ -58,8 +58,42 @@ Layout make_layout(const Plan& P, int T, int N) {
 
 }  // namespace
 
+// Optional kernel-class timing with HIP events on the caller's stream.
+struct Profiler {
+    struct Rec { int cls; hipEvent_t a, b; int64_t launches; };
+    int mask = 0;
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+    bool on(int cls) const { return (mask >> cls) & 1; }
+    // returns the index of the open record or -1
+    int begin(int cls, hipStream_t s) {
+        if (!on(cls)) return -1;
+        Rec r{cls, get(), get(), 0};
+        if (!r.a || !r.b) return -1;
+        (void)hipEventRecord(r.a, s);
+        recs.push_back(r);
+        return (int)recs.size() - 1;
+    }
+    void end(int idx, int64_t launches, hipStream_t s) {
+        if (idx < 0) return;
+        recs[idx].launches = launches;
+        (void)hipEventRecord(recs[idx].b, s);
+    }
+    ~Profiler() {
+        for (Rec& r : recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+    }
+};
+
 struct rnn_graph {
     Plan plan;
+    Profiler prof;
     // state of the current window
     int T = 0, N = 0;
     char* ws = nullptr;
@@ -81,14 +115,19 @@ struct rnn_graph {
         return nullptr;
     }
     double* loss_ptr() const { return reinterpret_cast<double*>(ws + layout.sync_off); }
+    unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
+    int force_step_G = 0;
 };
 
 namespace {
 
 // Launches the GEMM problems of one component and direction, grouped by up to
 // GEMM_MAX_PROBLEMS destinations per launch and GEMM_MAX_PAIRS products per destination.
-hipError_t run_gemms(const rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bool backward, hipStream_t s) {
+hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bool backward, hipStream_t s) {
     const int64_t F = (int64_t)g->T * g->N;
+    if (probs.empty()) return hipSuccess;
+    const int prof = g->prof.begin(backward ? RNN_PROF_GEMM_BWD : RNN_PROF_GEMM_FWD, s);
+    int64_t n_launch = 0;
     size_t max_pairs = 0;
     for (const auto& p : probs) max_pairs = p.pairs.size() > max_pairs ? p.pairs.size() : max_pairs;
     for (size_t round = 0; round * GEMM_MAX_PAIRS < max_pairs; ++round) {
@@ -97,7 +136,7 @@ hipError_t run_gemms(const rnn_graph* g, const std::vector<GemmProblemPlan>& pro
         auto flush = [&]() -> hipError_t {
             if (grp.n_problems == 0) return hipSuccess;
             hipError_t e = launch_gemm_group(backward ? GEMM_NN : GEMM_NT, grp, s);
-            grp.n_problems = 0;
+            grp.n_problems = 0; ++n_launch;
             return e;
         };
         for (const auto& pp : probs) {
@@ -116,18 +155,36 @@ hipError_t run_gemms(const rnn_graph* g, const std::vector<GemmProblemPlan>& pro
         hipError_t e = flush();
         if (e != hipSuccess) return e;
     }
+    g->prof.end(prof, n_launch, s);
     return hipSuccess;
 }
 
-hipError_t run_phases(const rnn_graph* g, const CompPlan& cp, bool backward, hipStream_t s) {
+hipError_t run_phases(rnn_graph* g, const CompPlan& cp, bool backward, hipStream_t s) {
     const PlanView pv = g->view();
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     const int T = g->T, N = g->N;
     if (!cp.recurrent) {
+        const int prof = g->prof.begin(RNN_PROF_OTHER, s);
         for (const PhasePlan& ph : phases) {
             hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, 0, T, s);
             if (e != hipSuccess) return e;
         }
+        g->prof.end(prof, (int64_t)phases.size(), s);
+        return hipSuccess;
+    }
+    const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
+    int64_t n_launch = 0;
+    // Persistent kernel: all T steps in one launch, if the component fits its limits.
+    StepLaunchPlan lp;
+    const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
+    if (plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp)) {
+        for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) {
+            hipError_t e = launch_fill_sentinel(g->buf(b), (int64_t)T * N * g->plan.buf_dim[b], s);
+            if (e != hipSuccess) return e;
+        }
+        hipError_t e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, 1 << 22, s);
+        if (e != hipSuccess) return e;
+        g->prof.end(prof, 1, s);
         return hipSuccess;
     }
     for (int step = 0; step < T; ++step) {
@@ -136,11 +193,14 @@ hipError_t run_phases(const rnn_graph* g, const CompPlan& cp, bool backward, hip
             if (ph.mv_off >= 0) {
                 hipError_t e = launch_step_matvec(pv, ph.mv_off, ph.n_mv_tasks, ph.mv_max_out, g->weights, T, N, t, s);
                 if (e != hipSuccess) return e;
+                ++n_launch;
             }
             hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, t, t + 1, s);
             if (e != hipSuccess) return e;
+            ++n_launch;
         }
     }
+    g->prof.end(prof, n_launch, s);
     return hipSuccess;
 }
 
@@ -163,6 +223,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (!g) return fail(RNN_ERR_NO_MEMORY, "out of host memory");
     std::string err;
     if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
+    if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
     *out = g;
     return RNN_OK;
 }
@@ -323,9 +384,11 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
 
     // Weight-gradient GEMMs: the contraction runs over frames, split over blockIdx.z.
     GemmGroup grp; std::memset(&grp, 0, sizeof(grp));
-    int64_t tiles = 0;
+    int64_t tiles = 0, n_launch = 0;
+    const int prof = g->prof.begin(RNN_PROF_GEMM_GRAD, s);
     auto flush = [&]() -> hipError_t {
         if (grp.n_problems == 0) return hipSuccess;
+        ++n_launch;
         int split = (int)((1024 + tiles - 1) / tiles);
         const int max_split = (int)((F + 127) / 128);
         if (split > max_split) split = max_split;
@@ -349,13 +412,44 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
     }
     e = flush();
     if (e != hipSuccess) return fail_hip(e, "gradient GEMM");
+    g->prof.end(prof, n_launch, s);
     e = launch_colsum(g->view(), P.colsum_off, P.n_colsum, P.colsum_max_dim, g->weights, d_grads, T, N, s);
     if (e != hipSuccess) return fail_hip(e, "diagonal / bias gradient");
     if (loss) {
-        e = hipMemcpyAsync(loss, g->loss_ptr(), sizeof(double), hipMemcpyDeviceToHost, s);
+        unsigned char back[32];
+        e = hipMemcpyAsync(back, g->loss_ptr(), sizeof(back), hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) return fail_hip(e, "loss read-back");
+        std::memcpy(loss, back, sizeof(double));
+        unsigned flag; std::memcpy(&flag, back + 16, 4);
+        if (flag) return fail(RNN_ERR_DEVICE, "a recurrent step kernel ran into its wait limit (results are invalid)");
     }
+    return RNN_OK;
+}
+
+int rnn_profile_enable(rnn_graph* g, int32_t class_mask) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    g->prof.mask = class_mask & ((1 << RNN_PROF_CLASSES) - 1);
+    return RNN_OK;
+}
+
+int rnn_profile_read(rnn_graph* g, int32_t cls, double* ms, int64_t* launches) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (cls < 0 || cls >= RNN_PROF_CLASSES) return fail(RNN_ERR_INVALID_ARGUMENT, "unknown kernel class");
+    double total = 0.0; int64_t n = 0;
+    std::vector<Profiler::Rec> keep;
+    for (Profiler::Rec& r : g->prof.recs) {
+        if (r.cls != cls) { keep.push_back(r); continue; }
+        hipError_t e = hipEventSynchronize(r.b);
+        float t = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+        g->prof.pool.push_back(r.a); g->prof.pool.push_back(r.b);
+        if (e != hipSuccess) { g->prof.recs.swap(keep); return fail_hip(e, "event read"); }
+        total += t; n += r.launches;
+    }
+    g->prof.recs.swap(keep);
+    if (ms) *ms = total;
+    if (launches) *launches = n;
     return RNN_OK;
 }
 

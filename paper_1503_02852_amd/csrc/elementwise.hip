@@ -8,15 +8,24 @@
 namespace rnng {
 namespace {
 
-__global__ __launch_bounds__(256) void node_program_kernel(PlanView pv, int prog_off, int max_dim,
+// One thread per (frame, stream, unit); the accumulator entries of the program (if any) are
+// read from their one-frame buffers.
+__global__ __launch_bounds__(256)
+void node_program_kernel(PlanView pv, int prog_off, int max_dim,
                                                            const float* __restrict__ weights,
                                                            int T, int N, int t0, long long total) {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
-    const int i = (int)(idx % max_dim);
     const long long row = idx / max_dim;
+    const UnitMap um{0, 1, (int)(idx - row * max_dim)};
     const int t = t0 + (int)(row / N), n = (int)(row % N);
-    run_node_program(pv, pv.words + prog_off, weights, T, N, t, n, i);
+    const ProgramView pg(pv.words + prog_off);
+    float s[MAX_SLOTS];
+    auto acc = [&](int buf, int dim, int nn, int i, int) { return pv.buf_ptr[buf][(size_t)nn * dim + i]; };
+    load_gathers(s, pg, pv, um, T, N, t, n, acc, true);
+    load_invariants(s, pg, weights, um);
+    run_ops(s, pg);
+    run_stores(s, pg, pv, um, N, t, n, [](float* p, float v) { *p = v; });
 }
 
 // One wavefront per output unit u of a task; all streams n in a loop.
@@ -100,7 +109,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off,
                                                      float* __restrict__ grads, int T, int N) {
     __shared__ float part[4][64];
     const int32_t* w = pv.words + tasks_off;
-    for (int task = 0; task < (int)blockIdx.y; ++task) w += CS_HEADER_WORDS + w[CS_NFACTORS] * FACTOR_WORDS;
+    for (int task = 0; task < (int)blockIdx.y; ++task) w += CS_HEADER_WORDS + w[CS_NFACTORS] * CF_WORDS;
     const int dim = w[CS_DIM], nf = w[CS_NFACTORS];
     const int i = blockIdx.x * 64 + threadIdx.x;
     const long long rows = (long long)T * N;
@@ -109,8 +118,14 @@ __global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off,
         for (long long r = (long long)blockIdx.z * 4 + threadIdx.y; r < rows; r += 4LL * gridDim.z) {
             const int t = (int)(r / N), n = (int)(r % N);
             float prod = 1.0f;
-            for (int j = 0; j < nf; ++j)
-                prod *= factor_value(pv, w + CS_HEADER_WORDS + j * FACTOR_WORDS, weights, nullptr, T, N, t, n, i);
+            for (int j = 0; j < nf; ++j) {
+                const int32_t* f = w + CS_HEADER_WORDS + j * CF_WORDS;
+                const int frame = t + f[CF_FRAME_OFF];
+                float v = 0.0f;
+                if (frame >= 0 && frame < T) v = pv.buf_ptr[f[CF_BUF]][((size_t)frame * N + n) * dim + i];
+                if (f[CF_W_OFF] >= 0) v *= weights[f[CF_W_OFF] + i];
+                prod *= v;
+            }
             s += prod;
         }
     }

@@ -1,4 +1,7 @@
 // Device-side interpreter of node programs (see program.h for the encoding).
+//
+// All control flow depends only on program words, which are forced into scalar registers, so
+// the slot file is indexed with uniform indices and stays in vector registers.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -15,69 +18,106 @@ __device__ __forceinline__ float tanh_f(float x) {
     return copysignf(r, x);
 }
 
-// Value of one factor for (frame t, stream n, unit i).  `words` points at the factor.
-__device__ __forceinline__ float factor_value(const PlanView& pv, const int32_t* __restrict__ f,
-                                              const float* __restrict__ weights, const float* slots,
-                                              int T, int N, int t, int n, int i) {
-    float v;
-    const int slot = f[FACTOR_SLOT];
-    if (slot >= 0) {
-        v = slots[slot];
-    } else {
-        const int frame = t + f[FACTOR_FRAME_OFF];
-        if (frame < 0 || frame >= T) return 0.0f;
-        const int buf = f[FACTOR_BUF];
-        v = pv.buf_ptr[buf][((size_t)frame * N + n) * pv.buf_dim[buf] + i];
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Ownership of units: workgroup part `w` of `G` owns units [w * chunk, (w + 1) * chunk) of a
+// layer of width dim, chunk = ceil(dim / G).  A thread works on local unit il of every layer.
+struct UnitMap {
+    int w, G, il;
+    __device__ __forceinline__ int unit(int dim, bool& active) const {
+        const int chunk = (dim + G - 1) / G;
+        const int i = w * chunk + il;
+        active = il < chunk && i < dim;
+        return i;
     }
-    const int w_off = f[FACTOR_W_OFF];
-    if (w_off >= 0) v *= weights[w_off + i];
-    return v;
+};
+
+struct ProgramView {
+    const int32_t* ga; const int32_t* iv; const int32_t* mo; const int32_t* st;
+    int n_gather, n_inv, n_ops, n_stores;
+    __device__ __forceinline__ explicit ProgramView(const int32_t* p) {
+        n_gather = uni(p[PG_NGATHER]); n_inv = uni(p[PG_NINV]); n_ops = uni(p[PG_NOPS]); n_stores = uni(p[PG_NSTORES]);
+        ga = p + PG_HEADER_WORDS; iv = ga + n_gather * GA_WORDS; mo = iv + n_inv * IV_WORDS; st = mo + n_ops * MO_WORDS;
+    }
+};
+
+// slots [n_gather, n_gather + n_inv): diagonal weights and biases (independent of t and n).
+__device__ __forceinline__ void load_invariants(float (&s)[MAX_SLOTS], const ProgramView& pg,
+                                                const float* __restrict__ weights, const UnitMap& um) {
+    for (int v = 0; v < pg.n_inv; ++v) {
+        const int32_t* e = pg.iv + v * IV_WORDS;
+        bool active;
+        const int i = um.unit(uni(e[IV_DIM]), active);
+        s[pg.n_gather + v] = active ? weights[uni(e[IV_W_OFF]) + i] : 0.0f;
+    }
 }
 
-// Evaluates every NodeOp of a program for one (t, n, i).  Control flow depends only on the
-// program words, so it is uniform across a wavefront; lanes with i >= dim of an op idle.
-__device__ __forceinline__ void run_node_program(const PlanView& pv, const int32_t* __restrict__ prog,
-                                                 const float* __restrict__ weights,
-                                                 int T, int N, int t, int n, int i) {
-    float slots[MAX_SLOTS];
-    const int n_ops = prog[PROG_NOPS];
-    const int32_t* w = prog + PROG_HEADER_WORDS;
-    for (int o = 0; o < n_ops; ++o) {
-        const int dim = w[OP_DIM];
-        const int n_terms = w[OP_NTERMS];
-        const bool active = i < dim;
-        float v = 0.0f;
-        if (active) {
-            const int pre = w[OP_PRE_BUF], bias = w[OP_BIAS_OFF], acc = w[OP_ACC_BUF];
-            if (pre >= 0) v += pv.buf_ptr[pre][((size_t)t * N + n) * dim + i];
-            if (bias >= 0) v += weights[bias + i];
-            if (acc >= 0) v += pv.buf_ptr[acc][(size_t)n * dim + i];
+// slots [0, n_gather): values of frame tensors at (t + frame_off, n, i); AccFn supplies the
+// matrix-vector accumulator entries: acc(buffer id, dim, n, i, il).
+template <class AccFn>
+__device__ __forceinline__ void load_gathers(float (&s)[MAX_SLOTS], const ProgramView& pg, const PlanView& pv,
+                                             const UnitMap& um, int T, int N, int t, int n, AccFn acc, bool with_acc) {
+    for (int g = 0; g < pg.n_gather; ++g) {
+        const int32_t* e = pg.ga + g * GA_WORDS;
+        const int dim = uni(e[GA_DIM]), buf = uni(e[GA_BUF]);
+        bool active;
+        const int i = um.unit(dim, active);
+        if (uni(e[GA_KIND]) == GA_KIND_ACC) {
+            if (with_acc) s[g] = active ? acc(buf, dim, n, i, um.il) : 0.0f;
+        } else {
+            const int frame = t + uni(e[GA_FRAME_OFF]);
+            float v = 0.0f;
+            if (active && frame >= 0 && frame < T) v = pv.buf_ptr[buf][((size_t)frame * N + n) * dim + i];
+            s[g] = v;
         }
-        const int32_t* tw = w + OP_HEADER_WORDS;
-        for (int q = 0; q < n_terms; ++q) {
-            const int nf = tw[0];
-            ++tw;
-            float prod = 1.0f;
-            for (int j = 0; j < nf; ++j) {
-                if (active) prod *= factor_value(pv, tw, weights, slots, T, N, t, n, i);
-                tw += FACTOR_WORDS;
-            }
-            v += prod;
+    }
+}
+
+// Only the accumulator slots (used when the other gathers were issued earlier).
+template <class AccFn>
+__device__ __forceinline__ void load_accumulators(float (&s)[MAX_SLOTS], const ProgramView& pg, const UnitMap& um,
+                                                  int n, AccFn acc) {
+    for (int g = 0; g < pg.n_gather; ++g) {
+        const int32_t* e = pg.ga + g * GA_WORDS;
+        if (uni(e[GA_KIND]) != GA_KIND_ACC) continue;
+        const int dim = uni(e[GA_DIM]);
+        bool active;
+        const int i = um.unit(dim, active);
+        s[g] = active ? acc(uni(e[GA_BUF]), dim, n, i, um.il) : 0.0f;
+    }
+}
+
+__device__ __forceinline__ void run_ops(float (&s)[MAX_SLOTS], const ProgramView& pg) {
+    for (int p = 0; p < pg.n_ops; ++p) {
+        const int packed = uni(pg.mo[p * MO_WORDS + MO_PACKED]);
+        const int opc = packed & 0xFF, d = (packed >> 8) & 0xFF, a = (packed >> 16) & 0xFF, b = (packed >> 24) & 0xFF;
+        const float va = s[a];
+        float r;
+        switch (opc) {
+            case MOP_MOV: r = va; break;
+            case MOP_ADD: r = va + s[b]; break;
+            case MOP_MUL: r = va * s[b]; break;
+            case MOP_FMA: r = fmaf(va, s[b], s[uni(pg.mo[p * MO_WORDS + MO_C])]); break;
+            case MOP_SIG: r = sigmoid_f(va); break;
+            case MOP_TANH: r = tanh_f(va); break;
+            case MOP_DSIG: { const float y = s[b]; r = va * y * (1.0f - y); break; }
+            case MOP_DTANH: { const float y = s[b]; r = va * (1.0f - y * y); break; }
+            default: r = 0.0f; break;
         }
-        if (active) {
-            const int post = w[OP_POST];
-            if (post == POST_SIGMOID) v = sigmoid_f(v);
-            else if (post == POST_TANH) v = tanh_f(v);
-            else if (post >= POST_DSIGMOID) {
-                const int db = w[OP_DERIV_BUF];
-                const float y = pv.buf_ptr[db][((size_t)t * N + n) * dim + i];
-                v *= (post == POST_DSIGMOID) ? y * (1.0f - y) : (1.0f - y * y);
-            }
-            pv.buf_ptr[w[OP_OUT_BUF]][((size_t)t * N + n) * dim + i] = v;
-        }
-        const int os = w[OP_OUT_SLOT];
-        if (os >= 0) slots[os] = v;
-        w = tw;
+        s[d] = r;
+    }
+}
+
+// StoreFn(ptr, value) performs the store (plain, or with a wider visibility scope).
+template <class StoreFn>
+__device__ __forceinline__ void run_stores(const float (&s)[MAX_SLOTS], const ProgramView& pg, const PlanView& pv,
+                                           const UnitMap& um, int N, int t, int n, StoreFn store) {
+    for (int q = 0; q < pg.n_stores; ++q) {
+        const int32_t* e = pg.st + q * ST_WORDS;
+        const int dim = uni(e[ST_DIM]);
+        bool active;
+        const int i = um.unit(dim, active);
+        if (active) store(pv.buf_ptr[uni(e[ST_BUF])] + ((size_t)t * N + n) * dim + i, s[uni(e[ST_SLOT])]);
     }
 }
 

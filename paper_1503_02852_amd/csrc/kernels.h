@@ -56,4 +56,19 @@ hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max
                          int T, int N, hipStream_t stream);
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream);
 
+// ---------------------------------------------------------------------------------------
+// Persistent recurrent-step kernel (all T steps of one recurrent node and direction)
+// ---------------------------------------------------------------------------------------
+constexpr size_t STEP_LDS_LIMIT = 140 * 1024;   // dynamic LDS per workgroup (static tables take the rest of 160 KiB)
+struct StepLaunchPlan {
+    bool ok; int G, NB, xcd_stride; size_t lds_bytes;
+};
+// Chooses the number of workgroups for a component's step descriptor; ok = false if the
+// component does not fit the kernel's limits (then the caller steps with per-frame launches).
+bool plan_step_launch(const int32_t* words, int desc_off, int N, int force_G, StepLaunchPlan& out);
+hipError_t launch_recurrent_steps(const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
+                                  unsigned* ctrl, int T, int N, bool backward, int spin_limit, hipStream_t stream);
+// Fills n floats with the "not yet written" bit pattern the step kernel's consumers wait on.
+hipError_t launch_fill_sentinel(float* p, int64_t n, hipStream_t stream);
+
 }  // namespace rnng

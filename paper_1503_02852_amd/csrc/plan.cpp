@@ -5,8 +5,10 @@
 // connections and then the delay-0 part level by level.  The backward direction uses the
 // reversed order (Section 3.1, last sentences) with the delta / epsilon equations of Section 2.2.
 #include "plan.h"
+#include "step_layout.h"
 
 #include <algorithm>
+#include <array>
 #include <map>
 
 namespace rnng {
@@ -19,31 +21,106 @@ int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 struct FactorH { int buf, frame_off, w_off, slot; };
 struct TermH { std::vector<FactorH> f; };
+enum { POST_NONE = 0, POST_SIGMOID = 1, POST_TANH = 2, POST_DSIGMOID = 3, POST_DTANH = 4 };
 struct OpH {
-    int post = POST_NONE, dim = 0, out_buf = -1, pre_buf = -1, bias_off = -1, acc_buf = -1,
+    int post = POST_NONE, dim = 0, out_buf = -1, pre_buf = -1, bias_off = -1, acc_buf = -1, acc_task = 0,
         deriv_buf = -1, out_slot = -1;
+    bool new_program = false;   // must not share a program with the operation before it
     std::vector<TermH> terms;
 };
 struct MvEdgeH { int w_off, k_len, transposed, src_buf, frame_off; };
 struct MvTaskH { int n_out, acc_buf; std::vector<MvEdgeH> edges; };
 
-int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& ops, int& max_dim) {
-    int off = (int)w.size();
-    max_dim = 0;
-    for (const OpH& o : ops) max_dim = std::max(max_dim, o.dim);
-    w.push_back((int)ops.size());
-    w.push_back(max_dim);
-    for (const OpH& o : ops) {
-        int32_t h[OP_HEADER_WORDS];
-        h[OP_POST] = o.post; h[OP_DIM] = o.dim; h[OP_OUT_BUF] = o.out_buf; h[OP_PRE_BUF] = o.pre_buf;
-        h[OP_BIAS_OFF] = o.bias_off; h[OP_ACC_BUF] = o.acc_buf; h[OP_DERIV_BUF] = o.deriv_buf;
-        h[OP_OUT_SLOT] = o.out_slot; h[OP_NTERMS] = (int)o.terms.size();
-        w.insert(w.end(), h, h + OP_HEADER_WORDS);
-        for (const TermH& t : o.terms) {
-            w.push_back((int)t.f.size());
-            for (const FactorH& f : t.f) { w.push_back(f.buf); w.push_back(f.frame_off); w.push_back(f.w_off); w.push_back(f.slot); }
-        }
+// Lowers a list of node operations (each a sum of products of factors, then an activation or
+// a derivative factor) to the straight-line slot program described in program.h.
+struct Lowering {
+    std::vector<std::array<int, 4>> gathers;   // buf, frame_off, dim, kind
+    std::vector<std::array<int, 2>> invs;      // w_off, dim
+    int gather_slot(int buf, int frame_off, int dim, int kind) {
+        for (size_t i = 0; i < gathers.size(); ++i)
+            if (gathers[i][0] == buf && gathers[i][1] == frame_off && gathers[i][3] == kind) return (int)i;
+        gathers.push_back({buf, frame_off, dim, kind});
+        return (int)gathers.size() - 1;
     }
+    int inv_index(int w_off, int dim) {
+        for (size_t i = 0; i < invs.size(); ++i) if (invs[i][0] == w_off) return (int)i;
+        invs.push_back({w_off, dim});
+        return (int)invs.size() - 1;
+    }
+};
+
+// Returns the word offset of the program, or -1 (with err set) if it needs too many slots.
+int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int first, int last,
+                 const std::vector<int>& buf_dim, int& max_dim, bool dry_run) {
+    // results of operations outside [first, last) are read back from their buffers
+    std::vector<OpH> ops(all_ops.begin() + first, all_ops.begin() + last);
+    for (OpH& o : ops)
+        for (TermH& t : o.terms)
+            for (FactorH& f : t.f) f.slot = (f.slot >= first && f.slot < last) ? f.slot - first : -1;
+    Lowering L;
+    // pass 1: collect loads so that their slots are known before any op is emitted
+    for (const OpH& o : ops) {
+        if (o.pre_buf >= 0) L.gather_slot(o.pre_buf, 0, o.dim, GA_KIND_FRAMES);
+        if (o.bias_off >= 0) L.inv_index(o.bias_off, o.dim);
+        if (o.acc_buf >= 0) L.gather_slot(o.acc_buf, o.acc_task, o.dim, GA_KIND_ACC);
+        for (const TermH& t : o.terms)
+            for (const FactorH& f : t.f) {
+                if (f.slot < 0) L.gather_slot(f.buf, f.frame_off, buf_dim[f.buf], GA_KIND_FRAMES);
+                if (f.w_off >= 0 || f.w_off <= -1000) L.inv_index(f.w_off, buf_dim[f.buf]);
+            }
+        if (o.deriv_buf >= 0) L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES);
+    }
+    const int ng = (int)L.gathers.size(), ni = (int)L.invs.size();
+    const int res0 = ng + ni, tmp = res0 + (int)ops.size(), n_slots = tmp + 1;
+    if (n_slots > MAX_SLOTS || ng > STEP_MAX_GATHERS) return -1;
+    if (dry_run) return 0;
+    std::vector<std::array<int, 2>> mops;      // packed, c
+    std::vector<std::array<int, 4>> stores;    // buf, slot, dim, flags
+    auto mop = [&](int opc, int d, int a, int b, int c) { mops.push_back({opc | d << 8 | a << 16 | b << 24, c}); };
+    max_dim = 0;
+    for (size_t r = 0; r < ops.size(); ++r) {
+        const OpH& o = ops[r];
+        max_dim = std::max(max_dim, o.dim);
+        const int R = res0 + (int)r;
+        std::vector<std::vector<int>> summands;
+        if (o.pre_buf >= 0) summands.push_back({L.gather_slot(o.pre_buf, 0, o.dim, GA_KIND_FRAMES)});
+        if (o.bias_off >= 0) summands.push_back({ng + L.inv_index(o.bias_off, o.dim)});
+        if (o.acc_buf >= 0) summands.push_back({L.gather_slot(o.acc_buf, o.acc_task, o.dim, GA_KIND_ACC)});
+        for (const TermH& t : o.terms) {
+            std::vector<int> atoms;
+            for (const FactorH& f : t.f) {
+                atoms.push_back(f.slot >= 0 ? res0 + f.slot : L.gather_slot(f.buf, f.frame_off, buf_dim[f.buf], GA_KIND_FRAMES));
+                if (f.w_off >= 0 || f.w_off <= -1000) atoms.push_back(ng + L.inv_index(f.w_off, buf_dim[f.buf]));
+            }
+            summands.push_back(atoms);
+        }
+        bool have = false;
+        for (const std::vector<int>& a : summands) {
+            if (a.size() == 1) {
+                if (!have) mop(MOP_MOV, R, a[0], 0, 0); else mop(MOP_ADD, R, R, a[0], 0);
+            } else {
+                int p = a[0];
+                for (size_t j = 1; j + 1 < a.size(); ++j) { mop(MOP_MUL, tmp, p, a[j], 0); p = tmp; }
+                if (!have) mop(MOP_MUL, R, p, a.back(), 0); else mop(MOP_FMA, R, p, a.back(), R);
+            }
+            have = true;
+        }
+        if (!have) mop(MOP_ZERO, R, 0, 0, 0);
+        if (o.post == POST_SIGMOID) mop(MOP_SIG, R, R, 0, 0);
+        else if (o.post == POST_TANH) mop(MOP_TANH, R, R, 0, 0);
+        else if (o.post == POST_DSIGMOID) mop(MOP_DSIG, R, R, L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES), 0);
+        else if (o.post == POST_DTANH) mop(MOP_DTANH, R, R, L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES), 0);
+        stores.push_back({o.out_buf, R, o.dim, 0});
+    }
+    const int off = (int)w.size();
+    int32_t h[PG_HEADER_WORDS] = {0};
+    h[PG_NGATHER] = ng; h[PG_NINV] = ni; h[PG_NOPS] = (int)mops.size(); h[PG_NSTORES] = (int)stores.size();
+    h[PG_MAXDIM] = max_dim; h[PG_NSLOTS] = n_slots;
+    w.insert(w.end(), h, h + PG_HEADER_WORDS);
+    for (auto& g : L.gathers) w.insert(w.end(), g.begin(), g.end());
+    for (auto& v : L.invs) w.insert(w.end(), v.begin(), v.end());
+    for (auto& m : mops) w.insert(w.end(), m.begin(), m.end());
+    for (auto& st : stores) w.insert(w.end(), st.begin(), st.end());
     return off;
 }
 
@@ -61,6 +138,82 @@ int emit_matvecs(std::vector<int32_t>& w, const std::vector<MvTaskH>& tasks, int
     return off;
 }
 
+}  // namespace
+
+namespace {
+
+bool op_fits(const OpH& o, const std::vector<int>& buf_dim, int slot_margin) {
+    std::vector<OpH> one(1, o);
+    for (TermH& t : one[0].terms) for (FactorH& f : t.f) f.slot = -1;
+    // the margin is honoured by adding dummy invariant loads
+    for (int i = 0; i < slot_margin; ++i) one[0].terms.push_back(TermH{{FactorH{o.out_buf, 0, -1000 - i, -1}}});
+    std::vector<int32_t> sink; int md = 0;
+    return emit_program(sink, one, 0, 1, buf_dim, md, true) == 0;
+}
+
+// A layer whose own sum has too many element-wise terms for one program is cut into parts that
+// accumulate through a scratch tensor (part_buf): part 1 stores its partial sum, the next part
+// starts from it, the last part applies the activation / derivative and stores the result.
+bool split_wide_ops(std::vector<OpH>& ops, const std::vector<int>& part_bufs, const std::vector<int>& buf_dim,
+                    std::vector<char>& buf_alloc, std::string& err) {
+    std::vector<OpH> out;
+    std::vector<int> new_index(ops.size(), 0);
+    for (size_t r = 0; r < ops.size(); ++r) {
+        const OpH& o = ops[r];
+        if (op_fits(o, buf_dim, 0)) { new_index[r] = (int)out.size(); out.push_back(o); continue; }
+        const int pb = part_bufs[r];
+        buf_alloc[pb] = 1;
+        OpH cur = o; cur.terms.clear(); cur.post = POST_NONE; cur.deriv_buf = -1; cur.out_buf = pb;
+        for (const TermH& t : o.terms) {
+            OpH trial = cur; trial.terms.push_back(t);
+            if (op_fits(trial, buf_dim, 2)) { cur = trial; continue; }
+            if (cur.terms.empty() && cur.pre_buf < 0 && cur.acc_buf < 0 && cur.bias_off < 0) {
+                err = "a connection into a multiplicative layer has too many sibling connections for one step program";
+                return false;
+            }
+            out.push_back(cur);
+            cur = OpH(); cur.dim = o.dim; cur.pre_buf = pb; cur.out_buf = pb; cur.new_program = true; cur.terms.push_back(t);
+            if (!op_fits(cur, buf_dim, 2)) {
+                err = "a connection into a multiplicative layer has too many sibling connections for one step program";
+                return false;
+            }
+        }
+        cur.post = o.post; cur.deriv_buf = o.deriv_buf; cur.out_buf = o.out_buf;
+        new_index[r] = (int)out.size();
+        out.push_back(cur);
+    }
+    for (size_t r = 0; r < out.size(); ++r) out[r].out_slot = (int)r;
+    for (OpH& o : out)
+        for (TermH& t : o.terms)
+            for (FactorH& f : t.f) if (f.slot >= 0) f.slot = new_index[f.slot];
+    ops.swap(out);
+    return true;
+}
+
+// Emits the node operations of one phase as one or more programs; a phase is split when its
+// operations together need more slots than a thread holds.  The matrix-vector tasks go with
+// the first part (their sources never depend on this phase's own results).
+bool emit_phase(Plan& P, std::vector<PhasePlan>& out, const std::vector<MvTaskH>& tasks, std::vector<OpH> ops,
+                const std::vector<int>& part_bufs, std::string& err) {
+    if (!split_wide_ops(ops, part_bufs, P.buf_dim, P.buf_alloc, err)) return false;
+    int first = 0;
+    bool first_part = true;
+    const int n = (int)ops.size();
+    while (first < n) {
+        int last = first + 1, md = 0;
+        if (emit_program(P.words, ops, first, last, P.buf_dim, md, true) < 0) {
+            err = "a layer has too many element-wise connections for one step program";
+            return false;
+        }
+        while (last < n && !ops[last].new_program && emit_program(P.words, ops, first, last + 1, P.buf_dim, md, true) == 0) ++last;
+        PhasePlan ph;
+        if (first_part && !tasks.empty()) { ph.mv_off = emit_matvecs(P.words, tasks, ph.mv_max_out); ph.n_mv_tasks = (int)tasks.size(); }
+        ph.prog_off = emit_program(P.words, ops, first, last, P.buf_dim, ph.max_dim, false);
+        out.push_back(ph);
+        first = last; first_part = false;
+    }
+    return true;
+}
 }  // namespace
 
 bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges, Plan& P, std::string& err) {
@@ -109,9 +262,18 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     const std::vector<GNode>& xn = P.xnodes;
     const std::vector<GEdge>& xe = P.xedges;
     const Schedule& S = P.xsched;
-    P.n_bufs = 3 * K;
+    P.n_bufs = 5 * K;
     P.buf_dim.assign(P.n_bufs, 0);
-    for (int k = 0; k < K; ++k) P.buf_dim[P.ybuf(k)] = P.buf_dim[P.dbuf(k)] = P.buf_dim[P.abuf(k)] = xn[k].dim;
+    P.buf_alloc.assign(P.n_bufs, 0);
+    for (int k = 0; k < K; ++k) {
+        for (int b : {P.ybuf(k), P.dbuf(k), P.abuf(k), P.pbuf(k), P.qbuf(k)}) P.buf_dim[b] = xn[k].dim;
+        if (xn[k].kind != NODE_INPUT) P.buf_alloc[P.ybuf(k)] = P.buf_alloc[P.dbuf(k)] = 1;
+    }
+    // y_src of a full connection inside a recurrent node is read by all workgroups during the
+    // forward step loop, ds_dst during the backward one
+    std::vector<char> shared_y(K, 0), shared_d(K, 0);
+    for (int m = 0; m < M; ++m)
+        if (xe[m].wkind == W_FULL && S.edge_class[m] != EDGE_BATCHED) { shared_y[xe[m].src] = 1; shared_d[xe[m].dst] = 1; }
 
     std::vector<std::vector<int>> in_e(K), out_e(K);
     for (int m = 0; m < M; ++m) { in_e[xe[m].dst].push_back(m); out_e[xe[m].src].push_back(m); }
@@ -141,17 +303,18 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
 
         // ---- forward ----
         for (int k : members) {
-            GemmProblemPlan gp; gp.c_buf = P.ybuf(k); gp.n = xn[k].dim;
+            GemmProblemPlan gp; gp.c_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k); gp.n = xn[k].dim;
             for (int m : in_e[k])
                 if (xe[m].wkind == W_FULL && S.edge_class[m] == EDGE_BATCHED)
                     gp.pairs.push_back(GemmPairPlan{P.ybuf(xe[m].src), -1, full_off(m), xn[xe[m].src].dim, xe[m].delay});
-            if (!gp.pairs.empty()) cp.fwd_gemms.push_back(gp);
+            if (!gp.pairs.empty()) { cp.fwd_gemms.push_back(gp); P.buf_alloc[gp.c_buf] = 1; }
+            if (shared_y[k]) cp.fwd_shared_bufs.push_back(P.ybuf(k));
+            if (shared_d[k]) cp.bwd_shared_bufs.push_back(P.dbuf(k));
             if (xn[k].act == ACT_SOFTMAX) cp.softmax_node = k;
         }
         for (int p = 0; p < n_phases; ++p) {
             std::vector<int> np;
             for (int k : members) if (phase[k] == p) np.push_back(k);
-            if ((int)np.size() > MAX_SLOTS) { err = "a recurrent node has too many layers in one step phase"; return false; }
             std::map<int, int> slot;
             for (size_t i = 0; i < np.size(); ++i) slot[np[i]] = (int)i;
             std::vector<MvTaskH> tasks; std::vector<OpH> ops;
@@ -164,8 +327,11 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                 for (int m : in_e[k]) {
                     const GEdge& e = xe[m];
                     if (e.wkind == W_FULL) {
-                        if (S.edge_class[m] == EDGE_BATCHED) o.pre_buf = P.ybuf(k);
-                        else task.edges.push_back(MvEdgeH{(int)full_off(m), xn[e.src].dim, 0, P.ybuf(e.src), -e.delay});
+                        if (S.edge_class[m] == EDGE_BATCHED) o.pre_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k);
+                        else {
+                            task.edges.push_back(MvEdgeH{(int)full_off(m), xn[e.src].dim, 0, P.ybuf(e.src), -e.delay});
+                            cp.step_weight_floats += (int64_t)xn[k].dim * xn[e.src].dim;
+                        }
                         continue;
                     }
                     FactorH f{P.ybuf(e.src), -e.delay, w_off_of(m), -1};
@@ -174,24 +340,30 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     else { TermH t; t.f.push_back(f); o.terms.push_back(t); }
                 }
                 if (xn[k].kind == NODE_MUL) o.terms.push_back(product);
-                if (!task.edges.empty()) { o.acc_buf = task.acc_buf; tasks.push_back(task); }
+                if (!task.edges.empty()) { o.acc_buf = task.acc_buf; o.acc_task = (int)tasks.size(); tasks.push_back(task); P.buf_alloc[task.acc_buf] = 2; }
                 ops.push_back(o);
             }
-            PhasePlan ph;
-            if (!tasks.empty()) { ph.mv_off = emit_matvecs(P.words, tasks, ph.mv_max_out); ph.n_mv_tasks = (int)tasks.size(); }
-            ph.prog_off = emit_program(P.words, ops, ph.max_dim);
-            cp.fwd_phases.push_back(ph);
+            std::vector<int> part_bufs;
+            for (int k : np) part_bufs.push_back(P.pbuf(k));
+            if (!emit_phase(P, cp.fwd_phases, tasks, ops, part_bufs, err)) return false;
         }
         cp.has_fwd_program = true;
+        auto emit_desc = [&](const std::vector<PhasePlan>& phs) {
+            const int off = (int)P.words.size();
+            P.words.push_back((int)phs.size());
+            for (const PhasePlan& ph : phs) { P.words.push_back(ph.mv_off); P.words.push_back(ph.prog_off); }
+            return off;
+        };
+        cp.fwd_desc_off = emit_desc(cp.fwd_phases);
 
         // ---- backward ----
         if (cp.softmax_node >= 0) continue;   // output delta comes from the softmax / cross-entropy kernel
         for (int j : members) {
-            GemmProblemPlan gp; gp.c_buf = P.dbuf(j); gp.n = xn[j].dim;
+            GemmProblemPlan gp; gp.c_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); gp.n = xn[j].dim;
             for (int m : out_e[j])
                 if (xe[m].wkind == W_FULL && S.edge_class[m] == EDGE_BATCHED)
                     gp.pairs.push_back(GemmPairPlan{P.dbuf(xe[m].dst), -1, full_off(m), xn[xe[m].dst].dim, xe[m].delay});
-            if (!gp.pairs.empty()) cp.bwd_gemms.push_back(gp);
+            if (!gp.pairs.empty()) { cp.bwd_gemms.push_back(gp); P.buf_alloc[gp.c_buf] = 1; }
         }
         for (int p = n_phases - 1; p >= 0; --p) {
             std::vector<int> np;
@@ -209,7 +381,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     const GEdge& e = xe[m];
                     const int k = e.dst;
                     if (e.wkind == W_FULL) {
-                        if (S.edge_class[m] == EDGE_BATCHED) o.pre_buf = P.dbuf(j);
+                        if (S.edge_class[m] == EDGE_BATCHED) o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j);
                         else task.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
                         continue;
                     }
@@ -222,15 +394,15 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                             if (m2 != m) t.f.push_back(FactorH{P.ybuf(xe[m2].src), e.delay - xe[m2].delay, w_off_of(m2), -1});
                     o.terms.push_back(t);
                 }
-                if (!task.edges.empty()) { o.acc_buf = task.acc_buf; tasks.push_back(task); }
+                if (!task.edges.empty()) { o.acc_buf = task.acc_buf; o.acc_task = (int)tasks.size(); tasks.push_back(task); P.buf_alloc[task.acc_buf] = 2; }
                 ops.push_back(o);
             }
-            PhasePlan ph;
-            if (!tasks.empty()) { ph.mv_off = emit_matvecs(P.words, tasks, ph.mv_max_out); ph.n_mv_tasks = (int)tasks.size(); }
-            ph.prog_off = emit_program(P.words, ops, ph.max_dim);
-            cp.bwd_phases.push_back(ph);
+            std::vector<int> part_bufs;
+            for (int j : np) part_bufs.push_back(P.qbuf(j));
+            if (!emit_phase(P, cp.bwd_phases, tasks, ops, part_bufs, err)) return false;
         }
         cp.has_bwd_program = true;
+        cp.bwd_desc_off = emit_desc(cp.bwd_phases);
     }
 
     // ---- weight gradients ----
@@ -242,7 +414,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     P.n_colsum = 0;
     auto emit_colsum = [&](int dim, int out_off, const std::vector<FactorH>& fs) {
         P.words.push_back(dim); P.words.push_back(out_off); P.words.push_back((int)fs.size());
-        for (const FactorH& f : fs) { P.words.push_back(f.buf); P.words.push_back(f.frame_off); P.words.push_back(f.w_off); P.words.push_back(f.slot); }
+        for (const FactorH& f : fs) { P.words.push_back(f.buf); P.words.push_back(f.frame_off); P.words.push_back(f.w_off); }
         ++P.n_colsum; P.colsum_max_dim = std::max(P.colsum_max_dim, dim);
     };
     for (int m = 0; m < M; ++m) {

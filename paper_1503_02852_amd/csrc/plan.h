@@ -45,6 +45,11 @@ struct CompPlan {
     std::vector<GemmProblemPlan> fwd_gemms, bwd_gemms;
     std::vector<PhasePlan> fwd_phases, bwd_phases;   // bwd_phases already in execution order
     bool has_fwd_program = false, has_bwd_program = false;
+    int fwd_desc_off = -1, bwd_desc_off = -1;  // step descriptors: [n_phases, (mv_off, prog_off)...]
+    // buffers that workgroups of the persistent step kernel read from each other (sources of
+    // full connections inside the recurrent node); they are pre-filled with a sentinel
+    std::vector<int> fwd_shared_bufs, bwd_shared_bufs;
+    int64_t step_weight_floats = 0;         // weights of all full connections inside the component
 };
 
 struct Plan {
@@ -55,9 +60,12 @@ struct Plan {
     std::vector<GNode> xnodes; std::vector<GEdge> xedges; std::vector<int> xedge_param; Schedule xsched;
     // parameter layout (original indexing)
     std::vector<int64_t> edge_off, edge_len, bias_off, bias_len; int64_t n_params = 0;
-    // buffers: y of exec node k -> k; ds of k -> K + k; accumulator of k -> 2K + k
+    // buffers: y of exec node k -> k; ds of k -> K + k; matrix-vector accumulator of k -> 2K + k;
+    // batched pre-activation of k kept apart from y_k -> 3K + k, likewise for ds_k -> 4K + k
+    // (used when y_k / ds_k is read by other workgroups during the step loop)
     int n_bufs = 0;
     std::vector<int> buf_dim;
+    std::vector<char> buf_alloc;            // 0 not in the workspace, 1 [T][N][dim], 2 [N][dim]
     std::vector<CompPlan> comps;
     std::vector<GradGemmPlan> grad_gemms;
     int colsum_off = -1, n_colsum = 0, colsum_max_dim = 0;
@@ -67,6 +75,8 @@ struct Plan {
     int ybuf(int k) const { return k; }
     int dbuf(int k) const { return (int)xnodes.size() + k; }
     int abuf(int k) const { return 2 * (int)xnodes.size() + k; }
+    int pbuf(int k) const { return 3 * (int)xnodes.size() + k; }
+    int qbuf(int k) const { return 4 * (int)xnodes.size() + k; }
 };
 
 // Returns false and a reason on an invalid graph.

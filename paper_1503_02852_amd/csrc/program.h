@@ -2,38 +2,51 @@
 // planner emits and the HIP kernels interpret.  Plain int32 words in device memory.
 //
 // A "buffer" is a [T][N][dim] float tensor (node activations y_k, node state gradients
-// dE/ds_k) or a one-frame [N][dim] scratch tensor (matrix-vector accumulators); kernels get
-// a table of base pointers and widths indexed by buffer id.
+// dE/ds_k, batched pre-activations) or a one-frame [N][dim] tensor (matrix-vector
+// accumulators); kernels get a table of base pointers and widths indexed by buffer id.
 //
-// NodeOp (one per node and direction), evaluated for every (frame t, stream n, unit i < dim):
-//     v = [pre_buf(t,n,i)] + [weights[bias_off + i]] + [acc_buf(n,i)] + sum over terms
-//     term   = product over its factors
-//     factor = value(buf, t + frame_off, n, i) * [weights[w_off + i]]
-//              value is taken from register slot `slot` if slot >= 0 (a result of an earlier
-//              NodeOp of the same program invocation), is 0 if the frame lies outside the window
-//     out    = post(v):  forward: v, sigmoid(v), tanh(v)
-//                        backward: v * y(1-y) or v * (1-y^2) with y = deriv_buf(t,n,i)
-//     out is stored to out_buf(t,n,i) and kept in register slot out_slot.
-// This covers the additive layer (sum of weighted activations), the multiplicative layer (one
-// term with one factor per incoming connection), and in the backward direction the delta of a
-// node as the sum over its outgoing connections of W^T eps, where eps for a multiplicative
-// destination carries the product of the destination's other incoming connection outputs
-// (paper Section 2.1 forward equations and Section 2.2 delta / epsilon equations).
+// A node program evaluates, for one (frame t, stream n, unit i), all layers of one phase of a
+// component in one direction.  It is straight-line code over a small register file of slots:
+//   gather   slot g      <- buffer(t + frame_off, n, i), 0 outside the window   (loads, hoistable)
+//   inv      next slots  <- weights[w_off + i]  (diagonal weights, biases; do not depend on t)
+//   ops      slot dst    <- op(slot a, slot b, slot c)
+//   stores   buffer(t, n, i) <- slot
+// which covers the additive layer (sum of weighted activations, Section 2.1), the
+// multiplicative layer (product of the incoming connection outputs), the activation functions,
+// and in the backward direction delta_k = (sum over outgoing connections of W^T eps) * f'(s_k)
+// with eps of a multiplicative destination carrying the product of that destination's other
+// incoming connection outputs (Section 2.2).
 #pragma once
 #include <cstdint>
 
 namespace rnng {
 
-enum { POST_NONE = 0, POST_SIGMOID = 1, POST_TANH = 2, POST_DSIGMOID = 3, POST_DTANH = 4 };
-
 enum {
-    OP_POST = 0, OP_DIM, OP_OUT_BUF, OP_PRE_BUF, OP_BIAS_OFF, OP_ACC_BUF, OP_DERIV_BUF,
-    OP_OUT_SLOT, OP_NTERMS, OP_HEADER_WORDS
+    MOP_MOV = 0,    // d = a
+    MOP_ADD = 1,    // d = a + b
+    MOP_MUL = 2,    // d = a * b
+    MOP_FMA = 3,    // d = a * b + c
+    MOP_SIG = 4,    // d = 1 / (1 + exp(-a))
+    MOP_TANH = 5,   // d = tanh(a)
+    MOP_DSIG = 6,   // d = a * b * (1 - b)
+    MOP_DTANH = 7,  // d = a * (1 - b * b)
+    MOP_ZERO = 8    // d = 0
 };
-enum { FACTOR_BUF = 0, FACTOR_FRAME_OFF, FACTOR_W_OFF, FACTOR_SLOT, FACTOR_WORDS };
 
-// Node program: [n_ops, max_dim, ops...]; op = header, then per term [n_factors, factors...].
-enum { PROG_NOPS = 0, PROG_MAXDIM, PROG_HEADER_WORDS };
+// Program header, then gather entries, inv entries, ops, stores.
+enum { PG_NGATHER = 0, PG_NINV, PG_NOPS, PG_NSTORES, PG_MAXDIM, PG_NSLOTS, PG_HEADER_WORDS = 8 };
+enum { GA_BUF = 0, GA_FRAME_OFF, GA_DIM, GA_KIND, GA_WORDS };   // kind: 0 frame tensor, 1 accumulator
+enum { GA_KIND_FRAMES = 0, GA_KIND_ACC = 1 };
+enum { IV_W_OFF = 0, IV_DIM, IV_WORDS };
+enum { MO_PACKED = 0, MO_C, MO_WORDS };                         // packed = opcode | dst << 8 | a << 16 | b << 24
+enum { ST_BUF = 0, ST_SLOT, ST_DIM, ST_FLAGS, ST_WORDS };
+
+constexpr int MAX_SLOTS = 32;     // a 32-float slot file stays in vector registers (indexed with uniform indices)
+
+inline int program_words(const int32_t* p) {
+    return PG_HEADER_WORDS + p[PG_NGATHER] * GA_WORDS + p[PG_NINV] * IV_WORDS + p[PG_NOPS] * MO_WORDS +
+           p[PG_NSTORES] * ST_WORDS;
+}
 
 // Matrix-vector task list: [n_tasks, tasks...]; task = [n_out, acc_buf, n_edges, edges...];
 // edge = [w_off, k_len, transposed, src_buf, frame_off].
@@ -43,10 +56,11 @@ enum { MV_NOUT = 0, MV_ACC_BUF, MV_NEDGES, MV_HEADER_WORDS };
 enum { MVE_W_OFF = 0, MVE_KLEN, MVE_TRANSPOSED, MVE_SRC_BUF, MVE_FRAME_OFF, MVE_WORDS };
 
 // Column-sum task (gradients of diagonal weights and biases):
-//   grads[out_off + i] = sum over t, n of the product of the factors.   [dim, out_off, n_factors, factors...]
+//   grads[out_off + i] = sum over t, n of the product of the factors;
+//   factor = buffer(t + frame_off, n, i) * [weights[w_off + i]].
+//   [dim, out_off, n_factors, factors...], factor = [buf, frame_off, w_off]
 enum { CS_DIM = 0, CS_OUT_OFF, CS_NFACTORS, CS_HEADER_WORDS };
-
-constexpr int MAX_SLOTS = 32;
+enum { CF_BUF = 0, CF_FRAME_OFF, CF_W_OFF, CF_WORDS };
 
 // Device view of the plan tables.
 struct PlanView {

@@ -146,3 +146,12 @@ def test_generalized_full_width_reduced_window():
     """The generalized configuration at its full widths and stream count (3 x 1024, N = 64) over a
     24-frame window, which the oracle finishes in seconds."""
     run_both(wl.make_config("generalized_n64", T=24), check_all_nodes=True, label="generalized_n64_T24")
+
+
+@pytest.mark.parametrize("seed", [8, 17])
+def test_dense_random_graph_splits_step_programs(seed):
+    """Dense random graphs whose recurrent node needs more element-wise values per step than one
+    program holds: the planner splits the step into several programs (and wide sums into parts)."""
+    rng = np.random.default_rng(1000 + seed)
+    spec = wl.random_graph(rng, n_inner=3 + seed % 9, p_edge=0.15 + 0.05 * (seed % 6), max_delay=3, n_inputs=1 + seed % 2)
+    run_both(wl.make_workload(f"dense{seed}", spec, T=9, N=2, seed=seed, scale=0.5, bias_scale=0.3))
