@@ -136,6 +136,15 @@ int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds);
  *   loss     HOST double or NULL; if given the call synchronises the stream and stores E_total. */
 int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream);
 
+/* The recurrent-step kernel is specialised at run time for each recurrent node's element-wise
+ * step program (compiled with hiprtc on first use, cached per process by program structure).
+ * rnn_specialise compiles the kernels this graph needs for N streams ahead of the first window;
+ * it needs no GPU.  Returns the number of kernels compiled or found in the cache (0 if N is
+ * served by kernels that are not specialised), or RNN_ERR_DEVICE with the compiler log as
+ * message.  If specialisation is unavailable at run time the library falls back to the
+ * interpreting build of the same kernel; RNNG_JIT=0 in the environment forces that. */
+int rnn_specialise(rnn_graph* g, int32_t N);
+
 /* Kernel-class timing for benchmarks: HIP events are recorded on the call's stream around the
  * launches of every class whose bit is set in class_mask (0 switches timing off; it is off by
  * default and costs nothing then).  rnn_profile_read waits for the recorded events, stores the

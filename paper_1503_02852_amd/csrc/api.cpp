@@ -4,11 +4,13 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "../../include/rnngraph.h"
+#include "jit.h"
 #include "kernels.h"
 #include "plan.h"
 
@@ -117,6 +119,14 @@ struct rnn_graph {
     double* loss_ptr() const { return reinterpret_cast<double*>(ws + layout.sync_off); }
     unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
     int force_step_G = 0;
+    bool use_jit = true;
+    std::map<int, std::string> jit_sources;   // key: component * 32 + backward * 16 + NB
+    const std::string& jit_source(int comp, bool backward, int NB) {
+        const int key = comp * 32 + (backward ? 16 : 0) + NB;
+        auto it = jit_sources.find(key);
+        if (it == jit_sources.end()) it = jit_sources.emplace(key, jit_step_source(plan, plan.comps[comp], backward, NB)).first;
+        return it->second;
+    }
 };
 
 namespace {
@@ -159,7 +169,8 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
     return hipSuccess;
 }
 
-hipError_t run_phases(rnn_graph* g, const CompPlan& cp, bool backward, hipStream_t s) {
+hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
+    const CompPlan& cp = g->plan.comps[comp];
     const PlanView pv = g->view();
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     const int T = g->T, N = g->N;
@@ -182,7 +193,19 @@ hipError_t run_phases(rnn_graph* g, const CompPlan& cp, bool backward, hipStream
             hipError_t e = launch_fill_sentinel(g->buf(b), (int64_t)T * N * g->plan.buf_dim[b], s);
             if (e != hipSuccess) return e;
         }
-        hipError_t e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, 1 << 22, s);
+        const int spin_limit = 1 << 22;
+        hipError_t e = hipErrorUnknown;
+        if (g->use_jit) {
+            // component-specialised build of the same kernel; the interpreted build is the fallback
+            const std::string& src = g->jit_source(comp, backward, lp.NB);
+            if (hipFunction_t fn = jit_step_function(src)) {
+                StepArgs a;
+                fill_step_args(a, pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit);
+                e = jit_launch(fn, a, lp, s);
+                if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(src); }
+            }
+        }
+        if (e != hipSuccess) e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, s);
         if (e != hipSuccess) return e;
         g->prof.end(prof, 1, s);
         return hipSuccess;
@@ -224,6 +247,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     std::string err;
     if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
+    if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
     *out = g;
     return RNN_OK;
 }
@@ -309,7 +333,7 @@ int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inpu
         if (!cp.has_fwd_program) continue;
         e = run_gemms(g, cp.fwd_gemms, false, s);
         if (e != hipSuccess) return fail_hip(e, "forward GEMM");
-        e = run_phases(g, cp, false, s);
+        e = run_phases(g, (int)(&cp - P.comps.data()), false, s);
         if (e != hipSuccess) return fail_hip(e, "forward node program");
         if (cp.softmax_node >= 0) {
             e = launch_softmax_rows(g->buf(P.ybuf(cp.softmax_node)), (int64_t)T * N, P.xnodes[cp.softmax_node].dim, s);
@@ -355,7 +379,7 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
         if (!cp.has_bwd_program) continue;
         e = run_gemms(g, cp.bwd_gemms, true, s);
         if (e != hipSuccess) return fail_hip(e, "backward GEMM");
-        e = run_phases(g, cp, true, s);
+        e = run_phases(g, c, true, s);
         if (e != hipSuccess) return fail_hip(e, "backward node program");
     }
     g->bptt_done = true;
@@ -425,6 +449,26 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
         if (flag) return fail(RNN_ERR_DEVICE, "a recurrent step kernel ran into its wait limit (results are invalid)");
     }
     return RNN_OK;
+}
+
+int rnn_specialise(rnn_graph* g, int32_t N) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "N must be positive");
+    const int NB = step_nb_for(N);
+    if (NB == 0 || !g->use_jit) return 0;
+    int n = 0;
+    for (size_t c = 0; c < g->plan.comps.size(); ++c) {
+        const CompPlan& cp = g->plan.comps[c];
+        if (!cp.recurrent) continue;
+        for (int backward = 0; backward < 2; ++backward) {
+            if (backward ? !cp.has_bwd_program : !cp.has_fwd_program) continue;
+            std::string log;
+            if (!jit_compile(g->jit_source((int)c, backward != 0, NB), &log))
+                return fail(RNN_ERR_DEVICE, "step kernel specialisation failed: " + log);
+            ++n;
+        }
+    }
+    return n;
 }
 
 int rnn_profile_enable(rnn_graph* g, int32_t class_mask) {

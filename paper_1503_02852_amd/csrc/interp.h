@@ -33,9 +33,10 @@ struct UnitMap {
 };
 
 struct ProgramView {
-    const int32_t* ga; const int32_t* iv; const int32_t* mo; const int32_t* st;
+    cwords_t ga; cwords_t iv; cwords_t mo; cwords_t st;
     int n_gather, n_inv, n_ops, n_stores;
-    __device__ __forceinline__ explicit ProgramView(const int32_t* p) {
+    __device__ __forceinline__ explicit ProgramView(const int32_t* gp) {
+        cwords_t p = (cwords_t)gp;
         n_gather = uni(p[PG_NGATHER]); n_inv = uni(p[PG_NINV]); n_ops = uni(p[PG_NOPS]); n_stores = uni(p[PG_NSTORES]);
         ga = p + PG_HEADER_WORDS; iv = ga + n_gather * GA_WORDS; mo = iv + n_inv * IV_WORDS; st = mo + n_ops * MO_WORDS;
     }
@@ -45,7 +46,7 @@ struct ProgramView {
 __device__ __forceinline__ void load_invariants(float (&s)[MAX_SLOTS], const ProgramView& pg,
                                                 const float* __restrict__ weights, const UnitMap& um) {
     for (int v = 0; v < pg.n_inv; ++v) {
-        const int32_t* e = pg.iv + v * IV_WORDS;
+        cwords_t e = pg.iv + v * IV_WORDS;
         bool active;
         const int i = um.unit(uni(e[IV_DIM]), active);
         s[pg.n_gather + v] = active ? weights[uni(e[IV_W_OFF]) + i] : 0.0f;
@@ -58,7 +59,7 @@ template <class AccFn>
 __device__ __forceinline__ void load_gathers(float (&s)[MAX_SLOTS], const ProgramView& pg, const PlanView& pv,
                                              const UnitMap& um, int T, int N, int t, int n, AccFn acc, bool with_acc) {
     for (int g = 0; g < pg.n_gather; ++g) {
-        const int32_t* e = pg.ga + g * GA_WORDS;
+        cwords_t e = pg.ga + g * GA_WORDS;
         const int dim = uni(e[GA_DIM]), buf = uni(e[GA_BUF]);
         bool active;
         const int i = um.unit(dim, active);
@@ -67,7 +68,7 @@ __device__ __forceinline__ void load_gathers(float (&s)[MAX_SLOTS], const Progra
         } else {
             const int frame = t + uni(e[GA_FRAME_OFF]);
             float v = 0.0f;
-            if (active && frame >= 0 && frame < T) v = pv.buf_ptr[buf][((size_t)frame * N + n) * dim + i];
+            if (active && frame >= 0 && frame < T) v = ((cbufs_t)pv.buf_ptr)[buf][((size_t)frame * N + n) * dim + i];
             s[g] = v;
         }
     }
@@ -78,7 +79,7 @@ template <class AccFn>
 __device__ __forceinline__ void load_accumulators(float (&s)[MAX_SLOTS], const ProgramView& pg, const UnitMap& um,
                                                   int n, AccFn acc) {
     for (int g = 0; g < pg.n_gather; ++g) {
-        const int32_t* e = pg.ga + g * GA_WORDS;
+        cwords_t e = pg.ga + g * GA_WORDS;
         if (uni(e[GA_KIND]) != GA_KIND_ACC) continue;
         const int dim = uni(e[GA_DIM]);
         bool active;
@@ -113,11 +114,11 @@ template <class StoreFn>
 __device__ __forceinline__ void run_stores(const float (&s)[MAX_SLOTS], const ProgramView& pg, const PlanView& pv,
                                            const UnitMap& um, int N, int t, int n, StoreFn store) {
     for (int q = 0; q < pg.n_stores; ++q) {
-        const int32_t* e = pg.st + q * ST_WORDS;
+        cwords_t e = pg.st + q * ST_WORDS;
         const int dim = uni(e[ST_DIM]);
         bool active;
         const int i = um.unit(dim, active);
-        if (active) store(pv.buf_ptr[uni(e[ST_BUF])] + ((size_t)t * N + n) * dim + i, s[uni(e[ST_SLOT])]);
+        if (active) store(((cbufs_t)pv.buf_ptr)[uni(e[ST_BUF])] + ((size_t)t * N + n) * dim + i, s[uni(e[ST_SLOT])]);
     }
 }
 

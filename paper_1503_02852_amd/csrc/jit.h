@@ -1,0 +1,26 @@
+// Run-time specialisation of the persistent recurrent-step kernel (see jit.cpp).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+
+#include "kernels.h"
+#include "plan.h"
+#include "step_layout.h"
+
+namespace rnng {
+
+// HIP source of the step kernel specialised for one component and direction.
+std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, int NB);
+// Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
+// compile fails (the log, if any, goes to *log).  Needs no GPU.
+bool jit_compile(const std::string& source, std::string* log);
+// Loaded kernel for the source, or nullptr (then the interpreted kernel is used).
+hipFunction_t jit_step_function(const std::string& source);
+void jit_mark_failed(const std::string& source);
+hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream);
+
+void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
+                    unsigned* ctrl, int T, int N, bool backward, int spin_limit);
+
+}  // namespace rnng

@@ -65,6 +65,7 @@ struct StepLaunchPlan {
 };
 // Chooses the number of workgroups for a component's step descriptor; ok = false if the
 // component does not fit the kernel's limits (then the caller steps with per-frame launches).
+int step_nb_for(int N);   // streams per pass of the step kernel for N streams (0: not supported)
 bool plan_step_launch(const int32_t* words, int desc_off, int N, int force_G, StepLaunchPlan& out);
 hipError_t launch_recurrent_steps(const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
                                   unsigned* ctrl, int T, int N, bool backward, int spin_limit, hipStream_t stream);

@@ -17,7 +17,11 @@
 // with eps of a multiplicative destination carrying the product of that destination's other
 // incoming connection outputs (Section 2.2).
 #pragma once
+#if !defined(__HIPCC_RTC__)
 #include <cstdint>
+#else
+typedef signed int int32_t;   // the run-time compiler has no <cstdint>
+#endif
 
 namespace rnng {
 
@@ -61,6 +65,16 @@ enum { MVE_W_OFF = 0, MVE_KLEN, MVE_TRANSPOSED, MVE_SRC_BUF, MVE_FRAME_OFF, MVE_
 //   [dim, out_off, n_factors, factors...], factor = [buf, frame_off, w_off]
 enum { CS_DIM = 0, CS_OUT_OFF, CS_NFACTORS, CS_HEADER_WORDS };
 enum { CF_BUF = 0, CF_FRAME_OFF, CF_W_OFF, CF_WORDS };
+
+// Plan words and the buffer table never change while a kernel runs: device code reads them
+// through the constant address space, which makes uniform reads scalar loads.
+#if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC_RTC__)
+#define RNNG_CONST_AS __attribute__((address_space(4)))
+#else
+#define RNNG_CONST_AS
+#endif
+typedef const RNNG_CONST_AS int32_t* cwords_t;
+typedef float* const RNNG_CONST_AS* cbufs_t;
 
 // Device view of the plan tables.
 struct PlanView {

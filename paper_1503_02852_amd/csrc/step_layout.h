@@ -7,11 +7,13 @@
 // each served by L consecutive lanes that split the contraction; a lane's weights are stored
 // lane-major ([edge][j][thread][4 floats]) so every ds_read_b128 of a wavefront is contiguous.
 #pragma once
+#if !defined(__HIPCC_RTC__)
 #include <cstdint>
+#endif
 
 #include "program.h"
 
-#if defined(__HIPCC__)
+#if defined(__HIPCC__) || defined(__HIPCC_RTC__)
 #define RNNG_HD __host__ __device__
 #else
 #define RNNG_HD
@@ -45,6 +47,14 @@ struct StepLayout {
     int n_phases, n_sources, total_floats;
     StepPhase ph[STEP_MAX_PHASES];
     StepSource src[STEP_MAX_SOURCES];
+};
+
+struct StepArgs {
+    float* const* buf_ptr;                   // buffer table (read-only for the kernel's lifetime)
+    const int32_t* words;                    // plan words (likewise)
+    const float* weights;
+    unsigned* ctrl;                          // [0]: set to 1 when a wait ran into the spin limit
+    int desc_off, T, N, backward, G, xcd_stride, spin_limit;
 };
 
 RNNG_HD inline int step_pow2_floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
