@@ -145,6 +145,12 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream);
  * interpreting build of the same kernel; RNNG_JIT=0 in the environment forces that. */
 int rnn_specialise(rnn_graph* g, int32_t N);
 
+/* Debugging aid: synchronises the device and copies the first `bytes` (at most 1024) of the
+ * workspace's control-word area to HOST memory: E_total (double) at byte 0, the step kernels'
+ * wait-limit flag (uint32) at byte 16, and, if the step kernels were built with RNNG_STEP_TRACE=1
+ * in the environment, 64 cycle stamps (uint64) at byte 80. */
+int rnn_debug_read_control(rnn_graph* g, void* out, int32_t bytes);
+
 /* Kernel-class timing for benchmarks: HIP events are recorded on the call's stream around the
  * launches of every class whose bit is set in class_mask (0 switches timing off; it is off by
  * default and costs nothing then).  rnn_profile_read waits for the recorded events, stores the

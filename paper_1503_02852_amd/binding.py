@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(_HERE, "librnngraph.so")
 
 EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_param_count",
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
-           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_specialise", "rnn_profile_enable",
+           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_specialise", "rnn_debug_read_control",
+           "rnn_profile_enable",
            "rnn_profile_read",
            "rnn_last_error"]
 
@@ -65,6 +66,8 @@ def load_library(build_if_missing=True):
     lib.rnn_grads.restype = C.c_int
     lib.rnn_specialise.argtypes = [vp, C.c_int32]
     lib.rnn_specialise.restype = C.c_int
+    lib.rnn_debug_read_control.argtypes = [vp, vp, C.c_int32]
+    lib.rnn_debug_read_control.restype = C.c_int
     lib.rnn_profile_enable.argtypes = [vp, C.c_int32]
     lib.rnn_profile_enable.restype = C.c_int
     lib.rnn_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), i64p]
@@ -187,6 +190,11 @@ class Graph:
 
     def specialise(self, N):
         return _check(self.lib.rnn_specialise(self.handle, N))
+
+    def debug_read_control(self, nbytes=1024):
+        buf = (C.c_ubyte * nbytes)()
+        _check(self.lib.rnn_debug_read_control(self.handle, buf, nbytes))
+        return bytes(buf)
 
     def profile_enable(self, class_mask):
         _check(self.lib.rnn_profile_enable(self.handle, class_mask))

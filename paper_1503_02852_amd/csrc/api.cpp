@@ -120,12 +120,30 @@ struct rnn_graph {
     unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
     int force_step_G = 0;
     bool use_jit = true;
-    std::map<int, std::string> jit_sources;   // key: component * 32 + backward * 16 + NB
-    const std::string& jit_source(int comp, bool backward, int NB) {
-        const int key = comp * 32 + (backward ? 16 : 0) + NB;
-        auto it = jit_sources.find(key);
-        if (it == jit_sources.end()) it = jit_sources.emplace(key, jit_step_source(plan, plan.comps[comp], backward, NB)).first;
-        return it->second;
+    // Run-time specialised step kernels, chosen once per (component, direction, stream count).
+    struct JitChoice { bool wave = false; StepLaunchPlan lp; std::string source; };
+    std::map<long long, JitChoice> jit_choices;
+    const JitChoice& jit_choice(int comp, bool backward, int N) {
+        const long long key = ((long long)comp * 2 + (backward ? 1 : 0)) * 4096 + N;
+        auto it = jit_choices.find(key);
+        if (it != jit_choices.end()) return it->second;
+        JitChoice c;
+        const CompPlan& cp = plan.comps[comp];
+        // 1. wave-autonomous variant: weights in registers, no barriers (single-phase components)
+        const int wave_G[6] = {32, 64, 128, 256, 16, 8};
+        for (int i = 0; i < 6 && c.source.empty(); ++i) {
+            const int G = force_step_G > 0 ? force_step_G : wave_G[i];
+            c.source = jit_wave_source(plan, cp, backward, N, G);
+            if (!c.source.empty()) {
+                c.wave = true; c.lp.ok = true; c.lp.G = G; c.lp.NB = step_nb_for(N); c.lp.lds_bytes = 0;
+                c.lp.xcd_stride = G <= 32 ? 8 : 1;
+            }
+            if (force_step_G > 0) break;
+        }
+        // 2. LDS-resident variant
+        if (c.source.empty() && plan_step_launch(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, N, force_step_G, c.lp))
+            c.source = jit_step_source(plan, cp, backward, c.lp.NB);
+        return jit_choices.emplace(key, c).first->second;
     }
 };
 
@@ -196,13 +214,15 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
         const int spin_limit = 1 << 22;
         hipError_t e = hipErrorUnknown;
         if (g->use_jit) {
-            // component-specialised build of the same kernel; the interpreted build is the fallback
-            const std::string& src = g->jit_source(comp, backward, lp.NB);
-            if (hipFunction_t fn = jit_step_function(src)) {
-                StepArgs a;
-                fill_step_args(a, pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit);
-                e = jit_launch(fn, a, lp, s);
-                if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(src); }
+            // component-specialised build of the kernel; the interpreting build below is the fallback
+            const rnn_graph::JitChoice& jc = g->jit_choice(comp, backward, N);
+            if (!jc.source.empty()) {
+                if (hipFunction_t fn = jit_step_function(jc.source)) {
+                    StepArgs a;
+                    fill_step_args(a, pv, jc.lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit);
+                    e = jit_launch(fn, a, jc.lp, s);
+                    if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(jc.source); }
+                }
             }
         }
         if (e != hipSuccess) e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, s);
@@ -463,12 +483,24 @@ int rnn_specialise(rnn_graph* g, int32_t N) {
         for (int backward = 0; backward < 2; ++backward) {
             if (backward ? !cp.has_bwd_program : !cp.has_fwd_program) continue;
             std::string log;
-            if (!jit_compile(g->jit_source((int)c, backward != 0, NB), &log))
+            const rnn_graph::JitChoice& jc = g->jit_choice((int)c, backward != 0, N);
+            if (jc.source.empty()) continue;
+            if (!jit_compile(jc.source, &log))
                 return fail(RNN_ERR_DEVICE, "step kernel specialisation failed: " + log);
             ++n;
         }
     }
     return n;
+}
+
+int rnn_debug_read_control(rnn_graph* g, void* out, int32_t bytes) {
+    if (!g || !out) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (!g->ws) return fail(RNN_ERR_SEQUENCE, "no window yet");
+    if (bytes <= 0 || bytes > (int32_t)SYNC_BYTES) return fail(RNN_ERR_INVALID_ARGUMENT, "at most 1024 bytes");
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(out, g->ws + g->layout.sync_off, (size_t)bytes, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(e, "control word read-back");
+    return RNN_OK;
 }
 
 int rnn_profile_enable(rnn_graph* g, int32_t class_mask) {

@@ -78,30 +78,51 @@ void emit_ops(std::ostringstream& o, const int32_t* pw) {
 
 }  // namespace
 
+namespace {
+
+void emit_phase_descriptor(std::ostringstream& o, const Plan& P, const PhasePlan& ph, int p, int acc_phase) {
+    const int32_t* pw = &P.words[ph.prog_off];
+    const int ng = pw[PG_NGATHER], ni = pw[PG_NINV], nops = pw[PG_NOPS], nst = pw[PG_NSTORES];
+    o << "struct PH" << p << " {\n";
+    o << "    static constexpr int P = " << p << ", NG = " << ng << ", NI = " << ni << ", NST = " << nst
+      << ", HAS_TASKS = " << (ph.mv_off >= 0 ? 1 : 0) << ", ACC_PHASE = " << acc_phase << ";\n";
+    auto gw = [&](int g, int field) { return pw[PG_HEADER_WORDS + g * GA_WORDS + field]; };
+    auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases) {
+        o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
+        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
+        o << "            default: return 0;\n        }\n    }\n";
+    };
+    std::vector<std::pair<int, int>> kinds, auxs, sidx, cidx, sgather;
+    int ns = 0, nc = 0;
+    for (int g = 0; g < ng; ++g) {
+        const int kind = gw(g, GA_KIND);
+        kinds.push_back({g, kind});
+        if (kind == GA_KIND_CARRY) { auxs.push_back({g, gw(g, GA_AUX)}); cidx.push_back({g, nc++}); }
+        if (kind == GA_KIND_ACC) auxs.push_back({g, gw(g, GA_FRAME_OFF)});   // index of the task in its phase
+        if (kind == GA_KIND_STATIC) { sidx.push_back({g, ns}); sgather.push_back({ns, g}); ++ns; }
+    }
+    o << "    static constexpr int NS = " << ns << ", NC = " << nc << ";\n";
+    emit_switch("gkind", "g", kinds); emit_switch("gaux", "g", auxs); emit_switch("sidx", "g", sidx);
+    emit_switch("cidx", "g", cidx); emit_switch("sgather", "si", sgather);
+    const int32_t* st = pw + PG_HEADER_WORDS + ng * GA_WORDS + ni * IV_WORDS + nops * MO_WORDS;
+    std::vector<std::pair<int, int>> slots;
+    for (int q = 0; q < nst; ++q) slots.push_back({q, st[q * ST_WORDS + ST_SLOT]});
+    emit_switch("stslot", "q", slots);
+    o << "    static __device__ __forceinline__ void ops(float* s) {\n";
+    emit_ops(o, pw);
+    o << "    }\n};\n";
+}
+
+}  // namespace
+
 std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, int NB) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     int acc_phase = 0;
     for (size_t p = 0; p < phases.size(); ++p) {
-        const PhasePlan& ph = phases[p];
-        const int32_t* pw = &P.words[ph.prog_off];
-        const int ng = pw[PG_NGATHER], ni = pw[PG_NINV], nops = pw[PG_NOPS], nst = pw[PG_NSTORES];
-        if (ph.mv_off >= 0) acc_phase = (int)p;
-        o << "struct PH" << p << " {\n";
-        o << "    static constexpr int P = " << p << ", NG = " << ng << ", NI = " << ni << ", NST = " << nst
-          << ", HAS_TASKS = " << (ph.mv_off >= 0 ? 1 : 0) << ", ACC_PHASE = " << acc_phase << ";\n";
-        o << "    static __device__ __forceinline__ constexpr int gkind(int g) {\n        switch (g) {\n";
-        for (int g = 0; g < ng; ++g)
-            if (pw[PG_HEADER_WORDS + g * GA_WORDS + GA_KIND] == GA_KIND_ACC) o << "            case " << g << ": return 1;\n";
-        o << "            default: return 0;\n        }\n    }\n";
-        const int32_t* st = pw + PG_HEADER_WORDS + ng * GA_WORDS + ni * IV_WORDS + nops * MO_WORDS;
-        o << "    static __device__ __forceinline__ constexpr int stslot(int q) {\n        switch (q) {\n";
-        for (int q = 0; q < nst; ++q) o << "            case " << q << ": return " << st[q * ST_WORDS + ST_SLOT] << ";\n";
-        o << "            default: return 0;\n        }\n    }\n";
-        o << "    static __device__ __forceinline__ void ops(float* s) {\n";
-        emit_ops(o, pw);
-        o << "    }\n};\n";
+        if (phases[p].mv_off >= 0) acc_phase = (int)p;
+        emit_phase_descriptor(o, P, phases[p], (int)p, acc_phase);
     }
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
@@ -111,13 +132,87 @@ std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, in
          "    if (w < 0) return;\n"
          "    const int tid = threadIdx.x;\n";
     for (size_t p = 0; p < phases.size(); ++p)
-        o << "    PhaseRegs<PH" << p << "> r" << p << "; phase_setup<PH" << p << ", " << NB << ">(r" << p << ", a, sh, w, tid);\n";
-    o << "    bool dead = false;\n"
+        o << "    PhaseRegs<PH" << p << "> r" << p << "; phase_setup<PH" << p << ", " << NB << ">(r" << p << ", a, sh, lds, w, tid);\n";
+    o << "    __syncthreads();\n"
+         "    bool dead = false;\n"
          "    for (int step = 0; step < a.T; ++step) {\n"
          "        const int t = a.backward ? a.T - 1 - step : step;\n";
     for (size_t p = 0; p < phases.size(); ++p)
-        o << "        phase_step<PH" << p << ", " << NB << ", " << phases.size() << ">(r" << p << ", a, sh, lds, t, tid, dead);\n";
+        o << "        phase_step<PH" << p << ", " << NB << ", " << phases.size() << ">(r" << p << ", a, sh, lds, step, t, tid, dead);\n";
     o << "    }\n}\n";
+    return o.str();
+}
+
+// Wave-autonomous variant: single-phase components whose weight rows fit the register file.
+// Returns an empty string if the component (with G workgroups and N streams) is not eligible.
+std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G) {
+    const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
+    const int NB = step_nb_for(N);
+    if (phases.size() != 1 || NB == 0) return "";
+    StepLayout lay;
+    compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, NB, N, lay);
+    if (!lay.ok) return "";
+    const StepPhase& ph = lay.ph[0];
+    const int UW = (ph.item_chunk + 3) / 4;
+    if (UW * NB > 8) return "";
+    std::vector<int> F(lay.n_sources), xoff(lay.n_sources);
+    int XF = 0;
+    for (int s = 0; s < lay.n_sources; ++s) { F[s] = (lay.src[s].k_len + 63) / 64; xoff[s] = XF; XF += F[s]; }
+    if (XF * NB > 96) return "";
+    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 16 || NB * 64 * F[s] > 8 * 256) return "";
+    int per_unit = 0;
+    for (int t = 0; t < ph.n_tasks; ++t) for (int e = 0; e < ph.task[t].n_edges; ++e) per_unit += F[ph.task[t].e[e].src];
+    const int RW = UW * per_unit;
+    if (RW > 384) return "";
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    emit_phase_descriptor(o, P, phases[0], 0, 0);
+    auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases) {
+        o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
+        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
+        o << "            default: return 0;\n        }\n    }\n";
+    };
+    o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
+      << ", RW = " << RW << ", XF = " << XF << ";\n";
+    std::vector<std::pair<int, int>> ne, es, fs, xo, wo;
+    for (int t = 0; t < ph.n_tasks; ++t) {
+        ne.push_back({t, ph.task[t].n_edges});
+        for (int e = 0; e < ph.task[t].n_edges; ++e) es.push_back({t * STEP_MAX_EDGES + e, ph.task[t].e[e].src});
+    }
+    for (int s = 0; s < lay.n_sources; ++s) { fs.push_back({s, F[s]}); xo.push_back({s, xoff[s]}); }
+    int woff = 0;
+    for (int ul = 0; ul < UW; ++ul)
+        for (int t = 0; t < ph.n_tasks; ++t)
+            for (int e = 0; e < ph.task[t].n_edges; ++e) {
+                wo.push_back({(ul * (ph.n_tasks > 0 ? ph.n_tasks : 1) + t) * STEP_MAX_EDGES + e, woff});
+                woff += F[ph.task[t].e[e].src];
+            }
+    emit_switch("nedges", "task", ne); emit_switch("esrc_", "key", es); emit_switch("F", "s", fs);
+    emit_switch("xoff", "s", xo); emit_switch("woff_", "key", wo);
+    o << "    static __device__ __forceinline__ constexpr int esrc(int task, int e) { return esrc_(task * " << STEP_MAX_EDGES << " + e); }\n";
+    o << "    static __device__ __forceinline__ constexpr int woff(int ul, int task, int e) { return woff_((ul * "
+      << (ph.n_tasks > 0 ? ph.n_tasks : 1) << " + task) * " << STEP_MAX_EDGES << " + e); }\n};\n";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    __shared__ StepShared sh;\n"
+         "    __shared__ float ring_all[4][WaveRing<PH0, MV, " << NB << ">::FLOATS];\n"
+         "    __shared__ __attribute__((aligned(16))) float xs_all[2 * GroupX<MV, " << NB << ">::FLOATS];\n"
+         "    const int w = wave_prologue<MV, " << NB << ">(a, sh);\n"
+         "    if (w < 0) return;\n"
+         "    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n"
+         "    const bool has_units = wave * MV::UW < sh.lay.ph[0].item_chunk;   // else: only helps polling\n"
+         "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
+         "    float* ring = ring_all[wave];\n"
+         "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", true>(r0, a, sh, nullptr, w, tid);\n"
+         "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
+         "    WaveRing<PH0, MV, " << NB << "> rg; wave_ring_setup<PH0, MV, " << NB << ">(rg, a, sh, w, tid);\n"
+         "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, 0, 0, lane);\n"
+         "    __syncthreads();\n"
+         "    bool dead = false;\n"
+         "    for (int step = 0; step < a.T; ++step) {\n"
+         "        const int t = a.backward ? a.T - 1 - step : step;\n"
+         "        wave_step<PH0, MV, " << NB << ">(r0, wv, rg, a, ring, xs_all, has_units, step, t, tid, dead);\n"
+         "    }\n}\n";
     return o.str();
 }
 
@@ -127,6 +222,11 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     if (it != g_cache.end()) return !it->second.failed;
     CacheEntry& ce = g_cache[source];
     ce.failed = true;
+    if (const char* dump = std::getenv("RNNG_JIT_DUMP")) {   // debugging aid: keep the generated sources
+        static int counter = 0;
+        const std::string path = std::string(dump) + "/rnng_step_jit_" + std::to_string(counter++) + ".hip";
+        if (FILE* f = std::fopen(path.c_str(), "w")) { std::fwrite(source.data(), 1, source.size(), f); std::fclose(f); }
+    }
     g_rtc.load();
     if (!g_rtc.ok) { if (log_out) *log_out = "libhiprtc.so could not be loaded"; return false; }
     const char* header_src[3] = {RNNG_SRC_program_h, RNNG_SRC_step_layout_h, RNNG_SRC_step_device_h};
@@ -136,9 +236,10 @@ bool jit_compile(const std::string& source, std::string* log_out) {
         if (log_out) *log_out = "hiprtcCreateProgram failed";
         return false;
     }
-    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
-                          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-    const hiprtcResult r = g_rtc.compile(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
+    std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
+                                     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    if (const char* env = std::getenv("RNNG_STEP_TRACE")) if (std::atoi(env) != 0) opts.push_back("-DRNNG_STEP_TRACE=1");
+    const hiprtcResult r = g_rtc.compile(prog, (int)opts.size(), opts.data());
     size_t ls = 0;
     g_rtc.log_size(prog, &ls);
     if (ls > 1 && log_out) { log_out->assign(ls, '\0'); g_rtc.log(prog, &(*log_out)[0]); }
@@ -162,6 +263,7 @@ hipFunction_t jit_step_function(const std::string& source) {
     if (hipModuleGetFunction(&ce.fn, ce.module, "rnng_step_jit") != hipSuccess) { ce.failed = true; ce.fn = nullptr; return nullptr; }
     // more than 64 KiB of dynamic LDS needs an opt-in; an error here surfaces at launch
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ce.fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)STEP_LDS_LIMIT);
+    (void)hipGetLastError();   // a refusal must not linger as the thread's last error
     return ce.fn;
 }
 

@@ -12,6 +12,8 @@ namespace rnng {
 
 // HIP source of the step kernel specialised for one component and direction.
 std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, int NB);
+// Same for the wave-autonomous variant with G workgroups; empty if the component is not eligible.
+std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G);
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
 // compile fails (the log, if any, goes to *log).  Needs no GPU.
 bool jit_compile(const std::string& source, std::string* log);

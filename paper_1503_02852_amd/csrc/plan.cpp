@@ -26,6 +26,8 @@ struct OpH {
     int post = POST_NONE, dim = 0, out_buf = -1, pre_buf = -1, bias_off = -1, acc_buf = -1, acc_task = 0,
         deriv_buf = -1, out_slot = -1;
     bool new_program = false;   // must not share a program with the operation before it
+    bool pre_static = false;    // pre_buf was written before the step loop (batched GEMM), not by an earlier part
+    bool partial_out = false;   // out_buf holds a partial sum, not the layer's value
     std::vector<TermH> terms;
 };
 struct MvEdgeH { int w_off, k_len, transposed, src_buf, frame_off; };
@@ -33,6 +35,12 @@ struct MvTaskH { int n_out, acc_buf; std::vector<MvEdgeH> edges; };
 
 // Lowers a list of node operations (each a sum of products of factors, then an activation or
 // a derivative factor) to the straight-line slot program described in program.h.
+// What a program's loads may assume about its component's step loop.
+struct EmitCtx {
+    const std::vector<char>* written = nullptr;   // per buffer: written during this component's step loop
+    int step_dir = 0;                             // -1 forward, +1 backward: frame offset of "the previous step"; 0: not stepped
+};
+
 struct Lowering {
     std::vector<std::array<int, 4>> gathers;   // buf, frame_off, dim, kind
     std::vector<std::array<int, 2>> invs;      // w_off, dim
@@ -51,7 +59,7 @@ struct Lowering {
 
 // Returns the word offset of the program, or -1 (with err set) if it needs too many slots.
 int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int first, int last,
-                 const std::vector<int>& buf_dim, int& max_dim, bool dry_run) {
+                 const std::vector<int>& buf_dim, int& max_dim, bool dry_run, const EmitCtx* ctx = nullptr) {
     // results of operations outside [first, last) are read back from their buffers
     std::vector<OpH> ops(all_ops.begin() + first, all_ops.begin() + last);
     for (OpH& o : ops)
@@ -117,7 +125,20 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
     h[PG_NGATHER] = ng; h[PG_NINV] = ni; h[PG_NOPS] = (int)mops.size(); h[PG_NSTORES] = (int)stores.size();
     h[PG_MAXDIM] = max_dim; h[PG_NSLOTS] = n_slots;
     w.insert(w.end(), h, h + PG_HEADER_WORDS);
-    for (auto& g : L.gathers) w.insert(w.end(), g.begin(), g.end());
+    for (auto& g : L.gathers) {
+        int kind = g[3], aux = 0;
+        if (kind == GA_KIND_FRAMES && ctx && ctx->step_dir != 0) {
+            const int buf = g[0], off = g[1];
+            if (!(*ctx->written)[buf]) kind = GA_KIND_STATIC;
+            else {
+                for (size_t r = 0; r < ops.size(); ++r) {
+                    if (off == 0 && ops[r].pre_buf == buf && ops[r].pre_static) { kind = GA_KIND_STATIC; break; }
+                    if (off == ctx->step_dir && ops[r].out_buf == buf && !ops[r].partial_out) { kind = GA_KIND_CARRY; aux = res0 + (int)r; break; }
+                }
+            }
+        }
+        w.push_back(g[0]); w.push_back(g[1]); w.push_back(g[2]); w.push_back(kind); w.push_back(aux);
+    }
     for (auto& v : L.invs) w.insert(w.end(), v.begin(), v.end());
     for (auto& m : mops) w.insert(w.end(), m.begin(), m.end());
     for (auto& st : stores) w.insert(w.end(), st.begin(), st.end());
@@ -163,7 +184,7 @@ bool split_wide_ops(std::vector<OpH>& ops, const std::vector<int>& part_bufs, co
         if (op_fits(o, buf_dim, 0)) { new_index[r] = (int)out.size(); out.push_back(o); continue; }
         const int pb = part_bufs[r];
         buf_alloc[pb] = 1;
-        OpH cur = o; cur.terms.clear(); cur.post = POST_NONE; cur.deriv_buf = -1; cur.out_buf = pb;
+        OpH cur = o; cur.terms.clear(); cur.post = POST_NONE; cur.deriv_buf = -1; cur.out_buf = pb; cur.partial_out = true;
         for (const TermH& t : o.terms) {
             OpH trial = cur; trial.terms.push_back(t);
             if (op_fits(trial, buf_dim, 2)) { cur = trial; continue; }
@@ -172,13 +193,13 @@ bool split_wide_ops(std::vector<OpH>& ops, const std::vector<int>& part_bufs, co
                 return false;
             }
             out.push_back(cur);
-            cur = OpH(); cur.dim = o.dim; cur.pre_buf = pb; cur.out_buf = pb; cur.new_program = true; cur.terms.push_back(t);
+            cur = OpH(); cur.dim = o.dim; cur.pre_buf = pb; cur.out_buf = pb; cur.new_program = true; cur.partial_out = true; cur.terms.push_back(t);
             if (!op_fits(cur, buf_dim, 2)) {
                 err = "a connection into a multiplicative layer has too many sibling connections for one step program";
                 return false;
             }
         }
-        cur.post = o.post; cur.deriv_buf = o.deriv_buf; cur.out_buf = o.out_buf;
+        cur.post = o.post; cur.deriv_buf = o.deriv_buf; cur.out_buf = o.out_buf; cur.partial_out = false;
         new_index[r] = (int)out.size();
         out.push_back(cur);
     }
@@ -194,8 +215,10 @@ bool split_wide_ops(std::vector<OpH>& ops, const std::vector<int>& part_bufs, co
 // operations together need more slots than a thread holds.  The matrix-vector tasks go with
 // the first part (their sources never depend on this phase's own results).
 bool emit_phase(Plan& P, std::vector<PhasePlan>& out, const std::vector<MvTaskH>& tasks, std::vector<OpH> ops,
-                const std::vector<int>& part_bufs, std::string& err) {
+                const std::vector<int>& part_bufs, std::vector<char> written, int step_dir, std::string& err) {
     if (!split_wide_ops(ops, part_bufs, P.buf_dim, P.buf_alloc, err)) return false;
+    for (const OpH& o : ops) written[o.out_buf] = 1;
+    EmitCtx ctx; ctx.written = &written; ctx.step_dir = step_dir;
     int first = 0;
     bool first_part = true;
     const int n = (int)ops.size();
@@ -208,7 +231,7 @@ bool emit_phase(Plan& P, std::vector<PhasePlan>& out, const std::vector<MvTaskH>
         while (last < n && !ops[last].new_program && emit_program(P.words, ops, first, last + 1, P.buf_dim, md, true) == 0) ++last;
         PhasePlan ph;
         if (first_part && !tasks.empty()) { ph.mv_off = emit_matvecs(P.words, tasks, ph.mv_max_out); ph.n_mv_tasks = (int)tasks.size(); }
-        ph.prog_off = emit_program(P.words, ops, first, last, P.buf_dim, ph.max_dim, false);
+        ph.prog_off = emit_program(P.words, ops, first, last, P.buf_dim, ph.max_dim, false, &ctx);
         out.push_back(ph);
         first = last; first_part = false;
     }
@@ -327,7 +350,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                 for (int m : in_e[k]) {
                     const GEdge& e = xe[m];
                     if (e.wkind == W_FULL) {
-                        if (S.edge_class[m] == EDGE_BATCHED) o.pre_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k);
+                        if (S.edge_class[m] == EDGE_BATCHED) { o.pre_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k); o.pre_static = true; }
                         else {
                             task.edges.push_back(MvEdgeH{(int)full_off(m), xn[e.src].dim, 0, P.ybuf(e.src), -e.delay});
                             cp.step_weight_floats += (int64_t)xn[k].dim * xn[e.src].dim;
@@ -345,7 +368,9 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             }
             std::vector<int> part_bufs;
             for (int k : np) part_bufs.push_back(P.pbuf(k));
-            if (!emit_phase(P, cp.fwd_phases, tasks, ops, part_bufs, err)) return false;
+            std::vector<char> written(P.n_bufs, 0);
+            for (int k : members) written[P.ybuf(k)] = 1;
+            if (!emit_phase(P, cp.fwd_phases, tasks, ops, part_bufs, written, cp.recurrent ? -1 : 0, err)) return false;
         }
         cp.has_fwd_program = true;
         auto emit_desc = [&](const std::vector<PhasePlan>& phs) {
@@ -381,7 +406,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     const GEdge& e = xe[m];
                     const int k = e.dst;
                     if (e.wkind == W_FULL) {
-                        if (S.edge_class[m] == EDGE_BATCHED) o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j);
+                        if (S.edge_class[m] == EDGE_BATCHED) { o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); o.pre_static = true; }
                         else task.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
                         continue;
                     }
@@ -399,7 +424,9 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             }
             std::vector<int> part_bufs;
             for (int j : np) part_bufs.push_back(P.qbuf(j));
-            if (!emit_phase(P, cp.bwd_phases, tasks, ops, part_bufs, err)) return false;
+            std::vector<char> written(P.n_bufs, 0);
+            for (int k : members) written[P.dbuf(k)] = 1;
+            if (!emit_phase(P, cp.bwd_phases, tasks, ops, part_bufs, written, cp.recurrent ? 1 : 0, err)) return false;
         }
         cp.has_bwd_program = true;
         cp.bwd_desc_off = emit_desc(cp.bwd_phases);

@@ -39,8 +39,17 @@ enum {
 
 // Program header, then gather entries, inv entries, ops, stores.
 enum { PG_NGATHER = 0, PG_NINV, PG_NOPS, PG_NSTORES, PG_MAXDIM, PG_NSLOTS, PG_HEADER_WORDS = 8 };
-enum { GA_BUF = 0, GA_FRAME_OFF, GA_DIM, GA_KIND, GA_WORDS };   // kind: 0 frame tensor, 1 accumulator
-enum { GA_KIND_FRAMES = 0, GA_KIND_ACC = 1 };
+enum { GA_BUF = 0, GA_FRAME_OFF, GA_DIM, GA_KIND, GA_AUX, GA_WORDS };
+// Gather kinds.  FRAMES, STATIC and CARRY all mean "buffer(t + frame_off, n, i)"; the distinction
+// only tells a step kernel how it may obtain the value:
+//   FRAMES  written by the same component during the step loop: load it coherently, this step
+//   ACC     matrix-vector accumulator (frame_off = index of the task in its phase)
+//   STATIC  not written during this component's step loop before it is read (outputs of earlier
+//           components, forward activations in the backward pass, batched pre-activations): may
+//           be loaded early and cached
+//   CARRY   the value this same program computed in the previous step (aux = its result slot):
+//           may be kept in a register instead of being re-loaded
+enum { GA_KIND_FRAMES = 0, GA_KIND_ACC = 1, GA_KIND_STATIC = 2, GA_KIND_CARRY = 3 };
 enum { IV_W_OFF = 0, IV_DIM, IV_WORDS };
 enum { MO_PACKED = 0, MO_C, MO_WORDS };                         // packed = opcode | dst << 8 | a << 16 | b << 24
 enum { ST_BUF = 0, ST_SLOT, ST_DIM, ST_FLAGS, ST_WORDS };

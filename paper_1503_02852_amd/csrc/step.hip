@@ -44,7 +44,7 @@ void recurrent_step_kernel(StepArgs a) {
                 for (int g = 0; g < STEP_MAX_GATHERS; ++g) {
                     if (g < pg.n_gather) {
                         cwords_t e = pg.ga + g * GA_WORDS;
-                        if (e[GA_KIND] == GA_KIND_FRAMES) {
+                        if (e[GA_KIND] != GA_KIND_ACC) {
                             const int dim = e[GA_DIM];
                             bool active;
                             const int i = um.unit(dim, active);

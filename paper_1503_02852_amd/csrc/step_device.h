@@ -26,11 +26,12 @@ typedef float sfloatx4 __attribute__((ext_vector_type(4)));
 typedef float sfloatx2 __attribute__((ext_vector_type(2)));
 
 
-__device__ __forceinline__ float step_sigmoid(float x) { return 1.0f / (1.0f + __expf(-x)); }
+// v_rcp_f32 / v_exp_f32 (about 1 ulp each) instead of an IEEE division: far inside the 1e-4 bar.
+__device__ __forceinline__ float step_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+// tanh without cancellation near 0: t = e^{-2|x|}; tanh|x| = (1 - t) / (1 + t).
 __device__ __forceinline__ float step_tanh(float x) {
-    const float ax = fabsf(x);
-    const float t = __expf(-2.0f * ax);
-    return copysignf((1.0f - t) / (1.0f + t), x);
+    const float t = __expf(-2.0f * fabsf(x));
+    return copysignf((1.0f - t) * __builtin_amdgcn_rcpf(1.0f + t), x);
 }
 __device__ __forceinline__ int suni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -267,7 +268,9 @@ __device__ __forceinline__ void poll_phase_sources(const StepArgs& a, const Step
 
 // ---------------------------------------------------------------------------------------------
 // Run-time specialised phases.  PH is a generated descriptor:
-//   static constexpr int P, NG, NI, NST, HAS_TASKS, ACC_PHASE; constexpr gkind(g), stslot(q);
+//   static constexpr int P, NG, NI, NST, NS, NC, HAS_TASKS, ACC_PHASE;
+//   constexpr gkind(g), gaux(g) (CARRY: result slot), sidx(g) (index among the STATIC gathers),
+//   cidx(g) (index among the CARRY gathers), sgather(si) (gather index of static si), stslot(q);
 //   static void ops(float* s)   straight-line code over the slot file.
 // Buffer ids, widths, frame offsets and weight offsets are NOT baked into the code: they are read
 // from the phase's program words at set-up, so components of equal structure share a binary.
@@ -275,18 +278,46 @@ __device__ __forceinline__ void poll_phase_sources(const StepArgs& a, const Step
 template <class PH>
 struct PhaseRegs {
     const float* gptr[PH::NG > 0 ? PH::NG : 1];   // frame-0 address of the thread's element (nullptr: idle lane)
-    long long gstride[PH::NG > 0 ? PH::NG : 1];   // floats per frame
-    int goff[PH::NG > 0 ? PH::NG : 1];            // frame offset; for accumulator entries: LDS float index
+    int gstride[PH::NG > 0 ? PH::NG : 1];         // floats per frame (uniform)
+    int goff[PH::NG > 0 ? PH::NG : 1];            // frame offset; ACC: LDS float index; STATIC with ring: index in a ring row
     float* sptr[PH::NST > 0 ? PH::NST : 1];
-    long long sstride[PH::NST > 0 ? PH::NST : 1];
+    int sstride[PH::NST > 0 ? PH::NST : 1];       // floats per frame (uniform)
     float inv[PH::NI > 0 ? PH::NI : 1];
+    float carry[PH::NC > 0 ? PH::NC : 1];
+    // loader side of the static-gather ring: this thread's (static gather, item) pairs
+    const float* pbase[STEP_PF_PAIRS_PER_THREAD];
+    long long pstride[STEP_PF_PAIRS_PER_THREAD];
+    int poff[STEP_PF_PAIRS_PER_THREAD];
+    int pf_steps, pf_shift, pf_base, pairs;
     MatvecRegs mv;
     PhaseSources src;
     int n;                                        // stream of the thread's item, -1: none
 };
 
-template <class PH, int NB>
-__device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a, const StepShared& sh, int w, int tid) {
+// Loads one block of pf_steps steps of static gather values into ring half `half`.
+template <class PH>
+__device__ __forceinline__ void ring_fill(const PhaseRegs<PH>& r, const StepArgs& a, float* lds, int first_step, int half, int tid) {
+#pragma unroll
+    for (int q = 0; q < STEP_PF_PAIRS_PER_THREAD; ++q) {
+        if (r.pbase[q] == nullptr) continue;
+        float v[STEP_PF_MAX_STEPS];
+#pragma unroll
+        for (int j = 0; j < STEP_PF_MAX_STEPS; ++j) {
+            v[j] = 0.0f;
+            const int st = first_step + j;
+            if (j < r.pf_steps && st < a.T) {
+                const int frame = (a.backward ? a.T - 1 - st : st) + r.poff[q];
+                if (frame >= 0 && frame < a.T) v[j] = r.pbase[q][frame * r.pstride[q]];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < STEP_PF_MAX_STEPS; ++j)
+            if (j < r.pf_steps) lds[r.pf_base + (half * r.pf_steps + j) * r.pairs + q * STEP_THREADS + tid] = v[j];
+    }
+}
+
+template <class PH, int NB, bool WAVE = false>
+__device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a, const StepShared& sh, float* lds, int w, int tid) {
     const StepPhase& ph = sh.lay.ph[PH::P];
     cwords_t pw = (cwords_t)a.words + suni(ph.prog_off);
     const unsigned item = sh.iteminfo[PH::P][tid];
@@ -294,20 +325,26 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
     r.n = (item >> 16) == 0xFFFF ? -1 : (int)(item >> 16);
     const int G = a.G, N = a.N;
     const StepPhase& aph = sh.lay.ph[PH::ACC_PHASE];
+    const int item_chunk = suni(ph.item_chunk), items = item_chunk * N;
+    r.pf_steps = suni(ph.pf_steps); r.pf_base = suni(ph.pf_base); r.pairs = PH::NS * items;
+    r.pf_shift = 0;
+    while ((1 << r.pf_shift) < r.pf_steps) ++r.pf_shift;
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
         cwords_t e = pw + PG_HEADER_WORDS + g * GA_WORDS;
         const int dim = e[GA_DIM];
         const int chunk = (dim + G - 1) / G, i = w * chunk + il;
         const bool active = r.n >= 0 && il < chunk && i < dim;
+        r.gstride[g] = suni(N * dim);
         if (PH::gkind(g) == GA_KIND_ACC) {
             r.gptr[g] = active ? a.weights : nullptr;   // any non-null marker
             r.goff[g] = aph.acc_base + (e[GA_FRAME_OFF] * aph.cmax + il) * NB + (r.n >= 0 ? r.n : 0);
-            r.gstride[g] = 0;
+        } else if (PH::gkind(g) == GA_KIND_STATIC && (WAVE || r.pf_steps > 0)) {
+            r.gptr[g] = active ? a.weights : nullptr;
+            r.goff[g] = PH::sidx(g) * items + (r.n >= 0 ? r.n : 0) * item_chunk + il;
         } else {
             r.gptr[g] = active ? ((cbufs_t)a.buf_ptr)[e[GA_BUF]] + (size_t)r.n * dim + i : nullptr;
             r.goff[g] = e[GA_FRAME_OFF];
-            r.gstride[g] = (long long)N * dim;
         }
     }
     cwords_t iv = pw + PG_HEADER_WORDS + PH::NG * GA_WORDS;
@@ -324,41 +361,477 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
         const int chunk = (dim + G - 1) / G, i = w * chunk + il;
         const bool active = r.n >= 0 && il < chunk && i < dim;
         r.sptr[q] = active ? ((cbufs_t)a.buf_ptr)[st[q * ST_WORDS + ST_BUF]] + (size_t)r.n * dim + i : nullptr;
-        r.sstride[q] = (long long)N * dim;
+        r.sstride[q] = suni(N * dim);
     }
+#pragma unroll
+    for (int c = 0; c < (PH::NC > 0 ? PH::NC : 1); ++c) r.carry[c] = 0.0f;
+    // ring loader pairs: pair index pi = q * 256 + tid -> (static gather si, item)
+#pragma unroll
+    for (int q = 0; q < STEP_PF_PAIRS_PER_THREAD; ++q) {
+        r.pbase[q] = nullptr; r.pstride[q] = 0; r.poff[q] = 0;
+        const int pi = q * STEP_THREADS + tid;
+        if (!WAVE && PH::NS > 0 && r.pf_steps > 0 && pi < r.pairs) {
+            const int si = pi / items, it = pi - si * items;
+            const int n2 = it / item_chunk, il2 = it - n2 * item_chunk;
+            cwords_t e = pw + PG_HEADER_WORDS + PH::sgather(si) * GA_WORDS;
+            const int dim = e[GA_DIM];
+            const int chunk = (dim + G - 1) / G, i = w * chunk + il2;
+            if (il2 < chunk && i < dim) {
+                r.pbase[q] = ((cbufs_t)a.buf_ptr)[e[GA_BUF]] + (size_t)n2 * dim + i;
+                r.pstride[q] = (long long)N * dim; r.poff[q] = e[GA_FRAME_OFF];
+            }
+        }
+    }
+    if (WAVE) return;   // the wave-autonomous variant has its own matrix-vector and ring set-up
     if (PH::HAS_TASKS) { matvec_setup<NB>(r.mv, sh, PH::P, tid); sources_setup(r.src, a, sh, PH::P); }
+    if (PH::NS > 0 && r.pf_steps > 0) ring_fill<PH>(r, a, lds, 0, 0, tid);
 }
 
+// Optional cycle stamps of one workgroup's steps 64..71 (8 stamps per step, written behind the
+// control words) for tuning; compiled in only when RNNG_STEP_TRACE is defined for the run-time build.
+#if defined(RNNG_STEP_TRACE)
+#define RNNG_STAMP(i)                                                                                       \
+    if (blockIdx.x == 0 && tid == 0 && step >= 64 && step < 72)                                             \
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[(step - 64) * 8 + (i)] = clock64()
+#else
+#define RNNG_STAMP(i)
+#endif
+
 template <class PH, int NB, int NPHASES>
-__device__ __forceinline__ void phase_step(const PhaseRegs<PH>& r, const StepArgs& a, const StepShared& sh, float* lds,
-                                           int t, int tid, bool& dead) {
+__device__ __forceinline__ void phase_step(PhaseRegs<PH>& r, const StepArgs& a, const StepShared& sh, float* lds,
+                                           int step, int t, int tid, bool& dead) {
     float s[MAX_SLOTS];
-    // 1. element-wise inputs (own units): issued first, consumed after the matrix-vector part
+    RNNG_STAMP(0);
+    const bool ring = PH::NS > 0 && r.pf_steps > 0;
+    const int js = ring ? (step & (r.pf_steps - 1)) : 0;
+    const int blk = ring ? (step >> r.pf_shift) : 0;
+    // 1. element-wise inputs (own units).  Values this program produced in the previous step come
+    //    from registers, values that do not change during the step loop from the LDS ring (loaded a
+    //    block of steps ahead); anything else is loaded coherently now and consumed after the
+    //    matrix-vector part.
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
-        if (PH::gkind(g) == GA_KIND_FRAMES) {
+        if (PH::gkind(g) == GA_KIND_CARRY) {
+            s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+        } else if (PH::gkind(g) == GA_KIND_STATIC && ring) {
+            s[g] = r.gptr[g] != nullptr ? lds[r.pf_base + ((blk & 1) * r.pf_steps + js) * r.pairs + r.goff[g]] : 0.0f;
+        } else if (PH::gkind(g) != GA_KIND_ACC) {
             const int frame = t + r.goff[g];
             float v = 0.0f;
-            if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + frame * r.gstride[g]);
+            if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) {
+                if (PH::gkind(g) == GA_KIND_STATIC) v = r.gptr[g][(long long)frame * r.gstride[g]];
+                else v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+            }
             s[g] = v;
         }
     }
 #pragma unroll
     for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+    RNNG_STAMP(1);
     if (PH::HAS_TASKS) {
         poll_sources(r.src, a, lds, t, tid, dead);
+        RNNG_STAMP(2);
         __syncthreads();
+        RNNG_STAMP(3);
         matvec_run<NB>(r.mv, lds);
+        RNNG_STAMP(4);
         __syncthreads();
     }
+    RNNG_STAMP(5);
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
         if (PH::gkind(g) == GA_KIND_ACC) s[g] = r.gptr[g] != nullptr ? lds[r.goff[g]] : 0.0f;
     PH::ops(s);
+    RNNG_STAMP(6);
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if (r.sptr[q] != nullptr) store_shared(r.sptr[q] + t * r.sstride[q], s[PH::stslot(q)]);
-    if (NPHASES > 1) __syncthreads();
+        if (r.sptr[q] != nullptr) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g)
+        if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+    RNNG_STAMP(7);
+    // at the first step of a block: fetch the next block of static values into the other ring half
+    if (ring && js == 0 && step + r.pf_steps < a.T) ring_fill<PH>(r, a, lds, step + r.pf_steps, (blk + 1) & 1, tid);
+    if (NPHASES > 1 || (ring && !PH::HAS_TASKS)) __syncthreads();
+}
+
+
+// =============================================================================================
+// Wave-autonomous variant (run-time specialised, single-phase components, few streams).
+//
+// Each wavefront owns UW units of every layer and is self-sufficient: its rows of the full
+// weight matrices live in its vector registers (a row's contraction is spread over the 64
+// lanes, F = ceil(K / 64) consecutive elements per lane), it polls the shared source vectors
+// straight into registers, reduces each row with DPP adds, and runs the element-wise program
+// for its own units on its first lanes.  There is no LDS staging of weights or vectors and no
+// workgroup barrier inside the time loop; a workgroup is just four such wavefronts on one CU.
+//
+// MV is a generated descriptor:
+//   static constexpr int NT (tasks), UW (units per wavefront), NSRC, RW (weight registers),
+//   XF (source registers per stream);  constexpr nedges(task), esrc(task, e), F(src), xoff(src),
+//   woff(ul, task, e).
+// =============================================================================================
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+#define RNNG_DPP(ctrl, rmask) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rmask, 0xf, false))
+    v += RNNG_DPP(0xB1, 0xf);    // quad_perm [1,0,3,2]
+    v += RNNG_DPP(0x4E, 0xf);    // quad_perm [2,3,0,1]
+    v += RNNG_DPP(0x141, 0xf);   // row_half_mirror
+    v += RNNG_DPP(0x140, 0xf);   // row_mirror: every lane of a 16-lane row holds the row's sum
+    v += RNNG_DPP(0x142, 0xa);   // row_bcast:15 into rows 1 and 3
+    v += RNNG_DPP(0x143, 0xc);   // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+#undef RNNG_DPP
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+constexpr int WAVE_RING_STEPS = 16;
+constexpr int WAVE_FMAX = 16;   // elements of one contraction per lane (K <= 1024)
+
+template <class MV>
+struct WaveRegs {
+    float wr[MV::RW > 0 ? MV::RW : 1];
+    const float* xsrc[MV::NSRC > 0 ? MV::NSRC : 1];    // frame 0 of each shared source vector (uniform)
+    long long xstride[MV::NSRC > 0 ? MV::NSRC : 1];    // floats per frame
+    int xfoff[MV::NSRC > 0 ? MV::NSRC : 1], xk[MV::NSRC > 0 ? MV::NSRC : 1];
+};
+
+// Layout (thread 0), item table for the wave-autonomous mapping.  Returns the part index or -1.
+template <class MV, int NB>
+__device__ __forceinline__ int wave_prologue(const StepArgs& a, StepShared& sh) {
+    int w = blockIdx.x;
+    if (a.xcd_stride > 1) {
+        if (w % a.xcd_stride) return -1;
+        w /= a.xcd_stride;
+    }
+    if (w >= a.G) return -1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) compute_step_layout(a.words, a.desc_off, a.G, NB, a.N, sh.lay);
+    const int ul = lane % MV::UW, n = lane / MV::UW;
+    sh.iteminfo[0][tid] = (unsigned)(wave * MV::UW + ul) | ((unsigned)(n < a.N ? n : 0xFFFF) << 16);
+    __syncthreads();
+    return w;
+}
+
+template <class MV>
+__device__ __forceinline__ void wave_setup(WaveRegs<MV>& wv, const StepArgs& a, const StepShared& sh, int w, int tid) {
+    const StepPhase& ph = sh.lay.ph[0];
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int s = 0; s < MV::NSRC; ++s) {
+        const StepSource& sc = sh.lay.src[s];
+        const int K = suni(sc.k_len);
+        wv.xk[s] = K; wv.xfoff[s] = suni(sc.frame_off); wv.xstride[s] = (long long)a.N * K;
+        wv.xsrc[s] = ((cbufs_t)a.buf_ptr)[suni(sc.buf)];
+    }
+#pragma unroll
+    for (int ul = 0; ul < MV::UW; ++ul) {
+#pragma unroll
+        for (int task = 0; task < MV::NT; ++task) {
+            const StepTask& tk = ph.task[task];
+            const int chunk = suni(tk.chunk), n_out = suni(tk.n_out);
+            const int ulw = wave * MV::UW + ul, u = w * chunk + ulw;
+            const bool uok = ulw < chunk && u < n_out;
+#pragma unroll
+            for (int e = 0; e < STEP_MAX_EDGES; ++e) {
+                if (e < MV::nedges(task)) {
+                    const int K = suni(tk.e[e].k_len), transposed = suni(tk.e[e].transposed);
+                    const float* W = a.weights + suni(tk.e[e].w_off);
+                    const int F = MV::F(MV::esrc(task, e));
+#pragma unroll
+                    for (int f = 0; f < WAVE_FMAX; ++f) {
+                        if (f < F) {
+                            const int k = F * lane + f;
+                            float v = 0.0f;
+                            if (uok && k < K) v = transposed ? W[(size_t)k * n_out + u] : W[(size_t)u * K + k];
+                            wv.wr[MV::woff(ul, task, e) + f] = v;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Loader side of a wavefront's private ring of STATIC gather values: pair = (static gather, item).
+template <class PH, class MV, int NB>
+struct WaveRing {
+    static constexpr int ITEMS = MV::UW * NB;
+    static constexpr int PAIRS = PH::NS * ITEMS;
+    static constexpr int QN = (PAIRS + 63) / 64;
+    static constexpr int FLOATS = 2 * WAVE_RING_STEPS * (PAIRS > 0 ? PAIRS : 1);
+    const float* pbase[QN > 0 ? QN : 1];
+    long long pstride[QN > 0 ? QN : 1];
+    int poff[QN > 0 ? QN : 1];
+};
+
+template <class PH, class MV, int NB>
+__device__ __forceinline__ void wave_ring_setup(WaveRing<PH, MV, NB>& rg, const StepArgs& a, const StepShared& sh, int w, int tid) {
+    typedef WaveRing<PH, MV, NB> RG;
+    const int lane = tid & 63, wave = tid >> 6;
+    cwords_t pw = (cwords_t)a.words + suni(sh.lay.ph[0].prog_off);
+#pragma unroll
+    for (int q = 0; q < RG::QN; ++q) {
+        rg.pbase[q] = nullptr; rg.pstride[q] = 0; rg.poff[q] = 0;
+        const int pi = q * 64 + lane;
+        if (pi < RG::PAIRS) {
+            const int si = pi / RG::ITEMS, it = pi - si * RG::ITEMS;
+            const int n2 = it / MV::UW, il2 = wave * MV::UW + (it - n2 * MV::UW);
+            cwords_t e = pw + PG_HEADER_WORDS + PH::sgather(si) * GA_WORDS;
+            const int dim = e[GA_DIM];
+            const int chunk = (dim + a.G - 1) / a.G, i = w * chunk + il2;
+            if (n2 < a.N && il2 < chunk && i < dim) {
+                rg.pbase[q] = ((cbufs_t)a.buf_ptr)[e[GA_BUF]] + (size_t)n2 * dim + i;
+                rg.pstride[q] = (long long)a.N * dim; rg.poff[q] = e[GA_FRAME_OFF];
+            }
+        }
+    }
+}
+
+template <class PH, class MV, int NB>
+__device__ __forceinline__ void wave_ring_fill(const WaveRing<PH, MV, NB>& rg, const StepArgs& a, float* ring, int first_step,
+                                               int half, int lane) {
+    typedef WaveRing<PH, MV, NB> RG;
+#pragma unroll
+    for (int q = 0; q < RG::QN; ++q) {
+        float v[WAVE_RING_STEPS];
+#pragma unroll
+        for (int j = 0; j < WAVE_RING_STEPS; ++j) {
+            v[j] = 0.0f;
+            const int st = first_step + j;
+            if (rg.pbase[q] != nullptr && st < a.T) {
+                const int frame = (a.backward ? a.T - 1 - st : st) + rg.poff[q];
+                if (frame >= 0 && frame < a.T) v[j] = rg.pbase[q][frame * rg.pstride[q]];
+            }
+        }
+        if (q * 64 + lane < RG::PAIRS) {
+#pragma unroll
+            for (int j = 0; j < WAVE_RING_STEPS; ++j) ring[(half * WAVE_RING_STEPS + j) * RG::PAIRS + q * 64 + lane] = v[j];
+        }
+    }
+    // other lanes of this wavefront read these values in later steps
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// The workgroup's four wavefronts poll the shared source vectors together (each element is
+// fetched once per workgroup, all loads of one attempt are issued before any is checked) and
+// hand them to each other through a double-buffered LDS area; one workgroup barrier per step.
+template <class MV, int NB>
+struct GroupX {
+    static constexpr int FLOATS = NB * 64 * (MV::XF > 0 ? MV::XF : 1);     // one buffer
+    static __device__ __forceinline__ constexpr int off(int s) { return NB * 64 * MV::xoff(s); }
+    static __device__ __forceinline__ constexpr int pairs_per_thread(int s) { return (NB * 64 * MV::F(s) / 2 + STEP_THREADS - 1) / STEP_THREADS; }
+    static __device__ __forceinline__ constexpr int words_per_thread(int s) { return (NB * 64 * MV::F(s) + STEP_THREADS - 1) / STEP_THREADS; }
+};
+constexpr int GROUP_MAX_LOADS = 8;   // per thread and source (N * K <= 2048 elements when K is odd, 4096 when even)
+
+template <class MV, int NB>
+__device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int t, int tid, bool& dead) {
+    typedef GroupX<MV, NB> GX;
+    unsigned long long v64[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
+    unsigned v32[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
+    int spins = 0;
+    for (;;) {
+        bool ok = true;
+#pragma unroll
+        for (int s = 0; s < MV::NSRC; ++s) {
+            const int K = wv.xk[s], total = a.N * K;
+            const int frame = t + wv.xfoff[s];
+            if (frame < 0 || frame >= a.T) continue;
+            const float* g = wv.xsrc[s] + frame * wv.xstride[s];
+            if ((K & 1) == 0) {
+#pragma unroll
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
+                    const int p = tid + STEP_THREADS * j;
+                    if (j < GX::pairs_per_thread(s) && 2 * p < total) {
+                        v64[s][j] = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(g) + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = ok && (unsigned)v64[s][j] != STEP_SENTINEL && (unsigned)(v64[s][j] >> 32) != STEP_SENTINEL;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
+                    const int p = tid + STEP_THREADS * j;
+                    if (j < GX::words_per_thread(s) && p < total) {
+                        v32[s][j] = __hip_atomic_load(reinterpret_cast<const unsigned*>(g) + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = ok && v32[s][j] != STEP_SENTINEL;
+                    }
+                }
+            }
+        }
+        if (ok || dead) break;
+        if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+    }
+#pragma unroll
+    for (int s = 0; s < MV::NSRC; ++s) {
+        const int K = wv.xk[s], total = a.N * K;
+        const int frame = t + wv.xfoff[s];
+        const bool in_window = frame >= 0 && frame < a.T;
+        float* x = xs + GX::off(s);
+        const int ROW = 64 * MV::F(s);
+        if ((K & 1) == 0) {
+#pragma unroll
+            for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
+                const int p = tid + STEP_THREADS * j;
+                if (j < GX::pairs_per_thread(s) && 2 * p < total) {
+                    int n = 0, k = 2 * p;
+                    if (NB > 1) { n = k / K; k -= n * K; }
+                    sfloatx2 o = {0.0f, 0.0f};
+                    if (in_window) { o.x = __uint_as_float((unsigned)v64[s][j]); o.y = __uint_as_float((unsigned)(v64[s][j] >> 32)); }
+                    *reinterpret_cast<sfloatx2*>(&x[n * ROW + k]) = o;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
+                const int p = tid + STEP_THREADS * j;
+                if (j < GX::words_per_thread(s) && p < total) {
+                    int n = 0, k = p;
+                    if (NB > 1) { n = k / K; k -= n * K; }
+                    x[n * ROW + k] = in_window ? __uint_as_float(v32[s][j]) : 0.0f;
+                }
+            }
+        }
+    }
+}
+
+// Sums every p[v] over the 64 lanes.  Pairs of values are folded with the lane-swap
+// instructions (upper / lower 32 lanes, then odd / even 16-lane rows), which halves the number
+// of registers per level; the last four levels are DPP adds inside the 16-lane rows.  tot[v] is
+// wave-uniform.
+template <int NV>
+__device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&tot)[NV]) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    constexpr int N32 = (NV + 1) / 2, N16 = (N32 + 1) / 2;
+    float c[N32], e[N16];
+#pragma unroll
+    for (int i = 0; i < N32; ++i) {
+        const float x = p[2 * i], y = (2 * i + 1 < NV) ? p[2 * i + 1] : p[2 * i];
+        const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+        c[i] = __uint_as_float(r.x) + __uint_as_float(r.y);     // lanes 0-31: x, lanes 32-63: y
+    }
+#pragma unroll
+    for (int j = 0; j < N16; ++j) {
+        const float x = c[2 * j], y = (2 * j + 1 < N32) ? c[2 * j + 1] : c[2 * j];
+        const u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+        float v = __uint_as_float(r.x) + __uint_as_float(r.y);  // rows: p[4j], p[4j+2], p[4j+1], p[4j+3]
+#define RNNG_DPP(ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, false))
+        v += RNNG_DPP(0xB1);
+        v += RNNG_DPP(0x4E);
+        v += RNNG_DPP(0x141);
+        v += RNNG_DPP(0x140);
+#undef RNNG_DPP
+        e[j] = v;
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int i = v / 2, row = (v % 2) * 2 + (i % 2);
+        tot[v] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, e[i / 2]), 16 * row));
+    }
+}
+
+template <class PH, class MV, int NB>
+__device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const WaveRing<PH, MV, NB>& rg,
+                                          const StepArgs& a, float* ring, float* xs_all, bool has_units, int step, int t, int tid,
+                                          bool& dead) {
+    typedef WaveRing<PH, MV, NB> RG;
+    typedef GroupX<MV, NB> GX;
+    const int lane = tid & 63;
+    float s[MAX_SLOTS];
+    RNNG_STAMP(0);
+    const int js = step & (WAVE_RING_STEPS - 1), blk = step >> 4;
+    static_assert(WAVE_RING_STEPS == 16, "blk uses a shift by 4");
+    const int ul_l = lane % MV::UW, n_l = lane / MV::UW;
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g) {
+        if (PH::gkind(g) == GA_KIND_CARRY) {
+            s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+        } else if (PH::gkind(g) == GA_KIND_STATIC) {
+            // idle lanes read a valid (unused) ring entry instead of branching around the load
+            const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
+            s[g] = ring[((blk & 1) * WAVE_RING_STEPS + js) * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
+        } else if (PH::gkind(g) == GA_KIND_FRAMES) {
+            const int frame = t + r.goff[g];
+            float v = 0.0f;
+            if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+            s[g] = v;
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+    RNNG_STAMP(1);
+    float xr[NB][MV::XF > 0 ? MV::XF : 1];
+    if (MV::NSRC > 0) {
+        float* xs = xs_all + (step & 1) * GX::FLOATS;
+        group_poll<MV, NB>(xs, wv, a, t, tid, dead);
+        __syncthreads();
+        if (!has_units) return;
+#pragma unroll
+        for (int sidx = 0; sidx < MV::NSRC; ++sidx)
+#pragma unroll
+            for (int n = 0; n < NB; ++n)
+#pragma unroll
+                for (int f = 0; f < WAVE_FMAX; ++f)
+                    if (f < MV::F(sidx)) xr[n][MV::xoff(sidx) + f] = xs[GX::off(sidx) + n * 64 * MV::F(sidx) + MV::F(sidx) * lane + f];
+    } else if (!has_units) {
+        return;
+    }
+    RNNG_STAMP(2);
+    // rows: partial dot products, cross-lane reduction, result picked by the owning item lane
+    constexpr int NV = (MV::UW * MV::NT * NB) > 0 ? (MV::UW * MV::NT * NB) : 1;
+    float part[NV], tot[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) part[v] = 0.0f;
+#pragma unroll
+    for (int ul = 0; ul < MV::UW; ++ul) {
+#pragma unroll
+        for (int task = 0; task < MV::NT; ++task) {
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                float p = 0.0f;
+#pragma unroll
+                for (int e = 0; e < STEP_MAX_EDGES; ++e) {
+                    if (e < MV::nedges(task)) {
+                        const int sidx = MV::esrc(task, e);
+#pragma unroll
+                        for (int f = 0; f < WAVE_FMAX; ++f)
+                            if (f < MV::F(sidx)) p = fmaf(wv.wr[MV::woff(ul, task, e) + f], xr[n][MV::xoff(sidx) + f], p);
+                    }
+                }
+                part[(ul * MV::NT + task) * NB + n] = p;
+            }
+        }
+    }
+    float acc[MV::NT > 0 ? MV::NT : 1];
+#pragma unroll
+    for (int task = 0; task < (MV::NT > 0 ? MV::NT : 1); ++task) acc[task] = 0.0f;
+    if (MV::NT > 0) {
+        wave_reduce_many<NV>(part, tot);
+#pragma unroll
+        for (int ul = 0; ul < MV::UW; ++ul)
+#pragma unroll
+            for (int task = 0; task < MV::NT; ++task)
+#pragma unroll
+                for (int n = 0; n < NB; ++n)
+                    if (ul_l == ul && n_l == n) acc[task] = tot[(ul * MV::NT + task) * NB + n];
+    }
+    RNNG_STAMP(3);
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g)
+        if (PH::gkind(g) == GA_KIND_ACC) s[g] = acc[PH::gaux(g)];
+    PH::ops(s);
+    RNNG_STAMP(4);
+#pragma unroll
+    for (int q = 0; q < PH::NST; ++q)
+        if (r.sptr[q] != nullptr) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g)
+        if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+    RNNG_STAMP(5);
+    if (PH::NS > 0 && js == 0 && step + WAVE_RING_STEPS < a.T)
+        wave_ring_fill<PH, MV, NB>(rg, a, ring, step + WAVE_RING_STEPS, (blk + 1) & 1, lane);
+    RNNG_STAMP(6);
+    RNNG_STAMP(7);
 }
 
 }  // namespace rnng

@@ -26,7 +26,11 @@ constexpr int STEP_MAX_PHASES = 6;
 constexpr int STEP_MAX_TASKS = 12;     // per phase
 constexpr int STEP_MAX_EDGES = 4;      // per task
 constexpr int STEP_MAX_SOURCES = 8;    // distinct (buffer, frame offset) vectors read per step
+constexpr int STEP_PF_MAX_STEPS = 16;  // steps per block of early-loaded static gather values
+constexpr int STEP_PF_PAIRS_PER_THREAD = 2;
 constexpr int STEP_MAX_GATHERS = 24;   // per program (loads are issued from an unrolled loop)
+
+RNNG_HD inline int step_pow2_floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 
 struct StepEdge { int w_off, k_len, transposed, src; };    // src = index into StepLayout::src
 struct StepTask { int n_out, chunk, n_edges; StepEdge e[STEP_MAX_EDGES]; };
@@ -38,6 +42,7 @@ struct StepPhase {
     int w_base[STEP_MAX_EDGES];          // float offset of the weight region of edge index e
     int acc_base;                        // float offset of the accumulators [slot][NB]
     int item_chunk;                      // element-wise items: local unit = tid % item_chunk, stream = tid / item_chunk
+    int n_static, pf_steps, pf_base;     // ring of early-loaded STATIC gather values: [2][pf_steps][n_static * items]
     StepTask task[STEP_MAX_TASKS];
 };
 struct StepSource { int buf, frame_off, k_len, k_pad, x_base, first_phase; };
@@ -57,7 +62,6 @@ struct StepArgs {
     int desc_off, T, N, backward, G, xcd_stride, spin_limit;
 };
 
-RNNG_HD inline int step_pow2_floor(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
 
 // words: plan words; desc_off: step descriptor; G workgroups; NB streams per pass; N streams.
 RNNG_HD inline void compute_step_layout(const int32_t* words, int desc_off, int G, int NB, int N, StepLayout& out) {
@@ -75,6 +79,18 @@ RNNG_HD inline void compute_step_layout(const int32_t* words, int desc_off, int 
         if (pg[PG_NGATHER] > STEP_MAX_GATHERS) { out.why = 2; return; }
         ph.item_chunk = (pg[PG_MAXDIM] + G - 1) / G;
         if (ph.item_chunk * N > STEP_THREADS) { out.why = 3; return; }
+        ph.n_static = 0; ph.pf_steps = 0; ph.pf_base = 0;
+        for (int g = 0; g < pg[PG_NGATHER]; ++g)
+            if (pg[PG_HEADER_WORDS + g * GA_WORDS + GA_KIND] == GA_KIND_STATIC) ++ph.n_static;
+        {
+            const int pairs = ph.n_static * ph.item_chunk * N;
+            if (pairs > 0 && pairs <= STEP_PF_PAIRS_PER_THREAD * STEP_THREADS) {
+                int st = step_pow2_floor(4096 / pairs);
+                ph.pf_steps = st < 2 ? 2 : st > STEP_PF_MAX_STEPS ? STEP_PF_MAX_STEPS : st;
+                ph.pf_base = cur; cur += 2 * ph.pf_steps * pairs;
+                cur = (cur + 3) / 4 * 4;
+            }
+        }
         if (ph.mv_off < 0) continue;
         const int32_t* w = words + ph.mv_off;
         ph.n_tasks = w[0];
