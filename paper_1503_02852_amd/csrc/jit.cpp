@@ -105,9 +105,12 @@ void emit_phase_descriptor(std::ostringstream& o, const Plan& P, const PhasePlan
     emit_switch("gkind", "g", kinds); emit_switch("gaux", "g", auxs); emit_switch("sidx", "g", sidx);
     emit_switch("cidx", "g", cidx); emit_switch("sgather", "si", sgather);
     const int32_t* st = pw + PG_HEADER_WORDS + ng * GA_WORDS + ni * IV_WORDS + nops * MO_WORDS;
-    std::vector<std::pair<int, int>> slots;
-    for (int q = 0; q < nst; ++q) slots.push_back({q, st[q * ST_WORDS + ST_SLOT]});
-    emit_switch("stslot", "q", slots);
+    std::vector<std::pair<int, int>> slots, shareds;
+    for (int q = 0; q < nst; ++q) {
+        slots.push_back({q, st[q * ST_WORDS + ST_SLOT]});
+        if (st[q * ST_WORDS + ST_FLAGS] & 1) shareds.push_back({q, 1});
+    }
+    emit_switch("stslot", "q", slots); emit_switch("stshared", "q", shareds);
     o << "    static __device__ __forceinline__ void ops(float* s) {\n";
     emit_ops(o, pw);
     o << "    }\n};\n";
@@ -206,13 +209,17 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
          "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", true>(r0, a, sh, nullptr, w, tid);\n"
          "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
          "    WaveRing<PH0, MV, " << NB << "> rg; wave_ring_setup<PH0, MV, " << NB << ">(rg, a, sh, w, tid);\n"
-         "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, 0, 0, lane);\n"
+         "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, lane);\n"
+         "    float pf[2][WaveRing<PH0, MV, " << NB << ">::QNA] = {{0.0f}};\n"
          "    __syncthreads();\n"
+         "    float dfv[PH0::NST > 0 ? PH0::NST : 1] = {0.0f};\n"
          "    bool dead = false;\n"
          "    for (int step = 0; step < a.T; ++step) {\n"
          "        const int t = a.backward ? a.T - 1 - step : step;\n"
-         "        wave_step<PH0, MV, " << NB << ">(r0, wv, rg, a, ring, xs_all, has_units, step, t, tid, dead);\n"
-         "    }\n}\n";
+         "        wave_step<PH0, MV, " << NB << ", WaveRing<PH0, MV, " << NB << ">::QNA>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, t, tid, dead);\n"
+         "    }\n"
+         "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv, a.backward ? 0 : a.T - 1);\n"
+         "}\n";
     return o.str();
 }
 

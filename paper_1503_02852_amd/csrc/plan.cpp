@@ -38,6 +38,7 @@ struct MvTaskH { int n_out, acc_buf; std::vector<MvEdgeH> edges; };
 // What a program's loads may assume about its component's step loop.
 struct EmitCtx {
     const std::vector<char>* written = nullptr;   // per buffer: written during this component's step loop
+    const std::vector<char>* shared = nullptr;    // per buffer: read by other workgroups during the step loop
     int step_dir = 0;                             // -1 forward, +1 backward: frame offset of "the previous step"; 0: not stepped
 };
 
@@ -141,7 +142,10 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
     }
     for (auto& v : L.invs) w.insert(w.end(), v.begin(), v.end());
     for (auto& m : mops) w.insert(w.end(), m.begin(), m.end());
-    for (auto& st : stores) w.insert(w.end(), st.begin(), st.end());
+    for (auto& st : stores) {
+        if (ctx && ctx->shared && (*ctx->shared)[st[0]]) st[3] |= 1;
+        w.insert(w.end(), st.begin(), st.end());
+    }
     return off;
 }
 
@@ -215,10 +219,11 @@ bool split_wide_ops(std::vector<OpH>& ops, const std::vector<int>& part_bufs, co
 // operations together need more slots than a thread holds.  The matrix-vector tasks go with
 // the first part (their sources never depend on this phase's own results).
 bool emit_phase(Plan& P, std::vector<PhasePlan>& out, const std::vector<MvTaskH>& tasks, std::vector<OpH> ops,
-                const std::vector<int>& part_bufs, std::vector<char> written, int step_dir, std::string& err) {
+                const std::vector<int>& part_bufs, std::vector<char> written, const std::vector<char>& shared, int step_dir,
+                std::string& err) {
     if (!split_wide_ops(ops, part_bufs, P.buf_dim, P.buf_alloc, err)) return false;
     for (const OpH& o : ops) written[o.out_buf] = 1;
-    EmitCtx ctx; ctx.written = &written; ctx.step_dir = step_dir;
+    EmitCtx ctx; ctx.written = &written; ctx.shared = &shared; ctx.step_dir = step_dir;
     int first = 0;
     bool first_part = true;
     const int n = (int)ops.size();
@@ -370,7 +375,9 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             for (int k : np) part_bufs.push_back(P.pbuf(k));
             std::vector<char> written(P.n_bufs, 0);
             for (int k : members) written[P.ybuf(k)] = 1;
-            if (!emit_phase(P, cp.fwd_phases, tasks, ops, part_bufs, written, cp.recurrent ? -1 : 0, err)) return false;
+            std::vector<char> shared(P.n_bufs, 0);
+            for (int k : members) if (shared_y[k]) shared[P.ybuf(k)] = 1;
+            if (!emit_phase(P, cp.fwd_phases, tasks, ops, part_bufs, written, shared, cp.recurrent ? -1 : 0, err)) return false;
         }
         cp.has_fwd_program = true;
         auto emit_desc = [&](const std::vector<PhasePlan>& phs) {
@@ -426,7 +433,9 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             for (int j : np) part_bufs.push_back(P.qbuf(j));
             std::vector<char> written(P.n_bufs, 0);
             for (int k : members) written[P.dbuf(k)] = 1;
-            if (!emit_phase(P, cp.bwd_phases, tasks, ops, part_bufs, written, cp.recurrent ? 1 : 0, err)) return false;
+            std::vector<char> shared(P.n_bufs, 0);
+            for (int k : members) if (shared_d[k]) shared[P.dbuf(k)] = 1;
+            if (!emit_phase(P, cp.bwd_phases, tasks, ops, part_bufs, written, shared, cp.recurrent ? 1 : 0, err)) return false;
         }
         cp.has_bwd_program = true;
         cp.bwd_desc_off = emit_desc(cp.bwd_phases);

@@ -52,7 +52,7 @@ enum { GA_BUF = 0, GA_FRAME_OFF, GA_DIM, GA_KIND, GA_AUX, GA_WORDS };
 enum { GA_KIND_FRAMES = 0, GA_KIND_ACC = 1, GA_KIND_STATIC = 2, GA_KIND_CARRY = 3 };
 enum { IV_W_OFF = 0, IV_DIM, IV_WORDS };
 enum { MO_PACKED = 0, MO_C, MO_WORDS };                         // packed = opcode | dst << 8 | a << 16 | b << 24
-enum { ST_BUF = 0, ST_SLOT, ST_DIM, ST_FLAGS, ST_WORDS };
+enum { ST_BUF = 0, ST_SLOT, ST_DIM, ST_FLAGS, ST_WORDS };         // flags bit 0: other workgroups poll this buffer
 
 constexpr int MAX_SLOTS = 32;     // a 32-float slot file stays in vector registers (indexed with uniform indices)
 

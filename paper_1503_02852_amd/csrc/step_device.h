@@ -557,7 +557,8 @@ struct WaveRing {
     static constexpr int ITEMS = MV::UW * NB;
     static constexpr int PAIRS = PH::NS * ITEMS;
     static constexpr int QN = (PAIRS + 63) / 64;
-    static constexpr int FLOATS = 2 * WAVE_RING_STEPS * (PAIRS > 0 ? PAIRS : 1);
+    static constexpr int QNA = QN > 0 ? QN : 1;
+    static constexpr int FLOATS = WAVE_RING_STEPS * (PAIRS > 0 ? PAIRS : 1);
     const float* pbase[QN > 0 ? QN : 1];
     long long pstride[QN > 0 ? QN : 1];
     int poff[QN > 0 ? QN : 1];
@@ -586,31 +587,45 @@ __device__ __forceinline__ void wave_ring_setup(WaveRing<PH, MV, NB>& rg, const 
     }
 }
 
-template <class PH, class MV, int NB>
-__device__ __forceinline__ void wave_ring_fill(const WaveRing<PH, MV, NB>& rg, const StepArgs& a, float* ring, int first_step,
-                                               int half, int lane) {
+// The ring holds the static values of the next WAVE_RING_STEPS steps, one row per step (row =
+// step mod WAVE_RING_STEPS).  wave_ring_load fetches this lane's pairs for one step into
+// registers, wave_ring_store puts them into that step's row; the time loop loads the row of step
+// st + WAVE_RING_STEPS right after it has consumed the row of step st and stores it two steps
+// later, so the load's latency never sits in front of a wait.
+template <class PH, class MV, int NB, int QNA>
+__device__ __forceinline__ void wave_ring_load(float (&v)[QNA],
+                                               const WaveRing<PH, MV, NB>& rg, const StepArgs& a, int st) {
     typedef WaveRing<PH, MV, NB> RG;
 #pragma unroll
     for (int q = 0; q < RG::QN; ++q) {
-        float v[WAVE_RING_STEPS];
-#pragma unroll
-        for (int j = 0; j < WAVE_RING_STEPS; ++j) {
-            v[j] = 0.0f;
-            const int st = first_step + j;
-            if (rg.pbase[q] != nullptr && st < a.T) {
-                const int frame = (a.backward ? a.T - 1 - st : st) + rg.poff[q];
-                if (frame >= 0 && frame < a.T) v[j] = rg.pbase[q][frame * rg.pstride[q]];
-            }
-        }
-        if (q * 64 + lane < RG::PAIRS) {
-#pragma unroll
-            for (int j = 0; j < WAVE_RING_STEPS; ++j) ring[(half * WAVE_RING_STEPS + j) * RG::PAIRS + q * 64 + lane] = v[j];
+        v[q] = 0.0f;
+        if (rg.pbase[q] != nullptr && st < a.T) {
+            const int frame = (a.backward ? a.T - 1 - st : st) + rg.poff[q];
+            if (frame >= 0 && frame < a.T) v[q] = rg.pbase[q][frame * rg.pstride[q]];
         }
     }
+}
+template <class PH, class MV, int NB, int QNA>
+__device__ __forceinline__ void wave_ring_store(const float (&v)[QNA],
+                                                float* ring, int st, int lane) {
+    typedef WaveRing<PH, MV, NB> RG;
+#pragma unroll
+    for (int q = 0; q < RG::QN; ++q)
+        if (q * 64 + lane < RG::PAIRS) ring[(st & (WAVE_RING_STEPS - 1)) * RG::PAIRS + q * 64 + lane] = v[q];
     // other lanes of this wavefront read these values in later steps
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// Rows of the first WAVE_RING_STEPS steps, before the time loop.
+template <class PH, class MV, int NB>
+__device__ __forceinline__ void wave_ring_fill(const WaveRing<PH, MV, NB>& rg, const StepArgs& a, float* ring, int lane) {
+    typedef WaveRing<PH, MV, NB> RG;
+    for (int st = 0; st < WAVE_RING_STEPS; ++st) {
+        float v[RG::QNA];
+        wave_ring_load<PH, MV, NB, RG::QNA>(v, rg, a, st);
+        wave_ring_store<PH, MV, NB, RG::QNA>(v, ring, st, lane);
+    }
 }
 
 // The workgroup's four wavefronts poll the shared source vectors together (each element is
@@ -662,6 +677,12 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
         if (ok || dead) break;
         if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
     }
+#if defined(RNNG_STEP_TRACE)
+    if (blockIdx.x == 0 && tid == 0 && t >= 64 && t < 72) {
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (t - 64)] = spins;
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (t - 64)] = clock64();
+    }
+#endif
 #pragma unroll
     for (int s = 0; s < MV::NSRC; ++s) {
         const int K = wv.xk[s], total = a.N * K;
@@ -730,8 +751,18 @@ __device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&t
     }
 }
 
-template <class PH, class MV, int NB>
+// Stores of values no other workgroup waits for are issued one step late (after the next step's
+// poll), so that they do not sit in front of that poll in the wavefront's memory queue.
+template <class PH, int NSTA>
+__device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA], int t_prev) {
+#pragma unroll
+    for (int q = 0; q < PH::NST; ++q)
+        if (!PH::stshared(q) && r.sptr[q] != nullptr) r.sptr[q][(long long)t_prev * r.sstride[q]] = dfv[q];
+}
+
+template <class PH, class MV, int NB, int QNA, int NSTA>
 __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const WaveRing<PH, MV, NB>& rg,
+                                          float (&pf)[2][QNA], float (&dfv)[NSTA],
                                           const StepArgs& a, float* ring, float* xs_all, bool has_units, int step, int t, int tid,
                                           bool& dead) {
     typedef WaveRing<PH, MV, NB> RG;
@@ -739,8 +770,12 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     const int lane = tid & 63;
     float s[MAX_SLOTS];
     RNNG_STAMP(0);
-    const int js = step & (WAVE_RING_STEPS - 1), blk = step >> 4;
-    static_assert(WAVE_RING_STEPS == 16, "blk uses a shift by 4");
+    const int js = step & (WAVE_RING_STEPS - 1);
+    // the row loaded two steps ago (for step - 2 + WAVE_RING_STEPS) goes into the ring now
+    if (PH::NS > 0 && has_units && step > 1) {
+        if (step & 1) wave_ring_store<PH, MV, NB, QNA>(pf[1], ring, step - 2, lane);
+        else wave_ring_store<PH, MV, NB, QNA>(pf[0], ring, step - 2, lane);
+    }
     const int ul_l = lane % MV::UW, n_l = lane / MV::UW;
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
@@ -749,7 +784,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
         } else if (PH::gkind(g) == GA_KIND_STATIC) {
             // idle lanes read a valid (unused) ring entry instead of branching around the load
             const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
-            s[g] = ring[((blk & 1) * WAVE_RING_STEPS + js) * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
+            s[g] = ring[js * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
         } else if (PH::gkind(g) == GA_KIND_FRAMES) {
             const int frame = t + r.goff[g];
             float v = 0.0f;
@@ -765,6 +800,9 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
         float* xs = xs_all + (step & 1) * GX::FLOATS;
         group_poll<MV, NB>(xs, wv, a, t, tid, dead);
         __syncthreads();
+#if defined(RNNG_STEP_TRACE)
+        if (blockIdx.x == 0 && tid == 0 && t >= 64 && t < 72) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (t - 64)] = clock64();
+#endif
         if (!has_units) return;
 #pragma unroll
         for (int sidx = 0; sidx < MV::NSRC; ++sidx)
@@ -777,6 +815,12 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
         return;
     }
     RNNG_STAMP(2);
+    // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
+    if (step > 0) wave_flush_stores<PH>(r, dfv, a.backward ? t + 1 : t - 1);
+    if (PH::NS > 0) {
+        if (step & 1) wave_ring_load<PH, MV, NB, QNA>(pf[1], rg, a, step + WAVE_RING_STEPS);
+        else wave_ring_load<PH, MV, NB, QNA>(pf[0], rg, a, step + WAVE_RING_STEPS);
+    }
     // rows: partial dot products, cross-lane reduction, result picked by the owning item lane
     constexpr int NV = (MV::UW * MV::NT * NB) > 0 ? (MV::UW * MV::NT * NB) : 1;
     float part[NV], tot[NV];
@@ -822,14 +866,14 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     PH::ops(s);
     RNNG_STAMP(4);
 #pragma unroll
-    for (int q = 0; q < PH::NST; ++q)
-        if (r.sptr[q] != nullptr) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+    for (int q = 0; q < PH::NST; ++q) {
+        if (PH::stshared(q)) { if (r.sptr[q] != nullptr) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]); }
+        else dfv[q] = s[PH::stslot(q)];
+    }
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
         if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
     RNNG_STAMP(5);
-    if (PH::NS > 0 && js == 0 && step + WAVE_RING_STEPS < a.T)
-        wave_ring_fill<PH, MV, NB>(rg, a, ring, step + WAVE_RING_STEPS, (blk + 1) & 1, lane);
     RNNG_STAMP(6);
     RNNG_STAMP(7);
 }
