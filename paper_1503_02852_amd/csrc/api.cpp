@@ -140,7 +140,18 @@ struct rnn_graph {
             }
             if (force_step_G > 0) break;
         }
-        // 2. LDS-resident variant
+        // 2. matrix-core variant for many streams: weights in LDS, MFMA, the smallest workgroup count that fits
+        if (c.source.empty() && N > 8) {
+            const int mfma_G[5] = {32, 64, 128, 256, 16};
+            for (int i = 0; i < 5 && c.source.empty(); ++i) {
+                const int G = force_step_G > 0 ? force_step_G : mfma_G[i];
+                size_t lds = 0;
+                c.source = jit_mstep_source(plan, cp, backward, N, G, &lds);
+                if (!c.source.empty()) { c.lp.ok = true; c.lp.G = G; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = G <= 32 ? 8 : 1; }
+                if (force_step_G > 0) break;
+            }
+        }
+        // 3. LDS-resident variant
         if (c.source.empty() && plan_step_launch(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, N, force_step_G, c.lp))
             c.source = jit_step_source(plan, cp, backward, c.lp.NB);
         return jit_choices.emplace(key, c).first->second;
@@ -203,32 +214,36 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
     }
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     int64_t n_launch = 0;
-    // Persistent kernel: all T steps in one launch, if the component fits its limits.
+    // Persistent kernel: all T steps in one launch.  First choice is the build specialised at run
+    // time for this component; the interpreting build serves components it cannot take or when
+    // the run-time compiler is unavailable; stepping with per-frame launches is the last resort.
     StepLaunchPlan lp;
     const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
-    if (plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp)) {
+    const rnn_graph::JitChoice* jc = g->use_jit ? &g->jit_choice(comp, backward, N) : nullptr;
+    const bool have_jit = jc && !jc->source.empty();
+    const bool have_interp = plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
+    if (have_jit || have_interp) {
         for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) {
             hipError_t e = launch_fill_sentinel(g->buf(b), (int64_t)T * N * g->plan.buf_dim[b], s);
             if (e != hipSuccess) return e;
         }
         const int spin_limit = 1 << 22;
         hipError_t e = hipErrorUnknown;
-        if (g->use_jit) {
-            // component-specialised build of the kernel; the interpreting build below is the fallback
-            const rnn_graph::JitChoice& jc = g->jit_choice(comp, backward, N);
-            if (!jc.source.empty()) {
-                if (hipFunction_t fn = jit_step_function(jc.source)) {
-                    StepArgs a;
-                    fill_step_args(a, pv, jc.lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit);
-                    e = jit_launch(fn, a, jc.lp, s);
-                    if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(jc.source); }
-                }
+        if (have_jit) {
+            if (hipFunction_t fn = jit_step_function(jc->source)) {
+                StepArgs a;
+                fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit);
+                e = jit_launch(fn, a, jc->lp, s);
+                if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(jc->source); }
             }
         }
-        if (e != hipSuccess) e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, s);
-        if (e != hipSuccess) return e;
-        g->prof.end(prof, 1, s);
-        return hipSuccess;
+        if (e != hipSuccess && have_interp)
+            e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, s);
+        if (e == hipSuccess) {
+            g->prof.end(prof, 1, s);
+            return hipSuccess;
+        }
+        if (have_interp) return e;
     }
     for (int step = 0; step < T; ++step) {
         const int t = backward ? T - 1 - step : step;
@@ -474,8 +489,7 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
 int rnn_specialise(rnn_graph* g, int32_t N) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "N must be positive");
-    const int NB = step_nb_for(N);
-    if (NB == 0 || !g->use_jit) return 0;
+    if (!g->use_jit) return 0;
     int n = 0;
     for (size_t c = 0; c < g->plan.comps.size(); ++c) {
         const CompPlan& cp = g->plan.comps[c];

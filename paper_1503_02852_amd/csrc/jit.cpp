@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "embedded_sources.h"
+#include "step_device.h"
 
 namespace rnng {
 namespace {
@@ -206,7 +207,7 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
          "    const bool has_units = wave * MV::UW < sh.lay.ph[0].item_chunk;   // else: only helps polling\n"
          "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
          "    float* ring = ring_all[wave];\n"
-         "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", true>(r0, a, sh, nullptr, w, tid);\n"
+         "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", 1>(r0, a, sh, nullptr, w, tid);\n"
          "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
          "    WaveRing<PH0, MV, " << NB << "> rg; wave_ring_setup<PH0, MV, " << NB << ">(rg, a, sh, w, tid);\n"
          "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, lane);\n"
@@ -220,6 +221,39 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
          "    }\n"
          "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv, a.backward ? 0 : a.T - 1);\n"
          "}\n";
+    return o.str();
+}
+
+// Matrix-core variant for N >= 9 streams (single-phase components).  Empty if not eligible;
+// otherwise *lds_bytes receives the dynamic LDS size.
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes) {
+    const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
+    if (phases.size() != 1 || N < 1) return "";
+    StepLayout lay;
+    compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
+    if (!lay.ok) return "";
+    MLayout ml;
+    compute_mstep_layout(lay, N, ml);
+    if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return "";
+    const int MT = (N + 15) / 16;
+    int nts_max = 1;
+    std::vector<std::pair<int, int>> nts;
+    for (int s = 0; s < ml.n_src; ++s) { const int v = (ml.rows[s] + 15) / 16; nts.push_back({s, v}); nts_max = v > nts_max ? v : nts_max; }
+    if (MT * nts_max > 16) return "";     // accumulator registers
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    emit_phase_descriptor(o, P, phases[0], 0, 0);
+    o << "struct MM {\n    static constexpr int MT = " << MT << ", NSRC = " << ml.n_src << ", NTS_MAX = " << nts_max << ";\n";
+    o << "    static __device__ __forceinline__ constexpr int nts(int s) {\n        switch (s) {\n";
+    for (auto& c : nts) o << "            case " << c.first << ": return " << c.second << ";\n";
+    o << "            default: return 0;\n        }\n    }\n};\n";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
+         "    __shared__ MShared ms;\n"
+         "    mstep_kernel_body<PH0, MM>(a, ms, lds);\n"
+         "}\n";
+    *lds_bytes = (size_t)ml.total_floats * 4;
     return o.str();
 }
 

@@ -14,6 +14,8 @@ namespace rnng {
 std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, int NB);
 // Same for the wave-autonomous variant with G workgroups; empty if the component is not eligible.
 std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G);
+// Matrix-core variant for many streams; *lds_bytes receives the dynamic LDS size.
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes);
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
 // compile fails (the log, if any, goes to *log).  Needs no GPU.
 bool jit_compile(const std::string& source, std::string* log);

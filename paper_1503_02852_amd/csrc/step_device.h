@@ -316,7 +316,9 @@ __device__ __forceinline__ void ring_fill(const PhaseRegs<PH>& r, const StepArgs
     }
 }
 
-template <class PH, int NB, bool WAVE = false>
+// MODE 0: LDS variant (static gathers through the workgroup ring); 1: wave-autonomous variant
+// (per-wavefront ring, own matrix-vector set-up); 2: static gathers are loaded directly.
+template <class PH, int NB, int MODE = 0>
 __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a, const StepShared& sh, float* lds, int w, int tid) {
     const StepPhase& ph = sh.lay.ph[PH::P];
     cwords_t pw = (cwords_t)a.words + suni(ph.prog_off);
@@ -339,7 +341,7 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
         if (PH::gkind(g) == GA_KIND_ACC) {
             r.gptr[g] = active ? a.weights : nullptr;   // any non-null marker
             r.goff[g] = aph.acc_base + (e[GA_FRAME_OFF] * aph.cmax + il) * NB + (r.n >= 0 ? r.n : 0);
-        } else if (PH::gkind(g) == GA_KIND_STATIC && (WAVE || r.pf_steps > 0)) {
+        } else if (PH::gkind(g) == GA_KIND_STATIC && (MODE == 1 || (MODE == 0 && r.pf_steps > 0))) {
             r.gptr[g] = active ? a.weights : nullptr;
             r.goff[g] = PH::sidx(g) * items + (r.n >= 0 ? r.n : 0) * item_chunk + il;
         } else {
@@ -370,7 +372,7 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
     for (int q = 0; q < STEP_PF_PAIRS_PER_THREAD; ++q) {
         r.pbase[q] = nullptr; r.pstride[q] = 0; r.poff[q] = 0;
         const int pi = q * STEP_THREADS + tid;
-        if (!WAVE && PH::NS > 0 && r.pf_steps > 0 && pi < r.pairs) {
+        if (MODE == 0 && PH::NS > 0 && r.pf_steps > 0 && pi < r.pairs) {
             const int si = pi / items, it = pi - si * items;
             const int n2 = it / item_chunk, il2 = it - n2 * item_chunk;
             cwords_t e = pw + PG_HEADER_WORDS + PH::sgather(si) * GA_WORDS;
@@ -382,7 +384,7 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
             }
         }
     }
-    if (WAVE) return;   // the wave-autonomous variant has its own matrix-vector and ring set-up
+    if (MODE != 0) return;   // the other variants have their own matrix-vector and ring set-up
     if (PH::HAS_TASKS) { matvec_setup<NB>(r.mv, sh, PH::P, tid); sources_setup(r.src, a, sh, PH::P); }
     if (PH::NS > 0 && r.pf_steps > 0) ring_fill<PH>(r, a, lds, 0, 0, tid);
 }
@@ -876,6 +878,278 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(5);
     RNNG_STAMP(6);
     RNNG_STAMP(7);
+}
+
+
+// =============================================================================================
+// Matrix-core variant (run-time specialised, single-phase components, many streams).
+//
+// With N >= 9 streams a step's full connections are skinny GEMMs: acc[n][row] = sum_k
+// x_s[n][k] * W[row][k] over the shared source tensors x_s [N][K_s].  Each workgroup owns a
+// chunk of every layer's units and keeps its weight rows resident in LDS ([row][k], one block of
+// rows per (source, task, edge)).  Per step it polls every source tensor in K-chunks into LDS
+// (sentinel protocol, 128-bit coherent loads), multiplies with v_mfma_f32_16x16x4_f32 (streams
+// are the M dimension, weight rows the N dimension, the four wavefronts split K), adds the
+// per-source accumulators into one [n][row] LDS tile, and runs the element-wise program with
+// one thread per (stream, unit).
+//
+// MM is a generated descriptor: static constexpr int MT (ceil(N / 16)), NSRC, NTS_MAX;
+// constexpr nts(s): 16-row tiles of source s.
+// =============================================================================================
+typedef float mfloatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned muintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int MSTEP_MAX_BLOCKS = 16;     // (task, edge) blocks per source
+
+struct MLayout {
+    int ok, n_src, cmax, kc, xstride, xbase, accbase, accstride, total_floats;
+    int wbase[STEP_MAX_SOURCES], wstride[STEP_MAX_SOURCES], rows[STEP_MAX_SOURCES], nblk[STEP_MAX_SOURCES];
+    short blk_task[STEP_MAX_SOURCES][MSTEP_MAX_BLOCKS], blk_edge[STEP_MAX_SOURCES][MSTEP_MAX_BLOCKS];
+};
+
+// Same on host and device.  lay is the generic step layout (tasks, sources) for G workgroups.
+RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, MLayout& m) {
+    m.ok = 0;
+    if (!lay.ok || lay.n_phases != 1) return;
+    const StepPhase& ph = lay.ph[0];
+    if (ph.item_chunk * N > STEP_THREADS) return;
+    m.n_src = lay.n_sources; m.cmax = ph.cmax;
+    const int npad = (N + 15) / 16 * 16;
+    int kc = 8192 / npad / 64 * 64;
+    if (kc < 64) return;
+    if (kc > 1024) kc = 1024;
+    int kmax = 0;
+    for (int s = 0; s < lay.n_sources; ++s) kmax = lay.src[s].k_len > kmax ? lay.src[s].k_len : kmax;
+    const int kmax_pad = (kmax + 63) / 64 * 64;
+    if (kc > kmax_pad) kc = kmax_pad;
+    m.kc = kc; m.xstride = kc + 4;
+    int cur = 0;
+    for (int s = 0; s < lay.n_sources; ++s) {
+        m.nblk[s] = 0;
+        for (int t = 0; t < ph.n_tasks; ++t)
+            for (int e = 0; e < ph.task[t].n_edges; ++e)
+                if (ph.task[t].e[e].src == s) {
+                    if (m.nblk[s] == MSTEP_MAX_BLOCKS) return;
+                    m.blk_task[s][m.nblk[s]] = (short)t; m.blk_edge[s][m.nblk[s]] = (short)e; ++m.nblk[s];
+                }
+        m.rows[s] = m.nblk[s] * ph.cmax;
+        m.wstride[s] = (lay.src[s].k_len + 63) / 64 * 64 + 4;
+        m.wbase[s] = cur; cur += m.rows[s] * m.wstride[s];
+    }
+    m.xbase = cur; cur += npad * m.xstride;
+    m.accstride = ph.n_tasks * ph.cmax + 1;
+    m.accbase = cur; cur += npad * m.accstride;
+    m.total_floats = cur;
+    m.ok = 1;
+}
+
+struct MShared { StepShared sh; MLayout ml; };
+
+template <class PH, class MM>
+__device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms, float* lds) {
+    int w = blockIdx.x;
+    if (a.xcd_stride > 1) {
+        if (w % a.xcd_stride) return;
+        w /= a.xcd_stride;
+    }
+    if (w >= a.G) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int N = a.N, T = a.T;
+    StepShared& sh = ms.sh;
+    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, N, sh.lay); compute_mstep_layout(sh.lay, N, ms.ml); }
+    __syncthreads();
+    const StepPhase& ph = sh.lay.ph[0];
+    const MLayout& ml = ms.ml;
+    {
+        const int ic = ph.item_chunk;
+        const int il = tid % ic, n = tid / ic;
+        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N ? n : 0xFFFF) << 16);
+    }
+    for (int i = tid; i < ml.total_floats; i += STEP_THREADS) lds[i] = 0.0f;
+    __syncthreads();
+    // resident weights: W_lds[s][blk * cmax + ul][k]
+    const int cmax = suni(ml.cmax);
+    for (int s = 0; s < ml.n_src; ++s) {
+        const int K = sh.lay.src[s].k_len;
+        for (int b = 0; b < ml.nblk[s]; ++b) {
+            const StepTask& task = ph.task[ml.blk_task[s][b]];
+            const StepEdge ed = task.e[ml.blk_edge[s][b]];
+            const float* W = a.weights + ed.w_off;
+            for (int i = tid; i < cmax * K; i += STEP_THREADS) {
+                const int ul = i / K, k = i - ul * K;
+                const int u = w * task.chunk + ul;
+                float v = 0.0f;
+                if (ul < task.chunk && u < task.n_out) v = ed.transposed ? W[(size_t)k * task.n_out + u] : W[(size_t)u * K + k];
+                lds[ml.wbase[s] + (b * cmax + ul) * ml.wstride[s] + k] = v;
+            }
+        }
+    }
+    PhaseRegs<PH> r;
+    phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
+    __syncthreads();
+
+    const int kc = suni(ml.kc), xstride = suni(ml.xstride), xbase = suni(ml.xbase);
+    const int accbase = suni(ml.accbase), accstride = suni(ml.accstride);
+    const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    bool dead = false;
+    for (int step = 0; step < T; ++step) {
+        const int t = a.backward ? T - 1 - step : step;
+        float s[MAX_SLOTS];
+        // element-wise inputs: registers (carry), plain loads (static), coherent loads (dynamic)
+#pragma unroll
+        for (int g = 0; g < PH::NG; ++g) {
+            if (PH::gkind(g) == GA_KIND_CARRY) {
+                s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+            } else if (PH::gkind(g) != GA_KIND_ACC) {
+                const int frame = t + r.goff[g];
+                float v = 0.0f;
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < T) {
+                    if (PH::gkind(g) == GA_KIND_STATIC) v = r.gptr[g][(long long)frame * r.gstride[g]];
+                    else v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                }
+                s[g] = v;
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+        // accumulator tile to zero
+        for (int i = tid; i < ((N + 15) / 16 * 16) * accstride; i += STEP_THREADS) lds[accbase + i] = 0.0f;
+
+#pragma unroll
+        for (int sidx = 0; sidx < MM::NSRC; ++sidx) {
+            const StepSource& sc = sh.lay.src[sidx];
+            const int K = suni(sc.k_len), frame = t + suni(sc.frame_off);
+            if (frame < 0 || frame >= T) continue;
+            const int rows = suni(ml.rows[sidx]), wbase = suni(ml.wbase[sidx]), wstride = suni(ml.wstride[sidx]);
+            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)frame * N * K;
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, N * K * 4, 0x00020000);
+            mfloatx4 acc[MM::MT][MM::NTS_MAX];
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MM::NTS_MAX; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int k0 = 0; k0 < K; k0 += kc) {
+                const int klen = K - k0 < kc ? K - k0 : kc;
+                __syncthreads();                       // the previous chunk has been consumed
+                // ---- poll the chunk x[n][k0 .. k0 + klen) into LDS, zero the tail of the chunk ----
+                if ((K & 3) == 0) {
+                    const int q4 = klen >> 2, total = N * q4;
+                    for (int base = 0; base < total; base += 8 * STEP_THREADS) {
+                        muintx4 v[8];
+                        int spins = 0;
+                        for (;;) {
+                            bool ok = true;
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const int p = base + tid + STEP_THREADS * j;
+                                if (p < total) {
+                                    const int n = p / q4, q = p - n * q4;
+                                    v[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (n * K + k0 + 4 * q) * 4, 0, 16);
+                                }
+                            }
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const int p = base + tid + STEP_THREADS * j;
+                                if (p < total)
+                                    ok = ok && v[j].x != STEP_SENTINEL && v[j].y != STEP_SENTINEL && v[j].z != STEP_SENTINEL && v[j].w != STEP_SENTINEL;
+                            }
+                            if (ok || dead) break;
+                            if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int p = base + tid + STEP_THREADS * j;
+                            if (p < total) {
+                                const int n = p / q4, q = p - n * q4;
+                                *reinterpret_cast<muintx4*>(&lds[xbase + n * xstride + 4 * q]) = v[j];
+                            }
+                        }
+                    }
+                } else {
+                    const int total = N * klen;
+                    for (int p = tid; p < total; p += STEP_THREADS) {
+                        const int n = p / klen, k = p - n * klen;
+                        unsigned v;
+                        int spins = 0;
+                        for (;;) {
+                            v = __hip_atomic_load(reinterpret_cast<const unsigned*>(g) + (size_t)n * K + k0 + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (v != STEP_SENTINEL || dead) break;
+                            if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+                        }
+                        lds[xbase + n * xstride + k] = __uint_as_float(v);
+                    }
+                }
+                if (klen < kc) {
+                    const int tail = kc - klen;
+                    for (int p = tid; p < N * tail; p += STEP_THREADS) { const int n = p / tail, k = klen + p - n * tail; lds[xbase + n * xstride + k] = 0.0f; }
+                }
+                __syncthreads();
+                // ---- MFMA: wavefront `wave` takes k in [wave * kc / 4, (wave + 1) * kc / 4) of the chunk ----
+                const int kw = kc >> 2;
+                for (int kk = wave * kw; kk < (wave + 1) * kw; kk += 16) {
+                    if (kk >= klen) break;
+                    mfloatx4 av[MM::MT], bv[MM::NTS_MAX];
+#pragma unroll
+                    for (int mt = 0; mt < MM::MT; ++mt)
+                        av[mt] = *reinterpret_cast<const mfloatx4*>(&lds[xbase + (mt * 16 + (lane & 15)) * xstride + kk + 4 * (lane >> 4)]);
+#pragma unroll
+                    for (int nt = 0; nt < MM::NTS_MAX; ++nt) {
+                        if (nt < MM::nts(sidx)) {
+                            const int row = nt * 16 + (lane & 15);
+                            const int rr = row < rows ? row : 0;
+                            mfloatx4 b4 = *reinterpret_cast<const mfloatx4*>(&lds[wbase + rr * wstride + k0 + kk + 4 * (lane >> 4)]);
+                            if (row >= rows) b4 = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+                            bv[nt] = b4;
+                        }
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < MM::NTS_MAX; ++nt)
+                            if (nt < MM::nts(sidx)) {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][i], bv[nt][i], acc[mt][nt], 0, 0, 0);
+                            }
+                }
+            }
+            // ---- add this source's accumulators into the [n][row] tile: column j of the source's
+            //      tile belongs to block j / cmax (a task), unit j % cmax ----
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MM::NTS_MAX; ++nt)
+                    if (nt < MM::nts(sidx)) {
+                        const int col = nt * 16 + (lane & 15);
+                        if (col < rows) {
+                            const int b = col / cmax, ul = col - b * cmax;
+                            const int row = ml.blk_task[sidx][b] * cmax + ul;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int m = mt * 16 + 4 * (lane >> 4) + i;
+                                if (m < N) atomicAdd(&lds[accbase + m * accstride + row], acc[mt][nt][i]);
+                            }
+                        }
+                    }
+        }
+        __syncthreads();
+        // ---- element-wise program: one thread per (stream, unit) ----
+        if (r.n >= 0) {
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_ACC) s[g] = r.gptr[g] != nullptr ? lds[accbase + r.n * accstride + PH::gaux(g) * cmax + item_il] : 0.0f;
+            PH::ops(s);
+#pragma unroll
+            for (int q = 0; q < PH::NST; ++q) {
+                if (r.sptr[q] == nullptr) continue;
+                if (PH::stshared(q)) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+                else r.sptr[q][(long long)t * r.sstride[q]] = s[PH::stslot(q)];
+            }
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+        }
+        __syncthreads();   // the accumulator tile is zeroed again at the top of the next step
+    }
 }
 
 }  // namespace rnng

@@ -22,9 +22,9 @@
 namespace rnng {
 
 constexpr int STEP_THREADS = 256;
-constexpr int STEP_MAX_PHASES = 6;
-constexpr int STEP_MAX_TASKS = 12;     // per phase
-constexpr int STEP_MAX_EDGES = 4;      // per task
+constexpr int STEP_MAX_PHASES = 4;
+constexpr int STEP_MAX_TASKS = 8;      // per phase
+constexpr int STEP_MAX_EDGES = 8;      // per task
 constexpr int STEP_MAX_SOURCES = 8;    // distinct (buffer, frame offset) vectors read per step
 constexpr int STEP_PF_MAX_STEPS = 16;  // steps per block of early-loaded static gather values
 constexpr int STEP_PF_PAIRS_PER_THREAD = 2;

@@ -155,3 +155,14 @@ def test_dense_random_graph_splits_step_programs(seed):
     rng = np.random.default_rng(1000 + seed)
     spec = wl.random_graph(rng, n_inner=3 + seed % 9, p_edge=0.15 + 0.05 * (seed % 6), max_delay=3, n_inputs=1 + seed % 2)
     run_both(wl.make_workload(f"dense{seed}", spec, T=9, N=2, seed=seed, scale=0.5, bias_scale=0.3))
+
+
+def test_many_streams_ragged_widths():
+    """More than 8 streams (matrix-core step kernel) with widths and a stream count that are not
+    multiples of the MFMA tile or of 4."""
+    run_both(wl.make_workload("ragged_n19", wl.lstm_net(37, [130, 67], 13), T=12, N=19, seed=12, scale=0.2, bias_scale=0.1))
+    run_both(wl.make_workload("elman_n33", wl.elman_net(20, 150, 11), T=9, N=33, seed=13, scale=0.15))
+
+
+def test_many_streams_generalized_small():
+    run_both(wl.make_workload("gen_n24", wl.generalized_net(24, 96, 3, 10), T=10, N=24, seed=14, scale=0.15, bias_scale=0.1))
