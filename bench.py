@@ -2,12 +2,15 @@
 """Benchmark of the forward + BPTT hot path on one MI355X.
 
 A step is one pass of the whole hot path over one window of seeded synthetic input:
-rnn_forward + rnn_bptt + rnn_grads (all weight gradients), inputs / targets / weights already
-resident in HBM.  Prints ONE JSON line: frames/s, the roofline record of the dominant kernel
-(recurrent-node step kernels, timed live with HIP events on the launch stream) and the float64
+rnn_forward + rnn_bptt + rnn_grads (all weight gradients), with inputs / targets / weights already
+resident in HBM.  Prints ONE JSON line: frames/s, the roofline record of the dominant kernel (the
+persistent recurrent-step kernel, timed live with HIP events on the launch stream) and the float64
 oracle timed on the host cores on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload speech_n1] [--no-cpu-baseline]
+
+Workloads: speech_n1 (default: 2 x 256 peephole LSTM, T = 1024, N = 1), charlm_n1, charlm_n32,
+generalized_n64, tiny.
 """
 import argparse
 import json
@@ -25,13 +28,22 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix peak
 
 def recurrent_bytes_per_step(spec, sched):
     """Algorithmic bytes per time step and direction: every weight of a connection inside a
-    recurrent node is touched once per step (full matrices and diagonal vectors)."""
+    recurrent node is touched once per step (full matrices and diagonal vectors), 4 bytes each."""
     total = 0
     for m, e in enumerate(spec.edges):
         if sched["edge_class"][m] == 0:
             continue
         ns, nd = spec.nodes[e["src"]]["dim"], spec.nodes[e["dst"]]["dim"]
         total += 4 * (nd * ns if e["wkind"] == 0 else nd if e["wkind"] == 1 else 0)
+    return total
+
+
+def recurrent_flops_per_step(spec, sched, N):
+    """2 flops per full-matrix weight inside a recurrent node per stream and direction."""
+    total = 0
+    for m, e in enumerate(spec.edges):
+        if sched["edge_class"][m] != 0 and e["wkind"] == 0:
+            total += 2 * spec.nodes[e["src"]]["dim"] * spec.nodes[e["dst"]]["dim"] * N
     return total
 
 
@@ -50,7 +62,6 @@ def paper_rule_flops_per_frame(spec):
 def cpu_baseline(name, T_sample):
     """The oracle as it stands on a bounded sample: the same network and stream count over the
     first T_sample frames of the window."""
-    import numpy as np  # noqa: F401
     import workloads as wl
     from oracle import graph_oracle as go
     w = wl.make_config(name, T=T_sample)
@@ -68,6 +79,16 @@ def cpu_baseline(name, T_sample):
                 sample=f"{name}: first {w.T} of the window's frames x {w.N} streams, one forward+BPTT in float64 numpy, {dt:.1f} s")
 
 
+def load_traffic(workload):
+    """HBM bytes per step-kernel launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    try:
+        with open(path) as f:
+            return json.load(f)["hbm_bytes_per_launch"]
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,10 +96,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="speech_n1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the path shards over streams with one gradient "
-              "all-reduce per window, which is described in DESIGN.md and not built. Use --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; the path would shard over streams with one gradient "
+              "all-reduce per window (DESIGN.md), which is not built. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -88,30 +111,37 @@ def main():
     w = wl.make_config(args.workload)
     win = window_for(w, "cuda:0")
     sched = win.g.schedule()
+    win.g.specialise(w.N)
     for _ in range(args.warmup):
         win.step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
-    PROF_STEP_FWD, PROF_STEP_BWD, PROF_GEMM_FWD, PROF_GEMM_BWD, PROF_GEMM_GRAD, PROF_OTHER = range(6)
-    win.g.profile_enable((1 << PROF_STEP_FWD) | (1 << PROF_STEP_BWD))
+    PROF = dict(step_fwd=0, step_bwd=1, gemm_fwd=2, gemm_bwd=3, gemm_grad=4, other=5)
+    # timed region: K steps; HIP events only around the dominant class (the step kernels)
+    win.g.profile_enable((1 << PROF["step_fwd"]) | (1 << PROF["step_bwd"]))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         win.step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_f, n_f = win.g.profile_read(PROF_STEP_FWD)
-    ms_b, n_b = win.g.profile_read(PROF_STEP_BWD)
+    ms_f, n_f = win.g.profile_read(PROF["step_fwd"])
+    ms_b, n_b = win.g.profile_read(PROF["step_bwd"])
     win.g.profile_enable(0)
 
     # class breakdown in a second, separately timed pass (events around every class)
+    reps = max(1, min(args.steps, 5))
     win.g.profile_enable(0x3F)
-    for _ in range(max(1, min(args.steps, 5))):
+    for _ in range(reps):
         win.step()
     torch.cuda.synchronize()
-    reps = max(1, min(args.steps, 5))
     breakdown = {}
-    for cls, nm in enumerate(["step_fwd", "step_bwd", "gemm_fwd", "gemm_bwd", "gemm_grad", "other"]):
+    for nm, cls in PROF.items():
         ms, n = win.g.profile_read(cls)
         breakdown[nm] = dict(ms_per_step=ms / reps, launches_per_step=n / reps)
     win.g.profile_enable(0)
@@ -120,30 +150,47 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     value = frames * args.steps / dt
 
-    # Roofline of the dominant kernel class: the recurrent-node step loops (both directions).
-    # One "launch" here is one time step of one direction over all recurrent nodes' layers is
-    # not meaningful across layers of different width, so the unit is the window: algorithmic
-    # bytes = (bytes per step, all recurrent nodes) x T x 2 directions; duration = the summed
-    # step-loop time per window measured by the events above.
-    step_bytes = recurrent_bytes_per_step(w.spec, sched)
-    window_bytes = step_bytes * w.T * 2
+    # Roofline of the dominant kernel: the persistent recurrent-step kernel.  One launch runs all T
+    # steps of one recurrent node in one direction; its algorithmic bytes are the node's recurrent
+    # weight bytes, touched once per step: (bytes per step over all recurrent nodes) x T x 2
+    # directions, spread over the launches of one window.
+    n_launch = (n_f + n_b) / args.steps
+    window_bytes = recurrent_bytes_per_step(w.spec, sched) * w.T * 2
     loop_ms = (ms_f + ms_b) / args.steps
+    avg_launch_ms = loop_ms / n_launch if n_launch else 0.0
     achieved = window_bytes / (loop_ms * 1e-3) / 1e9 if loop_ms > 0 else 0.0
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=None, kernel="recurrent step loops (forward + backward)",
-                    algorithmic_bytes_per_window=window_bytes, loop_ms_per_window=loop_ms,
-                    launches_per_window=(n_f + n_b) / args.steps)
+                    traffic=load_traffic(args.workload),
+                    kernel="rnng_step_jit (persistent recurrent-step kernel, forward and backward launches)",
+                    algorithmic_bytes_per_launch=window_bytes / n_launch if n_launch else 0,
+                    avg_launch_ms=avg_launch_ms, launches_per_window=n_launch,
+                    us_per_layer_step=avg_launch_ms * 1e3 / w.T if w.T else 0.0,
+                    recurrent_tflops=recurrent_flops_per_step(w.spec, sched, w.N) * w.T * 2 / (loop_ms * 1e-3) / 1e12 if loop_ms > 0 else 0.0)
 
-    flops = paper_rule_flops_per_frame(w.spec) * frames
+    # batched edge GEMMs against the fp32 MFMA peak (secondary record)
+    gemm_flops = {"gemm_fwd": 0, "gemm_bwd": 0, "gemm_grad": 0}
+    for m, e in enumerate(w.spec.edges):
+        if e["wkind"] != 0:
+            continue
+        fl = 2 * w.spec.nodes[e["src"]]["dim"] * w.spec.nodes[e["dst"]]["dim"] * frames
+        gemm_flops["gemm_grad"] += fl
+        if sched["edge_class"][m] == 0:
+            gemm_flops["gemm_fwd"] += fl
+            if w.spec.nodes[e["src"]]["kind"] != 0:
+                gemm_flops["gemm_bwd"] += fl
+    gemms = {k: dict(tflops=(gemm_flops[k] / (breakdown[k]["ms_per_step"] * 1e-3) / 1e12) if breakdown[k]["ms_per_step"] > 0 else 0.0,
+                     frac_of_fp32_mfma_peak=(gemm_flops[k] / (breakdown[k]["ms_per_step"] * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS)
+                     if breakdown[k]["ms_per_step"] > 0 else 0.0) for k in gemm_flops}
+
     out = dict(metric="forward+BPTT frames/sec (fp32)", value=value, unit="frames/s", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f32", data="synthetic",
                config=dict(workload=args.workload, T=w.T, N=w.N, nodes=len(w.spec.nodes), edges=len(w.spec.edges),
                            params=w.n_params(), frames_per_window=frames),
-               paper_rule_gflops=flops / (ms_per_step * 1e-3) / 1e9,
-               breakdown=breakdown, roofline=roofline)
+               paper_rule_gflops=paper_rule_flops_per_frame(w.spec) * frames / (ms_per_step * 1e-3) / 1e9,
+               breakdown=breakdown, batched_gemms=gemms, roofline=roofline)
     if not args.no_cpu_baseline:
-        T_sample = {"tiny": 20, "speech_n1": 1024, "charlm_n1": 512, "charlm_n32": 128, "generalized_n64": 8}[args.workload]
+        T_sample = {"tiny": 20, "speech_n1": 1024, "charlm_n1": 512, "charlm_n32": 256, "generalized_n64": 16}[args.workload]
         out["cpu_baseline"] = cpu_baseline(args.workload, T_sample)
     print(json.dumps(out))
 
