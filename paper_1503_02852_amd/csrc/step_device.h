@@ -995,6 +995,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     for (int step = 0; step < T; ++step) {
         const int t = a.backward ? T - 1 - step : step;
         float s[MAX_SLOTS];
+        RNNG_STAMP(0);
         // element-wise inputs: registers (carry), plain loads (static), coherent loads (dynamic)
 #pragma unroll
         for (int g = 0; g < PH::NG; ++g) {
@@ -1014,6 +1015,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
         // accumulator tile to zero
         for (int i = tid; i < ((N + 15) / 16 * 16) * accstride; i += STEP_THREADS) lds[accbase + i] = 0.0f;
+        RNNG_STAMP(1);
 
 #pragma unroll
         for (int sidx = 0; sidx < MM::NSRC; ++sidx) {
@@ -1084,6 +1086,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                     for (int p = tid; p < N * tail; p += STEP_THREADS) { const int n = p / tail, k = klen + p - n * tail; lds[xbase + n * xstride + k] = 0.0f; }
                 }
                 __syncthreads();
+                if (sidx == 0 && k0 == 0) { RNNG_STAMP(2); }
                 // ---- MFMA: wavefront `wave` takes k in [wave * kc / 4, (wave + 1) * kc / 4) of the chunk ----
                 const int kw = kc >> 2;
                 for (int kk = wave * kw; kk < (wave + 1) * kw; kk += 16) {
@@ -1131,7 +1134,9 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                         }
                     }
         }
+        RNNG_STAMP(3);
         __syncthreads();
+        RNNG_STAMP(4);
         // ---- element-wise program: one thread per (stream, unit) ----
         if (r.n >= 0) {
 #pragma unroll
@@ -1148,7 +1153,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             for (int g = 0; g < PH::NG; ++g)
                 if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
         }
+        RNNG_STAMP(5);
         __syncthreads();   // the accumulator tile is zeroed again at the top of the next step
+        RNNG_STAMP(6);
+        RNNG_STAMP(7);
     }
 }
 
