@@ -156,6 +156,28 @@ struct rnn_graph {
             c.source = jit_step_source(plan, cp, backward, c.lp.NB);
         return jit_choices.emplace(key, c).first->second;
     }
+    // Chains of recurrent components run side by side in one launch (wave-autonomous members only).
+    struct ChainChoice { std::string source; std::vector<int> G; };
+    std::map<long long, ChainChoice> chain_choices;
+    bool use_chains = true;
+    const ChainChoice& chain_choice(int chain, bool backward, int N) {
+        const long long key = ((long long)chain * 2 + (backward ? 1 : 0)) * 4096 + N;
+        auto it = chain_choices.find(key);
+        if (it != chain_choices.end()) return it->second;
+        ChainChoice c;
+        const ChainPlan& ch = plan.chains[chain];
+        if (use_jit && use_chains && force_step_G <= 0) {
+            for (const CompPlan& m : ch.members) {
+                int pick = 0;
+                for (int G : {32, 16, 8})
+                    if (!jit_wave_source(plan, m, backward, N, G).empty()) { pick = G; break; }
+                if (!pick) break;
+                c.G.push_back(pick);
+            }
+            if (c.G.size() == ch.members.size()) c.source = jit_chain_source(plan, ch, backward, N, c.G);
+        }
+        return chain_choices.emplace(key, c).first->second;
+    }
 };
 
 namespace {
@@ -262,6 +284,37 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
     return hipSuccess;
 }
 
+// All members of a chain in one persistent launch.  hipErrorNotSupported: no such kernel for this
+// chain (the caller then runs the members one after another).
+hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s) {
+    const ChainPlan& ch = g->plan.chains[chain];
+    const rnn_graph::ChainChoice& cc = g->chain_choice(chain, backward, g->N);
+    if (cc.source.empty()) return hipErrorNotSupported;
+    hipFunction_t fn = jit_step_function(cc.source);
+    if (!fn) return hipErrorNotSupported;
+    const PlanView pv = g->view();
+    const int T = g->T, N = g->N;
+    const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
+    for (const CompPlan& m : ch.members)
+        for (int b : backward ? m.bwd_shared_bufs : m.fwd_shared_bufs) {
+            hipError_t e = launch_fill_sentinel(g->buf(b), (int64_t)T * N * g->plan.buf_dim[b], s);
+            if (e != hipSuccess) return e;
+        }
+    StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;
+    StepArgs a;
+    fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
+                   T, N, backward, 1 << 22);
+    a.n_groups = (int)ch.members.size();
+    for (int i = 0; i < a.n_groups; ++i) {
+        a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
+        a.grp_G[i] = cc.G[i];
+    }
+    hipError_t e = jit_launch(fn, a, lp, s);
+    if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(cc.source); return hipErrorNotSupported; }
+    g->prof.end(prof, 1, s);
+    return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -282,6 +335,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     std::string err;
     if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
+    if (const char* env = std::getenv("RNNG_CHAIN")) g->use_chains = std::atoi(env) != 0;
     if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
     *out = g;
     return RNN_OK;
@@ -364,11 +418,24 @@ int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inpu
     e = launch_fill(reinterpret_cast<float*>(g->ws + L.sync_off), SYNC_BYTES / 4, 0.0f, s);
     if (e != hipSuccess) return fail_hip(e, "control word reset");
 
+    int chain_done_to = -1;   // components up to this index were run as a chain
     for (const CompPlan& cp : P.comps) {
         if (!cp.has_fwd_program) continue;
+        const int c = (int)(&cp - P.comps.data());
+        if (c <= chain_done_to) continue;
+        if (cp.chain >= 0 && P.chains[cp.chain].first == c && !g->chain_choice(cp.chain, false, N).source.empty()) {
+            const ChainPlan& ch = P.chains[cp.chain];
+            for (const CompPlan& m : ch.members) {
+                e = run_gemms(g, m.fwd_gemms, false, s);
+                if (e != hipSuccess) return fail_hip(e, "forward GEMM");
+            }
+            e = run_chain(g, cp.chain, false, s);
+            if (e == hipSuccess) { chain_done_to = ch.last; continue; }
+            if (e != hipErrorNotSupported) return fail_hip(e, "forward chain kernel");
+        }
         e = run_gemms(g, cp.fwd_gemms, false, s);
         if (e != hipSuccess) return fail_hip(e, "forward GEMM");
-        e = run_phases(g, (int)(&cp - P.comps.data()), false, s);
+        e = run_phases(g, c, false, s);
         if (e != hipSuccess) return fail_hip(e, "forward node program");
         if (cp.softmax_node >= 0) {
             e = launch_softmax_rows(g->buf(P.ybuf(cp.softmax_node)), (int64_t)T * N, P.xnodes[cp.softmax_node].dim, s);
@@ -412,6 +479,16 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
             continue;
         }
         if (!cp.has_bwd_program) continue;
+        if (cp.chain >= 0 && P.chains[cp.chain].last == c && !g->chain_choice(cp.chain, true, N).source.empty()) {
+            const ChainPlan& ch = P.chains[cp.chain];
+            for (const CompPlan& m : ch.members) {
+                e = run_gemms(g, m.bwd_gemms, true, s);
+                if (e != hipSuccess) return fail_hip(e, "backward GEMM");
+            }
+            e = run_chain(g, cp.chain, true, s);
+            if (e == hipSuccess) { c = ch.first; continue; }
+            if (e != hipErrorNotSupported) return fail_hip(e, "backward chain kernel");
+        }
         e = run_gemms(g, cp.bwd_gemms, true, s);
         if (e != hipSuccess) return fail_hip(e, "backward GEMM");
         e = run_phases(g, c, true, s);
@@ -504,6 +581,15 @@ int rnn_specialise(rnn_graph* g, int32_t N) {
             ++n;
         }
     }
+    for (size_t ci = 0; ci < g->plan.chains.size(); ++ci)
+        for (int backward = 0; backward < 2; ++backward) {
+            const rnn_graph::ChainChoice& cc = g->chain_choice((int)ci, backward != 0, N);
+            if (cc.source.empty()) continue;
+            std::string log;
+            if (!jit_compile(cc.source, &log))
+                return fail(RNN_ERR_DEVICE, "chain step kernel specialisation failed: " + log);
+            ++n;
+        }
     return n;
 }
 

@@ -148,28 +148,29 @@ std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, in
 }
 
 // Wave-autonomous variant: single-phase components whose weight rows fit the register file.
-// Returns an empty string if the component (with G workgroups and N streams) is not eligible.
-std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G) {
+// Emits namespace <ns> { PH0, MV, body(a, w) } for one component; false if the component (with
+// G workgroups and N streams) is not eligible.
+namespace {
+bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N, int G, const std::string& ns) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     const int NB = step_nb_for(N);
-    if (phases.size() != 1 || NB == 0) return "";
+    if (phases.size() != 1 || NB == 0) return false;
     StepLayout lay;
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, NB, N, lay);
-    if (!lay.ok) return "";
+    if (!lay.ok) return false;
     const StepPhase& ph = lay.ph[0];
     const int UW = (ph.item_chunk + 3) / 4;
-    if (UW * NB > 8) return "";
+    if (UW * NB > 8) return false;
     std::vector<int> F(lay.n_sources), xoff(lay.n_sources);
     int XF = 0;
     for (int s = 0; s < lay.n_sources; ++s) { F[s] = (lay.src[s].k_len + 63) / 64; xoff[s] = XF; XF += F[s]; }
-    if (XF * NB > 96) return "";
-    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 16 || NB * 64 * F[s] > 8 * 256) return "";
+    if (XF * NB > 96) return false;
+    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 16 || NB * 64 * F[s] > 8 * 256) return false;
     int per_unit = 0;
     for (int t = 0; t < ph.n_tasks; ++t) for (int e = 0; e < ph.task[t].n_edges; ++e) per_unit += F[ph.task[t].e[e].src];
     const int RW = UW * per_unit;
-    if (RW > 384) return "";
-    std::ostringstream o;
-    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    if (RW > 384) return false;
+    o << "namespace " << ns << " {\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
     auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases) {
         o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
@@ -178,7 +179,8 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
     };
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
       << ", RW = " << RW << ", XF = " << XF << ";\n";
-    std::vector<std::pair<int, int>> ne, es, fs, xo, wo;
+    std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
+    for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});
     for (int t = 0; t < ph.n_tasks; ++t) {
         ne.push_back({t, ph.task[t].n_edges});
         for (int e = 0; e < ph.task[t].n_edges; ++e) es.push_back({t * STEP_MAX_EDGES + e, ph.task[t].e[e].src});
@@ -192,17 +194,15 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
                 woff += F[ph.task[t].e[e].src];
             }
     emit_switch("nedges", "task", ne); emit_switch("esrc_", "key", es); emit_switch("F", "s", fs);
-    emit_switch("xoff", "s", xo); emit_switch("woff_", "key", wo);
+    emit_switch("xoff", "s", xo); emit_switch("woff_", "key", wo); emit_switch("K", "s", ks);
     o << "    static __device__ __forceinline__ constexpr int esrc(int task, int e) { return esrc_(task * " << STEP_MAX_EDGES << " + e); }\n";
     o << "    static __device__ __forceinline__ constexpr int woff(int ul, int task, int e) { return woff_((ul * "
       << (ph.n_tasks > 0 ? ph.n_tasks : 1) << " + task) * " << STEP_MAX_EDGES << " + e); }\n};\n";
-    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
-         "void rnng_step_jit(StepArgs a) {\n"
+    o << "__device__ __forceinline__ void body(const StepArgs& a, int w) {\n"
          "    __shared__ StepShared sh;\n"
          "    __shared__ float ring_all[4][WaveRing<PH0, MV, " << NB << ">::FLOATS];\n"
          "    __shared__ __attribute__((aligned(16))) float xs_all[2 * GroupX<MV, " << NB << ">::FLOATS];\n"
-         "    const int w = wave_prologue<MV, " << NB << ">(a, sh);\n"
-         "    if (w < 0) return;\n"
+         "    wave_prologue<MV, " << NB << ">(a, sh);\n"
          "    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n"
          "    const bool has_units = wave * MV::UW < sh.lay.ph[0].item_chunk;   // else: only helps polling\n"
          "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
@@ -220,7 +220,43 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
          "        wave_step<PH0, MV, " << NB << ", WaveRing<PH0, MV, " << NB << ">::QNA>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, t, tid, dead);\n"
          "    }\n"
          "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv, a.backward ? 0 : a.T - 1);\n"
+         "}\n}  // namespace " << ns << "\n";
+    return true;
+}
+}  // namespace
+
+std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G) {
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    if (!emit_wave_group(o, P, cp, backward, N, G, "grp0")) return "";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    const int w = step_part_index(a);\n"
+         "    if (w < 0) return;\n"
+         "    grp0::body(a, w);\n"
          "}\n";
+    return o.str();
+}
+
+// Chain of recurrent components side by side in one launch: group g (component members[g], with
+// G[g] workgroups on XCD g) runs its own wave-autonomous body; a member's full connections from
+// earlier members are ordinary polled sources, so the groups trail each other by about one step.
+std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G) {
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    const int n = (int)ch.members.size();
+    if (n < 2 || n > STEP_MAX_GROUPS || (int)G.size() != n) return "";
+    for (int g = 0; g < n; ++g)
+        if (G[g] > 32 || !emit_wave_group(o, P, ch.members[g], backward, N, G[g], "grp" + std::to_string(g))) return "";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    const int grp = blockIdx.x & 7, w = blockIdx.x >> 3;\n"
+         "    if (grp >= a.n_groups || w >= a.grp_G[grp]) return;\n"
+         "    StepArgs b = a;\n"
+         "    b.desc_off = a.grp_desc_off[grp]; b.G = a.grp_G[grp];\n"
+         "    switch (grp) {\n";
+    for (int g = 0; g < n; ++g) o << "        case " << g << ": grp" << g << "::body(b, w); break;\n";
+    o << "        default: break;\n    }\n}\n";
     return o.str();
 }
 
@@ -279,7 +315,9 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     }
     std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
                                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-    if (const char* env = std::getenv("RNNG_STEP_TRACE")) if (std::atoi(env) != 0) opts.push_back("-DRNNG_STEP_TRACE=1");
+    std::string trace_opt;
+    if (const char* env = std::getenv("RNNG_STEP_TRACE"))
+        if (std::atoi(env) > 0) { trace_opt = "-DRNNG_STEP_TRACE=" + std::to_string(std::atoi(env)); opts.push_back(trace_opt.c_str()); }
     const hiprtcResult r = g_rtc.compile(prog, (int)opts.size(), opts.data());
     size_t ls = 0;
     g_rtc.log_size(prog, &ls);

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <string>
+#include <vector>
 
 #include "kernels.h"
 #include "plan.h"
@@ -14,6 +15,9 @@ namespace rnng {
 std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, int NB);
 // Same for the wave-autonomous variant with G workgroups; empty if the component is not eligible.
 std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G);
+// Chain of recurrent components side by side in one launch, member g with G[g] <= 32 workgroups;
+// empty if a member is not eligible for the wave-autonomous variant.
+std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G);
 // Matrix-core variant for many streams; *lds_bytes receives the dynamic LDS size.
 std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes);
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the

@@ -308,13 +308,15 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     auto w_off_of = [&](int m) -> int { return xe[m].wkind == W_DIAG ? (int)P.edge_off[P.xedge_param[m]] : -1; };
     auto full_off = [&](int m) -> int64_t { return P.edge_off[P.xedge_param[m]]; };
 
-    P.comps.assign(S.n_comps, CompPlan());
-    for (int c = 0; c < S.n_comps; ++c) {
-        CompPlan& cp = P.comps[c];
+    // Lowers component c into cp.  fused[m] marks full connections between different recurrent
+    // components that the step kernel evaluates itself (as if they were delayed connections of
+    // the component) instead of taking them from a GEMM over all frames.
+    auto lower_component = [&](int c, const std::vector<char>& fused, CompPlan& cp) -> bool {
+        auto batched = [&](int m) { return S.edge_class[m] == EDGE_BATCHED && !fused[m]; };
         cp.recurrent = S.comp_recurrent[c] != 0;
         std::vector<int> members;
         for (int k : S.comp_nodes[c]) if (xn[k].kind != NODE_INPUT) members.push_back(k);
-        if (members.empty()) continue;
+        if (members.empty()) return true;
         std::sort(members.begin(), members.end(), [&](int a, int b) {
             return S.node_level[a] != S.node_level[b] ? S.node_level[a] < S.node_level[b] : a < b;
         });
@@ -333,7 +335,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         for (int k : members) {
             GemmProblemPlan gp; gp.c_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k); gp.n = xn[k].dim;
             for (int m : in_e[k])
-                if (xe[m].wkind == W_FULL && S.edge_class[m] == EDGE_BATCHED)
+                if (xe[m].wkind == W_FULL && batched(m))
                     gp.pairs.push_back(GemmPairPlan{P.ybuf(xe[m].src), -1, full_off(m), xn[xe[m].src].dim, xe[m].delay});
             if (!gp.pairs.empty()) { cp.fwd_gemms.push_back(gp); P.buf_alloc[gp.c_buf] = 1; }
             if (shared_y[k]) cp.fwd_shared_bufs.push_back(P.ybuf(k));
@@ -355,7 +357,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                 for (int m : in_e[k]) {
                     const GEdge& e = xe[m];
                     if (e.wkind == W_FULL) {
-                        if (S.edge_class[m] == EDGE_BATCHED) { o.pre_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k); o.pre_static = true; }
+                        if (batched(m)) { o.pre_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k); o.pre_static = true; }
                         else {
                             task.edges.push_back(MvEdgeH{(int)full_off(m), xn[e.src].dim, 0, P.ybuf(e.src), -e.delay});
                             cp.step_weight_floats += (int64_t)xn[k].dim * xn[e.src].dim;
@@ -389,11 +391,11 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         cp.fwd_desc_off = emit_desc(cp.fwd_phases);
 
         // ---- backward ----
-        if (cp.softmax_node >= 0) continue;   // output delta comes from the softmax / cross-entropy kernel
+        if (cp.softmax_node >= 0) return true;   // output delta comes from the softmax / cross-entropy kernel
         for (int j : members) {
             GemmProblemPlan gp; gp.c_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); gp.n = xn[j].dim;
             for (int m : out_e[j])
-                if (xe[m].wkind == W_FULL && S.edge_class[m] == EDGE_BATCHED)
+                if (xe[m].wkind == W_FULL && batched(m))
                     gp.pairs.push_back(GemmPairPlan{P.dbuf(xe[m].dst), -1, full_off(m), xn[xe[m].dst].dim, xe[m].delay});
             if (!gp.pairs.empty()) { cp.bwd_gemms.push_back(gp); P.buf_alloc[gp.c_buf] = 1; }
         }
@@ -413,7 +415,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     const GEdge& e = xe[m];
                     const int k = e.dst;
                     if (e.wkind == W_FULL) {
-                        if (S.edge_class[m] == EDGE_BATCHED) { o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); o.pre_static = true; }
+                        if (batched(m)) { o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); o.pre_static = true; }
                         else task.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
                         continue;
                     }
@@ -439,6 +441,63 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         }
         cp.has_bwd_program = true;
         cp.bwd_desc_off = emit_desc(cp.bwd_phases);
+        return true;
+    };
+    P.comps.assign(S.n_comps, CompPlan());
+    const std::vector<char> none(M, 0);
+    for (int c = 0; c < S.n_comps; ++c)
+        if (!lower_component(c, none, P.comps[c])) return false;
+
+    // ---- chains of recurrent components that one step kernel can run side by side ----
+    // Consecutive single-phase recurrent components c, c + 1, ... form a chain if every connection
+    // between two of them is a full one whose source is already exchanged between workgroups in
+    // the forward loop and whose destination is in the backward loop, and every other connection
+    // of a member comes from a component before the chain or leads to one after it.
+    {
+        auto single_phase = [&](const CompPlan& cp) {
+            return cp.recurrent && cp.fwd_phases.size() == 1 && cp.bwd_phases.size() == 1 && cp.softmax_node < 0;
+        };
+        int c = 0;
+        while (c < S.n_comps) {
+            if (!single_phase(P.comps[c])) { ++c; continue; }
+            int last = c;
+            while (last + 1 < S.n_comps && last + 1 - c + 1 <= STEP_MAX_GROUPS && single_phase(P.comps[last + 1])) {
+                // try to extend the chain [c, last] by last + 1
+                const int cand = last + 1;
+                bool ok = true, linked = false;
+                for (int m = 0; m < M && ok; ++m) {
+                    const int cs = S.node_comp[xe[m].src], cd = S.node_comp[xe[m].dst];
+                    if (cs == cd) continue;
+                    const bool s_in = cs >= c && cs <= cand, d_in = cd >= c && cd <= cand;
+                    if (s_in && d_in) {
+                        if (xe[m].wkind != W_FULL || !shared_y[xe[m].src] || !shared_d[xe[m].dst] || cs > cd) ok = false;
+                        else if (cd == cand) linked = true;
+                    } else if (s_in && cd < cand) ok = false;       // leaves the chain into an earlier component
+                    else if (d_in && cs > c) ok = false;            // enters the chain from a later component
+                }
+                if (!ok || !linked) break;
+                last = cand;
+            }
+            if (last > c) {
+                std::vector<char> fused(M, 0);
+                for (int m = 0; m < M; ++m) {
+                    const int cs = S.node_comp[xe[m].src], cd = S.node_comp[xe[m].dst];
+                    if (cs != cd && cs >= c && cs <= last && cd >= c && cd <= last) fused[m] = 1;
+                }
+                ChainPlan ch; ch.first = c; ch.last = last;
+                for (int k = c; k <= last; ++k) {
+                    CompPlan fc;
+                    if (!lower_component(k, fused, fc)) return false;
+                    if (fc.fwd_phases.size() != 1 || fc.bwd_phases.size() != 1) { ch.members.clear(); break; }
+                    ch.members.push_back(fc);
+                }
+                if (!ch.members.empty()) {
+                    for (int k = c; k <= last; ++k) P.comps[k].chain = (int)P.chains.size();
+                    P.chains.push_back(ch);
+                }
+            }
+            c = last + 1;
+        }
     }
 
     // ---- weight gradients ----

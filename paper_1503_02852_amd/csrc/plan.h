@@ -50,6 +50,16 @@ struct CompPlan {
     // full connections inside the recurrent node); they are pre-filled with a sentinel
     std::vector<int> fwd_shared_bufs, bwd_shared_bufs;
     int64_t step_weight_floats = 0;         // weights of all full connections inside the component
+    int chain = -1;                         // index into Plan::chains if the component is a chain member
+};
+
+// Consecutive recurrent components first..last whose step loops can run side by side in one
+// kernel launch: members[i] is component first + i lowered with the full connections between
+// chain members taken into the step loop (read with the sentinel protocol like a component's own
+// delayed connections) instead of into a GEMM over all frames.
+struct ChainPlan {
+    int first = 0, last = 0;
+    std::vector<CompPlan> members;
 };
 
 struct Plan {
@@ -67,6 +77,7 @@ struct Plan {
     std::vector<int> buf_dim;
     std::vector<char> buf_alloc;            // 0 not in the workspace, 1 [T][N][dim], 2 [N][dim]
     std::vector<CompPlan> comps;
+    std::vector<ChainPlan> chains;
     std::vector<GradGemmPlan> grad_gemms;
     int colsum_off = -1, n_colsum = 0, colsum_max_dim = 0;
     std::vector<int32_t> words;             // all programs

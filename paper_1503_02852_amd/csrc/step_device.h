@@ -24,6 +24,13 @@ namespace rnng {
 constexpr unsigned STEP_SENTINEL = 0xFFFFFFFFu;
 typedef float sfloatx4 __attribute__((ext_vector_type(4)));
 typedef float sfloatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned suintx2 __attribute__((ext_vector_type(2)));
+// Buffer loads that poll shared vectors are device-coherent (sc1).  Unlike atomic loads they are
+// not each followed by a wait, so all loads of a polling attempt are in flight together; a
+// compiler barrier at the top of each attempt keeps them from being merged across attempts.
+constexpr int STEP_COHERENT_AUX = 16;
+__device__ __forceinline__ void step_compiler_barrier() { asm volatile("" ::: "memory"); }
+constexpr int STEP_RSRC_FLAGS = 0x00020000;
 
 
 // v_rcp_f32 / v_exp_f32 (about 1 ulp each) instead of an IEEE division: far inside the 1e-4 bar.
@@ -390,10 +397,11 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
 }
 
 // Optional cycle stamps of one workgroup's steps 64..71 (8 stamps per step, written behind the
-// control words) for tuning; compiled in only when RNNG_STEP_TRACE is defined for the run-time build.
+// control words) for tuning; compiled in only when RNNG_STEP_TRACE is defined for the run-time build
+// (its value is the traced block index plus one).
 #if defined(RNNG_STEP_TRACE)
 #define RNNG_STAMP(i)                                                                                       \
-    if (blockIdx.x == 0 && tid == 0 && step >= 64 && step < 72)                                             \
+    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= 64 && step < 72)                                           \
         reinterpret_cast<unsigned long long*>(a.ctrl + 16)[(step - 64) * 8 + (i)] = clock64()
 #else
 #define RNNG_STAMP(i)
@@ -470,8 +478,8 @@ __device__ __forceinline__ void phase_step(PhaseRegs<PH>& r, const StepArgs& a, 
 //
 // MV is a generated descriptor:
 //   static constexpr int NT (tasks), UW (units per wavefront), NSRC, RW (weight registers),
-//   XF (source registers per stream);  constexpr nedges(task), esrc(task, e), F(src), xoff(src),
-//   woff(ul, task, e).
+//   XF (source registers per stream);  constexpr nedges(task), esrc(task, e), F(src), K(src),
+//   xoff(src), woff(ul, task, e).
 // =============================================================================================
 __device__ __forceinline__ float wave_sum_dpp(float v) {
 #define RNNG_DPP(ctrl, rmask) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rmask, 0xf, false))
@@ -496,21 +504,24 @@ struct WaveRegs {
     int xfoff[MV::NSRC > 0 ? MV::NSRC : 1], xk[MV::NSRC > 0 ? MV::NSRC : 1];
 };
 
-// Layout (thread 0), item table for the wave-autonomous mapping.  Returns the part index or -1.
-template <class MV, int NB>
-__device__ __forceinline__ int wave_prologue(const StepArgs& a, StepShared& sh) {
+// Layout (thread 0), item table for the wave-autonomous mapping.
+// Part index of this workgroup in a single-component launch, or -1 if it has no part.
+__device__ __forceinline__ int step_part_index(const StepArgs& a) {
     int w = blockIdx.x;
     if (a.xcd_stride > 1) {
         if (w % a.xcd_stride) return -1;
         w /= a.xcd_stride;
     }
-    if (w >= a.G) return -1;
+    return w < a.G ? w : -1;
+}
+
+template <class MV, int NB>
+__device__ __forceinline__ void wave_prologue(const StepArgs& a, StepShared& sh) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) compute_step_layout(a.words, a.desc_off, a.G, NB, a.N, sh.lay);
     const int ul = lane % MV::UW, n = lane / MV::UW;
     sh.iteminfo[0][tid] = (unsigned)(wave * MV::UW + ul) | ((unsigned)(n < a.N ? n : 0xFFFF) << 16);
     __syncthreads();
-    return w;
 }
 
 template <class MV>
@@ -645,51 +656,62 @@ constexpr int GROUP_MAX_LOADS = 8;   // per thread and source (N * K <= 2048 ele
 template <class MV, int NB>
 __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int t, int tid, bool& dead) {
     typedef GroupX<MV, NB> GX;
-    unsigned long long v64[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
+    suintx2 v64[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
     unsigned v32[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
+    // One buffer descriptor per source; a frame outside the window gets an empty one.  Loads
+    // beyond a descriptor's size return zero, so no load needs a branch around it.
+    __amdgpu_buffer_rsrc_t rs[MV::NSRC > 0 ? MV::NSRC : 1];
+#pragma unroll
+    for (int s = 0; s < MV::NSRC; ++s) {
+        const int frame = t + wv.xfoff[s];
+        const bool in_window = frame >= 0 && frame < a.T;
+        const float* g = wv.xsrc[s] + (in_window ? frame : 0) * wv.xstride[s];
+        rs[s] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? a.N * MV::K(s) * 4 : 0, STEP_RSRC_FLAGS);
+    }
     int spins = 0;
     for (;;) {
+        // all loads of an attempt are issued back to back (device-coherent buffer loads; atomic
+        // loads would each be followed by a wait), then checked
+        step_compiler_barrier();
+#pragma unroll
+        for (int s = 0; s < MV::NSRC; ++s) {
+            if ((MV::K(s) & 1) == 0) {
+#pragma unroll
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                    if (j < GX::pairs_per_thread(s)) v64[s][j] = __builtin_amdgcn_raw_buffer_load_b64(rs[s], (tid + STEP_THREADS * j) * 8, 0, STEP_COHERENT_AUX);
+            } else {
+#pragma unroll
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                    if (j < GX::words_per_thread(s)) v32[s][j] = __builtin_amdgcn_raw_buffer_load_b32(rs[s], (tid + STEP_THREADS * j) * 4, 0, STEP_COHERENT_AUX);
+            }
+        }
         bool ok = true;
 #pragma unroll
         for (int s = 0; s < MV::NSRC; ++s) {
-            const int K = wv.xk[s], total = a.N * K;
-            const int frame = t + wv.xfoff[s];
-            if (frame < 0 || frame >= a.T) continue;
-            const float* g = wv.xsrc[s] + frame * wv.xstride[s];
-            if ((K & 1) == 0) {
+            if ((MV::K(s) & 1) == 0) {
 #pragma unroll
-                for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
-                    const int p = tid + STEP_THREADS * j;
-                    if (j < GX::pairs_per_thread(s) && 2 * p < total) {
-                        v64[s][j] = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(g) + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ok = ok && (unsigned)v64[s][j] != STEP_SENTINEL && (unsigned)(v64[s][j] >> 32) != STEP_SENTINEL;
-                    }
-                }
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                    if (j < GX::pairs_per_thread(s)) ok = ok && v64[s][j].x != STEP_SENTINEL && v64[s][j].y != STEP_SENTINEL;
             } else {
 #pragma unroll
-                for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
-                    const int p = tid + STEP_THREADS * j;
-                    if (j < GX::words_per_thread(s) && p < total) {
-                        v32[s][j] = __hip_atomic_load(reinterpret_cast<const unsigned*>(g) + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ok = ok && v32[s][j] != STEP_SENTINEL;
-                    }
-                }
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                    if (j < GX::words_per_thread(s)) ok = ok && v32[s][j] != STEP_SENTINEL;
             }
         }
         if (ok || dead) break;
         if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
     }
 #if defined(RNNG_STEP_TRACE)
-    if (blockIdx.x == 0 && tid == 0 && t >= 64 && t < 72) {
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (t - 64)] = spins;
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (t - 64)] = clock64();
+    const int trace_step = a.backward ? a.T - 1 - t : t;
+    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= 64 && trace_step < 72) {
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (trace_step - 64)] = spins;
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (trace_step - 64)] = clock64();
     }
 #endif
+    // out-of-window frames and lanes beyond the vector arrive as zeros
 #pragma unroll
     for (int s = 0; s < MV::NSRC; ++s) {
-        const int K = wv.xk[s], total = a.N * K;
-        const int frame = t + wv.xfoff[s];
-        const bool in_window = frame >= 0 && frame < a.T;
+        const int K = MV::K(s), total = a.N * K;
         float* x = xs + GX::off(s);
         const int ROW = 64 * MV::F(s);
         if ((K & 1) == 0) {
@@ -699,8 +721,7 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
                 if (j < GX::pairs_per_thread(s) && 2 * p < total) {
                     int n = 0, k = 2 * p;
                     if (NB > 1) { n = k / K; k -= n * K; }
-                    sfloatx2 o = {0.0f, 0.0f};
-                    if (in_window) { o.x = __uint_as_float((unsigned)v64[s][j]); o.y = __uint_as_float((unsigned)(v64[s][j] >> 32)); }
+                    const sfloatx2 o = {__uint_as_float(v64[s][j].x), __uint_as_float(v64[s][j].y)};
                     *reinterpret_cast<sfloatx2*>(&x[n * ROW + k]) = o;
                 }
             }
@@ -711,7 +732,7 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
                 if (j < GX::words_per_thread(s) && p < total) {
                     int n = 0, k = p;
                     if (NB > 1) { n = k / K; k -= n * K; }
-                    x[n * ROW + k] = in_window ? __uint_as_float(v32[s][j]) : 0.0f;
+                    x[n * ROW + k] = __uint_as_float(v32[s][j]);
                 }
             }
         }
@@ -803,7 +824,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
         group_poll<MV, NB>(xs, wv, a, t, tid, dead);
         __syncthreads();
 #if defined(RNNG_STEP_TRACE)
-        if (blockIdx.x == 0 && tid == 0 && t >= 64 && t < 72) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (t - 64)] = clock64();
+        if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= 64 && step < 72) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - 64)] = clock64();
 #endif
         if (!has_units) return;
 #pragma unroll
@@ -1041,12 +1062,13 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                         int spins = 0;
                         for (;;) {
                             bool ok = true;
+                            step_compiler_barrier();
 #pragma unroll
                             for (int j = 0; j < 8; ++j) {
                                 const int p = base + tid + STEP_THREADS * j;
                                 if (p < total) {
                                     const int n = p / q4, q = p - n * q4;
-                                    v[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (n * K + k0 + 4 * q) * 4, 0, 16);
+                                    v[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (n * K + k0 + 4 * q) * 4, 0, STEP_COHERENT_AUX);
                                 }
                             }
 #pragma unroll

@@ -54,12 +54,18 @@ struct StepLayout {
     StepSource src[STEP_MAX_SOURCES];
 };
 
+constexpr int STEP_MAX_GROUPS = 4;
+
 struct StepArgs {
     float* const* buf_ptr;                   // buffer table (read-only for the kernel's lifetime)
     const int32_t* words;                    // plan words (likewise)
     const float* weights;
     unsigned* ctrl;                          // [0]: set to 1 when a wait ran into the spin limit
     int desc_off, T, N, backward, G, xcd_stride, spin_limit;
+    // Chain launches (several recurrent components side by side): group g runs descriptor
+    // grp_desc_off[g] on grp_G[g] workgroups; block b belongs to group b % 8, part b / 8, which
+    // puts each group on one XCD.  n_groups == 0: a single component (desc_off, G, xcd_stride).
+    int n_groups, grp_desc_off[STEP_MAX_GROUPS], grp_G[STEP_MAX_GROUPS];
 };
 
 
