@@ -215,10 +215,12 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    __syncthreads();\n"
          "    float dfv[PH0::NST > 0 ? PH0::NST : 1] = {0.0f};\n"
          "    bool dead = false;\n"
-         "    for (int step = 0; step < a.T; ++step) {\n"
-         "        const int t = a.backward ? a.T - 1 - step : step;\n"
-         "        wave_step<PH0, MV, " << NB << ", WaveRing<PH0, MV, " << NB << ">::QNA>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, t, tid, dead);\n"
+         "    int step = 0;\n"
+         "    for (; step + 1 < a.T; step += 2) {\n"
+         "        wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, a.backward ? a.T - 1 - step : step, tid, dead);\n"
+         "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, a.backward ? a.T - 2 - step : step + 1, tid, dead);\n"
          "    }\n"
+         "    if (step < a.T) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, a.backward ? a.T - 1 - step : step, tid, dead);\n"
          "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv, a.backward ? 0 : a.T - 1);\n"
          "}\n}  // namespace " << ns << "\n";
     return true;

@@ -783,7 +783,10 @@ __device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const 
         if (!PH::stshared(q) && r.sptr[q] != nullptr) r.sptr[q][(long long)t_prev * r.sstride[q]] = dfv[q];
 }
 
-template <class PH, class MV, int NB, int QNA, int NSTA>
+// PAR is the parity of `step` (the time loop is unrolled by two so that the register pair pf is
+// indexed statically: a run-time index would make the compiler merge in-flight loads at the loop
+// end, which costs a full memory wait per step).
+template <class PH, class MV, int NB, int PAR, int QNA, int NSTA>
 __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const WaveRing<PH, MV, NB>& rg,
                                           float (&pf)[2][QNA], float (&dfv)[NSTA],
                                           const StepArgs& a, float* ring, float* xs_all, bool has_units, int step, int t, int tid,
@@ -795,10 +798,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(0);
     const int js = step & (WAVE_RING_STEPS - 1);
     // the row loaded two steps ago (for step - 2 + WAVE_RING_STEPS) goes into the ring now
-    if (PH::NS > 0 && has_units && step > 1) {
-        if (step & 1) wave_ring_store<PH, MV, NB, QNA>(pf[1], ring, step - 2, lane);
-        else wave_ring_store<PH, MV, NB, QNA>(pf[0], ring, step - 2, lane);
-    }
+    if (PH::NS > 0 && has_units && step > 1) wave_ring_store<PH, MV, NB, QNA>(pf[PAR], ring, step - 2, lane);
     const int ul_l = lane % MV::UW, n_l = lane / MV::UW;
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
@@ -820,7 +820,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(1);
     float xr[NB][MV::XF > 0 ? MV::XF : 1];
     if (MV::NSRC > 0) {
-        float* xs = xs_all + (step & 1) * GX::FLOATS;
+        float* xs = xs_all + PAR * GX::FLOATS;
         group_poll<MV, NB>(xs, wv, a, t, tid, dead);
         __syncthreads();
 #if defined(RNNG_STEP_TRACE)
@@ -840,10 +840,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(2);
     // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
     if (step > 0) wave_flush_stores<PH>(r, dfv, a.backward ? t + 1 : t - 1);
-    if (PH::NS > 0) {
-        if (step & 1) wave_ring_load<PH, MV, NB, QNA>(pf[1], rg, a, step + WAVE_RING_STEPS);
-        else wave_ring_load<PH, MV, NB, QNA>(pf[0], rg, a, step + WAVE_RING_STEPS);
-    }
+    if (PH::NS > 0) wave_ring_load<PH, MV, NB, QNA>(pf[PAR], rg, a, step + WAVE_RING_STEPS);
     // rows: partial dot products, cross-lane reduction, result picked by the owning item lane
     constexpr int NV = (MV::UW * MV::NT * NB) > 0 ? (MV::UW * MV::NT * NB) : 1;
     float part[NV], tot[NV];
