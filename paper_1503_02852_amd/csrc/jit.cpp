@@ -208,6 +208,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
          "    float* ring = ring_all[wave];\n"
          "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", 1>(r0, a, sh, nullptr, w, tid);\n"
+         "    wave_store_setup<PH0>(r0, a);\n"
          "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
          "    WaveRing<PH0, MV, " << NB << "> rg; wave_ring_setup<PH0, MV, " << NB << ">(rg, a, sh, w, tid);\n"
          "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, lane);\n"
@@ -221,7 +222,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, a.backward ? a.T - 2 - step : step + 1, tid, dead);\n"
          "    }\n"
          "    if (step < a.T) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, a.backward ? a.T - 1 - step : step, tid, dead);\n"
-         "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv, a.backward ? 0 : a.T - 1);\n"
+         "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv);\n"
          "}\n}  // namespace " << ns << "\n";
     return true;
 }

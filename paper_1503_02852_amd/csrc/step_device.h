@@ -289,6 +289,11 @@ struct PhaseRegs {
     int goff[PH::NG > 0 ? PH::NG : 1];            // frame offset; ACC: LDS float index; STATIC with ring: index in a ring row
     float* sptr[PH::NST > 0 ? PH::NST : 1];
     int sstride[PH::NST > 0 ? PH::NST : 1];       // floats per frame (uniform)
+    // wave-autonomous variant: store address of the current step's frame, advanced by sdelta
+    // floats per step (negative in the backward loop); bit q of sok: this lane stores buffer q
+    float* scur[PH::NST > 0 ? PH::NST : 1];
+    int sdelta[PH::NST > 0 ? PH::NST : 1];
+    unsigned sok;
     float inv[PH::NI > 0 ? PH::NI : 1];
     float carry[PH::NC > 0 ? PH::NC : 1];
     // loader side of the static-gather ring: this thread's (static gather, item) pairs
@@ -564,6 +569,18 @@ __device__ __forceinline__ void wave_setup(WaveRegs<MV>& wv, const StepArgs& a, 
     }
 }
 
+template <class PH>
+__device__ __forceinline__ void wave_store_setup(PhaseRegs<PH>& r, const StepArgs& a) {
+    r.sok = 0;
+#pragma unroll
+    for (int q = 0; q < PH::NST; ++q) {
+        const bool ok = r.sptr[q] != nullptr;
+        r.sok |= ok ? (1u << q) : 0u;
+        r.scur[q] = ok ? r.sptr[q] + (long long)(a.backward ? a.T - 1 : 0) * r.sstride[q] : nullptr;
+        r.sdelta[q] = a.backward ? -r.sstride[q] : r.sstride[q];
+    }
+}
+
 // Loader side of a wavefront's private ring of STATIC gather values: pair = (static gather, item).
 template <class PH, class MV, int NB>
 struct WaveRing {
@@ -777,10 +794,10 @@ __device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&t
 // Stores of values no other workgroup waits for are issued one step late (after the next step's
 // poll), so that they do not sit in front of that poll in the wavefront's memory queue.
 template <class PH, int NSTA>
-__device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA], int t_prev) {
+__device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA]) {
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if (!PH::stshared(q) && r.sptr[q] != nullptr) r.sptr[q][(long long)t_prev * r.sstride[q]] = dfv[q];
+        if (!PH::stshared(q) && ((r.sok >> q) & 1)) r.scur[q][0] = dfv[q];
 }
 
 // PAR is the parity of `step` (the time loop is unrolled by two so that the register pair pf is
@@ -839,7 +856,11 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     }
     RNNG_STAMP(2);
     // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
-    if (step > 0) wave_flush_stores<PH>(r, dfv, a.backward ? t + 1 : t - 1);
+    if (step > 0) {
+        wave_flush_stores<PH>(r, dfv);
+#pragma unroll
+        for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
+    }
     if (PH::NS > 0) wave_ring_load<PH, MV, NB, QNA>(pf[PAR], rg, a, step + WAVE_RING_STEPS);
     // rows: partial dot products, cross-lane reduction, result picked by the owning item lane
     constexpr int NV = (MV::UW * MV::NT * NB) > 0 ? (MV::UW * MV::NT * NB) : 1;
@@ -887,7 +908,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(4);
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q) {
-        if (PH::stshared(q)) { if (r.sptr[q] != nullptr) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]); }
+        if (PH::stshared(q)) { if ((r.sok >> q) & 1) store_shared(r.scur[q], s[PH::stslot(q)]); }
         else dfv[q] = s[PH::stslot(q)];
     }
 #pragma unroll

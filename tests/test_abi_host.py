@@ -129,3 +129,24 @@ def test_runtime_argument_errors_without_gpu_work():
         g.forward(None, [1], 4, 1, 256, 1 << 30)
     assert ei.value.code == -1
     assert g.workspace_bytes(4, 1) > 0
+
+
+def test_stacked_layers_get_a_side_by_side_step_kernel(monkeypatch):
+    """Two stacked LSTM layers form a chain: besides one step kernel per layer and direction the
+    run-time compiler builds one kernel per direction that runs both layers in one launch."""
+    import workloads as wl
+    from paper_1503_02852_amd import binding
+    spec = wl.lstm_net(8, [16, 16], 4)
+    monkeypatch.setenv("RNNG_CHAIN", "0")
+    g0 = binding.Graph(spec.node_array(), spec.edge_array())
+    n_plain = g0.specialise(1)
+    monkeypatch.setenv("RNNG_CHAIN", "1")
+    g1 = binding.Graph(spec.node_array(), spec.edge_array())
+    n_all = g1.specialise(1)
+    if n_plain == 0:
+        pytest.skip("run-time compiler not available")
+    assert n_plain == 4 and n_all == 6
+    # a layer pair linked through a non-recurrent node is not a chain
+    spec5 = wl.generalized_net(8, 16, 2, 4)
+    g2 = binding.Graph(spec5.node_array(), spec5.edge_array())
+    assert g2.specialise(1) == 4

@@ -166,3 +166,41 @@ def test_many_streams_ragged_widths():
 
 def test_many_streams_generalized_small():
     run_both(wl.make_workload("gen_n24", wl.generalized_net(24, 96, 3, 10), T=10, N=24, seed=14, scale=0.15, bias_scale=0.1))
+
+
+# ---- recurrent components that run side by side in one launch (stacked layers linked by full edges) ----
+
+def test_three_layer_lstm_stack():
+    spec = wl.lstm_net(12, [20, 24, 16], 5)
+    run_both(wl.make_workload("lstm3", spec, T=19, N=2, seed=21, scale=0.4, bias_scale=0.3, masked_fraction=0.2))
+
+
+def test_stacked_elman_layers_with_delayed_link():
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 9, name="x")
+    h1 = g.add_node(wl.ADD, wl.TANH, 37, has_bias=True, name="h1")
+    h2 = g.add_node(wl.ADD, wl.SIGMOID, 22, has_bias=True, name="h2")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 6, has_bias=True, is_output=True, name="out")
+    g.add_edge(x, h1, wl.FULL, 0); g.add_edge(h1, h1, wl.FULL, 1)
+    g.add_edge(h1, h2, wl.FULL, 0); g.add_edge(h1, h2, wl.FULL, 2)      # the link between the layers, also delayed
+    g.add_edge(h2, h2, wl.FULL, 1); g.add_edge(h2, h2, wl.FULL, 3)
+    g.add_edge(h2, out, wl.FULL, 0); g.add_edge(h1, out, wl.FULL, 1)    # the lower layer also feeds the output
+    run_both(wl.make_workload("elman2", g, T=23, N=3, seed=22, scale=0.3, bias_scale=0.2))
+
+
+def test_lstm_stack_with_skip_connection_from_the_input():
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 10, name="x")
+    l1 = wl.add_lstm_layer(g, x, 18, "L1")
+    l2 = wl.add_lstm_layer(g, l1["h"], 18, "L2")
+    g.add_edge(x, l2["g"], wl.FULL, 1)               # a batched edge into the upper layer from outside the stack
+    g.add_edge(l1["h"], l2["i"], wl.FULL, 2)         # a second, delayed link between the layers
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 4, has_bias=True, is_output=True, name="out")
+    g.add_edge(l2["h"], out, wl.FULL, 0)
+    run_both(wl.make_workload("lstm_skip", g, T=17, N=1, seed=23, scale=0.4, bias_scale=0.3))
+
+
+def test_lstm_stack_single_frame_and_two_frames():
+    spec = wl.lstm_net(6, [10, 12], 3)
+    run_both(wl.make_workload("lstm2_T1", spec, T=1, N=2, seed=24, scale=0.5))
+    run_both(wl.make_workload("lstm2_T2", spec, T=2, N=1, seed=25, scale=0.5))
