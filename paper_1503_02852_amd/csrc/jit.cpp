@@ -272,20 +272,44 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
     if (!lay.ok) return "";
     MLayout ml;
-    compute_mstep_layout(lay, N, ml);
+    compute_mstep_layout(lay, N, (int)(STEP_LDS_LIMIT / 4), ml);
     if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return "";
-    const int MT = (N + 15) / 16;
-    int nts_max = 1;
-    std::vector<std::pair<int, int>> nts;
-    for (int s = 0; s < ml.n_src; ++s) { const int v = (ml.rows[s] + 15) / 16; nts.push_back({s, v}); nts_max = v > nts_max ? v : nts_max; }
-    if (MT * nts_max > 16) return "";     // accumulator registers
+    const StepPhase& ph = lay.ph[0];
+    const int MT = (N + 15) / 16, NTU = (ph.n_tasks * ph.cmax + 15) / 16;
+    if (MT * NTU > 16) return "";     // accumulator registers
+    const int npad = MT * 16, L = npad * ml.kc / 1024, D = L <= 4 ? 4 : 2;
+    int qshift = 0;
+    while ((1 << qshift) < ml.kc / 4) ++qshift;
+    if (L < 1 || L > 8 || L * 1024 != npad * ml.kc || (1 << qshift) != ml.kc / 4) return "";
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
-    o << "struct MM {\n    static constexpr int MT = " << MT << ", NSRC = " << ml.n_src << ", NTS_MAX = " << nts_max << ";\n";
-    o << "    static __device__ __forceinline__ constexpr int nts(int s) {\n        switch (s) {\n";
-    for (auto& c : nts) o << "            case " << c.first << ": return " << c.second << ";\n";
-    o << "            default: return 0;\n        }\n    }\n};\n";
+    auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases, int dflt) {
+        o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
+        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
+        o << "            default: return " << dflt << ";\n        }\n    }\n";
+    };
+    o << "struct MM {\n    static constexpr int MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
+      << ", KC = " << ml.kc << ", L = " << L << ", D = " << D << ", QSHIFT = " << qshift << ", CMAX = " << ml.cmax
+      << ", XDB = " << ml.xdb << ", PRIV = " << ml.priv << ", ACCS = " << ml.accstride << ";\n";
+    std::vector<std::pair<int, int>> ks, blk, used, ngr;
+    for (int s = 0; s < ml.n_src; ++s) {
+        ks.push_back({s, lay.src[s].k_len});
+        for (int t = 0; t < ph.n_tasks; ++t) if (ml.blk[s][t] >= 0) blk.push_back({s * STEP_MAX_TASKS + t, ml.blk[s][t]});
+        for (int nt = 0; nt < NTU; ++nt) {
+            bool any = false;
+            for (int col = nt * 16; col < nt * 16 + 16; ++col) {
+                const int t = col / ml.cmax;
+                if (t < ph.n_tasks && ml.blk[s][t] >= 0) any = true;
+            }
+            if (any) used.push_back({s * 16 + nt, 1});
+        }
+        ngr.push_back({s, ((lay.src[s].k_len + ml.kc - 1) / ml.kc + D - 1) / D});
+    }
+    emit_switch("K", "s", ks, 0); emit_switch("blk_", "key", blk, -1); emit_switch("used_", "key", used, 0);
+    emit_switch("ngr", "s", ngr, 0);
+    o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n";
+    o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
          "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"

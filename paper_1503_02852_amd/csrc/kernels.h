@@ -59,7 +59,6 @@ hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream);
 // ---------------------------------------------------------------------------------------
 // Persistent recurrent-step kernel (all T steps of one recurrent node and direction)
 // ---------------------------------------------------------------------------------------
-constexpr size_t STEP_LDS_LIMIT = 140 * 1024;   // dynamic LDS per workgroup (static tables take the rest of 160 KiB)
 struct StepLaunchPlan {
     bool ok; int G, NB, xcd_stride; size_t lds_bytes;
 };

@@ -30,6 +30,13 @@ typedef unsigned suintx2 __attribute__((ext_vector_type(2)));
 // compiler barrier at the top of each attempt keeps them from being merged across attempts.
 constexpr int STEP_COHERENT_AUX = 16;
 __device__ __forceinline__ void step_compiler_barrier() { asm volatile("" ::: "memory"); }
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for the
+// wavefront's global loads and stores, so loads issued ahead stay in flight across it.
+__device__ __forceinline__ void step_lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 constexpr int STEP_RSRC_FLAGS = 0x00020000;
 
 
@@ -839,7 +846,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     if (MV::NSRC > 0) {
         float* xs = xs_all + PAR * GX::FLOATS;
         group_poll<MV, NB>(xs, wv, a, t, tid, dead);
-        __syncthreads();
+        step_lds_barrier();
 #if defined(RNNG_STEP_TRACE)
         if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= 64 && step < 72) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - 64)] = clock64();
 #endif
@@ -923,61 +930,91 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 // =============================================================================================
 // Matrix-core variant (run-time specialised, single-phase components, many streams).
 //
-// With N >= 9 streams a step's full connections are skinny GEMMs: acc[n][row] = sum_k
-// x_s[n][k] * W[row][k] over the shared source tensors x_s [N][K_s].  Each workgroup owns a
-// chunk of every layer's units and keeps its weight rows resident in LDS ([row][k], one block of
-// rows per (source, task, edge)).  Per step it polls every source tensor in K-chunks into LDS
-// (sentinel protocol, 128-bit coherent loads), multiplies with v_mfma_f32_16x16x4_f32 (streams
-// are the M dimension, weight rows the N dimension, the four wavefronts split K), adds the
-// per-source accumulators into one [n][row] LDS tile, and runs the element-wise program with
-// one thread per (stream, unit).
+// With N >= 9 streams a step's full connections are skinny GEMMs: acc[n][row] = sum_s sum_k
+// x_s[n][k] * W_s[row][k] over the shared source tensors x_s [N][K_s], row = task * cmax + local
+// unit.  Each workgroup owns a chunk of every layer's units and keeps its weight rows resident in
+// LDS (per source one block of cmax rows for every task the source feeds; a task the source does
+// not feed reads a shared row of zeros).  Per step it polls every source tensor in chunks of KC
+// columns (sentinel protocol, 128-bit coherent loads, D chunks in flight in registers, two
+// chunk buffers in LDS), multiplies with v_mfma_f32_16x16x4_f32 (streams are the M dimension,
+// rows the N dimension, the four wavefronts split each chunk's columns), keeps one accumulator
+// set for all sources, and runs the element-wise program with one thread per (stream, unit).
 //
-// MM is a generated descriptor: static constexpr int MT (ceil(N / 16)), NSRC, NTS_MAX;
-// constexpr nts(s): 16-row tiles of source s.
+// MM is a generated descriptor:
+//   static constexpr int MT (16-stream tiles), NSRC, NTU (16-row tiles), KC, L (128-bit loads per
+//   thread and chunk = MT * 16 * KC / 1024), D (chunks in flight, 2 or 4), QSHIFT (log2(KC / 4)), CMAX,
+//   XDB (1: two chunk buffers in LDS, 0: one), PRIV (per-wavefront accumulator tiles: 1 in the
+//   idle chunk buffer, 2 in a region of their own; 0: one tile, LDS atomics),
+//   ACCS (row stride of an accumulator tile);
+//   constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task) (row block of the task
+//   in source s, -1: none), used(s, nt).
 // =============================================================================================
 typedef float mfloatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned muintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int MSTEP_MAX_BLOCKS = 16;     // (task, edge) blocks per source
+template <int V> struct StepIntC { static constexpr int value = V; };
+template <int C, int N, class F>
+__device__ __forceinline__ void step_static_for(F&& f) {
+    if constexpr (C < N) { f(StepIntC<C>{}); step_static_for<C + 1, N>(f); }
+}
 
 struct MLayout {
-    int ok, n_src, cmax, kc, xstride, xbase, accbase, accstride, total_floats;
-    int wbase[STEP_MAX_SOURCES], wstride[STEP_MAX_SOURCES], rows[STEP_MAX_SOURCES], nblk[STEP_MAX_SOURCES];
-    short blk_task[STEP_MAX_SOURCES][MSTEP_MAX_BLOCKS], blk_edge[STEP_MAX_SOURCES][MSTEP_MAX_BLOCKS];
+    int ok, n_src, cmax, kc, xstride, xbuf, xbase, zrow, accbase, accstride, priv, xdb, nch, total_floats;
+    int wbase[STEP_MAX_SOURCES], wstride[STEP_MAX_SOURCES], rows[STEP_MAX_SOURCES];
+    short blk[STEP_MAX_SOURCES][STEP_MAX_TASKS];     // row block of (source, task) or -1
 };
 
 // Same on host and device.  lay is the generic step layout (tasks, sources) for G workgroups.
-RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, MLayout& m) {
+RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int lds_limit_floats, MLayout& m) {
     m.ok = 0;
-    if (!lay.ok || lay.n_phases != 1) return;
+    if (!lay.ok || lay.n_phases != 1 || lay.n_sources < 1) return;
     const StepPhase& ph = lay.ph[0];
     if (ph.item_chunk * N > STEP_THREADS) return;
     m.n_src = lay.n_sources; m.cmax = ph.cmax;
     const int npad = (N + 15) / 16 * 16;
-    int kc = 8192 / npad / 64 * 64;
-    if (kc < 64) return;
-    if (kc > 1024) kc = 1024;
-    int kmax = 0;
-    for (int s = 0; s < lay.n_sources; ++s) kmax = lay.src[s].k_len > kmax ? lay.src[s].k_len : kmax;
-    const int kmax_pad = (kmax + 63) / 64 * 64;
-    if (kc > kmax_pad) kc = kmax_pad;
-    m.kc = kc; m.xstride = kc + 4;
+    int kmax = 0, wsmax = 0;
+    for (int s = 0; s < lay.n_sources; ++s) {
+        if (lay.src[s].k_len & 3) return;               // rows are read with 128-bit loads
+        kmax = lay.src[s].k_len > kmax ? lay.src[s].k_len : kmax;
+    }
     int cur = 0;
     for (int s = 0; s < lay.n_sources; ++s) {
-        m.nblk[s] = 0;
-        for (int t = 0; t < ph.n_tasks; ++t)
+        int nb = 0;
+        for (int t = 0; t < STEP_MAX_TASKS; ++t) {
+            m.blk[s][t] = -1;
+            if (t >= ph.n_tasks) continue;
             for (int e = 0; e < ph.task[t].n_edges; ++e)
-                if (ph.task[t].e[e].src == s) {
-                    if (m.nblk[s] == MSTEP_MAX_BLOCKS) return;
-                    m.blk_task[s][m.nblk[s]] = (short)t; m.blk_edge[s][m.nblk[s]] = (short)e; ++m.nblk[s];
-                }
-        m.rows[s] = m.nblk[s] * ph.cmax;
+                if (ph.task[t].e[e].src == s && m.blk[s][t] < 0) m.blk[s][t] = (short)nb++;
+        }
+        m.rows[s] = nb * ph.cmax;
         m.wstride[s] = (lay.src[s].k_len + 63) / 64 * 64 + 4;
+        wsmax = m.wstride[s] > wsmax ? m.wstride[s] : wsmax;
         m.wbase[s] = cur; cur += m.rows[s] * m.wstride[s];
     }
-    m.xbase = cur; cur += npad * m.xstride;
-    m.accstride = ph.n_tasks * ph.cmax + 1;
-    m.accbase = cur; cur += npad * m.accstride;
+    m.zrow = cur; cur += wsmax;
+    const int ntu = (ph.n_tasks * ph.cmax + 15) / 16;
+    m.accstride = ntu * 16 + 4;                         // = 4 (mod 16): conflict-free tile rows
+    // chunks of 4 loads per thread (then 4 chunks are in flight) unless the sources are narrow or
+    // there are many streams; two chunk buffers if they fit (then the idle one can take the
+    // per-wavefront accumulator tiles), else one
+    int kc = 64;
+    while (kc < 1024 && 2 * kc * npad <= 4096 && kc < kmax) kc *= 2;
+    if (kc * npad > 8192) return;
+    // accumulators reach the element-wise threads through one tile per wavefront (priv: 1 = in the
+    // idle chunk buffer, 2 = in a region of their own) or, if LDS is short, through one tile and
+    // LDS atomics (priv = 0)
+    const int xbuf = npad * (kc + 4), tile = npad * m.accstride;
+    m.xdb = 1;
+    if (xbuf >= 4 * tile && cur + 2 * xbuf <= lds_limit_floats) m.priv = 1;
+    else if (cur + 2 * xbuf + 4 * tile <= lds_limit_floats) m.priv = 2;
+    else if (cur + 2 * xbuf + tile <= lds_limit_floats) m.priv = 0;
+    else if (cur + xbuf + 4 * tile <= lds_limit_floats) { m.xdb = 0; m.priv = 2; }
+    else if (cur + xbuf + tile <= lds_limit_floats) { m.xdb = 0; m.priv = 0; }
+    else return;
+    m.kc = kc; m.xstride = kc + 4; m.xbuf = xbuf;
+    m.xbase = cur; cur += (m.xdb ? 2 : 1) * xbuf;
+    m.accbase = cur; cur += m.priv == 1 ? 0 : m.priv == 2 ? 4 * tile : tile;
+    m.nch = 0;
     m.total_floats = cur;
     m.ok = 1;
 }
@@ -995,7 +1032,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = a.N, T = a.T;
     StepShared& sh = ms.sh;
-    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, N, sh.lay); compute_mstep_layout(sh.lay, N, ms.ml); }
+    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, N, sh.lay); compute_mstep_layout(sh.lay, N, (int)(STEP_LDS_LIMIT / 4), ms.ml); }
     __syncthreads();
     const StepPhase& ph = sh.lay.ph[0];
     const MLayout& ml = ms.ml;
@@ -1006,20 +1043,25 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     }
     for (int i = tid; i < ml.total_floats; i += STEP_THREADS) lds[i] = 0.0f;
     __syncthreads();
-    // resident weights: W_lds[s][blk * cmax + ul][k]
-    const int cmax = suni(ml.cmax);
+    // resident weights: W_lds[s][blk(s, task) * cmax + ul][k]; edges of one task that share a
+    // source add up in one row
+    constexpr int CMAX = MM::CMAX;
     for (int s = 0; s < ml.n_src; ++s) {
         const int K = sh.lay.src[s].k_len;
-        for (int b = 0; b < ml.nblk[s]; ++b) {
-            const StepTask& task = ph.task[ml.blk_task[s][b]];
-            const StepEdge ed = task.e[ml.blk_edge[s][b]];
-            const float* W = a.weights + ed.w_off;
-            for (int i = tid; i < cmax * K; i += STEP_THREADS) {
-                const int ul = i / K, k = i - ul * K;
-                const int u = w * task.chunk + ul;
-                float v = 0.0f;
-                if (ul < task.chunk && u < task.n_out) v = ed.transposed ? W[(size_t)k * task.n_out + u] : W[(size_t)u * K + k];
-                lds[ml.wbase[s] + (b * cmax + ul) * ml.wstride[s] + k] = v;
+        for (int t = 0; t < ph.n_tasks; ++t) {
+            const StepTask& task = ph.task[t];
+            for (int e = 0; e < task.n_edges; ++e) {
+                const StepEdge ed = task.e[e];
+                if (ed.src != s) continue;
+                const float* W = a.weights + ed.w_off;
+                for (int i = tid; i < CMAX * K; i += STEP_THREADS) {
+                    const int ul = i / K, k = i - ul * K;
+                    const int u = w * task.chunk + ul;
+                    float v = 0.0f;
+                    if (ul < task.chunk && u < task.n_out) v = ed.transposed ? W[(size_t)k * task.n_out + u] : W[(size_t)u * K + k];
+                    lds[ml.wbase[s] + (ml.blk[s][t] * CMAX + ul) * ml.wstride[s] + k] += v;
+                }
+                __syncthreads();
             }
         }
     }
@@ -1027,19 +1069,49 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
     __syncthreads();
 
-    const int kc = suni(ml.kc), xstride = suni(ml.xstride), xbase = suni(ml.xbase);
-    const int accbase = suni(ml.accbase), accstride = suni(ml.accstride);
+    constexpr int KC = MM::KC, L = MM::L, D = MM::D, Q4 = KC / 4, KW = KC / 4;     // KW: columns per wavefront and chunk
+    constexpr int NPAD = MM::MT * 16, XSTRIDE = KC + 4, XBUF = NPAD * XSTRIDE, ACCS = MM::ACCS;
+    const int xbase = suni(ml.xbase), accbase = suni(ml.accbase);
     const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    // this thread's L slots of a chunk: stream n, 4-column group q (the same for every chunk)
+    int slot_n[L], slot_q[L], slot_lds[L];
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        const int p = tid + STEP_THREADS * j;
+        slot_n[j] = p >> MM::QSHIFT; slot_q[j] = p & (Q4 - 1);
+        slot_lds[j] = slot_n[j] * XSTRIDE + 4 * slot_q[j];
+    }
+    // LDS address of the weight row behind each of this lane's tile columns, per source
+    int brow[MM::NSRC][MM::NTU];
+#pragma unroll
+    for (int sidx = 0; sidx < MM::NSRC; ++sidx)
+#pragma unroll
+        for (int nt = 0; nt < MM::NTU; ++nt) {
+            const int col = nt * 16 + (lane & 15);
+            const int task = col / CMAX, ul = col - task * CMAX;
+            int b = -1;
+#pragma unroll
+            for (int t2 = 0; t2 < STEP_MAX_TASKS; ++t2) if (task == t2) b = MM::blk(sidx, t2);
+            brow[sidx][nt] = (b >= 0 ? suni(ml.wbase[sidx]) + (b * CMAX + ul) * suni(ml.wstride[sidx]) : suni(ml.zrow)) + 4 * (lane >> 4);
+        }
+    // A-operand address of this lane inside a chunk buffer
+    int arow[MM::MT];
+#pragma unroll
+    for (int mt = 0; mt < MM::MT; ++mt) arow[mt] = (mt * 16 + (lane & 15)) * XSTRIDE + wave * KW + 4 * (lane >> 4);
+
     bool dead = false;
+    float sn[PH::NG > 0 ? PH::NG : 1];      // STATIC inputs of the next step, loaded one step ahead
     for (int step = 0; step < T; ++step) {
         const int t = a.backward ? T - 1 - step : step;
         float s[MAX_SLOTS];
         RNNG_STAMP(0);
-        // element-wise inputs: registers (carry), plain loads (static), coherent loads (dynamic)
+        // element-wise inputs: registers (carry), early loads (static), coherent loads (dynamic)
 #pragma unroll
         for (int g = 0; g < PH::NG; ++g) {
             if (PH::gkind(g) == GA_KIND_CARRY) {
                 s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+            } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
+                s[g] = sn[g];
             } else if (PH::gkind(g) != GA_KIND_ACC) {
                 const int frame = t + r.goff[g];
                 float v = 0.0f;
@@ -1052,136 +1124,175 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         }
 #pragma unroll
         for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
-        // accumulator tile to zero
-        for (int i = tid; i < ((N + 15) / 16 * 16) * accstride; i += STEP_THREADS) lds[accbase + i] = 0.0f;
+        if (!MM::PRIV)   // the shared accumulator tile to zero (the flush comes after at least one barrier)
+            for (int i = tid; i < NPAD * ACCS; i += STEP_THREADS) lds[accbase + i] = 0.0f;
         RNNG_STAMP(1);
 
+        // one buffer descriptor per source tensor; a frame outside the window gets an empty one
+        // (all its loads return zeros, which pass the sentinel check and contribute nothing)
+        __amdgpu_buffer_rsrc_t rs[MM::NSRC];
 #pragma unroll
         for (int sidx = 0; sidx < MM::NSRC; ++sidx) {
             const StepSource& sc = sh.lay.src[sidx];
-            const int K = suni(sc.k_len), frame = t + suni(sc.frame_off);
-            if (frame < 0 || frame >= T) continue;
-            const int rows = suni(ml.rows[sidx]), wbase = suni(ml.wbase[sidx]), wstride = suni(ml.wstride[sidx]);
-            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)frame * N * K;
-            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, N * K * 4, 0x00020000);
-            mfloatx4 acc[MM::MT][MM::NTS_MAX];
+            const int frame = t + suni(sc.frame_off);
+            const bool in_window = frame >= 0 && frame < T;
+            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)(in_window ? frame : 0) * N * MM::K(sidx);
+            rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * MM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
+        }
+        auto prefetch_statics = [&]() {
+            if (step + 1 < T) {
+                const int t2 = a.backward ? t - 1 : t + 1;
 #pragma unroll
-            for (int mt = 0; mt < MM::MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < MM::NTS_MAX; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
-            for (int k0 = 0; k0 < K; k0 += kc) {
-                const int klen = K - k0 < kc ? K - k0 : kc;
-                __syncthreads();                       // the previous chunk has been consumed
-                // ---- poll the chunk x[n][k0 .. k0 + klen) into LDS, zero the tail of the chunk ----
-                if ((K & 3) == 0) {
-                    const int q4 = klen >> 2, total = N * q4;
-                    for (int base = 0; base < total; base += 8 * STEP_THREADS) {
-                        muintx4 v[8];
-                        int spins = 0;
-                        for (;;) {
-                            bool ok = true;
-                            step_compiler_barrier();
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) {
-                                const int p = base + tid + STEP_THREADS * j;
-                                if (p < total) {
-                                    const int n = p / q4, q = p - n * q4;
-                                    v[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (n * K + k0 + 4 * q) * 4, 0, STEP_COHERENT_AUX);
-                                }
-                            }
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) {
-                                const int p = base + tid + STEP_THREADS * j;
-                                if (p < total)
-                                    ok = ok && v[j].x != STEP_SENTINEL && v[j].y != STEP_SENTINEL && v[j].z != STEP_SENTINEL && v[j].w != STEP_SENTINEL;
-                            }
-                            if (ok || dead) break;
-                            if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
-                        }
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            const int p = base + tid + STEP_THREADS * j;
-                            if (p < total) {
-                                const int n = p / q4, q = p - n * q4;
-                                *reinterpret_cast<muintx4*>(&lds[xbase + n * xstride + 4 * q]) = v[j];
-                            }
-                        }
+                for (int g = 0; g < PH::NG; ++g)
+                    if (PH::gkind(g) == GA_KIND_STATIC) {
+                        const int frame = t2 + r.goff[g];
+                        float x = 0.0f;
+                        if (r.gptr[g] != nullptr && frame >= 0 && frame < T) x = r.gptr[g][(long long)frame * r.gstride[g]];
+                        sn[g] = x;
                     }
-                } else {
-                    const int total = N * klen;
-                    for (int p = tid; p < total; p += STEP_THREADS) {
-                        const int n = p / klen, k = p - n * klen;
-                        unsigned v;
-                        int spins = 0;
-                        for (;;) {
-                            v = __hip_atomic_load(reinterpret_cast<const unsigned*>(g) + (size_t)n * K + k0 + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (v != STEP_SENTINEL || dead) break;
-                            if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
-                        }
-                        lds[xbase + n * xstride + k] = __uint_as_float(v);
-                    }
-                }
-                if (klen < kc) {
-                    const int tail = kc - klen;
-                    for (int p = tid; p < N * tail; p += STEP_THREADS) { const int n = p / tail, k = klen + p - n * tail; lds[xbase + n * xstride + k] = 0.0f; }
-                }
-                __syncthreads();
-                if (sidx == 0 && k0 == 0) { RNNG_STAMP(2); }
-                // ---- MFMA: wavefront `wave` takes k in [wave * kc / 4, (wave + 1) * kc / 4) of the chunk ----
-                const int kw = kc >> 2;
-                for (int kk = wave * kw; kk < (wave + 1) * kw; kk += 16) {
-                    if (kk >= klen) break;
-                    mfloatx4 av[MM::MT], bv[MM::NTS_MAX];
-#pragma unroll
-                    for (int mt = 0; mt < MM::MT; ++mt)
-                        av[mt] = *reinterpret_cast<const mfloatx4*>(&lds[xbase + (mt * 16 + (lane & 15)) * xstride + kk + 4 * (lane >> 4)]);
-#pragma unroll
-                    for (int nt = 0; nt < MM::NTS_MAX; ++nt) {
-                        if (nt < MM::nts(sidx)) {
-                            const int row = nt * 16 + (lane & 15);
-                            const int rr = row < rows ? row : 0;
-                            mfloatx4 b4 = *reinterpret_cast<const mfloatx4*>(&lds[wbase + rr * wstride + k0 + kk + 4 * (lane >> 4)]);
-                            if (row >= rows) b4 = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
-                            bv[nt] = b4;
-                        }
-                    }
-#pragma unroll
-                    for (int mt = 0; mt < MM::MT; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < MM::NTS_MAX; ++nt)
-                            if (nt < MM::nts(sidx)) {
-#pragma unroll
-                                for (int i = 0; i < 4; ++i) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][i], bv[nt][i], acc[mt][nt], 0, 0, 0);
-                            }
-                }
             }
-            // ---- add this source's accumulators into the [n][row] tile: column j of the source's
-            //      tile belongs to block j / cmax (a task), unit j % cmax ----
+        };
+        // ---- chunk pipeline ----
+        // A source's columns are cut into groups of D chunks (the last group padded with empty
+        // chunks whose loads all return zero).  Chunk i of a group lives in register set i and
+        // LDS buffer i & 1, so every index is static although the loop over a source's groups is
+        // not unrolled.  D chunks are in flight: the loads of chunk i of the next group (or of
+        // the next source's first group) are issued as soon as chunk i has been put into LDS.
+        muintx4 v[D][L];
+        auto issue = [&](auto ii, auto ss, int k0) {
+            constexpr int i = decltype(ii)::value, sidx = decltype(ss)::value;
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                const int k = k0 + 4 * slot_q[j];
+                // streams beyond N and columns beyond K read as zeros (offset outside the descriptor)
+                const int off = (slot_n[j] < N && k < MM::K(sidx)) ? (slot_n[j] * MM::K(sidx) + k) * 4 : 0x7FFFFFF0;
+                v[i][j] = __builtin_amdgcn_raw_buffer_load_b128(rs[sidx], off, 0, STEP_COHERENT_AUX);
+            }
+        };
+        step_static_for<0, D>([&](auto ii) { issue(ii, StepIntC<0>{}, decltype(ii)::value * KC); });
+        mfloatx4 acc[MM::MT][MM::NTU];
+#pragma unroll
+        for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < MM::NTU; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+
+        step_static_for<0, MM::NSRC>([&](auto ss) {
+            constexpr int sidx = decltype(ss)::value;
+            constexpr int NGR = MM::ngr(sidx);
+            constexpr int KP = (MM::K(sidx) + 63) / 64 * 64;              // weight rows are zero-padded up to here
+            constexpr bool ragged = NGR * D * KC > KP;                    // some chunk reaches beyond KP
+#pragma unroll 1
+            for (int g = 0; g < NGR; ++g) {
+                step_static_for<0, D>([&](auto ii) {
+                    constexpr int i = decltype(ii)::value;
+                    const int k0 = (g * D + i) * KC;
+                    // ---- complete the chunk: every element must have left the sentinel ----
+                    // (the first check stands apart from the retry loop so that it waits for this
+                    // chunk's loads only, not for the younger chunks' loads behind them)
+                    auto complete = [&]() {
+                        bool ok = true;
+#pragma unroll
+                        for (int j = 0; j < L; ++j)
+                            ok = ok && v[i][j].x != STEP_SENTINEL && v[i][j].y != STEP_SENTINEL && v[i][j].z != STEP_SENTINEL && v[i][j].w != STEP_SENTINEL;
+                        return ok;
+                    };
+                    // The chunk goes into LDS on the fast path and, separately, after the retry
+                    // loop: merged, the stores would wait for every load in flight.
+                    const int xb = xbase + (MM::XDB ? (i & 1) * XBUF : 0);
+                    if (!MM::XDB && (sidx > 0 || i > 0 || g > 0)) step_lds_barrier();      // the previous chunk's readers are done with the buffer
+                    auto put = [&]() {
+#pragma unroll
+                        for (int j = 0; j < L; ++j) *reinterpret_cast<muintx4*>(&lds[xb + slot_lds[j]]) = v[i][j];
+                    };
+                    if (complete() || dead) {
+                        put();
+                    } else {
+                        int spins = 0;
+                        for (;;) {
+                            if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+                            step_compiler_barrier();
+                            issue(ii, ss, k0);
+                            if (complete()) break;
+                        }
+                        put();
+                        step_compiler_barrier();      // keeps the two copies of the stores apart
+                    }
+                    if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); }
+                    step_lds_barrier();      // chunk visible (two buffers: the previous chunk's readers use the other one)
+                    if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
+                    if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(7); }
+                    // ---- loads of the chunk that takes this register set next ----
+                    if (g + 1 < NGR) {
+                        issue(ii, ss, k0 + D * KC);
+                    } else if (sidx + 1 < MM::NSRC) {
+                        issue(ii, StepIntC<(sidx + 1 < MM::NSRC ? sidx + 1 : sidx)>{}, i * KC);
+                    } else if (i == 0) {
+                        prefetch_statics();
+                    }
+                    // ---- matrix cores: this wavefront's KW columns of the chunk ----
+#pragma unroll
+                    for (int kk = 0; kk < KW; kk += 16) {
+                        if (ragged && k0 + wave * KW + kk >= KP) continue;
+                        mfloatx4 av[MM::MT], bv[MM::NTU];
+#pragma unroll
+                        for (int mt = 0; mt < MM::MT; ++mt) av[mt] = *reinterpret_cast<const mfloatx4*>(&lds[xb + arow[mt] + kk]);
+#pragma unroll
+                        for (int nt = 0; nt < MM::NTU; ++nt)
+                            if (MM::used(sidx, nt)) bv[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * KW + kk]);
+#pragma unroll
+                        for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                            for (int nt = 0; nt < MM::NTU; ++nt)
+                                if (MM::used(sidx, nt)) {
+#pragma unroll
+                                    for (int q = 0; q < 4; ++q) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][q], bv[nt][q], acc[mt][nt], 0, 0, 0);
+                                }
+                    }
+                });
+            }
+        });
+        // ---- hand the accumulators to the element-wise threads ----
+        if (MM::PRIV) {
+            // each wavefront stores its partial tile into the chunk buffer that the last chunk did not use
+            const int tb = (MM::PRIV == 1 ? xbase : accbase) + wave * (NPAD * ACCS);      // chunk buffer 0 is idle: the last chunk of a step uses buffer 1
 #pragma unroll
             for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < MM::NTS_MAX; ++nt)
-                    if (nt < MM::nts(sidx)) {
-                        const int col = nt * 16 + (lane & 15);
-                        if (col < rows) {
-                            const int b = col / cmax, ul = col - b * cmax;
-                            const int row = ml.blk_task[sidx][b] * cmax + ul;
+                for (int nt = 0; nt < MM::NTU; ++nt)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int m = mt * 16 + 4 * (lane >> 4) + i;
-                                if (m < N) atomicAdd(&lds[accbase + m * accstride + row], acc[mt][nt][i]);
-                            }
-                        }
+                    for (int i = 0; i < 4; ++i)
+                        lds[tb + (mt * 16 + 4 * (lane >> 4) + i) * ACCS + nt * 16 + (lane & 15)] = acc[mt][nt][i];
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MM::NTU; ++nt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int m = mt * 16 + 4 * (lane >> 4) + i;
+                        if (m < N) atomicAdd(&lds[accbase + m * ACCS + nt * 16 + (lane & 15)], acc[mt][nt][i]);
                     }
         }
         RNNG_STAMP(3);
-        __syncthreads();
+        step_lds_barrier();
         RNNG_STAMP(4);
         // ---- element-wise program: one thread per (stream, unit) ----
         if (r.n >= 0) {
 #pragma unroll
             for (int g = 0; g < PH::NG; ++g)
-                if (PH::gkind(g) == GA_KIND_ACC) s[g] = r.gptr[g] != nullptr ? lds[accbase + r.n * accstride + PH::gaux(g) * cmax + item_il] : 0.0f;
+                if (PH::gkind(g) == GA_KIND_ACC) {
+                    float x = 0.0f;
+                    if (r.gptr[g] != nullptr) {
+                        const int col = PH::gaux(g) * CMAX + item_il;
+                        if (MM::PRIV) {
+                            const int tb = (MM::PRIV == 1 ? xbase : accbase) + r.n * ACCS + col;
+                            x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
+                        } else {
+                            x = lds[accbase + r.n * ACCS + col];
+                        }
+                    }
+                    s[g] = x;
+                }
             PH::ops(s);
 #pragma unroll
             for (int q = 0; q < PH::NST; ++q) {
@@ -1194,9 +1305,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
         }
         RNNG_STAMP(5);
-        __syncthreads();   // the accumulator tile is zeroed again at the top of the next step
-        RNNG_STAMP(6);
-        RNNG_STAMP(7);
+        step_lds_barrier();   // the chunk buffers are written again at the top of the next step
     }
 }
 
