@@ -342,6 +342,8 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     }
     std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
                                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    std::string sleep_opt;
+    if (const char* env = std::getenv("RNNG_MSTEP_SLEEP")) { sleep_opt = "-DMSTEP_RETRY_SLEEP=" + std::to_string(std::atoi(env)); opts.push_back(sleep_opt.c_str()); }
     std::string trace_opt;
     if (const char* env = std::getenv("RNNG_STEP_TRACE"))
         if (std::atoi(env) > 0) { trace_opt = "-DRNNG_STEP_TRACE=" + std::to_string(std::atoi(env)); opts.push_back(trace_opt.c_str()); }

@@ -952,6 +952,9 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 typedef float mfloatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned muintx4 __attribute__((ext_vector_type(4)));
 
+#if !defined(MSTEP_RETRY_SLEEP)
+#define MSTEP_RETRY_SLEEP 0      // units of 64 clocks; measured: backing off only costs time
+#endif
 template <int V> struct StepIntC { static constexpr int value = V; };
 template <int C, int N, class F>
 __device__ __forceinline__ void step_static_for(F&& f) {
@@ -1210,6 +1213,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                         int spins = 0;
                         for (;;) {
                             if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+                            __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);      // back off: retries compete with the producers' stores
                             step_compiler_barrier();
                             issue(ii, ss, k0);
                             if (complete()) break;
