@@ -116,6 +116,24 @@ int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N);
 int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs,
                 int32_t T, int32_t N, void* d_workspace, int64_t ws_bytes, void* hip_stream);
 
+/* Forward pass over frames [t_begin, t_end) of a window of T frames (Section 3.2, BPTT(h; h'):
+ * the forward pass advances by h' new frames while the backward pass covers the last h frames).
+ * Frames [0, t_begin) must already hold the results of earlier calls on the same workspace with
+ * the same T and N (RNN_ERR_SEQUENCE otherwise): delayed connections read them as y(t - d), so a
+ * window computed in pieces equals the window computed at once.  Arguments as in rnn_forward,
+ * which is rnn_forward_range(.., 0, T, ..).  rnn_bptt needs the whole window computed. */
+int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* d_inputs,
+                      int32_t T, int32_t N, int32_t t_begin, int32_t t_end,
+                      void* d_workspace, int64_t ws_bytes, void* hip_stream);
+
+/* Moves the window `frames` frames ahead in time (Section 3.2): every node's activations of
+ * frame t + frames become those of frame t, for t < T - frames; the last `frames` frames are then
+ * undefined until rnn_forward_range(.., T - frames, T, ..) has computed them from the caller's
+ * equally shifted input tensors.  1 <= frames < T; needs a completely computed window.
+ * Activations older than the window start are dropped: a delayed connection longer than
+ * T - frames reads zeros there (Section 2.2's truncation at the window). */
+int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream);
+
 /* DEVICE view of node's activations y [T][N][dim] inside the workspace of the last rnn_forward
  * (for an input node: the caller's own input tensor). */
 int rnn_output(const rnn_graph* g, int32_t node, const float** d_y);

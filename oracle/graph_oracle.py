@@ -24,7 +24,9 @@ Readings where the paper is silent (all listed in the design notes of the reposi
 
 Parity pins (tests/, `-m "not gpu"`): a separately written textbook peephole LSTM and
 Elman net with hand-derived full BPTT, central finite differences of E_total,
-stream-independence, delay-line, unreachable-node and relabelling invariants.
+stream-independence, delay-line, unreachable-node and relabelling invariants; bptt_window
+against bptt itself (whole sequence), against a fresh window when the carried state is exactly
+zero, and against the window alone on a delay-free graph.
 """
 from __future__ import annotations
 
@@ -217,6 +219,29 @@ def bptt(nodes, edges, weights, biases, y, z, targets, T, N):
                 if nodes[e["src"]]["kind"] != INPUT:
                     acc[e["src"]][tau] += _apply_weight_transposed(e, W[m], eps)
     return grad_w, grad_b, delta
+
+
+def bptt_window(nodes, edges, weights, biases, y_long, targets_long, t_first, T, N):
+    """BPTT(h; h') of Section 3.2: the forward pass has run over a longer sequence (y_long from
+    `forward`), the backward pass covers only its T frames [t_first, t_first + T).
+
+    Reading (the paper does not say what the backward pass sees before the window): everything
+    before the window start counts as zero in the backward pass, exactly like the frames before a
+    fresh window -- the in-window activations keep the values the carried state gave them, the
+    connection outputs z_m(t) with t - d_m before the window start are zero, and the weight
+    gradient has no term for them.  With t_first = 0 and T the whole sequence this is `bptt`."""
+    y = [np.array(a[t_first:t_first + T], dtype=np.float64) for a in y_long]
+    W = [None if w is None else np.asarray(w, dtype=np.float64) for w in weights]
+    z = [np.zeros((T, N, nodes[e["dst"]]["dim"])) for e in edges]
+    for m, e in enumerate(edges):
+        for t in range(T):
+            tau = t - e["delay"]
+            if tau >= 0:
+                z[m][t] = _apply_weight(e, W[m], y[e["src"]][tau])
+    targets = {k: np.asarray(v)[t_first:t_first + T] for k, v in targets_long.items()}
+    E = loss(nodes, y, targets)
+    grad_w, grad_b, delta = bptt(nodes, edges, weights, biases, y, z, targets, T, N)
+    return dict(y=y, z=z, loss=E, grad_w=grad_w, grad_b=grad_b, delta=delta)
 
 
 def forward_bptt(nodes, edges, weights, biases, inputs, targets, T, N):

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "librnngraph.so")
 
 EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_param_count",
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
+           "rnn_forward_range", "rnn_shift_window",
            "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_specialise", "rnn_debug_read_control",
            "rnn_profile_enable",
            "rnn_profile_read",
@@ -56,6 +57,10 @@ def load_library(build_if_missing=True):
     lib.rnn_workspace_bytes.restype = C.c_int64
     lib.rnn_forward.argtypes = [vp, vp, C.POINTER(vp), C.c_int32, C.c_int32, vp, C.c_int64, vp]
     lib.rnn_forward.restype = C.c_int
+    lib.rnn_forward_range.argtypes = [vp, vp, C.POINTER(vp), C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int64, vp]
+    lib.rnn_forward_range.restype = C.c_int
+    lib.rnn_shift_window.argtypes = [vp, C.c_int32, vp]
+    lib.rnn_shift_window.restype = C.c_int
     lib.rnn_output.argtypes = [vp, C.c_int32, C.POINTER(vp)]
     lib.rnn_output.restype = C.c_int
     lib.rnn_bptt.argtypes = [vp, vp, C.POINTER(vp), vp]
@@ -173,6 +178,13 @@ class Graph:
     def forward(self, d_weights, d_inputs, T, N, d_workspace, ws_bytes, stream=0):
         arr = (C.c_void_p * max(1, len(d_inputs)))(*d_inputs)
         _check(self.lib.rnn_forward(self.handle, d_weights, arr, T, N, d_workspace, ws_bytes, stream))
+
+    def forward_range(self, d_weights, d_inputs, T, N, t_begin, t_end, d_workspace, ws_bytes, stream=0):
+        arr = (C.c_void_p * max(1, len(d_inputs)))(*d_inputs)
+        _check(self.lib.rnn_forward_range(self.handle, d_weights, arr, T, N, t_begin, t_end, d_workspace, ws_bytes, stream))
+
+    def shift_window(self, frames, stream=0):
+        _check(self.lib.rnn_shift_window(self.handle, frames, stream))
 
     def output_ptr(self, node):
         p = C.c_void_p()

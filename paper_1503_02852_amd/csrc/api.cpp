@@ -104,6 +104,8 @@ struct rnn_graph {
     std::vector<const float*> inputs;     // per exec node id (input nodes only)
     const float* weights = nullptr;
     bool fwd_done = false, bptt_done = false;
+    int fwd_upto = 0;                     // frames [0, fwd_upto) of the current window hold forward results
+    bool framewise = false;               // benchmark mode: every frame on its own, no batching over frames
     PlanView view() const {
         PlanView pv;
         pv.buf_ptr = reinterpret_cast<float* const*>(ws + layout.table_off);
@@ -184,9 +186,11 @@ namespace {
 
 // Launches the GEMM problems of one component and direction, grouped by up to
 // GEMM_MAX_PROBLEMS destinations per launch and GEMM_MAX_PAIRS products per destination.
-hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bool backward, hipStream_t s) {
+// Rows of frames [t0, t1) only.
+hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bool backward, hipStream_t s, int t0, int t1) {
     const int64_t F = (int64_t)g->T * g->N;
-    if (probs.empty()) return hipSuccess;
+    const int64_t r0 = (int64_t)t0 * g->N, rows = (int64_t)(t1 - t0) * g->N;
+    if (probs.empty() || rows <= 0) return hipSuccess;
     const int prof = g->prof.begin(backward ? RNN_PROF_GEMM_BWD : RNN_PROF_GEMM_FWD, s);
     int64_t n_launch = 0;
     size_t max_pairs = 0;
@@ -203,13 +207,13 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
         for (const auto& pp : probs) {
             if (pp.pairs.size() <= round * GEMM_MAX_PAIRS) continue;
             GemmProblem& gp = grp.p[grp.n_problems];
-            gp.C = g->buf(pp.c_buf); gp.ldc = pp.n; gp.M = (int)F; gp.N = pp.n; gp.n_pairs = 0;
+            gp.C = g->buf(pp.c_buf) + r0 * pp.n; gp.ldc = pp.n; gp.M = (int)rows; gp.N = pp.n; gp.n_pairs = 0;
             for (size_t q = round * GEMM_MAX_PAIRS; q < pp.pairs.size() && gp.n_pairs < GEMM_MAX_PAIRS; ++q) {
                 const GemmPairPlan& pr = pp.pairs[q];
                 GemmPair& o = gp.pairs[gp.n_pairs++];
                 o.A = g->buf(pr.a_buf); o.B = g->weights + pr.b_w_off; o.K = pr.k_len; o.lda = pr.k_len;
                 o.ldb = backward ? pp.n : pr.k_len;
-                o.a_row_off = (backward ? pr.delay : -pr.delay) * g->N; o.a_rows = (int)F;
+                o.a_row_off = (int)r0 + (backward ? pr.delay : -pr.delay) * g->N; o.a_rows = (int)F;
             }
             if (++grp.n_problems == GEMM_MAX_PROBLEMS) { hipError_t e = flush(); if (e != hipSuccess) return e; }
         }
@@ -220,7 +224,7 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
     return hipSuccess;
 }
 
-hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
+hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0, int t1) {
     const CompPlan& cp = g->plan.comps[comp];
     const PlanView pv = g->view();
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
@@ -228,7 +232,7 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
     if (!cp.recurrent) {
         const int prof = g->prof.begin(RNN_PROF_OTHER, s);
         for (const PhasePlan& ph : phases) {
-            hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, 0, T, s);
+            hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, t0, t1, s);
             if (e != hipSuccess) return e;
         }
         g->prof.end(prof, (int64_t)phases.size(), s);
@@ -242,11 +246,12 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
     StepLaunchPlan lp;
     const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
     const rnn_graph::JitChoice* jc = g->use_jit ? &g->jit_choice(comp, backward, N) : nullptr;
-    const bool have_jit = jc && !jc->source.empty();
-    const bool have_interp = plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
+    const bool have_jit = jc && !jc->source.empty() && !g->framewise;
+    const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
     if (have_jit || have_interp) {
         for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) {
-            hipError_t e = launch_fill_sentinel(g->buf(b), (int64_t)T * N * g->plan.buf_dim[b], s);
+            const int64_t fr = (int64_t)N * g->plan.buf_dim[b];
+            hipError_t e = launch_fill_sentinel(g->buf(b) + t0 * fr, (t1 - t0) * fr, s);
             if (e != hipSuccess) return e;
         }
         const int spin_limit = 1 << 22;
@@ -254,21 +259,21 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
         if (have_jit) {
             if (hipFunction_t fn = jit_step_function(jc->source)) {
                 StepArgs a;
-                fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit);
+                fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
                 e = jit_launch(fn, a, jc->lp, s);
                 if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(jc->source); }
             }
         }
         if (e != hipSuccess && have_interp)
-            e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, s);
+            e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1, s);
         if (e == hipSuccess) {
             g->prof.end(prof, 1, s);
             return hipSuccess;
         }
         if (have_interp) return e;
     }
-    for (int step = 0; step < T; ++step) {
-        const int t = backward ? T - 1 - step : step;
+    for (int step = 0; step < t1 - t0; ++step) {
+        const int t = backward ? t1 - 1 - step : t0 + step;
         for (const PhasePlan& ph : phases) {
             if (ph.mv_off >= 0) {
                 hipError_t e = launch_step_matvec(pv, ph.mv_off, ph.n_mv_tasks, ph.mv_max_out, g->weights, T, N, t, s);
@@ -286,7 +291,7 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s) {
 
 // All members of a chain in one persistent launch.  hipErrorNotSupported: no such kernel for this
 // chain (the caller then runs the members one after another).
-hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s) {
+hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0, int t1) {
     const ChainPlan& ch = g->plan.chains[chain];
     const rnn_graph::ChainChoice& cc = g->chain_choice(chain, backward, g->N);
     if (cc.source.empty()) return hipErrorNotSupported;
@@ -297,13 +302,14 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s) {
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     for (const CompPlan& m : ch.members)
         for (int b : backward ? m.bwd_shared_bufs : m.fwd_shared_bufs) {
-            hipError_t e = launch_fill_sentinel(g->buf(b), (int64_t)T * N * g->plan.buf_dim[b], s);
+            const int64_t fr = (int64_t)N * g->plan.buf_dim[b];
+            hipError_t e = launch_fill_sentinel(g->buf(b) + t0 * fr, (t1 - t0) * fr, s);
             if (e != hipSuccess) return e;
         }
     StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;
     StepArgs a;
     fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
-                   T, N, backward, 1 << 22);
+                   T, N, backward, 1 << 22, t0, t1);
     a.n_groups = (int)ch.members.size();
     for (int i = 0; i < a.n_groups; ++i) {
         a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
@@ -336,6 +342,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
     if (const char* env = std::getenv("RNNG_CHAIN")) g->use_chains = std::atoi(env) != 0;
+    if (const char* env = std::getenv("RNNG_SCHEDULE")) g->framewise = std::string(env) == "framewise";
     if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
     *out = g;
     return RNN_OK;
@@ -385,13 +392,50 @@ int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N) {
     return make_layout(g->plan, T, N).total;
 }
 
-int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs, int32_t T, int32_t N,
-                void* d_workspace, int64_t ws_bytes, void* hip_stream) {
+namespace {
+
+// Forward pass over frames [t0, t1) of the current window: components in schedule order.
+int forward_frames(rnn_graph* g, int t0, int t1, hipStream_t s) {
+    const Plan& P = g->plan;
+    const int N = g->N;
+    hipError_t e;
+    int chain_done_to = -1;   // components up to this index were run as a chain
+    for (const CompPlan& cp : P.comps) {
+        if (!cp.has_fwd_program) continue;
+        const int c = (int)(&cp - P.comps.data());
+        if (c <= chain_done_to) continue;
+        if (!g->framewise && cp.chain >= 0 && P.chains[cp.chain].first == c && !g->chain_choice(cp.chain, false, N).source.empty()) {
+            const ChainPlan& ch = P.chains[cp.chain];
+            for (const CompPlan& m : ch.members) {
+                e = run_gemms(g, m.fwd_gemms, false, s, t0, t1);
+                if (e != hipSuccess) return fail_hip(e, "forward GEMM");
+            }
+            e = run_chain(g, cp.chain, false, s, t0, t1);
+            if (e == hipSuccess) { chain_done_to = ch.last; continue; }
+            if (e != hipErrorNotSupported) return fail_hip(e, "forward chain kernel");
+        }
+        e = run_gemms(g, cp.fwd_gemms, false, s, t0, t1);
+        if (e != hipSuccess) return fail_hip(e, "forward GEMM");
+        e = run_phases(g, c, false, s, t0, t1);
+        if (e != hipSuccess) return fail_hip(e, "forward node program");
+        if (cp.softmax_node >= 0) {
+            const int dim = P.xnodes[cp.softmax_node].dim;
+            e = launch_softmax_rows(g->buf(P.ybuf(cp.softmax_node)) + (int64_t)t0 * N * dim, (int64_t)(t1 - t0) * N, dim, s);
+            if (e != hipSuccess) return fail_hip(e, "softmax");
+        }
+    }
+    return RNN_OK;
+}
+
+}  // namespace
+
+int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* d_inputs, int32_t T, int32_t N,
+                      int32_t t_begin, int32_t t_end, void* d_workspace, int64_t ws_bytes, void* hip_stream) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
-    g->fwd_done = g->bptt_done = false;
     if (!d_weights || !d_inputs) return fail(RNN_ERR_INVALID_ARGUMENT, "weights / inputs pointer is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
     if ((int64_t)T * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
+    if (t_begin < 0 || t_end > T || t_begin >= t_end) return fail(RNN_ERR_INVALID_ARGUMENT, "frame range must satisfy 0 <= t_begin < t_end <= T");
     const Plan& P = g->plan;
     for (size_t i = 0; i < P.input_nodes.size(); ++i)
         if (!d_inputs[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
@@ -399,7 +443,13 @@ int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inpu
     if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
     if (ws_bytes < L.total) return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(L.total) + " bytes");
+    if (t_begin > 0) {
+        // the earlier frames must be there: same window shape and workspace, computed up to t_begin
+        if (g->ws != static_cast<char*>(d_workspace) || g->T != T || g->N != N || g->fwd_upto < t_begin)
+            return fail(RNN_ERR_SEQUENCE, "frames before t_begin have not been computed in this workspace");
+    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    g->fwd_done = g->bptt_done = false;
 
     g->T = T; g->N = N; g->ws = static_cast<char*>(d_workspace); g->layout = L; g->weights = d_weights;
     g->inputs.assign(P.xnodes.size(), nullptr);
@@ -418,31 +468,46 @@ int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inpu
     e = launch_fill(reinterpret_cast<float*>(g->ws + L.sync_off), SYNC_BYTES / 4, 0.0f, s);
     if (e != hipSuccess) return fail_hip(e, "control word reset");
 
-    int chain_done_to = -1;   // components up to this index were run as a chain
-    for (const CompPlan& cp : P.comps) {
-        if (!cp.has_fwd_program) continue;
-        const int c = (int)(&cp - P.comps.data());
-        if (c <= chain_done_to) continue;
-        if (cp.chain >= 0 && P.chains[cp.chain].first == c && !g->chain_choice(cp.chain, false, N).source.empty()) {
-            const ChainPlan& ch = P.chains[cp.chain];
-            for (const CompPlan& m : ch.members) {
-                e = run_gemms(g, m.fwd_gemms, false, s);
-                if (e != hipSuccess) return fail_hip(e, "forward GEMM");
-            }
-            e = run_chain(g, cp.chain, false, s);
-            if (e == hipSuccess) { chain_done_to = ch.last; continue; }
-            if (e != hipErrorNotSupported) return fail_hip(e, "forward chain kernel");
+    if (g->framewise) {
+        for (int t = t_begin; t < t_end; ++t) {
+            const int rc = forward_frames(g, t, t + 1, s);
+            if (rc != RNN_OK) return rc;
         }
-        e = run_gemms(g, cp.fwd_gemms, false, s);
-        if (e != hipSuccess) return fail_hip(e, "forward GEMM");
-        e = run_phases(g, c, false, s);
-        if (e != hipSuccess) return fail_hip(e, "forward node program");
-        if (cp.softmax_node >= 0) {
-            e = launch_softmax_rows(g->buf(P.ybuf(cp.softmax_node)), (int64_t)T * N, P.xnodes[cp.softmax_node].dim, s);
-            if (e != hipSuccess) return fail_hip(e, "softmax");
+    } else {
+        const int rc = forward_frames(g, t_begin, t_end, s);
+        if (rc != RNN_OK) return rc;
+    }
+    g->fwd_upto = t_end;
+    g->fwd_done = t_end == T;
+    return RNN_OK;
+}
+
+int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs, int32_t T, int32_t N,
+                void* d_workspace, int64_t ws_bytes, void* hip_stream) {
+    return rnn_forward_range(g, d_weights, d_inputs, T, N, 0, T, d_workspace, ws_bytes, hip_stream);
+}
+
+int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (!g->ws || g->fwd_upto != g->T) return fail(RNN_ERR_SEQUENCE, "rnn_shift_window needs a completely computed window");
+    if (frames <= 0 || frames >= g->T) return fail(RNN_ERR_INVALID_ARGUMENT, "frames must lie in [1, T - 1]");
+    const Plan& P = g->plan;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int T = g->T;
+    // y(t) <- y(t + frames), block by block in stream order so that source and destination of one copy never overlap
+    for (size_t k = 0; k < P.xnodes.size(); ++k) {
+        const int b = P.ybuf((int)k);
+        if (P.xnodes[k].kind == NODE_INPUT || g->layout.buf_off[b] < 0) continue;
+        const int64_t fr = (int64_t)g->N * P.buf_dim[b];
+        float* y = g->buf(b);
+        for (int t = 0; t + frames < T; t += frames) {
+            const int n = std::min(frames, T - frames - t);
+            hipError_t e = hipMemcpyAsync(y + t * fr, y + (t + frames) * fr, (size_t)n * fr * sizeof(float), hipMemcpyDeviceToDevice, s);
+            if (e != hipSuccess) return fail_hip(e, "window shift");
         }
     }
-    g->fwd_done = true;
+    g->fwd_upto = T - frames;
+    g->fwd_done = g->bptt_done = false;
     return RNN_OK;
 }
 
@@ -467,32 +532,45 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
     const int T = g->T, N = g->N;
     hipError_t e = launch_fill(reinterpret_cast<float*>(g->loss_ptr()), 2, 0.0f, s);
     if (e != hipSuccess) return fail_hip(e, "loss reset");
-    for (int c = (int)P.comps.size() - 1; c >= 0; --c) {
-        const CompPlan& cp = P.comps[c];
-        if (cp.softmax_node >= 0) {
-            const int k = cp.softmax_node;
-            size_t oi = 0;
-            while (oi < P.output_nodes.size() && P.output_nodes[oi] != k) ++oi;
-            e = launch_softmax_ce_delta(g->buf(P.ybuf(k)), d_targets[oi], g->buf(P.dbuf(k)), g->loss_ptr(),
-                                        (int64_t)T * N, P.xnodes[k].dim, s);
-            if (e != hipSuccess) return fail_hip(e, "softmax / cross-entropy delta");
-            continue;
-        }
-        if (!cp.has_bwd_program) continue;
-        if (cp.chain >= 0 && P.chains[cp.chain].last == c && !g->chain_choice(cp.chain, true, N).source.empty()) {
-            const ChainPlan& ch = P.chains[cp.chain];
-            for (const CompPlan& m : ch.members) {
-                e = run_gemms(g, m.bwd_gemms, true, s);
-                if (e != hipSuccess) return fail_hip(e, "backward GEMM");
+    // the output deltas of all frames first (they depend on the forward pass only)
+    for (const CompPlan& cp : P.comps) {
+        if (cp.softmax_node < 0) continue;
+        const int k = cp.softmax_node;
+        size_t oi = 0;
+        while (oi < P.output_nodes.size() && P.output_nodes[oi] != k) ++oi;
+        e = launch_softmax_ce_delta(g->buf(P.ybuf(k)), d_targets[oi], g->buf(P.dbuf(k)), g->loss_ptr(),
+                                    (int64_t)T * N, P.xnodes[k].dim, s);
+        if (e != hipSuccess) return fail_hip(e, "softmax / cross-entropy delta");
+    }
+    auto backward_frames = [&](int t0, int t1) -> int {
+        for (int c = (int)P.comps.size() - 1; c >= 0; --c) {
+            const CompPlan& cp = P.comps[c];
+            if (cp.softmax_node >= 0 || !cp.has_bwd_program) continue;
+            if (!g->framewise && cp.chain >= 0 && P.chains[cp.chain].last == c && !g->chain_choice(cp.chain, true, N).source.empty()) {
+                const ChainPlan& ch = P.chains[cp.chain];
+                for (const CompPlan& m : ch.members) {
+                    e = run_gemms(g, m.bwd_gemms, true, s, t0, t1);
+                    if (e != hipSuccess) return fail_hip(e, "backward GEMM");
+                }
+                e = run_chain(g, cp.chain, true, s, t0, t1);
+                if (e == hipSuccess) { c = ch.first; continue; }
+                if (e != hipErrorNotSupported) return fail_hip(e, "backward chain kernel");
             }
-            e = run_chain(g, cp.chain, true, s);
-            if (e == hipSuccess) { c = ch.first; continue; }
-            if (e != hipErrorNotSupported) return fail_hip(e, "backward chain kernel");
+            e = run_gemms(g, cp.bwd_gemms, true, s, t0, t1);
+            if (e != hipSuccess) return fail_hip(e, "backward GEMM");
+            e = run_phases(g, c, true, s, t0, t1);
+            if (e != hipSuccess) return fail_hip(e, "backward node program");
         }
-        e = run_gemms(g, cp.bwd_gemms, true, s);
-        if (e != hipSuccess) return fail_hip(e, "backward GEMM");
-        e = run_phases(g, c, true, s);
-        if (e != hipSuccess) return fail_hip(e, "backward node program");
+        return RNN_OK;
+    };
+    if (g->framewise) {
+        for (int t = T - 1; t >= 0; --t) {
+            const int rc = backward_frames(t, t + 1);
+            if (rc != RNN_OK) return rc;
+        }
+    } else {
+        const int rc = backward_frames(0, T);
+        if (rc != RNN_OK) return rc;
     }
     g->bptt_done = true;
     return RNN_OK;

@@ -139,8 +139,9 @@ std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, in
         o << "    PhaseRegs<PH" << p << "> r" << p << "; phase_setup<PH" << p << ", " << NB << ">(r" << p << ", a, sh, lds, w, tid);\n";
     o << "    __syncthreads();\n"
          "    bool dead = false;\n"
-         "    for (int step = 0; step < a.T; ++step) {\n"
-         "        const int t = a.backward ? a.T - 1 - step : step;\n";
+         "    const int nsteps = step_count(a);\n"
+         "    for (int step = 0; step < nsteps; ++step) {\n"
+         "        const int t = step_frame(a, step);\n";
     for (size_t p = 0; p < phases.size(); ++p)
         o << "        phase_step<PH" << p << ", " << NB << ", " << phases.size() << ">(r" << p << ", a, sh, lds, step, t, tid, dead);\n";
     o << "    }\n}\n";
@@ -217,12 +218,13 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    float dfv[PH0::NST > 0 ? PH0::NST : 1] = {0.0f};\n"
          "    bool dead = false;\n"
          "    int step = 0;\n"
-         "    for (; step + 1 < a.T; step += 2) {\n"
-         "        wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, a.backward ? a.T - 1 - step : step, tid, dead);\n"
-         "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, a.backward ? a.T - 2 - step : step + 1, tid, dead);\n"
+         "    const int nsteps = step_count(a);\n"
+         "    for (; step + 1 < nsteps; step += 2) {\n"
+         "        wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
+         "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead);\n"
          "    }\n"
-         "    if (step < a.T) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, a.backward ? a.T - 1 - step : step, tid, dead);\n"
-         "    if (has_units && a.T > 0) wave_flush_stores<PH0>(r0, dfv);\n"
+         "    if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
+         "    if (has_units && nsteps > 0) wave_flush_stores<PH0>(r0, dfv);\n"
          "}\n}  // namespace " << ns << "\n";
     return true;
 }

@@ -29,6 +29,6 @@ void jit_mark_failed(const std::string& source);
 hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream);
 
 void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
-                    unsigned* ctrl, int T, int N, bool backward, int spin_limit);
+                    unsigned* ctrl, int T, int N, bool backward, int spin_limit, int t_begin, int t_end);
 
 }  // namespace rnng

@@ -67,7 +67,8 @@ struct StepLaunchPlan {
 int step_nb_for(int N);   // streams per pass of the step kernel for N streams (0: not supported)
 bool plan_step_launch(const int32_t* words, int desc_off, int N, int force_G, StepLaunchPlan& out);
 hipError_t launch_recurrent_steps(const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
-                                  unsigned* ctrl, int T, int N, bool backward, int spin_limit, hipStream_t stream);
+                                  unsigned* ctrl, int T, int N, bool backward, int spin_limit, int t_begin, int t_end,
+                                  hipStream_t stream);
 // Fills n floats with the "not yet written" bit pattern the step kernel's consumers wait on.
 hipError_t launch_fill_sentinel(float* p, int64_t n, hipStream_t stream);
 

@@ -26,8 +26,9 @@ void recurrent_step_kernel(StepArgs a) {
     float s[MAX_SLOTS];
     bool dead = false;
     int acc_phase = 0;
-    for (int step = 0; step < T; ++step) {
-        const int t = a.backward ? T - 1 - step : step;
+    const int nsteps = step_count(a);
+    for (int step = 0; step < nsteps; ++step) {
+        const int t = step_frame(a, step);
         for (int p = 0; p < n_phases; ++p) {
             const StepPhase& ph = lay.ph[p];
             const ProgramView pg(a.words + suni(ph.prog_off));
@@ -121,7 +122,8 @@ bool plan_step_launch(const int32_t* words, int desc_off, int N, int force_G, St
 }
 
 void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
-                    unsigned* ctrl, int T, int N, bool backward, int spin_limit) {
+                    unsigned* ctrl, int T, int N, bool backward, int spin_limit, int t_begin, int t_end) {
+    a.t_begin = t_begin; a.t_end = t_end;
     a.buf_ptr = pv.buf_ptr; a.words = pv.words; a.weights = weights; a.ctrl = ctrl; a.desc_off = desc_off;
     a.T = T; a.N = N; a.backward = backward ? 1 : 0; a.G = lp.G; a.xcd_stride = lp.xcd_stride; a.spin_limit = spin_limit;
     a.n_groups = 0;
@@ -129,9 +131,10 @@ void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, i
 }
 
 hipError_t launch_recurrent_steps(const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
-                                  unsigned* ctrl, int T, int N, bool backward, int spin_limit, hipStream_t stream) {
+                                  unsigned* ctrl, int T, int N, bool backward, int spin_limit, int t_begin, int t_end,
+                                  hipStream_t stream) {
     StepArgs a;
-    fill_step_args(a, pv, lp, desc_off, weights, ctrl, T, N, backward, spin_limit);
+    fill_step_args(a, pv, lp, desc_off, weights, ctrl, T, N, backward, spin_limit, t_begin, t_end);
     const dim3 grid(lp.G * lp.xcd_stride), block(STEP_THREADS);
     hipError_t e = hipSuccess;
 #define RNNG_LAUNCH(NBV)                                                                                              \

@@ -324,8 +324,8 @@ __device__ __forceinline__ void ring_fill(const PhaseRegs<PH>& r, const StepArgs
         for (int j = 0; j < STEP_PF_MAX_STEPS; ++j) {
             v[j] = 0.0f;
             const int st = first_step + j;
-            if (j < r.pf_steps && st < a.T) {
-                const int frame = (a.backward ? a.T - 1 - st : st) + r.poff[q];
+            if (j < r.pf_steps && st < step_count(a)) {
+                const int frame = step_frame(a, st) + r.poff[q];
                 if (frame >= 0 && frame < a.T) v[j] = r.pbase[q][frame * r.pstride[q]];
             }
         }
@@ -434,7 +434,12 @@ __device__ __forceinline__ void phase_step(PhaseRegs<PH>& r, const StepArgs& a, 
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
         if (PH::gkind(g) == GA_KIND_CARRY) {
-            s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+            if (step > 0) {
+                s[g] = r.carry[PH::cidx(g)];
+            } else {      // first step of this call: the previous frame's value, if the window has one
+                const int frame = t + r.goff[g];
+                s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+            }
         } else if (PH::gkind(g) == GA_KIND_STATIC && ring) {
             s[g] = r.gptr[g] != nullptr ? lds[r.pf_base + ((blk & 1) * r.pf_steps + js) * r.pairs + r.goff[g]] : 0.0f;
         } else if (PH::gkind(g) != GA_KIND_ACC) {
@@ -473,7 +478,7 @@ __device__ __forceinline__ void phase_step(PhaseRegs<PH>& r, const StepArgs& a, 
         if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
     RNNG_STAMP(7);
     // at the first step of a block: fetch the next block of static values into the other ring half
-    if (ring && js == 0 && step + r.pf_steps < a.T) ring_fill<PH>(r, a, lds, step + r.pf_steps, (blk + 1) & 1, tid);
+    if (ring && js == 0 && step + r.pf_steps < step_count(a)) ring_fill<PH>(r, a, lds, step + r.pf_steps, (blk + 1) & 1, tid);
     if (NPHASES > 1 || (ring && !PH::HAS_TASKS)) __syncthreads();
 }
 
@@ -583,7 +588,7 @@ __device__ __forceinline__ void wave_store_setup(PhaseRegs<PH>& r, const StepArg
     for (int q = 0; q < PH::NST; ++q) {
         const bool ok = r.sptr[q] != nullptr;
         r.sok |= ok ? (1u << q) : 0u;
-        r.scur[q] = ok ? r.sptr[q] + (long long)(a.backward ? a.T - 1 : 0) * r.sstride[q] : nullptr;
+        r.scur[q] = ok ? r.sptr[q] + (long long)step_frame(a, 0) * r.sstride[q] : nullptr;
         r.sdelta[q] = a.backward ? -r.sstride[q] : r.sstride[q];
     }
 }
@@ -636,8 +641,8 @@ __device__ __forceinline__ void wave_ring_load(float (&v)[QNA],
 #pragma unroll
     for (int q = 0; q < RG::QN; ++q) {
         v[q] = 0.0f;
-        if (rg.pbase[q] != nullptr && st < a.T) {
-            const int frame = (a.backward ? a.T - 1 - st : st) + rg.poff[q];
+        if (rg.pbase[q] != nullptr && st < step_count(a)) {
+            const int frame = step_frame(a, st) + rg.poff[q];
             if (frame >= 0 && frame < a.T) v[q] = rg.pbase[q][frame * rg.pstride[q]];
         }
     }
@@ -726,7 +731,7 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
         if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
     }
 #if defined(RNNG_STEP_TRACE)
-    const int trace_step = a.backward ? a.T - 1 - t : t;
+    const int trace_step = a.backward ? a.t_end - 1 - t : t - a.t_begin;
     if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= 64 && trace_step < 72) {
         reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (trace_step - 64)] = spins;
         reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (trace_step - 64)] = clock64();
@@ -827,7 +832,12 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
         if (PH::gkind(g) == GA_KIND_CARRY) {
-            s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+            if (step > 0) {
+                s[g] = r.carry[PH::cidx(g)];
+            } else {      // first step of this call: the previous frame's value, if the window has one
+                const int frame = t + r.goff[g];
+                s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+            }
         } else if (PH::gkind(g) == GA_KIND_STATIC) {
             // idle lanes read a valid (unused) ring entry instead of branching around the load
             const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
@@ -1104,15 +1114,21 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 
     bool dead = false;
     float sn[PH::NG > 0 ? PH::NG : 1];      // STATIC inputs of the next step, loaded one step ahead
-    for (int step = 0; step < T; ++step) {
-        const int t = a.backward ? T - 1 - step : step;
+    const int nsteps = step_count(a);
+    for (int step = 0; step < nsteps; ++step) {
+        const int t = step_frame(a, step);
         float s[MAX_SLOTS];
         RNNG_STAMP(0);
         // element-wise inputs: registers (carry), early loads (static), coherent loads (dynamic)
 #pragma unroll
         for (int g = 0; g < PH::NG; ++g) {
             if (PH::gkind(g) == GA_KIND_CARRY) {
-                s[g] = step > 0 ? r.carry[PH::cidx(g)] : 0.0f;
+                if (step > 0) {
+                s[g] = r.carry[PH::cidx(g)];
+            } else {      // first step of this call: the previous frame's value, if the window has one
+                const int frame = t + r.goff[g];
+                s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+            }
             } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
                 s[g] = sn[g];
             } else if (PH::gkind(g) != GA_KIND_ACC) {
@@ -1143,7 +1159,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * MM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
         }
         auto prefetch_statics = [&]() {
-            if (step + 1 < T) {
+            if (step + 1 < nsteps) {
                 const int t2 = a.backward ? t - 1 : t + 1;
 #pragma unroll
                 for (int g = 0; g < PH::NG; ++g)

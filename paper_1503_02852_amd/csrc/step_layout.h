@@ -67,7 +67,13 @@ struct StepArgs {
     // grp_desc_off[g] on grp_G[g] workgroups; block b belongs to group b % 8, part b / 8, which
     // puts each group on one XCD.  n_groups == 0: a single component (desc_off, G, xcd_stride).
     int n_groups, grp_desc_off[STEP_MAX_GROUPS], grp_G[STEP_MAX_GROUPS];
+    // Frames [t_begin, t_end) are computed (forward: ascending, backward: descending); frames of
+    // the window outside this range hold the results of earlier calls (T is the whole window).
+    int t_begin, t_end;
 };
+
+RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }
+RNNG_HD inline int step_frame(const StepArgs& a, int st) { return a.backward ? a.t_end - 1 - st : a.t_begin + st; }
 
 
 // words: plan words; desc_off: step descriptor; G workgroups; NB streams per pass; N streams.

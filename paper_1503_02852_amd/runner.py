@@ -48,6 +48,27 @@ class Window:
         self.g.forward(self.weights.data_ptr(), [self.inputs[k].data_ptr() for k in self.g.input_nodes],
                        self.T, self.N, self.ws_ptr, self.ws_bytes, self._stream())
 
+    def forward_range(self, t_begin, t_end):
+        """Frames [t_begin, t_end) of the window; the frames before them come from earlier calls."""
+        self.g.forward_range(self.weights.data_ptr(), [self.inputs[k].data_ptr() for k in self.g.input_nodes],
+                             self.T, self.N, t_begin, t_end, self.ws_ptr, self.ws_bytes, self._stream())
+
+    def advance(self, new_inputs, new_targets):
+        """Moves the window ahead by the number of frames in new_inputs ([frames][N][dim] per input
+        node; new_targets [frames][N] per output node): shifts the activations and the caller-owned
+        input / target tensors, then computes the new frames from the carried state."""
+        frames = int(next(iter(new_inputs.values())).shape[0])
+        self.g.shift_window(frames, self._stream())
+        for k in self.g.input_nodes:
+            x = self.inputs[k]
+            x[:self.T - frames] = x[frames:].clone()
+            x[self.T - frames:] = torch.from_numpy(np.ascontiguousarray(new_inputs[k], dtype=np.float32)).to(self.dev)
+        for k in self.g.output_nodes:
+            d = self.targets[k]
+            d[:self.T - frames] = d[frames:].clone()
+            d[self.T - frames:] = torch.from_numpy(np.ascontiguousarray(new_targets[k], dtype=np.int32)).to(self.dev)
+        self.forward_range(self.T - frames, self.T)
+
     def bptt(self):
         self.g.bptt(self.weights.data_ptr(), [self.targets[k].data_ptr() for k in self.g.output_nodes], self._stream())
 

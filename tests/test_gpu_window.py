@@ -1,0 +1,117 @@
+"""GPU parity for BPTT(h; h') of Section 3.2: a window computed in pieces, a window moved ahead
+with the state carried over, and the frame-by-frame schedule (no batching over frames), against
+the float64 oracle.  Bars as in test_gpu_parity.py."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import graph_oracle as go
+from tests.test_gpu_parity import GRAD_TOL, OUT_TOL, nerr
+
+pytestmark = pytest.mark.gpu
+
+
+def check_against(win, w, ref, label):
+    for k in range(len(w.spec.nodes)):
+        if w.spec.nodes[k]["kind"] == wl.INPUT:
+            continue
+        e = nerr(win.node_output(k), ref["y"][k])
+        assert e < OUT_TOL, (label, "y", w.spec.nodes[k]["name"], e)
+        e = nerr(win.node_state_grad(k), -ref["delta"][k])
+        assert e < GRAD_TOL, (label, "ds", w.spec.nodes[k]["name"], e)
+    gw, gb = win.grads_unpacked()
+    for m, g in enumerate(ref["grad_w"]):
+        if g is not None:
+            e = nerr(gw[m], g)
+            assert e < GRAD_TOL, (label, "grad_w", m, e)
+    for k, g in enumerate(ref["grad_b"]):
+        if g is not None:
+            e = nerr(gb[k], g)
+            assert e < GRAD_TOL, (label, "grad_b", k, e)
+
+
+WINDOW_NETS = {
+    "lstm2": lambda: (wl.lstm_net(10, [24, 20], 5), 1),
+    "lstm2_streams": lambda: (wl.lstm_net(10, [24, 20], 5), 3),
+    "generalized": lambda: (wl.generalized_net(8, 16, 2, 4), 2),
+    "lstm_many_streams": lambda: (wl.lstm_net(8, [32], 4), 20),
+}
+
+
+@pytest.mark.parametrize("name", sorted(WINDOW_NETS))
+def test_window_computed_in_pieces_equals_the_window_at_once(name):
+    from paper_1503_02852_amd.runner import window_for
+    spec, N = WINDOW_NETS[name]()
+    w = wl.make_workload(name, spec, T=24, N=N, seed=41, scale=0.4, bias_scale=0.3, masked_fraction=0.3)
+    print(f"[window] pieces {name}: T={w.T} N={w.N}", flush=True)
+    ref = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+    win = window_for(w)
+    for t0, t1 in ((0, 7), (7, 8), (8, 19), (19, 24)):
+        win.forward_range(t0, t1)
+    win.bptt()
+    loss = win.compute_grads(want_loss=True)
+    check_against(win, w, ref, name)
+    assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
+
+
+def test_forward_range_needs_the_earlier_frames():
+    from paper_1503_02852_amd.binding import RnnError
+    from paper_1503_02852_amd.runner import window_for
+    w = wl.make_workload("seq", wl.lstm_net(6, [8], 3), T=10, N=1, seed=42)
+    win = window_for(w)
+    with pytest.raises(RnnError):
+        win.forward_range(4, 10)          # nothing computed yet
+    win.forward_range(0, 4)
+    with pytest.raises(RnnError):
+        win.forward_range(6, 10)          # gap
+    with pytest.raises(RnnError):
+        win.bptt()                        # window incomplete
+    win.forward_range(4, 10)
+    win.bptt()
+
+
+@pytest.mark.parametrize("name", sorted(WINDOW_NETS))
+def test_window_moved_ahead_with_carried_state(name):
+    """Forward over T frames, then the window advances twice by h' = T / 2 new frames.  Activations
+    must equal the oracle's forward pass over the whole sequence; the gradients (targets of the
+    older half masked) must equal the oracle's backward pass over the window's frames."""
+    from paper_1503_02852_amd.runner import window_for
+    spec, N = WINDOW_NETS[name]()
+    T, hp = 16, 8
+    L = T + 2 * hp
+    long = wl.make_workload(name, spec, T=L, N=N, seed=43, scale=0.4, bias_scale=0.3)
+    print(f"[window] carry {name}: T={T} h'={hp} N={N}", flush=True)
+    y_long, _ = go.forward(long.spec.nodes, long.spec.edges, long.weights, long.biases, long.inputs, L, N)
+    first = wl.Workload(name=name, spec=spec, T=T, N=N, weights=long.weights, biases=long.biases,
+                        inputs={k: v[:T].copy() for k, v in long.inputs.items()},
+                        targets={k: v[:T].copy() for k, v in long.targets.items()})
+    win = window_for(first)
+    win.forward()
+    for step in (1, 2):
+        a, b = step * hp, step * hp + T
+        new_targets = {k: v[b - hp:b] for k, v in long.targets.items()}
+        win.advance({k: v[b - hp:b] for k, v in long.inputs.items()}, new_targets)
+        # the older part of the window has been trained on already: mask it
+        masked = {k: v[a:b].copy() for k, v in long.targets.items()}
+        for k in masked:
+            masked[k][:T - hp] = -1
+            win.targets[k][:T - hp] = -1
+        win.bptt()
+        loss = win.compute_grads(want_loss=True)
+        tl = {k: np.concatenate([np.full_like(v[:a], -1), masked[k], np.full_like(v[b:], -1)]) for k, v in long.targets.items()}
+        ref = go.bptt_window(long.spec.nodes, long.spec.edges, long.weights, long.biases, y_long, tl, a, T, N)
+        check_against(win, first, ref, f"{name} advance {step}")
+        assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
+
+
+def test_frame_by_frame_schedule_gives_the_same_results(monkeypatch):
+    """The baseline schedule of Section 4 (every frame on its own) must reach the oracle as well."""
+    from paper_1503_02852_amd.runner import window_for
+    monkeypatch.setenv("RNNG_SCHEDULE", "framewise")
+    w = wl.make_workload("framewise", wl.generalized_net(8, 16, 2, 4), T=11, N=2, seed=44, scale=0.4, bias_scale=0.3)
+    ref = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+    win = window_for(w)
+    win.forward(); win.bptt()
+    loss = win.compute_grads(want_loss=True)
+    check_against(win, w, ref, "framewise")
+    assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))

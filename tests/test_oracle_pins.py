@@ -294,3 +294,93 @@ def test_delay0_cycle_is_rejected():
     g.add_edge(x, a, wl.FULL); g.add_edge(a, b, wl.FULL); g.add_edge(b, a, wl.FULL, 0)
     with pytest.raises(ValueError):
         go.delay0_topological_order(g.nodes, g.edges)
+
+
+# ---- BPTT(h; h') of Section 3.2: backward pass over the last frames of a longer forward pass ----
+
+def test_windowed_bptt_over_the_whole_sequence_is_plain_bptt():
+    w = wl.make_workload("gen", wl.generalized_net(5, 6, 2, 3), T=9, N=2, seed=31, scale=0.6, bias_scale=0.3)
+    ref = run_oracle(w)
+    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, ref["y"], w.targets, 0, w.T, w.N)
+    assert win["loss"] == pytest.approx(ref["loss"], rel=1e-14)
+    for a, b in zip(win["grad_w"], ref["grad_w"]):
+        if b is not None:
+            np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-15)
+    for k in range(len(w.spec.nodes)):
+        np.testing.assert_allclose(win["delta"][k], ref["delta"][k], rtol=1e-13, atol=1e-15)
+
+
+def test_windowed_bptt_with_zero_carried_state_is_a_fresh_window():
+    """Zero inputs and zero biases keep every LSTM activation that feeds a delayed connection
+    (c, h) at exactly zero, so the state carried into the window is the fresh state and the window
+    must give what forward + BPTT on its frames alone gives."""
+    spec = wl.lstm_net(4, [5, 6], 3)
+    L, T, N = 13, 8, 2
+    w = wl.make_workload("carry0", spec, T=L, N=N, seed=32, scale=0.7, bias_scale=0.0)
+    t_first = L - T
+    for k in w.inputs:
+        w.inputs[k][:t_first] = 0.0
+    # the output bias may be anything; the LSTM gate biases are zero (bias_scale = 0)
+    y, _ = go.forward(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, L, N)
+    for name in ("L1.c", "L1.h", "L2.c", "L2.h"):
+        assert np.all(y[spec.node_by_name(name)][:t_first] == 0.0)
+    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, y, w.targets, t_first, T, N)
+    fresh = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases,
+                            {k: v[t_first:] for k, v in w.inputs.items()}, {k: v[t_first:] for k, v in w.targets.items()}, T, N)
+    assert win["loss"] == pytest.approx(fresh["loss"], rel=1e-13)
+    for a, b in zip(win["grad_w"], fresh["grad_w"]):
+        if b is not None:
+            np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+    for a, b in zip(win["grad_b"], fresh["grad_b"]):
+        if b is not None:
+            np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_windowed_bptt_on_a_delay_free_graph_is_the_window_alone():
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 4, name="x")
+    a = g.add_node(wl.ADD, wl.TANH, 6, has_bias=True, name="a")
+    b = g.add_node(wl.ADD, wl.SIGMOID, 6, has_bias=True, name="b")
+    m = g.add_node(wl.MUL, wl.LINEAR, 6, name="m")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 3, has_bias=True, is_output=True, name="out")
+    g.add_edge(x, a, wl.FULL, 0); g.add_edge(x, b, wl.FULL, 0)
+    g.add_edge(a, m, wl.IDENTITY, 0); g.add_edge(b, m, wl.DIAG, 0); g.add_edge(m, out, wl.FULL, 0)
+    L, T, N = 11, 5, 3
+    w = wl.make_workload("ff", g, T=L, N=N, seed=33, scale=0.8, bias_scale=0.5)
+    y, _ = go.forward(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, L, N)
+    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, y, w.targets, L - T, T, N)
+    alone = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases,
+                            {k: v[L - T:] for k, v in w.inputs.items()}, {k: v[L - T:] for k, v in w.targets.items()}, T, N)
+    for p, q in zip(win["grad_w"], alone["grad_w"]):
+        if q is not None:
+            np.testing.assert_allclose(p, q, rtol=1e-12, atol=1e-14)
+
+
+def test_windowed_bptt_counts_pre_window_connection_outputs_as_zero():
+    """Hand-derived one-frame window.  p(t) = u(t) * x(t-1), u = w x, y = softmax(W2 p); the window
+    is the sequence's second frame.  The forward value p keeps x of the frame before the window,
+    but in the backward pass that connection output counts as zero: eps on u -> p is
+    delta_p * 0, so dE/dw = 0, while dE/dW2 = -(d - y) p^T with the true p."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 1, name="x")
+    u = g.add_node(wl.ADD, wl.LINEAR, 1, name="u")
+    p = g.add_node(wl.MUL, wl.LINEAR, 1, name="p")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 2, is_output=True, name="out")
+    e_w = g.add_edge(x, u, wl.FULL, 0)
+    g.add_edge(u, p, wl.IDENTITY, 0)
+    g.add_edge(x, p, wl.IDENTITY, 1)
+    e_w2 = g.add_edge(p, out, wl.FULL, 0)
+    weights = [None] * len(g.edges)
+    weights[e_w] = np.array([[0.7]]); weights[e_w2] = np.array([[0.4], [-0.9]])
+    biases = [None] * len(g.nodes)
+    xs = np.array([1.5, -2.0]).reshape(2, 1, 1)
+    targets = {out: np.array([[1], [0]])}
+    y, _ = go.forward(g.nodes, g.edges, weights, biases, {x: xs}, 2, 1)
+    p1 = 0.7 * (-2.0) * 1.5
+    assert y[p][1, 0, 0] == pytest.approx(p1)
+    win = go.bptt_window(g.nodes, g.edges, weights, biases, y, targets, 1, 1, 1)
+    s = np.array([0.4 * p1, -0.9 * p1])
+    sm = np.exp(s) / np.exp(s).sum()
+    assert win["loss"] == pytest.approx(-np.log(sm[0]))
+    np.testing.assert_allclose(win["grad_w"][e_w2][:, 0], (sm - np.array([1.0, 0.0])) * p1, rtol=1e-12)
+    assert win["grad_w"][e_w][0, 0] == 0.0
