@@ -10,7 +10,7 @@ oracle timed on the host cores on a bounded sample of the same workload.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload speech_n1] [--no-cpu-baseline] [--no-framewise]
 
 Workloads: speech_n1 (default: 2 x 256 peephole LSTM, T = 1024, N = 1), charlm_n1, charlm_n32,
-generalized_n64, tiny.
+generalized_n64, tiny; the paper's Section 4 shapes lm_elman_n1, lm_lstm_n1 (38,000-512-20,000, T = 2048).
 """
 import argparse
 import json
@@ -216,7 +216,8 @@ def main():
                                          speedup_of_default_schedule=value / (frames / dt_fw))
         del win_fw
     if not args.no_cpu_baseline:
-        T_sample = {"tiny": 20, "speech_n1": 1024, "charlm_n1": 512, "charlm_n32": 256, "generalized_n64": 16}[args.workload]
+        T_sample = {"tiny": 20, "speech_n1": 1024, "charlm_n1": 512, "charlm_n32": 256, "generalized_n64": 16,
+                    "lm_elman_n1": 256, "lm_lstm_n1": 256}[args.workload]
         out["cpu_baseline"] = cpu_baseline(args.workload, T_sample)
     print(json.dumps(out))
 

@@ -204,3 +204,10 @@ def test_lstm_stack_single_frame_and_two_frames():
     spec = wl.lstm_net(6, [10, 12], 3)
     run_both(wl.make_workload("lstm2_T1", spec, T=1, N=2, seed=24, scale=0.5))
     run_both(wl.make_workload("lstm2_T2", spec, T=2, N=1, seed=25, scale=0.5))
+
+
+# ---- the paper's own Section 4 network shapes (38,000-word one-hot input, 20,000-way softmax) ----
+
+@pytest.mark.parametrize("name", ["lm_elman_n1", "lm_lstm_n1"])
+def test_language_model_shapes_short_window(name):
+    run_both(wl.make_config(name, T=24, N=2), check_all_nodes=True, label=name)

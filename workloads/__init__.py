@@ -267,6 +267,21 @@ def draw_symbol_streams(spec, rng, T, N):
     return {x: inp}, {o: tgt}
 
 
+def draw_word_streams(spec, rng, T, N):
+    """Word-LM-shaped data (the shape of the paper's Section 4 experiment): input frame t is the
+    one-hot of a uniform word over the input vocabulary, the target a uniform word over the
+    (smaller) output vocabulary.  Streams are drawn in order."""
+    (x,) = spec.input_nodes()
+    (o,) = spec.output_nodes()
+    V, Vo = spec.nodes[x]["dim"], spec.nodes[o]["dim"]
+    inp = np.zeros((T, N, V), dtype=np.float32)
+    tgt = np.zeros((T, N), dtype=np.int32)
+    for n in range(N):
+        inp[np.arange(T), n, rng.integers(0, V, size=T)] = 1.0
+        tgt[:, n] = rng.integers(0, Vo, size=T)
+    return {x: inp}, {o: tgt}
+
+
 class Workload:
     def __init__(self, name, spec, T, N, weights, biases, inputs, targets):
         self.name, self.spec, self.T, self.N = name, spec, T, N
@@ -278,6 +293,7 @@ class Workload:
 
 
 CONFIG_NAMES = ["tiny", "speech_n1", "charlm_n1", "charlm_n32", "generalized_n64"]
+EXPERIMENT_SHAPES = ["lm_elman_n1", "lm_lstm_n1"]      # the paper's own Section 4 network shapes, synthetic words
 
 
 def make_config(name, seed=0, T=None, N=None, bias_scale=0.0):
@@ -294,6 +310,10 @@ def make_config(name, seed=0, T=None, N=None, bias_scale=0.0):
         spec, T0, N0, a, kind = lstm_net(30, [512, 512], 30), 256, 32, 0.08, "symbols"
     elif name == "generalized_n64":
         spec, T0, N0, a, kind = generalized_net(128, 1024, 3, 256), 128, 64, 0.05, "gauss"
+    elif name == "lm_elman_n1":      # Section 4: Elman network 38,000-512-20,000, mini-batch 1,024, BPTT(2h'; h')
+        spec, T0, N0, a, kind = elman_net(38000, 512, 20000), 2048, 1, 0.05, "words"
+    elif name == "lm_lstm_n1":       # Section 4: LSTM without the block-output -> gate recurrence, same sizes
+        spec, T0, N0, a, kind = lstm_net(38000, [512], 20000, output_recurrence=False), 2048, 1, 0.05, "words"
     else:
         raise ValueError(name)
     T = T0 if T is None else T
@@ -302,6 +322,8 @@ def make_config(name, seed=0, T=None, N=None, bias_scale=0.0):
     if kind == "gauss":
         inputs = draw_gaussian_inputs(spec, rng, T, N)
         targets = draw_class_targets(spec, rng, T, N)
+    elif kind == "words":
+        inputs, targets = draw_word_streams(spec, rng, T, N)
     else:
         inputs, targets = draw_symbol_streams(spec, rng, T, N)
     return Workload(name, spec, T, N, weights, biases, inputs, targets)
