@@ -200,6 +200,22 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
         grp.split_k = 1; grp.accumulate = round > 0;
         auto flush = [&]() -> hipError_t {
             if (grp.n_problems == 0) return hipSuccess;
+            // Few output tiles and a long contraction (huge input layers): split the contraction over
+            // more workgroups, which add their parts atomically into the zeroed destination.
+            int64_t tiles = 0; int kmax = 0;
+            for (int i = 0; i < grp.n_problems; ++i) {
+                tiles += (int64_t)((grp.p[i].M + 127) / 128) * ((grp.p[i].N + 127) / 128);
+                for (int q = 0; q < grp.p[i].n_pairs; ++q) kmax = std::max(kmax, grp.p[i].pairs[q].K);
+            }
+            int split = 1;
+            if (tiles < 256) split = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, kmax / 512), (512 + tiles - 1) / tiles));
+            grp.split_k = split;
+            if (split > 1 && !grp.accumulate)
+                for (int i = 0; i < grp.n_problems; ++i) {
+                    hipError_t e = launch_fill(grp.p[i].C, (int64_t)grp.p[i].M * grp.p[i].ldc, 0.0f, s);
+                    if (e != hipSuccess) return e;
+                    ++n_launch;
+                }
             hipError_t e = launch_gemm_group(backward ? GEMM_NN : GEMM_NT, grp, s);
             grp.n_problems = 0; ++n_launch;
             return e;
