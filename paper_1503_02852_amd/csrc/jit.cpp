@@ -179,7 +179,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         o << "            default: return 0;\n        }\n    }\n";
     };
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
-      << ", RW = " << RW << ", XF = " << XF << ";\n";
+      << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ";\n";
     std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
     for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});
     for (int t = 0; t < ph.n_tasks; ++t) {
@@ -224,7 +224,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead);\n"
          "    }\n"
          "    if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
-         "    if (has_units && nsteps > 0) wave_flush_stores<PH0>(r0, dfv);\n"
+         "    if (!MV::EARLY && has_units && nsteps > 0) wave_flush_stores<PH0>(r0, dfv);\n"
          "}\n}  // namespace " << ns << "\n";
     return true;
 }

@@ -495,7 +495,7 @@ __device__ __forceinline__ void phase_step(PhaseRegs<PH>& r, const StepArgs& a, 
 //
 // MV is a generated descriptor:
 //   static constexpr int NT (tasks), UW (units per wavefront), NSRC, RW (weight registers),
-//   XF (source registers per stream);  constexpr nedges(task), esrc(task, e), F(src), K(src),
+//   XF (source registers per stream), EARLY (placement of the non-shared stores);  constexpr nedges(task), esrc(task, e), F(src), K(src),
 //   xoff(src), woff(ul, task, e).
 // =============================================================================================
 __device__ __forceinline__ float wave_sum_dpp(float v) {
@@ -803,8 +803,9 @@ __device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&t
     }
 }
 
-// Stores of values no other workgroup waits for are issued one step late (after the next step's
-// poll), so that they do not sit in front of that poll in the wavefront's memory queue.
+// Stores of values no other workgroup waits for are issued either right behind the shared stores
+// (MV::EARLY, forward loops: measured faster, their acknowledgements overlap the exchange) or one
+// step late, after the next step's poll (backward loops: measured faster there).
 template <class PH, int NSTA>
 __device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA]) {
 #pragma unroll
@@ -873,7 +874,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     }
     RNNG_STAMP(2);
     // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
-    if (step > 0) {
+    if (!MV::EARLY && step > 0) {
         wave_flush_stores<PH>(r, dfv);
 #pragma unroll
         for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
@@ -927,6 +928,12 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     for (int q = 0; q < PH::NST; ++q) {
         if (PH::stshared(q)) { if ((r.sok >> q) & 1) store_shared(r.scur[q], s[PH::stslot(q)]); }
         else dfv[q] = s[PH::stslot(q)];
+    }
+    if (MV::EARLY) {
+        // the other stores right behind the shared ones: their acknowledgements overlap the exchange
+        wave_flush_stores<PH>(r, dfv);
+#pragma unroll
+        for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
     }
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
