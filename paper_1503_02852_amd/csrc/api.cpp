@@ -3,6 +3,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <cstring>
 #include <map>
 #include <new>
@@ -35,8 +36,11 @@ struct Layout {
 };
 constexpr int64_t SYNC_BYTES = 1024;
 
+int64_t g_layout_skew = 4352;      // bytes, a multiple of 256 (RNNG_LAYOUT_SKEW overrides: tuning aid)
+
 Layout make_layout(const Plan& P, int T, int N) {
     Layout L;
+    int n_alloc = 0;
     const int K = (int)P.xnodes.size();
     int64_t cur = 0;
     L.table_off = cur; cur += (int64_t)P.n_bufs * 8;
@@ -53,6 +57,10 @@ Layout make_layout(const Plan& P, int T, int N) {
         if (!P.buf_alloc[b]) continue;
         const int64_t rows = P.buf_alloc[b] == 1 ? F : N;
         L.buf_off[b] = cur; cur = align_up(cur + rows * P.buf_dim[b] * 4, 256);
+        // Tensors of the same shape would lie a power of two apart, so the lines that a step polls
+        // in several tensors at the same frame would all fall on the same memory channel: skew them.
+        cur += g_layout_skew * (1 + n_alloc % 13);
+        ++n_alloc;
     }
     L.total = cur;
     return L;
@@ -240,6 +248,24 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
     return hipSuccess;
 }
 
+// Sentinel prefill of the tensors that workgroups poll during frames [t0, t1).  The wave-autonomous
+// kernel polls the interleaved bundle tensors instead of bundled members; the members are filled as
+// well, so that a fall-back to another kernel build finds them prepared.
+hipError_t fill_shared(rnn_graph* g, const std::vector<int>& bufs, bool with_bundles, int t0, int t1, hipStream_t s) {
+    std::vector<int> list(bufs);
+    if (with_bundles)
+        for (int b : bufs) {
+            const int bi = g->plan.bundle_of[b];
+            if (bi >= 0 && std::find(list.begin(), list.end(), g->plan.bundles[bi].ebuf) == list.end()) list.push_back(g->plan.bundles[bi].ebuf);
+        }
+    for (int b : list) {
+        const int64_t fr = (int64_t)g->N * g->plan.buf_dim[b];
+        hipError_t e = launch_fill_sentinel(g->buf(b) + t0 * fr, (t1 - t0) * fr, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0, int t1) {
     const CompPlan& cp = g->plan.comps[comp];
     const PlanView pv = g->view();
@@ -265,11 +291,8 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
     const bool have_jit = jc && !jc->source.empty() && !g->framewise;
     const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
     if (have_jit || have_interp) {
-        for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) {
-            const int64_t fr = (int64_t)N * g->plan.buf_dim[b];
-            hipError_t e = launch_fill_sentinel(g->buf(b) + t0 * fr, (t1 - t0) * fr, s);
-            if (e != hipSuccess) return e;
-        }
+        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, have_jit && jc->wave, t0, t1, s);
+        if (fe != hipSuccess) return fe;
         const int spin_limit = 1 << 22;
         hipError_t e = hipErrorUnknown;
         if (have_jit) {
@@ -316,12 +339,10 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int 
     const PlanView pv = g->view();
     const int T = g->T, N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
-    for (const CompPlan& m : ch.members)
-        for (int b : backward ? m.bwd_shared_bufs : m.fwd_shared_bufs) {
-            const int64_t fr = (int64_t)N * g->plan.buf_dim[b];
-            hipError_t e = launch_fill_sentinel(g->buf(b) + t0 * fr, (t1 - t0) * fr, s);
-            if (e != hipSuccess) return e;
-        }
+    for (const CompPlan& m : ch.members) {
+        hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, true, t0, t1, s);
+        if (e != hipSuccess) return e;
+    }
     StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;
     StepArgs a;
     fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
@@ -359,6 +380,9 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
     if (const char* env = std::getenv("RNNG_CHAIN")) g->use_chains = std::atoi(env) != 0;
     if (const char* env = std::getenv("RNNG_SCHEDULE")) g->framewise = std::string(env) == "framewise";
+    if (const char* env = std::getenv("RNNG_LAYOUT_SKEW")) g_layout_skew = std::atoll(env) / 256 * 256;
+    if (const char* env = std::getenv("RNNG_BUNDLE"))
+        if (std::atoi(env) == 0) g->plan.bundle_of.assign(g->plan.bundle_of.size(), -1);      // tuning aid: no exchange bundles
     if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
     *out = g;
     return RNN_OK;

@@ -166,7 +166,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     int XF = 0;
     for (int s = 0; s < lay.n_sources; ++s) { F[s] = (lay.src[s].k_len + 63) / 64; xoff[s] = XF; XF += F[s]; }
     if (XF * NB > 96) return false;
-    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 16 || NB * 64 * F[s] > 8 * 256) return false;
+    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 16) return false;
     int per_unit = 0;
     for (int t = 0; t < ph.n_tasks; ++t) for (int e = 0; e < ph.task[t].n_edges; ++e) per_unit += F[ph.task[t].e[e].src];
     const int RW = UW * per_unit;
@@ -178,8 +178,52 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
         o << "            default: return 0;\n        }\n    }\n";
     };
+    // polled regions: sources that belong to an exchange bundle share the bundle's interleaved tensor
+    struct Region { int buf, foff, rk, fr, off; };
+    std::vector<Region> regs;
+    std::vector<int> sreg(lay.n_sources), sb(lay.n_sources), sj(lay.n_sources);
+    int XFR = 0;
+    for (int s = 0; s < lay.n_sources; ++s) {
+        const int bi = P.bundle_of[lay.src[s].buf];
+        int rbuf = lay.src[s].buf, B = 1, j = 0;
+        if (bi >= 0) {
+            const BundlePlan& bp = P.bundles[bi];
+            rbuf = bp.ebuf; B = bp.B;
+            for (int m = 0; m < 4; ++m) if (bp.members[m] == lay.src[s].buf) j = m;
+        }
+        int r = 0;
+        for (; r < (int)regs.size(); ++r) if (regs[r].buf == rbuf && regs[r].foff == lay.src[s].frame_off) break;
+        if (r == (int)regs.size()) {
+            const int fr = F[s] * B;
+            regs.push_back(Region{rbuf, lay.src[s].frame_off, lay.src[s].k_len * B, fr, XFR});
+            XFR += fr;
+        }
+        sreg[s] = r; sb[s] = B; sj[s] = j;
+    }
+    for (const Region& rg : regs) if (NB * rg.rk > ((rg.rk & 1) ? 2048 : 4096)) return false;
+    // bundle stores: stores of this program into bundle members
+    const int32_t* pw0 = P.words.data() + phases[0].prog_off;
+    const int32_t* st0 = pw0 + PG_HEADER_WORDS + pw0[PG_NGATHER] * GA_WORDS + pw0[PG_NINV] * IV_WORDS + pw0[PG_NOPS] * MO_WORDS;
+    struct BStore { int bundle; int q[4]; };
+    std::vector<BStore> bstores;
+    std::vector<std::pair<int, int>> bundled;
+    for (int q = 0; q < pw0[PG_NSTORES]; ++q) {
+        if (!(st0[q * ST_WORDS + ST_FLAGS] & 1)) continue;
+        const int bi = P.bundle_of[st0[q * ST_WORDS + ST_BUF]];
+        if (bi < 0) continue;
+        size_t k = 0;
+        for (; k < bstores.size(); ++k) if (bstores[k].bundle == bi) break;
+        if (k == bstores.size()) bstores.push_back(BStore{bi, {-1, -1, -1, -1}});
+        for (int m = 0; m < 4; ++m) if (P.bundles[bi].members[m] == st0[q * ST_WORDS + ST_BUF]) bstores[k].q[m] = q;
+        bundled.push_back({q, 1});
+    }
+    for (const BStore& b : bstores) {
+        // every member must be stored by this program, member 0 included
+        for (int m = 0; m < 4; ++m) if ((P.bundles[b.bundle].members[m] >= 0) != (b.q[m] >= 0)) return false;
+    }
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
-      << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ";\n";
+      << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ", NREG = " << regs.size()
+      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ";\n";
     std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
     for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});
     for (int t = 0; t < ph.n_tasks; ++t) {
@@ -196,6 +240,36 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
             }
     emit_switch("nedges", "task", ne); emit_switch("esrc_", "key", es); emit_switch("F", "s", fs);
     emit_switch("xoff", "s", xo); emit_switch("woff_", "key", wo); emit_switch("K", "s", ks);
+    {
+        std::vector<std::pair<int, int>> rb, rf, rk, fr, ro, sr, sbb, sjj, be, bB, bd, bm, bq;
+        for (int r = 0; r < (int)regs.size(); ++r) {
+            rb.push_back({r, regs[r].buf}); rf.push_back({r, regs[r].foff}); rk.push_back({r, regs[r].rk});
+            fr.push_back({r, regs[r].fr}); ro.push_back({r, regs[r].off});
+        }
+        for (int s2 = 0; s2 < lay.n_sources; ++s2) { sr.push_back({s2, sreg[s2]}); sbb.push_back({s2, sb[s2]}); sjj.push_back({s2, sj[s2]}); }
+        for (int k = 0; k < (int)bstores.size(); ++k) {
+            const BundlePlan& bp = P.bundles[bstores[k].bundle];
+            be.push_back({k, bp.ebuf}); bB.push_back({k, bp.B}); bd.push_back({k, bp.dim}); bm.push_back({k, bp.members[0]});
+            for (int m = 0; m < 4; ++m) bq.push_back({k * 4 + m, bstores[k].q[m]});
+        }
+        std::vector<std::pair<int, int>> rbf, rsr;
+        for (int r = 0; r < (int)regs.size(); ++r) {
+            int B = 1;
+            for (int s2 = 0; s2 < lay.n_sources; ++s2) if (sreg[s2] == r) B = sb[s2];
+            rbf.push_back({r, B});
+            for (int m = 0; m < 4; ++m) {
+                int src = -1;
+                for (int s2 = 0; s2 < lay.n_sources; ++s2) if (sreg[s2] == r && sj[s2] == m) src = s2;
+                rsr.push_back({r * 4 + m, src});
+            }
+        }
+        emit_switch("rbuf", "r", rb); emit_switch("rfoff", "r", rf); emit_switch("RK", "r", rk); emit_switch("RB", "r", rbf);
+        emit_switch("rsrc_", "key", rsr);
+        o << "    static __device__ __forceinline__ constexpr int rsrc(int r, int j) { return rsrc_(r * 4 + j); }\n";
+        emit_switch("bs_ebuf", "b", be); emit_switch("bs_B", "b", bB); emit_switch("bs_dim", "b", bd); emit_switch("bs_member0", "b", bm);
+        emit_switch("bs_q_", "key", bq); emit_switch("bundled", "q", bundled);
+        o << "    static __device__ __forceinline__ constexpr int bs_q(int b, int j) { return bs_q_(b * 4 + j); }\n";
+    }
     o << "    static __device__ __forceinline__ constexpr int esrc(int task, int e) { return esrc_(task * " << STEP_MAX_EDGES << " + e); }\n";
     o << "    static __device__ __forceinline__ constexpr int woff(int ul, int task, int e) { return woff_((ul * "
       << (ph.n_tasks > 0 ? ph.n_tasks : 1) << " + task) * " << STEP_MAX_EDGES << " + e); }\n};\n";
@@ -211,20 +285,22 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", 1>(r0, a, sh, nullptr, w, tid);\n"
          "    wave_store_setup<PH0>(r0, a);\n"
          "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
+         "    wave_bundle_setup<PH0, MV>(wv, r0, a);\n"
          "    WaveRing<PH0, MV, " << NB << "> rg; wave_ring_setup<PH0, MV, " << NB << ">(rg, a, sh, w, tid);\n"
          "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, lane);\n"
          "    float pf[2][WaveRing<PH0, MV, " << NB << ">::QNA] = {{0.0f}};\n"
          "    __syncthreads();\n"
          "    float dfv[PH0::NST > 0 ? PH0::NST : 1] = {0.0f};\n"
          "    bool dead = false;\n"
+         "    int pdelay = 0;\n"
          "    int step = 0;\n"
          "    const int nsteps = step_count(a);\n"
          "    for (; step + 1 < nsteps; step += 2) {\n"
-         "        wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
-         "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead);\n"
+         "        wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
+         "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead, pdelay);\n"
          "    }\n"
-         "    if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
-         "    if (!MV::EARLY && has_units && nsteps > 0) wave_flush_stores<PH0>(r0, dfv);\n"
+         "    if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
+         "    if (!MV::EARLY && has_units && nsteps > 0) wave_flush_stores<PH0, MV>(r0, dfv);\n"
          "}\n}  // namespace " << ns << "\n";
     return true;
 }
@@ -344,8 +420,17 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     }
     std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
                                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    std::string inc_opt, dec_opt;
+    if (const char* env = std::getenv("RNNG_WAVE_POLL_INC")) { inc_opt = "-DWAVE_POLL_INC=" + std::to_string(std::atoi(env)); opts.push_back(inc_opt.c_str()); }
+    if (const char* env = std::getenv("RNNG_WAVE_POLL_DEC_MASK")) { dec_opt = "-DWAVE_POLL_DEC_MASK=" + std::to_string(std::atoi(env)); opts.push_back(dec_opt.c_str()); }
+    std::string adapt_opt;
+    if (const char* env = std::getenv("RNNG_WAVE_ADAPTIVE")) { adapt_opt = "-DWAVE_ADAPTIVE_POLL=" + std::to_string(std::atoi(env)); opts.push_back(adapt_opt.c_str()); }
+    std::string wsleep_opt;
+    if (const char* env = std::getenv("RNNG_WAVE_SLEEP")) { wsleep_opt = "-DWAVE_RETRY_SLEEP=" + std::to_string(std::atoi(env)); opts.push_back(wsleep_opt.c_str()); }
     std::string sleep_opt;
     if (const char* env = std::getenv("RNNG_MSTEP_SLEEP")) { sleep_opt = "-DMSTEP_RETRY_SLEEP=" + std::to_string(std::atoi(env)); opts.push_back(sleep_opt.c_str()); }
+    std::string trace_at_opt;
+    if (const char* env = std::getenv("RNNG_STEP_TRACE_AT")) { trace_at_opt = "-DRNNG_STEP_TRACE_AT=" + std::to_string(std::atoi(env)); opts.push_back(trace_at_opt.c_str()); }
     std::string trace_opt;
     if (const char* env = std::getenv("RNNG_STEP_TRACE"))
         if (std::atoi(env) > 0) { trace_opt = "-DRNNG_STEP_TRACE=" + std::to_string(std::atoi(env)); opts.push_back(trace_opt.c_str()); }

@@ -500,6 +500,35 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         }
     }
 
+    // ---- exchange bundles: equally wide shared tensors of one single-phase recurrent component ----
+    {
+        auto make_bundles = [&](const std::vector<int>& shared_bufs) {
+            size_t i = 0;
+            while (i < shared_bufs.size()) {
+                size_t j = i + 1;
+                while (j < shared_bufs.size() && j - i < 4 && P.buf_dim[shared_bufs[j]] == P.buf_dim[shared_bufs[i]]) ++j;
+                if (j - i >= 2) {
+                    BundlePlan b;
+                    b.B = j - i == 2 ? 2 : 4; b.dim = P.buf_dim[shared_bufs[i]];
+                    for (size_t m = i; m < j; ++m) b.members[m - i] = shared_bufs[m];
+                    b.ebuf = (int)P.buf_dim.size();
+                    P.buf_dim.push_back(b.B * b.dim); P.buf_alloc.push_back(1);
+                    P.bundles.push_back(b);
+                }
+                i = j;
+            }
+        };
+        for (const CompPlan& cp : P.comps) {
+            if (!cp.recurrent || cp.fwd_phases.size() != 1 || cp.bwd_phases.size() != 1) continue;
+            make_bundles(cp.fwd_shared_bufs);
+            make_bundles(cp.bwd_shared_bufs);
+        }
+        P.n_bufs = (int)P.buf_dim.size();
+        P.bundle_of.assign(P.n_bufs, -1);
+        for (size_t i = 0; i < P.bundles.size(); ++i)
+            for (int m : P.bundles[i].members) if (m >= 0) P.bundle_of[m] = (int)i;
+    }
+
     // ---- weight gradients ----
     for (int m = 0; m < M; ++m)
         if (xe[m].wkind == W_FULL)

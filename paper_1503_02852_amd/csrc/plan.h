@@ -62,6 +62,17 @@ struct ChainPlan {
     std::vector<CompPlan> members;
 };
 
+// Exchange bundle: up to four equally wide tensors that one step program stores and other
+// workgroups poll (an LSTM's four gate deltas in the backward loop).  The wave-autonomous step
+// kernel writes them with ONE coherent store per lane into the interleaved tensor `ebuf`
+// ([frame][stream][unit][B]) and polls that instead of the members: every additional coherent
+// store per step costs about a quarter of a microsecond of exchange time.  Other kernels ignore
+// bundles and use the member tensors.
+struct BundlePlan {
+    int ebuf = -1, B = 0, dim = 0;
+    int members[4] = {-1, -1, -1, -1};      // buffer ids; -1: padding lane (stored as zero)
+};
+
 struct Plan {
     // original graph and its canonical schedule (what rnn_graph_schedule exports)
     std::vector<GNode> nodes; std::vector<GEdge> edges; Schedule sched;
@@ -78,6 +89,8 @@ struct Plan {
     std::vector<char> buf_alloc;            // 0 not in the workspace, 1 [T][N][dim], 2 [N][dim]
     std::vector<CompPlan> comps;
     std::vector<ChainPlan> chains;
+    std::vector<BundlePlan> bundles;
+    std::vector<int> bundle_of;             // per buffer id: index into bundles or -1
     std::vector<GradGemmPlan> grad_gemms;
     int colsum_off = -1, n_colsum = 0, colsum_max_dim = 0;
     std::vector<int32_t> words;             // all programs

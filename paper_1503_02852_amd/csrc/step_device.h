@@ -25,6 +25,8 @@ constexpr unsigned STEP_SENTINEL = 0xFFFFFFFFu;
 typedef float sfloatx4 __attribute__((ext_vector_type(4)));
 typedef float sfloatx2 __attribute__((ext_vector_type(2)));
 typedef unsigned suintx2 __attribute__((ext_vector_type(2)));
+typedef float mfloatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned muintx4 __attribute__((ext_vector_type(4)));
 // Buffer loads that poll shared vectors are device-coherent (sc1).  Unlike atomic loads they are
 // not each followed by a wait, so all loads of a polling attempt are in flight together; a
 // compiler barrier at the top of each attempt keeps them from being merged across attempts.
@@ -412,9 +414,12 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
 // control words) for tuning; compiled in only when RNNG_STEP_TRACE is defined for the run-time build
 // (its value is the traced block index plus one).
 #if defined(RNNG_STEP_TRACE)
+#if !defined(RNNG_STEP_TRACE_AT)
+#define RNNG_STEP_TRACE_AT 64
+#endif
 #define RNNG_STAMP(i)                                                                                       \
-    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= 64 && step < 72)                                           \
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[(step - 64) * 8 + (i)] = clock64()
+    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= RNNG_STEP_TRACE_AT && step < RNNG_STEP_TRACE_AT + 8)         \
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[(step - RNNG_STEP_TRACE_AT) * 8 + (i)] = clock64()
 #else
 #define RNNG_STAMP(i)
 #endif
@@ -495,8 +500,11 @@ __device__ __forceinline__ void phase_step(PhaseRegs<PH>& r, const StepArgs& a, 
 //
 // MV is a generated descriptor:
 //   static constexpr int NT (tasks), UW (units per wavefront), NSRC, RW (weight registers),
+//   NREG (polled regions: single shared vectors or exchange bundles), XFR, NBS (bundle stores),
 //   XF (source registers per stream), EARLY (placement of the non-shared stores);  constexpr nedges(task), esrc(task, e), F(src), K(src),
-//   xoff(src), woff(ul, task, e).
+//   xoff(src), woff(ul, task, e); per region rbuf, rfoff, RK (floats per stream), RB (interleave
+//   factor), rsrc(r, j) (source that reads member j, -1: none); per bundle store bs_ebuf, bs_B,
+//   bs_dim, bs_member0, bs_q(bs, j) (store index of member j or -1); bundled(q).
 // =============================================================================================
 __device__ __forceinline__ float wave_sum_dpp(float v) {
 #define RNNG_DPP(ctrl, rmask) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rmask, 0xf, false))
@@ -516,12 +524,16 @@ constexpr int WAVE_FMAX = 16;   // elements of one contraction per lane (K <= 10
 template <class MV>
 struct WaveRegs {
     float wr[MV::RW > 0 ? MV::RW : 1];
-    const float* xsrc[MV::NSRC > 0 ? MV::NSRC : 1];    // frame 0 of each shared source vector (uniform)
-    long long xstride[MV::NSRC > 0 ? MV::NSRC : 1];    // floats per frame
-    int xfoff[MV::NSRC > 0 ? MV::NSRC : 1], xk[MV::NSRC > 0 ? MV::NSRC : 1];
+    // polled regions (a shared vector, or an exchange bundle of several): frame 0, floats per frame, frame offset
+    const float* xsrc[MV::NREG > 0 ? MV::NREG : 1];
+    long long xstride[MV::NREG > 0 ? MV::NREG : 1];
+    int xfoff[MV::NREG > 0 ? MV::NREG : 1];
+    // bundle stores: frame 0 of the interleaved tensor, floats per frame, this lane's byte offset in a frame
+    float* bbase[MV::NBS > 0 ? MV::NBS : 1];
+    long long bstride[MV::NBS > 0 ? MV::NBS : 1];
+    int bvoff[MV::NBS > 0 ? MV::NBS : 1];
 };
 
-// Layout (thread 0), item table for the wave-autonomous mapping.
 // Part index of this workgroup in a single-component launch, or -1 if it has no part.
 __device__ __forceinline__ int step_part_index(const StepArgs& a) {
     int w = blockIdx.x;
@@ -546,11 +558,9 @@ __device__ __forceinline__ void wave_setup(WaveRegs<MV>& wv, const StepArgs& a, 
     const StepPhase& ph = sh.lay.ph[0];
     const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-    for (int s = 0; s < MV::NSRC; ++s) {
-        const StepSource& sc = sh.lay.src[s];
-        const int K = suni(sc.k_len);
-        wv.xk[s] = K; wv.xfoff[s] = suni(sc.frame_off); wv.xstride[s] = (long long)a.N * K;
-        wv.xsrc[s] = ((cbufs_t)a.buf_ptr)[suni(sc.buf)];
+    for (int r = 0; r < MV::NREG; ++r) {
+        wv.xfoff[r] = MV::rfoff(r); wv.xstride[r] = (long long)a.N * MV::RK(r);
+        wv.xsrc[r] = ((cbufs_t)a.buf_ptr)[MV::rbuf(r)];
     }
 #pragma unroll
     for (int ul = 0; ul < MV::UW; ++ul) {
@@ -591,6 +601,25 @@ __device__ __forceinline__ void wave_store_setup(PhaseRegs<PH>& r, const StepArg
         r.scur[q] = ok ? r.sptr[q] + (long long)step_frame(a, 0) * r.sstride[q] : nullptr;
         r.sdelta[q] = a.backward ? -r.sstride[q] : r.sstride[q];
     }
+}
+
+// Bundle stores: the lane that stores member values of a bundle (same item for all members) writes
+// them as one vector into the interleaved exchange tensor.
+template <class PH, class MV>
+__device__ __forceinline__ void wave_bundle_setup(WaveRegs<MV>& wv, const PhaseRegs<PH>& r, const StepArgs& a) {
+#pragma unroll
+    for (int bs = 0; bs < MV::NBS; ++bs) {
+        wv.bbase[bs] = ((cbufs_t)a.buf_ptr)[MV::bs_ebuf(bs)];
+        wv.bstride[bs] = (long long)a.N * MV::bs_dim(bs) * MV::bs_B(bs);
+        const int q0 = MV::bs_q(bs, 0);       // member 0 always exists
+        const float* mbase = ((cbufs_t)a.buf_ptr)[MV::bs_member0(bs)];
+        wv.bvoff[bs] = r.sptr[q0] != nullptr ? (int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4 : 0x7FFFFFF0;
+    }
+}
+
+__device__ __forceinline__ unsigned step_shared_bits(float v) {
+    const unsigned b = __float_as_uint(v);
+    return b == STEP_SENTINEL ? 0x7FC00000u : b;    // a NaN result must not look like "not yet written"
 }
 
 // Loader side of a wavefront's private ring of STATIC gather values: pair = (static gather, item).
@@ -675,36 +704,55 @@ __device__ __forceinline__ void wave_ring_fill(const WaveRing<PH, MV, NB>& rg, c
 // hand them to each other through a double-buffered LDS area; one workgroup barrier per step.
 template <class MV, int NB>
 struct GroupX {
+    // LDS: one block [stream][64 * F] per source (bundles are de-interleaved on the way in)
     static constexpr int FLOATS = NB * 64 * (MV::XF > 0 ? MV::XF : 1);     // one buffer
     static __device__ __forceinline__ constexpr int off(int s) { return NB * 64 * MV::xoff(s); }
-    static __device__ __forceinline__ constexpr int pairs_per_thread(int s) { return (NB * 64 * MV::F(s) / 2 + STEP_THREADS - 1) / STEP_THREADS; }
-    static __device__ __forceinline__ constexpr int words_per_thread(int s) { return (NB * 64 * MV::F(s) + STEP_THREADS - 1) / STEP_THREADS; }
+    static __device__ __forceinline__ constexpr int pairs_per_thread(int r) { return (NB * MV::RK(r) / 2 + STEP_THREADS - 1) / STEP_THREADS; }
+    static __device__ __forceinline__ constexpr int words_per_thread(int r) { return (NB * MV::RK(r) + STEP_THREADS - 1) / STEP_THREADS; }
 };
-constexpr int GROUP_MAX_LOADS = 8;   // per thread and source (N * K <= 2048 elements when K is odd, 4096 when even)
+#if !defined(WAVE_ADAPTIVE_POLL)
+#define WAVE_ADAPTIVE_POLL 1
+#endif
+#if !defined(WAVE_POLL_INC)
+#define WAVE_POLL_INC 2
+#endif
+#if !defined(WAVE_POLL_DEC_MASK)
+#define WAVE_POLL_DEC_MASK 63
+#endif
+#if !defined(WAVE_RETRY_SLEEP)
+#define WAVE_RETRY_SLEEP 0      // units of 64 clocks between polling attempts
+#endif
+constexpr int GROUP_MAX_LOADS = 8;   // per thread and region (N * K <= 2048 elements when K is odd, 4096 when even)
 
 template <class MV, int NB>
-__device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int t, int tid, bool& dead) {
+__device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, int& pdelay) {
     typedef GroupX<MV, NB> GX;
-    suintx2 v64[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
-    unsigned v32[MV::NSRC > 0 ? MV::NSRC : 1][GROUP_MAX_LOADS];
+    suintx2 v64[MV::NREG > 0 ? MV::NREG : 1][GROUP_MAX_LOADS];
+    unsigned v32[MV::NREG > 0 ? MV::NREG : 1][GROUP_MAX_LOADS];
     // One buffer descriptor per source; a frame outside the window gets an empty one.  Loads
     // beyond a descriptor's size return zero, so no load needs a branch around it.
-    __amdgpu_buffer_rsrc_t rs[MV::NSRC > 0 ? MV::NSRC : 1];
+    __amdgpu_buffer_rsrc_t rs[MV::NREG > 0 ? MV::NREG : 1];
 #pragma unroll
-    for (int s = 0; s < MV::NSRC; ++s) {
+    for (int s = 0; s < MV::NREG; ++s) {
         const int frame = t + wv.xfoff[s];
         const bool in_window = frame >= 0 && frame < a.T;
         const float* g = wv.xsrc[s] + (in_window ? frame : 0) * wv.xstride[s];
-        rs[s] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? a.N * MV::K(s) * 4 : 0, STEP_RSRC_FLAGS);
+        rs[s] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? a.N * MV::RK(s) * 4 : 0, STEP_RSRC_FLAGS);
     }
+    // A first attempt that comes back with a sentinel costs a whole extra round trip, so the
+    // first attempt is held back until the data is usually there: the hold-off grows when a
+    // first attempt fails and shrinks slowly while they succeed.
+#if WAVE_ADAPTIVE_POLL
+    for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
+#endif
     int spins = 0;
     for (;;) {
         // all loads of an attempt are issued back to back (device-coherent buffer loads; atomic
         // loads would each be followed by a wait), then checked
         step_compiler_barrier();
 #pragma unroll
-        for (int s = 0; s < MV::NSRC; ++s) {
-            if ((MV::K(s) & 1) == 0) {
+        for (int s = 0; s < MV::NREG; ++s) {
+            if ((MV::RK(s) & 1) == 0) {
 #pragma unroll
                 for (int j = 0; j < GROUP_MAX_LOADS; ++j)
                     if (j < GX::pairs_per_thread(s)) v64[s][j] = __builtin_amdgcn_raw_buffer_load_b64(rs[s], (tid + STEP_THREADS * j) * 8, 0, STEP_COHERENT_AUX);
@@ -716,8 +764,8 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
         }
         bool ok = true;
 #pragma unroll
-        for (int s = 0; s < MV::NSRC; ++s) {
-            if ((MV::K(s) & 1) == 0) {
+        for (int s = 0; s < MV::NREG; ++s) {
+            if ((MV::RK(s) & 1) == 0) {
 #pragma unroll
                 for (int j = 0; j < GROUP_MAX_LOADS; ++j)
                     if (j < GX::pairs_per_thread(s)) ok = ok && v64[s][j].x != STEP_SENTINEL && v64[s][j].y != STEP_SENTINEL;
@@ -729,39 +777,56 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
         }
         if (ok || dead) break;
         if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+        __builtin_amdgcn_s_sleep(WAVE_RETRY_SLEEP);
     }
+#if WAVE_ADAPTIVE_POLL
+    if (__builtin_amdgcn_ballot_w64(spins > 0) != 0) pdelay = pdelay + WAVE_POLL_INC < 48 ? pdelay + WAVE_POLL_INC : 48;
+    else if ((step & WAVE_POLL_DEC_MASK) == WAVE_POLL_DEC_MASK && pdelay > 0) --pdelay;
+#endif
 #if defined(RNNG_STEP_TRACE)
     const int trace_step = a.backward ? a.t_end - 1 - t : t - a.t_begin;
-    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= 64 && trace_step < 72) {
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (trace_step - 64)] = spins;
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (trace_step - 64)] = clock64();
+    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= RNNG_STEP_TRACE_AT && trace_step < RNNG_STEP_TRACE_AT + 8) {
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (trace_step - RNNG_STEP_TRACE_AT)] = spins;
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (trace_step - RNNG_STEP_TRACE_AT)] = clock64();
     }
 #endif
-    // out-of-window frames and lanes beyond the vector arrive as zeros
+    // out-of-window frames and lanes beyond the vector arrive as zeros; a bundle's interleaved
+    // elements [unit][B] go to the blocks of the sources that read its members
 #pragma unroll
-    for (int s = 0; s < MV::NSRC; ++s) {
-        const int K = MV::K(s), total = a.N * K;
-        float* x = xs + GX::off(s);
-        const int ROW = 64 * MV::F(s);
-        if ((K & 1) == 0) {
+    for (int r = 0; r < MV::NREG; ++r) {
+            const int RK = MV::RK(r), B = MV::RB(r), K = RK / B, total = a.N * RK;
+        if ((RK & 1) == 0) {
 #pragma unroll
             for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
                 const int p = tid + STEP_THREADS * j;
-                if (j < GX::pairs_per_thread(s) && 2 * p < total) {
-                    int n = 0, k = 2 * p;
-                    if (NB > 1) { n = k / K; k -= n * K; }
-                    const sfloatx2 o = {__uint_as_float(v64[s][j].x), __uint_as_float(v64[s][j].y)};
-                    *reinterpret_cast<sfloatx2*>(&x[n * ROW + k]) = o;
+                if (j < GX::pairs_per_thread(r) && 2 * p < total) {
+                    int n = 0, e = 2 * p;
+                    if (NB > 1) { n = e / RK; e -= n * RK; }
+                    if (B == 1) {
+                        const sfloatx2 o = {__uint_as_float(v64[r][j].x), __uint_as_float(v64[r][j].y)};
+                        *reinterpret_cast<sfloatx2*>(&xs[GX::off(MV::rsrc(r, 0)) + n * 64 * MV::F(MV::rsrc(r, 0)) + e]) = o;
+                    } else {
+                        // e = k * B + m with m even: members m and m + 1 of unit k
+                        const int k = e / B, m = e - k * B;
+#pragma unroll
+                        for (int mm = 0; mm < 4; mm += 2) {
+                            if (mm < B && m == mm) {
+                                if (MV::rsrc(r, mm) >= 0) xs[GX::off(MV::rsrc(r, mm) >= 0 ? MV::rsrc(r, mm) : 0) + n * 64 * MV::F(MV::rsrc(r, mm) >= 0 ? MV::rsrc(r, mm) : 0) + k] = __uint_as_float(v64[r][j].x);
+                                if (MV::rsrc(r, mm + 1) >= 0) xs[GX::off(MV::rsrc(r, mm + 1) >= 0 ? MV::rsrc(r, mm + 1) : 0) + n * 64 * MV::F(MV::rsrc(r, mm + 1) >= 0 ? MV::rsrc(r, mm + 1) : 0) + k] = __uint_as_float(v64[r][j].y);
+                            }
+                        }
+                    }
+                    (void)K;
                 }
             }
         } else {
 #pragma unroll
             for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
                 const int p = tid + STEP_THREADS * j;
-                if (j < GX::words_per_thread(s) && p < total) {
+                if (j < GX::words_per_thread(r) && p < total) {
                     int n = 0, k = p;
-                    if (NB > 1) { n = k / K; k -= n * K; }
-                    x[n * ROW + k] = __uint_as_float(v32[s][j]);
+                    if (NB > 1) { n = k / RK; k -= n * RK; }
+                    xs[GX::off(MV::rsrc(r, 0)) + n * 64 * MV::F(MV::rsrc(r, 0)) + k] = __uint_as_float(v32[r][j]);      // odd widths are never bundled
                 }
             }
         }
@@ -806,11 +871,11 @@ __device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&t
 // Stores of values no other workgroup waits for are issued either right behind the shared stores
 // (MV::EARLY, forward loops: measured faster, their acknowledgements overlap the exchange) or one
 // step late, after the next step's poll (backward loops: measured faster there).
-template <class PH, int NSTA>
+template <class PH, class MV, int NSTA>
 __device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA]) {
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if (!PH::stshared(q) && ((r.sok >> q) & 1)) r.scur[q][0] = dfv[q];
+        if ((!PH::stshared(q) || MV::bundled(q)) && ((r.sok >> q) & 1)) r.scur[q][0] = dfv[q];
 }
 
 // PAR is the parity of `step` (the time loop is unrolled by two so that the register pair pf is
@@ -820,7 +885,7 @@ template <class PH, class MV, int NB, int PAR, int QNA, int NSTA>
 __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const WaveRing<PH, MV, NB>& rg,
                                           float (&pf)[2][QNA], float (&dfv)[NSTA],
                                           const StepArgs& a, float* ring, float* xs_all, bool has_units, int step, int t, int tid,
-                                          bool& dead) {
+                                          bool& dead, int& pdelay) {
     typedef WaveRing<PH, MV, NB> RG;
     typedef GroupX<MV, NB> GX;
     const int lane = tid & 63;
@@ -856,10 +921,10 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     float xr[NB][MV::XF > 0 ? MV::XF : 1];
     if (MV::NSRC > 0) {
         float* xs = xs_all + PAR * GX::FLOATS;
-        group_poll<MV, NB>(xs, wv, a, t, tid, dead);
+        group_poll<MV, NB>(xs, wv, a, step, t, tid, dead, pdelay);
         step_lds_barrier();
 #if defined(RNNG_STEP_TRACE)
-        if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= 64 && step < 72) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - 64)] = clock64();
+        if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= RNNG_STEP_TRACE_AT && step < RNNG_STEP_TRACE_AT + 8) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - RNNG_STEP_TRACE_AT)] = clock64();
 #endif
         if (!has_units) return;
 #pragma unroll
@@ -875,7 +940,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(2);
     // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
     if (!MV::EARLY && step > 0) {
-        wave_flush_stores<PH>(r, dfv);
+        wave_flush_stores<PH, MV>(r, dfv);
 #pragma unroll
         for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
     }
@@ -926,12 +991,28 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(4);
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q) {
-        if (PH::stshared(q)) { if ((r.sok >> q) & 1) store_shared(r.scur[q], s[PH::stslot(q)]); }
+        if (PH::stshared(q) && !MV::bundled(q)) { if ((r.sok >> q) & 1) store_shared(r.scur[q], s[PH::stslot(q)]); }
         else dfv[q] = s[PH::stslot(q)];
+    }
+    // bundles: one coherent vector store per lane (lanes without an item store outside the descriptor)
+#pragma unroll
+    for (int bs = 0; bs < MV::NBS; ++bs) {
+        float* frame = wv.bbase[bs] + (long long)t * wv.bstride[bs];
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(frame, 0, a.N * MV::bs_dim(bs) * MV::bs_B(bs) * 4, STEP_RSRC_FLAGS);
+        unsigned vb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vb[j] = (j < MV::bs_B(bs) && MV::bs_q(bs, j) >= 0) ? step_shared_bits(s[PH::stslot(MV::bs_q(bs, j) >= 0 ? MV::bs_q(bs, j) : 0)]) : 0u;
+        if (MV::bs_B(bs) == 4) {
+            const muintx4 v4 = {vb[0], vb[1], vb[2], vb[3]};
+            __builtin_amdgcn_raw_buffer_store_b128(v4, rs, wv.bvoff[bs], 0, STEP_COHERENT_AUX);
+        } else {
+            const suintx2 v2 = {vb[0], vb[1]};
+            __builtin_amdgcn_raw_buffer_store_b64(v2, rs, wv.bvoff[bs], 0, STEP_COHERENT_AUX);
+        }
     }
     if (MV::EARLY) {
         // the other stores right behind the shared ones: their acknowledgements overlap the exchange
-        wave_flush_stores<PH>(r, dfv);
+        wave_flush_stores<PH, MV>(r, dfv);
 #pragma unroll
         for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
     }
@@ -966,8 +1047,6 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 //   constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task) (row block of the task
 //   in source s, -1: none), used(s, nt).
 // =============================================================================================
-typedef float mfloatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned muintx4 __attribute__((ext_vector_type(4)));
 
 #if !defined(MSTEP_RETRY_SLEEP)
 #define MSTEP_RETRY_SLEEP 0      // units of 64 clocks; measured: backing off only costs time
