@@ -420,6 +420,8 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     }
     std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
                                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    std::string minc_opt;
+    if (const char* env = std::getenv("RNNG_MSTEP_POLL_INC")) { minc_opt = "-DMSTEP_POLL_INC=" + std::to_string(std::atoi(env)); opts.push_back(minc_opt.c_str()); }
     std::string inc_opt, dec_opt;
     if (const char* env = std::getenv("RNNG_WAVE_POLL_INC")) { inc_opt = "-DWAVE_POLL_INC=" + std::to_string(std::atoi(env)); opts.push_back(inc_opt.c_str()); }
     if (const char* env = std::getenv("RNNG_WAVE_POLL_DEC_MASK")) { dec_opt = "-DWAVE_POLL_DEC_MASK=" + std::to_string(std::atoi(env)); opts.push_back(dec_opt.c_str()); }

@@ -1048,6 +1048,9 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 //   in source s, -1: none), used(s, nt).
 // =============================================================================================
 
+#if !defined(MSTEP_POLL_INC)
+#define MSTEP_POLL_INC 2      // 0 switches the adaptive hold-off of the first loads off
+#endif
 #if !defined(MSTEP_RETRY_SLEEP)
 #define MSTEP_RETRY_SLEEP 0      // units of 64 clocks; measured: backing off only costs time
 #endif
@@ -1199,6 +1202,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     for (int mt = 0; mt < MM::MT; ++mt) arow[mt] = (mt * 16 + (lane & 15)) * XSTRIDE + wave * KW + 4 * (lane >> 4);
 
     bool dead = false;
+    int pdelay = 0;
     float sn[PH::NG > 0 ? PH::NG : 1];      // STATIC inputs of the next step, loaded one step ahead
     const int nsteps = step_count(a);
     for (int step = 0; step < nsteps; ++step) {
@@ -1274,6 +1278,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 v[i][j] = __builtin_amdgcn_raw_buffer_load_b128(rs[sidx], off, 0, STEP_COHERENT_AUX);
             }
         };
+        // hold the first loads back until the producers' stores are usually visible (a chunk that
+        // comes back with a sentinel is loaded again behind the chunks already in flight)
+        for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
+        bool retried = false;
         step_static_for<0, D>([&](auto ii) { issue(ii, StepIntC<0>{}, decltype(ii)::value * KC); });
         mfloatx4 acc[MM::MT][MM::NTU];
 #pragma unroll
@@ -1312,6 +1320,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                     if (complete() || dead) {
                         put();
                     } else {
+                        retried = true;
                         int spins = 0;
                         for (;;) {
                             if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
@@ -1357,6 +1366,8 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 });
             }
         });
+        if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
+        else if ((step & 63) == 63 && pdelay > 0) --pdelay;
         // ---- hand the accumulators to the element-wise threads ----
         if (MM::PRIV) {
             // each wavefront stores its partial tile into the chunk buffer that the last chunk did not use
