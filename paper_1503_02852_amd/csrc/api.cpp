@@ -546,6 +546,17 @@ int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream) {
             if (e != hipSuccess) return fail_hip(e, "window shift");
         }
     }
+    // interleaved exchange tensors of forward activations move along with their members
+    for (const BundlePlan& bp : P.bundles) {
+        if (bp.members[0] >= (int)P.xnodes.size() || g->layout.buf_off[bp.ebuf] < 0) continue;
+        const int64_t fr = (int64_t)g->N * P.buf_dim[bp.ebuf];
+        float* y = g->buf(bp.ebuf);
+        for (int t = 0; t + frames < T; t += frames) {
+            const int n = std::min(frames, T - frames - t);
+            hipError_t e = hipMemcpyAsync(y + t * fr, y + (t + frames) * fr, (size_t)n * fr * sizeof(float), hipMemcpyDeviceToDevice, s);
+            if (e != hipSuccess) return fail_hip(e, "window shift");
+        }
+    }
     g->fwd_upto = T - frames;
     g->fwd_done = g->bptt_done = false;
     return RNN_OK;
