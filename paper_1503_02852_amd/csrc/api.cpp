@@ -131,7 +131,8 @@ struct rnn_graph {
     int force_step_G = 0;
     bool use_jit = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false; StepLaunchPlan lp; std::string source; };
+    struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source; };
+    int force_step_J = 0;
     std::map<long long, JitChoice> jit_choices;
     const JitChoice& jit_choice(int comp, bool backward, int N) {
         const long long key = ((long long)comp * 2 + (backward ? 1 : 0)) * 4096 + N;
@@ -152,13 +153,25 @@ struct rnn_graph {
         }
         // 2. matrix-core variant for many streams: weights in LDS, MFMA, the smallest workgroup count that fits
         if (c.source.empty() && N > 8) {
-            const int mfma_G[5] = {32, 64, 128, 256, 16};
-            for (int i = 0; i < 5 && c.source.empty(); ++i) {
-                const int G = force_step_G > 0 ? force_step_G : mfma_G[i];
-                size_t lds = 0;
-                c.source = jit_mstep_source(plan, cp, backward, N, G, &lds);
-                if (!c.source.empty()) { c.lp.ok = true; c.lp.G = G; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = G <= 32 ? 8 : 1; }
-                if (force_step_G > 0) break;
+            // stream groups: as many as possible (every group halves the bytes a workgroup polls per
+            // step); unit chunks: as many as the 256 CUs allow while a workgroup still fills a
+            // 16-row tile, else the smallest count whose weight rows fit LDS
+            for (int J : {4, 2, 1}) {
+                if (force_step_J > 0 && J != force_step_J) continue;
+                JitChoice best; int best_rows = -1;
+                for (int G : {256, 128, 64, 32, 16}) {
+                    if (force_step_G > 0 && G != force_step_G) continue;
+                    size_t lds = 0; int rows = 0;
+                    std::string src = jit_mstep_source(plan, cp, backward, N, G, J, &lds, &rows);
+                    if (src.empty()) continue;
+                    if (best_rows < 0 || (best_rows < 16 && rows > best_rows)) {      // first hit = most workgroups; move to fewer only to fill a tile
+                        best.source = src; best.lp.ok = true; best.lp.G = G; best.lp.NB = 1; best.lp.lds_bytes = lds; best.J = J;
+                        best.lp.xcd_stride = G * J <= 32 ? 8 : 1;
+                        best_rows = rows;
+                    }
+                    if (best_rows >= 16) break;
+                }
+                if (!best.source.empty()) { c = best; break; }
             }
         }
         // 3. LDS-resident variant
@@ -299,7 +312,10 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
             if (hipFunction_t fn = jit_step_function(jc->source)) {
                 StepArgs a;
                 fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
-                e = jit_launch(fn, a, jc->lp, s);
+                a.J = jc->J;
+                StepLaunchPlan lp_all = jc->lp;
+                lp_all.G = jc->lp.G * jc->J;       // launch size; a.G stays the number of unit chunks
+                e = jit_launch(fn, a, lp_all, s);
                 if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(jc->source); }
             }
         }
@@ -378,6 +394,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     std::string err;
     if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
+    if (const char* env = std::getenv("RNNG_STEP_STREAM_GROUPS")) g->force_step_J = std::atoi(env);
     if (const char* env = std::getenv("RNNG_CHAIN")) g->use_chains = std::atoi(env) != 0;
     if (const char* env = std::getenv("RNNG_SCHEDULE")) g->framewise = std::string(env) == "framewise";
     if (const char* env = std::getenv("RNNG_LAYOUT_SKEW")) g_layout_skew = std::atoll(env) / 256 * 256;

@@ -343,9 +343,11 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
 
 // Matrix-core variant for N >= 9 streams (single-phase components).  Empty if not eligible;
 // otherwise *lds_bytes receives the dynamic LDS size.
-std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes) {
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J, size_t* lds_bytes, int* rows) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
-    if (phases.size() != 1 || N < 1) return "";
+    if (phases.size() != 1 || N_all < 1 || J < 1 || G * J > 256) return "";
+    if (J > 1 && N_all % (16 * J) != 0) return "";      // stream groups of whole 16-stream tiles
+    const int N = (N_all + J - 1) / J;                   // streams per workgroup
     StepLayout lay;
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
     if (!lay.ok) return "";
@@ -367,7 +369,7 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
         for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
         o << "            default: return " << dflt << ";\n        }\n    }\n";
     };
-    o << "struct MM {\n    static constexpr int MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
+    o << "struct MM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
       << ", KC = " << ml.kc << ", L = " << L << ", D = " << D << ", QSHIFT = " << qshift << ", CMAX = " << ml.cmax
       << ", XDB = " << ml.xdb << ", PRIV = " << ml.priv << ", ACCS = " << ml.accstride << ";\n";
     std::vector<std::pair<int, int>> ks, blk, used, ngr;
@@ -395,6 +397,7 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
          "    mstep_kernel_body<PH0, MM>(a, ms, lds);\n"
          "}\n";
     *lds_bytes = (size_t)ml.total_floats * 4;
+    if (rows) *rows = ph.n_tasks * ph.cmax;
     return o.str();
 }
 

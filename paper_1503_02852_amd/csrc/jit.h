@@ -19,7 +19,9 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
 // empty if a member is not eligible for the wave-autonomous variant.
 std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G);
 // Matrix-core variant for many streams; *lds_bytes receives the dynamic LDS size.
-std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes);
+// G unit chunks x J stream groups (N / J streams each).
+// *rows receives the accumulator rows per workgroup (tasks x units per chunk).
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int J, size_t* lds_bytes, int* rows = nullptr);
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
 // compile fails (the log, if any, goes to *log).  Needs no GPU.
 bool jit_compile(const std::string& source, std::string* log);

@@ -123,7 +123,7 @@ bool plan_step_launch(const int32_t* words, int desc_off, int N, int force_G, St
 
 void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
                     unsigned* ctrl, int T, int N, bool backward, int spin_limit, int t_begin, int t_end) {
-    a.t_begin = t_begin; a.t_end = t_end;
+    a.t_begin = t_begin; a.t_end = t_end; a.J = 1;
     a.buf_ptr = pv.buf_ptr; a.words = pv.words; a.weights = weights; a.ctrl = ctrl; a.desc_off = desc_off;
     a.T = T; a.N = N; a.backward = backward ? 1 : 0; a.G = lp.G; a.xcd_stride = lp.xcd_stride; a.spin_limit = spin_limit;
     a.n_groups = 0;

@@ -1039,7 +1039,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 // set for all sources, and runs the element-wise program with one thread per (stream, unit).
 //
 // MM is a generated descriptor:
-//   static constexpr int MT (16-stream tiles), NSRC, NTU (16-row tiles), KC, L (128-bit loads per
+//   static constexpr int NJ (streams per workgroup), MT (16-stream tiles), NSRC, NTU (16-row tiles), KC, L (128-bit loads per
 //   thread and chunk = MT * 16 * KC / 1024), D (chunks in flight, 2 or 4), QSHIFT (log2(KC / 4)), CMAX,
 //   XDB (1: two chunk buffers in LDS, 0: one), PRIV (per-wavefront accumulator tiles: 1 in the
 //   idle chunk buffer, 2 in a region of their own; 0: one tile, LDS atomics),
@@ -1130,18 +1130,22 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         if (w % a.xcd_stride) return;
         w /= a.xcd_stride;
     }
-    if (w >= a.G) return;
+    if (w >= a.G * a.J) return;
+    const int wj = w / a.G;      // stream group
+    w -= wj * a.G;               // unit chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int N = a.N, T = a.T;
+    const int T = a.T;
+    const int n0 = wj * MM::NJ;                                            // first stream of this workgroup
+    const int N = a.N - n0 < MM::NJ ? a.N - n0 : MM::NJ;                   // its streams
     StepShared& sh = ms.sh;
-    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, N, sh.lay); compute_mstep_layout(sh.lay, N, (int)(STEP_LDS_LIMIT / 4), ms.ml); }
+    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, MM::NJ, sh.lay); compute_mstep_layout(sh.lay, MM::NJ, (int)(STEP_LDS_LIMIT / 4), ms.ml); }
     __syncthreads();
     const StepPhase& ph = sh.lay.ph[0];
     const MLayout& ml = ms.ml;
     {
         const int ic = ph.item_chunk;
         const int il = tid % ic, n = tid / ic;
-        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N ? n : 0xFFFF) << 16);
+        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N ? n0 + n : 0xFFFF) << 16);      // global stream index
     }
     for (int i = tid; i < ml.total_floats; i += STEP_THREADS) lds[i] = 0.0f;
     __syncthreads();
@@ -1175,6 +1179,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     constexpr int NPAD = MM::MT * 16, XSTRIDE = KC + 4, XBUF = NPAD * XSTRIDE, ACCS = MM::ACCS;
     const int xbase = suni(ml.xbase), accbase = suni(ml.accbase);
     const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    const int item_n = tid / suni(ph.item_chunk);                          // local stream of this thread's item
     // this thread's L slots of a chunk: stream n, 4-column group q (the same for every chunk)
     int slot_n[L], slot_q[L], slot_lds[L];
 #pragma unroll
@@ -1245,7 +1250,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             const StepSource& sc = sh.lay.src[sidx];
             const int frame = t + suni(sc.frame_off);
             const bool in_window = frame >= 0 && frame < T;
-            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)(in_window ? frame : 0) * N * MM::K(sidx);
+            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + ((size_t)(in_window ? frame : 0) * a.N + n0) * MM::K(sidx);
             rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * MM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
         }
         auto prefetch_statics = [&]() {
@@ -1402,10 +1407,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                     if (r.gptr[g] != nullptr) {
                         const int col = PH::gaux(g) * CMAX + item_il;
                         if (MM::PRIV) {
-                            const int tb = (MM::PRIV == 1 ? xbase : accbase) + r.n * ACCS + col;
+                            const int tb = (MM::PRIV == 1 ? xbase : accbase) + item_n * ACCS + col;
                             x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
                         } else {
-                            x = lds[accbase + r.n * ACCS + col];
+                            x = lds[accbase + item_n * ACCS + col];
                         }
                     }
                     s[g] = x;

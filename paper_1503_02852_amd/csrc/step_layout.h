@@ -70,6 +70,9 @@ struct StepArgs {
     // Frames [t_begin, t_end) are computed (forward: ascending, backward: descending); frames of
     // the window outside this range hold the results of earlier calls (T is the whole window).
     int t_begin, t_end;
+    // Matrix-core build: the streams are split into J groups of N / J; workgroup w owns unit chunk
+    // w % G of stream group w / G (G * J workgroups in all).  1 elsewhere.
+    int J;
 };
 
 RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }
