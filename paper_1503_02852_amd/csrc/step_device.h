@@ -1273,15 +1273,19 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         // not unrolled.  D chunks are in flight: the loads of chunk i of the next group (or of
         // the next source's first group) are issued as soon as chunk i has been put into LDS.
         muintx4 v[D][L];
-        auto issue = [&](auto ii, auto ss, int k0) {
-            constexpr int i = decltype(ii)::value, sidx = decltype(ss)::value;
+        // Loads of one chunk (columns k0 ... of a source with K columns) into a register set.
+        // Streams beyond N and columns beyond K read as zeros (offset outside the descriptor).
+        auto load_chunk = [&](muintx4 (&dst)[L], const __amdgpu_buffer_rsrc_t& rsrc, int K, int k0) {
 #pragma unroll
             for (int j = 0; j < L; ++j) {
                 const int k = k0 + 4 * slot_q[j];
-                // streams beyond N and columns beyond K read as zeros (offset outside the descriptor)
-                const int off = (slot_n[j] < N && k < MM::K(sidx)) ? (slot_n[j] * MM::K(sidx) + k) * 4 : 0x7FFFFFF0;
-                v[i][j] = __builtin_amdgcn_raw_buffer_load_b128(rs[sidx], off, 0, STEP_COHERENT_AUX);
+                const int off = (slot_n[j] < N && k < K) ? (slot_n[j] * K + k) * 4 : 0x7FFFFFF0;
+                dst[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
             }
+        };
+        auto issue = [&](auto ii, auto ss, int k0) {
+            constexpr int i = decltype(ii)::value, sidx = decltype(ss)::value;
+            load_chunk(v[i], rs[sidx], MM::K(sidx), k0);
         };
         // hold the first loads back until the producers' stores are usually visible (a chunk that
         // comes back with a sentinel is loaded again behind the chunks already in flight)
@@ -1293,6 +1297,8 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < MM::NTU; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        constexpr bool PIPE = KW == 16;
+        mfloatx4 opa[2][MM::MT], opb[2][MM::NTU];      // PIPE: operands of the current and the previous chunk
 
         step_static_for<0, MM::NSRC>([&](auto ss) {
             constexpr int sidx = decltype(ss)::value;
@@ -1307,34 +1313,34 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                     // ---- complete the chunk: every element must have left the sentinel ----
                     // (the first check stands apart from the retry loop so that it waits for this
                     // chunk's loads only, not for the younger chunks' loads behind them)
-                    auto complete = [&]() {
+                    auto complete = [&](const muintx4 (&x)[L]) {
                         bool ok = true;
 #pragma unroll
                         for (int j = 0; j < L; ++j)
-                            ok = ok && v[i][j].x != STEP_SENTINEL && v[i][j].y != STEP_SENTINEL && v[i][j].z != STEP_SENTINEL && v[i][j].w != STEP_SENTINEL;
+                            ok = ok && x[j].x != STEP_SENTINEL && x[j].y != STEP_SENTINEL && x[j].z != STEP_SENTINEL && x[j].w != STEP_SENTINEL;
                         return ok;
                     };
-                    // The chunk goes into LDS on the fast path and, separately, after the retry
-                    // loop: merged, the stores would wait for every load in flight.
+                    // The retry path loads into registers of its own and stores them itself: if it
+                    // reloaded the pipelined register set, every later use of that set would have
+                    // to wait for all loads in flight.
                     const int xb = xbase + (MM::XDB ? (i & 1) * XBUF : 0);
                     if (!MM::XDB && (sidx > 0 || i > 0 || g > 0)) step_lds_barrier();      // the previous chunk's readers are done with the buffer
-                    auto put = [&]() {
+                    if (complete(v[i]) || dead) {
 #pragma unroll
                         for (int j = 0; j < L; ++j) *reinterpret_cast<muintx4*>(&lds[xb + slot_lds[j]]) = v[i][j];
-                    };
-                    if (complete() || dead) {
-                        put();
                     } else {
                         retried = true;
+                        muintx4 again[L];
                         int spins = 0;
                         for (;;) {
                             if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
-                            __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);      // back off: retries compete with the producers' stores
+                            __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
                             step_compiler_barrier();
-                            issue(ii, ss, k0);
-                            if (complete()) break;
+                            load_chunk(again, rs[sidx], MM::K(sidx), k0);
+                            if (complete(again)) break;
                         }
-                        put();
+#pragma unroll
+                        for (int j = 0; j < L; ++j) *reinterpret_cast<muintx4*>(&lds[xb + slot_lds[j]]) = again[j];
                         step_compiler_barrier();      // keeps the two copies of the stores apart
                     }
                     if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); }
@@ -1342,14 +1348,36 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                     if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
                     if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(7); }
                     // ---- loads of the chunk that takes this register set next ----
-                    if (g + 1 < NGR) {
-                        issue(ii, ss, k0 + D * KC);
-                    } else if (sidx + 1 < MM::NSRC) {
-                        issue(ii, StepIntC<(sidx + 1 < MM::NSRC ? sidx + 1 : sidx)>{}, i * KC);
+                    // (one load site: the descriptor and the columns are selected, not branched on)
+                    constexpr int snext = sidx + 1 < MM::NSRC ? sidx + 1 : sidx;
+                    const bool same = g + 1 < NGR;
+                    if (same || sidx + 1 < MM::NSRC) {
+                        const __amdgpu_buffer_rsrc_t rn = same ? rs[sidx] : rs[snext];
+                        load_chunk(v[i], rn, same ? MM::K(sidx) : MM::K(snext), same ? k0 + D * KC : i * KC);
                     } else if (i == 0) {
                         prefetch_statics();
                     }
                     // ---- matrix cores: this wavefront's KW columns of the chunk ----
+                    if constexpr (PIPE) {
+                        // one 16-column slice per chunk: read this chunk's operands now and multiply the
+                        // previous chunk's, so that the LDS latency hides behind the matrix cores
+                        const bool live = !(ragged && k0 + wave * KW >= KP);
+#pragma unroll
+                        for (int mt = 0; mt < MM::MT; ++mt)
+                            opa[i & 1][mt] = live ? *reinterpret_cast<const mfloatx4*>(&lds[xb + arow[mt]]) : mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                        for (int nt = 0; nt < MM::NTU; ++nt)      // tiles the source does not feed read the zero row
+                            opb[i & 1][nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + (live ? k0 + wave * KW : 0)]);
+                        if (!(i == 0 && sidx == 0 && g == 0)) {
+#pragma unroll
+                            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                                for (int nt = 0; nt < MM::NTU; ++nt)
+#pragma unroll
+                                    for (int q = 0; q < 4; ++q)
+                                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(opa[(i & 1) ^ 1][mt][q], opb[(i & 1) ^ 1][nt][q], acc[mt][nt], 0, 0, 0);
+                        }
+                    } else
 #pragma unroll
                     for (int kk = 0; kk < KW; kk += 16) {
                         if (ragged && k0 + wave * KW + kk >= KP) continue;
@@ -1371,6 +1399,14 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 });
             }
         });
+        if constexpr (PIPE) {      // the last chunk's operands (register set 1: D is even)
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MM::NTU; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(opa[1][mt][q], opb[1][nt][q], acc[mt][nt], 0, 0, 0);
+        }
         if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
         else if ((step & 63) == 63 && pdelay > 0) --pdelay;
         // ---- hand the accumulators to the element-wise threads ----
