@@ -7,7 +7,7 @@ resident in HBM.  Prints ONE JSON line: frames/s, the roofline record of the dom
 persistent recurrent-step kernel, timed live with HIP events on the launch stream) and the float64
 oracle timed on the host cores on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload speech_n1] [--no-cpu-baseline] [--no-framewise]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload speech_n1] [--no-cpu-baseline] [--no-framewise] [--index-input]
 
 Workloads: speech_n1 (default: 2 x 256 peephole LSTM, T = 1024, N = 1), charlm_n1, charlm_n32,
 generalized_n64, tiny; the paper's Section 4 shapes lm_elman_n1, lm_lstm_n1 (38,000-512-20,000, T = 2048).
@@ -17,6 +17,8 @@ import json
 import os
 import sys
 import time
+
+import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -103,6 +105,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-framewise", action="store_true",
                     help="skip the frame-by-frame schedule (the paper's baseline: no batching over frames)")
+    ap.add_argument("--index-input", action="store_true",
+                    help="give one-hot input layers as class indices (column gather / scatter-add instead of GEMMs "
+                         "over one-hot matrices); for the word-input workloads lm_*")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -117,6 +122,14 @@ def main():
 
     w = wl.make_config(args.workload)
     win = window_for(w, "cuda:0")
+    if args.index_input:
+        idx = {}
+        for k, x in w.inputs.items():
+            if not ((x == 0) | (x == 1)).all() or not (x.sum(axis=2) <= 1).all():
+                print(f"bench.py: --index-input needs one-hot input frames; input node {k} of {args.workload} is dense", file=sys.stderr)
+                sys.exit(2)
+            idx[k] = np.where(x.sum(axis=2) > 0, x.argmax(axis=2), -1)
+        win.set_onehot_inputs(idx)
     sched = win.g.schedule()
     win.g.specialise(w.N)
     for _ in range(args.warmup):
@@ -177,7 +190,7 @@ def main():
     # batched edge GEMMs against the fp32 MFMA peak (secondary record)
     gemm_flops = {"gemm_fwd": 0, "gemm_bwd": 0, "gemm_grad": 0}
     for m, e in enumerate(w.spec.edges):
-        if e["wkind"] != 0:
+        if e["wkind"] != 0 or (args.index_input and e["src"] in w.inputs):     # gathers and scatter-adds are no GEMMs
             continue
         fl = 2 * w.spec.nodes[e["src"]]["dim"] * w.spec.nodes[e["dst"]]["dim"] * frames
         gemm_flops["gemm_grad"] += fl
@@ -192,7 +205,7 @@ def main():
     out = dict(metric="forward+BPTT frames/sec (fp32)", value=value, unit="frames/s", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="f32", data="synthetic",
-               config=dict(workload=args.workload, T=w.T, N=w.N, nodes=len(w.spec.nodes), edges=len(w.spec.edges),
+               config=dict(workload=args.workload, input="class indices" if args.index_input else "dense", T=w.T, N=w.N, nodes=len(w.spec.nodes), edges=len(w.spec.edges),
                            params=w.n_params(), frames_per_window=frames),
                paper_rule_gflops=paper_rule_flops_per_frame(w.spec) * frames / (ms_per_step * 1e-3) / 1e9,
                breakdown=breakdown, batched_gemms=gemms, roofline=roofline)

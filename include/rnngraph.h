@@ -126,6 +126,16 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
                       int32_t T, int32_t N, int32_t t_begin, int32_t t_end,
                       void* d_workspace, int64_t ws_bytes, void* hip_stream);
 
+/* One-hot input layer (the 38,000-word input of Section 4): declares that input number `input`
+ * (position in increasing node id among the input nodes) is given as class indices instead of a
+ * dense tensor: d_indices is a DEVICE int32 [T][N] array, frame (t, n) of the node is the unit
+ * vector of class d_indices[t][n] (-1: the zero vector).  It must stay valid and unchanged from
+ * rnn_forward until rnn_grads has completed.  The full connections leaving the node become column
+ * gathers (forward) and scatter-adds (weight gradients) instead of GEMMs over a one-hot matrix;
+ * the node may only have full out-connections.  d_inputs[input] of rnn_forward is then ignored
+ * (may be NULL) and rnn_output of the node yields NULL.  d_indices = NULL returns to dense input. */
+int rnn_set_onehot_input(rnn_graph* g, int32_t input, const int32_t* d_indices);
+
 /* Moves the window `frames` frames ahead in time (Section 3.2): every node's activations of
  * frame t + frames become those of frame t, for t < T - frames; the last `frames` frames are then
  * undefined until rnn_forward_range(.., T - frames, T, ..) has computed them from the caller's

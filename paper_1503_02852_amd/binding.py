@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "librnngraph.so")
 
 EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_param_count",
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
-           "rnn_forward_range", "rnn_shift_window",
+           "rnn_forward_range", "rnn_shift_window", "rnn_set_onehot_input",
            "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_specialise", "rnn_debug_read_control",
            "rnn_profile_enable",
            "rnn_profile_read",
@@ -59,6 +59,8 @@ def load_library(build_if_missing=True):
     lib.rnn_forward.restype = C.c_int
     lib.rnn_forward_range.argtypes = [vp, vp, C.POINTER(vp), C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int64, vp]
     lib.rnn_forward_range.restype = C.c_int
+    lib.rnn_set_onehot_input.argtypes = [vp, C.c_int32, vp]
+    lib.rnn_set_onehot_input.restype = C.c_int
     lib.rnn_shift_window.argtypes = [vp, C.c_int32, vp]
     lib.rnn_shift_window.restype = C.c_int
     lib.rnn_output.argtypes = [vp, C.c_int32, C.POINTER(vp)]
@@ -182,6 +184,9 @@ class Graph:
     def forward_range(self, d_weights, d_inputs, T, N, t_begin, t_end, d_workspace, ws_bytes, stream=0):
         arr = (C.c_void_p * max(1, len(d_inputs)))(*d_inputs)
         _check(self.lib.rnn_forward_range(self.handle, d_weights, arr, T, N, t_begin, t_end, d_workspace, ws_bytes, stream))
+
+    def set_onehot_input(self, input_index, d_indices):
+        _check(self.lib.rnn_set_onehot_input(self.handle, input_index, d_indices))
 
     def shift_window(self, frames, stream=0):
         _check(self.lib.rnn_shift_window(self.handle, frames, stream))

@@ -110,6 +110,7 @@ struct rnn_graph {
     Layout layout;
     std::vector<char> blob;               // host copy of the plan tables (kept alive for the async upload)
     std::vector<const float*> inputs;     // per exec node id (input nodes only)
+    std::vector<const int32_t*> onehot;   // per exec node id: class indices of a one-hot input, or nullptr
     const float* weights = nullptr;
     bool fwd_done = false, bptt_done = false;
     int fwd_upto = 0;                     // frames [0, fwd_upto) of the current window hold forward results
@@ -126,6 +127,7 @@ struct rnn_graph {
         if (id < (int)inputs.size() && inputs[id]) return const_cast<float*>(inputs[id]);
         return nullptr;
     }
+    bool is_onehot(int buf) const { return buf >= 0 && buf < (int)onehot.size() && onehot[buf] != nullptr; }
     double* loss_ptr() const { return reinterpret_cast<double*>(ws + layout.sync_off); }
     unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
     int force_step_G = 0;
@@ -241,7 +243,10 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
             grp.n_problems = 0; ++n_launch;
             return e;
         };
-        for (const auto& pp : probs) {
+        for (const auto& pp0 : probs) {
+            // products with a one-hot source are column gathers, done after the GEMMs (below)
+            GemmProblemPlan pp; pp.c_buf = pp0.c_buf; pp.n = pp0.n;
+            for (const GemmPairPlan& pr : pp0.pairs) if (!g->is_onehot(pr.a_buf)) pp.pairs.push_back(pr);
             if (pp.pairs.size() <= round * GEMM_MAX_PAIRS) continue;
             GemmProblem& gp = grp.p[grp.n_problems];
             gp.C = g->buf(pp.c_buf) + r0 * pp.n; gp.ldc = pp.n; gp.M = (int)rows; gp.N = pp.n; gp.n_pairs = 0;
@@ -257,6 +262,18 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
         hipError_t e = flush();
         if (e != hipSuccess) return e;
     }
+    if (!backward)
+        for (const auto& pp : probs) {
+            bool first = true;
+            for (const GemmPairPlan& pr : pp.pairs) if (!g->is_onehot(pr.a_buf)) first = false;      // the GEMMs have written C
+            for (const GemmPairPlan& pr : pp.pairs) {
+                if (!g->is_onehot(pr.a_buf)) continue;
+                hipError_t e = launch_onehot_gather(g->buf(pp.c_buf), g->weights + pr.b_w_off, g->onehot[pr.a_buf], pp.n, pr.k_len, r0, rows,
+                                                    (int64_t)pr.delay * g->N, F, !first, s);
+                if (e != hipSuccess) return e;
+                first = false; ++n_launch;
+            }
+        }
     g->prof.end(prof, n_launch, s);
     return hipSuccess;
 }
@@ -495,7 +512,7 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
     if (t_begin < 0 || t_end > T || t_begin >= t_end) return fail(RNN_ERR_INVALID_ARGUMENT, "frame range must satisfy 0 <= t_begin < t_end <= T");
     const Plan& P = g->plan;
     for (size_t i = 0; i < P.input_nodes.size(); ++i)
-        if (!d_inputs[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
+        if (!d_inputs[i] && !g->is_onehot(P.input_nodes[i])) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
     Layout L = make_layout(P, T, N);
     if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
@@ -542,6 +559,21 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
 int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs, int32_t T, int32_t N,
                 void* d_workspace, int64_t ws_bytes, void* hip_stream) {
     return rnn_forward_range(g, d_weights, d_inputs, T, N, 0, T, d_workspace, ws_bytes, hip_stream);
+}
+
+int rnn_set_onehot_input(rnn_graph* g, int32_t input, const int32_t* d_indices) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    const Plan& P = g->plan;
+    if (input < 0 || input >= (int)P.input_nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "input index out of range");
+    const int k = P.input_nodes[input];
+    if (d_indices)
+        for (const GEdge& e : P.xedges)
+            if (e.src == k && e.wkind != W_FULL)
+                return fail(RNN_ERR_INVALID_ARGUMENT, "a one-hot input may only have full connections");
+    g->onehot.resize(P.xnodes.size(), nullptr);
+    g->onehot[k] = d_indices;
+    g->fwd_done = g->bptt_done = false; g->fwd_upto = 0;
+    return RNN_OK;
 }
 
 int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream) {
@@ -684,6 +716,12 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
     for (const GradGemmPlan& gg : P.grad_gemms) {
         const int64_t Kf = F - (int64_t)gg.delay * N;
         if (Kf <= 0) continue;
+        if (g->is_onehot(gg.src_buf)) {      // scatter-add instead of a GEMM over a one-hot matrix
+            e = launch_onehot_scatter(d_grads + gg.w_off, g->buf(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F, s);
+            if (e != hipSuccess) return fail_hip(e, "one-hot weight gradient");
+            ++n_launch;
+            continue;
+        }
         GemmProblem& gp = grp.p[grp.n_problems];
         gp.C = d_grads + gg.w_off; gp.ldc = gg.n_src; gp.M = gg.n_dst; gp.N = gg.n_src; gp.n_pairs = 1;
         GemmPair& o = gp.pairs[0];

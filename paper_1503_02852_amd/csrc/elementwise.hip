@@ -193,4 +193,49 @@ hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream) {
     return hipGetLastError();
 }
 
+
+namespace {
+// One-hot source (Section 4's word-input layer): C[f][j] (+)= W[j][idx[f - shift]] for rows f of
+// frames [row0, row0 + rows); an index of -1 (or a frame before the window) contributes nothing.
+__global__ __launch_bounds__(256) void onehot_gather_kernel(float* __restrict__ C, const float* __restrict__ W, const int* __restrict__ idx,
+                                                            int n_dst, int n_src, long long row0, long long rows, long long shift_rows,
+                                                            long long total_rows, int accumulate) {
+    for (long long r = blockIdx.x; r < rows; r += gridDim.x) {
+        const long long f = row0 + r, fs = f - shift_rows;
+        const int c = (fs >= 0 && fs < total_rows) ? idx[fs] : -1;
+        for (int j = threadIdx.x; j < n_dst; j += 256) {
+            const float v = (c >= 0 && c < n_src) ? W[(size_t)j * n_src + c] : 0.0f;
+            float* dst = C + f * n_dst + j;
+            *dst = accumulate ? *dst + v : v;
+        }
+    }
+}
+// G[j][idx[f - shift]] += ds[f][j] over all rows f >= shift.
+__global__ __launch_bounds__(256) void onehot_scatter_kernel(float* __restrict__ G, const float* __restrict__ ds, const int* __restrict__ idx,
+                                                             int n_dst, int n_src, long long shift_rows, long long total_rows) {
+    for (long long f = shift_rows + blockIdx.x; f < total_rows; f += gridDim.x) {
+        const int c = idx[f - shift_rows];
+        if (c < 0 || c >= n_src) continue;
+        for (int j = threadIdx.x; j < n_dst; j += 256) unsafeAtomicAdd(&G[(size_t)j * n_src + c], ds[f * n_dst + j]);
+    }
+}
+}  // namespace
+
+hipError_t launch_onehot_gather(float* C, const float* W, const int* idx, int n_dst, int n_src, int64_t row0, int64_t rows,
+                                int64_t shift_rows, int64_t total_rows, bool accumulate, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>(rows, 8192);
+    hipLaunchKernelGGL(onehot_gather_kernel, dim3(grid), dim3(256), 0, stream, C, W, idx, n_dst, n_src, (long long)row0, (long long)rows,
+                       (long long)shift_rows, (long long)total_rows, accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_onehot_scatter(float* G, const float* ds, const int* idx, int n_dst, int n_src, int64_t shift_rows, int64_t total_rows,
+                                 hipStream_t stream) {
+    if (total_rows - shift_rows <= 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>(total_rows - shift_rows, 8192);
+    hipLaunchKernelGGL(onehot_scatter_kernel, dim3(grid), dim3(256), 0, stream, G, ds, idx, n_dst, n_src, (long long)shift_rows, (long long)total_rows);
+    return hipGetLastError();
+}
+
 }  // namespace rnng

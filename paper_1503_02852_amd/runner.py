@@ -35,6 +35,19 @@ class Window:
             assert a.shape == (self.T, self.N, int(self.g.nodes[k, 2])), a.shape
             self.inputs[k] = torch.from_numpy(a).to(self.dev)
 
+    def set_onehot_inputs(self, indices):
+        """indices[k]: int [T][N] class indices of input node k, given instead of its dense tensor."""
+        self.onehot = getattr(self, "onehot", {})
+        for k, a in indices.items():
+            a = np.ascontiguousarray(a, dtype=np.int32)
+            assert a.shape == (self.T, self.N)
+            self.onehot[k] = torch.from_numpy(a).to(self.dev)
+            self.g.set_onehot_input(self.g.input_nodes.index(k), self.onehot[k].data_ptr())
+            self.inputs.pop(k, None)
+
+    def _input_ptrs(self):
+        return [self.inputs[k].data_ptr() if k in self.inputs else 0 for k in self.g.input_nodes]
+
     def set_targets(self, targets):
         for k in self.g.output_nodes:
             a = np.ascontiguousarray(targets[k], dtype=np.int32)
@@ -45,12 +58,12 @@ class Window:
         return torch.cuda.current_stream(self.dev).cuda_stream
 
     def forward(self):
-        self.g.forward(self.weights.data_ptr(), [self.inputs[k].data_ptr() for k in self.g.input_nodes],
+        self.g.forward(self.weights.data_ptr(), self._input_ptrs(),
                        self.T, self.N, self.ws_ptr, self.ws_bytes, self._stream())
 
     def forward_range(self, t_begin, t_end):
         """Frames [t_begin, t_end) of the window; the frames before them come from earlier calls."""
-        self.g.forward_range(self.weights.data_ptr(), [self.inputs[k].data_ptr() for k in self.g.input_nodes],
+        self.g.forward_range(self.weights.data_ptr(), self._input_ptrs(),
                              self.T, self.N, t_begin, t_end, self.ws_ptr, self.ws_bytes, self._stream())
 
     def advance(self, new_inputs, new_targets):
