@@ -279,7 +279,8 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    __shared__ __attribute__((aligned(16))) float xs_all[2 * GroupX<MV, " << NB << ">::FLOATS];\n"
          "    wave_prologue<MV, " << NB << ">(a, sh);\n"
          "    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n"
-         "    const bool has_units = wave * MV::UW < sh.lay.ph[0].item_chunk;   // else: only helps polling\n"
+         "    // same in all lanes; false: the wavefront only helps polling\n"
+         "    const bool has_units = MV::NSRC == 0 ? suni((int)(wave * MV::UW < sh.lay.ph[0].item_chunk)) != 0 : wave * MV::UW < sh.lay.ph[0].item_chunk;\n"
          "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
          "    float* ring = ring_all[wave];\n"
          "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", 1>(r0, a, sh, nullptr, w, tid);\n"
@@ -293,14 +294,20 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    float dfv[PH0::NST > 0 ? PH0::NST : 1] = {0.0f};\n"
          "    bool dead = false;\n"
          "    int pdelay = 0;\n"
-         "    int step = 0;\n"
          "    const int nsteps = step_count(a);\n"
-         "    for (; step + 1 < nsteps; step += 2) {\n"
-         "        wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
-         "        wave_step<PH0, MV, " << NB << ", 1>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead, pdelay);\n"
-         "    }\n"
-         "    if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
-         "    if (!MV::EARLY && has_units && nsteps > 0) wave_flush_stores<PH0, MV>(r0, dfv);\n"
+         "    auto loop = [&](auto hu) {\n"
+         "        constexpr int HU = decltype(hu)::value;\n"
+         "        int step = 0;\n"
+         "        for (; step + 1 < nsteps; step += 2) {\n"
+         "            wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
+         "            wave_step<PH0, MV, " << NB << ", 1, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead, pdelay);\n"
+         "        }\n"
+         "        if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
+         "        if (!MV::EARLY && (HU == 2 ? has_units : HU != 0) && nsteps > 0) wave_flush_stores<PH0, MV>(r0, dfv);\n"
+         "    };\n"
+         "    if (MV::NSRC > 0) loop(StepIntC<2>{});\n"
+         "    else if (has_units) loop(StepIntC<1>{});\n"
+         "    else if (MV::NSRC > 0) loop(StepIntC<0>{});\n"
          "}\n}  // namespace " << ns << "\n";
     return true;
 }

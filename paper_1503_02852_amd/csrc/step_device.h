@@ -50,7 +50,19 @@ __device__ __forceinline__ float step_tanh(float x) {
     return copysignf((1.0f - t) * __builtin_amdgcn_rcpf(1.0f + t), x);
 }
 __device__ __forceinline__ int suni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+// A pointer that is the same in every lane, said so to the compiler (it then stays in scalar
+// registers and can form a buffer descriptor without a loop over lanes).
+template <class T>
+__device__ __forceinline__ T* suni_ptr(T* p) {
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = (unsigned)suni((int)(unsigned)v), hi = (unsigned)suni((int)(unsigned)(v >> 32));
+    return reinterpret_cast<T*>(((unsigned long long)hi << 32) | lo);
+}
 
+__device__ __forceinline__ unsigned step_shared_bits(float v) {
+    const unsigned b = __float_as_uint(v);
+    return b == STEP_SENTINEL ? 0x7FC00000u : b;    // a NaN result must not look like "not yet written"
+}
 __device__ __forceinline__ void store_shared(float* p, float v) {
     unsigned b = __float_as_uint(v);
     if (b == STEP_SENTINEL) b = 0x7FC00000u;    // a NaN result must not look like "not yet written"
@@ -298,10 +310,18 @@ struct PhaseRegs {
     int goff[PH::NG > 0 ? PH::NG : 1];            // frame offset; ACC: LDS float index; STATIC with ring: index in a ring row
     float* sptr[PH::NST > 0 ? PH::NST : 1];
     int sstride[PH::NST > 0 ? PH::NST : 1];       // floats per frame (uniform)
-    // wave-autonomous variant: store address of the current step's frame, advanced by sdelta
-    // floats per step (negative in the backward loop); bit q of sok: this lane stores buffer q
+    float* sbase[PH::NST > 0 ? PH::NST : 1];      // frame-0 address of the stored tensor (uniform)
+    // wave-autonomous variant: the current step's frame of the stored tensor (uniform, advanced by
+    // sdelta floats per step, negative in the backward loop) and this lane's byte offset inside a
+    // frame; a lane that stores nothing has an offset beyond every frame, so its store is dropped
+    // by the buffer bounds check instead of being branched around
     float* scur[PH::NST > 0 ? PH::NST : 1];
     int sdelta[PH::NST > 0 ? PH::NST : 1];
+    int svoff[PH::NST > 0 ? PH::NST : 1];
+    // the same for kernels that wait for other workgroups every step anyway (measured: there the
+    // masked per-lane form is a little faster): this lane's address in the current frame, bit q
+    // of sok: this lane stores tensor q
+    float* slane[PH::NST > 0 ? PH::NST : 1];
     unsigned sok;
     float inv[PH::NI > 0 ? PH::NI : 1];
     float carry[PH::NC > 0 ? PH::NC : 1];
@@ -383,7 +403,8 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
         const int dim = st[q * ST_WORDS + ST_DIM];
         const int chunk = (dim + G - 1) / G, i = w * chunk + il;
         const bool active = r.n >= 0 && il < chunk && i < dim;
-        r.sptr[q] = active ? ((cbufs_t)a.buf_ptr)[st[q * ST_WORDS + ST_BUF]] + (size_t)r.n * dim + i : nullptr;
+        r.sbase[q] = suni_ptr(((cbufs_t)a.buf_ptr)[st[q * ST_WORDS + ST_BUF]]);
+        r.sptr[q] = active ? r.sbase[q] + (size_t)r.n * dim + i : nullptr;
         r.sstride[q] = suni(N * dim);
     }
 #pragma unroll
@@ -598,9 +619,30 @@ __device__ __forceinline__ void wave_store_setup(PhaseRegs<PH>& r, const StepArg
     for (int q = 0; q < PH::NST; ++q) {
         const bool ok = r.sptr[q] != nullptr;
         r.sok |= ok ? (1u << q) : 0u;
-        r.scur[q] = ok ? r.sptr[q] + (long long)step_frame(a, 0) * r.sstride[q] : nullptr;
+        r.slane[q] = ok ? r.sptr[q] + (long long)step_frame(a, 0) * r.sstride[q] : nullptr;
+        r.svoff[q] = ok ? (int)(r.sptr[q] - r.sbase[q]) * 4 : 0x7FFFFFF0;
+        r.scur[q] = r.sbase[q] + (long long)step_frame(a, 0) * r.sstride[q];
         r.sdelta[q] = a.backward ? -r.sstride[q] : r.sstride[q];
     }
+}
+
+// One value per lane into the current frame of stored tensor q.  BF (kernels without exchange):
+// unmasked buffer stores, see PhaseRegs::svoff; the compiler can then count the stores in flight
+// and a step never waits for their acknowledgements.
+template <class PH, bool BF>
+__device__ __forceinline__ void wave_store(const PhaseRegs<PH>& r, int q, float v, bool shared) {
+    if (BF) {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(r.scur[q], 0, r.sstride[q] * 4, STEP_RSRC_FLAGS);
+        if (shared) __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(v), rs, r.svoff[q], 0, STEP_COHERENT_AUX);
+        else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, r.svoff[q], 0, 0);
+    } else if ((r.sok >> q) & 1) {
+        if (shared) store_shared(r.slane[q], v); else r.slane[q][0] = v;
+    }
+}
+template <class PH>
+__device__ __forceinline__ void wave_store_advance(PhaseRegs<PH>& r) {
+#pragma unroll
+    for (int q = 0; q < PH::NST; ++q) { r.scur[q] += r.sdelta[q]; r.slane[q] += r.sdelta[q]; }
 }
 
 // Bundle stores: the lane that stores member values of a bundle (same item for all members) writes
@@ -615,11 +657,6 @@ __device__ __forceinline__ void wave_bundle_setup(WaveRegs<MV>& wv, const PhaseR
         const float* mbase = ((cbufs_t)a.buf_ptr)[MV::bs_member0(bs)];
         wv.bvoff[bs] = r.sptr[q0] != nullptr ? (int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4 : 0x7FFFFFF0;
     }
-}
-
-__device__ __forceinline__ unsigned step_shared_bits(float v) {
-    const unsigned b = __float_as_uint(v);
-    return b == STEP_SENTINEL ? 0x7FC00000u : b;    // a NaN result must not look like "not yet written"
 }
 
 // Loader side of a wavefront's private ring of STATIC gather values: pair = (static gather, item).
@@ -642,7 +679,8 @@ __device__ __forceinline__ void wave_ring_setup(WaveRing<PH, MV, NB>& rg, const 
     cwords_t pw = (cwords_t)a.words + suni(sh.lay.ph[0].prog_off);
 #pragma unroll
     for (int q = 0; q < RG::QN; ++q) {
-        rg.pbase[q] = nullptr; rg.pstride[q] = 0; rg.poff[q] = 0;
+        // lanes without a pair load one valid word that nobody reads
+        rg.pbase[q] = reinterpret_cast<const float*>(a.ctrl); rg.pstride[q] = 0; rg.poff[q] = 0;
         const int pi = q * 64 + lane;
         if (pi < RG::PAIRS) {
             const int si = pi / RG::ITEMS, it = pi - si * RG::ITEMS;
@@ -669,20 +707,38 @@ __device__ __forceinline__ void wave_ring_load(float (&v)[QNA],
     typedef WaveRing<PH, MV, NB> RG;
 #pragma unroll
     for (int q = 0; q < RG::QN; ++q) {
-        v[q] = 0.0f;
-        if (rg.pbase[q] != nullptr && st < step_count(a)) {
-            const int frame = step_frame(a, st) + rg.poff[q];
-            if (frame >= 0 && frame < a.T) v[q] = rg.pbase[q][frame * rg.pstride[q]];
+        if (MV::NSRC == 0) {
+            // kernels without exchange: no branch around the load (the compiler could not count
+            // the loads and stores in flight across one); steps past the end and frames outside
+            // the window read a clamped frame, and wave_ring_store replaces what that gave by
+            // zero: the loaded value is not touched before, so nothing waits for it here
+            const int stc = st < step_count(a) ? st : step_count(a) - 1;
+            const int frame = step_frame(a, stc) + rg.poff[q];
+            const int fc = frame < 0 ? 0 : (frame >= a.T ? a.T - 1 : frame);
+            v[q] = rg.pbase[q][fc * rg.pstride[q]];
+        } else {
+            v[q] = 0.0f;
+            if (rg.pstride[q] != 0 && st < step_count(a)) {
+                const int frame = step_frame(a, st) + rg.poff[q];
+                if (frame >= 0 && frame < a.T) v[q] = rg.pbase[q][frame * rg.pstride[q]];
+            }
         }
     }
 }
 template <class PH, class MV, int NB, int QNA>
-__device__ __forceinline__ void wave_ring_store(const float (&v)[QNA],
+__device__ __forceinline__ void wave_ring_store(const float (&v)[QNA], const WaveRing<PH, MV, NB>& rg, const StepArgs& a,
                                                 float* ring, int st, int lane) {
     typedef WaveRing<PH, MV, NB> RG;
 #pragma unroll
-    for (int q = 0; q < RG::QN; ++q)
-        if (q * 64 + lane < RG::PAIRS) ring[(st & (WAVE_RING_STEPS - 1)) * RG::PAIRS + q * 64 + lane] = v[q];
+    for (int q = 0; q < RG::QN; ++q) {
+        float x = v[q];
+        if (MV::NSRC == 0) {
+            const int stc = st < step_count(a) ? st : step_count(a) - 1;
+            const int frame = step_frame(a, stc) + rg.poff[q];
+            x = (frame >= 0 && frame < a.T) ? x : 0.0f;
+        }
+        if (q * 64 + lane < RG::PAIRS) ring[(st & (WAVE_RING_STEPS - 1)) * RG::PAIRS + q * 64 + lane] = x;
+    }
     // other lanes of this wavefront read these values in later steps
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -695,7 +751,7 @@ __device__ __forceinline__ void wave_ring_fill(const WaveRing<PH, MV, NB>& rg, c
     for (int st = 0; st < WAVE_RING_STEPS; ++st) {
         float v[RG::QNA];
         wave_ring_load<PH, MV, NB, RG::QNA>(v, rg, a, st);
-        wave_ring_store<PH, MV, NB, RG::QNA>(v, ring, st, lane);
+        wave_ring_store<PH, MV, NB, RG::QNA>(v, rg, a, ring, st, lane);
     }
 }
 
@@ -875,17 +931,22 @@ template <class PH, class MV, int NSTA>
 __device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA]) {
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if ((!PH::stshared(q) || MV::bundled(q)) && ((r.sok >> q) & 1)) r.scur[q][0] = dfv[q];
+        if (!PH::stshared(q) || MV::bundled(q)) wave_store<PH, MV::NSRC == 0>(r, q, dfv[q], false);
 }
 
 // PAR is the parity of `step` (the time loop is unrolled by two so that the register pair pf is
 // indexed statically: a run-time index would make the compiler merge in-flight loads at the loop
 // end, which costs a full memory wait per step).
-template <class PH, class MV, int NB, int PAR, int QNA, int NSTA>
+// HU: 1 for a wavefront that owns units, 0 for one that only helps polling, 2: has_units_rt says
+// which (0 / 1 give the unit-owning wavefronts a loop without a branch the compiler cannot see
+// through: behind such a branch it cannot count the loads and stores in flight and waits for all
+// of them).
+template <class PH, class MV, int NB, int PAR, int HU, int QNA, int NSTA>
 __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const WaveRing<PH, MV, NB>& rg,
                                           float (&pf)[2][QNA], float (&dfv)[NSTA],
-                                          const StepArgs& a, float* ring, float* xs_all, bool has_units, int step, int t, int tid,
+                                          const StepArgs& a, float* ring, float* xs_all, bool has_units_rt, int step, int t, int tid,
                                           bool& dead, int& pdelay) {
+    const bool has_units = HU == 2 ? has_units_rt : HU != 0;
     typedef WaveRing<PH, MV, NB> RG;
     typedef GroupX<MV, NB> GX;
     const int lane = tid & 63;
@@ -893,7 +954,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(0);
     const int js = step & (WAVE_RING_STEPS - 1);
     // the row loaded two steps ago (for step - 2 + WAVE_RING_STEPS) goes into the ring now
-    if (PH::NS > 0 && has_units && step > 1) wave_ring_store<PH, MV, NB, QNA>(pf[PAR], ring, step - 2, lane);
+    if (PH::NS > 0 && has_units && step > 1) wave_ring_store<PH, MV, NB, QNA>(pf[PAR], rg, a, ring, step - 2 + WAVE_RING_STEPS, lane);
     const int ul_l = lane % MV::UW, n_l = lane / MV::UW;
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g) {
@@ -941,8 +1002,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
     if (!MV::EARLY && step > 0) {
         wave_flush_stores<PH, MV>(r, dfv);
-#pragma unroll
-        for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
+        wave_store_advance<PH>(r);
     }
     if (PH::NS > 0) wave_ring_load<PH, MV, NB, QNA>(pf[PAR], rg, a, step + WAVE_RING_STEPS);
     // rows: partial dot products, cross-lane reduction, result picked by the owning item lane
@@ -991,7 +1051,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(4);
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q) {
-        if (PH::stshared(q) && !MV::bundled(q)) { if ((r.sok >> q) & 1) store_shared(r.scur[q], s[PH::stslot(q)]); }
+        if (PH::stshared(q) && !MV::bundled(q)) wave_store<PH, MV::NSRC == 0>(r, q, s[PH::stslot(q)], true);
         else dfv[q] = s[PH::stslot(q)];
     }
     // bundles: one coherent vector store per lane (lanes without an item store outside the descriptor)
@@ -1013,8 +1073,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     if (MV::EARLY) {
         // the other stores right behind the shared ones: their acknowledgements overlap the exchange
         wave_flush_stores<PH, MV>(r, dfv);
-#pragma unroll
-        for (int q = 0; q < PH::NST; ++q) r.scur[q] += r.sdelta[q];
+        wave_store_advance<PH>(r);
     }
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
