@@ -101,6 +101,13 @@ struct Profiler {
     }
 };
 
+// Which XCD the workgroups of a launch land on, observed once per device: xcc[r] is the hardware id
+// of the XCD that ran every workgroup b with b % 8 == r of a probe launch (workgroups are dealt to
+// the XCDs in turn), ok = false if some residue class was spread over several XCDs.  The step
+// kernels that keep a group of workgroups on one residue class then exchange through that XCD's L2
+// with plain stores, and each workgroup checks the id it was given against the one it runs on.
+struct XcdMap { bool known = false, ok = false; int xcc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; };
+
 struct rnn_graph {
     Plan plan;
     Profiler prof;
@@ -110,6 +117,7 @@ struct rnn_graph {
     Layout layout;
     std::vector<char> blob;               // host copy of the plan tables (kept alive for the async upload)
     std::vector<const float*> inputs;     // per exec node id (input nodes only)
+    const XcdMap* xcd = nullptr;          // set by the first forward call on this device
     std::vector<const int32_t*> onehot;   // per exec node id: class indices of a one-hot input, or nullptr
     const float* weights = nullptr;
     bool fwd_done = false, bptt_done = false;
@@ -278,6 +286,43 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
     return hipSuccess;
 }
 
+XcdMap g_xcd_map[64];
+bool g_xcd_local = true;       // RNNG_XCD_LOCAL=0: always write exchanged tensors through
+
+// scratch: SYNC_BYTES of device memory that may be overwritten
+hipError_t ensure_xcd_map(unsigned* scratch, hipStream_t s, const XcdMap** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    static XcdMap none;
+    if (dev < 0 || dev >= 64) { *out = &none; return hipSuccess; }
+    XcdMap& m = g_xcd_map[dev];
+    if (!m.known) {
+        constexpr int NB = (int)(SYNC_BYTES / 4);
+        unsigned host[NB];
+        e = launch_xcc_probe(scratch, NB, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(host, scratch, sizeof(host), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return e;
+        m.ok = true;
+        for (int r = 0; r < 8; ++r) {
+            m.xcc[r] = (int)host[r];
+            for (int b = r; b < NB; b += 8) m.ok = m.ok && host[b] == host[r];
+        }
+        m.known = true;
+    }
+    *out = &m;
+    return hipSuccess;
+}
+
+// The wave-autonomous kernels address a stored tensor through one buffer descriptor with 32-bit
+// offsets and park idle lanes 1 GiB beyond: every tensor of the window must stay below 1 GiB.
+bool wave_tensor_sizes_ok(const rnn_graph* g) {
+    int64_t maxdim = 1;
+    for (int b = 0; b < g->plan.n_bufs; ++b) maxdim = std::max<int64_t>(maxdim, g->plan.buf_dim[b]);
+    return (int64_t)g->T * g->N * maxdim * 4 < (int64_t(1) << 30);
+}
+
 // Sentinel prefill of the tensors that workgroups poll during frames [t0, t1).  The wave-autonomous
 // kernel polls the interleaved bundle tensors instead of bundled members; the members are filled as
 // well, so that a fall-back to another kernel build finds them prepared.
@@ -318,7 +363,7 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
     StepLaunchPlan lp;
     const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
     const rnn_graph::JitChoice* jc = g->use_jit ? &g->jit_choice(comp, backward, N) : nullptr;
-    const bool have_jit = jc && !jc->source.empty() && !g->framewise;
+    const bool have_jit = jc && !jc->source.empty() && !g->framewise && (!jc->wave || wave_tensor_sizes_ok(g));
     const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
     if (have_jit || have_interp) {
         hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, have_jit && jc->wave, t0, t1, s);
@@ -330,6 +375,7 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
                 StepArgs a;
                 fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
                 a.J = jc->J;
+                if (jc->wave && jc->lp.xcd_stride == 8 && g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[0] = g->xcd->xcc[0];
                 StepLaunchPlan lp_all = jc->lp;
                 lp_all.G = jc->lp.G * jc->J;       // launch size; a.G stays the number of unit chunks
                 e = jit_launch(fn, a, lp_all, s);
@@ -366,7 +412,7 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
 hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0, int t1) {
     const ChainPlan& ch = g->plan.chains[chain];
     const rnn_graph::ChainChoice& cc = g->chain_choice(chain, backward, g->N);
-    if (cc.source.empty()) return hipErrorNotSupported;
+    if (cc.source.empty() || !wave_tensor_sizes_ok(g)) return hipErrorNotSupported;
     hipFunction_t fn = jit_step_function(cc.source);
     if (!fn) return hipErrorNotSupported;
     const PlanView pv = g->view();
@@ -384,6 +430,7 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int 
     for (int i = 0; i < a.n_groups; ++i) {
         a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
         a.grp_G[i] = cc.G[i];
+        if (g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[i] = g->xcd->xcc[i];
     }
     hipError_t e = jit_launch(fn, a, lp, s);
     if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(cc.source); return hipErrorNotSupported; }
@@ -418,6 +465,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (const char* env = std::getenv("RNNG_BUNDLE"))
         if (std::atoi(env) == 0) g->plan.bundle_of.assign(g->plan.bundle_of.size(), -1);      // tuning aid: no exchange bundles
     if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
+    if (const char* env = std::getenv("RNNG_XCD_LOCAL")) g_xcd_local = std::atoi(env) != 0;
     *out = g;
     return RNN_OK;
 }
@@ -539,6 +587,10 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
     if (!P.words.empty()) std::memcpy(&g->blob[L.words_off], P.words.data(), P.words.size() * 4);
     hipError_t e = hipMemcpyAsync(g->ws, g->blob.data(), (size_t)L.blob_bytes, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail_hip(e, "plan table upload");
+    if (!g->xcd) {
+        e = ensure_xcd_map(reinterpret_cast<unsigned*>(g->ws + L.sync_off), s, &g->xcd);
+        if (e != hipSuccess) return fail_hip(e, "XCD probe");
+    }
     e = launch_fill(reinterpret_cast<float*>(g->ws + L.sync_off), SYNC_BYTES / 4, 0.0f, s);
     if (e != hipSuccess) return fail_hip(e, "control word reset");
 
@@ -742,6 +794,7 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
         if (e != hipSuccess) return fail_hip(e, "loss read-back");
         std::memcpy(loss, back, sizeof(double));
         unsigned flag; std::memcpy(&flag, back + 16, 4);
+        if (flag == 2) return fail(RNN_ERR_DEVICE, "a recurrent step kernel's workgroup ran on another XCD than the probe launch had shown (results are invalid; RNNG_XCD_LOCAL=0 avoids the assumption)");
         if (flag) return fail(RNN_ERR_DEVICE, "a recurrent step kernel ran into its wait limit (results are invalid)");
     }
     return RNN_OK;

@@ -152,7 +152,25 @@ std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, in
 // Emits namespace <ns> { PH0, MV, body(a, w) } for one component; false if the component (with
 // G workgroups and N streams) is not eligible.
 namespace {
-bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N, int G, const std::string& ns) {
+// Tensors that the wave-autonomous kernel of this component polls (an exchange bundle's
+// interleaved tensor stands for its members).
+std::vector<int> polled_buffers(const Plan& P, const CompPlan& cp, bool backward, int N, int G) {
+    std::vector<int> out;
+    const int NB = step_nb_for(N);
+    StepLayout lay;
+    compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, NB > 0 ? NB : 1, N, lay);
+    if (!lay.ok) return out;
+    for (int s = 0; s < lay.n_sources; ++s) {
+        const int bi = P.bundle_of[lay.src[s].buf];
+        out.push_back(bi >= 0 ? P.bundles[bi].ebuf : lay.src[s].buf);
+    }
+    return out;
+}
+
+// group: index of this component in a chain launch (0 for a launch of its own); foreign: tensors
+// that the other groups of the chain poll.
+bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N, int G, const std::string& ns,
+                     int group, const std::vector<int>& foreign) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     const int NB = step_nb_for(N);
     if (phases.size() != 1 || NB == 0) return false;
@@ -221,6 +239,19 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         // every member must be stored by this program, member 0 included
         for (int m = 0; m < 4; ++m) if ((P.bundles[b.bundle].members[m] >= 0) != (b.q[m] >= 0)) return false;
     }
+    // who polls an exchanged tensor: 0 this group only, 1 other groups only, 2 both
+    auto reader_mode = [&](int buf) {
+        bool own = false, other = false;
+        for (const Region& rg : regs) own = own || rg.buf == buf;
+        for (int f : foreign) other = other || f == buf;
+        return other ? (own ? 2 : 1) : 0;
+    };
+    std::vector<std::pair<int, int>> xmode, bs_xmode;
+    for (int q = 0; q < pw0[PG_NSTORES]; ++q) {
+        if (!(st0[q * ST_WORDS + ST_FLAGS] & 1) || P.bundle_of[st0[q * ST_WORDS + ST_BUF]] >= 0) continue;
+        xmode.push_back({q, reader_mode(st0[q * ST_WORDS + ST_BUF])});
+    }
+    for (size_t b = 0; b < bstores.size(); ++b) bs_xmode.push_back({(int)b, reader_mode(P.bundles[bstores[b].bundle].ebuf)});
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
       << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ", NREG = " << regs.size()
       << ", XFR = " << XFR << ", NBS = " << bstores.size() << ";\n";
@@ -268,6 +299,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         o << "    static __device__ __forceinline__ constexpr int rsrc(int r, int j) { return rsrc_(r * 4 + j); }\n";
         emit_switch("bs_ebuf", "b", be); emit_switch("bs_B", "b", bB); emit_switch("bs_dim", "b", bd); emit_switch("bs_member0", "b", bm);
         emit_switch("bs_q_", "key", bq); emit_switch("bundled", "q", bundled);
+        emit_switch("xmode", "q", xmode); emit_switch("bs_xmode", "b", bs_xmode);
         o << "    static __device__ __forceinline__ constexpr int bs_q(int b, int j) { return bs_q_(b * 4 + j); }\n";
     }
     o << "    static __device__ __forceinline__ constexpr int esrc(int task, int e) { return esrc_(task * " << STEP_MAX_EDGES << " + e); }\n";
@@ -287,6 +319,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    wave_store_setup<PH0>(r0, a);\n"
          "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
          "    wave_bundle_setup<PH0, MV>(wv, r0, a);\n"
+         "    wave_xcd_setup<MV>(wv, a, " << group << ");\n"
          "    WaveRing<PH0, MV, " << NB << "> rg; wave_ring_setup<PH0, MV, " << NB << ">(rg, a, sh, w, tid);\n"
          "    if (PH0::NS > 0) wave_ring_fill<PH0, MV, " << NB << ">(rg, a, ring, lane);\n"
          "    float pf[2][WaveRing<PH0, MV, " << NB << ">::QNA] = {{0.0f}};\n"
@@ -303,7 +336,9 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "            wave_step<PH0, MV, " << NB << ", 1, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead, pdelay);\n"
          "        }\n"
          "        if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
-         "        if (!MV::EARLY && (HU == 2 ? has_units : HU != 0) && nsteps > 0) wave_flush_stores<PH0, MV>(r0, dfv);\n"
+         "        const bool owns = HU == 2 ? has_units : HU != 0;\n"
+         "        if (!MV::EARLY && owns && nsteps > 0) wave_flush_stores<PH0, MV>(r0, dfv, a);\n"
+         "        if (wave_has_late_stores<MV>() && owns && nsteps > 0) wave_store_through_late<PH0, MV>(r0, wv, dfv, a, step_frame(a, nsteps - 1), MV::EARLY != 0);\n"
          "    };\n"
          "    if (MV::NSRC > 0) loop(StepIntC<2>{});\n"
          "    else if (has_units) loop(StepIntC<1>{});\n"
@@ -316,7 +351,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
 std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G) {
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
-    if (!emit_wave_group(o, P, cp, backward, N, G, "grp0")) return "";
+    if (!emit_wave_group(o, P, cp, backward, N, G, "grp0", 0, std::vector<int>())) return "";
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
          "    const int w = step_part_index(a);\n"
@@ -334,8 +369,13 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     const int n = (int)ch.members.size();
     if (n < 2 || n > STEP_MAX_GROUPS || (int)G.size() != n) return "";
-    for (int g = 0; g < n; ++g)
-        if (G[g] > 32 || !emit_wave_group(o, P, ch.members[g], backward, N, G[g], "grp" + std::to_string(g))) return "";
+    for (int g = 0; g < n; ++g) {
+        std::vector<int> foreign;
+        for (int h = 0; h < n; ++h)
+            if (h != g)
+                for (int b : polled_buffers(P, ch.members[h], backward, N, G[h])) foreign.push_back(b);
+        if (G[g] > 32 || !emit_wave_group(o, P, ch.members[g], backward, N, G[g], "grp" + std::to_string(g), g, foreign)) return "";
+    }
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
          "    const int grp = blockIdx.x & 7, w = blockIdx.x >> 3;\n"

@@ -55,6 +55,8 @@ hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float
 hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
                          int T, int N, hipStream_t stream);
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream);
+// Writes the hardware XCD id of workgroup b (256 threads each) to out[b], b < n_blocks.
+hipError_t launch_xcc_probe(unsigned* out, int n_blocks, hipStream_t stream);
 // One-hot sources given as class indices [total_rows]: C[f][j] (+)= W[j][idx[f - shift_rows]] for rows
 // [row0, row0 + rows), and the matching weight gradient G[j][idx[f - shift_rows]] += ds[f][j].
 hipError_t launch_onehot_gather(float* C, const float* W, const int* idx, int n_dst, int n_src, int64_t row0, int64_t rows,

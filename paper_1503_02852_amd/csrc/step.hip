@@ -121,13 +121,24 @@ bool plan_step_launch(const int32_t* words, int desc_off, int N, int force_G, St
     return false;
 }
 
+namespace {
+__global__ __launch_bounds__(STEP_THREADS) void xcc_probe_kernel(unsigned* out) {
+    if (threadIdx.x == 0) out[blockIdx.x] = (unsigned)step_xcc_id();
+}
+}  // namespace
+
+hipError_t launch_xcc_probe(unsigned* out, int n_blocks, hipStream_t stream) {
+    hipLaunchKernelGGL(xcc_probe_kernel, dim3(n_blocks), dim3(STEP_THREADS), 0, stream, out);
+    return hipGetLastError();
+}
+
 void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,
                     unsigned* ctrl, int T, int N, bool backward, int spin_limit, int t_begin, int t_end) {
     a.t_begin = t_begin; a.t_end = t_end; a.J = 1;
     a.buf_ptr = pv.buf_ptr; a.words = pv.words; a.weights = weights; a.ctrl = ctrl; a.desc_off = desc_off;
     a.T = T; a.N = N; a.backward = backward ? 1 : 0; a.G = lp.G; a.xcd_stride = lp.xcd_stride; a.spin_limit = spin_limit;
     a.n_groups = 0;
-    for (int g = 0; g < STEP_MAX_GROUPS; ++g) { a.grp_desc_off[g] = 0; a.grp_G[g] = 0; }
+    for (int g = 0; g < STEP_MAX_GROUPS; ++g) { a.grp_desc_off[g] = 0; a.grp_G[g] = 0; a.xcc_expect[g] = -1; }
 }
 
 hipError_t launch_recurrent_steps(const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,

@@ -63,10 +63,25 @@ __device__ __forceinline__ unsigned step_shared_bits(float v) {
     const unsigned b = __float_as_uint(v);
     return b == STEP_SENTINEL ? 0x7FC00000u : b;    // a NaN result must not look like "not yet written"
 }
+// Every tensor lives in device memory.  A pointer read from the buffer table is a generic one to
+// the compiler, and a store through it would be a FLAT instruction, which also counts as an LDS
+// operation: each later wait for LDS data would then wait for the store as well.
+typedef __attribute__((address_space(1))) unsigned step_guint_t;
+typedef __attribute__((address_space(1))) float step_gfloat_t;
+__device__ __forceinline__ step_guint_t* step_global_bits(float* p) { return (step_guint_t*)reinterpret_cast<unsigned*>(p); }
+__device__ __forceinline__ void store_plain(float* p, float v) { *(step_gfloat_t*)p = v; }
 __device__ __forceinline__ void store_shared(float* p, float v) {
-    unsigned b = __float_as_uint(v);
-    if (b == STEP_SENTINEL) b = 0x7FC00000u;    // a NaN result must not look like "not yet written"
-    __hip_atomic_store(reinterpret_cast<unsigned*>(p), b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(step_global_bits(p), step_shared_bits(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Plain store of an exchanged value: stays in this XCD's L2 (enough for readers on the same XCD).
+__device__ __forceinline__ void store_shared_local(float* p, float v) {
+    __hip_atomic_store(step_global_bits(p), step_shared_bits(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+// Hardware id of the XCD this wavefront runs on.
+__device__ __forceinline__ int step_xcc_id() {
+    unsigned id;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+    return (int)(id & 0xFu);
 }
 __device__ __forceinline__ float load_coherent(const float* p) {
     return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
@@ -311,18 +326,14 @@ struct PhaseRegs {
     float* sptr[PH::NST > 0 ? PH::NST : 1];
     int sstride[PH::NST > 0 ? PH::NST : 1];       // floats per frame (uniform)
     float* sbase[PH::NST > 0 ? PH::NST : 1];      // frame-0 address of the stored tensor (uniform)
-    // wave-autonomous variant: the current step's frame of the stored tensor (uniform, advanced by
-    // sdelta floats per step, negative in the backward loop) and this lane's byte offset inside a
-    // frame; a lane that stores nothing has an offset beyond every frame, so its store is dropped
-    // by the buffer bounds check instead of being branched around
-    float* scur[PH::NST > 0 ? PH::NST : 1];
+    // wave-autonomous variant: stores go through one buffer descriptor over the whole tensor
+    // (loop-invariant, in scalar registers) with a running per-lane byte offset svrun, advanced by
+    // sdelta floats per step (negative in the backward loop).  A lane that stores nothing runs
+    // far outside the tensor: its store is dropped by the bounds check instead of being branched
+    // around, so the compiler can count the stores in flight (and the loop has no branches per
+    // store).  Needs tensors below 1 GiB, which the host checks.
+    unsigned svrun[PH::NST > 0 ? PH::NST : 1];
     int sdelta[PH::NST > 0 ? PH::NST : 1];
-    int svoff[PH::NST > 0 ? PH::NST : 1];
-    // the same for kernels that wait for other workgroups every step anyway (measured: there the
-    // masked per-lane form is a little faster): this lane's address in the current frame, bit q
-    // of sok: this lane stores tensor q
-    float* slane[PH::NST > 0 ? PH::NST : 1];
-    unsigned sok;
     float inv[PH::NI > 0 ? PH::NI : 1];
     float carry[PH::NC > 0 ? PH::NC : 1];
     // loader side of the static-gather ring: this thread's (static gather, item) pairs
@@ -551,9 +562,26 @@ struct WaveRegs {
     int xfoff[MV::NREG > 0 ? MV::NREG : 1];
     // bundle stores: frame 0 of the interleaved tensor, floats per frame, this lane's byte offset in a frame
     float* bbase[MV::NBS > 0 ? MV::NBS : 1];
-    long long bstride[MV::NBS > 0 ? MV::NBS : 1];
-    int bvoff[MV::NBS > 0 ? MV::NBS : 1];
+    int bstride[MV::NBS > 0 ? MV::NBS : 1];
+    unsigned bvoff[MV::NBS > 0 ? MV::NBS : 1];      // (WAVE_NO_STORE: this lane stores nothing, as PhaseRegs::svrun)
+    // every workgroup of this group runs on one XCD: tensors exchanged inside the group are
+    // stored plainly (same in all lanes and workgroups of the group)
+    bool local;
 };
+
+// Exchanged tensors by reader (generated MV::xmode(q) / MV::bs_xmode(b)):
+//   0: polled inside this group only -> plain stores if the group sits on one XCD (a written-
+//      through store is acknowledged much later, and this wavefront's next polling loads only
+//      complete after the acknowledgement: loads and stores retire in issue order);
+//   1: polled by other groups of a chain only (other XCDs) -> written through;
+//   2: both -> plain store at once, and written through one step late, right after the next
+//      step's poll, where its acknowledgement overlaps the step's arithmetic.
+template <class MV>
+__device__ __forceinline__ void wave_xcd_setup(WaveRegs<MV>& wv, const StepArgs& a, int group) {
+    const int expect = a.xcc_expect[group];
+    wv.local = suni(expect) >= 0;
+    if (expect >= 0 && step_xcc_id() != expect && threadIdx.x == 0) atomicExch(a.ctrl, 2u);
+}
 
 // Part index of this workgroup in a single-component launch, or -1 if it has no part.
 __device__ __forceinline__ int step_part_index(const StepArgs& a) {
@@ -612,37 +640,32 @@ __device__ __forceinline__ void wave_setup(WaveRegs<MV>& wv, const StepArgs& a, 
     }
 }
 
+constexpr unsigned WAVE_NO_STORE = 0xC0000000u;       // +- 1 GiB stays outside a tensor below 1 GiB
+
 template <class PH>
 __device__ __forceinline__ void wave_store_setup(PhaseRegs<PH>& r, const StepArgs& a) {
-    r.sok = 0;
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q) {
-        const bool ok = r.sptr[q] != nullptr;
-        r.sok |= ok ? (1u << q) : 0u;
-        r.slane[q] = ok ? r.sptr[q] + (long long)step_frame(a, 0) * r.sstride[q] : nullptr;
-        r.svoff[q] = ok ? (int)(r.sptr[q] - r.sbase[q]) * 4 : 0x7FFFFFF0;
-        r.scur[q] = r.sbase[q] + (long long)step_frame(a, 0) * r.sstride[q];
         r.sdelta[q] = a.backward ? -r.sstride[q] : r.sstride[q];
+        r.svrun[q] = r.sptr[q] != nullptr ? (unsigned)(((int)(r.sptr[q] - r.sbase[q]) + step_frame(a, 0) * r.sstride[q]) * 4) : WAVE_NO_STORE;
     }
 }
 
-// One value per lane into the current frame of stored tensor q.  BF (kernels without exchange):
-// unmasked buffer stores, see PhaseRegs::svoff; the compiler can then count the stores in flight
-// and a step never waits for their acknowledgements.
-template <class PH, bool BF>
-__device__ __forceinline__ void wave_store(const PhaseRegs<PH>& r, int q, float v, bool shared) {
-    if (BF) {
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(r.scur[q], 0, r.sstride[q] * 4, STEP_RSRC_FLAGS);
-        if (shared) __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(v), rs, r.svoff[q], 0, STEP_COHERENT_AUX);
-        else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, r.svoff[q], 0, 0);
-    } else if ((r.sok >> q) & 1) {
-        if (shared) store_shared(r.slane[q], v); else r.slane[q][0] = v;
-    }
+// One value per lane into the current frame of stored tensor q.  mode 0: not exchanged, 1:
+// exchanged, plain store, 2: exchanged, written through; back: the previous step's frame (the
+// running offsets have moved on by one step already).
+template <class PH>
+__device__ __forceinline__ void wave_store(const PhaseRegs<PH>& r, int q, float v, int mode, const StepArgs& a, bool back = false) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(r.sbase[q], 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
+    const int off = (int)(back ? r.svrun[q] - (unsigned)(r.sdelta[q] * 4) : r.svrun[q]);
+    if (mode == 2) __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(v), rs, off, 0, STEP_COHERENT_AUX);
+    else if (mode == 1) __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(v), rs, off, 0, 0);
+    else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, off, 0, 0);
 }
 template <class PH>
 __device__ __forceinline__ void wave_store_advance(PhaseRegs<PH>& r) {
 #pragma unroll
-    for (int q = 0; q < PH::NST; ++q) { r.scur[q] += r.sdelta[q]; r.slane[q] += r.sdelta[q]; }
+    for (int q = 0; q < PH::NST; ++q) r.svrun[q] += (unsigned)(r.sdelta[q] * 4);
 }
 
 // Bundle stores: the lane that stores member values of a bundle (same item for all members) writes
@@ -652,10 +675,10 @@ __device__ __forceinline__ void wave_bundle_setup(WaveRegs<MV>& wv, const PhaseR
 #pragma unroll
     for (int bs = 0; bs < MV::NBS; ++bs) {
         wv.bbase[bs] = ((cbufs_t)a.buf_ptr)[MV::bs_ebuf(bs)];
-        wv.bstride[bs] = (long long)a.N * MV::bs_dim(bs) * MV::bs_B(bs);
+        wv.bstride[bs] = a.N * MV::bs_dim(bs) * MV::bs_B(bs);
         const int q0 = MV::bs_q(bs, 0);       // member 0 always exists
         const float* mbase = ((cbufs_t)a.buf_ptr)[MV::bs_member0(bs)];
-        wv.bvoff[bs] = r.sptr[q0] != nullptr ? (int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4 : 0x7FFFFFF0;
+        wv.bvoff[bs] = r.sptr[q0] != nullptr ? (unsigned)((int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4) : WAVE_NO_STORE;
     }
 }
 
@@ -928,10 +951,53 @@ __device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&t
 // (MV::EARLY, forward loops: measured faster, their acknowledgements overlap the exchange) or one
 // step late, after the next step's poll (backward loops: measured faster there).
 template <class PH, class MV, int NSTA>
-__device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA]) {
+__device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA], const StepArgs& a) {
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if (!PH::stshared(q) || MV::bundled(q)) wave_store<PH, MV::NSRC == 0>(r, q, dfv[q], false);
+        if (!PH::stshared(q) || MV::bundled(q)) wave_store<PH>(r, q, dfv[q], 0, a);
+}
+
+// One vector per lane into frame t of bundle bs (descriptor over the whole interleaved tensor).
+template <class MV>
+__device__ __forceinline__ void wave_bundle_store(const WaveRegs<MV>& wv, int bs, const StepArgs& a, int t, const unsigned (&vb)[4], bool through) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(wv.bbase[bs], 0, a.T * wv.bstride[bs] * 4, STEP_RSRC_FLAGS);
+    const int off = (int)(wv.bvoff[bs] + (unsigned)(t * wv.bstride[bs] * 4));
+    if (MV::bs_B(bs) == 4) {
+        const muintx4 v4 = {vb[0], vb[1], vb[2], vb[3]};
+        if (through) __builtin_amdgcn_raw_buffer_store_b128(v4, rs, off, 0, STEP_COHERENT_AUX);
+        else __builtin_amdgcn_raw_buffer_store_b128(v4, rs, off, 0, 0);
+    } else {
+        const suintx2 v2 = {vb[0], vb[1]};
+        if (through) __builtin_amdgcn_raw_buffer_store_b64(v2, rs, off, 0, STEP_COHERENT_AUX);
+        else __builtin_amdgcn_raw_buffer_store_b64(v2, rs, off, 0, 0);
+    }
+}
+
+// The written-through copies of the previous step's values that other groups poll as well
+// (xmode 2); t_prev is that step's frame.  advanced: the running store addresses already point
+// at the following frame.
+template <class PH, class MV, int NSTA>
+__device__ __forceinline__ void wave_store_through_late(const PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const float (&dfv)[NSTA],
+                                                        const StepArgs& a, int t_prev, bool advanced) {
+    if (!wv.local) return;      // they were written through at once
+#pragma unroll
+    for (int q = 0; q < PH::NST; ++q)
+        if (PH::stshared(q) && !MV::bundled(q) && MV::xmode(q) == 2) wave_store<PH>(r, q, dfv[q], 2, a, advanced);
+#pragma unroll
+    for (int bs = 0; bs < MV::NBS; ++bs) {
+        if (MV::bs_xmode(bs) != 2) continue;
+        unsigned vb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vb[j] = (j < MV::bs_B(bs) && MV::bs_q(bs, j) >= 0) ? step_shared_bits(dfv[MV::bs_q(bs, j) >= 0 ? MV::bs_q(bs, j) : 0]) : 0u;
+        wave_bundle_store<MV>(wv, bs, a, t_prev, vb, true);
+    }
+}
+template <class MV>
+__device__ __forceinline__ constexpr bool wave_has_late_stores() {
+    bool any = false;
+    for (int q = 0; q < MAX_SLOTS; ++q) any = any || MV::xmode(q) == 2;
+    for (int b = 0; b < 4; ++b) any = any || (b < MV::NBS && MV::bs_xmode(b) == 2);
+    return any;
 }
 
 // PAR is the parity of `step` (the time loop is unrolled by two so that the register pair pf is
@@ -999,9 +1065,10 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
         return;
     }
     RNNG_STAMP(2);
+    if (wave_has_late_stores<MV>() && step > 0) wave_store_through_late<PH, MV>(r, wv, dfv, a, step_frame(a, step - 1), MV::EARLY != 0);
     // the previous step's deferred stores, then the ring row of step + WAVE_RING_STEPS (stored next step)
     if (!MV::EARLY && step > 0) {
-        wave_flush_stores<PH, MV>(r, dfv);
+        wave_flush_stores<PH, MV>(r, dfv, a);
         wave_store_advance<PH>(r);
     }
     if (PH::NS > 0) wave_ring_load<PH, MV, NB, QNA>(pf[PAR], rg, a, step + WAVE_RING_STEPS);
@@ -1051,28 +1118,25 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     RNNG_STAMP(4);
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q) {
-        if (PH::stshared(q) && !MV::bundled(q)) wave_store<PH, MV::NSRC == 0>(r, q, s[PH::stslot(q)], true);
-        else dfv[q] = s[PH::stslot(q)];
+        if (PH::stshared(q) && !MV::bundled(q)) {
+            const bool through = MV::xmode(q) == 1 || !wv.local;
+            wave_store<PH>(r, q, s[PH::stslot(q)], through ? 2 : 1, a);
+            if (MV::xmode(q) == 2) dfv[q] = s[PH::stslot(q)];      // written through one step late
+        } else {
+            dfv[q] = s[PH::stslot(q)];
+        }
     }
     // bundles: one coherent vector store per lane (lanes without an item store outside the descriptor)
 #pragma unroll
     for (int bs = 0; bs < MV::NBS; ++bs) {
-        float* frame = wv.bbase[bs] + (long long)t * wv.bstride[bs];
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(frame, 0, a.N * MV::bs_dim(bs) * MV::bs_B(bs) * 4, STEP_RSRC_FLAGS);
         unsigned vb[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) vb[j] = (j < MV::bs_B(bs) && MV::bs_q(bs, j) >= 0) ? step_shared_bits(s[PH::stslot(MV::bs_q(bs, j) >= 0 ? MV::bs_q(bs, j) : 0)]) : 0u;
-        if (MV::bs_B(bs) == 4) {
-            const muintx4 v4 = {vb[0], vb[1], vb[2], vb[3]};
-            __builtin_amdgcn_raw_buffer_store_b128(v4, rs, wv.bvoff[bs], 0, STEP_COHERENT_AUX);
-        } else {
-            const suintx2 v2 = {vb[0], vb[1]};
-            __builtin_amdgcn_raw_buffer_store_b64(v2, rs, wv.bvoff[bs], 0, STEP_COHERENT_AUX);
-        }
+        wave_bundle_store<MV>(wv, bs, a, t, vb, MV::bs_xmode(bs) == 1 || !wv.local);
     }
     if (MV::EARLY) {
         // the other stores right behind the shared ones: their acknowledgements overlap the exchange
-        wave_flush_stores<PH, MV>(r, dfv);
+        wave_flush_stores<PH, MV>(r, dfv, a);
         wave_store_advance<PH>(r);
     }
 #pragma unroll
@@ -1515,7 +1579,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             for (int q = 0; q < PH::NST; ++q) {
                 if (r.sptr[q] == nullptr) continue;
                 if (PH::stshared(q)) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
-                else r.sptr[q][(long long)t * r.sstride[q]] = s[PH::stslot(q)];
+                else store_plain(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
             }
 #pragma unroll
             for (int g = 0; g < PH::NG; ++g)

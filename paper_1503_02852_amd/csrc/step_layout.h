@@ -73,6 +73,12 @@ struct StepArgs {
     // Matrix-core build: the streams are split into J groups of N / J; workgroup w owns unit chunk
     // w % G of stream group w / G (G * J workgroups in all).  1 elsewhere.
     int J;
+    // Wave-autonomous builds: hardware id of the XCD on which every workgroup of group g runs
+    // (single-component launch: entry 0), as the host has observed for this launch shape, or -1.
+    // With an id, tensors exchanged inside the group are written with plain stores (the XCD's L2
+    // holds them, and the group's polling loads are served there); a workgroup that finds itself
+    // on another XCD sets ctrl[0] = 2.  With -1 every exchanged tensor is written through.
+    int xcc_expect[STEP_MAX_GROUPS];
 };
 
 RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }
