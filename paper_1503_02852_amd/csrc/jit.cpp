@@ -404,10 +404,11 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
     const StepPhase& ph = lay.ph[0];
     const int MT = (N + 15) / 16, NTU = (ph.n_tasks * ph.cmax + 15) / 16;
     if (MT * NTU > 16) return "";     // accumulator registers
-    const int npad = MT * 16, L = npad * ml.kc / 1024, D = L <= 4 ? 4 : 2;
-    int qshift = 0;
-    while ((1 << qshift) < ml.kc / 4) ++qshift;
-    if (L < 1 || L > 8 || L * 1024 != npad * ml.kc || (1 << qshift) != ml.kc / 4) return "";
+    // chunks in flight: about 16 128-bit loads per lane, no more chunks than the widest source has
+    int kmax = 0;
+    for (int s = 0; s < ml.n_src; ++s) kmax = std::max(kmax, lay.src[s].k_len);
+    int D = 1;
+    while (D * 2 * MT <= 16 && D * 64 < kmax) D *= 2;
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
@@ -417,8 +418,7 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
         o << "            default: return " << dflt << ";\n        }\n    }\n";
     };
     o << "struct MM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
-      << ", KC = " << ml.kc << ", L = " << L << ", D = " << D << ", QSHIFT = " << qshift << ", CMAX = " << ml.cmax
-      << ", XDB = " << ml.xdb << ", PRIV = " << ml.priv << ", ACCS = " << ml.accstride << ";\n";
+      << ", D = " << D << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ";\n";
     std::vector<std::pair<int, int>> ks, blk, used, ngr;
     for (int s = 0; s < ml.n_src; ++s) {
         ks.push_back({s, lay.src[s].k_len});
@@ -431,7 +431,7 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
             }
             if (any) used.push_back({s * 16 + nt, 1});
         }
-        ngr.push_back({s, ((lay.src[s].k_len + ml.kc - 1) / ml.kc + D - 1) / D});
+        ngr.push_back({s, ((lay.src[s].k_len + 63) / 64 + D - 1) / D});
     }
     emit_switch("K", "s", ks, 0); emit_switch("blk_", "key", blk, -1); emit_switch("used_", "key", used, 0);
     emit_switch("ngr", "s", ngr, 0);

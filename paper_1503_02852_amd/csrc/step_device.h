@@ -1155,18 +1155,20 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 // x_s[n][k] * W_s[row][k] over the shared source tensors x_s [N][K_s], row = task * cmax + local
 // unit.  Each workgroup owns a chunk of every layer's units and keeps its weight rows resident in
 // LDS (per source one block of cmax rows for every task the source feeds; a task the source does
-// not feed reads a shared row of zeros).  Per step it polls every source tensor in chunks of KC
-// columns (sentinel protocol, 128-bit coherent loads, D chunks in flight in registers, two
-// chunk buffers in LDS), multiplies with v_mfma_f32_16x16x4_f32 (streams are the M dimension,
-// rows the N dimension, the four wavefronts split each chunk's columns), keeps one accumulator
-// set for all sources, and runs the element-wise program with one thread per (stream, unit).
+// not feed reads a shared row of zeros).  Per step every wavefront polls its own quarter of each
+// source's columns (sentinel protocol) with 128-bit coherent loads that ARE the A operands of
+// v_mfma_f32_16x16x4_f32: lane (m, q) of a wavefront loads x[16 mt + m][c + 4 q .. c + 4 q + 3]
+// and feeds word j of it to the j-th of four multiply steps, whose B operand is word j of the
+// 128-bit LDS read W[row][c + 4 q ..] (the order in which a dot product's columns are summed is
+// free).  Nothing of x passes through LDS and the wavefronts do not wait for each other inside a
+// step's contraction: D chunks of 64 columns (16 per wavefront) are in flight in registers, and a
+// chunk that comes back with a sentinel is loaded again by the wavefront that needs it.  One
+// accumulator set serves all sources; the four partial tiles meet in LDS, where the element-wise
+// program runs with one thread per (stream, unit).
 //
 // MM is a generated descriptor:
-//   static constexpr int NJ (streams per workgroup), MT (16-stream tiles), NSRC, NTU (16-row tiles), KC, L (128-bit loads per
-//   thread and chunk = MT * 16 * KC / 1024), D (chunks in flight, 2 or 4), QSHIFT (log2(KC / 4)), CMAX,
-//   XDB (1: two chunk buffers in LDS, 0: one), PRIV (per-wavefront accumulator tiles: 1 in the
-//   idle chunk buffer, 2 in a region of their own; 0: one tile, LDS atomics),
-//   ACCS (row stride of an accumulator tile);
+//   static constexpr int NJ (streams per workgroup), MT (16-stream tiles), NSRC, NTU (16-row
+//   tiles), D (chunks in flight), CMAX, ACCS (row stride of an accumulator tile);
 //   constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task) (row block of the task
 //   in source s, -1: none), used(s, nt).
 // =============================================================================================
@@ -1184,7 +1186,7 @@ __device__ __forceinline__ void step_static_for(F&& f) {
 }
 
 struct MLayout {
-    int ok, n_src, cmax, kc, xstride, xbuf, xbase, zrow, accbase, accstride, priv, xdb, nch, total_floats;
+    int ok, n_src, cmax, zrow, accbase, accstride, total_floats;
     int wbase[STEP_MAX_SOURCES], wstride[STEP_MAX_SOURCES], rows[STEP_MAX_SOURCES];
     short blk[STEP_MAX_SOURCES][STEP_MAX_TASKS];     // row block of (source, task) or -1
 };
@@ -1197,12 +1199,9 @@ RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int lds_l
     if (ph.item_chunk * N > STEP_THREADS) return;
     m.n_src = lay.n_sources; m.cmax = ph.cmax;
     const int npad = (N + 15) / 16 * 16;
-    int kmax = 0, wsmax = 0;
-    for (int s = 0; s < lay.n_sources; ++s) {
+    for (int s = 0; s < lay.n_sources; ++s)
         if (lay.src[s].k_len & 3) return;               // rows are read with 128-bit loads
-        kmax = lay.src[s].k_len > kmax ? lay.src[s].k_len : kmax;
-    }
-    int cur = 0;
+    int cur = 0, wsmax = 0;
     for (int s = 0; s < lay.n_sources; ++s) {
         int nb = 0;
         for (int t = 0; t < STEP_MAX_TASKS; ++t) {
@@ -1212,34 +1211,15 @@ RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int lds_l
                 if (ph.task[t].e[e].src == s && m.blk[s][t] < 0) m.blk[s][t] = (short)nb++;
         }
         m.rows[s] = nb * ph.cmax;
-        m.wstride[s] = (lay.src[s].k_len + 63) / 64 * 64 + 4;
+        m.wstride[s] = (lay.src[s].k_len + 63) / 64 * 64 + 4;      // zero-padded to whole chunks; = 4 (mod 32): conflict-free 128-bit reads
         wsmax = m.wstride[s] > wsmax ? m.wstride[s] : wsmax;
         m.wbase[s] = cur; cur += m.rows[s] * m.wstride[s];
     }
     m.zrow = cur; cur += wsmax;
     const int ntu = (ph.n_tasks * ph.cmax + 15) / 16;
     m.accstride = ntu * 16 + 4;                         // = 4 (mod 16): conflict-free tile rows
-    // chunks of 4 loads per thread (then 4 chunks are in flight) unless the sources are narrow or
-    // there are many streams; two chunk buffers if they fit (then the idle one can take the
-    // per-wavefront accumulator tiles), else one
-    int kc = 64;
-    while (kc < 1024 && 2 * kc * npad <= 4096 && kc < kmax) kc *= 2;
-    if (kc * npad > 8192) return;
-    // accumulators reach the element-wise threads through one tile per wavefront (priv: 1 = in the
-    // idle chunk buffer, 2 = in a region of their own) or, if LDS is short, through one tile and
-    // LDS atomics (priv = 0)
-    const int xbuf = npad * (kc + 4), tile = npad * m.accstride;
-    m.xdb = 1;
-    if (xbuf >= 4 * tile && cur + 2 * xbuf <= lds_limit_floats) m.priv = 1;
-    else if (cur + 2 * xbuf + 4 * tile <= lds_limit_floats) m.priv = 2;
-    else if (cur + 2 * xbuf + tile <= lds_limit_floats) m.priv = 0;
-    else if (cur + xbuf + 4 * tile <= lds_limit_floats) { m.xdb = 0; m.priv = 2; }
-    else if (cur + xbuf + tile <= lds_limit_floats) { m.xdb = 0; m.priv = 0; }
-    else return;
-    m.kc = kc; m.xstride = kc + 4; m.xbuf = xbuf;
-    m.xbase = cur; cur += (m.xdb ? 2 : 1) * xbuf;
-    m.accbase = cur; cur += m.priv == 1 ? 0 : m.priv == 2 ? 4 * tile : tile;
-    m.nch = 0;
+    m.accbase = cur; cur += 4 * npad * m.accstride;     // one partial tile per wavefront
+    if (cur > lds_limit_floats) return;
     m.total_floats = cur;
     m.ok = 1;
 }
@@ -1298,19 +1278,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
     __syncthreads();
 
-    constexpr int KC = MM::KC, L = MM::L, D = MM::D, Q4 = KC / 4, KW = KC / 4;     // KW: columns per wavefront and chunk
-    constexpr int NPAD = MM::MT * 16, XSTRIDE = KC + 4, XBUF = NPAD * XSTRIDE, ACCS = MM::ACCS;
-    const int xbase = suni(ml.xbase), accbase = suni(ml.accbase);
+    constexpr int D = MM::D, NPAD = MM::MT * 16, ACCS = MM::ACCS;
+    const int accbase = suni(ml.accbase);
     const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
     const int item_n = tid / suni(ph.item_chunk);                          // local stream of this thread's item
-    // this thread's L slots of a chunk: stream n, 4-column group q (the same for every chunk)
-    int slot_n[L], slot_q[L], slot_lds[L];
-#pragma unroll
-    for (int j = 0; j < L; ++j) {
-        const int p = tid + STEP_THREADS * j;
-        slot_n[j] = p >> MM::QSHIFT; slot_q[j] = p & (Q4 - 1);
-        slot_lds[j] = slot_n[j] * XSTRIDE + 4 * slot_q[j];
-    }
     // LDS address of the weight row behind each of this lane's tile columns, per source
     int brow[MM::NSRC][MM::NTU];
 #pragma unroll
@@ -1324,10 +1295,9 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             for (int t2 = 0; t2 < STEP_MAX_TASKS; ++t2) if (task == t2) b = MM::blk(sidx, t2);
             brow[sidx][nt] = (b >= 0 ? suni(ml.wbase[sidx]) + (b * CMAX + ul) * suni(ml.wstride[sidx]) : suni(ml.zrow)) + 4 * (lane >> 4);
         }
-    // A-operand address of this lane inside a chunk buffer
-    int arow[MM::MT];
-#pragma unroll
-    for (int mt = 0; mt < MM::MT; ++mt) arow[mt] = (mt * 16 + (lane & 15)) * XSTRIDE + wave * KW + 4 * (lane >> 4);
+    // this lane's A-operand element inside a chunk: stream 16 mt + (lane & 15), columns wcol ... wcol + 3
+    const int wcol = wave * 16 + 4 * (lane >> 4);
+    const int lrow = lane & 15;
 
     bool dead = false;
     int pdelay = 0;
@@ -1342,11 +1312,11 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         for (int g = 0; g < PH::NG; ++g) {
             if (PH::gkind(g) == GA_KIND_CARRY) {
                 if (step > 0) {
-                s[g] = r.carry[PH::cidx(g)];
-            } else {      // first step of this call: the previous frame's value, if the window has one
-                const int frame = t + r.goff[g];
-                s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
-            }
+                    s[g] = r.carry[PH::cidx(g)];
+                } else {      // first step of this call: the previous frame's value, if the window has one
+                    const int frame = t + r.goff[g];
+                    s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+                }
             } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
                 s[g] = sn[g];
             } else if (PH::gkind(g) != GA_KIND_ACC) {
@@ -1361,8 +1331,6 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         }
 #pragma unroll
         for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
-        if (!MM::PRIV)   // the shared accumulator tile to zero (the flush comes after at least one barrier)
-            for (int i = tid; i < NPAD * ACCS; i += STEP_THREADS) lds[accbase + i] = 0.0f;
         RNNG_STAMP(1);
 
         // one buffer descriptor per source tensor; a frame outside the window gets an empty one
@@ -1390,152 +1358,108 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             }
         };
         // ---- chunk pipeline ----
-        // A source's columns are cut into groups of D chunks (the last group padded with empty
-        // chunks whose loads all return zero).  Chunk i of a group lives in register set i and
-        // LDS buffer i & 1, so every index is static although the loop over a source's groups is
+        // A source's columns are cut into groups of D chunks of 64 columns (the last group padded
+        // with empty chunks whose loads all return zero).  Chunk i of a group lives in register
+        // set i, so every register index is static although the loop over a source's groups is
         // not unrolled.  D chunks are in flight: the loads of chunk i of the next group (or of
-        // the next source's first group) are issued as soon as chunk i has been put into LDS.
-        muintx4 v[D][L];
-        // Loads of one chunk (columns k0 ... of a source with K columns) into a register set.
-        // Streams beyond N and columns beyond K read as zeros (offset outside the descriptor).
-        auto load_chunk = [&](muintx4 (&dst)[L], const __amdgpu_buffer_rsrc_t& rsrc, int K, int k0) {
+        // the next source's first group) are issued as soon as chunk i has been checked.
+        muintx4 v[D][MM::MT];
+        // This lane's operands of one chunk (first column k0) of a source with K columns.  Streams
+        // beyond N and columns beyond K read as zeros (offset outside the descriptor).
+        auto load_chunk = [&](muintx4 (&dst)[MM::MT], const __amdgpu_buffer_rsrc_t& rsrc, int K, int k0) {
 #pragma unroll
-            for (int j = 0; j < L; ++j) {
-                const int k = k0 + 4 * slot_q[j];
-                const int off = (slot_n[j] < N && k < K) ? (slot_n[j] * K + k) * 4 : 0x7FFFFFF0;
-                dst[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
+            for (int mt = 0; mt < MM::MT; ++mt) {
+                const int n = mt * 16 + lrow, k = k0 + wcol;
+                const int off = (n < N && k < K) ? (n * K + k) * 4 : 0x7FFFFFF0;
+                dst[mt] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
             }
         };
-        auto issue = [&](auto ii, auto ss, int k0) {
-            constexpr int i = decltype(ii)::value, sidx = decltype(ss)::value;
-            load_chunk(v[i], rs[sidx], MM::K(sidx), k0);
-        };
-        // hold the first loads back until the producers' stores are usually visible (a chunk that
-        // comes back with a sentinel is loaded again behind the chunks already in flight)
+        // hold the first loads back until the producers' stores are usually visible
         for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
-        step_static_for<0, D>([&](auto ii) { issue(ii, StepIntC<0>{}, decltype(ii)::value * KC); });
+        step_static_for<0, D>([&](auto ii) { load_chunk(v[decltype(ii)::value], rs[0], MM::K(0), decltype(ii)::value * 64); });
         mfloatx4 acc[MM::MT][MM::NTU];
 #pragma unroll
         for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < MM::NTU; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
-        constexpr bool PIPE = KW == 16;
-        mfloatx4 opa[2][MM::MT], opb[2][MM::NTU];      // PIPE: operands of the current and the previous chunk
 
         step_static_for<0, MM::NSRC>([&](auto ss) {
             constexpr int sidx = decltype(ss)::value;
             constexpr int NGR = MM::ngr(sidx);
             constexpr int KP = (MM::K(sidx) + 63) / 64 * 64;              // weight rows are zero-padded up to here
-            constexpr bool ragged = NGR * D * KC > KP;                    // some chunk reaches beyond KP
+            constexpr bool ragged = NGR * D * 64 > KP;                    // some chunk lies beyond KP
 #pragma unroll 1
             for (int g = 0; g < NGR; ++g) {
                 step_static_for<0, D>([&](auto ii) {
                     constexpr int i = decltype(ii)::value;
-                    const int k0 = (g * D + i) * KC;
-                    // ---- complete the chunk: every element must have left the sentinel ----
-                    // (the first check stands apart from the retry loop so that it waits for this
-                    // chunk's loads only, not for the younger chunks' loads behind them)
-                    auto complete = [&](const muintx4 (&x)[L]) {
-                        bool ok = true;
+                    const int k0 = (g * D + i) * 64;
+                    const bool live = !(ragged && k0 >= KP);
+                    // the weights of this chunk (tiles the source does not feed read the zero row)
+                    mfloatx4 opb[MM::NTU];
 #pragma unroll
-                        for (int j = 0; j < L; ++j)
-                            ok = ok && x[j].x != STEP_SENTINEL && x[j].y != STEP_SENTINEL && x[j].z != STEP_SENTINEL && x[j].w != STEP_SENTINEL;
-                        return ok;
+                    for (int nt = 0; nt < MM::NTU; ++nt)
+                        if (MM::used(sidx, nt)) opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + (live ? k0 + wave * 16 : 0)]);
+                    // ---- complete the chunk: every element must have left the sentinel ----
+                    auto complete = [&](const muintx4 (&x)[MM::MT]) {
+                        unsigned m = 0;
+#pragma unroll
+                        for (int mt = 0; mt < MM::MT; ++mt) {
+                            const unsigned m1 = x[mt].x > x[mt].y ? x[mt].x : x[mt].y, m2 = x[mt].z > x[mt].w ? x[mt].z : x[mt].w;
+                            const unsigned m3 = m1 > m2 ? m1 : m2;
+                            m = m > m3 ? m : m3;
+                        }
+                        return __builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) == 0;
                     };
-                    // The retry path loads into registers of its own and stores them itself: if it
-                    // reloaded the pipelined register set, every later use of that set would have
-                    // to wait for all loads in flight.
-                    const int xb = xbase + (MM::XDB ? (i & 1) * XBUF : 0);
-                    if (!MM::XDB && (sidx > 0 || i > 0 || g > 0)) step_lds_barrier();      // the previous chunk's readers are done with the buffer
+                    // The retry path loads into registers of its own: if it reloaded the pipelined
+                    // register set, every later use of that set would wait for all loads in flight.
+                    muintx4 cur[MM::MT];
                     if (complete(v[i]) || dead) {
 #pragma unroll
-                        for (int j = 0; j < L; ++j) *reinterpret_cast<muintx4*>(&lds[xb + slot_lds[j]]) = v[i][j];
+                        for (int mt = 0; mt < MM::MT; ++mt) cur[mt] = v[i][mt];
                     } else {
                         retried = true;
-                        muintx4 again[L];
                         int spins = 0;
                         for (;;) {
-                            if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+                            if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
                             __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
                             step_compiler_barrier();
-                            load_chunk(again, rs[sidx], MM::K(sidx), k0);
-                            if (complete(again)) break;
+                            load_chunk(cur, rs[sidx], MM::K(sidx), k0);
+                            if (complete(cur)) break;
                         }
-#pragma unroll
-                        for (int j = 0; j < L; ++j) *reinterpret_cast<muintx4*>(&lds[xb + slot_lds[j]]) = again[j];
-                        step_compiler_barrier();      // keeps the two copies of the stores apart
                     }
-                    if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); }
-                    step_lds_barrier();      // chunk visible (two buffers: the previous chunk's readers use the other one)
                     if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
-                    if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(7); }
+                    if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); RNNG_STAMP(7); }
                     // ---- loads of the chunk that takes this register set next ----
                     // (one load site: the descriptor and the columns are selected, not branched on)
                     constexpr int snext = sidx + 1 < MM::NSRC ? sidx + 1 : sidx;
                     const bool same = g + 1 < NGR;
                     if (same || sidx + 1 < MM::NSRC) {
                         const __amdgpu_buffer_rsrc_t rn = same ? rs[sidx] : rs[snext];
-                        load_chunk(v[i], rn, same ? MM::K(sidx) : MM::K(snext), same ? k0 + D * KC : i * KC);
+                        load_chunk(v[i], rn, same ? MM::K(sidx) : MM::K(snext), same ? k0 + D * 64 : i * 64);
                     } else if (i == 0) {
                         prefetch_statics();
                     }
-                    // ---- matrix cores: this wavefront's KW columns of the chunk ----
-                    if constexpr (PIPE) {
-                        // one 16-column slice per chunk: read this chunk's operands now and multiply the
-                        // previous chunk's, so that the LDS latency hides behind the matrix cores
-                        const bool live = !(ragged && k0 + wave * KW >= KP);
-#pragma unroll
-                        for (int mt = 0; mt < MM::MT; ++mt)
-                            opa[i & 1][mt] = live ? *reinterpret_cast<const mfloatx4*>(&lds[xb + arow[mt]]) : mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                        for (int nt = 0; nt < MM::NTU; ++nt)      // tiles the source does not feed read the zero row
-                            opb[i & 1][nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + (live ? k0 + wave * KW : 0)]);
-                        if (!(i == 0 && sidx == 0 && g == 0)) {
-#pragma unroll
-                            for (int mt = 0; mt < MM::MT; ++mt)
-#pragma unroll
-                                for (int nt = 0; nt < MM::NTU; ++nt)
-#pragma unroll
-                                    for (int q = 0; q < 4; ++q)
-                                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(opa[(i & 1) ^ 1][mt][q], opb[(i & 1) ^ 1][nt][q], acc[mt][nt], 0, 0, 0);
-                        }
-                    } else
-#pragma unroll
-                    for (int kk = 0; kk < KW; kk += 16) {
-                        if (ragged && k0 + wave * KW + kk >= KP) continue;
-                        mfloatx4 av[MM::MT], bv[MM::NTU];
-#pragma unroll
-                        for (int mt = 0; mt < MM::MT; ++mt) av[mt] = *reinterpret_cast<const mfloatx4*>(&lds[xb + arow[mt] + kk]);
-#pragma unroll
-                        for (int nt = 0; nt < MM::NTU; ++nt)
-                            if (MM::used(sidx, nt)) bv[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * KW + kk]);
+                    // ---- matrix cores: this wavefront's 16 columns of the chunk ----
+                    if (live) {
 #pragma unroll
                         for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
                             for (int nt = 0; nt < MM::NTU; ++nt)
                                 if (MM::used(sidx, nt)) {
-#pragma unroll
-                                    for (int q = 0; q < 4; ++q) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][q], bv[nt][q], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].x), opb[nt][0], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].y), opb[nt][1], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].z), opb[nt][2], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
                                 }
                     }
                 });
             }
         });
-        if constexpr (PIPE) {      // the last chunk's operands (register set 1: D is even)
-#pragma unroll
-            for (int mt = 0; mt < MM::MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < MM::NTU; ++nt)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(opa[1][mt][q], opb[1][nt][q], acc[mt][nt], 0, 0, 0);
-        }
-        if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
-        else if ((step & 63) == 63 && pdelay > 0) --pdelay;
-        // ---- hand the accumulators to the element-wise threads ----
-        if (MM::PRIV) {
-            // each wavefront stores its partial tile into the chunk buffer that the last chunk did not use
-            const int tb = (MM::PRIV == 1 ? xbase : accbase) + wave * (NPAD * ACCS);      // chunk buffer 0 is idle: the last chunk of a step uses buffer 1
+        // ---- hand the accumulators to the element-wise threads: one partial tile per wavefront ----
+        // (the previous step's readers of the tiles are behind the barrier that ends a step)
+        {
+            const int tb = accbase + wave * (NPAD * ACCS);
 #pragma unroll
             for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
@@ -1543,19 +1467,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         lds[tb + (mt * 16 + 4 * (lane >> 4) + i) * ACCS + nt * 16 + (lane & 15)] = acc[mt][nt][i];
-        } else {
-#pragma unroll
-            for (int mt = 0; mt < MM::MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < MM::NTU; ++nt)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int m = mt * 16 + 4 * (lane >> 4) + i;
-                        if (m < N) atomicAdd(&lds[accbase + m * ACCS + nt * 16 + (lane & 15)], acc[mt][nt][i]);
-                    }
         }
         RNNG_STAMP(3);
-        step_lds_barrier();
+        if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
+        else if ((step & 63) == 63 && pdelay > 0) --pdelay;
         RNNG_STAMP(4);
         // ---- element-wise program: one thread per (stream, unit) ----
         if (r.n >= 0) {
@@ -1564,13 +1479,8 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 if (PH::gkind(g) == GA_KIND_ACC) {
                     float x = 0.0f;
                     if (r.gptr[g] != nullptr) {
-                        const int col = PH::gaux(g) * CMAX + item_il;
-                        if (MM::PRIV) {
-                            const int tb = (MM::PRIV == 1 ? xbase : accbase) + item_n * ACCS + col;
-                            x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
-                        } else {
-                            x = lds[accbase + item_n * ACCS + col];
-                        }
+                        const int tb = accbase + item_n * ACCS + PH::gaux(g) * CMAX + item_il;
+                        x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
                     }
                     s[g] = x;
                 }
@@ -1586,7 +1496,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
         }
         RNNG_STAMP(5);
-        step_lds_barrier();   // the chunk buffers are written again at the top of the next step
+        step_lds_barrier();   // the tiles are written again in the next step
     }
 }
 
