@@ -404,11 +404,18 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
     const StepPhase& ph = lay.ph[0];
     const int MT = (N + 15) / 16, NTU = (ph.n_tasks * ph.cmax + 15) / 16;
     if (MT * NTU > 16) return "";     // accumulator registers
-    // chunks in flight: about 16 128-bit loads per lane, no more chunks than the widest source has
+    // D register sets, D - 1 chunks in flight (see the kernel): about a dozen 128-bit loads per lane
+    // (measured: more in flight is slower), and among the depths up to that the one that pads the
+    // sources' chunk sequences least
     int kmax = 0;
     for (int s = 0; s < ml.n_src; ++s) kmax = std::max(kmax, lay.src[s].k_len);
-    int D = 1;
-    while (D * 2 * MT <= 16 && D * 64 < kmax) D *= 2;
+    const int dmax = std::max(2, std::min(12 / MT + 1, (kmax + 63) / 64 + 1));
+    int D = dmax, best_slots = 1 << 30;
+    for (int d = dmax; d >= std::max(2, dmax / 2); --d) {
+        int slots = 0;
+        for (int s = 0; s < ml.n_src; ++s) slots += ((lay.src[s].k_len + 63) / 64 + d - 1) / d * d;
+        if (slots < best_slots) { best_slots = slots; D = d; }
+    }
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);

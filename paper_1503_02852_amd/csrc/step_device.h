@@ -1295,9 +1295,17 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             for (int t2 = 0; t2 < STEP_MAX_TASKS; ++t2) if (task == t2) b = MM::blk(sidx, t2);
             brow[sidx][nt] = (b >= 0 ? suni(ml.wbase[sidx]) + (b * CMAX + ul) * suni(ml.wstride[sidx]) : suni(ml.zrow)) + 4 * (lane >> 4);
         }
-    // this lane's A-operand element inside a chunk: stream 16 mt + (lane & 15), columns wcol ... wcol + 3
+    // this lane's A-operand element inside a chunk: stream 16 mt + (lane & 15), columns wcol ... wcol + 3;
+    // its byte offset in chunk 0 of each source (a stream beyond N: outside the descriptor)
     const int wcol = wave * 16 + 4 * (lane >> 4);
-    const int lrow = lane & 15;
+    int aoff[MM::NSRC][MM::MT];
+#pragma unroll
+    for (int sidx = 0; sidx < MM::NSRC; ++sidx)
+#pragma unroll
+        for (int mt = 0; mt < MM::MT; ++mt) {
+            const int n = mt * 16 + (lane & 15);
+            aoff[sidx][mt] = n < N ? (n * MM::K(sidx) + wcol) * 4 : 0x7FFFFFF0;
+        }
 
     bool dead = false;
     int pdelay = 0;
@@ -1359,103 +1367,117 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         };
         // ---- chunk pipeline ----
         // A source's columns are cut into groups of D chunks of 64 columns (the last group padded
-        // with empty chunks whose loads all return zero).  Chunk i of a group lives in register
-        // set i, so every register index is static although the loop over a source's groups is
-        // not unrolled.  D chunks are in flight: the loads of chunk i of the next group (or of
-        // the next source's first group) are issued as soon as chunk i has been checked.
+        // with empty chunks that are skipped).  Chunk i of a group lives in register set i, so
+        // every register index is static although the loop over a source's groups is not
+        // unrolled.  D - 1 chunks are in flight: while chunk i is multiplied, the set of chunk
+        // i - 1 takes the loads of chunk i + D - 1 and chunk i + 1 is tested for sentinels.  These
+        // three run in one basic block (loads that have nothing to fetch get an offset outside
+        // the descriptor instead of a branch), so that the compiler can place the loads and the
+        // test between the matrix instructions, where the wavefront would otherwise idle.
         muintx4 v[D][MM::MT];
-        // This lane's operands of one chunk (first column k0) of a source with K columns.  Streams
-        // beyond N and columns beyond K read as zeros (offset outside the descriptor).
-        auto load_chunk = [&](muintx4 (&dst)[MM::MT], const __amdgpu_buffer_rsrc_t& rsrc, int K, int k0) {
+        // This lane's operands of the chunk with first column k0 of source S (on: else nothing is
+        // fetched).  Columns beyond K read as zeros; they exist only if K is no multiple of 64.
+        auto load_chunk = [&](muintx4 (&dst)[MM::MT], const __amdgpu_buffer_rsrc_t& rsrc, const int (&base)[MM::MT], int K, bool k_ragged, int k0, bool on) {
 #pragma unroll
             for (int mt = 0; mt < MM::MT; ++mt) {
-                const int n = mt * 16 + lrow, k = k0 + wcol;
-                const int off = (n < N && k < K) ? (n * K + k) * 4 : 0x7FFFFFF0;
+                int off = base[mt] + k0 * 4;
+                if (k_ragged) off = k0 + wcol < K ? off : 0x7FFFFFF0;
+                off = on ? off : 0x7FFFFFF0;
                 dst[mt] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
             }
+        };
+        // true if some element of the chunk still shows the sentinel (same in all lanes)
+        auto incomplete = [&](const muintx4 (&x)[MM::MT]) {
+            unsigned m = 0;
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt) {
+                const unsigned m1 = x[mt].x > x[mt].y ? x[mt].x : x[mt].y, m2 = x[mt].z > x[mt].w ? x[mt].z : x[mt].w;
+                const unsigned m3 = m1 > m2 ? m1 : m2;
+                m = m > m3 ? m : m3;
+            }
+            return __builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) != 0;
         };
         // hold the first loads back until the producers' stores are usually visible
         for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
-        step_static_for<0, D>([&](auto ii) { load_chunk(v[decltype(ii)::value], rs[0], MM::K(0), decltype(ii)::value * 64); });
+        step_static_for<0, D - 1>([&](auto ii) {
+            constexpr int i = decltype(ii)::value;
+            load_chunk(v[i], rs[0], aoff[0], MM::K(0), MM::K(0) % 64 != 0, i * 64, i * 64 < (MM::K(0) + 63) / 64 * 64);
+        });
         mfloatx4 acc[MM::MT][MM::NTU];
 #pragma unroll
         for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < MM::NTU; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        bool bad = incomplete(v[0]);      // of the chunk that comes next
 
         step_static_for<0, MM::NSRC>([&](auto ss) {
             constexpr int sidx = decltype(ss)::value;
             constexpr int NGR = MM::ngr(sidx);
             constexpr int KP = (MM::K(sidx) + 63) / 64 * 64;              // weight rows are zero-padded up to here
-            constexpr bool ragged = NGR * D * 64 > KP;                    // some chunk lies beyond KP
+            constexpr int snext = sidx + 1 < MM::NSRC ? sidx + 1 : sidx;
+            constexpr int KPN = (MM::K(snext) + 63) / 64 * 64;
 #pragma unroll 1
             for (int g = 0; g < NGR; ++g) {
                 step_static_for<0, D>([&](auto ii) {
                     constexpr int i = decltype(ii)::value;
+                    constexpr int j = (i + D - 1) % D;                   // register set of the chunk D - 1 positions ahead
+                    constexpr int i1 = (i + 1) % D;                      // register set of the next chunk
                     const int k0 = (g * D + i) * 64;
-                    const bool live = !(ragged && k0 >= KP);
-                    // the weights of this chunk (tiles the source does not feed read the zero row)
-                    mfloatx4 opb[MM::NTU];
-#pragma unroll
-                    for (int nt = 0; nt < MM::NTU; ++nt)
-                        if (MM::used(sidx, nt)) opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + (live ? k0 + wave * 16 : 0)]);
-                    // ---- complete the chunk: every element must have left the sentinel ----
-                    auto complete = [&](const muintx4 (&x)[MM::MT]) {
-                        unsigned m = 0;
-#pragma unroll
-                        for (int mt = 0; mt < MM::MT; ++mt) {
-                            const unsigned m1 = x[mt].x > x[mt].y ? x[mt].x : x[mt].y, m2 = x[mt].z > x[mt].w ? x[mt].z : x[mt].w;
-                            const unsigned m3 = m1 > m2 ? m1 : m2;
-                            m = m > m3 ? m : m3;
-                        }
-                        return __builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) == 0;
+                    // the chunk D - 1 positions ahead: in this source, or in the next one's first group
+                    const int gj = i == 0 ? g : g + 1;
+                    const bool same = gj < NGR;
+                    const int kj = same ? (gj * D + j) * 64 : j * 64;
+                    const bool on = same ? kj < KP : (sidx + 1 < MM::NSRC && kj < KPN);
+                    const __amdgpu_buffer_rsrc_t rn = same ? rs[sidx] : rs[snext];
+                    auto ahead = [&]() {
+                        if (same) load_chunk(v[j], rn, aoff[sidx], MM::K(sidx), MM::K(sidx) % 64 != 0, kj, on);
+                        else load_chunk(v[j], rn, aoff[snext], MM::K(snext), MM::K(snext) % 64 != 0, kj, on);
                     };
-                    // The retry path loads into registers of its own: if it reloaded the pipelined
-                    // register set, every later use of that set would wait for all loads in flight.
-                    muintx4 cur[MM::MT];
-                    if (complete(v[i]) || dead) {
+                    if (k0 < KP) {
+                        // the weights of this chunk (tiles the source does not feed read the zero row)
+                        mfloatx4 opb[MM::NTU];
 #pragma unroll
-                        for (int mt = 0; mt < MM::MT; ++mt) cur[mt] = v[i][mt];
-                    } else {
-                        retried = true;
-                        int spins = 0;
-                        for (;;) {
-                            if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
-                            __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
-                            step_compiler_barrier();
-                            load_chunk(cur, rs[sidx], MM::K(sidx), k0);
-                            if (complete(cur)) break;
+                        for (int nt = 0; nt < MM::NTU; ++nt)
+                            if (MM::used(sidx, nt)) opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * 16]);
+                        if (bad && !dead) {
+                            // the retry loads into registers of its own (a reload of the pipelined
+                            // set would make every later use of it wait for all loads in flight)
+                            retried = true;
+                            muintx4 again[MM::MT];
+                            int spins = 0;
+                            for (;;) {
+                                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                                __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
+                                step_compiler_barrier();
+                                load_chunk(again, rs[sidx], aoff[sidx], MM::K(sidx), MM::K(sidx) % 64 != 0, k0, true);
+                                if (!incomplete(again)) break;
+                            }
+#pragma unroll
+                            for (int mt = 0; mt < MM::MT; ++mt) v[i][mt] = again[mt];
                         }
-                    }
-                    if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
-                    if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); RNNG_STAMP(7); }
-                    // ---- loads of the chunk that takes this register set next ----
-                    // (one load site: the descriptor and the columns are selected, not branched on)
-                    constexpr int snext = sidx + 1 < MM::NSRC ? sidx + 1 : sidx;
-                    const bool same = g + 1 < NGR;
-                    if (same || sidx + 1 < MM::NSRC) {
-                        const __amdgpu_buffer_rsrc_t rn = same ? rs[sidx] : rs[snext];
-                        load_chunk(v[i], rn, same ? MM::K(sidx) : MM::K(snext), same ? k0 + D * 64 : i * 64);
-                    } else if (i == 0) {
-                        prefetch_statics();
-                    }
-                    // ---- matrix cores: this wavefront's 16 columns of the chunk ----
-                    if (live) {
+                        if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
+                        if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); RNNG_STAMP(7); }
+                        ahead();
+                        bad = incomplete(v[i1]);
 #pragma unroll
                         for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
                             for (int nt = 0; nt < MM::NTU; ++nt)
                                 if (MM::used(sidx, nt)) {
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].x), opb[nt][0], acc[mt][nt], 0, 0, 0);
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].y), opb[nt][1], acc[mt][nt], 0, 0, 0);
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].z), opb[nt][2], acc[mt][nt], 0, 0, 0);
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(cur[mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].x), opb[nt][0], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].y), opb[nt][1], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].z), opb[nt][2], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
                                 }
+                    } else {
+                        ahead();
+                        bad = incomplete(v[i1]);
                     }
                 });
             }
         });
+        prefetch_statics();
         // ---- hand the accumulators to the element-wise threads: one partial tile per wavefront ----
         // (the previous step's readers of the tiles are behind the barrier that ends a step)
         {
