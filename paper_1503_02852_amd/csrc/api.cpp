@@ -465,7 +465,10 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (const char* env = std::getenv("RNNG_BUNDLE"))
         if (std::atoi(env) == 0) g->plan.bundle_of.assign(g->plan.bundle_of.size(), -1);      // tuning aid: no exchange bundles
     if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
-    if (const char* env = std::getenv("RNNG_XCD_LOCAL")) g_xcd_local = std::atoi(env) != 0;
+    {
+        const char* env = std::getenv("RNNG_XCD_LOCAL");
+        g_xcd_local = env ? std::atoi(env) != 0 : true;
+    }
     *out = g;
     return RNN_OK;
 }

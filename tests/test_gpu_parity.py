@@ -175,6 +175,18 @@ def test_three_layer_lstm_stack():
     run_both(wl.make_workload("lstm3", spec, T=19, N=2, seed=21, scale=0.4, bias_scale=0.3, masked_fraction=0.2))
 
 
+@pytest.mark.parametrize("local", ["0", "1"])
+def test_exchange_written_through_and_through_the_xcd_cache(monkeypatch, local):
+    """Both forms of the exchange inside a group of workgroups (plain stores served by the XCD's
+    L2, or every exchanged tensor written through) on a stack (values that another group polls are
+    written through one step late) and on a single recurrent layer."""
+    monkeypatch.setenv("RNNG_XCD_LOCAL", local)
+    run_both(wl.make_workload("lstm3", wl.lstm_net(12, [20, 24, 16], 5), T=23, N=2, seed=22, scale=0.4, bias_scale=0.3, masked_fraction=0.2),
+             label=f"stack, RNNG_XCD_LOCAL={local}")
+    run_both(wl.make_workload("lstm1", wl.lstm_net(9, [40], 6), T=17, N=1, seed=23, scale=0.4, bias_scale=0.3), label=f"layer, RNNG_XCD_LOCAL={local}")
+    run_both(wl.make_workload("elman", wl.elman_net(7, 33, 4), T=12, N=3, seed=24, scale=0.4, bias_scale=0.3), label=f"elman, RNNG_XCD_LOCAL={local}")
+
+
 def test_stacked_elman_layers_with_delayed_link():
     g = wl.GraphSpec()
     x = g.add_node(wl.INPUT, wl.LINEAR, 9, name="x")
