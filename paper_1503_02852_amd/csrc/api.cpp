@@ -319,7 +319,11 @@ hipError_t ensure_xcd_map(unsigned* scratch, hipStream_t s, const XcdMap** out) 
 // offsets and park idle lanes 1 GiB beyond: every tensor of the window must stay below 1 GiB.
 bool wave_tensor_sizes_ok(const rnn_graph* g) {
     int64_t maxdim = 1;
-    for (int b = 0; b < g->plan.n_bufs; ++b) maxdim = std::max<int64_t>(maxdim, g->plan.buf_dim[b]);
+    for (int b = 0; b < g->plan.n_bufs; ++b) {
+        bool is_input = false;      // the caller's input tensors are never stored by a step kernel
+        for (int k : g->plan.input_nodes) is_input = is_input || g->plan.ybuf(k) == b;
+        if (!is_input) maxdim = std::max<int64_t>(maxdim, g->plan.buf_dim[b]);
+    }
     return (int64_t)g->T * g->N * maxdim * 4 < (int64_t(1) << 30);
 }
 
