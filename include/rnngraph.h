@@ -41,7 +41,8 @@ enum rnn_status {
     RNN_ERR_INVALID_GRAPH = -2,    /* the node / edge list violates a rule listed at rnn_graph_create */
     RNN_ERR_WORKSPACE = -3,        /* workspace NULL, misaligned or too small */
     RNN_ERR_SEQUENCE = -4,         /* rnn_bptt before rnn_forward, rnn_grads before rnn_bptt */
-    RNN_ERR_DEVICE = -5,           /* a HIP call failed or a kernel reported a step-barrier time-out */
+    RNN_ERR_DEVICE = -5,           /* a HIP call failed, or a kernel reported a wait that ran into its limit or a
+                                      workgroup placement other than the one observed for the device */
     RNN_ERR_NO_MEMORY = -6
 };
 
@@ -112,7 +113,11 @@ int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N);
  *              rnn_bptt and rnn_grads and must stay unchanged until rnn_grads has completed.
  *   d_workspace DEVICE, 256-byte aligned, at least rnn_workspace_bytes(g, T, N); it holds the
  *              window's state between rnn_forward, rnn_bptt and rnn_grads.
- * One graph handle serves one window at a time. */
+ * One graph handle serves one window at a time.  All work is queued on hip_stream; the first
+ * forward call of a process on a device also runs a short probe kernel and waits for it (it
+ * records on which XCD the workgroups of a launch land: recurrent layers whose workgroups share
+ * an XCD then exchange their state through that XCD's L2; RNNG_XCD_LOCAL=0 in the environment
+ * switches that off), later calls do not synchronise. */
 int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inputs,
                 int32_t T, int32_t N, void* d_workspace, int64_t ws_bytes, void* hip_stream);
 
