@@ -189,8 +189,10 @@ struct rnn_graph {
             c.source = jit_step_source(plan, cp, backward, c.lp.NB);
         return jit_choices.emplace(key, c).first->second;
     }
-    // Chains of recurrent components run side by side in one launch (wave-autonomous members only).
-    struct ChainChoice { std::string source; std::vector<int> G; };
+    // Chains of recurrent components run side by side in one launch: all members in the
+    // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
+    // workgroups shared among the members).
+    struct ChainChoice { std::string source; std::vector<int> G, J; bool mstep = false; size_t lds_bytes = 0; };
     std::map<long long, ChainChoice> chain_choices;
     bool use_chains = true;
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
@@ -208,6 +210,32 @@ struct rnn_graph {
                 c.G.push_back(pick);
             }
             if (c.G.size() == ch.members.size()) c.source = jit_chain_source(plan, ch, backward, N, c.G);
+            if (c.source.empty() && N > 8 && force_step_J <= 0) {
+                // matrix-core members: each gets an equal share of the 256 workgroups; per member the
+                // most stream groups, then the most unit chunks that fit the share (as for a single
+                // component: fewer only while a workgroup does not fill a 16-row tile)
+                const int share = 256 / (int)ch.members.size();
+                c.G.clear(); c.J.clear();
+                for (const CompPlan& m : ch.members) {
+                    int pg = 0, pj = 0, best_rows = -1;
+                    for (int J : {4, 2, 1}) {
+                        for (int G : {128, 64, 32, 16}) {
+                            if (G * J > share) continue;
+                            size_t lds = 0; int rows = 0;
+                            if (jit_mstep_source(plan, m, backward, N, G, J, &lds, &rows).empty()) continue;
+                            if (best_rows < 0 || (best_rows < 16 && rows > best_rows)) { pg = G; pj = J; best_rows = rows; }
+                            if (best_rows >= 16) break;
+                        }
+                        if (pg) break;
+                    }
+                    if (!pg) break;
+                    c.G.push_back(pg); c.J.push_back(pj);
+                }
+                if (c.G.size() == ch.members.size()) {
+                    c.source = jit_mstep_chain_source(plan, ch, backward, N, c.G, c.J, &c.lds_bytes);
+                    c.mstep = !c.source.empty();
+                }
+            }
         }
         return chain_choices.emplace(key, c).first->second;
     }
@@ -416,17 +444,21 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
 hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0, int t1) {
     const ChainPlan& ch = g->plan.chains[chain];
     const rnn_graph::ChainChoice& cc = g->chain_choice(chain, backward, g->N);
-    if (cc.source.empty() || !wave_tensor_sizes_ok(g)) return hipErrorNotSupported;
+    if (cc.source.empty() || (!cc.mstep && !wave_tensor_sizes_ok(g))) return hipErrorNotSupported;
     hipFunction_t fn = jit_step_function(cc.source);
     if (!fn) return hipErrorNotSupported;
     const PlanView pv = g->view();
     const int T = g->T, N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     for (const CompPlan& m : ch.members) {
-        hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, true, t0, t1, s);
+        hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s);
         if (e != hipSuccess) return e;
     }
     StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;
+    if (cc.mstep) {
+        lp.G = 0; lp.NB = 1; lp.lds_bytes = cc.lds_bytes; lp.xcd_stride = 1;
+        for (size_t i = 0; i < cc.G.size(); ++i) lp.G += cc.G[i] * cc.J[i];      // launch size
+    }
     StepArgs a;
     fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
                    T, N, backward, 1 << 22, t0, t1);
@@ -434,7 +466,12 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int 
     for (int i = 0; i < a.n_groups; ++i) {
         a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
         a.grp_G[i] = cc.G[i];
-        if (g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[i] = g->xcd->xcc[i];
+        if (cc.mstep) {
+            a.grp_J[i] = cc.J[i];
+            a.grp_first[i] = i == 0 ? 0 : a.grp_first[i - 1] + cc.G[i - 1] * cc.J[i - 1];
+        } else if (g_xcd_local && g->xcd && g->xcd->ok) {
+            a.xcc_expect[i] = g->xcd->xcc[i];
+        }
     }
     hipError_t e = jit_launch(fn, a, lp, s);
     if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(cc.source); return hipErrorNotSupported; }

@@ -390,20 +390,23 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
 
 // Matrix-core variant for N >= 9 streams (single-phase components).  Empty if not eligible;
 // otherwise *lds_bytes receives the dynamic LDS size.
-std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J, size_t* lds_bytes, int* rows) {
+namespace {
+// One component of a matrix-core kernel: descriptors PH0 and MM inside namespace ns.
+bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J,
+                      const std::string& ns, size_t* lds_bytes, int* rows) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
-    if (phases.size() != 1 || N_all < 1 || J < 1 || G * J > 256) return "";
-    if (J > 1 && N_all % (16 * J) != 0) return "";      // stream groups of whole 16-stream tiles
+    if (phases.size() != 1 || N_all < 1 || J < 1 || G * J > 256) return false;
+    if (J > 1 && N_all % (16 * J) != 0) return false;      // stream groups of whole 16-stream tiles
     const int N = (N_all + J - 1) / J;                   // streams per workgroup
     StepLayout lay;
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
-    if (!lay.ok) return "";
+    if (!lay.ok) return false;
     MLayout ml;
     compute_mstep_layout(lay, N, (int)(STEP_LDS_LIMIT / 4), ml);
-    if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return "";
+    if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return false;
     const StepPhase& ph = lay.ph[0];
     const int MT = (N + 15) / 16, NTU = (ph.n_tasks * ph.cmax + 15) / 16;
-    if (MT * NTU > 16) return "";     // accumulator registers
+    if (MT * NTU > 16) return false;     // accumulator registers
     // D register sets, D - 1 chunks in flight (see the kernel): about a dozen 128-bit loads per lane
     // (measured: more in flight is slower), and among the depths up to that the one that pads the
     // sources' chunk sequences least
@@ -416,8 +419,7 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
         for (int s = 0; s < ml.n_src; ++s) slots += ((lay.src[s].k_len + 63) / 64 + d - 1) / d * d;
         if (slots < best_slots) { best_slots = slots; D = d; }
     }
-    std::ostringstream o;
-    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    o << "namespace " << ns << " {\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
     auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases, int dflt) {
         o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
@@ -444,14 +446,61 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
     emit_switch("ngr", "s", ngr, 0);
     o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n";
     o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
+    o << "}  // namespace " << ns << "\n";
+    if (lds_bytes) *lds_bytes = (size_t)ml.total_floats * 4;
+    if (rows) *rows = ph.n_tasks * ph.cmax;
+    return true;
+}
+}  // namespace
+
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J, size_t* lds_bytes, int* rows) {
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    if (!emit_mstep_group(o, P, cp, backward, N_all, G, J, "grp0", lds_bytes, rows)) return "";
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
          "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
          "    __shared__ MShared ms;\n"
-         "    mstep_kernel_body<PH0, MM>(a, ms, lds);\n"
+         "    int w = blockIdx.x;\n"
+         "    if (a.xcd_stride > 1) {\n"
+         "        if (w % a.xcd_stride) return;\n"
+         "        w /= a.xcd_stride;\n"
+         "    }\n"
+         "    mstep_kernel_body<grp0::PH0, grp0::MM>(a, ms, lds, w);\n"
          "}\n";
-    *lds_bytes = (size_t)ml.total_floats * 4;
-    if (rows) *rows = ph.n_tasks * ph.cmax;
+    return o.str();
+}
+
+// Several components side by side (a chain): group g takes the blocks [grp_first[g], ...).
+std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
+                                   const std::vector<int>& J, size_t* lds_bytes) {
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    const int n = (int)ch.members.size();
+    if (n < 2 || n > STEP_MAX_GROUPS || (int)G.size() != n || (int)J.size() != n) return "";
+    size_t lds_max = 0;
+    int total = 0;
+    for (int g = 0; g < n; ++g) {
+        size_t lds = 0;
+        if (!emit_mstep_group(o, P, ch.members[g], backward, N, G[g], J[g], "grp" + std::to_string(g), &lds, nullptr)) return "";
+        lds_max = std::max(lds_max, lds);
+        total += G[g] * J[g];
+    }
+    if (total > 256) return "";      // every workgroup must be resident: they wait for each other
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
+         "    __shared__ MShared ms;\n"
+         "    const int b = blockIdx.x;\n"
+         "    StepArgs c = a;\n";
+    for (int g = 0; g < n; ++g)
+        o << "    if (b >= a.grp_first[" << g << "] && b < a.grp_first[" << g << "] + a.grp_G[" << g << "] * a.grp_J[" << g << "]) {\n"
+             "        c.desc_off = a.grp_desc_off[" << g << "]; c.G = a.grp_G[" << g << "]; c.J = a.grp_J[" << g << "];\n"
+             "        mstep_kernel_body<grp" << g << "::PH0, grp" << g << "::MM>(c, ms, lds, b - a.grp_first[" << g << "]);\n"
+             "        return;\n"
+             "    }\n";
+    o << "}\n";
+    if (lds_bytes) *lds_bytes = lds_max;
     return o.str();
 }
 

@@ -22,6 +22,10 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
 // G unit chunks x J stream groups (N / J streams each).
 // *rows receives the accumulator rows per workgroup (tasks x units per chunk).
 std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int J, size_t* lds_bytes, int* rows = nullptr);
+// Chain of matrix-core components in one launch: member g on G[g] unit chunks x J[g] stream groups
+// (at most 256 workgroups in all).  Empty if some member is not eligible.
+std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
+                                   const std::vector<int>& J, size_t* lds_bytes);
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
 // compile fails (the log, if any, goes to *log).  Needs no GPU.
 bool jit_compile(const std::string& source, std::string* log);

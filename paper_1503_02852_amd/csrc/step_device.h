@@ -1227,13 +1227,9 @@ RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int lds_l
 struct MShared { StepShared sh; MLayout ml; };
 
 template <class PH, class MM>
-__device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms, float* lds) {
-    int w = blockIdx.x;
-    if (a.xcd_stride > 1) {
-        if (w % a.xcd_stride) return;
-        w /= a.xcd_stride;
-    }
-    if (w >= a.G * a.J) return;
+// w: index of this workgroup among the a.G * a.J workgroups of the component.
+__device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms, float* lds, int w) {
+    if (w < 0 || w >= a.G * a.J) return;
     const int wj = w / a.G;      // stream group
     w -= wj * a.G;               // unit chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

@@ -67,6 +67,9 @@ struct StepArgs {
     // grp_desc_off[g] on grp_G[g] workgroups; block b belongs to group b % 8, part b / 8, which
     // puts each group on one XCD.  n_groups == 0: a single component (desc_off, G, xcd_stride).
     int n_groups, grp_desc_off[STEP_MAX_GROUPS], grp_G[STEP_MAX_GROUPS];
+    // Chains of the matrix-core build: group g takes the blocks [grp_first[g], grp_first[g] +
+    // grp_G[g] * grp_J[g]) (all groups use all XCDs).
+    int grp_J[STEP_MAX_GROUPS], grp_first[STEP_MAX_GROUPS];
     // Frames [t_begin, t_end) are computed (forward: ascending, backward: descending); frames of
     // the window outside this range hold the results of earlier calls (T is the whole window).
     int t_begin, t_end;

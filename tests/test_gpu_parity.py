@@ -175,6 +175,28 @@ def test_three_layer_lstm_stack():
     run_both(wl.make_workload("lstm3", spec, T=19, N=2, seed=21, scale=0.4, bias_scale=0.3, masked_fraction=0.2))
 
 
+@pytest.mark.parametrize("layers,N", [([24, 20], 16), ([16, 24, 12], 20), ([40, 36], 33)])
+def test_lstm_stack_with_many_streams_runs_side_by_side(layers, N):
+    """Stacked layers at N >= 9 (matrix-core build): the members of a stack share one launch."""
+    spec = wl.lstm_net(12, layers, 5)
+    run_both(wl.make_workload("lstm_stack_streams", spec, T=15, N=N, seed=31, scale=0.4, bias_scale=0.3, masked_fraction=0.2))
+
+
+def test_many_stream_stack_in_one_launch_equals_layers_one_after_another(monkeypatch):
+    from paper_1503_02852_amd.runner import window_for
+    spec = wl.lstm_net(10, [32, 28], 6)
+    w = wl.make_workload("stack", spec, T=13, N=24, seed=32, scale=0.4, bias_scale=0.3)
+    outs = []
+    for chain in ("1", "0"):
+        monkeypatch.setenv("RNNG_CHAIN", chain)
+        win = window_for(w)
+        win.forward(); win.bptt(); win.compute_grads()
+        gw, gb = win.grads_unpacked()
+        outs.append(([win.node_output(k).copy() for k in spec.output_nodes()], [g.copy() for g in gw if g is not None]))
+    for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
+        assert nerr(a, b) < OUT_TOL
+
+
 @pytest.mark.parametrize("local", ["0", "1"])
 def test_exchange_written_through_and_through_the_xcd_cache(monkeypatch, local):
     """Both forms of the exchange inside a group of workgroups (plain stores served by the XCD's
