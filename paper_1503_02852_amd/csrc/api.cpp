@@ -32,13 +32,15 @@ struct Layout {
     int64_t table_off = 0, dims_off = 0, words_off = 0, blob_bytes = 0;
     int64_t sync_off = 0;                 // 1 KiB of zero-initialised control words; the loss (double) sits at its start
     std::vector<int64_t> buf_off;         // per buffer id, bytes; -1 = not in the workspace
+    int64_t partial_off = -1;             // partial sums of the two-dimensional matrix-core kernels (one launch at a time)
     int64_t total = 0;
 };
 constexpr int64_t SYNC_BYTES = 1024;
 
 int64_t g_layout_skew = 4352;      // bytes, a multiple of 256 (RNNG_LAYOUT_SKEW overrides: tuning aid)
 
-Layout make_layout(const Plan& P, int T, int N) {
+// partial_floats: floats per frame of the largest partial-sum tensor any launch of the window needs
+Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats) {
     Layout L;
     int n_alloc = 0;
     const int K = (int)P.xnodes.size();
@@ -62,6 +64,7 @@ Layout make_layout(const Plan& P, int T, int N) {
         cur += g_layout_skew * (1 + n_alloc % 13);
         ++n_alloc;
     }
+    if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)T * partial_floats * 4, 256); }
     L.total = cur;
     return L;
 }
@@ -141,7 +144,7 @@ struct rnn_graph {
     int force_step_G = 0;
     bool use_jit = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source; };
+    struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
     std::map<long long, JitChoice> jit_choices;
     const JitChoice& jit_choice(int comp, bool backward, int N) {
@@ -162,6 +165,27 @@ struct rnn_graph {
             if (force_step_G > 0) break;
         }
         // 2. matrix-core variant for many streams: weights in LDS, MFMA, the smallest workgroup count that fits
+        // 2a. many streams and wide sources: the two-dimensional split, where a workgroup polls a
+        //     sixteenth of every source (worth its second exchange once the one-dimensional split
+        //     would poll a quarter of a megabyte per workgroup and step, and while a workgroup has
+        //     few rows: then the one-dimensional split wastes most of its 16-row tiles, whereas
+        //     here several workgroups' rows share a tile and the partial sums stay small; measured
+        //     on generalized_n64: backward (4 rows) faster, forward (16 rows) slower)
+        if (c.source.empty() && N > 8 && force_step_G <= 0 && force_step_J <= 0 &&
+            !(std::getenv("RNNG_MSTEP_2D") && std::atoi(std::getenv("RNNG_MSTEP_2D")) == 0)) {
+            StepLayout lay;
+            compute_step_layout(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, 256, 1, N, lay);
+            int64_t polled = 0;
+            if (lay.ok) for (int sidx = 0; sidx < lay.n_sources; ++sidx) polled += (int64_t)N * lay.src[sidx].k_len * 4;
+            if (polled >= 256 * 1024) {
+                size_t lds = 0; int64_t pf = 0;
+                std::string src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
+                if (!src.empty() && (pf <= (int64_t)256 * 16 * 8 * ((N + 15) / 16 * 16) || std::getenv("RNNG_MSTEP_2D"))) {      // at most 8 rows per workgroup (below)
+                    c.source = src; c.lp.ok = true; c.lp.G = 256; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
+                    c.two_d = true; c.partial_floats = pf;
+                }
+            }
+        }
         if (c.source.empty() && N > 8) {
             // stream groups: as many as possible (every group halves the bytes a workgroup polls per
             // step); unit chunks: as many as the 256 CUs allow while a workgroup still fills a
@@ -188,6 +212,22 @@ struct rnn_graph {
         if (c.source.empty() && plan_step_launch(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, N, force_step_G, c.lp))
             c.source = jit_step_source(plan, cp, backward, c.lp.NB);
         return jit_choices.emplace(key, c).first->second;
+    }
+    // floats per frame of the largest partial-sum tensor that a step launch of a window with N streams needs
+    int64_t partial_frame_floats(int N) {
+        int64_t m = 0;
+        if (!use_jit) return 0;
+        for (size_t c = 0; c < plan.comps.size(); ++c) {
+            const CompPlan& cp = plan.comps[c];
+            if (!cp.recurrent) continue;
+            for (int backward = 0; backward < 2; ++backward) {
+                if (backward ? !cp.has_bwd_program : !cp.has_fwd_program) continue;
+                if (cp.chain >= 0 && !chain_choice(cp.chain, backward != 0, N).source.empty()) continue;
+                const JitChoice& jc = jit_choice((int)c, backward != 0, N);
+                if (jc.two_d) m = std::max(m, jc.partial_floats);
+            }
+        }
+        return m;
     }
     // Chains of recurrent components run side by side in one launch: all members in the
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
@@ -407,6 +447,13 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
                 StepArgs a;
                 fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
                 a.J = jc->J;
+                if (jc->two_d) {
+                    if (g->layout.partial_off < 0) return hipErrorInvalidValue;
+                    a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
+                    e = launch_fill_sentinel(a.partial + (int64_t)t0 * jc->partial_floats, (int64_t)(t1 - t0) * jc->partial_floats, s);
+                    if (e != hipSuccess) return e;
+                    e = hipErrorUnknown;
+                }
                 if (jc->wave && jc->lp.xcd_stride == 8 && g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[0] = g->xcd->xcc[0];
                 StepLaunchPlan lp_all = jc->lp;
                 lp_all.G = jc->lp.G * jc->J;       // launch size; a.G stays the number of unit chunks
@@ -555,7 +602,7 @@ int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
     if ((int64_t)T * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
-    return make_layout(g->plan, T, N).total;
+    return make_layout(g->plan, T, N, const_cast<rnn_graph*>(g)->partial_frame_floats(N)).total;
 }
 
 namespace {
@@ -605,7 +652,7 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
     const Plan& P = g->plan;
     for (size_t i = 0; i < P.input_nodes.size(); ++i)
         if (!d_inputs[i] && !g->is_onehot(P.input_nodes[i])) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
-    Layout L = make_layout(P, T, N);
+    Layout L = make_layout(P, T, N, g->partial_frame_floats(N));
     if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
     if (ws_bytes < L.total) return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(L.total) + " bytes");

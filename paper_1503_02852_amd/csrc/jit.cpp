@@ -471,6 +471,54 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
     return o.str();
 }
 
+// Matrix-core variant with the two-dimensional split (G workgroups in row groups of GJ).  Empty
+// if not eligible; otherwise *lds_bytes receives the dynamic LDS size and *partial_floats the
+// floats per frame of the partial-sum tensor.
+std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int GJ, size_t* lds_bytes,
+                              int64_t* partial_floats) {
+    const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
+    if (phases.size() != 1 || N < 1 || N > 64 || G > 256 || GJ != 16 || G % GJ != 0) return "";
+    StepLayout lay;
+    compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
+    if (!lay.ok) return "";
+    M2Layout ml;
+    compute_mstep2_layout(lay, N, GJ, (int)(STEP_LDS_LIMIT / 4), ml);
+    if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return "";
+    const StepPhase& ph = lay.ph[0];
+    const int MT = (N + 15) / 16, RT = ph.n_tasks * ph.cmax;
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    emit_phase_descriptor(o, P, phases[0], 0, 0);
+    auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases, int dflt) {
+        o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
+        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
+        o << "            default: return " << dflt << ";\n        }\n    }\n";
+    };
+    std::vector<std::pair<int, int>> ks, kss, nch, pos0, blk;
+    int pos = 0, nchmax = 0;
+    for (int s = 0; s < ml.n_src; ++s) {
+        const int K = lay.src[s].k_len, KS = K / GJ;
+        ks.push_back({s, K}); kss.push_back({s, KS}); nch.push_back({s, KS / 64}); pos0.push_back({s, pos});
+        pos += KS / 64; nchmax = std::max(nchmax, KS / 64);
+        for (int t = 0; t < ph.n_tasks; ++t) if (ml.blk[s][t] >= 0) blk.push_back({s * STEP_MAX_TASKS + t, ml.blk[s][t]});
+    }
+    if (pos > 24) return "";      // the chunk sequence is unrolled
+    o << "struct M2 {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", GJ = " << GJ << ", RT = " << RT
+      << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ", NCHMAX = " << nchmax << ";\n";
+    emit_switch("K", "s", ks, 0); emit_switch("KS", "s", kss, 0); emit_switch("nch", "s", nch, 0); emit_switch("pos0", "s", pos0, 0);
+    emit_switch("blk_", "key", blk, -1);
+    o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n};\n";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
+         "    __shared__ M2Shared ms;\n"
+         "    mstep2_kernel_body<PH0, M2>(a, ms, lds, (int)blockIdx.x);\n"
+         "}\n";
+    if (lds_bytes) *lds_bytes = (size_t)ml.total_floats * 4;
+    if (partial_floats) *partial_floats = (int64_t)G * GJ * RT * (MT * 16);
+    return o.str();
+}
+
 // Several components side by side (a chain): group g takes the blocks [grp_first[g], ...).
 std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
                                    const std::vector<int>& J, size_t* lds_bytes) {

@@ -22,6 +22,10 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
 // G unit chunks x J stream groups (N / J streams each).
 // *rows receives the accumulator rows per workgroup (tasks x units per chunk).
 std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int J, size_t* lds_bytes, int* rows = nullptr);
+// Matrix-core variant with the two-dimensional split (row groups of GJ workgroups that share
+// the columns of every source; partial sums travel through a tensor of *partial_floats floats per frame).
+std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int GJ, size_t* lds_bytes,
+                              int64_t* partial_floats);
 // Chain of matrix-core components in one launch: member g on G[g] unit chunks x J[g] stream groups
 // (at most 256 workgroups in all).  Empty if some member is not eligible.
 std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,

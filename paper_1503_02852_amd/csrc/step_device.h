@@ -1518,4 +1518,351 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     }
 }
 
+// =============================================================================================
+// Matrix-core variant with a two-dimensional split (many streams, wide layers).
+//
+// In the variant above every workgroup polls every source tensor whole (N * K values per source
+// and step), and with wide layers that polling is all a step waits for.  Here the G workgroups
+// form G / GJ row groups of GJ workgroups.  Workgroup (gi, gj) still owns the units of chunk
+// w = gi * GJ + gj for the element-wise program, but of the contraction it does column slice gj
+// (K / GJ columns of every source) for the rows of ALL GJ members of its row group: it polls
+// only its slice, multiplies (each wavefront four members' row tiles, operands straight from the
+// polling loads as above) and stores the partial sums, written through, into
+// partial[frame][member][gj][row][stream].  Then it polls the GJ partial sums of its own rows,
+// adds them and runs the element-wise program.  Per step a workgroup polls N * K / GJ values per
+// source (four times, once per wavefront) plus GJ * rows * N partial sums, instead of N * K.
+//
+// M2 is a generated descriptor:
+//   static constexpr int NJ (streams), MT (16-stream tiles), NSRC, GJ, RT (rows of a member:
+//   tasks * cmax <= 16), CMAX, ACCS, NCHMAX; constexpr K(s), KS(s) (columns of a slice, a multiple
+//   of 64), nch(s) = KS(s) / 64, pos0(s) (chunks of the sources before s), blk(s, task).
+// =============================================================================================
+struct M2Layout {
+    int ok, n_src, cmax, zrow, accbase, accstride, total_floats;
+    int wbase[STEP_MAX_SOURCES], wstride[STEP_MAX_SOURCES], rows[STEP_MAX_SOURCES];
+    short blk[STEP_MAX_SOURCES][STEP_MAX_TASKS];
+};
+
+RNNG_HD inline void compute_mstep2_layout(const StepLayout& lay, int N, int GJ, int lds_limit_floats, M2Layout& m) {
+    m.ok = 0;
+    if (!lay.ok || lay.n_phases != 1 || lay.n_sources < 1) return;
+    const StepPhase& ph = lay.ph[0];
+    if (ph.item_chunk * N > STEP_THREADS || ph.n_tasks * ph.cmax > 16) return;
+    m.n_src = lay.n_sources; m.cmax = ph.cmax;
+    const int npad = (N + 15) / 16 * 16;
+    int cur = 0, wsmax = 0;
+    for (int s = 0; s < lay.n_sources; ++s) {
+        if (lay.src[s].k_len % (64 * GJ)) return;       // slices of whole 64-column chunks
+        int nb = 0;
+        for (int t = 0; t < STEP_MAX_TASKS; ++t) {
+            m.blk[s][t] = -1;
+            if (t >= ph.n_tasks) continue;
+            for (int e = 0; e < ph.task[t].n_edges; ++e)
+                if (ph.task[t].e[e].src == s && m.blk[s][t] < 0) m.blk[s][t] = (short)nb++;
+        }
+        m.rows[s] = nb * ph.cmax;
+        m.wstride[s] = lay.src[s].k_len / GJ + 4;
+        wsmax = m.wstride[s] > wsmax ? m.wstride[s] : wsmax;
+        m.wbase[s] = cur; cur += GJ * m.rows[s] * m.wstride[s];
+    }
+    m.zrow = cur; cur += wsmax;
+    m.accstride = 16 + 4;
+    m.accbase = cur; cur += npad * m.accstride;
+    if (cur > lds_limit_floats) return;
+    m.total_floats = cur;
+    m.ok = 1;
+}
+
+struct M2Shared { StepShared sh; M2Layout ml; };
+
+// w: index of this workgroup among the a.G workgroups of the component.
+template <class PH, class M2>
+__device__ __forceinline__ void mstep2_kernel_body(const StepArgs& a, M2Shared& ms, float* lds, int w) {
+    if (w < 0 || w >= a.G) return;
+    constexpr int GJ = M2::GJ, RT = M2::RT, CMAX = M2::CMAX, NPAD = M2::MT * 16, ACCS = M2::ACCS, NQ = NPAD / 4;
+    // A wavefront multiplies the rows of four members.  A member with few rows does not fill a
+    // 16-row tile: PACK members share one (RP rows each), so the wavefront has TPW tiles.
+    constexpr int RP = RT <= 4 ? 4 : RT <= 8 ? 8 : 16, PACK = 16 / RP, TT = GJ / PACK;      // TT row tiles in all
+    // Work of a step = (stream tile, row tile) pairs.  With 1, 2 or 4 stream tiles a wavefront takes
+    // ONE stream tile (so that no polled value is loaded by two wavefronts) and TT * MT / 4 row
+    // tiles; with 3 it takes all stream tiles and a quarter of the row tiles.
+    constexpr bool BY_STREAMS = M2::MT == 1 || M2::MT == 2 || M2::MT == 4;
+    constexpr int MTW = BY_STREAMS ? 1 : M2::MT, WPS = BY_STREAMS ? 4 / M2::MT : 4, TPW = TT / WPS;
+    static_assert(TT % WPS == 0, "row tiles must divide among the wavefronts");
+    const int gi = w / GJ, gj = w - gi * GJ;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mt0 = BY_STREAMS ? wave / WPS : 0, tl0 = (wave % WPS) * TPW;      // this wavefront's stream tile and first row tile
+    const int T = a.T, N = a.N;
+    StepShared& sh = ms.sh;
+    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, M2::NJ, sh.lay); compute_mstep2_layout(sh.lay, M2::NJ, GJ, (int)(STEP_LDS_LIMIT / 4), ms.ml); }
+    __syncthreads();
+    const StepPhase& ph = sh.lay.ph[0];
+    const M2Layout& ml = ms.ml;
+    {
+        const int ic = ph.item_chunk;
+        const int il = tid % ic, n = tid / ic;
+        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N ? n : 0xFFFF) << 16);
+    }
+    for (int i = tid; i < ml.total_floats; i += STEP_THREADS) lds[i] = 0.0f;
+    __syncthreads();
+    // resident weights: column slice gj of the rows of every member m of this row group
+    for (int s = 0; s < ml.n_src; ++s) {
+        const int K = sh.lay.src[s].k_len, KS = K / GJ;
+        for (int t = 0; t < ph.n_tasks; ++t) {
+            const StepTask& task = ph.task[t];
+            for (int e = 0; e < task.n_edges; ++e) {
+                const StepEdge ed = task.e[e];
+                if (ed.src != s) continue;
+                const float* W = a.weights + ed.w_off;
+                for (int i = tid; i < GJ * CMAX * KS; i += STEP_THREADS) {
+                    const int m = i / (CMAX * KS), rem = i - m * (CMAX * KS);
+                    const int ul = rem / KS, kk = rem - ul * KS;
+                    const int u = (gi * GJ + m) * task.chunk + ul, k = gj * KS + kk;
+                    float v = 0.0f;
+                    if (ul < task.chunk && u < task.n_out) v = ed.transposed ? W[(size_t)k * task.n_out + u] : W[(size_t)u * K + k];
+                    lds[ml.wbase[s] + (m * ml.rows[s] + ml.blk[s][t] * CMAX + ul) * ml.wstride[s] + kk] += v;
+                }
+                __syncthreads();
+            }
+        }
+    }
+    PhaseRegs<PH> r;
+    phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
+    __syncthreads();
+
+    const int accbase = suni(ml.accbase);
+    const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    const int item_n = tid / suni(ph.item_chunk);
+    // weight row behind this lane's tile column (member, row) in each of the wavefront's tiles
+    int brow[M2::NSRC][TPW];
+#pragma unroll
+    for (int sidx = 0; sidx < M2::NSRC; ++sidx)
+#pragma unroll
+        for (int tl = 0; tl < TPW; ++tl) {
+            const int col = lane & 15, m = (tl0 + tl) * PACK + col / RP, row = col % RP;
+            const int task = row / CMAX, ul = row - task * CMAX;
+            int b = -1;
+#pragma unroll
+            for (int t2 = 0; t2 < STEP_MAX_TASKS; ++t2) if (task == t2) b = M2::blk(sidx, t2);
+            brow[sidx][tl] = (b >= 0 && row < RT && m < GJ ? suni(ml.wbase[sidx]) + (m * suni(ml.rows[sidx]) + b * CMAX + ul) * suni(ml.wstride[sidx]) : suni(ml.zrow)) + 4 * (lane >> 4);
+        }
+    // A operands: stream 16 mt + (lane & 15), columns gj * KS + 64 c + 16 kb + 4 (lane >> 4) ...
+    int aoff[M2::NSRC][MTW];
+#pragma unroll
+    for (int sidx = 0; sidx < M2::NSRC; ++sidx)
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt) {
+            const int n = (mt0 + mt) * 16 + (lane & 15);
+            aoff[sidx][mt] = n < N ? (n * M2::K(sidx) + gj * M2::KS(sidx) + 4 * (lane >> 4)) * 4 : 0x7FFFFFF0;
+        }
+    // partial sums: [frame][workgroup][slice][row][stream]
+    const long long pframe = (long long)a.G * GJ * RT * NPAD;      // floats per frame
+    int poff_store[MTW][TPW];      // where this lane's four streams of (stream tile, row tile) go, bytes inside a frame
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+        for (int tl = 0; tl < TPW; ++tl) {
+            const int col = lane & 15, m = (tl0 + tl) * PACK + col / RP, row = col % RP;
+            poff_store[mt][tl] = (row < RT && m < GJ) ? ((((gi * GJ + m) * GJ + gj) * RT + row) * NPAD + (mt0 + mt) * 16 + 4 * (lane >> 4)) * 4 : 0x7FFFFFF0;
+        }
+    const int prow = tid / NQ, pnq = tid - prow * NQ;      // phase 2: this thread adds row prow, streams 4 pnq ...
+    const int poff_load = prow < RT ? ((w * GJ * RT + prow) * NPAD + 4 * pnq) * 4 : 0x7FFFFFF0;      // slice j adds j * RT * NPAD * 4
+
+    bool dead = false;
+    int pdelay = 0;
+    float sn[PH::NG > 0 ? PH::NG : 1];
+    const int nsteps = step_count(a);
+    for (int step = 0; step < nsteps; ++step) {
+        const int t = step_frame(a, step);
+        float s[MAX_SLOTS];
+        RNNG_STAMP(0);
+#pragma unroll
+        for (int g = 0; g < PH::NG; ++g) {
+            if (PH::gkind(g) == GA_KIND_CARRY) {
+                if (step > 0) {
+                    s[g] = r.carry[PH::cidx(g)];
+                } else {
+                    const int frame = t + r.goff[g];
+                    s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+                }
+            } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
+                s[g] = sn[g];
+            } else if (PH::gkind(g) != GA_KIND_ACC) {
+                const int frame = t + r.goff[g];
+                float v = 0.0f;
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < T) {
+                    if (PH::gkind(g) == GA_KIND_STATIC) v = r.gptr[g][(long long)frame * r.gstride[g]];
+                    else v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                }
+                s[g] = v;
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+        RNNG_STAMP(1);
+
+        __amdgpu_buffer_rsrc_t rs[M2::NSRC];
+#pragma unroll
+        for (int sidx = 0; sidx < M2::NSRC; ++sidx) {
+            const StepSource& sc = sh.lay.src[sidx];
+            const int frame = t + suni(sc.frame_off);
+            const bool in_window = frame >= 0 && frame < T;
+            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)(in_window ? frame : 0) * a.N * M2::K(sidx);
+            rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * M2::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
+        }
+        const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(a.partial + (long long)t * pframe, 0, (int)(pframe * 4), STEP_RSRC_FLAGS);
+
+        // ---- phase 1: this slice's share of the row group's contraction ----
+        // The chunks of all sources form one sequence; chunk p lives in register set p & 1 and
+        // the loads of chunk p + 1 are issued before chunk p is multiplied.
+        muintx4 v[2][4][MTW];
+        auto load_chunk = [&](muintx4 (&dst)[4][MTW], auto ss, int c) {
+            constexpr int S = decltype(ss)::value;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt)
+                    dst[kb][mt] = __builtin_amdgcn_raw_buffer_load_b128(rs[S], aoff[S][mt] + (c * 64 + kb * 16) * 4, 0, STEP_COHERENT_AUX);
+        };
+        auto incomplete = [&](const muintx4 (&x)[4][MTW]) {
+            unsigned m = 0;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int mt = 0; mt < MTW; ++mt) {
+                    const unsigned m1 = x[kb][mt].x > x[kb][mt].y ? x[kb][mt].x : x[kb][mt].y, m2 = x[kb][mt].z > x[kb][mt].w ? x[kb][mt].z : x[kb][mt].w;
+                    const unsigned m3 = m1 > m2 ? m1 : m2;
+                    m = m > m3 ? m : m3;
+                }
+            return __builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) != 0;
+        };
+        for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
+        bool retried = false;
+        load_chunk(v[0], StepIntC<0>{}, 0);
+        mfloatx4 acc[MTW][TPW];
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int tau = 0; tau < TPW; ++tau) acc[mt][tau] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        step_static_for<0, M2::NSRC>([&](auto ss) {
+            constexpr int sidx = decltype(ss)::value;
+            step_static_for<0, M2::NCHMAX>([&](auto cc) {
+                constexpr int c = decltype(cc)::value;
+                if constexpr (c < M2::nch(sidx)) {
+                    constexpr int set = (M2::pos0(sidx) + c) & 1;
+                    // loads of the next chunk of the sequence into the other set
+                    if constexpr (c + 1 < M2::nch(sidx)) load_chunk(v[set ^ 1], ss, c + 1);
+                    else if constexpr (sidx + 1 < M2::NSRC) load_chunk(v[set ^ 1], StepIntC<(sidx + 1 < M2::NSRC ? sidx + 1 : sidx)>{}, 0);
+                    if (incomplete(v[set]) && !dead) {
+                        retried = true;
+                        muintx4 again[4][MTW];
+                        int spins = 0;
+                        for (;;) {
+                            if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                            __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
+                            step_compiler_barrier();
+                            load_chunk(again, ss, c);
+                            if (!incomplete(again)) break;
+                        }
+#pragma unroll
+                        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                            for (int mt = 0; mt < MTW; ++mt) v[set][kb][mt] = again[kb][mt];
+                    }
+                    if (sidx == 0 && c == 0) { RNNG_STAMP(2); }
+#pragma unroll
+                    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                        for (int tau = 0; tau < TPW; ++tau) {
+                            const mfloatx4 b = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][tau] + c * 64 + kb * 16]);
+#pragma unroll
+                            for (int mt = 0; mt < MTW; ++mt) {
+                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].x), b[0], acc[mt][tau], 0, 0, 0);
+                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].y), b[1], acc[mt][tau], 0, 0, 0);
+                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].z), b[2], acc[mt][tau], 0, 0, 0);
+                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].w), b[3], acc[mt][tau], 0, 0, 0);
+                            }
+                        }
+                }
+            });
+        });
+        // the partial sums of (member, row, four streams) to their owners, written through
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+            for (int tau = 0; tau < TPW; ++tau) {
+                const muintx4 o = {step_shared_bits(acc[mt][tau][0]), step_shared_bits(acc[mt][tau][1]), step_shared_bits(acc[mt][tau][2]), step_shared_bits(acc[mt][tau][3])};
+                __builtin_amdgcn_raw_buffer_store_b128(o, rp, poff_store[mt][tau], 0, STEP_COHERENT_AUX);
+            }
+        // STATIC inputs of the next step
+        if (step + 1 < nsteps) {
+            const int t2 = a.backward ? t - 1 : t + 1;
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_STATIC) {
+                    const int frame = t2 + r.goff[g];
+                    float x = 0.0f;
+                    if (r.gptr[g] != nullptr && frame >= 0 && frame < T) x = r.gptr[g][(long long)frame * r.gstride[g]];
+                    sn[g] = x;
+                }
+        }
+        RNNG_STAMP(3);
+        // ---- phase 2: add the GJ partial sums of this workgroup's own rows ----
+        {
+            muintx4 q[GJ];
+            int spins = 0;
+            for (;;) {
+                step_compiler_barrier();
+#pragma unroll
+                for (int j = 0; j < GJ; ++j) q[j] = __builtin_amdgcn_raw_buffer_load_b128(rp, poff_load + j * RT * NPAD * 4, 0, STEP_COHERENT_AUX);
+                unsigned m = 0;
+#pragma unroll
+                for (int j = 0; j < GJ; ++j) {
+                    const unsigned m1 = q[j].x > q[j].y ? q[j].x : q[j].y, m2 = q[j].z > q[j].w ? q[j].z : q[j].w;
+                    const unsigned m3 = m1 > m2 ? m1 : m2;
+                    m = m > m3 ? m : m3;
+                }
+                if (__builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) == 0 || dead) break;
+                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
+            }
+            float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int j = 0; j < GJ; ++j) {
+                sum[0] += __uint_as_float(q[j].x); sum[1] += __uint_as_float(q[j].y);
+                sum[2] += __uint_as_float(q[j].z); sum[3] += __uint_as_float(q[j].w);
+            }
+            if (prow < RT) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) lds[accbase + (4 * pnq + e) * ACCS + prow] = sum[e];
+            }
+        }
+        if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
+        else if ((step & 63) == 63 && pdelay > 0) --pdelay;
+        RNNG_STAMP(4);
+        // ---- element-wise program: one thread per (stream, unit) ----
+        if (r.n >= 0) {
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_ACC) {
+                    float x = 0.0f;
+                    if (r.gptr[g] != nullptr) x = lds[accbase + item_n * ACCS + PH::gaux(g) * CMAX + item_il];
+                    s[g] = x;
+                }
+            PH::ops(s);
+#pragma unroll
+            for (int q = 0; q < PH::NST; ++q) {
+                if (r.sptr[q] == nullptr) continue;
+                if (PH::stshared(q)) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+                else store_plain(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+            }
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+        }
+        RNNG_STAMP(5);
+        step_lds_barrier();   // the tile is written again in the next step
+    }
+}
+
 }  // namespace rnng

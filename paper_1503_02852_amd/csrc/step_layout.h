@@ -82,6 +82,9 @@ struct StepArgs {
     // holds them, and the group's polling loads are served there); a workgroup that finds itself
     // on another XCD sets ctrl[0] = 2.  With -1 every exchanged tensor is written through.
     int xcc_expect[STEP_MAX_GROUPS];
+    // Matrix-core build with the two-dimensional split: the partial sums that the workgroups hand
+    // to each other, [frame][workgroup][column slice][row][stream] (sentinel-filled by the host).
+    float* partial;
 };
 
 RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }
