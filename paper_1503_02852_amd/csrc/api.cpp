@@ -177,10 +177,11 @@ struct rnn_graph {
             compute_step_layout(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, 256, 1, N, lay);
             int64_t polled = 0;
             if (lay.ok) for (int sidx = 0; sidx < lay.n_sources; ++sidx) polled += (int64_t)N * lay.src[sidx].k_len * 4;
-            if (polled >= 256 * 1024) {
+            const bool forced = std::getenv("RNNG_MSTEP_2D") != nullptr;      // = 1: wherever the kernel can run (tests)
+            if (polled >= 256 * 1024 || forced) {
                 size_t lds = 0; int64_t pf = 0;
                 std::string src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
-                if (!src.empty() && (pf <= (int64_t)256 * 16 * 8 * ((N + 15) / 16 * 16) || std::getenv("RNNG_MSTEP_2D"))) {      // at most 8 rows per workgroup (below)
+                if (!src.empty() && (pf <= (int64_t)256 * 16 * 8 * ((N + 15) / 16 * 16) || forced)) {      // at most 8 rows per workgroup (above)
                     c.source = src; c.lp.ok = true; c.lp.G = 256; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
                     c.two_d = true; c.partial_floats = pf;
                 }

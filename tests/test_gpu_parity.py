@@ -197,6 +197,23 @@ def test_many_stream_stack_in_one_launch_equals_layers_one_after_another(monkeyp
         assert nerr(a, b) < OUT_TOL
 
 
+@pytest.mark.parametrize("kind,N", [("elman", 16), ("lstm", 24), ("lstm", 40), ("elman", 64)])
+def test_wide_layers_with_the_two_dimensional_split(monkeypatch, kind, N):
+    """1024-wide recurrent layers at many streams with the matrix-core kernel's two-dimensional
+    split forced for both directions: 4 and 16 rows per workgroup, 1 to 4 stream tiles (3 tiles take
+    the other assignment of tiles to wavefronts), a window computed in two pieces."""
+    from paper_1503_02852_amd.runner import window_for
+    monkeypatch.setenv("RNNG_MSTEP_2D", "1")
+    spec = wl.elman_net(12, 1024, 6) if kind == "elman" else wl.lstm_net(12, [1024], 6)
+    w = wl.make_workload(f"wide_{kind}", spec, T=5, N=N, seed=41, scale=0.05, bias_scale=0.1, masked_fraction=0.2)
+    win, ref = run_both(w, label=f"2-D split, {kind}, N={N}")
+    win2 = window_for(w)
+    win2.forward_range(0, 2); win2.forward_range(2, 5)
+    win2.bptt(); win2.compute_grads()
+    for k in w.spec.output_nodes():
+        assert nerr(win2.node_output(k), ref["y"][k]) < OUT_TOL
+
+
 @pytest.mark.parametrize("local", ["0", "1"])
 def test_exchange_written_through_and_through_the_xcd_cache(monkeypatch, local):
     """Both forms of the exchange inside a group of workgroups (plain stores served by the XCD's
