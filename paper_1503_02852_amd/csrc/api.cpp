@@ -179,9 +179,15 @@ struct rnn_graph {
             if (lay.ok) for (int sidx = 0; sidx < lay.n_sources; ++sidx) polled += (int64_t)N * lay.src[sidx].k_len * 4;
             const bool forced = std::getenv("RNNG_MSTEP_2D") != nullptr;      // = 1: wherever the kernel can run (tests)
             if (polled >= 256 * 1024 || forced) {
+                // row groups of 16 while a workgroup has at most 8 rows; of 4 with more rows, so that
+                // the partial sums a workgroup writes and polls per step stay at N * 64 values
+                const int rows = lay.ph[0].n_tasks * lay.ph[0].cmax;
+                int gj = rows <= 8 ? 16 : 4;
+                if (const char* env = std::getenv("RNNG_MSTEP_2D_GROUP")) gj = std::atoi(env);
                 size_t lds = 0; int64_t pf = 0;
-                std::string src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
-                if (!src.empty() && (pf <= (int64_t)256 * 16 * 8 * ((N + 15) / 16 * 16) || forced)) {      // at most 8 rows per workgroup (above)
+                std::string src = jit_mstep2_source(plan, cp, backward, N, 256, gj, &lds, &pf);
+                if (src.empty() && gj != 16) src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
+                if (!src.empty()) {
                     c.source = src; c.lp.ok = true; c.lp.G = 256; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
                     c.two_d = true; c.partial_floats = pf;
                 }

@@ -477,7 +477,7 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
 std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int GJ, size_t* lds_bytes,
                               int64_t* partial_floats) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
-    if (phases.size() != 1 || N < 1 || N > 64 || G > 256 || GJ != 16 || G % GJ != 0) return "";
+    if (phases.size() != 1 || N < 1 || N > 64 || G > 256 || (GJ != 16 && GJ != 4) || G % GJ != 0) return "";
     StepLayout lay;
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
     if (!lay.ok) return "";
@@ -486,6 +486,11 @@ std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, 
     if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return "";
     const StepPhase& ph = lay.ph[0];
     const int MT = (N + 15) / 16, RT = ph.n_tasks * ph.cmax;
+    {   // the row tiles must divide among the wavefronts (see the kernel)
+        const int RP = RT <= 4 ? 4 : RT <= 8 ? 8 : 16, TT = GJ / (16 / RP);
+        const int WPS = (MT == 1 || MT == 2 || MT == 4) ? 4 / MT : 4;
+        if (TT < 1 || TT % WPS != 0) return "";
+    }
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
