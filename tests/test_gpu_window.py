@@ -62,6 +62,7 @@ WINDOW_NETS = {
     "lstm2_streams": lambda: (wl.lstm_net(10, [24, 20], 5), 3),
     "generalized": lambda: (wl.generalized_net(8, 16, 2, 4), 2),
     "lstm_many_streams": lambda: (wl.lstm_net(8, [32], 4), 20),
+    "lstm2_many_streams": lambda: (wl.lstm_net(8, [32, 24], 4), 18),
 }
 
 
