@@ -113,7 +113,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path would shard over streams with one gradient "
-              "all-reduce per window (DESIGN.md), which is not built. Use --gpus 1.", file=sys.stderr)
+              "all-reduce per window, which is not built. Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
