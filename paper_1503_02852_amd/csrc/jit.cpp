@@ -508,9 +508,16 @@ std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, 
         for (int t = 0; t < ph.n_tasks; ++t) if (ml.blk[s][t] >= 0) blk.push_back({s * STEP_MAX_TASKS + t, ml.blk[s][t]});
     }
     if (pos > 24) return "";      // the chunk sequence is unrolled
+    // register sets: one position in flight while one is multiplied (measured: loads issued
+    // earlier come back with sentinels more often, and the reloads cost more than the overlap gains)
+    const int DS = std::max(1, std::min(pos, 2));
+    std::vector<std::pair<int, int>> psrc, pchunk;
+    for (int s2 = 0, q = 0; s2 < ml.n_src; ++s2)
+        for (int c = 0; c < lay.src[s2].k_len / GJ / 64; ++c, ++q) { psrc.push_back({q, s2}); pchunk.push_back({q, c}); }
+    (void)nchmax;
     o << "struct M2 {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", GJ = " << GJ << ", RT = " << RT
-      << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ", NCHMAX = " << nchmax << ";\n";
-    emit_switch("K", "s", ks, 0); emit_switch("KS", "s", kss, 0); emit_switch("nch", "s", nch, 0); emit_switch("pos0", "s", pos0, 0);
+      << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ", PT = " << pos << ", DS = " << DS << ";\n";
+    emit_switch("K", "s", ks, 0); emit_switch("KS", "s", kss, 0); emit_switch("psrc", "p", psrc, 0); emit_switch("pchunk", "p", pchunk, 0);
     emit_switch("blk_", "key", blk, -1);
     o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n};\n";
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"

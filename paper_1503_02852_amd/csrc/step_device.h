@@ -1534,8 +1534,9 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 //
 // M2 is a generated descriptor:
 //   static constexpr int NJ (streams), MT (16-stream tiles), NSRC, GJ, RT (rows of a member:
-//   tasks * cmax <= 16), CMAX, ACCS, NCHMAX; constexpr K(s), KS(s) (columns of a slice, a multiple
-//   of 64), nch(s) = KS(s) / 64, pos0(s) (chunks of the sources before s), blk(s, task).
+//   tasks * cmax <= 16), CMAX, ACCS, PT (64-column chunks of all sources' slices), DS (register
+//   sets); constexpr K(s), KS(s) (columns of a slice, a multiple of 64), psrc(p) / pchunk(p)
+//   (source and chunk of position p), blk(s, task).
 // =============================================================================================
 struct M2Layout {
     int ok, n_src, cmax, zrow, accbase, accstride, total_floats;
@@ -1713,9 +1714,12 @@ __device__ __forceinline__ void mstep2_kernel_body(const StepArgs& a, M2Shared& 
         const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(a.partial + (long long)t * pframe, 0, (int)(pframe * 4), STEP_RSRC_FLAGS);
 
         // ---- phase 1: this slice's share of the row group's contraction ----
-        // The chunks of all sources form one sequence; chunk p lives in register set p & 1 and
-        // the loads of chunk p + 1 are issued before chunk p is multiplied.
-        muintx4 v[2][4][MTW];
+        // The 64-column chunks of all sources form one sequence of PT positions (generated:
+        // M2::psrc(p), M2::pchunk(p)).  Position p lives in register set p % DS; DS - 1 positions
+        // are in flight: the loads of position p + DS - 1 are issued when position p is checked
+        // (into the set of position p - 1, whose multiplications have been issued).
+        constexpr int PT = M2::PT, DS = M2::DS;
+        muintx4 v[DS][4][MTW];
         auto load_chunk = [&](muintx4 (&dst)[4][MTW], auto ss, int c) {
             constexpr int S = decltype(ss)::value;
 #pragma unroll
@@ -1738,53 +1742,49 @@ __device__ __forceinline__ void mstep2_kernel_body(const StepArgs& a, M2Shared& 
         };
         for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
-        load_chunk(v[0], StepIntC<0>{}, 0);
+        step_static_for<0, DS - 1>([&](auto pp) {
+            constexpr int q = decltype(pp)::value;
+            if constexpr (q < PT) load_chunk(v[q], StepIntC<M2::psrc(q)>{}, M2::pchunk(q));
+        });
         mfloatx4 acc[MTW][TPW];
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
             for (int tau = 0; tau < TPW; ++tau) acc[mt][tau] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
-        step_static_for<0, M2::NSRC>([&](auto ss) {
-            constexpr int sidx = decltype(ss)::value;
-            step_static_for<0, M2::NCHMAX>([&](auto cc) {
-                constexpr int c = decltype(cc)::value;
-                if constexpr (c < M2::nch(sidx)) {
-                    constexpr int set = (M2::pos0(sidx) + c) & 1;
-                    // loads of the next chunk of the sequence into the other set
-                    if constexpr (c + 1 < M2::nch(sidx)) load_chunk(v[set ^ 1], ss, c + 1);
-                    else if constexpr (sidx + 1 < M2::NSRC) load_chunk(v[set ^ 1], StepIntC<(sidx + 1 < M2::NSRC ? sidx + 1 : sidx)>{}, 0);
-                    if (incomplete(v[set]) && !dead) {
-                        retried = true;
-                        muintx4 again[4][MTW];
-                        int spins = 0;
-                        for (;;) {
-                            if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
-                            __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
-                            step_compiler_barrier();
-                            load_chunk(again, ss, c);
-                            if (!incomplete(again)) break;
-                        }
-#pragma unroll
-                        for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                            for (int mt = 0; mt < MTW; ++mt) v[set][kb][mt] = again[kb][mt];
-                    }
-                    if (sidx == 0 && c == 0) { RNNG_STAMP(2); }
-#pragma unroll
-                    for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                        for (int tau = 0; tau < TPW; ++tau) {
-                            const mfloatx4 b = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][tau] + c * 64 + kb * 16]);
-#pragma unroll
-                            for (int mt = 0; mt < MTW; ++mt) {
-                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].x), b[0], acc[mt][tau], 0, 0, 0);
-                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].y), b[1], acc[mt][tau], 0, 0, 0);
-                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].z), b[2], acc[mt][tau], 0, 0, 0);
-                                acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].w), b[3], acc[mt][tau], 0, 0, 0);
-                            }
-                        }
+        step_static_for<0, PT>([&](auto pp) {
+            constexpr int pos = decltype(pp)::value, set = pos % DS, sidx = M2::psrc(pos), c = M2::pchunk(pos);
+            constexpr int q = pos + DS - 1;
+            if constexpr (q < PT) load_chunk(v[q % DS], StepIntC<M2::psrc(q < PT ? q : 0)>{}, M2::pchunk(q < PT ? q : 0));
+            if (incomplete(v[set]) && !dead) {
+                retried = true;
+                muintx4 again[4][MTW];
+                int spins = 0;
+                for (;;) {
+                    if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                    __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
+                    step_compiler_barrier();
+                    load_chunk(again, StepIntC<sidx>{}, c);
+                    if (!incomplete(again)) break;
                 }
-            });
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int mt = 0; mt < MTW; ++mt) v[set][kb][mt] = again[kb][mt];
+            }
+            if (pos == 0) { RNNG_STAMP(2); }
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int tau = 0; tau < TPW; ++tau) {
+                    const mfloatx4 b = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][tau] + c * 64 + kb * 16]);
+#pragma unroll
+                    for (int mt = 0; mt < MTW; ++mt) {
+                        acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].x), b[0], acc[mt][tau], 0, 0, 0);
+                        acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].y), b[1], acc[mt][tau], 0, 0, 0);
+                        acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].z), b[2], acc[mt][tau], 0, 0, 0);
+                        acc[mt][tau] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[set][kb][mt].w), b[3], acc[mt][tau], 0, 0, 0);
+                    }
+                }
         });
         // the partial sums of (member, row, four streams) to their owners, written through
 #pragma unroll
