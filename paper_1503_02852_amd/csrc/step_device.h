@@ -789,8 +789,13 @@ struct GroupX {
     static __device__ __forceinline__ constexpr int pairs_per_thread(int r) { return (NB * MV::RK(r) / 2 + STEP_THREADS - 1) / STEP_THREADS; }
     static __device__ __forceinline__ constexpr int words_per_thread(int r) { return (NB * MV::RK(r) + STEP_THREADS - 1) / STEP_THREADS; }
 };
+// Hold-off of a step's first polling attempt (lengthened when a first attempt fails, shortened
+// slowly otherwise).  Off by default: it removed a bistable slow mode while every exchanged value
+// was written through and stored behind branches, but with the exchange in the XCD's L2 and
+// branch-free stores a failed first attempt is cheap and the hold-off only costs time (measured:
+// speech_n1 2.79 -> 2.66 ms per window without it, stable over repeated runs).
 #if !defined(WAVE_ADAPTIVE_POLL)
-#define WAVE_ADAPTIVE_POLL 1
+#define WAVE_ADAPTIVE_POLL 0
 #endif
 #if !defined(WAVE_POLL_INC)
 #define WAVE_POLL_INC 2
