@@ -783,9 +783,25 @@ __device__ __forceinline__ void wave_ring_fill(const WaveRing<PH, MV, NB>& rg, c
 // hand them to each other through a double-buffered LDS area; one workgroup barrier per step.
 template <class MV, int NB>
 struct GroupX {
-    // LDS: one block [stream][64 * F] per source (bundles are de-interleaved on the way in)
-    static constexpr int FLOATS = NB * 64 * (MV::XF > 0 ? MV::XF : 1);     // one buffer
-    static __device__ __forceinline__ constexpr int off(int s) { return NB * 64 * MV::xoff(s); }
+    // LDS: one block [stream][quad][lane][4] per source (bundles are de-interleaved on the way
+    // in).  Lane l multiplies the F consecutive elements F l ... F l + F - 1 of a vector; they are
+    // kept as quads [f / 4][l][f % 4], so that a wavefront's 128-bit read of one quad covers 1 KiB
+    // of consecutive addresses: no bank conflicts (element-major order has lanes F floats apart,
+    // which for F = 8 makes every fourth lane hit the same banks and the four wavefronts' reads,
+    // 64 KiB per step in charlm_n1's backward loop, take four times as long).
+    static __device__ __forceinline__ constexpr int F4(int s) { return (MV::F(s) + 3) / 4 * 4; }
+    static __device__ __forceinline__ constexpr int off(int s) {
+        int o = 0;
+        for (int i = 0; i < s; ++i) o += NB * 64 * F4(i);
+        return o;
+    }
+    static constexpr int FLOATS = off(MV::NSRC) > 0 ? off(MV::NSRC) : 1;     // one buffer
+    // LDS index of element k of source s, stream n / of value f of lane l
+    static __device__ __forceinline__ int pos(int s, int n, int k) {
+        const int l = k / MV::F(s), f = k - l * MV::F(s);
+        return off(s) + n * 64 * F4(s) + ((f >> 2) * 64 + l) * 4 + (f & 3);
+    }
+    static __device__ __forceinline__ int lane_pos(int s, int n, int l, int f) { return off(s) + n * 64 * F4(s) + ((f >> 2) * 64 + l) * 4 + (f & 3); }
     static __device__ __forceinline__ constexpr int pairs_per_thread(int r) { return (NB * MV::RK(r) / 2 + STEP_THREADS - 1) / STEP_THREADS; }
     static __device__ __forceinline__ constexpr int words_per_thread(int r) { return (NB * MV::RK(r) + STEP_THREADS - 1) / STEP_THREADS; }
 };
@@ -887,16 +903,21 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
                     int n = 0, e = 2 * p;
                     if (NB > 1) { n = e / RK; e -= n * RK; }
                     if (B == 1) {
-                        const sfloatx2 o = {__uint_as_float(v64[r][j].x), __uint_as_float(v64[r][j].y)};
-                        *reinterpret_cast<sfloatx2*>(&xs[GX::off(MV::rsrc(r, 0)) + n * 64 * MV::F(MV::rsrc(r, 0)) + e]) = o;
+                        if (MV::F(MV::rsrc(r, 0)) % 2 == 0) {      // both halves belong to one lane's quad
+                            const sfloatx2 o = {__uint_as_float(v64[r][j].x), __uint_as_float(v64[r][j].y)};
+                            *reinterpret_cast<sfloatx2*>(&xs[GX::pos(MV::rsrc(r, 0), n, e)]) = o;
+                        } else {
+                            xs[GX::pos(MV::rsrc(r, 0), n, e)] = __uint_as_float(v64[r][j].x);
+                            xs[GX::pos(MV::rsrc(r, 0), n, e + 1)] = __uint_as_float(v64[r][j].y);
+                        }
                     } else {
                         // e = k * B + m with m even: members m and m + 1 of unit k
                         const int k = e / B, m = e - k * B;
 #pragma unroll
                         for (int mm = 0; mm < 4; mm += 2) {
                             if (mm < B && m == mm) {
-                                if (MV::rsrc(r, mm) >= 0) xs[GX::off(MV::rsrc(r, mm) >= 0 ? MV::rsrc(r, mm) : 0) + n * 64 * MV::F(MV::rsrc(r, mm) >= 0 ? MV::rsrc(r, mm) : 0) + k] = __uint_as_float(v64[r][j].x);
-                                if (MV::rsrc(r, mm + 1) >= 0) xs[GX::off(MV::rsrc(r, mm + 1) >= 0 ? MV::rsrc(r, mm + 1) : 0) + n * 64 * MV::F(MV::rsrc(r, mm + 1) >= 0 ? MV::rsrc(r, mm + 1) : 0) + k] = __uint_as_float(v64[r][j].y);
+                                if (MV::rsrc(r, mm) >= 0) xs[GX::pos(MV::rsrc(r, mm) >= 0 ? MV::rsrc(r, mm) : 0, n, k)] = __uint_as_float(v64[r][j].x);
+                                if (MV::rsrc(r, mm + 1) >= 0) xs[GX::pos(MV::rsrc(r, mm + 1) >= 0 ? MV::rsrc(r, mm + 1) : 0, n, k)] = __uint_as_float(v64[r][j].y);
                             }
                         }
                     }
@@ -910,7 +931,7 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
                 if (j < GX::words_per_thread(r) && p < total) {
                     int n = 0, k = p;
                     if (NB > 1) { n = k / RK; k -= n * RK; }
-                    xs[GX::off(MV::rsrc(r, 0)) + n * 64 * MV::F(MV::rsrc(r, 0)) + k] = __uint_as_float(v32[r][j]);      // odd widths are never bundled
+                    xs[GX::pos(MV::rsrc(r, 0), n, k)] = __uint_as_float(v32[r][j]);      // odd widths are never bundled
                 }
             }
         }
@@ -1065,7 +1086,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
             for (int n = 0; n < NB; ++n)
 #pragma unroll
                 for (int f = 0; f < WAVE_FMAX; ++f)
-                    if (f < MV::F(sidx)) xr[n][MV::xoff(sidx) + f] = xs[GX::off(sidx) + n * 64 * MV::F(sidx) + MV::F(sidx) * lane + f];
+                    if (f < MV::F(sidx)) xr[n][MV::xoff(sidx) + f] = xs[GX::lane_pos(sidx, n, lane, f)];
     } else if (!has_units) {
         return;
     }
