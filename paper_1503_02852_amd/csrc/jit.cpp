@@ -252,9 +252,15 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         xmode.push_back({q, reader_mode(st0[q * ST_WORDS + ST_BUF])});
     }
     for (size_t b = 0; b < bstores.size(); ++b) bs_xmode.push_back({(int)b, reader_mode(P.bundles[bstores[b].bundle].ebuf)});
+    // When every wavefront owns units (one loop, no helper path), a step's first polling attempt
+    // can go out at the end of the step before.  Measured: faster with 16 units per workgroup
+    // (charlm_n1 2.45 -> 2.38 ms per window, lm_elman_n1 6.40 -> 6.33), slower with 8 (speech_n1
+    // 2.545 -> 2.577) and with helper wavefronts (tiny).  RNNG_WAVE_POLL_EARLY = 0 / 1 overrides.
+    bool poll_early = 3 * UW < ph.item_chunk && UW >= 4;
+    if (const char* env = std::getenv("RNNG_WAVE_POLL_EARLY")) poll_early = std::atoi(env) != 0;
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
       << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ", NREG = " << regs.size()
-      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ";\n";
+      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ", PE = " << (poll_early ? 1 : 0) << ";\n";
     std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
     for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});
     for (int t = 0; t < ph.n_tasks; ++t) {
@@ -312,7 +318,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    wave_prologue<MV, " << NB << ">(a, sh);\n"
          "    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n"
          "    // same in all lanes; false: the wavefront only helps polling\n"
-         "    const bool has_units = MV::NSRC == 0 ? suni((int)(wave * MV::UW < sh.lay.ph[0].item_chunk)) != 0 : wave * MV::UW < sh.lay.ph[0].item_chunk;\n"
+         "    const bool has_units = suni((int)(wave * MV::UW < sh.lay.ph[0].item_chunk)) != 0;\n"
          "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
          "    float* ring = ring_all[wave];\n"
          "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", 1>(r0, a, sh, nullptr, w, tid);\n"
@@ -326,21 +332,24 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    __syncthreads();\n"
          "    float dfv[PH0::NST > 0 ? PH0::NST : 1] = {0.0f};\n"
          "    bool dead = false;\n"
-         "    int pdelay = 0;\n"
          "    const int nsteps = step_count(a);\n"
+         "    if (nsteps > 0) wave_carry_init<PH0>(r0, a);\n"
+         "    PollRegs<MV> pr;\n"
+         "    if (MV::NSRC > 0 && nsteps > 0 && MV::PE) group_poll_issue<MV, " << NB << ">(pr, wv, a, step_frame(a, 0), tid);\n"
          "    auto loop = [&](auto hu) {\n"
          "        constexpr int HU = decltype(hu)::value;\n"
          "        int step = 0;\n"
          "        for (; step + 1 < nsteps; step += 2) {\n"
-         "            wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
-         "            wave_step<PH0, MV, " << NB << ", 1, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead, pdelay);\n"
+         "            wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, pr, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
+         "            wave_step<PH0, MV, " << NB << ", 1, HU>(r0, wv, rg, pf, dfv, pr, a, ring, xs_all, has_units, step + 1, step_frame(a, step + 1), tid, dead);\n"
          "        }\n"
-         "        if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead, pdelay);\n"
+         "        if (step < nsteps) wave_step<PH0, MV, " << NB << ", 0, HU>(r0, wv, rg, pf, dfv, pr, a, ring, xs_all, has_units, step, step_frame(a, step), tid, dead);\n"
          "        const bool owns = HU == 2 ? has_units : HU != 0;\n"
          "        if (!MV::EARLY && owns && nsteps > 0) wave_flush_stores<PH0, MV>(r0, dfv, a);\n"
          "        if (wave_has_late_stores<MV>() && owns && nsteps > 0) wave_store_through_late<PH0, MV>(r0, wv, dfv, a, step_frame(a, nsteps - 1), MV::EARLY != 0);\n"
          "    };\n"
-         "    if (MV::NSRC > 0) loop(StepIntC<2>{});\n"
+         "    // every wavefront owns units: one loop without the helper's path\n"
+         "    if (MV::NSRC > 0 && !(3 * MV::UW < " << ph.item_chunk << ")) loop(StepIntC<2>{});\n"
          "    else if (has_units) loop(StepIntC<1>{});\n"
          "    else if (MV::NSRC > 0) loop(StepIntC<0>{});\n"
          "}\n}  // namespace " << ns << "\n";
@@ -588,12 +597,15 @@ bool jit_compile(const std::string& source, std::string* log_out) {
                                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
     std::string minc_opt;
     if (const char* env = std::getenv("RNNG_MSTEP_POLL_INC")) { minc_opt = "-DMSTEP_POLL_INC=" + std::to_string(std::atoi(env)); opts.push_back(minc_opt.c_str()); }
-    std::string inc_opt, dec_opt;
-    if (const char* env = std::getenv("RNNG_WAVE_POLL_INC")) { inc_opt = "-DWAVE_POLL_INC=" + std::to_string(std::atoi(env)); opts.push_back(inc_opt.c_str()); }
-    if (const char* env = std::getenv("RNNG_WAVE_POLL_DEC_MASK")) { dec_opt = "-DWAVE_POLL_DEC_MASK=" + std::to_string(std::atoi(env)); opts.push_back(dec_opt.c_str()); }
-    std::string adapt_opt;
-    if (const char* env = std::getenv("RNNG_WAVE_ADAPTIVE")) { adapt_opt = "-DWAVE_ADAPTIVE_POLL=" + std::to_string(std::atoi(env)); opts.push_back(adapt_opt.c_str()); }
     std::string wsleep_opt;
+    // tuning aid: further -D options for the run-time build, separated by blanks
+    std::vector<std::string> extra_defs;
+    if (const char* env = std::getenv("RNNG_JIT_DEFINES")) {
+        std::istringstream in(env);
+        for (std::string d; in >> d;)
+            if (d.rfind("-D", 0) == 0) extra_defs.push_back(d);
+    }
+    for (const std::string& d : extra_defs) opts.push_back(d.c_str());
     if (const char* env = std::getenv("RNNG_WAVE_SLEEP")) { wsleep_opt = "-DWAVE_RETRY_SLEEP=" + std::to_string(std::atoi(env)); opts.push_back(wsleep_opt.c_str()); }
     std::string sleep_opt;
     if (const char* env = std::getenv("RNNG_MSTEP_SLEEP")) { sleep_opt = "-DMSTEP_RETRY_SLEEP=" + std::to_string(std::atoi(env)); opts.push_back(sleep_opt.c_str()); }

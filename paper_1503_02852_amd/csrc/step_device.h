@@ -730,22 +730,15 @@ __device__ __forceinline__ void wave_ring_load(float (&v)[QNA],
     typedef WaveRing<PH, MV, NB> RG;
 #pragma unroll
     for (int q = 0; q < RG::QN; ++q) {
-        if (MV::NSRC == 0) {
-            // kernels without exchange: no branch around the load (the compiler could not count
-            // the loads and stores in flight across one); steps past the end and frames outside
-            // the window read a clamped frame, and wave_ring_store replaces what that gave by
-            // zero: the loaded value is not touched before, so nothing waits for it here
-            const int stc = st < step_count(a) ? st : step_count(a) - 1;
-            const int frame = step_frame(a, stc) + rg.poff[q];
-            const int fc = frame < 0 ? 0 : (frame >= a.T ? a.T - 1 : frame);
-            v[q] = rg.pbase[q][fc * rg.pstride[q]];
-        } else {
-            v[q] = 0.0f;
-            if (rg.pstride[q] != 0 && st < step_count(a)) {
-                const int frame = step_frame(a, st) + rg.poff[q];
-                if (frame >= 0 && frame < a.T) v[q] = rg.pbase[q][frame * rg.pstride[q]];
-            }
-        }
+        // no branch around the load (the compiler could not count the loads and stores in flight
+        // across one and would wait for all of them, the written-through stores included); steps
+        // past the end and frames outside the window read a clamped frame, and wave_ring_store
+        // replaces what that gave by zero: the loaded value is not touched before, so nothing
+        // waits for it here
+        const int stc = st < step_count(a) ? st : step_count(a) - 1;
+        const int frame = step_frame(a, stc) + rg.poff[q];
+        const int fc = frame < 0 ? 0 : (frame >= a.T ? a.T - 1 : frame);
+        v[q] = rg.pbase[q][fc * rg.pstride[q]];
     }
 }
 template <class PH, class MV, int NB, int QNA>
@@ -754,12 +747,11 @@ __device__ __forceinline__ void wave_ring_store(const float (&v)[QNA], const Wav
     typedef WaveRing<PH, MV, NB> RG;
 #pragma unroll
     for (int q = 0; q < RG::QN; ++q) {
-        float x = v[q];
-        if (MV::NSRC == 0) {
-            const int stc = st < step_count(a) ? st : step_count(a) - 1;
-            const int frame = step_frame(a, stc) + rg.poff[q];
-            x = (frame >= 0 && frame < a.T) ? x : 0.0f;
-        }
+        const int stc = st < step_count(a) ? st : step_count(a) - 1;
+        const int frame = step_frame(a, stc) + rg.poff[q];
+        // (lanes without a unit hold a word nobody reads; kernels with exchange zero it all the same)
+        const bool valid = frame >= 0 && frame < a.T && (MV::NSRC == 0 || (rg.pstride[q] != 0 && st < step_count(a)));
+        const float x = valid ? v[q] : 0.0f;
         if (q * 64 + lane < RG::PAIRS) ring[(st & (WAVE_RING_STEPS - 1)) * RG::PAIRS + q * 64 + lane] = x;
     }
     // other lanes of this wavefront read these values in later steps
@@ -805,63 +797,55 @@ struct GroupX {
     static __device__ __forceinline__ constexpr int pairs_per_thread(int r) { return (NB * MV::RK(r) / 2 + STEP_THREADS - 1) / STEP_THREADS; }
     static __device__ __forceinline__ constexpr int words_per_thread(int r) { return (NB * MV::RK(r) + STEP_THREADS - 1) / STEP_THREADS; }
 };
-// Hold-off of a step's first polling attempt (lengthened when a first attempt fails, shortened
-// slowly otherwise).  Off by default: it removed a bistable slow mode while every exchanged value
-// was written through and stored behind branches, but with the exchange in the XCD's L2 and
-// branch-free stores a failed first attempt is cheap and the hold-off only costs time (measured:
-// speech_n1 2.79 -> 2.66 ms per window without it, stable over repeated runs).
-#if !defined(WAVE_ADAPTIVE_POLL)
-#define WAVE_ADAPTIVE_POLL 0
-#endif
-#if !defined(WAVE_POLL_INC)
-#define WAVE_POLL_INC 2
-#endif
-#if !defined(WAVE_POLL_DEC_MASK)
-#define WAVE_POLL_DEC_MASK 63
-#endif
 #if !defined(WAVE_RETRY_SLEEP)
 #define WAVE_RETRY_SLEEP 0      // units of 64 clocks between polling attempts
 #endif
 constexpr int GROUP_MAX_LOADS = 8;   // per thread and region (N * K <= 2048 elements when K is odd, 4096 when even)
 
-template <class MV, int NB>
-__device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, int& pdelay) {
-    typedef GroupX<MV, NB> GX;
+// The registers a step's polling loads land in.  A step's first attempt is issued at the end of
+// the step before (right behind that step's stores), so they live across steps.
+template <class MV>
+struct PollRegs {
     suintx2 v64[MV::NREG > 0 ? MV::NREG : 1][GROUP_MAX_LOADS];
     unsigned v32[MV::NREG > 0 ? MV::NREG : 1][GROUP_MAX_LOADS];
-    // One buffer descriptor per source; a frame outside the window gets an empty one.  Loads
-    // beyond a descriptor's size return zero, so no load needs a branch around it.
-    __amdgpu_buffer_rsrc_t rs[MV::NREG > 0 ? MV::NREG : 1];
+};
+
+// One polling attempt for frame t: all loads are issued back to back (device-coherent buffer
+// loads; atomic loads would each be followed by a wait).  One buffer descriptor per source; a
+// frame outside the window gets an empty one.  Loads beyond a descriptor's size return zero, so no
+// load needs a branch around it.
+template <class MV, int NB>
+__device__ __forceinline__ void group_poll_issue(PollRegs<MV>& pr, const WaveRegs<MV>& wv, const StepArgs& a, int t, int tid) {
+    typedef GroupX<MV, NB> GX;
+    step_compiler_barrier();
 #pragma unroll
     for (int s = 0; s < MV::NREG; ++s) {
         const int frame = t + wv.xfoff[s];
         const bool in_window = frame >= 0 && frame < a.T;
         const float* g = wv.xsrc[s] + (in_window ? frame : 0) * wv.xstride[s];
-        rs[s] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? a.N * MV::RK(s) * 4 : 0, STEP_RSRC_FLAGS);
-    }
-    // A first attempt that comes back with a sentinel costs a whole extra round trip, so the
-    // first attempt is held back until the data is usually there: the hold-off grows when a
-    // first attempt fails and shrinks slowly while they succeed.
-#if WAVE_ADAPTIVE_POLL
-    for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
-#endif
-    int spins = 0;
-    for (;;) {
-        // all loads of an attempt are issued back to back (device-coherent buffer loads; atomic
-        // loads would each be followed by a wait), then checked
-        step_compiler_barrier();
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? a.N * MV::RK(s) * 4 : 0, STEP_RSRC_FLAGS);
+        if ((MV::RK(s) & 1) == 0) {
 #pragma unroll
-        for (int s = 0; s < MV::NREG; ++s) {
-            if ((MV::RK(s) & 1) == 0) {
+            for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                if (j < GX::pairs_per_thread(s)) pr.v64[s][j] = __builtin_amdgcn_raw_buffer_load_b64(rs, (tid + STEP_THREADS * j) * 8, 0, STEP_COHERENT_AUX);
+        } else {
 #pragma unroll
-                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
-                    if (j < GX::pairs_per_thread(s)) v64[s][j] = __builtin_amdgcn_raw_buffer_load_b64(rs[s], (tid + STEP_THREADS * j) * 8, 0, STEP_COHERENT_AUX);
-            } else {
-#pragma unroll
-                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
-                    if (j < GX::words_per_thread(s)) v32[s][j] = __builtin_amdgcn_raw_buffer_load_b32(rs[s], (tid + STEP_THREADS * j) * 4, 0, STEP_COHERENT_AUX);
-            }
+            for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                if (j < GX::words_per_thread(s)) pr.v32[s][j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (tid + STEP_THREADS * j) * 4, 0, STEP_COHERENT_AUX);
         }
+    }
+    step_compiler_barrier();
+}
+
+// Completes the polling of frame t, whose first attempt is already under way: the step's work
+// that does not need the polled vectors (mid) runs under it, then the loads are checked and
+// repeated until none holds a sentinel, and the vectors go to LDS.
+template <class MV, int NB, class Mid>
+__device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, Mid&& mid) {
+    typedef GroupX<MV, NB> GX;
+    auto& v64 = pr.v64;
+    auto& v32 = pr.v32;
+    auto all_ok = [&]() {
         bool ok = true;
 #pragma unroll
         for (int s = 0; s < MV::NREG; ++s) {
@@ -875,14 +859,17 @@ __device__ __forceinline__ void group_poll(float* xs, const WaveRegs<MV>& wv, co
                     if (j < GX::words_per_thread(s)) ok = ok && v32[s][j] != STEP_SENTINEL;
             }
         }
+        return ok;
+    };
+    mid();
+    int spins = 0;
+    for (;;) {
+        const bool ok = all_ok();
         if (ok || dead) break;
         if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
         __builtin_amdgcn_s_sleep(WAVE_RETRY_SLEEP);
+        group_poll_issue<MV, NB>(pr, wv, a, t, tid);
     }
-#if WAVE_ADAPTIVE_POLL
-    if (__builtin_amdgcn_ballot_w64(spins > 0) != 0) pdelay = pdelay + WAVE_POLL_INC < 48 ? pdelay + WAVE_POLL_INC : 48;
-    else if ((step & WAVE_POLL_DEC_MASK) == WAVE_POLL_DEC_MASK && pdelay > 0) --pdelay;
-#endif
 #if defined(RNNG_STEP_TRACE)
     const int trace_step = a.backward ? a.t_end - 1 - t : t - a.t_begin;
     if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= RNNG_STEP_TRACE_AT && trace_step < RNNG_STEP_TRACE_AT + 8) {
@@ -1033,11 +1020,25 @@ __device__ __forceinline__ constexpr bool wave_has_late_stores() {
 // which (0 / 1 give the unit-owning wavefronts a loop without a branch the compiler cannot see
 // through: behind such a branch it cannot count the loads and stores in flight and waits for all
 // of them).
+// Register-carried values of a call's first step: the previous frame's, if the window has one
+// (before the time loop, so that no step has a load behind a branch).
+template <class PH>
+__device__ __forceinline__ void wave_carry_init(PhaseRegs<PH>& r, const StepArgs& a) {
+    const int t = step_frame(a, 0);
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g) {
+        if (PH::gkind(g) == GA_KIND_CARRY) {
+            const int frame = t + r.goff[g];
+            r.carry[PH::cidx(g)] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+        }
+    }
+}
+
 template <class PH, class MV, int NB, int PAR, int HU, int QNA, int NSTA>
 __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& wv, const WaveRing<PH, MV, NB>& rg,
-                                          float (&pf)[2][QNA], float (&dfv)[NSTA],
+                                          float (&pf)[2][QNA], float (&dfv)[NSTA], PollRegs<MV>& pr,
                                           const StepArgs& a, float* ring, float* xs_all, bool has_units_rt, int step, int t, int tid,
-                                          bool& dead, int& pdelay) {
+                                          bool& dead) {
     const bool has_units = HU == 2 ? has_units_rt : HU != 0;
     typedef WaveRing<PH, MV, NB> RG;
     typedef GroupX<MV, NB> GX;
@@ -1045,41 +1046,43 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     float s[MAX_SLOTS];
     RNNG_STAMP(0);
     const int js = step & (WAVE_RING_STEPS - 1);
-    // the row loaded two steps ago (for step - 2 + WAVE_RING_STEPS) goes into the ring now
-    if (PH::NS > 0 && has_units && step > 1) wave_ring_store<PH, MV, NB, QNA>(pf[PAR], rg, a, ring, step - 2 + WAVE_RING_STEPS, lane);
     const int ul_l = lane % MV::UW, n_l = lane / MV::UW;
+    auto gathers = [&]() {
+        // the row loaded two steps ago (for step - 2 + WAVE_RING_STEPS) goes into the ring now
+        if (PH::NS > 0 && has_units && step > 1) wave_ring_store<PH, MV, NB, QNA>(pf[PAR], rg, a, ring, step - 2 + WAVE_RING_STEPS, lane);
 #pragma unroll
-    for (int g = 0; g < PH::NG; ++g) {
-        if (PH::gkind(g) == GA_KIND_CARRY) {
-            if (step > 0) {
-                s[g] = r.carry[PH::cidx(g)];
-            } else {      // first step of this call: the previous frame's value, if the window has one
+        for (int g = 0; g < PH::NG; ++g) {
+            if (PH::gkind(g) == GA_KIND_CARRY) {
+                s[g] = r.carry[PH::cidx(g)];      // the first step's: wave_carry_init
+            } else if (PH::gkind(g) == GA_KIND_STATIC) {
+                // idle lanes read a valid (unused) ring entry instead of branching around the load
+                const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
+                s[g] = ring[js * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
+            } else if (PH::gkind(g) == GA_KIND_FRAMES) {
                 const int frame = t + r.goff[g];
-                s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+                float v = 0.0f;
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                s[g] = v;
             }
-        } else if (PH::gkind(g) == GA_KIND_STATIC) {
-            // idle lanes read a valid (unused) ring entry instead of branching around the load
-            const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
-            s[g] = ring[js * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
-        } else if (PH::gkind(g) == GA_KIND_FRAMES) {
-            const int frame = t + r.goff[g];
-            float v = 0.0f;
-            if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
-            s[g] = v;
         }
-    }
 #pragma unroll
-    for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
-    RNNG_STAMP(1);
+        for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+    };
     float xr[NB][MV::XF > 0 ? MV::XF : 1];
+    if (MV::NSRC == 0) gathers();
+    RNNG_STAMP(1);
     if (MV::NSRC > 0) {
         float* xs = xs_all + PAR * GX::FLOATS;
-        group_poll<MV, NB>(xs, wv, a, step, t, tid, dead, pdelay);
+        if (!MV::PE) group_poll_issue<MV, NB>(pr, wv, a, t, tid);
+        group_poll<MV, NB>(pr, xs, wv, a, step, t, tid, dead, gathers);
         step_lds_barrier();
 #if defined(RNNG_STEP_TRACE)
         if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= RNNG_STEP_TRACE_AT && step < RNNG_STEP_TRACE_AT + 8) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - RNNG_STEP_TRACE_AT)] = clock64();
 #endif
-        if (!has_units) return;
+        if (!has_units) {
+            if (MV::PE) group_poll_issue<MV, NB>(pr, wv, a, step_frame(a, step + 1), tid);
+            return;
+        }
 #pragma unroll
         for (int sidx = 0; sidx < MV::NSRC; ++sidx)
 #pragma unroll
@@ -1168,6 +1171,10 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
         if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+    // PE: the next step's first polling attempt goes out right behind this step's stores (after
+    // the launch's last step it polls a frame nobody waits for, or none: nothing checks what it
+    // returns); otherwise at the start of the next step
+    if (MV::NSRC > 0 && MV::PE) group_poll_issue<MV, NB>(pr, wv, a, step_frame(a, step + 1), tid);
     RNNG_STAMP(5);
     RNNG_STAMP(6);
     RNNG_STAMP(7);
