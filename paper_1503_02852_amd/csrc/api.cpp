@@ -144,7 +144,7 @@ struct rnn_graph {
     int force_step_G = 0;
     bool use_jit = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source; bool two_d = false; int64_t partial_floats = 0; };
+    struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
     std::map<long long, JitChoice> jit_choices;
     const JitChoice& jit_choice(int comp, bool backward, int N) {
@@ -239,7 +239,7 @@ struct rnn_graph {
     // Chains of recurrent components run side by side in one launch: all members in the
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
     // workgroups shared among the members).
-    struct ChainChoice { std::string source; std::vector<int> G, J; bool mstep = false; size_t lds_bytes = 0; };
+    struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false; size_t lds_bytes = 0; };
     std::map<long long, ChainChoice> chain_choices;
     bool use_chains = true;
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
@@ -402,6 +402,28 @@ bool wave_tensor_sizes_ok(const rnn_graph* g) {
     return (int64_t)g->T * g->N * maxdim * 4 < (int64_t(1) << 30);
 }
 
+// The wave-autonomous kernels can store through ONE buffer descriptor when everything they store
+// lies in a window of at most 2 GiB: the workspace, if it is that small and holds every tensor
+// but the caller's inputs (which no step kernel stores).  The kernel variant is the same source
+// behind one definition.
+bool wave_store_window_ok(const rnn_graph* g) {
+    if (g->layout.total > (int64_t(1) << 31)) return false;
+    for (int b = 0; b < g->plan.n_bufs; ++b) {
+        bool is_input = false;
+        for (int k : g->plan.input_nodes) is_input = is_input || g->plan.ybuf(k) == b;
+        if (is_input) continue;
+        const char* p = reinterpret_cast<const char*>(g->buf(b));
+        if (p == nullptr) continue;      // no storage: never stored
+        const int64_t bytes = (int64_t)g->T * g->N * g->plan.buf_dim[b] * 4;
+        if (p < g->ws || p + bytes > g->ws + g->layout.total) return false;
+    }
+    return true;
+}
+const std::string& windowed(const std::string& source, std::string& cache) {
+    if (cache.empty()) cache = "#define RNNG_STORE_WINDOW 1\n" + source;
+    return cache;
+}
+
 // Sentinel prefill of the tensors that workgroups poll during frames [t0, t1).  The wave-autonomous
 // kernel polls the interleaved bundle tensors instead of bundled members; the members are filled as
 // well, so that a fall-back to another kernel build finds them prepared.
@@ -441,7 +463,7 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
     // the run-time compiler is unavailable; stepping with per-frame launches is the last resort.
     StepLaunchPlan lp;
     const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
-    const rnn_graph::JitChoice* jc = g->use_jit ? &g->jit_choice(comp, backward, N) : nullptr;
+    rnn_graph::JitChoice* jc = g->use_jit ? const_cast<rnn_graph::JitChoice*>(&g->jit_choice(comp, backward, N)) : nullptr;
     const bool have_jit = jc && !jc->source.empty() && !g->framewise && (!jc->wave || wave_tensor_sizes_ok(g));
     const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
     if (have_jit || have_interp) {
@@ -450,9 +472,11 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
         const int spin_limit = 1 << 22;
         hipError_t e = hipErrorUnknown;
         if (have_jit) {
-            if (hipFunction_t fn = jit_step_function(jc->source)) {
+            const bool window = jc->wave && wave_store_window_ok(g);
+            if (hipFunction_t fn = jit_step_function(window ? windowed(jc->source, jc->source_window) : jc->source)) {
                 StepArgs a;
                 fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
+                if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
                 a.J = jc->J;
                 if (jc->two_d) {
                     if (g->layout.partial_off < 0) return hipErrorInvalidValue;
@@ -497,9 +521,10 @@ hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int 
 // chain (the caller then runs the members one after another).
 hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0, int t1) {
     const ChainPlan& ch = g->plan.chains[chain];
-    const rnn_graph::ChainChoice& cc = g->chain_choice(chain, backward, g->N);
+    rnn_graph::ChainChoice& cc = const_cast<rnn_graph::ChainChoice&>(g->chain_choice(chain, backward, g->N));
     if (cc.source.empty() || (!cc.mstep && !wave_tensor_sizes_ok(g))) return hipErrorNotSupported;
-    hipFunction_t fn = jit_step_function(cc.source);
+    const bool window = !cc.mstep && wave_store_window_ok(g);
+    hipFunction_t fn = jit_step_function(window ? windowed(cc.source, cc.source_window) : cc.source);
     if (!fn) return hipErrorNotSupported;
     const PlanView pv = g->view();
     const int T = g->T, N = g->N;
@@ -516,6 +541,7 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int 
     StepArgs a;
     fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
                    T, N, backward, 1 << 22, t0, t1);
+    if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
     a.n_groups = (int)ch.members.size();
     for (int i = 0; i < a.n_groups; ++i) {
         a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;

@@ -260,7 +260,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     if (const char* env = std::getenv("RNNG_WAVE_POLL_EARLY")) poll_early = std::atoi(env) != 0;
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
       << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ", NREG = " << regs.size()
-      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ", PE = " << (poll_early ? 1 : 0) << ";\n";
+      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ", PE = " << (poll_early ? 1 : 0) << ", SW = RNNG_STORE_WINDOW;\n";
     std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
     for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});
     for (int t = 0; t < ph.n_tasks; ++t) {
@@ -322,7 +322,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
          "    for (int i = tid; i < 2 * GroupX<MV, " << NB << ">::FLOATS; i += 256) xs_all[i] = 0.0f;\n"
          "    float* ring = ring_all[wave];\n"
          "    PhaseRegs<PH0> r0; phase_setup<PH0, " << NB << ", 1>(r0, a, sh, nullptr, w, tid);\n"
-         "    wave_store_setup<PH0>(r0, a);\n"
+         "    wave_store_setup<PH0, MV>(r0, a);\n"
          "    WaveRegs<MV> wv; wave_setup<MV>(wv, a, sh, w, tid);\n"
          "    wave_bundle_setup<PH0, MV>(wv, r0, a);\n"
          "    wave_xcd_setup<MV>(wv, a, " << group << ");\n"

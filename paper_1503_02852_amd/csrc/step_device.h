@@ -640,23 +640,39 @@ __device__ __forceinline__ void wave_setup(WaveRegs<MV>& wv, const StepArgs& a, 
     }
 }
 
+// 1: the wave-autonomous kernels are built for one store window (the launcher puts the definition
+// in front of the generated source when the workspace fits)
+#if !defined(RNNG_STORE_WINDOW)
+#define RNNG_STORE_WINDOW 0
+#endif
 constexpr unsigned WAVE_NO_STORE = 0xC0000000u;       // +- 1 GiB stays outside a tensor below 1 GiB
 
-template <class PH>
+// MV::SW: every stored tensor lies in one window of at most 2 GiB (the host checks it: the
+// workspace), and all stores go through ONE descriptor over that window instead of one per
+// tensor, which frees four scalar registers per stored tensor (with ten stored tensors the
+// descriptors alone pushed the time loop into scalar spills, ~50 v_readlane per step).  Parked
+// lanes stay outside: WAVE_NO_STORE +- 1 GiB is beyond 2 GiB.
+template <class PH, class MV>
 __device__ __forceinline__ void wave_store_setup(PhaseRegs<PH>& r, const StepArgs& a) {
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q) {
         r.sdelta[q] = a.backward ? -r.sstride[q] : r.sstride[q];
-        r.svrun[q] = r.sptr[q] != nullptr ? (unsigned)(((int)(r.sptr[q] - r.sbase[q]) + step_frame(a, 0) * r.sstride[q]) * 4) : WAVE_NO_STORE;
+        const float* base = MV::SW ? a.store_base : r.sbase[q];
+        r.svrun[q] = r.sptr[q] != nullptr ? (unsigned)(((int)(r.sptr[q] - base) + step_frame(a, 0) * r.sstride[q]) * 4) : WAVE_NO_STORE;
     }
+}
+template <class PH, class MV>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t wave_store_rsrc(const PhaseRegs<PH>& r, int q, const StepArgs& a) {
+    if (MV::SW) return __builtin_amdgcn_make_buffer_rsrc(a.store_base, 0, (int)a.store_bytes, STEP_RSRC_FLAGS);
+    return __builtin_amdgcn_make_buffer_rsrc(r.sbase[q], 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
 }
 
 // One value per lane into the current frame of stored tensor q.  mode 0: not exchanged, 1:
 // exchanged, plain store, 2: exchanged, written through; back: the previous step's frame (the
 // running offsets have moved on by one step already).
-template <class PH>
+template <class PH, class MV>
 __device__ __forceinline__ void wave_store(const PhaseRegs<PH>& r, int q, float v, int mode, const StepArgs& a, bool back = false) {
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(r.sbase[q], 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rs = wave_store_rsrc<PH, MV>(r, q, a);
     const int off = (int)(back ? r.svrun[q] - (unsigned)(r.sdelta[q] * 4) : r.svrun[q]);
     if (mode == 2) __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(v), rs, off, 0, STEP_COHERENT_AUX);
     else if (mode == 1) __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(v), rs, off, 0, 0);
@@ -678,7 +694,8 @@ __device__ __forceinline__ void wave_bundle_setup(WaveRegs<MV>& wv, const PhaseR
         wv.bstride[bs] = a.N * MV::bs_dim(bs) * MV::bs_B(bs);
         const int q0 = MV::bs_q(bs, 0);       // member 0 always exists
         const float* mbase = ((cbufs_t)a.buf_ptr)[MV::bs_member0(bs)];
-        wv.bvoff[bs] = r.sptr[q0] != nullptr ? (unsigned)((int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4) : WAVE_NO_STORE;
+        wv.bvoff[bs] = r.sptr[q0] != nullptr ? (unsigned)((int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4) + (MV::SW ? (unsigned)((wv.bbase[bs] - a.store_base) * 4) : 0u)
+                                             : WAVE_NO_STORE;
     }
 }
 
@@ -967,13 +984,14 @@ template <class PH, class MV, int NSTA>
 __device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA], const StepArgs& a) {
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if (!PH::stshared(q) || MV::bundled(q)) wave_store<PH>(r, q, dfv[q], 0, a);
+        if (!PH::stshared(q) || MV::bundled(q)) wave_store<PH, MV>(r, q, dfv[q], 0, a);
 }
 
 // One vector per lane into frame t of bundle bs (descriptor over the whole interleaved tensor).
 template <class MV>
 __device__ __forceinline__ void wave_bundle_store(const WaveRegs<MV>& wv, int bs, const StepArgs& a, int t, const unsigned (&vb)[4], bool through) {
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(wv.bbase[bs], 0, a.T * wv.bstride[bs] * 4, STEP_RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rs = MV::SW ? __builtin_amdgcn_make_buffer_rsrc(a.store_base, 0, (int)a.store_bytes, STEP_RSRC_FLAGS)
+                                             : __builtin_amdgcn_make_buffer_rsrc(wv.bbase[bs], 0, a.T * wv.bstride[bs] * 4, STEP_RSRC_FLAGS);
     const int off = (int)(wv.bvoff[bs] + (unsigned)(t * wv.bstride[bs] * 4));
     if (MV::bs_B(bs) == 4) {
         const muintx4 v4 = {vb[0], vb[1], vb[2], vb[3]};
@@ -995,7 +1013,7 @@ __device__ __forceinline__ void wave_store_through_late(const PhaseRegs<PH>& r, 
     if (!wv.local) return;      // they were written through at once
 #pragma unroll
     for (int q = 0; q < PH::NST; ++q)
-        if (PH::stshared(q) && !MV::bundled(q) && MV::xmode(q) == 2) wave_store<PH>(r, q, dfv[q], 2, a, advanced);
+        if (PH::stshared(q) && !MV::bundled(q) && MV::xmode(q) == 2) wave_store<PH, MV>(r, q, dfv[q], 2, a, advanced);
 #pragma unroll
     for (int bs = 0; bs < MV::NBS; ++bs) {
         if (MV::bs_xmode(bs) != 2) continue;
@@ -1149,7 +1167,7 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
     for (int q = 0; q < PH::NST; ++q) {
         if (PH::stshared(q) && !MV::bundled(q)) {
             const bool through = MV::xmode(q) == 1 || !wv.local;
-            wave_store<PH>(r, q, s[PH::stslot(q)], through ? 2 : 1, a);
+            wave_store<PH, MV>(r, q, s[PH::stslot(q)], through ? 2 : 1, a);
             if (MV::xmode(q) == 2) dfv[q] = s[PH::stslot(q)];      // written through one step late
         } else {
             dfv[q] = s[PH::stslot(q)];

@@ -85,6 +85,10 @@ struct StepArgs {
     // Matrix-core build with the two-dimensional split: the partial sums that the workgroups hand
     // to each other, [frame][workgroup][column slice][row][stream] (sentinel-filled by the host).
     float* partial;
+    // Wave-autonomous build compiled for one store window (MV::SW): the window that holds every
+    // tensor the kernel stores (the workspace; at most 2 GiB).
+    float* store_base;
+    unsigned store_bytes;
 };
 
 RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }
