@@ -143,6 +143,7 @@ struct rnn_graph {
     unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
     int force_step_G = 0;
     bool use_jit = true;
+    bool use_store_window = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
     struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
@@ -407,7 +408,7 @@ bool wave_tensor_sizes_ok(const rnn_graph* g) {
 // but the caller's inputs (which no step kernel stores).  The kernel variant is the same source
 // behind one definition.
 bool wave_store_window_ok(const rnn_graph* g) {
-    if (g->layout.total > (int64_t(1) << 31)) return false;
+    if (!g->use_store_window || g->layout.total > (int64_t(1) << 31)) return false;
     for (int b = 0; b < g->plan.n_bufs; ++b) {
         bool is_input = false;
         for (int k : g->plan.input_nodes) is_input = is_input || g->plan.ybuf(k) == b;
@@ -586,6 +587,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (const char* env = std::getenv("RNNG_BUNDLE"))
         if (std::atoi(env) == 0) g->plan.bundle_of.assign(g->plan.bundle_of.size(), -1);      // tuning aid: no exchange bundles
     if (const char* env = std::getenv("RNNG_JIT")) g->use_jit = std::atoi(env) != 0;
+    if (const char* env = std::getenv("RNNG_STORE_WINDOW")) g->use_store_window = std::atoi(env) != 0;
     {
         const char* env = std::getenv("RNNG_XCD_LOCAL");
         g_xcd_local = env ? std::atoi(env) != 0 : true;

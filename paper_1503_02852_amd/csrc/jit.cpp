@@ -253,10 +253,11 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     }
     for (size_t b = 0; b < bstores.size(); ++b) bs_xmode.push_back({(int)b, reader_mode(P.bundles[bstores[b].bundle].ebuf)});
     // When every wavefront owns units (one loop, no helper path), a step's first polling attempt
-    // can go out at the end of the step before.  Measured: faster with 16 units per workgroup
-    // (charlm_n1 2.45 -> 2.38 ms per window, lm_elman_n1 6.40 -> 6.33), slower with 8 (speech_n1
-    // 2.545 -> 2.577) and with helper wavefronts (tiny).  RNNG_WAVE_POLL_EARLY = 0 / 1 overrides.
-    bool poll_early = 3 * UW < ph.item_chunk && UW >= 4;
+    // can go out at the end of the step before.  Measured: faster in forward loops (speech_n1
+    // 0.98 -> 0.96 ms, charlm_n1 0.85 -> 0.83), slower in backward loops, whose deferred stores
+    // then queue behind it (1.27 -> 1.32, 1.35 -> 1.44), and with helper wavefronts (tiny).
+    // RNNG_WAVE_POLL_EARLY = 0 / 1 overrides.
+    bool poll_early = 3 * UW < ph.item_chunk && !backward;
     if (const char* env = std::getenv("RNNG_WAVE_POLL_EARLY")) poll_early = std::atoi(env) != 0;
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
       << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ", NREG = " << regs.size()
