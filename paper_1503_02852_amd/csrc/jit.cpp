@@ -252,15 +252,23 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         xmode.push_back({q, reader_mode(st0[q * ST_WORDS + ST_BUF])});
     }
     for (size_t b = 0; b < bstores.size(); ++b) bs_xmode.push_back({(int)b, reader_mode(P.bundles[bstores[b].bundle].ebuf)});
-    // When every wavefront owns units (one loop, no helper path), a step's first polling attempt
-    // can go out at the end of the step before.  Measured: faster in forward loops (speech_n1
-    // 0.98 -> 0.96 ms, charlm_n1 0.85 -> 0.83), slower in backward loops, whose deferred stores
-    // then queue behind it (1.27 -> 1.32, 1.35 -> 1.44), and with helper wavefronts (tiny).
-    // RNNG_WAVE_POLL_EARLY = 0 / 1 overrides.
-    bool poll_early = 3 * UW < ph.item_chunk && !backward;
+    // Two placements, both measured.  (1) The stores of values nobody polls go out right behind
+    // the exchanged ones (their acknowledgements overlap the exchange) or one step late, behind
+    // the next step's poll: forward loops are faster with the first; backward loops with the
+    // second when a wavefront has a long matrix-vector part for the late stores to hide under
+    // (charlm_n1: 4 units per wavefront, 1.35 against 1.48 ms), with the first when it is short
+    // (speech_n1: 2 units, 1.22 against 1.27 ms).  (2) When every wavefront owns units (one loop,
+    // no helper path), a step's first polling attempt can go out at the end of the step before:
+    // faster wherever the stores are early (speech_n1 0.98 -> 0.96 / 1.22 -> 1.20 ms, charlm_n1
+    // forward 0.85 -> 0.83), slower behind deferred stores (1.35 -> 1.44) and with helper
+    // wavefronts (tiny).  RNNG_WAVE_EARLY_STORES / RNNG_WAVE_POLL_EARLY = 0 / 1 override.
+    const bool all_own = 3 * UW < ph.item_chunk;
+    bool early_stores = !backward || (all_own && UW <= 2);
+    if (const char* env = std::getenv("RNNG_WAVE_EARLY_STORES")) early_stores = std::atoi(env) != 0;
+    bool poll_early = all_own && early_stores;
     if (const char* env = std::getenv("RNNG_WAVE_POLL_EARLY")) poll_early = std::atoi(env) != 0;
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
-      << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (backward ? 0 : 1) << ", NREG = " << regs.size()
+      << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (early_stores ? 1 : 0) << ", NREG = " << regs.size()
       << ", XFR = " << XFR << ", NBS = " << bstores.size() << ", PE = " << (poll_early ? 1 : 0) << ", SW = RNNG_STORE_WINDOW;\n";
     std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
     for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});

@@ -978,8 +978,8 @@ __device__ __forceinline__ void wave_reduce_many(const float (&p)[NV], float (&t
 }
 
 // Stores of values no other workgroup waits for are issued either right behind the shared stores
-// (MV::EARLY, forward loops: measured faster, their acknowledgements overlap the exchange) or one
-// step late, after the next step's poll (backward loops: measured faster there).
+// (MV::EARLY: their acknowledgements overlap the exchange) or one step late, after the next step's
+// poll, under the matrix-vector part; the generator picks per kernel from measurements.
 template <class PH, class MV, int NSTA>
 __device__ __forceinline__ void wave_flush_stores(const PhaseRegs<PH>& r, const float (&dfv)[NSTA], const StepArgs& a) {
 #pragma unroll

@@ -230,10 +230,12 @@ def test_exchange_written_through_and_through_the_xcd_cache(monkeypatch, local):
 @pytest.mark.parametrize("early", ["0", "1"])
 def test_store_descriptors_and_poll_placement(monkeypatch, window, early):
     """The wave-autonomous kernels with one buffer descriptor over the workspace or one per stored
-    tensor, and with a step's first polling attempt issued at its start or behind the stores of
-    the step before (also with wavefronts that own no units: 33 units on 32 workgroups)."""
+    tensor, with a step's first polling attempt issued at its start or behind the stores of the
+    step before, and with the stores nobody polls early or one step late, in all four pairings
+    (also with wavefronts that own no units: 33 units on 32 workgroups)."""
     monkeypatch.setenv("RNNG_STORE_WINDOW", window)
     monkeypatch.setenv("RNNG_WAVE_POLL_EARLY", early)
+    monkeypatch.setenv("RNNG_WAVE_EARLY_STORES", early if window == "1" else str(1 - int(early)))
     tag = f"RNNG_STORE_WINDOW={window} RNNG_WAVE_POLL_EARLY={early}"
     run_both(wl.make_workload("lstm2", wl.lstm_net(12, [64, 48], 5), T=19, N=2, seed=31, scale=0.4, bias_scale=0.3, masked_fraction=0.2), label="stack, " + tag)
     run_both(wl.make_workload("lstm1", wl.lstm_net(9, [512], 6), T=9, N=1, seed=32, scale=0.2, bias_scale=0.3), label="wide layer, " + tag)
