@@ -269,7 +269,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     if (const char* env = std::getenv("RNNG_WAVE_POLL_EARLY")) poll_early = std::atoi(env) != 0;
     o << "struct MV {\n    static constexpr int NT = " << ph.n_tasks << ", UW = " << UW << ", NSRC = " << lay.n_sources
       << ", RW = " << RW << ", XF = " << XF << ", EARLY = " << (early_stores ? 1 : 0) << ", NREG = " << regs.size()
-      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ", PE = " << (poll_early ? 1 : 0) << ", SW = RNNG_STORE_WINDOW;\n";
+      << ", XFR = " << XFR << ", NBS = " << bstores.size() << ", PE = " << (poll_early ? 1 : 0) << ", SW = RNNG_STORE_WINDOW, N = " << N << ";\n";
     std::vector<std::pair<int, int>> ne, es, fs, xo, wo, ks;
     for (int s = 0; s < lay.n_sources; ++s) ks.push_back({s, lay.src[s].k_len});
     for (int t = 0; t < ph.n_tasks; ++t) {

@@ -608,7 +608,7 @@ __device__ __forceinline__ void wave_setup(WaveRegs<MV>& wv, const StepArgs& a, 
     const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int r = 0; r < MV::NREG; ++r) {
-        wv.xfoff[r] = MV::rfoff(r); wv.xstride[r] = (long long)a.N * MV::RK(r);
+        wv.xfoff[r] = MV::rfoff(r); wv.xstride[r] = (long long)MV::N * MV::RK(r);
         wv.xsrc[r] = ((cbufs_t)a.buf_ptr)[MV::rbuf(r)];
     }
 #pragma unroll
@@ -691,7 +691,7 @@ __device__ __forceinline__ void wave_bundle_setup(WaveRegs<MV>& wv, const PhaseR
 #pragma unroll
     for (int bs = 0; bs < MV::NBS; ++bs) {
         wv.bbase[bs] = ((cbufs_t)a.buf_ptr)[MV::bs_ebuf(bs)];
-        wv.bstride[bs] = a.N * MV::bs_dim(bs) * MV::bs_B(bs);
+        wv.bstride[bs] = MV::N * MV::bs_dim(bs) * MV::bs_B(bs);
         const int q0 = MV::bs_q(bs, 0);       // member 0 always exists
         const float* mbase = ((cbufs_t)a.buf_ptr)[MV::bs_member0(bs)];
         wv.bvoff[bs] = r.sptr[q0] != nullptr ? (unsigned)((int)(r.sptr[q0] - mbase) * MV::bs_B(bs) * 4) + (MV::SW ? (unsigned)((wv.bbase[bs] - a.store_base) * 4) : 0u)
@@ -840,7 +840,7 @@ __device__ __forceinline__ void group_poll_issue(PollRegs<MV>& pr, const WaveReg
         const int frame = t + wv.xfoff[s];
         const bool in_window = frame >= 0 && frame < a.T;
         const float* g = wv.xsrc[s] + (in_window ? frame : 0) * wv.xstride[s];
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? a.N * MV::RK(s) * 4 : 0, STEP_RSRC_FLAGS);
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? MV::N * MV::RK(s) * 4 : 0, STEP_RSRC_FLAGS);
         if ((MV::RK(s) & 1) == 0) {
 #pragma unroll
             for (int j = 0; j < GROUP_MAX_LOADS; ++j)
@@ -862,6 +862,7 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
     typedef GroupX<MV, NB> GX;
     auto& v64 = pr.v64;
     auto& v32 = pr.v32;
+    __builtin_assume(tid >= 0 && tid < STEP_THREADS);      // (lets the bounds tests of whole regions fold)
     auto all_ok = [&]() {
         bool ok = true;
 #pragma unroll
@@ -898,7 +899,7 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
     // elements [unit][B] go to the blocks of the sources that read its members
 #pragma unroll
     for (int r = 0; r < MV::NREG; ++r) {
-            const int RK = MV::RK(r), B = MV::RB(r), K = RK / B, total = a.N * RK;
+            const int RK = MV::RK(r), B = MV::RB(r), K = RK / B, total = MV::N * RK;      // (MV::N: the stream count the kernel is built for)
         if ((RK & 1) == 0) {
 #pragma unroll
             for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
@@ -914,8 +915,17 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
                             xs[GX::pos(MV::rsrc(r, 0), n, e)] = __uint_as_float(v64[r][j].x);
                             xs[GX::pos(MV::rsrc(r, 0), n, e + 1)] = __uint_as_float(v64[r][j].y);
                         }
-                    } else {
+                    } else if (MV::rsrc(r, 0) >= 0 && MV::rsrc(r, 1) >= 0 && (B == 2 || (MV::rsrc(r, 2) >= 0 && MV::rsrc(r, 3) >= 0))) {
+                        // every member is read here (they are equally wide, so their blocks differ
+                        // by the offset only): no branch per pair, the block is a select.
                         // e = k * B + m with m even: members m and m + 1 of unit k
+                        const int k = e / B, m = e - k * B, s0 = MV::rsrc(r, 0);
+                        const int at = GX::pos(s0, n, k) - GX::off(s0);
+                        int o0 = GX::off(s0), o1 = GX::off(MV::rsrc(r, 1));
+                        if (B == 4 && m != 0) { o0 = GX::off(MV::rsrc(r, 2)); o1 = GX::off(MV::rsrc(r, 3)); }
+                        xs[at + o0] = __uint_as_float(v64[r][j].x);
+                        xs[at + o1] = __uint_as_float(v64[r][j].y);
+                    } else {
                         const int k = e / B, m = e - k * B;
 #pragma unroll
                         for (int mm = 0; mm < 4; mm += 2) {
