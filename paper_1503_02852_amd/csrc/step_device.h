@@ -862,7 +862,15 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
     typedef GroupX<MV, NB> GX;
     auto& v64 = pr.v64;
     auto& v32 = pr.v32;
-    __builtin_assume(tid >= 0 && tid < STEP_THREADS);      // (lets the bounds tests of whole regions fold)
+    // The range of the thread index lets the bounds tests of whole regions fold.  That pays in
+    // kernels that poll bundles (two stores per pair: 1.30 -> 1.24 ms in charlm_n1's backward
+    // loop); the single stores of plain regions are faster behind their tests (each store then
+    // waits for its own load only: 0.83 against 0.89 ms in the forward loop), so kernels without
+    // bundles are not told.
+    bool bundles = false;
+#pragma unroll
+    for (int r = 0; r < MV::NREG; ++r) bundles = bundles || MV::RB(r) > 1;
+    if (bundles) __builtin_assume(tid >= 0 && tid < STEP_THREADS);
     auto all_ok = [&]() {
         bool ok = true;
 #pragma unroll
