@@ -819,6 +819,8 @@ struct GroupX {
 #endif
 constexpr int GROUP_MAX_LOADS = 8;   // per thread and region (N * K <= 2048 elements when K is odd, 4096 when even)
 
+constexpr unsigned WAVE_POLL_OUTSIDE = 0x40000000u;
+
 // The registers a step's polling loads land in.  A step's first attempt is issued at the end of
 // the step before (right behind that step's stores), so they live across steps.
 template <class MV>
@@ -837,18 +839,26 @@ __device__ __forceinline__ void group_poll_issue(PollRegs<MV>& pr, const WaveReg
     step_compiler_barrier();
 #pragma unroll
     for (int s = 0; s < MV::NREG; ++s) {
+        // one descriptor over the whole tensor (loop-invariant); a lane beyond the frame's vector
+        // and a frame outside the window each add 1 GiB to the offset, which lands beyond the
+        // tensor (below 1 GiB: the host checks it) without wrapping, so such loads return zero
         const int frame = t + wv.xfoff[s];
-        const bool in_window = frame >= 0 && frame < a.T;
-        const float* g = wv.xsrc[s] + (in_window ? frame : 0) * wv.xstride[s];
-        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? MV::N * MV::RK(s) * 4 : 0, STEP_RSRC_FLAGS);
+        const unsigned fo = (frame >= 0 && frame < a.T) ? (unsigned)(frame * (MV::N * MV::RK(s) * 4)) : WAVE_POLL_OUTSIDE;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(wv.xsrc[s]), 0, a.T * MV::N * MV::RK(s) * 4, STEP_RSRC_FLAGS);
         if ((MV::RK(s) & 1) == 0) {
 #pragma unroll
-            for (int j = 0; j < GROUP_MAX_LOADS; ++j)
-                if (j < GX::pairs_per_thread(s)) pr.v64[s][j] = __builtin_amdgcn_raw_buffer_load_b64(rs, (tid + STEP_THREADS * j) * 8, 0, STEP_COHERENT_AUX);
+            for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
+                const int p = tid + STEP_THREADS * j;
+                const unsigned lo = 2 * p < MV::N * MV::RK(s) ? (unsigned)(p * 8) : WAVE_POLL_OUTSIDE;
+                if (j < GX::pairs_per_thread(s)) pr.v64[s][j] = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lo + fo), 0, STEP_COHERENT_AUX);
+            }
         } else {
 #pragma unroll
-            for (int j = 0; j < GROUP_MAX_LOADS; ++j)
-                if (j < GX::words_per_thread(s)) pr.v32[s][j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (tid + STEP_THREADS * j) * 4, 0, STEP_COHERENT_AUX);
+            for (int j = 0; j < GROUP_MAX_LOADS; ++j) {
+                const int p = tid + STEP_THREADS * j;
+                const unsigned lo = p < MV::N * MV::RK(s) ? (unsigned)(p * 4) : WAVE_POLL_OUTSIDE;
+                if (j < GX::words_per_thread(s)) pr.v32[s][j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(lo + fo), 0, STEP_COHERENT_AUX);
+            }
         }
     }
     step_compiler_barrier();
@@ -891,8 +901,11 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
     int spins = 0;
     for (;;) {
         const bool ok = all_ok();
-        if (ok || dead) break;
-        if (++spins > a.spin_limit) { dead = true; atomicExch(a.ctrl, 1u); break; }
+        // one decision per wavefront (a scalar branch; per-lane loop exits cost ~25 scalar
+        // instructions of mask handling per step, and a wavefront issues one instruction every
+        // four clocks): a wavefront repeats all its loads while any lane holds a sentinel
+        if (__builtin_amdgcn_ballot_w64(!ok) == 0 || dead) break;
+        if (++spins > a.spin_limit) { dead = true; if ((tid & 63) == 0) atomicExch(a.ctrl, 1u); break; }
         __builtin_amdgcn_s_sleep(WAVE_RETRY_SLEEP);
         group_poll_issue<MV, NB>(pr, wv, a, t, tid);
     }
