@@ -150,3 +150,24 @@ def test_stacked_layers_get_a_side_by_side_step_kernel(monkeypatch):
     spec5 = wl.generalized_net(8, 16, 2, 4)
     g2 = binding.Graph(spec5.node_array(), spec5.edge_array())
     assert g2.specialise(1) == 4
+
+
+@pytest.mark.parametrize("early,window", [("1", "1"), ("0", "0")])
+def test_step_kernel_variants_compile(monkeypatch, early, window):
+    """The generated step kernels compile for gfx950 in both placements of the stores nobody polls
+    and of a step's first polling attempt, with one store window and with one descriptor per
+    stored tensor (a stack, and an Elman layer whose 33 units leave wavefronts without units)."""
+    import workloads as wl
+    from paper_1503_02852_amd import binding
+    monkeypatch.setenv("RNNG_WAVE_POLL_EARLY", early)
+    monkeypatch.setenv("RNNG_WAVE_EARLY_STORES", early)
+    monkeypatch.setenv("RNNG_JIT_DEFINES", f"-DRNNG_STORE_WINDOW={window}")
+    spec = wl.lstm_net(8, [16, 16], 4)
+    g = binding.Graph(spec.node_array(), spec.edge_array())
+    n = g.specialise(1)
+    if n == 0:
+        pytest.skip("run-time compiler not available")
+    assert n == 6
+    spec2 = wl.elman_net(7, 33, 4)
+    g2 = binding.Graph(spec2.node_array(), spec2.edge_array())
+    assert g2.specialise(3) == 2
