@@ -15,8 +15,12 @@ Readings where the paper is silent (all listed in the design notes of the reposi
   * a third weight kind "diagonal" besides "full" and "identity" (needed for peepholes);
   * y_k = f_k(s_k) is applied to multiplicative nodes too (Section 2.2's delta equation
     uses f_k' for any layer);
-  * activations before the window (frame index <= 0) are zero; error terms from frames
-    after the window are zero (truncation at the window edges, Section 2.2);
+  * a fresh window starts from zero activations (frame index <= 0); a window that carries
+    state (BPTT(h; h') of Section 3.2) starts from the activations the earlier frames left,
+    and its backward pass follows the last two equations of Section 2.2 literally: delta and
+    epsilon are propagated only while t > t0', but the connection outputs z_n(t) and the
+    weight-gradient terms eps_m(t) y_k(t - d_m)^T of the frames t > t0' use the real
+    y_k(t - d_m), also where t - d_m <= t0'; error terms from frames after the window are zero;
   * E_total = sum over frames, streams and output nodes of -ln y_target (natural log,
     no averaging); a target of -1 masks the frame;
   * the functions return dE_total/dW (the paper's nabla W = -sum eps y^T with
@@ -24,9 +28,12 @@ Readings where the paper is silent (all listed in the design notes of the reposi
 
 Parity pins (tests/, `-m "not gpu"`): a separately written textbook peephole LSTM and
 Elman net with hand-derived full BPTT, central finite differences of E_total,
-stream-independence, delay-line, unreachable-node and relabelling invariants; bptt_window
-against bptt itself (whole sequence), against a fresh window when the carried state is exactly
-zero, and against the window alone on a delay-free graph.
+stream-independence, delay-line, unreachable-node and relabelling invariants; forward with a
+carried history against one forward pass over the whole sequence; bptt_window against bptt itself
+(whole sequence), against central finite differences of the window's error with the pre-window
+activations held constant (which is the truncated gradient), against a textbook LSTM / Elman
+BPTT started from a non-zero state, against a hand-derived one-frame window, and against the
+window alone on a delay-free graph.
 """
 from __future__ import annotations
 
@@ -105,11 +112,15 @@ def _activation_derivative(act, y):
     raise ValueError(act)
 
 
-def forward(nodes, edges, weights, biases, inputs, T, N):
+def forward(nodes, edges, weights, biases, inputs, T, N, history=None):
     """Forward pass over frames 1..T (stored at index 0..T-1).
 
     weights[m]: float array [n_dst, n_src] (full), [dim] (diagonal) or None (identity).
     biases[k]:  float array [dim] or None.   inputs[k]: [T, N, dim] for every input node.
+    history[k] (optional, every node): [Hh, N, dim], the activations of the Hh frames in front of
+    the window (its last row is the frame right before the window), as left by an earlier
+    forward pass (Section 3.2: the forward pass of BPTT(h; h') continues from the carried
+    state); frames further back, and all of them without a history, are zero.
     Returns (y, z): y[k] is [T, N, dim] for every node; z[m] is [T, N, dim] for every edge
     (the connection outputs, which the multiplicative layers' backward pass needs)."""
     W = [None if w is None else np.asarray(w, dtype=np.float64) for w in weights]
@@ -123,6 +134,14 @@ def forward(nodes, edges, weights, biases, inputs, T, N):
     for k, n in enumerate(nodes):
         if n["kind"] == INPUT:
             y[k][:] = np.asarray(inputs[k], dtype=np.float64)
+    def source_activation(k, tau):
+        """y_k(tau); tau < 0 lies before the window: the carried history, else zero."""
+        if tau >= 0:
+            return y[k][tau]
+        if history is not None and -tau <= len(history[k]):
+            return np.asarray(history[k][len(history[k]) + tau], dtype=np.float64)
+        return None
+
     for t in range(T):
         for k in order:
             n = nodes[k]
@@ -130,9 +149,9 @@ def forward(nodes, edges, weights, biases, inputs, T, N):
                 continue
             for m in anterior[k]:
                 e = edges[m]
-                tau = t - e["delay"]
-                if tau >= 0:
-                    z[m][t] = _apply_weight(e, W[m], y[e["src"]][tau])
+                ysrc = source_activation(e["src"], t - e["delay"])
+                if ysrc is not None:
+                    z[m][t] = _apply_weight(e, W[m], ysrc)
                 # else: the source activation before the window is zero, so z stays zero
             if n["kind"] == ADD:
                 s = np.zeros((N, n["dim"]))
@@ -164,14 +183,19 @@ def loss(nodes, y, targets):
     return float(total)
 
 
-def bptt(nodes, edges, weights, biases, y, z, targets, T, N):
-    """Backward pass over frames T..1 in reverse delay-0 topological order.
+def bptt(nodes, edges, weights, biases, y, z, targets, T, N, t_first=0):
+    """Backward pass over frames T..t_first+1 (indices T-1 .. t_first) in reverse delay-0
+    topological order; t_first is the paper's truncation point t0' (Section 2.2).
 
     Works in the paper's variables: delta_k(t) = -dE/ds_k(t), eps_m(t) = -dE/dz_m(t);
-    output nodes start from delta = d - y (softmax with cross-entropy).  Returns
+    output nodes start from delta = d - y (softmax with cross-entropy).  delta and eps are
+    back-propagated only while t > t0': nothing is handed to a frame before t_first.  The
+    gradient sums run over t0' < t <= t1 with the real y_src(t - d_m) and the real connection
+    outputs z_n(t), also where t - d_m lies at or before t0' (frames before index 0 do not
+    exist: zero).  Returns
     (grad_w, grad_b, delta): grad_w[m] = -sum_t eps_m(t) y_src(t - d_m)^T summed over
     streams (None for identity edges), grad_b[k] = -sum_t delta_k(t), and delta[k] as
-    [T, N, dim] for every non-input node."""
+    [T, N, dim] for every non-input node (zero before t_first)."""
     W = [None if w is None else np.asarray(w, dtype=np.float64) for w in weights]
     order = delay0_topological_order(nodes, edges)
     anterior = [[] for _ in nodes]
@@ -181,7 +205,7 @@ def bptt(nodes, edges, weights, biases, y, z, targets, T, N):
     delta = [np.zeros((T, N, n["dim"])) for n in nodes]
     grad_w = [None if w is None else np.zeros_like(w) for w in W]
     grad_b = [None if b is None else np.zeros(nodes[k]["dim"]) for k, b in enumerate(biases)]
-    for t in range(T - 1, -1, -1):
+    for t in range(T - 1, t_first - 1, -1):
         for k in reversed(order):
             n = nodes[k]
             if n["kind"] == INPUT:
@@ -210,38 +234,32 @@ def bptt(nodes, edges, weights, biases, y, z, targets, T, N):
                             eps = eps * z[other][t]
                 tau = t - e["delay"]
                 if tau < 0:
-                    continue            # source frame lies before the window
+                    continue            # no such frame: its activation is zero
                 ysrc = y[e["src"]][tau]
                 if e["wkind"] == FULL:
                     grad_w[m] -= eps.T @ ysrc
                 elif e["wkind"] == DIAG:
                     grad_w[m] -= (eps * ysrc).sum(axis=0)
-                if nodes[e["src"]]["kind"] != INPUT:
+                if tau >= t_first and nodes[e["src"]]["kind"] != INPUT:
                     acc[e["src"]][tau] += _apply_weight_transposed(e, W[m], eps)
     return grad_w, grad_b, delta
 
 
-def bptt_window(nodes, edges, weights, biases, y_long, targets_long, t_first, T, N):
-    """BPTT(h; h') of Section 3.2: the forward pass has run over a longer sequence (y_long from
-    `forward`), the backward pass covers only its T frames [t_first, t_first + T).
-
-    Reading (the paper does not say what the backward pass sees before the window): everything
-    before the window start counts as zero in the backward pass, exactly like the frames before a
-    fresh window -- the in-window activations keep the values the carried state gave them, the
-    connection outputs z_m(t) with t - d_m before the window start are zero, and the weight
-    gradient has no term for them.  With t_first = 0 and T the whole sequence this is `bptt`."""
-    y = [np.array(a[t_first:t_first + T], dtype=np.float64) for a in y_long]
-    W = [None if w is None else np.asarray(w, dtype=np.float64) for w in weights]
-    z = [np.zeros((T, N, nodes[e["dst"]]["dim"])) for e in edges]
-    for m, e in enumerate(edges):
-        for t in range(T):
-            tau = t - e["delay"]
-            if tau >= 0:
-                z[m][t] = _apply_weight(e, W[m], y[e["src"]][tau])
-    targets = {k: np.asarray(v)[t_first:t_first + T] for k, v in targets_long.items()}
-    E = loss(nodes, y, targets)
-    grad_w, grad_b, delta = bptt(nodes, edges, weights, biases, y, z, targets, T, N)
-    return dict(y=y, z=z, loss=E, grad_w=grad_w, grad_b=grad_b, delta=delta)
+def bptt_window(nodes, edges, weights, biases, y_long, z_long, targets_long, t_first, T, N):
+    """BPTT(h; h') of Section 3.2: the forward pass has run over a longer sequence (y_long, z_long
+    from `forward`), the backward pass covers only its T frames [t_first, t_first + T), truncated
+    at t0' = t_first as the last two equations of Section 2.2 say: errors stop at the window
+    start, while the frames inside the window see the real activations of the frames before it.
+    The error counts the window's frames only.  With t_first = 0 and T the whole sequence this is
+    `bptt`.  Returned arrays cover the window's T frames."""
+    t_end = t_first + T
+    y_cut = [a[:t_end] for a in y_long]
+    z_cut = [a[:t_end] for a in z_long]
+    targets = {k: np.asarray(v)[:t_end] for k, v in targets_long.items()}
+    E = loss(nodes, [a[t_first:] for a in y_cut], {k: v[t_first:] for k, v in targets.items()})
+    grad_w, grad_b, delta = bptt(nodes, edges, weights, biases, y_cut, z_cut, targets, t_end, N, t_first)
+    return dict(y=[a[t_first:] for a in y_cut], z=[a[t_first:] for a in z_cut], loss=E, grad_w=grad_w, grad_b=grad_b,
+                delta=[a[t_first:] for a in delta])
 
 
 def forward_bptt(nodes, edges, weights, biases, inputs, targets, T, N):

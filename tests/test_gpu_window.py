@@ -109,7 +109,7 @@ def test_window_moved_ahead_with_carried_state(name):
     L = T + 2 * hp
     long = wl.make_workload(name, spec, T=L, N=N, seed=43, scale=0.4, bias_scale=0.3)
     print(f"[window] carry {name}: T={T} h'={hp} N={N}", flush=True)
-    y_long, _ = go.forward(long.spec.nodes, long.spec.edges, long.weights, long.biases, long.inputs, L, N)
+    y_long, z_long = go.forward(long.spec.nodes, long.spec.edges, long.weights, long.biases, long.inputs, L, N)
     first = wl.Workload(name=name, spec=spec, T=T, N=N, weights=long.weights, biases=long.biases,
                         inputs={k: v[:T].copy() for k, v in long.inputs.items()},
                         targets={k: v[:T].copy() for k, v in long.targets.items()})
@@ -127,7 +127,7 @@ def test_window_moved_ahead_with_carried_state(name):
         win.bptt()
         loss = win.compute_grads(want_loss=True)
         tl = {k: np.concatenate([np.full_like(v[:a], -1), masked[k], np.full_like(v[b:], -1)]) for k, v in long.targets.items()}
-        ref = go.bptt_window(long.spec.nodes, long.spec.edges, long.weights, long.biases, y_long, tl, a, T, N)
+        ref = go.bptt_window(long.spec.nodes, long.spec.edges, long.weights, long.biases, y_long, z_long, tl, a, T, N)
         check_against(win, first, ref, f"{name} advance {step}")
         assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
 

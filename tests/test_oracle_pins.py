@@ -298,16 +298,183 @@ def test_delay0_cycle_is_rejected():
 
 # ---- BPTT(h; h') of Section 3.2: backward pass over the last frames of a longer forward pass ----
 
+def max_delay(spec):
+    return max([e["delay"] for e in spec.edges] + [1])
+
+
+def history_before(y_long, t_first, depth):
+    """The `depth` frames in front of frame t_first of every node (zeros where the sequence has none)."""
+    hist = []
+    for a in y_long:
+        h = np.zeros((depth,) + a.shape[1:])
+        n = min(depth, t_first)
+        if n:
+            h[depth - n:] = a[t_first - n:t_first]
+        hist.append(h)
+    return hist
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_forward_with_history_continues_the_sequence(seed):
+    """Section 3.2: the forward pass of a later window starts from the state the earlier frames
+    left.  A sequence cut at any frame and continued from the d_max frames in front of the cut
+    must give the activations of the uncut forward pass."""
+    rng = np.random.default_rng(300 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, n_inputs=1 + seed % 2)
+    L, N = 11, 2
+    w = wl.make_workload("cut", spec, T=L, N=N, seed=seed, scale=0.8, bias_scale=0.5)
+    y_long, z_long = go.forward(spec.nodes, spec.edges, w.weights, w.biases, w.inputs, L, N)
+    for cut in (1, 4, 9):
+        hist = history_before(y_long, cut, max_delay(spec))
+        y2, z2 = go.forward(spec.nodes, spec.edges, w.weights, w.biases, {k: v[cut:] for k, v in w.inputs.items()}, L - cut, N, history=hist)
+        for k in range(len(spec.nodes)):
+            np.testing.assert_allclose(y2[k], y_long[k][cut:], rtol=1e-13, atol=1e-15)
+        for m in range(len(spec.edges)):
+            np.testing.assert_allclose(z2[m], z_long[m][cut:], rtol=1e-13, atol=1e-15)
+
+
 def test_windowed_bptt_over_the_whole_sequence_is_plain_bptt():
     w = wl.make_workload("gen", wl.generalized_net(5, 6, 2, 3), T=9, N=2, seed=31, scale=0.6, bias_scale=0.3)
     ref = run_oracle(w)
-    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, ref["y"], w.targets, 0, w.T, w.N)
+    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, ref["y"], ref["z"], w.targets, 0, w.T, w.N)
     assert win["loss"] == pytest.approx(ref["loss"], rel=1e-14)
     for a, b in zip(win["grad_w"], ref["grad_w"]):
         if b is not None:
             np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-15)
     for k in range(len(w.spec.nodes)):
         np.testing.assert_allclose(win["delta"][k], ref["delta"][k], rtol=1e-13, atol=1e-15)
+
+
+def check_truncated_gradient_by_finite_differences(w, t_first, n_probe=4, h=1e-5, tol=2e-6, seed=0):
+    """The truncated gradient of Section 2.2 (errors stop at t0', the sums over t0' < t <= t1 keep
+    the real y_k(t - d_m)) is the derivative of the window's error with every activation at or
+    before t0' held constant: central differences of exactly that function."""
+    spec, L, N = w.spec, w.T, w.N
+    T = L - t_first
+    y_long, z_long = go.forward(spec.nodes, spec.edges, w.weights, w.biases, w.inputs, L, N)
+    win = go.bptt_window(spec.nodes, spec.edges, w.weights, w.biases, y_long, z_long, w.targets, t_first, T, N)
+    hist = history_before(y_long, t_first, max_delay(spec))        # computed once, with the unperturbed weights
+    win_inputs = {k: v[t_first:] for k, v in w.inputs.items()}
+    win_targets = {k: v[t_first:] for k, v in w.targets.items()}
+
+    def window_error(weights, biases):
+        y, _ = go.forward(spec.nodes, spec.edges, weights, biases, win_inputs, T, N, history=hist)
+        return go.loss(spec.nodes, y, win_targets)
+
+    W64 = [None if a is None else a.astype(np.float64) for a in w.weights]
+    B64 = [None if a is None else a.astype(np.float64) for a in w.biases]
+    assert window_error(W64, B64) == pytest.approx(win["loss"], rel=1e-13)
+    rng = np.random.default_rng(seed)
+    n_nonzero = 0
+    for group, grads, store in (("w", win["grad_w"], W64), ("b", win["grad_b"], B64)):
+        for idx, g in enumerate(grads):
+            if g is None:
+                continue
+            flat = store[idx].reshape(-1)
+            for j in rng.choice(flat.size, size=min(n_probe, flat.size), replace=False):
+                old = flat[j]
+                flat[j] = old + h; ep = window_error(W64, B64)
+                flat[j] = old - h; em = window_error(W64, B64)
+                flat[j] = old
+                fd = (ep - em) / (2 * h)
+                an = g.reshape(-1)[j]
+                assert abs(fd - an) / max(1e-3, abs(fd), abs(an)) < tol, (group, idx, j, fd, an)
+                n_nonzero += abs(an) > 1e-9
+    assert n_nonzero > 0
+    return win
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_windowed_bptt_is_the_truncated_gradient_random_graphs(seed):
+    rng = np.random.default_rng(100 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, n_inputs=1 + seed % 2)
+    w = wl.make_workload("rand", spec, T=9, N=2, seed=seed, scale=0.8, bias_scale=0.5,
+                         masked_fraction=0.2 if seed % 2 else 0.0)
+    check_truncated_gradient_by_finite_differences(w, t_first=3 + seed % 3, seed=seed)
+
+
+def test_windowed_bptt_is_the_truncated_gradient_generalized_lstm():
+    spec = wl.generalized_net(3, 4, 2, 3)
+    w = wl.make_workload("gen", spec, T=8, N=2, seed=3, scale=0.8, bias_scale=0.5)
+    check_truncated_gradient_by_finite_differences(w, t_first=3, n_probe=3)
+
+
+def test_truncated_gradient_differs_from_a_fresh_window_when_state_is_carried():
+    """Guards the pins above against a vacuous pass: with a non-zero carried state the terms that
+    pair the window's first frames with pre-window activations are not zero."""
+    spec = wl.lstm_net(4, [5], 3)
+    L, T, N = 10, 5, 2
+    w = wl.make_workload("carry", spec, T=L, N=N, seed=34, scale=0.7, bias_scale=0.3)
+    y, z = go.forward(spec.nodes, spec.edges, w.weights, w.biases, w.inputs, L, N)
+    win = go.bptt_window(spec.nodes, spec.edges, w.weights, w.biases, y, z, w.targets, L - T, T, N)
+    # the window's frames alone, with everything before them zero in the backward pass as well
+    y0 = [a.copy() for a in y]; z0 = [a.copy() for a in z]
+    for a in y0 + z0:
+        a[:L - T] = 0.0
+    for m, e in enumerate(spec.edges):          # connection outputs that came from pre-window frames
+        if e["delay"] > 0:
+            z0[m][L - T:L - T + e["delay"]] = 0.0
+    cut = go.bptt_window(spec.nodes, spec.edges, w.weights, w.biases, y0, z0, w.targets, L - T, T, N)
+    m_hf = find_edge(spec, "L1.h", "L1.f", 1)
+    m_cf = find_edge(spec, "L1.c", "L1.f", 1)
+    assert relerr(cut["grad_w"][m_hf], win["grad_w"][m_hf]) > 1e-3
+    assert relerr(cut["grad_w"][m_cf], win["grad_w"][m_cf]) > 1e-3
+
+
+@pytest.mark.parametrize("hidden", [[6], [5, 7]])
+def test_windowed_bptt_equals_textbook_lstm_started_from_the_carried_state(hidden):
+    """Truncated BPTT over consecutive windows as textbooks have it: the window starts from
+    (h, c) of the frame before it, taken as constants.  The textbook net is written separately."""
+    L, T, N = 13, 7, 2
+    t_first = L - T
+    spec = wl.lstm_net(4, hidden, 5)
+    w = wl.make_workload("lstm", spec, L, N, seed=12, scale=0.7, bias_scale=0.5, masked_fraction=0.2)
+    y, z = go.forward(spec.nodes, spec.edges, w.weights, w.biases, w.inputs, L, N)
+    win = go.bptt_window(spec.nodes, spec.edges, w.weights, w.biases, y, z, w.targets, t_first, T, N)
+    (x,) = spec.input_nodes(); (out,) = spec.output_nodes()
+    tags = [f"L{l + 1}" for l in range(len(hidden))]
+    below = ["x"] + [f"{t}.h" for t in tags[:-1]]
+    params = [lstm_layer_params(w, t, b) for t, b in zip(tags, below)]
+    e_out = find_edge(spec, f"{tags[-1]}.h", "out")
+    tot = 0.0; G_layers = [None] * len(hidden); GWy = 0.0
+    for n in range(N):
+        state0 = [(y[spec.node_by_name(f"{t}.h")][t_first - 1, n], y[spec.node_by_name(f"{t}.c")][t_first - 1, n]) for t in tags]
+        loss, probs, grads, dWy, dby, hs = tb.lstm_stack_loss_and_grads(
+            params, w.weights[e_out], w.biases[out], w.inputs[x][t_first:, n], w.targets[out][t_first:, n], True, state0)
+        tot += loss
+        assert relerr(win["y"][out][:, n], probs) < 1e-12
+        for l in range(len(hidden)):
+            G_layers[l] = grads[l] if G_layers[l] is None else {k: G_layers[l][k] + grads[l][k] for k in grads[l]}
+        GWy = GWy + dWy
+    assert abs(win["loss"] - tot) < 1e-10 * max(1.0, abs(tot))
+    assert relerr(win["grad_w"][e_out], GWy) < 1e-11
+    for l, (t, b) in enumerate(zip(tags, below)):
+        em, bm = lstm_layer_edges(spec, t, b)
+        for name, m in em.items():
+            assert relerr(win["grad_w"][m], G_layers[l][name]) < 1e-10, (t, name)
+        for name, k in bm.items():
+            assert relerr(win["grad_b"][k], G_layers[l][name]) < 1e-10, (t, name)
+
+
+def test_windowed_bptt_equals_textbook_elman_started_from_the_carried_state():
+    L, T, N = 14, 6, 2
+    t_first = L - T
+    spec = wl.elman_net(5, 7, 4)
+    w = wl.make_workload("elman", spec, L, N, seed=5, scale=0.6, bias_scale=0.4, masked_fraction=0.15)
+    y, z = go.forward(spec.nodes, spec.edges, w.weights, w.biases, w.inputs, L, N)
+    win = go.bptt_window(spec.nodes, spec.edges, w.weights, w.biases, y, z, w.targets, t_first, T, N)
+    x, h, out = 0, 1, 2
+    tot = 0.0; G = None
+    for n in range(N):
+        loss, probs, g, hh = tb.elman_loss_and_grads(w.weights[0], w.weights[1], w.biases[h], w.weights[2], w.biases[out],
+                                                     w.inputs[x][t_first:, n], w.targets[out][t_first:, n], h0=y[h][t_first - 1, n])
+        tot += loss
+        assert relerr(win["y"][h][:, n], hh) < 1e-12
+        G = g if G is None else {k: G[k] + g[k] for k in g}
+    assert abs(win["loss"] - tot) < 1e-11 * max(1.0, abs(tot))
+    for m, name in ((0, "Wx"), (1, "Wh"), (2, "Wy")):
+        assert relerr(win["grad_w"][m], G[name]) < 1e-11
+    assert relerr(win["grad_b"][h], G["bh"]) < 1e-11
 
 
 def test_windowed_bptt_with_zero_carried_state_is_a_fresh_window():
@@ -321,10 +488,10 @@ def test_windowed_bptt_with_zero_carried_state_is_a_fresh_window():
     for k in w.inputs:
         w.inputs[k][:t_first] = 0.0
     # the output bias may be anything; the LSTM gate biases are zero (bias_scale = 0)
-    y, _ = go.forward(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, L, N)
+    y, z = go.forward(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, L, N)
     for name in ("L1.c", "L1.h", "L2.c", "L2.h"):
         assert np.all(y[spec.node_by_name(name)][:t_first] == 0.0)
-    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, y, w.targets, t_first, T, N)
+    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, y, z, w.targets, t_first, T, N)
     fresh = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases,
                             {k: v[t_first:] for k, v in w.inputs.items()}, {k: v[t_first:] for k, v in w.targets.items()}, T, N)
     assert win["loss"] == pytest.approx(fresh["loss"], rel=1e-13)
@@ -347,8 +514,8 @@ def test_windowed_bptt_on_a_delay_free_graph_is_the_window_alone():
     g.add_edge(a, m, wl.IDENTITY, 0); g.add_edge(b, m, wl.DIAG, 0); g.add_edge(m, out, wl.FULL, 0)
     L, T, N = 11, 5, 3
     w = wl.make_workload("ff", g, T=L, N=N, seed=33, scale=0.8, bias_scale=0.5)
-    y, _ = go.forward(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, L, N)
-    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, y, w.targets, L - T, T, N)
+    y, z = go.forward(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, L, N)
+    win = go.bptt_window(w.spec.nodes, w.spec.edges, w.weights, w.biases, y, z, w.targets, L - T, T, N)
     alone = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases,
                             {k: v[L - T:] for k, v in w.inputs.items()}, {k: v[L - T:] for k, v in w.targets.items()}, T, N)
     for p, q in zip(win["grad_w"], alone["grad_w"]):
@@ -356,11 +523,11 @@ def test_windowed_bptt_on_a_delay_free_graph_is_the_window_alone():
             np.testing.assert_allclose(p, q, rtol=1e-12, atol=1e-14)
 
 
-def test_windowed_bptt_counts_pre_window_connection_outputs_as_zero():
+def test_windowed_bptt_keeps_pre_window_connection_outputs():
     """Hand-derived one-frame window.  p(t) = u(t) * x(t-1), u = w x, y = softmax(W2 p); the window
-    is the sequence's second frame.  The forward value p keeps x of the frame before the window,
-    but in the backward pass that connection output counts as zero: eps on u -> p is
-    delta_p * 0, so dE/dw = 0, while dE/dW2 = -(d - y) p^T with the true p."""
+    is the sequence's second frame, t = 2, so x(t-1) lies before it.  Section 2.2's epsilon of the
+    multiplicative layer carries the real z_n(t): eps on u -> p is delta_p * x(t-1), hence
+    dE/dw = (W2^T (y - d)) x(t-1) x(t), and dE/dW2 = (y - d) p^T."""
     g = wl.GraphSpec()
     x = g.add_node(wl.INPUT, wl.LINEAR, 1, name="x")
     u = g.add_node(wl.ADD, wl.LINEAR, 1, name="u")
@@ -375,12 +542,15 @@ def test_windowed_bptt_counts_pre_window_connection_outputs_as_zero():
     biases = [None] * len(g.nodes)
     xs = np.array([1.5, -2.0]).reshape(2, 1, 1)
     targets = {out: np.array([[1], [0]])}
-    y, _ = go.forward(g.nodes, g.edges, weights, biases, {x: xs}, 2, 1)
+    y, z = go.forward(g.nodes, g.edges, weights, biases, {x: xs}, 2, 1)
     p1 = 0.7 * (-2.0) * 1.5
     assert y[p][1, 0, 0] == pytest.approx(p1)
-    win = go.bptt_window(g.nodes, g.edges, weights, biases, y, targets, 1, 1, 1)
+    win = go.bptt_window(g.nodes, g.edges, weights, biases, y, z, targets, 1, 1, 1)
     s = np.array([0.4 * p1, -0.9 * p1])
     sm = np.exp(s) / np.exp(s).sum()
+    dEds = sm - np.array([1.0, 0.0])
     assert win["loss"] == pytest.approx(-np.log(sm[0]))
-    np.testing.assert_allclose(win["grad_w"][e_w2][:, 0], (sm - np.array([1.0, 0.0])) * p1, rtol=1e-12)
-    assert win["grad_w"][e_w][0, 0] == 0.0
+    np.testing.assert_allclose(win["grad_w"][e_w2][:, 0], dEds * p1, rtol=1e-12)
+    dEdp = 0.4 * dEds[0] - 0.9 * dEds[1]
+    assert win["grad_w"][e_w][0, 0] == pytest.approx(dEdp * 1.5 * (-2.0), rel=1e-12)
+    assert abs(win["grad_w"][e_w][0, 0]) > 1e-3

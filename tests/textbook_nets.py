@@ -2,6 +2,8 @@
 forget gates and peephole connections, and an Elman network, each with a softmax output
 layer, cross-entropy loss and a hand-derived *full-gradient* BPTT (every path through
 h(t-1), c(t-1) and the peepholes is differentiated; no truncation inside the window).
+A sequence may start from a given state (h0, c0), which is then a constant of the window: the
+usual truncated BPTT over consecutive windows of one long sequence.
 
 The paper states that its generalized graph equations represent these networks and their
 BPTT training exactly (Sections 1, 2 and 4), so the graph oracle must agree with this file
@@ -28,14 +30,16 @@ class PeepholeLSTMLayer:
         self.p = {k: np.asarray(v, dtype=np.float64) for k, v in p.items()}
         self.use_h = use_h
 
-    def forward(self, xs):
+    def forward(self, xs, h0=None, c0=None):
         p = self.p
         T = xs.shape[0]
         H = p["bi"].shape[0]
         self.xs = xs
         self.i = np.zeros((T, H)); self.f = np.zeros((T, H)); self.g = np.zeros((T, H))
         self.c = np.zeros((T, H)); self.o = np.zeros((T, H)); self.h = np.zeros((T, H))
-        h_prev = np.zeros(H); c_prev = np.zeros(H)
+        self.h0 = np.zeros(H) if h0 is None else np.asarray(h0, dtype=np.float64)
+        self.c0 = np.zeros(H) if c0 is None else np.asarray(c0, dtype=np.float64)
+        h_prev = self.h0; c_prev = self.c0
         for t in range(T):
             x = xs[t]
             rec = (lambda name: p["Wh" + name] @ h_prev) if self.use_h else (lambda name: 0.0)
@@ -57,8 +61,8 @@ class PeepholeLSTMLayer:
         dh_next = np.zeros(H)      # dE/dh(t) through the gates of frame t+1
         dc_next = np.zeros(H)      # dE/dc(t) through frame t+1 (cell carry and peepholes)
         for t in range(T - 1, -1, -1):
-            c_prev = self.c[t - 1] if t > 0 else np.zeros(H)
-            h_prev = self.h[t - 1] if t > 0 else np.zeros(H)
+            c_prev = self.c[t - 1] if t > 0 else self.c0
+            h_prev = self.h[t - 1] if t > 0 else self.h0
             dh = dh_above[t] + dh_next
             tc = np.tanh(self.c[t])
             dao = dh * tc * self.o[t] * (1 - self.o[t])
@@ -84,14 +88,15 @@ class PeepholeLSTMLayer:
         return dx, G
 
 
-def lstm_stack_loss_and_grads(layer_params, Wy, by, xs, targets, use_h=True):
-    """Stacked peephole LSTM + softmax/cross-entropy for one stream.
+def lstm_stack_loss_and_grads(layer_params, Wy, by, xs, targets, use_h=True, state0=None):
+    """Stacked peephole LSTM + softmax/cross-entropy for one stream.  state0: per layer (h0, c0),
+    the state the sequence starts from (default zero).
     Returns (loss, probs [T, C], per-layer grads list, dWy, dby, per-layer h list)."""
     layers = [PeepholeLSTMLayer(p, use_h) for p in layer_params]
     a = np.asarray(xs, dtype=np.float64)
     hs = []
-    for L in layers:
-        a = L.forward(a)
+    for l, L in enumerate(layers):
+        a = L.forward(a) if state0 is None else L.forward(a, state0[l][0], state0[l][1])
         hs.append(a)
     Wy = np.asarray(Wy, dtype=np.float64); by = np.asarray(by, dtype=np.float64)
     T = a.shape[0]
@@ -113,16 +118,18 @@ def lstm_stack_loss_and_grads(layer_params, Wy, by, xs, targets, use_h=True):
     return loss, probs, grads, dWy, dby, hs
 
 
-def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets):
-    """h(t) = tanh(Wx x(t) + Wh h(t-1) + bh); p(t) = softmax(Wy h(t) + by); one stream."""
+def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets, h0=None):
+    """h(t) = tanh(Wx x(t) + Wh h(t-1) + bh); p(t) = softmax(Wy h(t) + by); one stream; h(-1) = h0
+    (a constant of the window; default zero)."""
     Wx, Wh, bh, Wy, by = (np.asarray(a, dtype=np.float64) for a in (Wx, Wh, bh, Wy, by))
     xs = np.asarray(xs, dtype=np.float64)
     T = xs.shape[0]
     H = bh.shape[0]
+    h0 = np.zeros(H) if h0 is None else np.asarray(h0, dtype=np.float64)
     h = np.zeros((T, H)); probs = np.zeros((T, by.shape[0]))
     loss = 0.0
     for t in range(T):
-        hp = h[t - 1] if t > 0 else np.zeros(H)
+        hp = h[t - 1] if t > 0 else h0
         h[t] = np.tanh(Wx @ xs[t] + Wh @ hp + bh)
         probs[t] = _softmax(Wy @ h[t] + by)
         if targets[t] >= 0:
@@ -136,7 +143,7 @@ def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets):
             dl = probs[t].copy(); dl[targets[t]] -= 1.0
         G["Wy"] += np.outer(dl, h[t]); G["by"] += dl
         da = (Wy.T @ dl + dh_next) * (1 - h[t] ** 2)
-        hp = h[t - 1] if t > 0 else np.zeros(H)
+        hp = h[t - 1] if t > 0 else h0
         G["Wx"] += np.outer(da, xs[t]); G["Wh"] += np.outer(da, hp); G["bh"] += da
         dh_next = Wh.T @ da
     return loss, probs, G, h
