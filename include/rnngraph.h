@@ -20,7 +20,10 @@
  *    void*; NULL = the default stream).
  *  - Frames x streams x units tensors are time-major row-major: element (t, n, i) of a node of
  *    width dim lives at ((t * N + n) * dim + i), t in [0, T), n in [0, N).
- *  - Activations before the window are zero; error terms from frames after the window are zero.
+ *  - A fresh window (rnn_forward) starts from zero activations; a window moved ahead with
+ *    rnn_shift_window starts from the activations the earlier frames left (Section 3.2).  Error
+ *    terms from frames after the window are zero, and errors are back-propagated through the
+ *    window's own frames only (Section 2.2: "while t > t0'").
  *  - All arithmetic is fp32.  Gradients are dE_total/dW, summed (not averaged) over frames
  *    and streams, E_total = sum over frames, streams and output nodes of -ln y_target.
  */
@@ -41,8 +44,9 @@ enum rnn_status {
     RNN_ERR_INVALID_GRAPH = -2,    /* the node / edge list violates a rule listed at rnn_graph_create */
     RNN_ERR_WORKSPACE = -3,        /* workspace NULL, misaligned or too small */
     RNN_ERR_SEQUENCE = -4,         /* rnn_bptt before rnn_forward, rnn_grads before rnn_bptt */
-    RNN_ERR_DEVICE = -5,           /* a HIP call failed, or a kernel reported a wait that ran into its limit or a
-                                      workgroup placement other than the one observed for the device */
+    RNN_ERR_DEVICE = -5,           /* a HIP call failed, a specialised kernel could not be built, loaded or launched, or a
+                                      kernel reported a wait that ran into its limit or a workgroup placement other than
+                                      the one observed for the device */
     RNN_ERR_NO_MEMORY = -6
 };
 
@@ -101,9 +105,10 @@ int64_t rnn_param_count(const rnn_graph* g);
 int rnn_edge_param_offset(const rnn_graph* g, int32_t edge, int64_t* off, int64_t* len);
 int rnn_bias_param_offset(const rnn_graph* g, int32_t node, int64_t* off, int64_t* len);
 
-/* Bytes of DEVICE workspace needed for a window of T frames and N streams (activations and
- * error terms of every node for every frame, the plan tables and step-barrier words).
- * Negative rnn_status on error. */
+/* Bytes of DEVICE workspace needed for a window of T frames and N streams: the plan tables, 1 KiB
+ * of control words (E_total, error flags) and, per node, activations and error terms for every
+ * frame of the window plus d_max history frames in front of it (d_max = the longest delay of any
+ * connection), which hold what the frames before the window left.  Negative rnn_status on error. */
 int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N);
 
 /* Forward pass over one window (Section 2.1 equations on the Section 3.1 schedule).
@@ -126,7 +131,8 @@ int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inpu
  * Frames [0, t_begin) must already hold the results of earlier calls on the same workspace with
  * the same T and N (RNN_ERR_SEQUENCE otherwise): delayed connections read them as y(t - d), so a
  * window computed in pieces equals the window computed at once.  Arguments as in rnn_forward,
- * which is rnn_forward_range(.., 0, T, ..).  rnn_bptt needs the whole window computed. */
+ * which is rnn_forward_range(.., 0, T, ..).  A call with t_begin = 0 starts a fresh window: zero
+ * state in front of it, control words cleared.  rnn_bptt needs the whole window computed. */
 int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* d_inputs,
                       int32_t T, int32_t N, int32_t t_begin, int32_t t_end,
                       void* d_workspace, int64_t ws_bytes, void* hip_stream);
@@ -145,8 +151,14 @@ int rnn_set_onehot_input(rnn_graph* g, int32_t input, const int32_t* d_indices);
  * frame t + frames become those of frame t, for t < T - frames; the last `frames` frames are then
  * undefined until rnn_forward_range(.., T - frames, T, ..) has computed them from the caller's
  * equally shifted input tensors.  1 <= frames < T; needs a completely computed window.
- * Activations older than the window start are dropped: a delayed connection longer than
- * T - frames reads zeros there (Section 2.2's truncation at the window). */
+ * The d_max frames in front of the new window start are kept as history (for an input node with a
+ * delayed or element-wise out-connection the library keeps its own copy, so the caller may
+ * overwrite its tensors right away): delayed connections read them in the forward pass, and in
+ * the backward pass the connection outputs z_n(t) of multiplicative layers and the weight-gradient
+ * terms eps_m(t) y_k(t - d_m)^T of the window's first frames use them, as the last two equations
+ * of Section 2.2 say (only the back-propagation of delta and epsilon stops at the window start).
+ * One-hot inputs given as class indices keep no history: their delayed connections see zero
+ * vectors before the window start. */
 int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream);
 
 /* DEVICE view of node's activations y [T][N][dim] inside the workspace of the last rnn_forward
@@ -156,7 +168,9 @@ int rnn_output(const rnn_graph* g, int32_t node, const float** d_y);
 /* Backward pass (Section 2.2: output delta from softmax + cross-entropy, delta and epsilon
  * back-propagated through the reversed schedule) for the window of the last rnn_forward.
  *   d_targets  HOST array with one DEVICE pointer per output node, in increasing node id, each
- *              an int32 [T][N] tensor of class indices; -1 means "no error at this frame".
+ *              an int32 [T][N] tensor of class indices; -1 means "no error at this frame".  An
+ *              index not below the layer's width leaves its frame out and raises a flag that
+ *              rnn_check and rnn_grads(loss) report as RNN_ERR_INVALID_ARGUMENT.
  * d_weights must hold the same values as in rnn_forward. */
 int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targets, void* hip_stream);
 
@@ -166,40 +180,28 @@ int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds);
 
 /* Weight gradients (last equation of Section 2.2, summed over the N streams as in Section 3.2).
  *   d_grads  DEVICE, rnn_param_count floats, overwritten with dE_total/dW in the parameter layout.
- *   loss     HOST double or NULL; if given the call synchronises the stream and stores E_total. */
+ *   loss     HOST double or NULL; if given the call synchronises the stream, stores E_total and
+ *            reports the window's error flags like rnn_check. */
 int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream);
+
+/* Waits for hip_stream and reports what the kernels of the current window have flagged since its
+ * rnn_forward (or rnn_forward_range(.., 0, ..)): RNN_ERR_DEVICE if a recurrent step kernel gave up
+ * a bounded wait or found itself on another XCD than observed (the window's activations and
+ * gradients are then invalid), RNN_ERR_INVALID_ARGUMENT for a target index out of range, else
+ * RNN_OK.  The asynchronous calls cannot report these themselves: callers that never pass `loss`
+ * to rnn_grads call this once per window, or every so many windows. */
+int rnn_check(rnn_graph* g, void* hip_stream);
 
 /* The recurrent-step kernel is specialised at run time for each recurrent node's element-wise
  * step program (compiled with hiprtc on first use, cached per process by program structure).
  * rnn_specialise compiles the kernels this graph needs for N streams ahead of the first window;
  * it needs no GPU.  Returns the number of kernels compiled or found in the cache (0 if N is
  * served by kernels that are not specialised), or RNN_ERR_DEVICE with the compiler log as
- * message.  If specialisation is unavailable at run time the library falls back to the
- * interpreting build of the same kernel; RNNG_JIT=0 in the environment forces that. */
+ * message.  Only where the run-time compiler cannot be loaded at all (no libhiprtc.so), or with
+ * RNNG_JIT=0 in the environment, the interpreting build of the same kernel takes over; a
+ * specialised kernel that fails to compile, load or launch is an error of the call that needs it,
+ * never a silent change of build (rnn_step_build in rnngraph_aux.h tells which build ran). */
 int rnn_specialise(rnn_graph* g, int32_t N);
-
-/* Debugging aid: synchronises the device and copies the first `bytes` (at most 1024) of the
- * workspace's control-word area to HOST memory: E_total (double) at byte 0, the step kernels'
- * wait-limit flag (uint32) at byte 16, and, if the step kernels were built with RNNG_STEP_TRACE=1
- * in the environment, 64 cycle stamps (uint64) at byte 80. */
-int rnn_debug_read_control(rnn_graph* g, void* out, int32_t bytes);
-
-/* Kernel-class timing for benchmarks: HIP events are recorded on the call's stream around the
- * launches of every class whose bit is set in class_mask (0 switches timing off; it is off by
- * default and costs nothing then).  rnn_profile_read waits for the recorded events, stores the
- * summed duration in milliseconds and the number of kernel launches of that class since the
- * last read (HOST pointers, either may be NULL) and resets both. */
-enum {
-    RNN_PROF_STEP_FWD = 0,   /* recurrent-node forward step kernels (Section 3.1 sequential part) */
-    RNN_PROF_STEP_BWD = 1,   /* recurrent-node backward step kernels */
-    RNN_PROF_GEMM_FWD = 2,   /* batched forward edge products */
-    RNN_PROF_GEMM_BWD = 3,   /* batched backward edge products */
-    RNN_PROF_GEMM_GRAD = 4,  /* weight-gradient GEMMs */
-    RNN_PROF_OTHER = 5,      /* element-wise programs over all frames, softmax, reductions, fills */
-    RNN_PROF_CLASSES = 6
-};
-int rnn_profile_enable(rnn_graph* g, int32_t class_mask);
-int rnn_profile_read(rnn_graph* g, int32_t cls, double* ms, int64_t* launches);
 
 /* Message for the last error on this thread (never NULL). */
 const char* rnn_last_error(void);

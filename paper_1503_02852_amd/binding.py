@@ -15,10 +15,11 @@ LIB_PATH = os.path.join(_HERE, "librnngraph.so")
 EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_param_count",
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
            "rnn_forward_range", "rnn_shift_window", "rnn_set_onehot_input",
-           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_specialise", "rnn_debug_read_control",
-           "rnn_profile_enable",
-           "rnn_profile_read",
+           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_check", "rnn_specialise",
            "rnn_last_error"]
+# measurement and inspection aids (include/rnngraph_aux.h)
+AUX_EXPORTS = ["rnn_step_build", "rnn_debug_read_control", "rnn_profile_enable", "rnn_profile_read", "rnn_plan_work"]
+BUILD_NAMES = {0: "none", 1: "wave", 2: "matrix", 3: "matrix_2d", 4: "lds", 5: "interpreted", 6: "per_frame", 7: "streaming"}
 
 _lib = None
 
@@ -71,6 +72,12 @@ def load_library(build_if_missing=True):
     lib.rnn_state_grad.restype = C.c_int
     lib.rnn_grads.argtypes = [vp, vp, C.POINTER(C.c_double), vp]
     lib.rnn_grads.restype = C.c_int
+    lib.rnn_check.argtypes = [vp, vp]
+    lib.rnn_check.restype = C.c_int
+    lib.rnn_step_build.argtypes = [vp, C.c_int32, C.c_int32, i32p]
+    lib.rnn_step_build.restype = C.c_int
+    lib.rnn_plan_work.argtypes = [vp, C.c_int32, C.c_int32, i64p, i64p]
+    lib.rnn_plan_work.restype = C.c_int
     lib.rnn_specialise.argtypes = [vp, C.c_int32]
     lib.rnn_specialise.restype = C.c_int
     lib.rnn_debug_read_control.argtypes = [vp, vp, C.c_int32]
@@ -207,6 +214,20 @@ class Graph:
 
     def specialise(self, N):
         return _check(self.lib.rnn_specialise(self.handle, N))
+
+    def check(self, stream=0):
+        _check(self.lib.rnn_check(self.handle, stream))
+
+    def step_build(self, node, backward=False):
+        """(name of the step-kernel build that last ran the recurrent node of `node`, shared a chain launch)."""
+        b = C.c_int32()
+        _check(self.lib.rnn_step_build(self.handle, node, 1 if backward else 0, C.byref(b)))
+        return BUILD_NAMES[b.value & 15], bool(b.value & 16)
+
+    def plan_work(self, T, N):
+        fl, by = (C.c_int64 * 5)(), (C.c_int64 * 2)()
+        _check(self.lib.rnn_plan_work(self.handle, T, N, fl, by))
+        return dict(zip(("gemm_fwd", "gemm_bwd", "gemm_grad", "step_fwd", "step_bwd"), list(fl))), dict(step_fwd=by[0], step_bwd=by[1])
 
     def debug_read_control(self, nbytes=1024):
         buf = (C.c_ubyte * nbytes)()

@@ -4,13 +4,17 @@
 #include <cstdio>
 #include <cstdlib>
 #include <algorithm>
+#include <array>
+#include <tuple>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "../../include/rnngraph.h"
+#include "../../include/rnngraph_aux.h"
 #include "jit.h"
 #include "kernels.h"
 #include "plan.h"
@@ -33,6 +37,7 @@ struct Layout {
     int64_t sync_off = 0;                 // 1 KiB of zero-initialised control words; the loss (double) sits at its start
     std::vector<int64_t> buf_off;         // per buffer id, bytes; -1 = not in the workspace
     int64_t partial_off = -1;             // partial sums of the two-dimensional matrix-core kernels (one launch at a time)
+    int64_t flags_off = 0;                // per buffer id: 1 = frame tensor of the workspace (has history frames)
     int64_t total = 0;
 };
 constexpr int64_t SYNC_BYTES = 1024;
@@ -47,13 +52,14 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats) {
     int64_t cur = 0;
     L.table_off = cur; cur += (int64_t)P.n_bufs * 8;
     L.dims_off = cur; cur += (int64_t)P.n_bufs * 4;
+    L.flags_off = cur; cur += (int64_t)P.n_bufs * 4;
     cur = align_up(cur, 16);
     L.words_off = cur; cur += (int64_t)P.words.size() * 4;
     L.blob_bytes = cur;
     cur = align_up(cur, 256);
     L.sync_off = cur; cur += SYNC_BYTES;
     L.buf_off.assign(P.n_bufs, -1);
-    const int64_t F = (int64_t)T * N;
+    const int64_t F = (int64_t)(T + P.hist) * N;      // every frame tensor has P.hist history frames in front
     (void)K;
     for (int b = 0; b < P.n_bufs; ++b) {
         if (!P.buf_alloc[b]) continue;
@@ -64,7 +70,7 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats) {
         cur += g_layout_skew * (1 + n_alloc % 13);
         ++n_alloc;
     }
-    if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)T * partial_floats * 4, 256); }
+    if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)(T + P.hist) * partial_floats * 4, 256); }
     L.total = cur;
     return L;
 }
@@ -114,8 +120,11 @@ struct XcdMap { bool known = false, ok = false; int xcc[8] = {0, 0, 0, 0, 0, 0, 
 struct rnn_graph {
     Plan plan;
     Profiler prof;
-    // state of the current window
+    // state of the current window: T frames as the caller counts them; inside the library a frame
+    // tensor has Ti() = hist() + T frames, the caller's frame t being internal frame hist() + t
     int T = 0, N = 0;
+    int hist() const { return plan.hist; }
+    int Ti() const { return T + plan.hist; }
     char* ws = nullptr;
     Layout layout;
     std::vector<char> blob;               // host copy of the plan tables (kept alive for the async upload)
@@ -126,6 +135,7 @@ struct rnn_graph {
     bool fwd_done = false, bptt_done = false;
     int fwd_upto = 0;                     // frames [0, fwd_upto) of the current window hold forward results
     bool framewise = false;               // benchmark mode: every frame on its own, no batching over frames
+    bool no_alloc = false;                // inside rnn_forward_static: load no code, create no events, stage no host copies
     PlanView view() const {
         PlanView pv;
         pv.buf_ptr = reinterpret_cast<float* const*>(ws + layout.table_off);
@@ -133,23 +143,35 @@ struct rnn_graph {
         pv.words = reinterpret_cast<const int32_t*>(ws + layout.words_off);
         return pv;
     }
+    // internal frame 0 of a workspace tensor; for an input read in place: the caller's tensor
+    // (its frame 0 is internal frame hist())
     float* buf(int id) const {
         if (layout.buf_off[id] >= 0) return reinterpret_cast<float*>(ws + layout.buf_off[id]);
         if (id < (int)inputs.size() && inputs[id]) return const_cast<float*>(inputs[id]);
         return nullptr;
     }
+    bool caller_input(int id) const { return layout.buf_off[id] < 0 && id < (int)inputs.size() && inputs[id] != nullptr; }
+    // the caller's frame 0 of a workspace tensor
+    float* frame0(int id) const { return buf(id) + (caller_input(id) ? 0 : (int64_t)hist() * N * plan.buf_dim[id]); }
     bool is_onehot(int buf) const { return buf >= 0 && buf < (int)onehot.size() && onehot[buf] != nullptr; }
     double* loss_ptr() const { return reinterpret_cast<double*>(ws + layout.sync_off); }
     unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
     int force_step_G = 0;
+    int spin_limit = 1 << 22;             // bound of every wait inside a step kernel (polling attempts)
+    int cu_count = 0;                     // compute units of the device of the current window (0: not asked yet)
+    // which build ran the step loop of component c in direction d at its last launch (RNN_BUILD_*, 0: none yet)
+    std::vector<std::array<int, 2>> served;
     bool use_jit = true;
     bool use_store_window = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
+    struct JitChoice { bool wave = false, mstep = false, stream = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
-    std::map<long long, JitChoice> jit_choices;
+    // the workgroups of a step launch wait for each other, so all of them must be resident at once:
+    // one per compute unit (256 on a whole MI355X, fewer on a partition)
+    int max_workgroups() const { return cu_count > 0 ? cu_count : 256; }
+    std::map<std::tuple<int, bool, int>, JitChoice> jit_choices;
     const JitChoice& jit_choice(int comp, bool backward, int N) {
-        const long long key = ((long long)comp * 2 + (backward ? 1 : 0)) * 4096 + N;
+        const std::tuple<int, bool, int> key(comp, backward, N);
         auto it = jit_choices.find(key);
         if (it != jit_choices.end()) return it->second;
         JitChoice c;
@@ -158,6 +180,7 @@ struct rnn_graph {
         const int wave_G[6] = {32, 64, 128, 256, 16, 8};
         for (int i = 0; i < 6 && c.source.empty(); ++i) {
             const int G = force_step_G > 0 ? force_step_G : wave_G[i];
+            if (G > max_workgroups()) { if (force_step_G > 0) break; continue; }
             c.source = jit_wave_source(plan, cp, backward, N, G);
             if (!c.source.empty()) {
                 c.wave = true; c.lp.ok = true; c.lp.G = G; c.lp.NB = step_nb_for(N); c.lp.lds_bytes = 0;
@@ -172,7 +195,7 @@ struct rnn_graph {
         //     few rows: then the one-dimensional split wastes most of its 16-row tiles, whereas
         //     here several workgroups' rows share a tile and the partial sums stay small; measured
         //     on generalized_n64: backward (4 rows) faster, forward (16 rows) slower)
-        if (c.source.empty() && N > 8 && force_step_G <= 0 && force_step_J <= 0 &&
+        if (c.source.empty() && N > 8 && force_step_G <= 0 && force_step_J <= 0 && max_workgroups() >= 256 &&
             !(std::getenv("RNNG_MSTEP_2D") && std::atoi(std::getenv("RNNG_MSTEP_2D")) == 0)) {
             StepLayout lay;
             compute_step_layout(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, 256, 1, N, lay);
@@ -190,7 +213,7 @@ struct rnn_graph {
                 if (src.empty() && gj != 16) src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
                 if (!src.empty()) {
                     c.source = src; c.lp.ok = true; c.lp.G = 256; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
-                    c.two_d = true; c.partial_floats = pf;
+                    c.two_d = true; c.mstep = true; c.partial_floats = pf;
                 }
             }
         }
@@ -203,11 +226,12 @@ struct rnn_graph {
                 JitChoice best; int best_rows = -1;
                 for (int G : {256, 128, 64, 32, 16}) {
                     if (force_step_G > 0 && G != force_step_G) continue;
+                    if (G * J > max_workgroups()) continue;
                     size_t lds = 0; int rows = 0;
                     std::string src = jit_mstep_source(plan, cp, backward, N, G, J, &lds, &rows);
                     if (src.empty()) continue;
                     if (best_rows < 0 || (best_rows < 16 && rows > best_rows)) {      // first hit = most workgroups; move to fewer only to fill a tile
-                        best.source = src; best.lp.ok = true; best.lp.G = G; best.lp.NB = 1; best.lp.lds_bytes = lds; best.J = J;
+                        best.source = src; best.mstep = true; best.lp.ok = true; best.lp.G = G; best.lp.NB = 1; best.lp.lds_bytes = lds; best.J = J;
                         best.lp.xcd_stride = G * J <= 32 ? 8 : 1;
                         best_rows = rows;
                     }
@@ -241,10 +265,10 @@ struct rnn_graph {
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
     // workgroups shared among the members).
     struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false; size_t lds_bytes = 0; };
-    std::map<long long, ChainChoice> chain_choices;
+    std::map<std::tuple<int, bool, int>, ChainChoice> chain_choices;
     bool use_chains = true;
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
-        const long long key = ((long long)chain * 2 + (backward ? 1 : 0)) * 4096 + N;
+        const std::tuple<int, bool, int> key(chain, backward, N);
         auto it = chain_choices.find(key);
         if (it != chain_choices.end()) return it->second;
         ChainChoice c;
@@ -262,7 +286,7 @@ struct rnn_graph {
                 // matrix-core members: each gets an equal share of the 256 workgroups; per member the
                 // most stream groups, then the most unit chunks that fit the share (as for a single
                 // component: fewer only while a workgroup does not fill a 16-row tile)
-                const int share = 256 / (int)ch.members.size();
+                const int share = std::min(256, max_workgroups()) / (int)ch.members.size();
                 c.G.clear(); c.J.clear();
                 for (const CompPlan& m : ch.members) {
                     int pg = 0, pj = 0, best_rows = -1;
@@ -295,7 +319,8 @@ namespace {
 // GEMM_MAX_PROBLEMS destinations per launch and GEMM_MAX_PAIRS products per destination.
 // Rows of frames [t0, t1) only.
 hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bool backward, hipStream_t s, int t0, int t1) {
-    const int64_t F = (int64_t)g->T * g->N;
+    // t0, t1: internal frames
+    const int64_t F = (int64_t)g->Ti() * g->N, HN = (int64_t)g->hist() * g->N;
     const int64_t r0 = (int64_t)t0 * g->N, rows = (int64_t)(t1 - t0) * g->N;
     if (probs.empty() || rows <= 0) return hipSuccess;
     const int prof = g->prof.begin(backward ? RNN_PROF_GEMM_BWD : RNN_PROF_GEMM_FWD, s);
@@ -340,6 +365,8 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
                 o.A = g->buf(pr.a_buf); o.B = g->weights + pr.b_w_off; o.K = pr.k_len; o.lda = pr.k_len;
                 o.ldb = backward ? pp.n : pr.k_len;
                 o.a_row_off = (int)r0 + (backward ? pr.delay : -pr.delay) * g->N; o.a_rows = (int)F;
+                // an input read in place has the window's frames only: its row 0 is internal row HN
+                if (g->caller_input(pr.a_buf)) { o.a_row_off -= (int)HN; o.a_rows = (int)(F - HN); }
             }
             if (++grp.n_problems == GEMM_MAX_PROBLEMS) { hipError_t e = flush(); if (e != hipSuccess) return e; }
         }
@@ -352,8 +379,9 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
             for (const GemmPairPlan& pr : pp.pairs) if (!g->is_onehot(pr.a_buf)) first = false;      // the GEMMs have written C
             for (const GemmPairPlan& pr : pp.pairs) {
                 if (!g->is_onehot(pr.a_buf)) continue;
+                // the class indices are the caller's [T][N]: no history, frames before the window read as zero vectors
                 hipError_t e = launch_onehot_gather(g->buf(pp.c_buf), g->weights + pr.b_w_off, g->onehot[pr.a_buf], pp.n, pr.k_len, r0, rows,
-                                                    (int64_t)pr.delay * g->N, F, !first, s);
+                                                    HN + (int64_t)pr.delay * g->N, F - HN, !first, s);
                 if (e != hipSuccess) return e;
                 first = false; ++n_launch;
             }
@@ -396,11 +424,10 @@ hipError_t ensure_xcd_map(unsigned* scratch, hipStream_t s, const XcdMap** out) 
 bool wave_tensor_sizes_ok(const rnn_graph* g) {
     int64_t maxdim = 1;
     for (int b = 0; b < g->plan.n_bufs; ++b) {
-        bool is_input = false;      // the caller's input tensors are never stored by a step kernel
-        for (int k : g->plan.input_nodes) is_input = is_input || g->plan.ybuf(k) == b;
-        if (!is_input) maxdim = std::max<int64_t>(maxdim, g->plan.buf_dim[b]);
+        // the caller's input tensors are never stored by a step kernel
+        if (!g->caller_input(b)) maxdim = std::max<int64_t>(maxdim, g->plan.buf_dim[b]);
     }
-    return (int64_t)g->T * g->N * maxdim * 4 < (int64_t(1) << 30);
+    return (int64_t)g->Ti() * g->N * maxdim * 4 < (int64_t(1) << 30);
 }
 
 // The wave-autonomous kernels can store through ONE buffer descriptor when everything they store
@@ -410,12 +437,10 @@ bool wave_tensor_sizes_ok(const rnn_graph* g) {
 bool wave_store_window_ok(const rnn_graph* g) {
     if (!g->use_store_window || g->layout.total > (int64_t(1) << 31)) return false;
     for (int b = 0; b < g->plan.n_bufs; ++b) {
-        bool is_input = false;
-        for (int k : g->plan.input_nodes) is_input = is_input || g->plan.ybuf(k) == b;
-        if (is_input) continue;
+        if (g->caller_input(b)) continue;
         const char* p = reinterpret_cast<const char*>(g->buf(b));
         if (p == nullptr) continue;      // no storage: never stored
-        const int64_t bytes = (int64_t)g->T * g->N * g->plan.buf_dim[b] * 4;
+        const int64_t bytes = (int64_t)g->Ti() * g->N * g->plan.buf_dim[b] * 4;
         if (p < g->ws || p + bytes > g->ws + g->layout.total) return false;
     }
     return true;
@@ -443,96 +468,130 @@ hipError_t fill_shared(rnn_graph* g, const std::vector<int>& bufs, bool with_bun
     return hipSuccess;
 }
 
-hipError_t run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0, int t1) {
+// The workgroups of a persistent step launch wait for each other's results, so every one that takes
+// part must be resident at the same time: at most one per compute unit (each takes most of a CU's
+// LDS or registers).  A launch that cannot be co-resident is refused here, before it could hang.
+bool launch_fits_device(const rnn_graph* g, int participants, std::string& why) {
+    if (participants <= g->max_workgroups()) return true;
+    why = "the step kernel needs " + std::to_string(participants) + " co-resident workgroups, the device has " +
+          std::to_string(g->max_workgroups()) + " compute units";
+    return false;
+}
+
+// Result of a step-kernel launch attempt.  A specialised kernel that exists but cannot be compiled,
+// loaded or launched is an error (text in `err`), never a silent switch to another build; only
+// "there is no such kernel for this component" (or no run-time compiler on this machine) moves on
+// to the next build.
+struct StepRun { hipError_t e = hipSuccess; bool error = false; int code = RNN_ERR_DEVICE; std::string err; };
+StepRun step_error(hipError_t e, const std::string& what, int code = RNN_ERR_DEVICE) {
+    StepRun r; r.e = e == hipSuccess ? hipErrorUnknown : e; r.error = true; r.code = code;
+    r.err = what + (e != hipSuccess ? std::string(": ") + hipGetErrorString(e) : std::string());
+    return r;
+}
+
+// t0, t1: internal frames
+StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0, int t1) {
     const CompPlan& cp = g->plan.comps[comp];
     const PlanView pv = g->view();
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
-    const int T = g->T, N = g->N;
+    const int T = g->Ti(), N = g->N;
+    StepRun ok;
     if (!cp.recurrent) {
         const int prof = g->prof.begin(RNN_PROF_OTHER, s);
         for (const PhasePlan& ph : phases) {
             hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, t0, t1, s);
-            if (e != hipSuccess) return e;
+            if (e != hipSuccess) return step_error(e, "node program launch");
         }
         g->prof.end(prof, (int64_t)phases.size(), s);
-        return hipSuccess;
+        return ok;
     }
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     int64_t n_launch = 0;
-    // Persistent kernel: all T steps in one launch.  First choice is the build specialised at run
-    // time for this component; the interpreting build serves components it cannot take or when
-    // the run-time compiler is unavailable; stepping with per-frame launches is the last resort.
+    int& served = g->served[comp][backward ? 1 : 0];
+    // Persistent kernel: all steps in one launch.  First choice is the build specialised at run
+    // time for this component; the interpreting build serves components no specialised build
+    // takes, or all of them when the run-time compiler is unavailable; stepping with per-frame
+    // launches is the last resort.
     StepLaunchPlan lp;
     const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
-    rnn_graph::JitChoice* jc = g->use_jit ? const_cast<rnn_graph::JitChoice*>(&g->jit_choice(comp, backward, N)) : nullptr;
+    rnn_graph::JitChoice* jc = (g->use_jit && jit_available()) ? const_cast<rnn_graph::JitChoice*>(&g->jit_choice(comp, backward, N)) : nullptr;
     const bool have_jit = jc && !jc->source.empty() && !g->framewise && (!jc->wave || wave_tensor_sizes_ok(g));
     const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
-    if (have_jit || have_interp) {
-        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, have_jit && jc->wave, t0, t1, s);
-        if (fe != hipSuccess) return fe;
-        const int spin_limit = 1 << 22;
-        hipError_t e = hipErrorUnknown;
-        if (have_jit) {
-            const bool window = jc->wave && wave_store_window_ok(g);
-            if (hipFunction_t fn = jit_step_function(window ? windowed(jc->source, jc->source_window) : jc->source)) {
-                StepArgs a;
-                fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
-                if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
-                a.J = jc->J;
-                if (jc->two_d) {
-                    if (g->layout.partial_off < 0) return hipErrorInvalidValue;
-                    a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
-                    e = launch_fill_sentinel(a.partial + (int64_t)t0 * jc->partial_floats, (int64_t)(t1 - t0) * jc->partial_floats, s);
-                    if (e != hipSuccess) return e;
-                    e = hipErrorUnknown;
-                }
-                if (jc->wave && jc->lp.xcd_stride == 8 && g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[0] = g->xcd->xcc[0];
-                StepLaunchPlan lp_all = jc->lp;
-                lp_all.G = jc->lp.G * jc->J;       // launch size; a.G stays the number of unit chunks
-                e = jit_launch(fn, a, lp_all, s);
-                if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(jc->source); }
-            }
+    const int spin_limit = g->spin_limit;
+    if (have_jit) {
+        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, jc->wave, t0, t1, s);
+        if (fe != hipSuccess) return step_error(fe, "sentinel fill");
+        const bool window = jc->wave && wave_store_window_ok(g);
+        std::string why;
+        hipFunction_t fn = jit_step_function(window ? windowed(jc->source, jc->source_window) : jc->source, &why, !g->no_alloc);
+        if (!fn) return step_error(hipSuccess, "specialised step kernel unavailable: " + why, g->no_alloc ? RNN_ERR_SEQUENCE : RNN_ERR_DEVICE);
+        StepArgs a;
+        fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
+        if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
+        a.J = jc->J;
+        if (jc->two_d) {
+            if (g->layout.partial_off < 0) return step_error(hipErrorInvalidValue, "partial-sum tensor missing from the workspace");
+            a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
+            hipError_t e = launch_fill_sentinel(a.partial + (int64_t)t0 * jc->partial_floats, (int64_t)(t1 - t0) * jc->partial_floats, s);
+            if (e != hipSuccess) return step_error(e, "sentinel fill");
         }
-        if (e != hipSuccess && have_interp)
-            e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1, s);
-        if (e == hipSuccess) {
-            g->prof.end(prof, 1, s);
-            return hipSuccess;
-        }
-        if (have_interp) return e;
+        if (jc->wave && jc->lp.xcd_stride == 8 && g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[0] = g->xcd->xcc[0];
+        StepLaunchPlan lp_all = jc->lp;
+        lp_all.G = jc->lp.G * jc->J;       // launch size; a.G stays the number of unit chunks
+        if (!launch_fits_device(g, lp_all.G, why)) return step_error(hipSuccess, why);
+        hipError_t e = jit_launch(fn, a, lp_all, s);
+        if (e != hipSuccess) { (void)hipGetLastError(); return step_error(e, "specialised step kernel launch"); }
+        served = jc->wave ? RNN_BUILD_WAVE : jc->two_d ? RNN_BUILD_MATRIX_2D : jc->stream ? RNN_BUILD_STREAMING : jc->mstep ? RNN_BUILD_MATRIX : RNN_BUILD_LDS;
+        g->prof.end(prof, 1, s);
+        return ok;
+    }
+    if (have_interp) {
+        std::string why;
+        if (!launch_fits_device(g, lp.G, why)) return step_error(hipSuccess, why);
+        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, false, t0, t1, s);
+        if (fe != hipSuccess) return step_error(fe, "sentinel fill");
+        hipError_t e = launch_recurrent_steps(pv, lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1, s);
+        if (e != hipSuccess) return step_error(e, "interpreting step kernel launch");
+        served = RNN_BUILD_INTERPRETED;
+        g->prof.end(prof, 1, s);
+        return ok;
     }
     for (int step = 0; step < t1 - t0; ++step) {
         const int t = backward ? t1 - 1 - step : t0 + step;
         for (const PhasePlan& ph : phases) {
             if (ph.mv_off >= 0) {
                 hipError_t e = launch_step_matvec(pv, ph.mv_off, ph.n_mv_tasks, ph.mv_max_out, g->weights, T, N, t, s);
-                if (e != hipSuccess) return e;
+                if (e != hipSuccess) return step_error(e, "per-frame matrix-vector launch");
                 ++n_launch;
             }
             hipError_t e = launch_node_program(pv, ph.prog_off, ph.max_dim, g->weights, T, N, t, t + 1, s);
-            if (e != hipSuccess) return e;
+            if (e != hipSuccess) return step_error(e, "per-frame node program launch");
             ++n_launch;
         }
     }
+    served = RNN_BUILD_PER_FRAME;
     g->prof.end(prof, n_launch, s);
-    return hipSuccess;
+    return ok;
 }
 
-// All members of a chain in one persistent launch.  hipErrorNotSupported: no such kernel for this
-// chain (the caller then runs the members one after another).
-hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0, int t1) {
+// All members of a chain in one persistent launch.  e == hipErrorNotSupported without `error`: no
+// such kernel for this chain (the caller then runs the members one after another).
+StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0, int t1) {
     const ChainPlan& ch = g->plan.chains[chain];
+    StepRun none; none.e = hipErrorNotSupported;
+    if (!g->use_jit || !jit_available()) return none;
     rnn_graph::ChainChoice& cc = const_cast<rnn_graph::ChainChoice&>(g->chain_choice(chain, backward, g->N));
-    if (cc.source.empty() || (!cc.mstep && !wave_tensor_sizes_ok(g))) return hipErrorNotSupported;
+    if (cc.source.empty() || (!cc.mstep && !wave_tensor_sizes_ok(g))) return none;
     const bool window = !cc.mstep && wave_store_window_ok(g);
-    hipFunction_t fn = jit_step_function(window ? windowed(cc.source, cc.source_window) : cc.source);
-    if (!fn) return hipErrorNotSupported;
+    std::string why;
+    hipFunction_t fn = jit_step_function(window ? windowed(cc.source, cc.source_window) : cc.source, &why, !g->no_alloc);
+    if (!fn) return step_error(hipSuccess, "specialised chain step kernel unavailable: " + why, g->no_alloc ? RNN_ERR_SEQUENCE : RNN_ERR_DEVICE);
     const PlanView pv = g->view();
-    const int T = g->T, N = g->N;
+    const int T = g->Ti(), N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     for (const CompPlan& m : ch.members) {
         hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s);
-        if (e != hipSuccess) return e;
+        if (e != hipSuccess) return step_error(e, "sentinel fill");
     }
     StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;
     if (cc.mstep) {
@@ -541,7 +600,7 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int 
     }
     StepArgs a;
     fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
-                   T, N, backward, 1 << 22, t0, t1);
+                   T, N, backward, g->spin_limit, t0, t1);
     if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
     a.n_groups = (int)ch.members.size();
     for (int i = 0; i < a.n_groups; ++i) {
@@ -554,10 +613,15 @@ hipError_t run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int 
             a.xcc_expect[i] = g->xcd->xcc[i];
         }
     }
+    int participants = 0;
+    for (size_t i = 0; i < cc.G.size(); ++i) participants += cc.G[i] * (cc.mstep ? cc.J[i] : 1);
+    if (!launch_fits_device(g, participants, why)) return step_error(hipSuccess, why);
     hipError_t e = jit_launch(fn, a, lp, s);
-    if (e != hipSuccess) { (void)hipGetLastError(); jit_mark_failed(cc.source); return hipErrorNotSupported; }
+    if (e != hipSuccess) { (void)hipGetLastError(); return step_error(e, "specialised chain step kernel launch"); }
+    for (int c = ch.first; c <= ch.last; ++c) g->served[c][backward ? 1 : 0] = (cc.mstep ? RNN_BUILD_MATRIX : RNN_BUILD_WAVE) | RNN_BUILD_CHAIN;
     g->prof.end(prof, 1, s);
-    return hipSuccess;
+    StepRun ok;
+    return ok;
 }
 
 }  // namespace
@@ -579,6 +643,8 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (!g) return fail(RNN_ERR_NO_MEMORY, "out of host memory");
     std::string err;
     if (!build_plan(ns, es, g->plan, err)) { delete g; return fail(RNN_ERR_INVALID_GRAPH, err); }
+    g->served.assign(g->plan.comps.size(), std::array<int, 2>{0, 0});
+    if (const char* env = std::getenv("RNNG_SPIN_LIMIT")) g->spin_limit = std::max(1, std::atoi(env));
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
     if (const char* env = std::getenv("RNNG_STEP_STREAM_GROUPS")) g->force_step_J = std::atoi(env);
     if (const char* env = std::getenv("RNNG_CHAIN")) g->use_chains = std::atoi(env) != 0;
@@ -636,13 +702,28 @@ int rnn_bias_param_offset(const rnn_graph* g, int32_t node, int64_t* off, int64_
 int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
-    if ((int64_t)T * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
+    if ((int64_t)(T + g->plan.hist) * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
     return make_layout(g->plan, T, N, const_cast<rnn_graph*>(g)->partial_frame_floats(N)).total;
 }
 
 namespace {
 
-// Forward pass over frames [t0, t1) of the current window: components in schedule order.
+// Waits for the stream, then reads the control words of the current window: E_total (to *loss if
+// given) and the flags the kernels raise.  A raised flag means the window's results are invalid.
+int read_control(rnn_graph* g, double* loss, hipStream_t s) {
+    unsigned char back[32];
+    hipError_t e = hipMemcpyAsync(back, g->loss_ptr(), sizeof(back), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "control word read-back");
+    if (loss) std::memcpy(loss, back, sizeof(double));
+    unsigned flag; std::memcpy(&flag, back + 16, 4);
+    if (flag == 3) return fail(RNN_ERR_INVALID_ARGUMENT, "a target class index is not below the output layer's width (that frame was left out)");
+    if (flag == 2) return fail(RNN_ERR_DEVICE, "a recurrent step kernel's workgroup ran on another XCD than the probe launch had shown (results are invalid; RNNG_XCD_LOCAL=0 avoids the assumption)");
+    if (flag) return fail(RNN_ERR_DEVICE, "a recurrent step kernel ran into its wait limit (results are invalid)");
+    return RNN_OK;
+}
+
+// Forward pass over internal frames [t0, t1) of the current window: components in schedule order.
 int forward_frames(rnn_graph* g, int t0, int t1, hipStream_t s) {
     const Plan& P = g->plan;
     const int N = g->N;
@@ -658,14 +739,14 @@ int forward_frames(rnn_graph* g, int t0, int t1, hipStream_t s) {
                 e = run_gemms(g, m.fwd_gemms, false, s, t0, t1);
                 if (e != hipSuccess) return fail_hip(e, "forward GEMM");
             }
-            e = run_chain(g, cp.chain, false, s, t0, t1);
-            if (e == hipSuccess) { chain_done_to = ch.last; continue; }
-            if (e != hipErrorNotSupported) return fail_hip(e, "forward chain kernel");
+            const StepRun r = run_chain(g, cp.chain, false, s, t0, t1);
+            if (r.error) return fail(r.code, "forward: " + r.err);
+            if (r.e == hipSuccess) { chain_done_to = ch.last; continue; }
         }
         e = run_gemms(g, cp.fwd_gemms, false, s, t0, t1);
         if (e != hipSuccess) return fail_hip(e, "forward GEMM");
-        e = run_phases(g, c, false, s, t0, t1);
-        if (e != hipSuccess) return fail_hip(e, "forward node program");
+        const StepRun r = run_phases(g, c, false, s, t0, t1);
+        if (r.error) return fail(r.code, "forward: " + r.err);
         if (cp.softmax_node >= 0) {
             const int dim = P.xnodes[cp.softmax_node].dim;
             e = launch_softmax_rows(g->buf(P.ybuf(cp.softmax_node)) + (int64_t)t0 * N * dim, (int64_t)(t1 - t0) * N, dim, s);
@@ -682,14 +763,25 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (!d_weights || !d_inputs) return fail(RNN_ERR_INVALID_ARGUMENT, "weights / inputs pointer is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
-    if ((int64_t)T * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
+    if ((int64_t)(T + g->plan.hist) * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
     if (t_begin < 0 || t_end > T || t_begin >= t_end) return fail(RNN_ERR_INVALID_ARGUMENT, "frame range must satisfy 0 <= t_begin < t_end <= T");
     const Plan& P = g->plan;
     for (size_t i = 0; i < P.input_nodes.size(); ++i)
         if (!d_inputs[i] && !g->is_onehot(P.input_nodes[i])) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
-    Layout L = make_layout(P, T, N, g->partial_frame_floats(N));
     if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (ws_bytes < make_layout(P, T, N, g->partial_frame_floats(N)).total)
+        return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(make_layout(P, T, N, g->partial_frame_floats(N)).total) + " bytes");
+    if (g->cu_count == 0) {
+        // The step kernels' launch shapes depend on how many workgroups the device keeps resident.
+        int dev = 0, cus = 0;
+        hipError_t qe = hipGetDevice(&dev);
+        if (qe == hipSuccess) qe = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (qe != hipSuccess || cus <= 0) return fail_hip(qe, "device query");
+        if (cus != g->max_workgroups()) { g->jit_choices.clear(); g->chain_choices.clear(); }      // chosen for a whole device
+        g->cu_count = cus;
+    }
+    Layout L = make_layout(P, T, N, g->partial_frame_floats(N));
     if (ws_bytes < L.total) return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(L.total) + " bytes");
     if (t_begin > 0) {
         // the earlier frames must be there: same window shape and workspace, computed up to t_begin
@@ -710,23 +802,48 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
         std::memcpy(&g->blob[L.table_off + 8 * (int64_t)b], &p, 8);
     }
     std::memcpy(&g->blob[L.dims_off], P.buf_dim.data(), (size_t)P.n_bufs * 4);
+    for (int b = 0; b < P.n_bufs; ++b) {
+        const int32_t flag = (P.buf_alloc[b] == 1 && L.buf_off[b] >= 0) ? 1 : 0;
+        std::memcpy(&g->blob[L.flags_off + 4 * (int64_t)b], &flag, 4);
+    }
     if (!P.words.empty()) std::memcpy(&g->blob[L.words_off], P.words.data(), P.words.size() * 4);
-    hipError_t e = hipMemcpyAsync(g->ws, g->blob.data(), (size_t)L.blob_bytes, hipMemcpyHostToDevice, s);
+    // (without allocations: as kernel arguments, which need no staging buffer of the runtime's)
+    hipError_t e = g->no_alloc ? launch_upload_words(reinterpret_cast<uint32_t*>(g->ws), reinterpret_cast<const uint32_t*>(g->blob.data()), L.blob_bytes / 4, s)
+                               : hipMemcpyAsync(g->ws, g->blob.data(), (size_t)L.blob_bytes, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail_hip(e, "plan table upload");
     if (!g->xcd) {
         e = ensure_xcd_map(reinterpret_cast<unsigned*>(g->ws + L.sync_off), s, &g->xcd);
         if (e != hipSuccess) return fail_hip(e, "XCD probe");
     }
-    e = launch_fill(reinterpret_cast<float*>(g->ws + L.sync_off), SYNC_BYTES / 4, 0.0f, s);
-    if (e != hipSuccess) return fail_hip(e, "control word reset");
+    const int H = P.hist;
+    if (t_begin == 0) {
+        // A new window: the control words (loss, error flags) start at zero, and so do the history
+        // frames in front of every frame tensor (the state before a fresh window is zero).  Pieces
+        // of a window computed later keep the flags an earlier piece has raised.
+        e = launch_fill(reinterpret_cast<float*>(g->ws + L.sync_off), SYNC_BYTES / 4, 0.0f, s);
+        if (e != hipSuccess) return fail_hip(e, "control word reset");
+        if (H > 0) {
+            e = launch_zero_history(g->view().buf_ptr, g->view().buf_dim, reinterpret_cast<const int32_t*>(g->ws + L.flags_off), P.n_bufs, (int64_t)H * N, s);
+            if (e != hipSuccess) return fail_hip(e, "history reset");
+        }
+    }
+    // inputs that are not read in place: the new frames go behind the history frames of their copy
+    for (size_t i = 0; i < P.input_nodes.size(); ++i) {
+        const int k = P.input_nodes[i];
+        if (!P.input_staged[k] || g->is_onehot(k)) continue;
+        const int64_t fr = (int64_t)N * P.xnodes[k].dim;
+        e = hipMemcpyAsync(g->buf(P.ybuf(k)) + (int64_t)(H + t_begin) * fr, d_inputs[i] + (int64_t)t_begin * fr,
+                           (size_t)(t_end - t_begin) * fr * sizeof(float), hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail_hip(e, "input copy");
+    }
 
     if (g->framewise) {
         for (int t = t_begin; t < t_end; ++t) {
-            const int rc = forward_frames(g, t, t + 1, s);
+            const int rc = forward_frames(g, H + t, H + t + 1, s);
             if (rc != RNN_OK) return rc;
         }
     } else {
-        const int rc = forward_frames(g, t_begin, t_end, s);
+        const int rc = forward_frames(g, H + t_begin, H + t_end, s);
         if (rc != RNN_OK) return rc;
     }
     g->fwd_upto = t_end;
@@ -760,31 +877,33 @@ int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream) {
     if (frames <= 0 || frames >= g->T) return fail(RNN_ERR_INVALID_ARGUMENT, "frames must lie in [1, T - 1]");
     const Plan& P = g->plan;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int T = g->T;
-    // y(t) <- y(t + frames), block by block in stream order so that source and destination of one copy never overlap
-    for (size_t k = 0; k < P.xnodes.size(); ++k) {
-        const int b = P.ybuf((int)k);
-        if (P.xnodes[k].kind == NODE_INPUT || g->layout.buf_off[b] < 0) continue;
+    const int Ti = g->Ti();
+    // y(t) <- y(t + frames) for every stored frame, the history frames in front of the window
+    // included: they then hold the frames right before the new window start.  Block by block in
+    // stream order, so that source and destination of one copy never overlap.
+    auto shift = [&](int b) -> hipError_t {
         const int64_t fr = (int64_t)g->N * P.buf_dim[b];
         float* y = g->buf(b);
-        for (int t = 0; t + frames < T; t += frames) {
-            const int n = std::min(frames, T - frames - t);
+        for (int t = 0; t + frames < Ti; t += frames) {
+            const int n = std::min(frames, Ti - frames - t);
             hipError_t e = hipMemcpyAsync(y + t * fr, y + (t + frames) * fr, (size_t)n * fr * sizeof(float), hipMemcpyDeviceToDevice, s);
-            if (e != hipSuccess) return fail_hip(e, "window shift");
+            if (e != hipSuccess) return e;
         }
+        return hipSuccess;
+    };
+    for (size_t k = 0; k < P.xnodes.size(); ++k) {
+        const int b = P.ybuf((int)k);
+        if (g->layout.buf_off[b] < 0) continue;      // an input read in place: the caller shifts it
+        hipError_t e = shift(b);
+        if (e != hipSuccess) return fail_hip(e, "window shift");
     }
     // interleaved exchange tensors of forward activations move along with their members
     for (const BundlePlan& bp : P.bundles) {
         if (bp.members[0] >= (int)P.xnodes.size() || g->layout.buf_off[bp.ebuf] < 0) continue;
-        const int64_t fr = (int64_t)g->N * P.buf_dim[bp.ebuf];
-        float* y = g->buf(bp.ebuf);
-        for (int t = 0; t + frames < T; t += frames) {
-            const int n = std::min(frames, T - frames - t);
-            hipError_t e = hipMemcpyAsync(y + t * fr, y + (t + frames) * fr, (size_t)n * fr * sizeof(float), hipMemcpyDeviceToDevice, s);
-            if (e != hipSuccess) return fail_hip(e, "window shift");
-        }
+        hipError_t e = shift(bp.ebuf);
+        if (e != hipSuccess) return fail_hip(e, "window shift");
     }
-    g->fwd_upto = T - frames;
+    g->fwd_upto = g->T - frames;
     g->fwd_done = g->bptt_done = false;
     return RNN_OK;
 }
@@ -793,7 +912,8 @@ int rnn_output(const rnn_graph* g, int32_t node, const float** d_y) {
     if (!g || !d_y) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
     if (node < 0 || node >= (int)g->plan.nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "node index out of range");
     if (!g->fwd_done) return fail(RNN_ERR_SEQUENCE, "rnn_output before rnn_forward");
-    *d_y = g->buf(g->plan.ybuf(node));
+    const int b = g->plan.ybuf(node);
+    *d_y = g->plan.nodes[node].kind == NODE_INPUT ? g->inputs[b] : g->frame0(b);
     return RNN_OK;
 }
 
@@ -807,7 +927,7 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
         if (!d_targets[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "a target tensor pointer is NULL");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     g->weights = d_weights;
-    const int T = g->T, N = g->N;
+    const int T = g->T, N = g->N, H = g->hist();
     hipError_t e = launch_fill(reinterpret_cast<float*>(g->loss_ptr()), 2, 0.0f, s);
     if (e != hipSuccess) return fail_hip(e, "loss reset");
     // the output deltas of all frames first (they depend on the forward pass only)
@@ -816,7 +936,7 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
         const int k = cp.softmax_node;
         size_t oi = 0;
         while (oi < P.output_nodes.size() && P.output_nodes[oi] != k) ++oi;
-        e = launch_softmax_ce_delta(g->buf(P.ybuf(k)), d_targets[oi], g->buf(P.dbuf(k)), g->loss_ptr(),
+        e = launch_softmax_ce_delta(g->frame0(P.ybuf(k)), d_targets[oi], g->frame0(P.dbuf(k)), g->loss_ptr(), g->ctrl_ptr(),
                                     (int64_t)T * N, P.xnodes[k].dim, s);
         if (e != hipSuccess) return fail_hip(e, "softmax / cross-entropy delta");
     }
@@ -830,24 +950,26 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
                     e = run_gemms(g, m.bwd_gemms, true, s, t0, t1);
                     if (e != hipSuccess) return fail_hip(e, "backward GEMM");
                 }
-                e = run_chain(g, cp.chain, true, s, t0, t1);
-                if (e == hipSuccess) { c = ch.first; continue; }
-                if (e != hipErrorNotSupported) return fail_hip(e, "backward chain kernel");
+                const StepRun r = run_chain(g, cp.chain, true, s, t0, t1);
+                if (r.error) return fail(RNN_ERR_DEVICE, "backward: " + r.err);
+                if (r.e == hipSuccess) { c = ch.first; continue; }
             }
             e = run_gemms(g, cp.bwd_gemms, true, s, t0, t1);
             if (e != hipSuccess) return fail_hip(e, "backward GEMM");
-            e = run_phases(g, c, true, s, t0, t1);
-            if (e != hipSuccess) return fail_hip(e, "backward node program");
+            const StepRun r = run_phases(g, c, true, s, t0, t1);
+            if (r.error) return fail(RNN_ERR_DEVICE, "backward: " + r.err);
         }
         return RNN_OK;
     };
+    // Errors are back-propagated through the window's own frames only (Section 2.2: while t > t0');
+    // the history frames in front are read (y of earlier frames), never written.
     if (g->framewise) {
         for (int t = T - 1; t >= 0; --t) {
-            const int rc = backward_frames(t, t + 1);
+            const int rc = backward_frames(H + t, H + t + 1);
             if (rc != RNN_OK) return rc;
         }
     } else {
-        const int rc = backward_frames(0, T);
+        const int rc = backward_frames(H, H + T);
         if (rc != RNN_OK) return rc;
     }
     g->bptt_done = true;
@@ -859,7 +981,7 @@ int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds) {
     if (node < 0 || node >= (int)g->plan.nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "node index out of range");
     if (g->plan.nodes[node].kind == NODE_INPUT) return fail(RNN_ERR_INVALID_ARGUMENT, "input nodes have no state gradient");
     if (!g->bptt_done) return fail(RNN_ERR_SEQUENCE, "rnn_state_grad before rnn_bptt");
-    *d_ds = g->buf(g->plan.dbuf(node));
+    *d_ds = g->frame0(g->plan.dbuf(node));
     return RNN_OK;
 }
 
@@ -869,8 +991,8 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
     if (!d_grads) return fail(RNN_ERR_INVALID_ARGUMENT, "gradient pointer is NULL");
     const Plan& P = g->plan;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int T = g->T, N = g->N;
-    const int64_t F = (int64_t)T * N;
+    const int T = g->T, N = g->N, H = g->hist();
+    const int64_t F = (int64_t)T * N;      // the window's own frames: the sums run over t0' < t <= t1
     hipError_t e = launch_fill(d_grads, P.n_params, 0.0f, s);
     if (e != hipSuccess) return fail_hip(e, "gradient reset");
 
@@ -892,10 +1014,9 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
         return r;
     };
     for (const GradGemmPlan& gg : P.grad_gemms) {
-        const int64_t Kf = F - (int64_t)gg.delay * N;
-        if (Kf <= 0) continue;
-        if (g->is_onehot(gg.src_buf)) {      // scatter-add instead of a GEMM over a one-hot matrix
-            e = launch_onehot_scatter(d_grads + gg.w_off, g->buf(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F, s);
+        if (g->is_onehot(gg.src_buf)) {      // scatter-add instead of a GEMM over a one-hot matrix (indices have no history: frames before the window are zero vectors)
+            if (F - (int64_t)gg.delay * N <= 0) continue;
+            e = launch_onehot_scatter(d_grads + gg.w_off, g->frame0(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F, s);
             if (e != hipSuccess) return fail_hip(e, "one-hot weight gradient");
             ++n_launch;
             continue;
@@ -903,33 +1024,40 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
         GemmProblem& gp = grp.p[grp.n_problems];
         gp.C = d_grads + gg.w_off; gp.ldc = gg.n_src; gp.M = gg.n_dst; gp.N = gg.n_src; gp.n_pairs = 1;
         GemmPair& o = gp.pairs[0];
-        o.A = g->buf(gg.dst_buf) + (int64_t)gg.delay * N * gg.n_dst; o.lda = gg.n_dst;
-        o.B = g->buf(gg.src_buf); o.ldb = gg.n_src; o.K = (int)Kf; o.a_row_off = 0; o.a_rows = (int)Kf;
+        // eps_m(t) of every frame of the window against y_src(t - d); for the window's first d
+        // frames that is a history frame (the real activation of a frame before the window)
+        o.A = g->frame0(gg.dst_buf); o.lda = gg.n_dst;
+        o.B = g->frame0(gg.src_buf) - (int64_t)gg.delay * N * gg.n_src; o.ldb = gg.n_src; o.K = (int)F; o.a_row_off = 0; o.a_rows = (int)F;
         tiles += (int64_t)((gg.n_dst + 127) / 128) * ((gg.n_src + 127) / 128);
         if (++grp.n_problems == GEMM_MAX_PROBLEMS) { e = flush(); if (e != hipSuccess) return fail_hip(e, "gradient GEMM"); }
     }
     e = flush();
     if (e != hipSuccess) return fail_hip(e, "gradient GEMM");
     g->prof.end(prof, n_launch, s);
-    e = launch_colsum(g->view(), P.colsum_off, P.n_colsum, P.colsum_max_dim, g->weights, d_grads, T, N, s);
+    e = launch_colsum(g->view(), P.colsum_off, P.n_colsum, P.colsum_max_dim, g->weights, d_grads, H + T, N, H, s);
     if (e != hipSuccess) return fail_hip(e, "diagonal / bias gradient");
-    if (loss) {
-        unsigned char back[32];
-        e = hipMemcpyAsync(back, g->loss_ptr(), sizeof(back), hipMemcpyDeviceToHost, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) return fail_hip(e, "loss read-back");
-        std::memcpy(loss, back, sizeof(double));
-        unsigned flag; std::memcpy(&flag, back + 16, 4);
-        if (flag == 2) return fail(RNN_ERR_DEVICE, "a recurrent step kernel's workgroup ran on another XCD than the probe launch had shown (results are invalid; RNNG_XCD_LOCAL=0 avoids the assumption)");
-        if (flag) return fail(RNN_ERR_DEVICE, "a recurrent step kernel ran into its wait limit (results are invalid)");
-    }
+    if (loss) return read_control(g, loss, s);
+    return RNN_OK;
+}
+
+int rnn_check(rnn_graph* g, void* hip_stream) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (!g->ws) return fail(RNN_ERR_SEQUENCE, "no window yet");
+    return read_control(g, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+int rnn_step_build(const rnn_graph* g, int32_t node, int32_t backward, int32_t* build) {
+    if (!g || !build) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (node < 0 || node >= (int)g->plan.nodes.size()) return fail(RNN_ERR_INVALID_ARGUMENT, "node index out of range");
+    const int c = g->plan.xsched.node_comp[node];
+    *build = g->plan.comps[c].recurrent ? g->served[c][backward ? 1 : 0] : RNN_BUILD_NONE;
     return RNN_OK;
 }
 
 int rnn_specialise(rnn_graph* g, int32_t N) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "N must be positive");
-    if (!g->use_jit) return 0;
+    if (!g->use_jit || !jit_available()) return 0;
     int n = 0;
     for (size_t c = 0; c < g->plan.comps.size(); ++c) {
         const CompPlan& cp = g->plan.comps[c];
@@ -954,6 +1082,37 @@ int rnn_specialise(rnn_graph* g, int32_t N) {
             ++n;
         }
     return n;
+}
+
+int rnn_plan_work(const rnn_graph* g, int32_t T, int32_t N, int64_t* flops, int64_t* step_bytes) {
+    if (!g || !flops || !step_bytes) return fail(RNN_ERR_INVALID_ARGUMENT, "NULL argument");
+    if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
+    const Plan& P = g->plan;
+    const int64_t F = (int64_t)T * N;
+    for (int i = 0; i < 5; ++i) flops[i] = 0;
+    step_bytes[0] = step_bytes[1] = 0;
+    // diagonal weights inside recurrent nodes (peepholes) are touched once per step as well
+    std::vector<int64_t> diag(P.comps.size(), 0);
+    for (size_t m = 0; m < P.xedges.size(); ++m)
+        if (P.xedges[m].wkind == W_DIAG && P.xsched.edge_class[m] != EDGE_BATCHED)
+            diag[P.xsched.node_comp[P.xedges[m].dst]] += P.xnodes[P.xedges[m].dst].dim;
+    for (size_t c = 0; c < P.comps.size(); ++c) {
+        for (int d = 0; d < 2; ++d) {
+            // the lowering that ran: as a member of a chain launch, or on its own
+            const CompPlan* cp = &P.comps[c];
+            if (cp->chain >= 0 && (g->served[c][d] & RNN_BUILD_CHAIN)) cp = &P.chains[cp->chain].members[c - P.chains[cp->chain].first];
+            for (const GemmProblemPlan& gp : d ? cp->bwd_gemms : cp->fwd_gemms)
+                for (const GemmPairPlan& pr : gp.pairs)
+                    if (!g->is_onehot(pr.a_buf)) flops[d] += 2 * (int64_t)gp.n * pr.k_len * F;
+            if (cp->recurrent) {
+                flops[3 + d] += 2 * cp->step_weight_floats * F;
+                step_bytes[d] += 4 * (cp->step_weight_floats + diag[c]);
+            }
+        }
+    }
+    for (const GradGemmPlan& gg : P.grad_gemms)
+        if (!g->is_onehot(gg.src_buf)) flops[2] += 2 * (int64_t)gg.n_dst * gg.n_src * F;
+    return RNN_OK;
 }
 
 int rnn_debug_read_control(rnn_graph* g, void* out, int32_t bytes) {

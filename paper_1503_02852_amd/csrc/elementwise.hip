@@ -84,13 +84,14 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ y
 }
 
 __global__ __launch_bounds__(256) void softmax_ce_delta_kernel(const float* __restrict__ y, const int32_t* __restrict__ targets,
-                                                               float* __restrict__ ds, double* loss, long long rows, int dim) {
+                                                               float* __restrict__ ds, double* loss, unsigned* flag, long long rows, int dim) {
     __shared__ float wl[4];
     const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float l = 0.0f;
     if (row < rows) {
-        const int tg = targets[row];
+        int tg = targets[row];
+        if (tg >= dim) { if (lane == 0) atomicMax(flag, 3u); tg = -1; }      // not a class of this layer: the frame is left out
         const float* p = y + row * dim;
         float* d = ds + row * dim;
         for (int i = lane; i < dim; i += 64) d[i] = tg >= 0 ? p[i] - (i == tg ? 1.0f : 0.0f) : 0.0f;
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(256) void softmax_ce_delta_kernel(const float* __re
 
 // grid: (ceil(dim / 64), n_tasks, row splits); block (64, 4).
 __global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off, const float* __restrict__ weights,
-                                                     float* __restrict__ grads, int T, int N) {
+                                                     float* __restrict__ grads, int T, int N, int t0) {
     __shared__ float part[4][64];
     const int32_t* w = pv.words + tasks_off;
     for (int task = 0; task < (int)blockIdx.y; ++task) w += CS_HEADER_WORDS + w[CS_NFACTORS] * CF_WORDS;
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off,
     const long long rows = (long long)T * N;
     float s = 0.0f;
     if (i < dim) {
-        for (long long r = (long long)blockIdx.z * 4 + threadIdx.y; r < rows; r += 4LL * gridDim.z) {
+        for (long long r = (long long)t0 * N + (long long)blockIdx.z * 4 + threadIdx.y; r < rows; r += 4LL * gridDim.z) {
             const int t = (int)(r / N), n = (int)(r % N);
             float prod = 1.0f;
             for (int j = 0; j < nf; ++j) {
@@ -165,23 +166,73 @@ hipError_t launch_softmax_rows(float* y, int64_t rows, int dim, hipStream_t stre
     return hipGetLastError();
 }
 
-hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss,
+hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss, unsigned* flag,
                                    int64_t rows, int dim, hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(softmax_ce_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, y, targets, ds, loss,
+    hipLaunchKernelGGL(softmax_ce_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, y, targets, ds, loss, flag,
                        (long long)rows, dim);
     return hipGetLastError();
 }
 
 hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
-                         int T, int N, hipStream_t stream) {
+                         int T, int N, int t0, hipStream_t stream) {
     if (n_tasks <= 0 || max_dim <= 0) return hipSuccess;
-    const long long rows = (long long)T * N;
+    const long long rows = (long long)(T - t0) * N;
     int splits = (int)((rows + 63) / 64);
     if (splits > 128) splits = 128;
     if (splits < 1) splits = 1;
     hipLaunchKernelGGL(colsum_kernel, dim3((max_dim + 63) / 64, n_tasks, splits), dim3(64, 4), 0, stream, pv, tasks_off,
-                       weights, grads, T, N);
+                       weights, grads, T, N, t0);
+    return hipGetLastError();
+}
+
+namespace {
+__global__ __launch_bounds__(256) void copy_kernel(float* __restrict__ dst, const float* __restrict__ src, long long n) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += 256LL * gridDim.x) dst[i] = src[i];
+}
+constexpr int UPLOAD_CHUNK_WORDS = 960;      // 3840 bytes of kernel arguments
+struct UploadChunk { uint32_t w[UPLOAD_CHUNK_WORDS]; };
+__global__ __launch_bounds__(256) void upload_words_kernel(uint32_t* __restrict__ dst, UploadChunk c, int n) {
+    for (int i = threadIdx.x; i < n; i += 256) dst[i] = c.w[i];
+}
+}  // namespace
+
+hipError_t launch_copy(float* dst, const float* src, int64_t n, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    long long blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dst, src, (long long)n);
+    return hipGetLastError();
+}
+
+hipError_t launch_upload_words(uint32_t* d_dst, const uint32_t* h_src, int64_t n, hipStream_t stream) {
+    for (int64_t off = 0; off < n; off += UPLOAD_CHUNK_WORDS) {
+        UploadChunk c;
+        const int m = (int)std::min<int64_t>(UPLOAD_CHUNK_WORDS, n - off);
+        for (int i = 0; i < m; ++i) c.w[i] = h_src[off + i];
+        hipLaunchKernelGGL(upload_words_kernel, dim3(1), dim3(256), 0, stream, d_dst + off, c, m);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+namespace {
+// One workgroup per buffer: the first `rows` rows of a flagged buffer become zero.
+__global__ __launch_bounds__(256) void zero_history_kernel(float* const* __restrict__ buf_ptr, const int32_t* __restrict__ buf_dim,
+                                                           const int32_t* __restrict__ buf_flags, long long rows) {
+    const int b = blockIdx.x;
+    if (buf_flags[b] != 1) return;
+    float* p = buf_ptr[b];
+    const long long n = rows * buf_dim[b];
+    for (long long i = threadIdx.x; i < n; i += 256) p[i] = 0.0f;
+}
+}  // namespace
+
+hipError_t launch_zero_history(float* const* buf_ptr, const int32_t* buf_dim, const int32_t* buf_flags, int n_bufs, int64_t rows,
+                               hipStream_t stream) {
+    if (n_bufs <= 0 || rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_history_kernel, dim3((unsigned)n_bufs), dim3(256), 0, stream, buf_ptr, buf_dim, buf_flags, (long long)rows);
     return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ struct Rtc {
     }
 };
 
-struct CacheEntry { std::vector<char> code; hipModule_t module = nullptr; hipFunction_t fn = nullptr; bool failed = false; };
+struct CacheEntry { std::vector<char> code; hipModule_t module = nullptr; hipFunction_t fn = nullptr; bool failed = false; std::string log; };
 
 std::mutex g_mutex;
 Rtc g_rtc;
@@ -585,7 +585,7 @@ std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool back
 bool jit_compile(const std::string& source, std::string* log_out) {
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_cache.find(source);
-    if (it != g_cache.end()) return !it->second.failed;
+    if (it != g_cache.end()) { if (it->second.failed && log_out) *log_out = it->second.log; return !it->second.failed; }
     CacheEntry& ce = g_cache[source];
     ce.failed = true;
     if (const char* dump = std::getenv("RNNG_JIT_DUMP")) {   // debugging aid: keep the generated sources
@@ -594,12 +594,13 @@ bool jit_compile(const std::string& source, std::string* log_out) {
         if (FILE* f = std::fopen(path.c_str(), "w")) { std::fwrite(source.data(), 1, source.size(), f); std::fclose(f); }
     }
     g_rtc.load();
-    if (!g_rtc.ok) { if (log_out) *log_out = "libhiprtc.so could not be loaded"; return false; }
+    if (!g_rtc.ok) { ce.log = "libhiprtc.so could not be loaded"; if (log_out) *log_out = ce.log; return false; }
     const char* header_src[3] = {RNNG_SRC_program_h, RNNG_SRC_step_layout_h, RNNG_SRC_step_device_h};
     const char* header_names[3] = {"program.h", "step_layout.h", "step_device.h"};
     hiprtcProgram prog = nullptr;
     if (g_rtc.create(&prog, source.c_str(), "rnng_step_jit.hip", 3, header_src, header_names) != HIPRTC_SUCCESS) {
-        if (log_out) *log_out = "hiprtcCreateProgram failed";
+        ce.log = "hiprtcCreateProgram failed";
+        if (log_out) *log_out = ce.log;
         return false;
     }
     std::vector<const char*> opts = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
@@ -626,7 +627,7 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     const hiprtcResult r = g_rtc.compile(prog, (int)opts.size(), opts.data());
     size_t ls = 0;
     g_rtc.log_size(prog, &ls);
-    if (ls > 1 && log_out) { log_out->assign(ls, '\0'); g_rtc.log(prog, &(*log_out)[0]); }
+    if (ls > 1) { ce.log.assign(ls, '\0'); g_rtc.log(prog, &ce.log[0]); if (log_out) *log_out = ce.log; }
     if (r != HIPRTC_SUCCESS) { g_rtc.destroy(&prog); return false; }
     size_t cs = 0;
     g_rtc.code_size(prog, &cs);
@@ -637,24 +638,33 @@ bool jit_compile(const std::string& source, std::string* log_out) {
     return !ce.failed;
 }
 
-hipFunction_t jit_step_function(const std::string& source) {
-    if (!jit_compile(source, nullptr)) return nullptr;
+bool jit_available() {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_rtc.load();
+    return g_rtc.ok;
+}
+
+hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load) {
+    if (!allow_load) {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        auto it = g_cache.find(source);
+        if (it != g_cache.end() && it->second.fn) return it->second.fn;
+        if (err) *err = "the kernel has not been loaded yet";
+        return nullptr;
+    }
+    std::string log;
+    if (!jit_compile(source, &log)) { if (err) *err = "compilation failed: " + log; return nullptr; }
     std::lock_guard<std::mutex> lock(g_mutex);
     CacheEntry& ce = g_cache[source];
     if (ce.fn) return ce.fn;
-    if (ce.failed) return nullptr;
-    if (hipModuleLoadData(&ce.module, ce.code.data()) != hipSuccess) { ce.failed = true; return nullptr; }
-    if (hipModuleGetFunction(&ce.fn, ce.module, "rnng_step_jit") != hipSuccess) { ce.failed = true; ce.fn = nullptr; return nullptr; }
+    hipError_t e = hipModuleLoadData(&ce.module, ce.code.data());
+    if (e != hipSuccess) { (void)hipGetLastError(); if (err) *err = std::string("hipModuleLoadData: ") + hipGetErrorString(e); return nullptr; }
+    e = hipModuleGetFunction(&ce.fn, ce.module, "rnng_step_jit");
+    if (e != hipSuccess) { (void)hipGetLastError(); ce.fn = nullptr; if (err) *err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e); return nullptr; }
     // more than 64 KiB of dynamic LDS needs an opt-in; an error here surfaces at launch
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ce.fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)STEP_LDS_LIMIT);
     (void)hipGetLastError();   // a refusal must not linger as the thread's last error
     return ce.fn;
-}
-
-void jit_mark_failed(const std::string& source) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    g_cache[source].failed = true;
-    g_cache[source].fn = nullptr;
 }
 
 hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream) {

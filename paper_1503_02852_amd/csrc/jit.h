@@ -33,9 +33,12 @@ std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool back
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
 // compile fails (the log, if any, goes to *log).  Needs no GPU.
 bool jit_compile(const std::string& source, std::string* log);
-// Loaded kernel for the source, or nullptr (then the interpreted kernel is used).
-hipFunction_t jit_step_function(const std::string& source);
-void jit_mark_failed(const std::string& source);
+// True if the run-time compiler can be loaded on this machine (else only the interpreting build exists).
+bool jit_available();
+// Loaded kernel for the source on the current device, or nullptr with the reason (compiler log,
+// loader error) in *err.  allow_load = false: only a kernel that is already loaded is returned
+// (nothing is compiled or loaded, so no memory is allocated).
+hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load = true);
 hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream);
 
 void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,

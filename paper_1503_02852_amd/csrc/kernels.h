@@ -49,12 +49,21 @@ hipError_t launch_step_matvec(const PlanView& pv, int mv_off, int n_tasks, int m
 // In-place row softmax over `rows` rows of width dim.
 hipError_t launch_softmax_rows(float* y, int64_t rows, int dim, hipStream_t stream);
 // ds = y - onehot(target) (0 where target < 0); *loss += sum of -ln y[target].
-hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss,
+// A target not below dim leaves its frame out and sets *flag to 3.
+hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss, unsigned* flag,
                                    int64_t rows, int dim, hipStream_t stream);
 // Column-sum tasks (diagonal-weight and bias gradients), atomically added into grads.
+// The sums run over frames [t0, T); factors may reach back to frames before t0.
 hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
-                         int T, int N, hipStream_t stream);
+                         int T, int N, int t0, hipStream_t stream);
+// Zeroes the first `rows` rows of every buffer whose flag is 1 (the history frames in front of a fresh window).
+hipError_t launch_zero_history(float* const* buf_ptr, const int32_t* buf_dim, const int32_t* buf_flags, int n_bufs, int64_t rows,
+                               hipStream_t stream);
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream);
+hipError_t launch_copy(float* dst, const float* src, int64_t n, hipStream_t stream);
+// n 32-bit words from HOST memory to DEVICE memory, carried as kernel arguments (the words are read
+// when the call is made; no staging buffer, no allocation).
+hipError_t launch_upload_words(uint32_t* d_dst, const uint32_t* h_src, int64_t n, hipStream_t stream);
 // Writes the hardware XCD id of workgroup b (256 threads each) to out[b], b < n_blocks.
 hipError_t launch_xcc_probe(unsigned* out, int n_blocks, hipStream_t stream);
 // One-hot sources given as class indices [total_rows]: C[f][j] (+)= W[j][idx[f - shift_rows]] for rows

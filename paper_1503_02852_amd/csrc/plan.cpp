@@ -293,9 +293,16 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     P.n_bufs = 5 * K;
     P.buf_dim.assign(P.n_bufs, 0);
     P.buf_alloc.assign(P.n_bufs, 0);
+    P.hist = 0;
+    P.input_staged.assign(K, 0);
+    for (int m = 0; m < M; ++m) {
+        P.hist = std::max(P.hist, xe[m].delay);
+        if (xn[xe[m].src].kind == NODE_INPUT && (xe[m].delay > 0 || xe[m].wkind != W_FULL)) P.input_staged[xe[m].src] = 1;
+    }
     for (int k = 0; k < K; ++k) {
         for (int b : {P.ybuf(k), P.dbuf(k), P.abuf(k), P.pbuf(k), P.qbuf(k)}) P.buf_dim[b] = xn[k].dim;
         if (xn[k].kind != NODE_INPUT) P.buf_alloc[P.ybuf(k)] = P.buf_alloc[P.dbuf(k)] = 1;
+        else if (P.input_staged[k]) P.buf_alloc[P.ybuf(k)] = 1;
     }
     // y_src of a full connection inside a recurrent node is read by all workgroups during the
     // forward step loop, ds_dst during the backward one

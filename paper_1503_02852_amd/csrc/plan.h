@@ -95,6 +95,17 @@ struct Plan {
     int colsum_off = -1, n_colsum = 0, colsum_max_dim = 0;
     std::vector<int32_t> words;             // all programs
     std::vector<int> input_nodes, output_nodes;   // original ids, increasing
+    // History: every tensor of the window is stored with `hist` frames in front of the window's
+    // first frame (hist = the longest delay of any connection).  They hold the activations that the
+    // frames before the window left (zero for a fresh window), so that delayed connections, the
+    // epsilon of multiplicative layers and the weight-gradient sums of the window's first frames
+    // read the real y(t - d) (Section 2.2, last two equations; Section 3.2, BPTT(h; h')).
+    int hist = 0;
+    // Input nodes are read in place from the caller's tensors, which have no history frames.  An
+    // input with a delayed or an element-wise (identity / diagonal) out-connection is copied into a
+    // workspace tensor of its own (with history) instead; the others are read by GEMMs only, which
+    // take the caller's rows directly.
+    std::vector<char> input_staged;               // per exec node id
 
     int ybuf(int k) const { return k; }
     int dbuf(int k) const { return (int)xnodes.size() + k; }

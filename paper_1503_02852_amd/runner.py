@@ -88,6 +88,10 @@ class Window:
     def compute_grads(self, want_loss=False):
         return self.g.grads(self.grads.data_ptr(), want_loss, self._stream())
 
+    def check(self):
+        """Waits for the stream; raises if a kernel of the current window has flagged an error."""
+        self.g.check(self._stream())
+
     def step(self):
         """One pass of the whole hot path: forward, BPTT, weight gradients (asynchronous)."""
         self.forward()

@@ -10,18 +10,19 @@ import pytest
 
 import workloads as wl
 from oracle import schedule_oracle as so
-from paper_1503_02852_amd import EXPORTS, LIB_PATH, Graph, RnnError, load_library
+from paper_1503_02852_amd import AUX_EXPORTS, EXPORTS, LIB_PATH, Graph, RnnError, load_library
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = load_library()
-    header = open(os.path.join(ROOT, "include", "rnngraph.h")).read()
-    declared = set(re.findall(r"\b(rnn_[a-z_]+)\s*\(", header))
-    assert declared == set(EXPORTS)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for header_name, names in (("rnngraph.h", EXPORTS), ("rnngraph_aux.h", AUX_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", header_name)).read()
+        declared = set(re.findall(r"^(?:int|int64_t|void|const char\*)\s+(rnn_[a-z_]+)\s*\(", header, flags=re.M))
+        assert declared == set(names), header_name
+        for name in declared:
+            assert hasattr(lib, name), name
     assert os.path.exists(LIB_PATH)
 
 

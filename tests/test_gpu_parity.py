@@ -11,6 +11,7 @@ from oracle import graph_oracle as go
 pytestmark = pytest.mark.gpu
 
 OUT_TOL, GRAD_TOL = 1e-4, 1e-3
+WORST = {}      # label -> worst normwise errors seen (printed; the full-size figures are quoted in the benchmark spec)
 
 
 def nerr(a, b):
@@ -53,7 +54,11 @@ def run_both(w, check_all_nodes=True, label=""):
         worst_g = max(worst_g, e)
         assert e < GRAD_TOL, (label, "grad_b", w.spec.nodes[k]["name"], e)
     assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"])), (label, loss, ref["loss"])
-    print(f"[parity] {label or w.name}: worst y {worst_y:.2e}  ds {worst_d:.2e}  grad {worst_g:.2e}  loss {loss:.6f}", flush=True)
+    win.check()
+    builds = sorted({win.g.step_build(k, b) for k in range(len(w.spec.nodes)) for b in (False, True)} - {("none", False)})
+    print(f"[parity] {label or w.name}: worst y {worst_y:.2e}  ds {worst_d:.2e}  grad {worst_g:.2e}  loss {loss:.6f}  "
+          f"step builds {builds}", flush=True)
+    WORST[label or w.name] = dict(y=worst_y, ds=worst_d, grad=worst_g)
     return win, ref
 
 
@@ -148,6 +153,14 @@ def test_generalized_full_width_reduced_window():
     run_both(wl.make_config("generalized_n64", T=24), check_all_nodes=True, label="generalized_n64_T24")
 
 
+def test_generalized_full_size():
+    """The generalized configuration as benchmarked: 3 x 1024, N = 64, T = 128 (the oracle needs
+    about half a minute)."""
+    win, _ = run_both(wl.make_config("generalized_n64"), check_all_nodes=True, label="generalized_n64")
+    spec = wl.make_config("generalized_n64", T=1).spec
+    assert win.g.step_build(spec.node_by_name("L1.h"))[0] in ("matrix", "matrix_2d")
+
+
 @pytest.mark.parametrize("seed", [8, 17])
 def test_dense_random_graph_splits_step_programs(seed):
     """Dense random graphs whose recurrent node needs more element-wise values per step than one
@@ -182,19 +195,99 @@ def test_lstm_stack_with_many_streams_runs_side_by_side(layers, N):
     run_both(wl.make_workload("lstm_stack_streams", spec, T=15, N=N, seed=31, scale=0.4, bias_scale=0.3, masked_fraction=0.2))
 
 
-def test_many_stream_stack_in_one_launch_equals_layers_one_after_another(monkeypatch):
-    from paper_1503_02852_amd.runner import window_for
+@pytest.mark.parametrize("chain", ["1", "0"])
+@pytest.mark.parametrize("N", [2, 24])
+def test_stack_in_one_launch_and_layers_one_after_another(monkeypatch, chain, N):
+    """Stacked layers in one step launch (the connections between them stepped) and one launch per
+    layer (those connections batched over frames, the paper's schedule), each against the oracle."""
+    monkeypatch.setenv("RNNG_CHAIN", chain)
     spec = wl.lstm_net(10, [32, 28], 6)
-    w = wl.make_workload("stack", spec, T=13, N=24, seed=32, scale=0.4, bias_scale=0.3)
-    outs = []
-    for chain in ("1", "0"):
-        monkeypatch.setenv("RNNG_CHAIN", chain)
-        win = window_for(w)
-        win.forward(); win.bptt(); win.compute_grads()
-        gw, gb = win.grads_unpacked()
-        outs.append(([win.node_output(k).copy() for k in spec.output_nodes()], [g.copy() for g in gw if g is not None]))
-    for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
-        assert nerr(a, b) < OUT_TOL
+    w = wl.make_workload("stack", spec, T=13, N=N, seed=32, scale=0.4, bias_scale=0.3)
+    win, _ = run_both(w, label=f"stack N={N} RNNG_CHAIN={chain}")
+    for name in ("L1.h", "L2.h"):
+        for backward in (False, True):
+            build, chained = win.g.step_build(spec.node_by_name(name), backward)
+            assert build == ("wave" if N <= 8 else "matrix") and chained == (chain == "1")
+
+
+def test_interpreting_build_of_the_step_kernel(monkeypatch):
+    """RNNG_JIT=0: the ahead-of-time build that interprets the step programs (it serves N <= 8;
+    more streams step with per-frame launches), single- and multi-phase components."""
+    monkeypatch.setenv("RNNG_JIT", "0")
+    spec = wl.lstm_net(12, [40, 24], 5)
+    win, _ = run_both(wl.make_workload("lstm2_interp", spec, T=17, N=3, seed=61, scale=0.4, bias_scale=0.3, masked_fraction=0.2), label="RNNG_JIT=0 stack")
+    assert win.g.step_build(spec.node_by_name("L1.h")) == ("interpreted", False)
+    assert win.g.step_build(spec.node_by_name("L2.c"), True) == ("interpreted", False)
+    spec = wl.generalized_net(8, 16, 2, 4)
+    run_both(wl.make_workload("gen_interp", spec, T=9, N=1, seed=62, scale=0.4, bias_scale=0.3), label="RNNG_JIT=0 generalized")
+    spec = wl.lstm_net(6, [20], 4)
+    win, _ = run_both(wl.make_workload("lstm_frames", spec, T=7, N=12, seed=63, scale=0.4, bias_scale=0.3), label="RNNG_JIT=0 N=12")
+    assert win.g.step_build(spec.node_by_name("L1.h")) == ("per_frame", False)
+
+
+def test_without_exchange_bundles(monkeypatch):
+    """RNNG_BUNDLE=0: every exchanged tensor polled on its own (no interleaved bundle tensors)."""
+    monkeypatch.setenv("RNNG_BUNDLE", "0")
+    spec = wl.lstm_net(12, [40, 24], 5)
+    win, _ = run_both(wl.make_workload("lstm2_nobundle", spec, T=17, N=2, seed=64, scale=0.4, bias_scale=0.3, masked_fraction=0.2), label="RNNG_BUNDLE=0")
+    assert win.g.step_build(spec.node_by_name("L1.h"), True) == ("wave", True)
+
+
+def test_target_index_out_of_range_is_reported():
+    from paper_1503_02852_amd.binding import RnnError
+    from paper_1503_02852_amd.runner import window_for
+    w = wl.make_workload("badtarget", wl.lstm_net(5, [8], 3), T=6, N=2, seed=65)
+    (out,) = w.spec.output_nodes()
+    w.targets[out][2, 1] = 3          # classes are 0..2
+    win = window_for(w)
+    win.forward(); win.bptt()
+    with pytest.raises(RnnError) as ei:
+        win.compute_grads(want_loss=True)
+    assert ei.value.code == -1
+    with pytest.raises(RnnError):
+        win.check()
+    # the flag belongs to that window: the next one starts clean
+    w.targets[out][2, 1] = -1
+    win.set_targets(w.targets)
+    win.forward(); win.bptt(); win.compute_grads(want_loss=True); win.check()
+    ref = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+    gw, _ = win.grads_unpacked()
+    for m, g in enumerate(ref["grad_w"]):
+        if g is not None:
+            assert nerr(gw[m], g) < GRAD_TOL
+
+
+def test_a_wait_that_runs_into_its_limit_is_reported_on_every_path(monkeypatch):
+    """RNNG_SPIN_LIMIT=1 makes every bounded wait of the step kernels give up after one repeat: the
+    kernels then stop waiting, run to their end and raise the error word.  rnn_check must report
+    it after a forward pass alone and after rnn_grads without a loss pointer; a window in which no
+    wait happened to expire must be correct."""
+    from paper_1503_02852_amd.binding import RnnError
+    from paper_1503_02852_amd.runner import window_for
+    monkeypatch.setenv("RNNG_SPIN_LIMIT", "1")
+    w = wl.make_workload("spin", wl.lstm_net(8, [64, 64], 4), T=200, N=1, seed=66, scale=0.3)
+    win = window_for(w)
+    win.forward()
+    flagged = False
+    try:
+        win.check()
+    except RnnError as e:
+        assert e.code == -5
+        flagged = True
+    win.bptt(); win.compute_grads(False)
+    try:
+        win.check()
+        assert not flagged      # a flag raised by the forward pass stays up for the whole window
+    except RnnError as e:
+        assert e.code == -5
+        flagged = True
+    print(f"[parity] spin limit 1: flagged = {flagged}", flush=True)
+    if not flagged:
+        ref = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+        gw, _ = win.grads_unpacked()
+        for m, g in enumerate(ref["grad_w"]):
+            if g is not None:
+                assert nerr(gw[m], g) < GRAD_TOL
 
 
 @pytest.mark.parametrize("kind,N", [("elman", 16), ("lstm", 24), ("lstm", 40), ("elman", 64)])

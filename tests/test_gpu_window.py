@@ -63,6 +63,11 @@ WINDOW_NETS = {
     "generalized": lambda: (wl.generalized_net(8, 16, 2, 4), 2),
     "lstm_many_streams": lambda: (wl.lstm_net(8, [32], 4), 20),
     "lstm2_many_streams": lambda: (wl.lstm_net(8, [32, 24], 4), 18),
+    # random graphs: delays up to 3, multiplicative nodes fed through delayed connections, inputs
+    # with delayed and element-wise out-connections (the library keeps its own history of those)
+    "random_a": lambda: (wl.random_graph(np.random.default_rng(501), n_inner=7, max_delay=3, n_inputs=2), 2),
+    "random_b": lambda: (wl.random_graph(np.random.default_rng(502), n_inner=8, max_delay=3, n_inputs=1), 3),
+    "random_many_streams": lambda: (wl.random_graph(np.random.default_rng(503), n_inner=6, max_delay=2, n_inputs=2), 11),
 }
 
 
@@ -115,6 +120,7 @@ def test_window_moved_ahead_with_carried_state(name):
                         targets={k: v[:T].copy() for k, v in long.targets.items()})
     win = window_for(first)
     win.forward()
+    differs = 0.0
     for step in (1, 2):
         a, b = step * hp, step * hp + T
         new_targets = {k: v[b - hp:b] for k, v in long.targets.items()}
@@ -130,6 +136,14 @@ def test_window_moved_ahead_with_carried_state(name):
         ref = go.bptt_window(long.spec.nodes, long.spec.edges, long.weights, long.biases, y_long, z_long, tl, a, T, N)
         check_against(win, first, ref, f"{name} advance {step}")
         assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
+        # what the same frames give as a fresh window (zero state in front): the carried history matters
+        fresh = go.forward_bptt(long.spec.nodes, long.spec.edges, long.weights, long.biases,
+                                {k: v[a:b] for k, v in long.inputs.items()}, masked, T, N)
+        for g1, g2 in zip(ref["grad_w"], fresh["grad_w"]):
+            if g1 is not None:
+                differs = max(differs, nerr(g2, g1))
+    if not name.startswith("random"):      # (in a random graph the state may hardly reach the unmasked frames)
+        assert differs > 1e-3, "the carried state made no difference: the test does not tell the two apart"
 
 
 def test_frame_by_frame_schedule_gives_the_same_results(monkeypatch):
