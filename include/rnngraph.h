@@ -203,6 +203,25 @@ int rnn_check(rnn_graph* g, void* hip_stream);
  * never a silent change of build (rnn_step_build in rnngraph_aux.h tells which build ran). */
 int rnn_specialise(rnn_graph* g, int32_t N);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): rnn_forward with the workspace in a device array that
+ * is part of the library image (RNN_STATIC_WORKSPACE_BYTES per GPU, held from the time the library
+ * is loaded until the process ends), and the output layers' activations copied to the caller.
+ *   d_inputs   as in rnn_forward.
+ *   d_outputs  HOST array with one DEVICE pointer per output node, in increasing node id, each a
+ *              [T][N][dim] float tensor that receives the node's activations y.
+ * The call allocates nothing on the device and loads no code: every kernel it needs must already
+ * be loaded, which one earlier rnn_forward of the same graph handle and N on this device (on a
+ * workspace of the caller's) has done; else RNN_ERR_SEQUENCE.  RNN_ERR_WORKSPACE if the window
+ * needs more than RNN_STATIC_WORKSPACE_BYTES (rnn_workspace_bytes tells), RNN_ERR_SEQUENCE if
+ * kernel-class timing is switched on (it creates events).  Afterwards the handle's window lives in
+ * the static array: rnn_output, rnn_bptt, rnn_grads work on it as after rnn_forward.  All calls
+ * on one GPU share that GPU's array, which keeps the last call's contents (the call clears what
+ * must start at zero): calls that overlap on one GPU, from any handle or stream, race. */
+#define RNN_STATIC_WORKSPACE_BYTES (32 * 1024 * 1024)
+int rnn_forward_static(rnn_graph* g, const float* d_weights, const float* const* d_inputs, float* const* d_outputs,
+                       int32_t T, int32_t N, void* hip_stream);
+
 /* Message for the last error on this thread (never NULL). */
 const char* rnn_last_error(void);
 

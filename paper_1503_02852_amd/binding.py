@@ -16,7 +16,7 @@ EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_p
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
            "rnn_forward_range", "rnn_shift_window", "rnn_set_onehot_input",
            "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_check", "rnn_specialise",
-           "rnn_last_error"]
+           "rnn_forward_static", "rnn_last_error"]
 # measurement and inspection aids (include/rnngraph_aux.h)
 AUX_EXPORTS = ["rnn_step_build", "rnn_debug_read_control", "rnn_profile_enable", "rnn_profile_read", "rnn_plan_work"]
 BUILD_NAMES = {0: "none", 1: "wave", 2: "matrix", 3: "matrix_2d", 4: "lds", 5: "interpreted", 6: "per_frame", 7: "streaming"}
@@ -60,6 +60,8 @@ def load_library(build_if_missing=True):
     lib.rnn_forward.restype = C.c_int
     lib.rnn_forward_range.argtypes = [vp, vp, C.POINTER(vp), C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_int64, vp]
     lib.rnn_forward_range.restype = C.c_int
+    lib.rnn_forward_static.argtypes = [vp, vp, C.POINTER(vp), C.POINTER(vp), C.c_int32, C.c_int32, vp]
+    lib.rnn_forward_static.restype = C.c_int
     lib.rnn_set_onehot_input.argtypes = [vp, C.c_int32, vp]
     lib.rnn_set_onehot_input.restype = C.c_int
     lib.rnn_shift_window.argtypes = [vp, C.c_int32, vp]
@@ -191,6 +193,11 @@ class Graph:
     def forward_range(self, d_weights, d_inputs, T, N, t_begin, t_end, d_workspace, ws_bytes, stream=0):
         arr = (C.c_void_p * max(1, len(d_inputs)))(*d_inputs)
         _check(self.lib.rnn_forward_range(self.handle, d_weights, arr, T, N, t_begin, t_end, d_workspace, ws_bytes, stream))
+
+    def forward_static(self, d_weights, d_inputs, d_outputs, T, N, stream=0):
+        arr = (C.c_void_p * max(1, len(d_inputs)))(*d_inputs)
+        out = (C.c_void_p * max(1, len(d_outputs)))(*d_outputs)
+        _check(self.lib.rnn_forward_static(self.handle, d_weights, arr, out, T, N, stream))
 
     def set_onehot_input(self, input_index, d_indices):
         _check(self.lib.rnn_set_onehot_input(self.handle, input_index, d_indices))

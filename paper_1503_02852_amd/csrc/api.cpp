@@ -856,6 +856,59 @@ int rnn_forward(rnn_graph* g, const float* d_weights, const float* const* d_inpu
     return rnn_forward_range(g, d_weights, d_inputs, T, N, 0, T, d_workspace, ws_bytes, hip_stream);
 }
 
+// ---- rnn_forward_static: the workspace of callers that cannot allocate -----------------------
+namespace {
+// Part of the library image: every GPU the library runs on holds its own copy of this array, at
+// its own address, until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; all device work goes through the address that call returns.
+static __device__ __align__(256) unsigned char scratch[RNN_STATIC_WORKSPACE_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+void* g_scratch_ptr[STATIC_MAX_DEVICES];      // per device: address of that GPU's copy (nullptr: not asked yet)
+std::mutex g_scratch_mutex;
+}  // namespace
+
+int rnn_forward_static(rnn_graph* g, const float* d_weights, const float* const* d_inputs, float* const* d_outputs,
+                       int32_t T, int32_t N, void* hip_stream) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    if (!d_outputs) return fail(RNN_ERR_INVALID_ARGUMENT, "outputs pointer is NULL");
+    const Plan& P = g->plan;
+    for (size_t i = 0; i < P.output_nodes.size(); ++i)
+        if (!d_outputs[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "an output tensor pointer is NULL");
+    if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
+    if (g->prof.mask != 0) return fail(RNN_ERR_SEQUENCE, "kernel-class timing creates events: switch it off for rnn_forward_static");
+    const int64_t need = make_layout(P, T, N, g->partial_frame_floats(N)).total;
+    if (need > (int64_t)RNN_STATIC_WORKSPACE_BYTES)
+        return fail(RNN_ERR_WORKSPACE, "the window needs " + std::to_string(need) + " bytes of workspace, the static workspace holds " +
+                                           std::to_string((int64_t)RNN_STATIC_WORKSPACE_BYTES));
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(RNN_ERR_DEVICE, "device index beyond the static workspace table");
+    void* ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            // once per device, with that device current: where this GPU keeps its copy of the array
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return fail_hip(e, "hipGetSymbolAddress(static workspace)");
+            g_scratch_ptr[dev] = p;
+        }
+        ws = g_scratch_ptr[dev];
+    }
+    g->no_alloc = true;
+    const int rc = rnn_forward_range(g, d_weights, d_inputs, T, N, 0, T, ws, RNN_STATIC_WORKSPACE_BYTES, hip_stream);
+    g->no_alloc = false;
+    if (rc != RNN_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    for (size_t i = 0; i < P.output_nodes.size(); ++i) {
+        const int k = P.output_nodes[i];
+        e = launch_copy(d_outputs[i], g->frame0(P.ybuf(k)), (int64_t)T * N * P.nodes[k].dim, s);
+        if (e != hipSuccess) return fail_hip(e, "output copy");
+    }
+    return RNN_OK;
+}
+
 int rnn_set_onehot_input(rnn_graph* g, int32_t input, const int32_t* d_indices) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     const Plan& P = g->plan;
