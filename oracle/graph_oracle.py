@@ -21,8 +21,12 @@ Readings where the paper is silent (all listed in the design notes of the reposi
     epsilon are propagated only while t > t0', but the connection outputs z_n(t) and the
     weight-gradient terms eps_m(t) y_k(t - d_m)^T of the frames t > t0' use the real
     y_k(t - d_m), also where t - d_m <= t0'; error terms from frames after the window are zero;
-  * E_total = sum over frames, streams and output nodes of -ln y_target (natural log,
-    no averaging); a target of -1 masks the frame;
+  * E_total = sum over frames, streams and output nodes of E(t) (no averaging).  Two error
+    criteria (Section 2.2: delta of an output layer follows "the error criterion defined by E(t)
+    and the activation function of the output layer"): is_output = 1, softmax with minimum
+    cross-entropy, E = -ln y_target (natural log), class targets, -1 masks the frame; is_output = 2,
+    squared error E = 1/2 sum_j (d_j - y_j)^2 (the MSE criterion Section 4 names) on a linear,
+    sigmoid or tanh output layer, dense targets, a NaN target element has no error;
   * the functions return dE_total/dW (the paper's nabla W = -sum eps y^T with
     eps = -dE/dz is exactly that).
 
@@ -40,6 +44,7 @@ from __future__ import annotations
 import numpy as np
 
 INPUT, ADD, MUL = 0, 1, 2
+CROSS_ENTROPY, SQUARED_ERROR = 1, 2          # values of a node's is_output
 LINEAR, SIGMOID, TANH, SOFTMAX = 0, 1, 2, 3
 FULL, DIAG, IDENTITY = 0, 1, 2
 
@@ -168,10 +173,15 @@ def forward(nodes, edges, weights, biases, inputs, T, N, history=None):
 
 
 def loss(nodes, y, targets):
-    """E_total: cross-entropy summed over frames, streams and output nodes."""
+    """E_total: the error criterion of every output node summed over frames and streams."""
     total = 0.0
     for k, n in enumerate(nodes):
         if not n["is_output"]:
+            continue
+        if n["is_output"] == SQUARED_ERROR:
+            d = np.asarray(targets[k], dtype=np.float64)
+            err = np.where(np.isnan(d), 0.0, d - y[k])
+            total += 0.5 * float((err * err).sum())
             continue
         tg = np.asarray(targets[k])
         T, N = tg.shape
@@ -188,7 +198,8 @@ def bptt(nodes, edges, weights, biases, y, z, targets, T, N, t_first=0):
     topological order; t_first is the paper's truncation point t0' (Section 2.2).
 
     Works in the paper's variables: delta_k(t) = -dE/ds_k(t), eps_m(t) = -dE/dz_m(t);
-    output nodes start from delta = d - y (softmax with cross-entropy).  delta and eps are
+    output nodes start from delta = d - y (softmax with cross-entropy) or, under the squared
+    error, delta = (d - y) f'(s).  delta and eps are
     back-propagated only while t > t0': nothing is handed to a frame before t_first.  The
     gradient sums run over t0' < t <= t1 with the real y_src(t - d_m) and the real connection
     outputs z_n(t), also where t - d_m lies at or before t0' (frames before index 0 do not
@@ -210,7 +221,11 @@ def bptt(nodes, edges, weights, biases, y, z, targets, T, N, t_first=0):
             n = nodes[k]
             if n["kind"] == INPUT:
                 continue
-            if n["is_output"]:
+            if n["is_output"] == SQUARED_ERROR:
+                # E(t) = 1/2 sum_j (d_j - y_j)^2, so -dE/ds_j = (d_j - y_j) f'(s_j)
+                d = np.asarray(targets[k], dtype=np.float64)[t]
+                delta[k][t] = np.where(np.isnan(d), 0.0, d - y[k][t]) * _activation_derivative(n["act"], y[k][t])
+            elif n["is_output"]:
                 d = np.zeros((N, n["dim"]))
                 tg = np.asarray(targets[k])[t]
                 for s in range(N):

@@ -554,3 +554,47 @@ def test_windowed_bptt_keeps_pre_window_connection_outputs():
     dEdp = 0.4 * dEds[0] - 0.9 * dEds[1]
     assert win["grad_w"][e_w][0, 0] == pytest.approx(dEdp * 1.5 * (-2.0), rel=1e-12)
     assert abs(win["grad_w"][e_w][0, 0]) > 1e-3
+
+
+# ---- the squared-error criterion (Section 2.2: delta of an output layer follows the error criterion; Section 4 names the MSE) ----
+
+@pytest.mark.parametrize("act", [wl.LINEAR, wl.SIGMOID, wl.TANH])
+def test_squared_error_output_layer_closed_form(act):
+    """One layer y = f(W x + b) under E = 1/2 sum (d - y)^2: dE/dW = sum_t ((y - d) f'(s)) x^T in
+    closed form, NaN targets left out, and delta = (d - y) f'(s)."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 5, name="x")
+    out = g.add_node(wl.ADD, act, 3, has_bias=True, is_output=wl.SQUARED_ERROR, name="out")
+    e = g.add_edge(x, out, wl.FULL, 0)
+    w = wl.make_workload("reg", g, T=7, N=2, seed=40 + act, scale=0.6, bias_scale=0.4, masked_fraction=0.3)
+    assert np.isnan(w.targets[out]).any() and not np.isnan(w.targets[out]).all()
+    r = run_oracle(w)
+    X = w.inputs[x].astype(np.float64)
+    S = X @ w.weights[e].astype(np.float64).T + w.biases[out]
+    Y = S if act == wl.LINEAR else 1 / (1 + np.exp(-S)) if act == wl.SIGMOID else np.tanh(S)
+    dY = np.ones_like(Y) if act == wl.LINEAR else Y * (1 - Y) if act == wl.SIGMOID else 1 - Y * Y
+    D = w.targets[out].astype(np.float64)
+    err = np.where(np.isnan(D), 0.0, Y - D)
+    assert r["loss"] == pytest.approx(0.5 * (err ** 2).sum(), rel=1e-13)
+    assert relerr(r["y"][out], Y) < 1e-14
+    np.testing.assert_allclose(r["delta"][out], -err * dY, rtol=1e-13, atol=1e-16)
+    assert relerr(r["grad_w"][e], np.einsum("tni,tnj->ij", err * dY, X)) < 1e-13
+    assert relerr(r["grad_b"][out], (err * dY).sum((0, 1))) < 1e-13
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_finite_differences_with_squared_error_outputs(seed):
+    """Random recurrent graphs with a softmax output and one or two squared-error outputs
+    (linear / sigmoid / tanh, masked elements): every gradient against central differences."""
+    rng = np.random.default_rng(700 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, squared_error_outputs=1 + seed % 2)
+    w = wl.make_workload("rand_sq", spec, T=6, N=2, seed=seed, scale=0.8, bias_scale=0.5, masked_fraction=0.25)
+    assert sum(n["is_output"] == wl.SQUARED_ERROR for n in spec.nodes) == 1 + seed % 2
+    check_finite_differences(w, n_probe=4, seed=seed)
+
+
+def test_squared_error_lstm_finite_differences_and_truncated_window():
+    spec = wl.lstm_net(3, [4], 3, squared_error_act=wl.TANH)
+    w = wl.make_workload("lstm_sq", spec, T=8, N=2, seed=44, scale=0.8, bias_scale=0.5, masked_fraction=0.2)
+    check_finite_differences(w, n_probe=3)
+    check_truncated_gradient_by_finite_differences(w, t_first=3, n_probe=3)

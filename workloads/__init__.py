@@ -10,6 +10,8 @@ Enumerations are the interface's integer codes (they appear in the C header too)
   node kind : 0 input, 1 additive, 2 multiplicative
   activation: 0 linear, 1 logistic sigmoid, 2 tanh, 3 softmax (output nodes only)
   weight kind: 0 full matrix [n_dst x n_src], 1 diagonal (vector), 2 identity
+  is_output : 0 no, 1 softmax output with class targets (cross-entropy), 2 output with dense
+              targets under the squared error (linear, sigmoid or tanh activation)
 """
 from __future__ import annotations
 
@@ -18,6 +20,7 @@ import numpy as np
 INPUT, ADD, MUL = 0, 1, 2
 LINEAR, SIGMOID, TANH, SOFTMAX = 0, 1, 2, 3
 FULL, DIAG, IDENTITY = 0, 1, 2
+CROSS_ENTROPY, SQUARED_ERROR = 1, 2
 
 
 class GraphSpec:
@@ -29,7 +32,7 @@ class GraphSpec:
 
     def add_node(self, kind, act, dim, has_bias=False, is_output=False, name=""):
         self.nodes.append(dict(kind=int(kind), act=int(act), dim=int(dim),
-                               has_bias=int(bool(has_bias)), is_output=int(bool(is_output)),
+                               has_bias=int(bool(has_bias)), is_output=int(is_output),
                                name=name or f"n{len(self.nodes)}"))
         return len(self.nodes) - 1
 
@@ -118,14 +121,19 @@ def add_lstm_layer(g, x, n_cells, tag, output_recurrence=True, extra_delay2_to_i
     return dict(i=i, f=f, g=gg, m_ig=mig, m_fc=mfc, c=c, o=o, tc=tc, h=h)
 
 
-def lstm_net(n_in, hidden, n_out, output_recurrence=True):
-    """Stacked peephole-LSTM layers with a softmax output layer on the top block output."""
+def lstm_net(n_in, hidden, n_out, output_recurrence=True, squared_error_act=None):
+    """Stacked peephole-LSTM layers with an output layer on the top block output: softmax with
+    class targets, or (squared_error_act = LINEAR / SIGMOID / TANH) a layer with dense targets
+    under the squared error."""
     g = GraphSpec()
     x = g.add_node(INPUT, LINEAR, n_in, name="x")
     top = x
     for l, H in enumerate(hidden):
         top = add_lstm_layer(g, top, H, f"L{l + 1}", output_recurrence)["h"]
-    out = g.add_node(ADD, SOFTMAX, n_out, has_bias=True, is_output=True, name="out")
+    if squared_error_act is None:
+        out = g.add_node(ADD, SOFTMAX, n_out, has_bias=True, is_output=CROSS_ENTROPY, name="out")
+    else:
+        out = g.add_node(ADD, squared_error_act, n_out, has_bias=True, is_output=SQUARED_ERROR, name="out")
     g.add_edge(top, out, FULL, 0)
     return g
 
@@ -166,7 +174,7 @@ def generalized_net(n_in=128, n_cells=1024, n_layers=3, n_out=256):
     return g
 
 
-def random_graph(rng, n_inner=6, max_dim=5, p_edge=0.35, max_delay=3, n_inputs=1, force_mul=True):
+def random_graph(rng, n_inner=6, max_dim=5, p_edge=0.35, max_delay=3, n_inputs=1, force_mul=True, squared_error_outputs=0):
     """A small random valid graph for brute-force / finite-difference tests: additive and
     multiplicative nodes, full / diagonal / identity edges, delays 0..max_delay, multiple
     edges between a node pair, self-loops; delay-0 edges only run from lower to higher node
@@ -206,6 +214,12 @@ def random_graph(rng, n_inner=6, max_dim=5, p_edge=0.35, max_delay=3, n_inputs=1
     k = int(rng.integers(1, max(2, n_inner // 2)))
     for s in rng.choice(inner, size=k, replace=False):
         g.add_edge(int(s), out, FULL, int(rng.integers(0, 2)))
+    # further output nodes with dense targets under the squared error (drawn after everything
+    # else, so that graphs without them are what they were)
+    for j in range(squared_error_outputs):
+        o2 = g.add_node(ADD, int(rng.integers(0, 3)), int(rng.integers(2, 5)), has_bias=True, is_output=SQUARED_ERROR, name=f"sq{j}")
+        for s in rng.choice(inner, size=int(rng.integers(1, 3)), replace=False):
+            g.add_edge(int(s), o2, FULL, int(rng.integers(0, 2)))
     return g
 
 
@@ -242,8 +256,16 @@ def draw_gaussian_inputs(spec, rng, T, N):
 
 
 def draw_class_targets(spec, rng, T, N, masked_fraction=0.0):
+    """Targets per output node: class indices [T, N] (int32, -1 = masked frame) for softmax
+    outputs, dense N(0, 1) vectors [T, N, dim] (float32, NaN = masked frame) for squared-error outputs."""
     tg = {}
     for k in spec.output_nodes():
+        if spec.nodes[k]["is_output"] == SQUARED_ERROR:
+            t = rng.standard_normal(size=(T, N, spec.nodes[k]["dim"])).astype(np.float32)
+            if masked_fraction > 0:
+                t[rng.random(size=(T, N)) < masked_fraction] = np.nan
+            tg[k] = t
+            continue
         t = rng.integers(0, spec.nodes[k]["dim"], size=(T, N)).astype(np.int32)
         if masked_fraction > 0:
             t[rng.random(size=(T, N)) < masked_fraction] = -1
@@ -294,6 +316,9 @@ class Workload:
 
 CONFIG_NAMES = ["tiny", "speech_n1", "charlm_n1", "charlm_n32", "generalized_n64"]
 EXPERIMENT_SHAPES = ["lm_elman_n1", "lm_lstm_n1"]      # the paper's own Section 4 network shapes, synthetic words
+# Section 4, second experiment (Fig. 4): peephole LSTM whose input, LSTM and output layers are all
+# H wide, mini-batch N * h' = 1,024 frames with BPTT(2h'; h'), i.e. a window of T = 2,048 / N frames
+FIG4_SHAPES = [f"fig4_h{H}_n{N}" for H in (1024, 2048, 4096) for N in (1, 16, 64)]
 
 
 def make_config(name, seed=0, T=None, N=None, bias_scale=0.0):
@@ -314,6 +339,9 @@ def make_config(name, seed=0, T=None, N=None, bias_scale=0.0):
         spec, T0, N0, a, kind = elman_net(38000, 512, 20000), 2048, 1, 0.05, "words"
     elif name == "lm_lstm_n1":       # Section 4: LSTM without the block-output -> gate recurrence, same sizes
         spec, T0, N0, a, kind = lstm_net(38000, [512], 20000, output_recurrence=False), 2048, 1, 0.05, "words"
+    elif name.startswith("fig4_h"):
+        H, N0 = (int(v) for v in name[len("fig4_h"):].split("_n"))
+        spec, T0, a, kind = lstm_net(H, [H], H), 2048 // N0, 0.02, "gauss"
     else:
         raise ValueError(name)
     T = T0 if T is None else T
