@@ -25,7 +25,8 @@
  *    terms from frames after the window are zero, and errors are back-propagated through the
  *    window's own frames only (Section 2.2: "while t > t0'").
  *  - All arithmetic is fp32.  Gradients are dE_total/dW, summed (not averaged) over frames
- *    and streams, E_total = sum over frames, streams and output nodes of -ln y_target.
+ *    and streams, E_total = sum over frames, streams and output nodes of E(t) (-ln y_target
+ *    or 1/2 |d - y|^2, by the output node's criterion).
  */
 #ifndef RNNGRAPH_H
 #define RNNGRAPH_H
@@ -54,8 +55,15 @@ enum rnn_status {
  * outputs, then an activation function) and multiplicative layers (element-wise product). */
 enum { RNN_NODE_INPUT = 0, RNN_NODE_ADD = 1, RNN_NODE_MUL = 2 };
 /* Activation functions f_k; softmax is allowed on output nodes only and is paired with the
- * cross-entropy criterion, the one case for which Section 2.2 gives the output delta. */
+ * cross-entropy criterion, the case for which Section 2.2 writes the output delta out. */
 enum { RNN_ACT_LINEAR = 0, RNN_ACT_SIGMOID = 1, RNN_ACT_TANH = 2, RNN_ACT_SOFTMAX = 3 };
+/* Values of rnn_node_desc.is_output.  Section 2.2 initialises the delta of an output layer
+ * "according to the error criterion defined by E(t) and the activation function of the output
+ * layer":  RNN_OUT_CROSS_ENTROPY: additive softmax layer, class-index targets,
+ * E(t) = -ln y_target, delta = d - y;  RNN_OUT_SQUARED_ERROR (the MSE criterion that Section 4
+ * names): additive layer with linear, sigmoid or tanh activation, dense targets,
+ * E(t) = 1/2 sum_j (d_j - y_j)^2, delta_j = (d_j - y_j) f'(s_j). */
+enum { RNN_OUT_NONE = 0, RNN_OUT_CROSS_ENTROPY = 1, RNN_OUT_SQUARED_ERROR = 2 };
 /* Weight kinds: full matrix [n_dst x n_src] (row-major, z = W y), diagonal (a vector, used for
  * peepholes) and identity (no parameters), cf. the Fig. 1 caption. */
 enum { RNN_W_FULL = 0, RNN_W_DIAG = 1, RNN_W_IDENTITY = 2 };
@@ -70,7 +78,8 @@ typedef struct { int32_t src, dst, delay, wkind; } rnn_edge_desc;
  * RNN_ERR_INVALID_GRAPH if: a node id is out of range; dim <= 0; an unknown kind / act / wkind;
  * an identity or diagonal edge joins nodes of different width; delay < 0; an edge enters an
  * input node; a non-input node has no incoming edge; an input node has a bias, an activation or
- * is an output; softmax on a non-output node or an output node that is not additive-softmax;
+ * is an output; softmax on a node that is not a cross-entropy output, a cross-entropy output
+ * that is not additive-softmax, a squared-error output that is not additive or has softmax;
  * an output node with outgoing edges; has_bias on a multiplicative node; there is no output
  * node; or the delay-0 edges contain a cycle (Section 3.1 needs the per-step remainder to be a
  * DAG). */
@@ -165,14 +174,16 @@ int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream);
  * (for an input node: the caller's own input tensor). */
 int rnn_output(const rnn_graph* g, int32_t node, const float** d_y);
 
-/* Backward pass (Section 2.2: output delta from softmax + cross-entropy, delta and epsilon
+/* Backward pass (Section 2.2: output delta from the error criterion, delta and epsilon
  * back-propagated through the reversed schedule) for the window of the last rnn_forward.
- *   d_targets  HOST array with one DEVICE pointer per output node, in increasing node id, each
- *              an int32 [T][N] tensor of class indices; -1 means "no error at this frame".  An
- *              index not below the layer's width leaves its frame out and raises a flag that
- *              rnn_check and rnn_grads(loss) report as RNN_ERR_INVALID_ARGUMENT.
+ *   d_targets  HOST array with one DEVICE pointer per output node, in increasing node id.
+ *              Cross-entropy output: an int32 [T][N] tensor of class indices; -1 means "no error
+ *              at this frame"; an index not below the layer's width leaves its frame out and
+ *              raises a flag that rnn_check and rnn_grads(loss) report as
+ *              RNN_ERR_INVALID_ARGUMENT.  Squared-error output: a float [T][N][dim] tensor of
+ *              target vectors; an element that is NaN carries no error.
  * d_weights must hold the same values as in rnn_forward. */
-int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targets, void* hip_stream);
+int rnn_bptt(rnn_graph* g, const float* d_weights, const void* const* d_targets, void* hip_stream);
 
 /* DEVICE view of dE_total/ds_k [T][N][dim] (the paper's -delta_k) after rnn_bptt; not defined
  * for input nodes. */

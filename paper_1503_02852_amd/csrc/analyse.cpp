@@ -28,10 +28,16 @@ std::string validate_graph(const std::vector<GNode>& nodes, const std::vector<GE
             e << "node " << k << ": an input node has no bias, no activation and is not an output"; return e.str();
         }
         if (n.kind == NODE_MUL && n.has_bias) { e << "node " << k << ": a multiplicative node has no bias"; return e.str(); }
-        if (n.is_output) {
+        if (n.is_output < OUT_NONE || n.is_output > OUT_SQUARED_ERROR) { e << "node " << k << ": unknown output kind " << n.is_output; return e.str(); }
+        if (n.is_output == OUT_CROSS_ENTROPY) {
             ++n_outputs;
             if (n.kind != NODE_ADD || n.act != ACT_SOFTMAX) {
-                e << "node " << k << ": an output node must be additive with softmax activation"; return e.str();
+                e << "node " << k << ": a cross-entropy output node must be additive with softmax activation"; return e.str();
+            }
+        } else if (n.is_output == OUT_SQUARED_ERROR) {
+            ++n_outputs;
+            if (n.kind != NODE_ADD || n.act == ACT_SOFTMAX) {
+                e << "node " << k << ": a squared-error output node must be additive with linear, sigmoid or tanh activation"; return e.str();
             }
         } else if (n.act == ACT_SOFTMAX) {
             e << "node " << k << ": softmax is allowed on output nodes only"; return e.str();

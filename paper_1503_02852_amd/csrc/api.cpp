@@ -637,7 +637,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (!nodes || n_nodes <= 0 || n_edges < 0 || (n_edges > 0 && !edges))
         return fail(RNN_ERR_INVALID_ARGUMENT, "node / edge list missing");
     std::vector<GNode> ns(n_nodes); std::vector<GEdge> es(n_edges);
-    for (int i = 0; i < n_nodes; ++i) ns[i] = GNode{nodes[i].kind, nodes[i].act, nodes[i].dim, nodes[i].has_bias != 0, nodes[i].is_output != 0};
+    for (int i = 0; i < n_nodes; ++i) ns[i] = GNode{nodes[i].kind, nodes[i].act, nodes[i].dim, nodes[i].has_bias != 0, nodes[i].is_output};
     for (int i = 0; i < n_edges; ++i) es[i] = GEdge{edges[i].src, edges[i].dst, edges[i].delay, edges[i].wkind};
     rnn_graph* g = new (std::nothrow) rnn_graph();
     if (!g) return fail(RNN_ERR_NO_MEMORY, "out of host memory");
@@ -970,7 +970,7 @@ int rnn_output(const rnn_graph* g, int32_t node, const float** d_y) {
     return RNN_OK;
 }
 
-int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targets, void* hip_stream) {
+int rnn_bptt(rnn_graph* g, const float* d_weights, const void* const* d_targets, void* hip_stream) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (!g->fwd_done) return fail(RNN_ERR_SEQUENCE, "rnn_bptt before rnn_forward");
     g->bptt_done = false;
@@ -985,18 +985,22 @@ int rnn_bptt(rnn_graph* g, const float* d_weights, const int32_t* const* d_targe
     if (e != hipSuccess) return fail_hip(e, "loss reset");
     // the output deltas of all frames first (they depend on the forward pass only)
     for (const CompPlan& cp : P.comps) {
-        if (cp.softmax_node < 0) continue;
-        const int k = cp.softmax_node;
+        const int k = cp.softmax_node >= 0 ? cp.softmax_node : cp.sqerr_node;
+        if (k < 0) continue;
         size_t oi = 0;
         while (oi < P.output_nodes.size() && P.output_nodes[oi] != k) ++oi;
-        e = launch_softmax_ce_delta(g->frame0(P.ybuf(k)), d_targets[oi], g->frame0(P.dbuf(k)), g->loss_ptr(), g->ctrl_ptr(),
-                                    (int64_t)T * N, P.xnodes[k].dim, s);
-        if (e != hipSuccess) return fail_hip(e, "softmax / cross-entropy delta");
+        if (cp.softmax_node >= 0)
+            e = launch_softmax_ce_delta(g->frame0(P.ybuf(k)), static_cast<const int32_t*>(d_targets[oi]), g->frame0(P.dbuf(k)), g->loss_ptr(),
+                                        g->ctrl_ptr(), (int64_t)T * N, P.xnodes[k].dim, s);
+        else
+            e = launch_squared_error_delta(g->frame0(P.ybuf(k)), static_cast<const float*>(d_targets[oi]), g->frame0(P.dbuf(k)), g->loss_ptr(),
+                                           (int64_t)T * N * P.xnodes[k].dim, P.xnodes[k].act, s);
+        if (e != hipSuccess) return fail_hip(e, "output delta");
     }
     auto backward_frames = [&](int t0, int t1) -> int {
         for (int c = (int)P.comps.size() - 1; c >= 0; --c) {
             const CompPlan& cp = P.comps[c];
-            if (cp.softmax_node >= 0 || !cp.has_bwd_program) continue;
+            if (cp.softmax_node >= 0 || cp.sqerr_node >= 0 || !cp.has_bwd_program) continue;
             if (!g->framewise && cp.chain >= 0 && P.chains[cp.chain].last == c && !g->chain_choice(cp.chain, true, N).source.empty()) {
                 const ChainPlan& ch = P.chains[cp.chain];
                 for (const CompPlan& m : ch.members) {

@@ -105,6 +105,29 @@ __global__ __launch_bounds__(256) void softmax_ce_delta_kernel(const float* __re
     }
 }
 
+// Squared error E = 1/2 sum_j (d_j - y_j)^2 on an output layer y = f(s) (Section 2.2: the output delta
+// follows the error criterion and the layer's activation): dE/ds = (y - d) f'(s).
+__global__ __launch_bounds__(256) void squared_error_delta_kernel(const float* __restrict__ y, const float* __restrict__ d,
+                                                                  float* __restrict__ ds, double* loss, long long n, int act) {
+    __shared__ float wl[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float l = 0.0f;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += 256LL * gridDim.x) {
+        const float yi = y[i], di = d[i];
+        const float err = di != di ? 0.0f : yi - di;      // a NaN target element carries no error
+        const float fp = act == 1 ? yi * (1.0f - yi) : act == 2 ? 1.0f - yi * yi : 1.0f;
+        ds[i] = err * fp;
+        l += 0.5f * err * err;
+    }
+    l = wave_sum(l);
+    if (lane == 0) wl[wave] = l;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double s = (double)wl[0] + (double)wl[1] + (double)wl[2] + (double)wl[3];
+        if (s != 0.0) atomicAdd(loss, s);
+    }
+}
+
 // grid: (ceil(dim / 64), n_tasks, row splits); block (64, 4).
 __global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off, const float* __restrict__ weights,
                                                      float* __restrict__ grads, int T, int N, int t0) {
@@ -171,6 +194,15 @@ hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float
     if (rows <= 0) return hipSuccess;
     hipLaunchKernelGGL(softmax_ce_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, y, targets, ds, loss, flag,
                        (long long)rows, dim);
+    return hipGetLastError();
+}
+
+hipError_t launch_squared_error_delta(const float* y, const float* d, float* ds, double* loss, int64_t n, int act,
+                                      hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    long long blocks = (n + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(squared_error_delta_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, y, d, ds, loss, (long long)n, act);
     return hipGetLastError();
 }
 

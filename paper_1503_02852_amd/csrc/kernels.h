@@ -52,6 +52,10 @@ hipError_t launch_softmax_rows(float* y, int64_t rows, int dim, hipStream_t stre
 // A target not below dim leaves its frame out and sets *flag to 3.
 hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss, unsigned* flag,
                                    int64_t rows, int dim, hipStream_t stream);
+// Squared-error output layer: ds = (y - d) f'(s) element by element (0 where d is NaN), f' from y
+// for act = linear / sigmoid / tanh; *loss += 1/2 sum (d - y)^2.
+hipError_t launch_squared_error_delta(const float* y, const float* d, float* ds, double* loss, int64_t n, int act,
+                                      hipStream_t stream);
 // Column-sum tasks (diagonal-weight and bias gradients), atomically added into grads.
 // The sums run over frames [t0, T); factors may reach back to frames before t0.
 hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,

@@ -348,6 +348,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             if (shared_y[k]) cp.fwd_shared_bufs.push_back(P.ybuf(k));
             if (shared_d[k]) cp.bwd_shared_bufs.push_back(P.dbuf(k));
             if (xn[k].act == ACT_SOFTMAX) cp.softmax_node = k;
+            else if (xn[k].is_output == OUT_SQUARED_ERROR) cp.sqerr_node = k;
         }
         for (int p = 0; p < n_phases; ++p) {
             std::vector<int> np;
@@ -398,7 +399,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         cp.fwd_desc_off = emit_desc(cp.fwd_phases);
 
         // ---- backward ----
-        if (cp.softmax_node >= 0) return true;   // output delta comes from the softmax / cross-entropy kernel
+        if (cp.softmax_node >= 0 || cp.sqerr_node >= 0) return true;   // the output delta comes from the error-criterion kernel
         for (int j : members) {
             GemmProblemPlan gp; gp.c_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); gp.n = xn[j].dim;
             for (int m : out_e[j])
@@ -462,7 +463,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     // of a member comes from a component before the chain or leads to one after it.
     {
         auto single_phase = [&](const CompPlan& cp) {
-            return cp.recurrent && cp.fwd_phases.size() == 1 && cp.bwd_phases.size() == 1 && cp.softmax_node < 0;
+            return cp.recurrent && cp.fwd_phases.size() == 1 && cp.bwd_phases.size() == 1 && cp.softmax_node < 0 && cp.sqerr_node < 0;
         };
         int c = 0;
         while (c < S.n_comps) {

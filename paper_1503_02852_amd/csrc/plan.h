@@ -42,6 +42,7 @@ struct PhasePlan {
 struct CompPlan {
     bool recurrent = false;
     int softmax_node = -1;                  // exec node id if this component is a softmax output node
+    int sqerr_node = -1;                    // exec node id if this component is a squared-error output node
     std::vector<GemmProblemPlan> fwd_gemms, bwd_gemms;
     std::vector<PhasePlan> fwd_phases, bwd_phases;   // bwd_phases already in execution order
     bool has_fwd_program = false, has_bwd_program = false;

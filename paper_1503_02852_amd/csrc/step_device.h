@@ -1947,4 +1947,256 @@ __device__ __forceinline__ void mstep2_kernel_body(const StepArgs& a, M2Shared& 
     }
 }
 
+// =============================================================================================
+// Streaming variant (run-time specialised, single-phase components, few streams, wide layers).
+//
+// From about 2,000 units on, the full weight matrices inside a recurrent node no longer fit the
+// registers and LDS of the chip (an LSTM layer of 4,096 cells has 256 MiB of them), so a time step
+// really is what the roofline model of the sequential part says: every weight is read from memory
+// once per step.  Each workgroup owns a chunk of every layer's units, as in the other variants, and
+// each of its four wavefronts owns UW of them.  A wavefront's work per step is a set of row
+// segments, one per (unit, task, edge): the weight row W_e[u][0 .. K_e) against source vector
+// x_src(e).  All segments advance together through the columns in chunks of 256 (lane l takes the
+// four columns 256 j + 4 l ...: a wavefront's load covers 1 KiB of consecutive addresses), PD chunks
+// ahead, so that NSEG * PD 128-bit loads per lane are in flight (tens of KiB per compute unit, which
+// is what it takes to keep the memory system busy); the loads of a step's first PD chunks are issued
+// before the step's exchange, because the weights do not depend on it.  The source vectors are
+// polled into LDS by the whole workgroup (sentinel protocol, all loads of an attempt in flight
+// together) and read from there once per (source, stream, chunk) for all segments.  Transposed
+// connections (the backward direction) read a transposed copy of the matrix, made once per window,
+// so that both directions stream rows.
+//
+// SS is a generated descriptor:
+//   static constexpr int NB (streams, padded), CMAX (units per workgroup), UW (units per
+//   wavefront), NT (tasks), NSRC, NSEG, PD, JMAX (256-column chunks of the longest row), NACC
+//   (= UW * NT), XF (floats of the LDS source area), ACCS (row stride of the accumulator area),
+//   PQ (128-bit polling loads per thread over all sources);
+//   constexpr seg_ul(i), seg_task(i), seg_edge(i), seg_src(i), K(s), KP(s) (padded to 256),
+//   xoff(s), pq0(s) / pqn(s) (first polling register and count of source s).
+// =============================================================================================
+struct SShared { StepShared sh; };
+
+template <class PH, class SS>
+__device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms, float* lds, int w) {
+    if (w < 0 || w >= a.G) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int T = a.T, N = a.N;
+    StepShared& sh = ms.sh;
+    if (tid == 0) compute_step_layout(a.words, a.desc_off, a.G, 1, N, sh.lay);
+    __syncthreads();
+    const StepPhase& ph = sh.lay.ph[0];
+    {
+        const int ic = ph.item_chunk;
+        const int il = tid % ic, n = tid / ic;
+        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N ? n : 0xFFFF) << 16);
+    }
+    constexpr int NB = SS::NB, UW = SS::UW, NT = SS::NT, NSEG = SS::NSEG, PD = SS::PD, JMAX = SS::JMAX, NACC = SS::NACC;
+    constexpr int ACCBASE = SS::XF, ACCS = SS::ACCS;
+    for (int i = tid; i < SS::XF + NB * ACCS; i += STEP_THREADS) lds[i] = 0.0f;
+    __syncthreads();
+    PhaseRegs<PH> r;
+    phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
+    const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    const int item_n = tid / suni(ph.item_chunk);
+
+    // this lane's byte offset in each segment's matrix at column chunk 0 (a segment without a unit
+    // behind it stays outside the descriptor: its loads return zeros)
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.weights), 0, (int)a.weight_bytes, STEP_RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rwt = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.weights_t), 0, (int)a.weight_bytes, STEP_RSRC_FLAGS);
+    unsigned voff[NSEG];
+    bool seg_t[NSEG];
+#pragma unroll
+    for (int i = 0; i < NSEG; ++i) {
+        const StepTask& tk = ph.task[SS::seg_task(i)];
+        const StepEdge ed = tk.e[SS::seg_edge(i)];
+        const int chunk = suni(tk.chunk), n_out = suni(tk.n_out);
+        const int ulw = wave * UW + SS::seg_ul(i), u = w * chunk + ulw;
+        const bool ok = ulw < chunk && u < n_out;
+        seg_t[i] = suni(ed.transposed) != 0;
+        voff[i] = ok ? (unsigned)(((long long)suni(ed.w_off) + (long long)u * suni(ed.k_len) + 4 * lane) * 4) : 0xC0000000u;
+    }
+    // weights of chunk j of every segment; columns beyond a row's end read as zero
+    auto load_chunk = [&](mfloatx4 (&dst)[NSEG], int j) {
+#pragma unroll
+        for (int i = 0; i < NSEG; ++i) {
+            constexpr int dummy = 0; (void)dummy;
+            const int K = SS::K(SS::seg_src(i));
+            unsigned off = voff[i] + (unsigned)(j * 1024);
+            if (K % 256 != 0) off = (256 * j + 4 * lane < K) ? off : 0xC0000000u;
+            else if (JMAX * 256 != K) off = (256 * j < K) ? off : 0xC0000000u;
+            const muintx4 v = seg_t[i] ? __builtin_amdgcn_raw_buffer_load_b128(rwt, (int)off, 0, 0)
+                                       : __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0);
+            dst[i] = mfloatx4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+        }
+    };
+
+    bool dead = false;
+    float sn[PH::NG > 0 ? PH::NG : 1];
+    const int nsteps = step_count(a);
+    mfloatx4 wq[PD][NSEG];
+    if (nsteps > 0) step_static_for<0, PD>([&](auto pp) { constexpr int p = decltype(pp)::value; if (p < JMAX) load_chunk(wq[p], p); });
+    for (int step = 0; step < nsteps; ++step) {
+        const int t = step_frame(a, step);
+        float s[MAX_SLOTS];
+        RNNG_STAMP(0);
+#pragma unroll
+        for (int g = 0; g < PH::NG; ++g) {
+            if (PH::gkind(g) == GA_KIND_CARRY) {
+                if (step > 0) {
+                    s[g] = r.carry[PH::cidx(g)];
+                } else {
+                    const int frame = t + r.goff[g];
+                    s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
+                }
+            } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
+                s[g] = sn[g];
+            } else if (PH::gkind(g) != GA_KIND_ACC) {
+                const int frame = t + r.goff[g];
+                float v = 0.0f;
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < T) {
+                    if (PH::gkind(g) == GA_KIND_STATIC) v = r.gptr[g][(long long)frame * r.gstride[g]];
+                    else v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                }
+                s[g] = v;
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+        RNNG_STAMP(1);
+
+        // ---- the exchange: the source vectors of this step into LDS ----
+        {
+            __amdgpu_buffer_rsrc_t rs[SS::NSRC];
+#pragma unroll
+            for (int sidx = 0; sidx < SS::NSRC; ++sidx) {
+                const StepSource& sc = sh.lay.src[sidx];
+                const int frame = t + suni(sc.frame_off);
+                const bool in_window = frame >= 0 && frame < T;
+                const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)(in_window ? frame : 0) * N * SS::K(sidx);
+                rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * SS::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
+            }
+            muintx4 pv[SS::PQ > 0 ? SS::PQ : 1];
+            int spins = 0;
+            for (;;) {
+                step_compiler_barrier();
+                unsigned m = 0;
+#pragma unroll
+                for (int sidx = 0; sidx < SS::NSRC; ++sidx)
+#pragma unroll
+                    for (int q = 0; q < SS::pqn(sidx); ++q)
+                        pv[SS::pq0(sidx) + q] = __builtin_amdgcn_raw_buffer_load_b128(rs[sidx], (tid + STEP_THREADS * q) * 16, 0, STEP_COHERENT_AUX);
+#pragma unroll
+                for (int q = 0; q < SS::PQ; ++q) {
+                    const unsigned m1 = pv[q].x > pv[q].y ? pv[q].x : pv[q].y, m2 = pv[q].z > pv[q].w ? pv[q].z : pv[q].w;
+                    const unsigned m3 = m1 > m2 ? m1 : m2;
+                    m = m > m3 ? m : m3;
+                }
+                if (__builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) == 0 || dead) break;
+                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+            }
+            // [stream][column] per source, rows padded to whole chunks (the padding stays zero)
+#pragma unroll
+            for (int sidx = 0; sidx < SS::NSRC; ++sidx)
+#pragma unroll
+                for (int q = 0; q < SS::pqn(sidx); ++q) {
+                    const int e4 = (tid + STEP_THREADS * q) * 4;      // element index in the frame [N][K]
+                    if (e4 < N * SS::K(sidx)) {
+                        const int n = e4 / SS::K(sidx), k = e4 - n * SS::K(sidx);
+                        const muintx4 v = pv[SS::pq0(sidx) + q];
+                        *reinterpret_cast<mfloatx4*>(&lds[SS::xoff(sidx) + n * SS::KP(sidx) + k]) =
+                            mfloatx4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+                    }
+                }
+        }
+        step_lds_barrier();
+        RNNG_STAMP(2);
+
+        // ---- the contraction: all segments advance together, PD chunks of loads ahead ----
+        float part[NACC][NB];
+#pragma unroll
+        for (int i = 0; i < NACC; ++i)
+#pragma unroll
+            for (int n = 0; n < NB; ++n) part[i][n] = 0.0f;
+        auto consume = [&](const mfloatx4 (&wv)[NSEG], int j) {
+#pragma unroll
+            for (int sidx = 0; sidx < SS::NSRC; ++sidx) {
+                if (256 * j >= SS::KP(sidx)) continue;
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    const mfloatx4 x = *reinterpret_cast<const mfloatx4*>(&lds[SS::xoff(sidx) + n * SS::KP(sidx) + 256 * j + 4 * lane]);
+#pragma unroll
+                    for (int i = 0; i < NSEG; ++i)
+                        if (SS::seg_src(i) == sidx) {
+                            float& p = part[SS::seg_ul(i) * NT + SS::seg_task(i)][n];
+                            p = fmaf(wv[i].x, x.x, p); p = fmaf(wv[i].y, x.y, p); p = fmaf(wv[i].z, x.z, p); p = fmaf(wv[i].w, x.w, p);
+                        }
+                }
+            }
+        };
+        constexpr int JR = (JMAX + PD - 1) / PD * PD;
+#pragma unroll 1
+        for (int jj = 0; jj < JR; jj += PD) {
+            step_static_for<0, PD>([&](auto pp) {
+                constexpr int p = decltype(pp)::value;
+                consume(wq[p], jj + p);
+                // the same register set takes chunk jj + p + PD; past the row's end the next step's first chunks
+                const int jn = jj + p + PD;
+                load_chunk(wq[p], jn < JR ? jn : jn - JR);
+            });
+        }
+        // (chunks JMAX .. JR - 1, if any, were loaded as zeros; the last PD loads are the next step's first chunks)
+        float tot[NACC * NB];
+        {
+            float flat[NACC * NB];
+#pragma unroll
+            for (int i = 0; i < NACC; ++i)
+#pragma unroll
+                for (int n = 0; n < NB; ++n) flat[i * NB + n] = part[i][n];
+            wave_reduce_many<NACC * NB>(flat, tot);
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int ul = 0; ul < UW; ++ul)
+#pragma unroll
+                for (int task = 0; task < NT; ++task)
+#pragma unroll
+                    for (int n = 0; n < NB; ++n)
+                        lds[ACCBASE + n * ACCS + task * SS::CMAX + wave * UW + ul] = tot[(ul * NT + task) * NB + n];
+        }
+        // STATIC inputs of the next step
+        if (step + 1 < nsteps) {
+            const int t2 = a.backward ? t - 1 : t + 1;
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_STATIC) {
+                    const int frame = t2 + r.goff[g];
+                    float x = 0.0f;
+                    if (r.gptr[g] != nullptr && frame >= 0 && frame < T) x = r.gptr[g][(long long)frame * r.gstride[g]];
+                    sn[g] = x;
+                }
+        }
+        RNNG_STAMP(3);
+        step_lds_barrier();
+        RNNG_STAMP(4);
+        // ---- element-wise program: one thread per (stream, unit) ----
+        if (r.n >= 0) {
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_ACC) s[g] = r.gptr[g] != nullptr ? lds[ACCBASE + item_n * ACCS + PH::gaux(g) * SS::CMAX + item_il] : 0.0f;
+            PH::ops(s);
+#pragma unroll
+            for (int q = 0; q < PH::NST; ++q) {
+                if (r.sptr[q] == nullptr) continue;
+                if (PH::stshared(q)) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+                else store_plain(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+            }
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+        }
+        RNNG_STAMP(5);
+        step_lds_barrier();   // the source and accumulator areas are written again in the next step
+    }
+}
+
 }  // namespace rnng

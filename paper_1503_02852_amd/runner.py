@@ -50,8 +50,12 @@ class Window:
 
     def set_targets(self, targets):
         for k in self.g.output_nodes:
-            a = np.ascontiguousarray(targets[k], dtype=np.int32)
-            assert a.shape == (self.T, self.N)
+            if int(self.g.nodes[k, 4]) == 2:      # squared-error output: dense target vectors
+                a = np.ascontiguousarray(targets[k], dtype=np.float32)
+                assert a.shape == (self.T, self.N, int(self.g.nodes[k, 2]))
+            else:
+                a = np.ascontiguousarray(targets[k], dtype=np.int32)
+                assert a.shape == (self.T, self.N)
             self.targets[k] = torch.from_numpy(a).to(self.dev)
 
     def _stream(self):
@@ -79,7 +83,7 @@ class Window:
         for k in self.g.output_nodes:
             d = self.targets[k]
             d[:self.T - frames] = d[frames:].clone()
-            d[self.T - frames:] = torch.from_numpy(np.ascontiguousarray(new_targets[k], dtype=np.int32)).to(self.dev)
+            d[self.T - frames:] = torch.from_numpy(np.ascontiguousarray(new_targets[k])).to(self.dev).to(d.dtype)
         self.forward_range(self.T - frames, self.T)
 
     def bptt(self):

@@ -103,6 +103,10 @@ def test_invalid_graphs_are_rejected():
     bad([X, [wl.MUL, wl.LINEAR, 3, 1, 0], O], [[0, 1, 0, 2], [1, 2, 0, 0]])     # bias on a multiplicative node
     bad([X, H], [[0, 1, 0, 0]])                                                 # no output node
     bad([X, [7, 0, 3, 0, 0], O], ok_edges)                                      # unknown kind
+    bad([X, H, [wl.ADD, wl.SOFTMAX, 2, 1, 2]], ok_edges)                        # squared-error output with softmax
+    bad([X, H, [wl.MUL, wl.LINEAR, 3, 0, 2]], [[0, 1, 0, 0], [1, 2, 0, 2]])     # squared-error output that is multiplicative
+    bad([X, H, [wl.ADD, wl.TANH, 2, 1, 3]], ok_edges)                           # unknown output kind
+    Graph(np.array([X, H, [wl.ADD, wl.TANH, 2, 1, 2]], np.int32), np.array(ok_edges, np.int32))      # a valid squared-error output
 
 
 def test_runtime_argument_errors_without_gpu_work():

@@ -371,3 +371,38 @@ def test_lstm_stack_single_frame_and_two_frames():
 @pytest.mark.parametrize("name", ["lm_elman_n1", "lm_lstm_n1"])
 def test_language_model_shapes_short_window(name):
     run_both(wl.make_config(name, T=24, N=2), check_all_nodes=True, label=name)
+
+
+# ---- output layers with dense targets under the squared error (Section 2.2: the output delta follows the error criterion) ----
+
+@pytest.mark.parametrize("act", [wl.LINEAR, wl.SIGMOID, wl.TANH])
+def test_squared_error_output_layer(act):
+    spec = wl.lstm_net(12, [40, 24], 7, squared_error_act=act)
+    run_both(wl.make_workload("lstm_sq", spec, T=21, N=3, seed=80 + act, scale=0.4, bias_scale=0.3, masked_fraction=0.25), label=f"squared error, act {act}")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_graphs_with_mixed_output_criteria(seed):
+    rng = np.random.default_rng(800 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, n_inputs=1 + seed % 2, squared_error_outputs=1 + seed % 2)
+    run_both(wl.make_workload(f"rand_sq{seed}", spec, T=9 + seed, N=1 + 5 * (seed % 3), seed=seed, scale=0.8, bias_scale=0.5, masked_fraction=0.2))
+
+
+def test_squared_error_many_streams_full_width_frame():
+    """A regression-shaped net at many streams: 256-wide LSTM, 130-wide linear output, N = 40."""
+    spec = wl.lstm_net(20, [256], 130, squared_error_act=wl.LINEAR)
+    run_both(wl.make_workload("lstm_sq_n40", spec, T=12, N=40, seed=84, scale=0.1, bias_scale=0.1), label="squared error, N = 40")
+
+
+# ---- Section 4, second experiment (Fig. 4): LSTM nets whose input, LSTM and output layers are equally wide ----
+
+@pytest.mark.parametrize("H,N,T", [(1024, 1, 6), (1024, 16, 5), (1024, 64, 4), (2048, 1, 6), (2048, 16, 4), (2048, 64, 3),
+                                   (4096, 1, 5), (4096, 16, 3), (4096, 64, 3)])
+def test_fig4_shapes_short_window(H, N, T):
+    """Full widths and stream counts over a short window (the full windows have 2,048 / N frames).
+    From 2,048 units on a layer's recurrent weights no longer fit on chip: the step kernel streams
+    them from memory every step."""
+    w = wl.make_config(f"fig4_h{H}_n{N}", T=T)
+    win, _ = run_both(w, check_all_nodes=True, label=f"fig4_h{H}_n{N}_T{T}")
+    print(f"[parity] fig4_h{H}_n{N}: forward build {win.g.step_build(w.spec.node_by_name('L1.h'))}, "
+          f"backward build {win.g.step_build(w.spec.node_by_name('L1.h'), True)}", flush=True)

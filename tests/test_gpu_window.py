@@ -68,7 +68,20 @@ WINDOW_NETS = {
     "random_a": lambda: (wl.random_graph(np.random.default_rng(501), n_inner=7, max_delay=3, n_inputs=2), 2),
     "random_b": lambda: (wl.random_graph(np.random.default_rng(502), n_inner=8, max_delay=3, n_inputs=1), 3),
     "random_many_streams": lambda: (wl.random_graph(np.random.default_rng(503), n_inner=6, max_delay=2, n_inputs=2), 11),
+    # dense targets under the squared error (masked by NaN)
+    "lstm_squared_error": lambda: (wl.lstm_net(10, [24], 5, squared_error_act=wl.TANH), 2),
+    "random_squared_error": lambda: (wl.random_graph(np.random.default_rng(504), n_inner=7, max_delay=3, squared_error_outputs=2), 2),
 }
+
+
+def mask_older_frames(targets, n_frames):
+    """No error at the first n_frames frames: class index -1, or NaN for dense target vectors."""
+    for k in targets:
+        if isinstance(targets[k], np.ndarray):
+            targets[k][:n_frames] = np.nan if targets[k].dtype.kind == "f" else -1
+        else:
+            targets[k][:n_frames] = float("nan") if targets[k].is_floating_point() else -1
+    return targets
 
 
 @pytest.mark.parametrize("name", sorted(WINDOW_NETS))
@@ -126,13 +139,11 @@ def test_window_moved_ahead_with_carried_state(name):
         new_targets = {k: v[b - hp:b] for k, v in long.targets.items()}
         win.advance({k: v[b - hp:b] for k, v in long.inputs.items()}, new_targets)
         # the older part of the window has been trained on already: mask it
-        masked = {k: v[a:b].copy() for k, v in long.targets.items()}
-        for k in masked:
-            masked[k][:T - hp] = -1
-            win.targets[k][:T - hp] = -1
+        masked = mask_older_frames({k: v[a:b].copy() for k, v in long.targets.items()}, T - hp)
+        mask_older_frames(win.targets, T - hp)
         win.bptt()
         loss = win.compute_grads(want_loss=True)
-        tl = {k: np.concatenate([np.full_like(v[:a], -1), masked[k], np.full_like(v[b:], -1)]) for k, v in long.targets.items()}
+        tl = {k: np.concatenate([v[:a], masked[k], v[b:]]) for k, v in long.targets.items()}      # (only the window's frames count)
         ref = go.bptt_window(long.spec.nodes, long.spec.edges, long.weights, long.biases, y_long, z_long, tl, a, T, N)
         check_against(win, first, ref, f"{name} advance {step}")
         assert abs(loss - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
