@@ -37,6 +37,7 @@ struct Layout {
     int64_t sync_off = 0;                 // 1 KiB of zero-initialised control words; the loss (double) sits at its start
     std::vector<int64_t> buf_off;         // per buffer id, bytes; -1 = not in the workspace
     int64_t partial_off = -1;             // partial sums of the two-dimensional matrix-core kernels (one launch at a time)
+    int64_t wt_off = -1;                  // transposed copies of the matrices the streaming kernels read transposed (parameter layout)
     int64_t flags_off = 0;                // per buffer id: 1 = frame tensor of the workspace (has history frames)
     int64_t total = 0;
 };
@@ -45,7 +46,8 @@ constexpr int64_t SYNC_BYTES = 1024;
 int64_t g_layout_skew = 4352;      // bytes, a multiple of 256 (RNNG_LAYOUT_SKEW overrides: tuning aid)
 
 // partial_floats: floats per frame of the largest partial-sum tensor any launch of the window needs
-Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats) {
+// transposed_copy: a streaming kernel of the window reads matrices transposed
+Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool transposed_copy) {
     Layout L;
     int n_alloc = 0;
     const int K = (int)P.xnodes.size();
@@ -71,6 +73,7 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats) {
         ++n_alloc;
     }
     if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)(T + P.hist) * partial_floats * 4, 256); }
+    if (transposed_copy) { L.wt_off = cur; cur = align_up(cur + P.n_params * 4, 256); }
     L.total = cur;
     return L;
 }
@@ -164,8 +167,9 @@ struct rnn_graph {
     bool use_jit = true;
     bool use_store_window = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false, mstep = false, stream = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
+    struct JitChoice { bool wave = false, mstep = false, stream = false, needs_t = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
+    bool prefer_streaming = false;        // RNNG_STEP_BUILD=stream
     // the workgroups of a step launch wait for each other, so all of them must be resident at once:
     // one per compute unit (256 on a whole MI355X, fewer on a partition)
     int max_workgroups() const { return cu_count > 0 ? cu_count : 256; }
@@ -176,9 +180,23 @@ struct rnn_graph {
         if (it != jit_choices.end()) return it->second;
         JitChoice c;
         const CompPlan& cp = plan.comps[comp];
+        auto try_streaming = [&]() {
+            if (!c.source.empty() || N > 8) return;
+            for (int G : {256, 128, 64, 32}) {
+                if (force_step_G > 0 && G != force_step_G) continue;
+                if (G > max_workgroups()) continue;
+                size_t lds = 0; bool tr = false;
+                std::string src = jit_sstep_source(plan, cp, backward, N, G, &lds, &tr);
+                if (src.empty()) continue;
+                c.source = src; c.stream = true; c.needs_t = tr;
+                c.lp.ok = true; c.lp.G = G; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
+                break;
+            }
+        };
+        if (prefer_streaming) try_streaming();      // (tests: the streaming variant on shapes the other variants would take)
         // 1. wave-autonomous variant: weights in registers, no barriers (single-phase components)
         const int wave_G[6] = {32, 64, 128, 256, 16, 8};
-        for (int i = 0; i < 6 && c.source.empty(); ++i) {
+        for (int i = 0; i < 6 && c.source.empty() && !c.stream; ++i) {
             const int G = force_step_G > 0 ? force_step_G : wave_G[i];
             if (G > max_workgroups()) { if (force_step_G > 0) break; continue; }
             c.source = jit_wave_source(plan, cp, backward, N, G);
@@ -243,6 +261,8 @@ struct rnn_graph {
         // 3. LDS-resident variant
         if (c.source.empty() && plan_step_launch(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, N, force_step_G, c.lp))
             c.source = jit_step_source(plan, cp, backward, c.lp.NB);
+        // 4. streaming variant: the weights do not fit on chip at all (wide layers); every step reads them from memory
+        try_streaming();
         return jit_choices.emplace(key, c).first->second;
     }
     // floats per frame of the largest partial-sum tensor that a step launch of a window with N streams needs
@@ -261,6 +281,20 @@ struct rnn_graph {
         }
         return m;
     }
+    // true if a step launch of a window with N streams reads transposed copies of weight matrices
+    bool transposed_copy(int N) {
+        if (!use_jit) return false;
+        for (size_t c = 0; c < plan.comps.size(); ++c) {
+            const CompPlan& cp = plan.comps[c];
+            if (!cp.recurrent) continue;
+            for (int backward = 0; backward < 2; ++backward) {
+                if (backward ? !cp.has_bwd_program : !cp.has_fwd_program) continue;
+                if (cp.chain >= 0 && !chain_choice(cp.chain, backward != 0, N).source.empty()) continue;
+                if (jit_choice((int)c, backward != 0, N).needs_t) return true;
+            }
+        }
+        return false;
+    }
     // Chains of recurrent components run side by side in one launch: all members in the
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
     // workgroups shared among the members).
@@ -273,7 +307,7 @@ struct rnn_graph {
         if (it != chain_choices.end()) return it->second;
         ChainChoice c;
         const ChainPlan& ch = plan.chains[chain];
-        if (use_jit && use_chains && force_step_G <= 0) {
+        if (use_jit && use_chains && force_step_G <= 0 && !prefer_streaming) {
             for (const CompPlan& m : ch.members) {
                 int pick = 0;
                 for (int G : {32, 16, 8})
@@ -535,6 +569,26 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
             hipError_t e = launch_fill_sentinel(a.partial + (int64_t)t0 * jc->partial_floats, (int64_t)(t1 - t0) * jc->partial_floats, s);
             if (e != hipSuccess) return step_error(e, "sentinel fill");
         }
+        if (jc->stream) {
+            a.weight_bytes = (unsigned)(g->plan.n_params * 4);
+            a.weights_t = g->weights;
+            if (jc->needs_t) {
+                // the matrices this direction reads transposed: a transposed copy at the same offsets, made per launch
+                if (g->layout.wt_off < 0) return step_error(hipErrorInvalidValue, "transposed weight copy missing from the workspace");
+                float* wt = reinterpret_cast<float*>(g->ws + g->layout.wt_off);
+                a.weights_t = wt;
+                StepLayout lay;
+                compute_step_layout(g->plan.words.data(), desc_off, jc->lp.G, 1, N, lay);
+                for (int t = 0; t < lay.ph[0].n_tasks; ++t)
+                    for (int e2 = 0; e2 < lay.ph[0].task[t].n_edges; ++e2) {
+                        const StepEdge& ed = lay.ph[0].task[t].e[e2];
+                        if (!ed.transposed) continue;
+                        // stored [k_len][n_out]; the kernel streams rows of [n_out][k_len]
+                        hipError_t te = launch_transpose(wt + ed.w_off, g->weights + ed.w_off, ed.k_len, lay.ph[0].task[t].n_out, s);
+                        if (te != hipSuccess) return step_error(te, "weight transposition");
+                    }
+            }
+        }
         if (jc->wave && jc->lp.xcd_stride == 8 && g_xcd_local && g->xcd && g->xcd->ok) a.xcc_expect[0] = g->xcd->xcc[0];
         StepLaunchPlan lp_all = jc->lp;
         lp_all.G = jc->lp.G * jc->J;       // launch size; a.G stays the number of unit chunks
@@ -648,6 +702,7 @@ int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes, const rnn_edge
     if (const char* env = std::getenv("RNNG_STEP_WORKGROUPS")) g->force_step_G = std::atoi(env);
     if (const char* env = std::getenv("RNNG_STEP_STREAM_GROUPS")) g->force_step_J = std::atoi(env);
     if (const char* env = std::getenv("RNNG_CHAIN")) g->use_chains = std::atoi(env) != 0;
+    if (const char* env = std::getenv("RNNG_STEP_BUILD")) g->prefer_streaming = std::string(env) == "stream";
     if (const char* env = std::getenv("RNNG_SCHEDULE")) g->framewise = std::string(env) == "framewise";
     if (const char* env = std::getenv("RNNG_LAYOUT_SKEW")) g_layout_skew = std::atoll(env) / 256 * 256;
     if (const char* env = std::getenv("RNNG_BUNDLE"))
@@ -703,7 +758,7 @@ int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
     if ((int64_t)(T + g->plan.hist) * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
-    return make_layout(g->plan, T, N, const_cast<rnn_graph*>(g)->partial_frame_floats(N)).total;
+    return make_layout(g->plan, T, N, const_cast<rnn_graph*>(g)->partial_frame_floats(N), const_cast<rnn_graph*>(g)->transposed_copy(N)).total;
 }
 
 namespace {
@@ -770,8 +825,8 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
         if (!d_inputs[i] && !g->is_onehot(P.input_nodes[i])) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
     if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
-    if (ws_bytes < make_layout(P, T, N, g->partial_frame_floats(N)).total)
-        return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(make_layout(P, T, N, g->partial_frame_floats(N)).total) + " bytes");
+    if (ws_bytes < make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N)).total)
+        return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N)).total) + " bytes");
     if (g->cu_count == 0) {
         // The step kernels' launch shapes depend on how many workgroups the device keeps resident.
         int dev = 0, cus = 0;
@@ -781,7 +836,7 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
         if (cus != g->max_workgroups()) { g->jit_choices.clear(); g->chain_choices.clear(); }      // chosen for a whole device
         g->cu_count = cus;
     }
-    Layout L = make_layout(P, T, N, g->partial_frame_floats(N));
+    Layout L = make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N));
     if (ws_bytes < L.total) return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(L.total) + " bytes");
     if (t_begin > 0) {
         // the earlier frames must be there: same window shape and workspace, computed up to t_begin
@@ -876,7 +931,7 @@ int rnn_forward_static(rnn_graph* g, const float* d_weights, const float* const*
         if (!d_outputs[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "an output tensor pointer is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
     if (g->prof.mask != 0) return fail(RNN_ERR_SEQUENCE, "kernel-class timing creates events: switch it off for rnn_forward_static");
-    const int64_t need = make_layout(P, T, N, g->partial_frame_floats(N)).total;
+    const int64_t need = make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N)).total;
     if (need > (int64_t)RNN_STATIC_WORKSPACE_BYTES)
         return fail(RNN_ERR_WORKSPACE, "the window needs " + std::to_string(need) + " bytes of workspace, the static workspace holds " +
                                            std::to_string((int64_t)RNN_STATIC_WORKSPACE_BYTES));

@@ -229,6 +229,25 @@ __global__ __launch_bounds__(256) void upload_words_kernel(uint32_t* __restrict_
 }
 }  // namespace
 
+namespace {
+__global__ __launch_bounds__(256) void transpose_kernel(float* __restrict__ dst, const float* __restrict__ src, int rows, int cols) {
+    __shared__ float tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(size_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) dst[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+}  // namespace
+
+hipError_t launch_transpose(float* dst, const float* src, int rows, int cols, hipStream_t stream) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(transpose_kernel, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(256), 0, stream, dst, src, rows, cols);
+    return hipGetLastError();
+}
+
 hipError_t launch_copy(float* dst, const float* src, int64_t n, hipStream_t stream) {
     if (n <= 0) return hipSuccess;
     long long blocks = (n + 255) / 256;

@@ -582,6 +582,86 @@ std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool back
     return o.str();
 }
 
+// Streaming variant for N <= 8 streams and layers whose weights do not fit on chip: G unit chunks,
+// weights read from memory every step.  Empty if not eligible; otherwise *lds_bytes receives the
+// dynamic LDS size and *transposed whether the kernel reads transposed copies of some matrices.
+std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed) {
+    const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
+    if (phases.size() != 1 || N < 1 || N > 8 || G < 1 || G > 256) return "";
+    if (P.n_params * 4 >= (int64_t(1) << 31)) return "";      // 32-bit byte offsets into the weight buffers
+    StepLayout lay;
+    compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
+    if (!lay.ok || lay.n_sources < 1) return "";
+    const StepPhase& ph = lay.ph[0];
+    if (ph.n_tasks < 1 || ph.item_chunk * N > STEP_THREADS) return "";
+    const int NT = ph.n_tasks, CMAX = ph.cmax, UW = (CMAX + 3) / 4;
+    struct Seg { int ul, task, edge, src, tr; };
+    std::vector<Seg> segs;
+    bool any_t = false;
+    for (int ul = 0; ul < UW; ++ul)
+        for (int t = 0; t < NT; ++t)
+            for (int e = 0; e < ph.task[t].n_edges; ++e) {
+                segs.push_back(Seg{ul, t, e, ph.task[t].e[e].src, ph.task[t].e[e].transposed});
+                any_t = any_t || ph.task[t].e[e].transposed;
+                if (ph.task[t].e[e].k_len != lay.src[ph.task[t].e[e].src].k_len) return "";
+            }
+    const int NSEG = (int)segs.size(), NACC = UW * NT;
+    if (NSEG < 1 || NSEG > 32 || NACC * N > 128) return "";
+    int JMAX = 0, XF = 0, PQ = 0;
+    std::vector<int> xoff(lay.n_sources), pq0(lay.n_sources), pqn(lay.n_sources);
+    for (int sidx = 0; sidx < lay.n_sources; ++sidx) {
+        const int K = lay.src[sidx].k_len;
+        if (K % 4 != 0) return "";
+        const int KP = (K + 255) / 256 * 256;
+        JMAX = std::max(JMAX, KP / 256);
+        xoff[sidx] = XF; XF += N * KP;
+        pq0[sidx] = PQ; pqn[sidx] = (N * K / 4 + STEP_THREADS - 1) / STEP_THREADS; PQ += pqn[sidx];
+    }
+    if (PQ > 48) return "";
+    const int ACCS = NT * CMAX + 1;
+    const size_t lds = (size_t)(XF + N * ACCS) * 4;
+    if (lds > STEP_LDS_LIMIT) return "";
+    // prefetch depth: about 32 128-bit loads per lane in flight, a power of two that divides the
+    // chunk count where it can (then the loop needs no bounds tests)
+    int PD = 1;
+    while (PD * 2 * NSEG <= 32 && PD * 2 <= 8 && PD * 2 <= JMAX) PD *= 2;
+    while (PD > 1 && JMAX % PD != 0) PD /= 2;
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    emit_phase_descriptor(o, P, phases[0], 0, 0);
+    auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases, int dflt) {
+        o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
+        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
+        o << "            default: return " << dflt << ";\n        }\n    }\n";
+    };
+    o << "struct SS {\n    static constexpr int NB = " << N << ", CMAX = " << CMAX << ", UW = " << UW << ", NT = " << NT << ", NSRC = " << lay.n_sources
+      << ", NSEG = " << NSEG << ", PD = " << PD << ", JMAX = " << JMAX << ", NACC = " << NACC << ", XF = " << XF << ", ACCS = " << ACCS
+      << ", PQ = " << PQ << ";\n";
+    std::vector<std::pair<int, int>> sul, stask, sedge, ssrc, str_, ks, kps, xo, p0, pn;
+    for (int i = 0; i < NSEG; ++i) {
+        sul.push_back({i, segs[i].ul}); stask.push_back({i, segs[i].task}); sedge.push_back({i, segs[i].edge});
+        ssrc.push_back({i, segs[i].src}); str_.push_back({i, segs[i].tr});
+    }
+    for (int sidx = 0; sidx < lay.n_sources; ++sidx) {
+        ks.push_back({sidx, lay.src[sidx].k_len}); kps.push_back({sidx, (lay.src[sidx].k_len + 255) / 256 * 256});
+        xo.push_back({sidx, xoff[sidx]}); p0.push_back({sidx, pq0[sidx]}); pn.push_back({sidx, pqn[sidx]});
+    }
+    emit_switch("seg_ul", "i", sul, 0); emit_switch("seg_task", "i", stask, 0); emit_switch("seg_edge", "i", sedge, 0);
+    emit_switch("seg_src", "i", ssrc, 0); emit_switch("seg_tr", "i", str_, 0);
+    emit_switch("K", "s", ks, 0); emit_switch("KP", "s", kps, 0); emit_switch("xoff", "s", xo, 0);
+    emit_switch("pq0", "s", p0, 0); emit_switch("pqn", "s", pn, 0);
+    o << "};\n";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
+         "    __shared__ SShared ms;\n"
+         "    sstep_kernel_body<PH0, SS>(a, ms, lds, (int)blockIdx.x);\n"
+         "}\n";
+    if (lds_bytes) *lds_bytes = lds;
+    if (transposed) *transposed = any_t;
+    return o.str();
+}
+
 bool jit_compile(const std::string& source, std::string* log_out) {
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_cache.find(source);

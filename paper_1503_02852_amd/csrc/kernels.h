@@ -65,6 +65,8 @@ hipError_t launch_zero_history(float* const* buf_ptr, const int32_t* buf_dim, co
                                hipStream_t stream);
 hipError_t launch_fill(float* p, int64_t n, float v, hipStream_t stream);
 hipError_t launch_copy(float* dst, const float* src, int64_t n, hipStream_t stream);
+// dst[c][r] = src[r][c] for a row-major rows x cols matrix.
+hipError_t launch_transpose(float* dst, const float* src, int rows, int cols, hipStream_t stream);
 // n 32-bit words from HOST memory to DEVICE memory, carried as kernel arguments (the words are read
 // when the call is made; no staging buffer, no allocation).
 hipError_t launch_upload_words(uint32_t* d_dst, const uint32_t* h_src, int64_t n, hipStream_t stream);

@@ -1971,7 +1971,7 @@ __device__ __forceinline__ void mstep2_kernel_body(const StepArgs& a, M2Shared& 
 //   wavefront), NT (tasks), NSRC, NSEG, PD, JMAX (256-column chunks of the longest row), NACC
 //   (= UW * NT), XF (floats of the LDS source area), ACCS (row stride of the accumulator area),
 //   PQ (128-bit polling loads per thread over all sources);
-//   constexpr seg_ul(i), seg_task(i), seg_edge(i), seg_src(i), K(s), KP(s) (padded to 256),
+//   constexpr seg_ul(i), seg_task(i), seg_edge(i), seg_src(i), seg_tr(i) (reads the transposed copy), K(s), KP(s) (padded to 256),
 //   xoff(s), pq0(s) / pqn(s) (first polling register and count of source s).
 // =============================================================================================
 struct SShared { StepShared sh; };
@@ -2003,8 +2003,8 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
     // behind it stays outside the descriptor: its loads return zeros)
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.weights), 0, (int)a.weight_bytes, STEP_RSRC_FLAGS);
     const __amdgpu_buffer_rsrc_t rwt = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.weights_t), 0, (int)a.weight_bytes, STEP_RSRC_FLAGS);
+    constexpr int JR = (JMAX + PD - 1) / PD * PD;      // chunk positions of a step (whole rounds of the PD register sets)
     unsigned voff[NSEG];
-    bool seg_t[NSEG];
 #pragma unroll
     for (int i = 0; i < NSEG; ++i) {
         const StepTask& tk = ph.task[SS::seg_task(i)];
@@ -2012,20 +2012,18 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
         const int chunk = suni(tk.chunk), n_out = suni(tk.n_out);
         const int ulw = wave * UW + SS::seg_ul(i), u = w * chunk + ulw;
         const bool ok = ulw < chunk && u < n_out;
-        seg_t[i] = suni(ed.transposed) != 0;
         voff[i] = ok ? (unsigned)(((long long)suni(ed.w_off) + (long long)u * suni(ed.k_len) + 4 * lane) * 4) : 0xC0000000u;
     }
     // weights of chunk j of every segment; columns beyond a row's end read as zero
     auto load_chunk = [&](mfloatx4 (&dst)[NSEG], int j) {
 #pragma unroll
         for (int i = 0; i < NSEG; ++i) {
-            constexpr int dummy = 0; (void)dummy;
             const int K = SS::K(SS::seg_src(i));
             unsigned off = voff[i] + (unsigned)(j * 1024);
             if (K % 256 != 0) off = (256 * j + 4 * lane < K) ? off : 0xC0000000u;
-            else if (JMAX * 256 != K) off = (256 * j < K) ? off : 0xC0000000u;
-            const muintx4 v = seg_t[i] ? __builtin_amdgcn_raw_buffer_load_b128(rwt, (int)off, 0, 0)
-                                       : __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0);
+            else if (JR * 256 != K) off = (256 * j < K) ? off : 0xC0000000u;
+            const muintx4 v = SS::seg_tr(i) ? __builtin_amdgcn_raw_buffer_load_b128(rwt, (int)off, 0, 0)
+                                            : __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0);
             dst[i] = mfloatx4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
         }
     };
@@ -2120,7 +2118,7 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
         auto consume = [&](const mfloatx4 (&wv)[NSEG], int j) {
 #pragma unroll
             for (int sidx = 0; sidx < SS::NSRC; ++sidx) {
-                if (256 * j >= SS::KP(sidx)) continue;
+                if (SS::KP(sidx) != JR * 256 && 256 * j >= SS::KP(sidx)) continue;
 #pragma unroll
                 for (int n = 0; n < NB; ++n) {
                     const mfloatx4 x = *reinterpret_cast<const mfloatx4*>(&lds[SS::xoff(sidx) + n * SS::KP(sidx) + 256 * j + 4 * lane]);
@@ -2133,7 +2131,6 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
                 }
             }
         };
-        constexpr int JR = (JMAX + PD - 1) / PD * PD;
 #pragma unroll 1
         for (int jj = 0; jj < JR; jj += PD) {
             step_static_for<0, PD>([&](auto pp) {
@@ -2161,7 +2158,7 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
                 for (int task = 0; task < NT; ++task)
 #pragma unroll
                     for (int n = 0; n < NB; ++n)
-                        lds[ACCBASE + n * ACCS + task * SS::CMAX + wave * UW + ul] = tot[(ul * NT + task) * NB + n];
+                        if (wave * UW + ul < SS::CMAX) lds[ACCBASE + n * ACCS + task * SS::CMAX + wave * UW + ul] = tot[(ul * NT + task) * NB + n];
         }
         // STATIC inputs of the next step
         if (step + 1 < nsteps) {

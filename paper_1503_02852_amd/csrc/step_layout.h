@@ -89,6 +89,10 @@ struct StepArgs {
     // tensor the kernel stores (the workspace; at most 2 GiB).
     float* store_base;
     unsigned store_bytes;
+    // Streaming build: a copy of the parameter buffer in which the matrices that the kernel reads
+    // transposed are stored transposed (same offsets), and the size of both buffers in bytes.
+    const float* weights_t;
+    unsigned weight_bytes;
 };
 
 RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }

@@ -406,3 +406,32 @@ def test_fig4_shapes_short_window(H, N, T):
     win, _ = run_both(w, check_all_nodes=True, label=f"fig4_h{H}_n{N}_T{T}")
     print(f"[parity] fig4_h{H}_n{N}: forward build {win.g.step_build(w.spec.node_by_name('L1.h'))}, "
           f"backward build {win.g.step_build(w.spec.node_by_name('L1.h'), True)}", flush=True)
+
+
+# ---- the streaming step kernel (weights read from memory every step) on small and ragged shapes ----
+
+@pytest.mark.parametrize("case", ["lstm_n1", "lstm_n3_ragged", "elman_n8", "generalized_n2", "stack_n1", "gates_n5"])
+def test_streaming_step_kernel_on_small_shapes(monkeypatch, case):
+    """RNNG_STEP_BUILD=stream makes the streaming variant take shapes the register / LDS variants
+    would serve: widths that are no multiples of 256 (ragged last chunk), of the 4 wavefronts'
+    share or of the workgroup count, several sources per task, 1 to 8 streams, both directions
+    (the backward one reads transposed copies), a window computed in two pieces."""
+    from paper_1503_02852_amd.runner import window_for
+    monkeypatch.setenv("RNNG_STEP_BUILD", "stream")
+    spec, T, N = {
+        "lstm_n1": (wl.lstm_net(12, [512], 6), 9, 1),
+        "lstm_n3_ragged": (wl.lstm_net(9, [300], 5), 7, 3),
+        "elman_n8": (wl.elman_net(7, 1100, 4), 6, 8),
+        "generalized_n2": (wl.generalized_net(8, 260, 2, 4), 8, 2),
+        "stack_n1": (wl.lstm_net(10, [768, 520], 6), 7, 1),
+        "gates_n5": (wl.lstm_net(6, [64], 4), 11, 5),
+    }[case]
+    w = wl.make_workload(case, spec, T=T, N=N, seed=90, scale=0.05 if max(n["dim"] for n in spec.nodes) > 400 else 0.2, bias_scale=0.2, masked_fraction=0.2)
+    win, ref = run_both(w, label=f"streaming {case}")
+    rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, b) == ("streaming", False) for k in rec for b in (False, True))
+    win2 = window_for(w)
+    win2.forward_range(0, 3); win2.forward_range(3, T)
+    win2.bptt(); win2.compute_grads(); win2.check()
+    for k in spec.output_nodes():
+        assert nerr(win2.node_output(k), ref["y"][k]) < OUT_TOL
