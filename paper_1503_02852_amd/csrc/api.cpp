@@ -181,12 +181,12 @@ struct rnn_graph {
         JitChoice c;
         const CompPlan& cp = plan.comps[comp];
         auto try_streaming = [&]() {
-            if (!c.source.empty() || N > 8) return;
+            if (!c.source.empty()) return;
             for (int G : {256, 128, 64, 32}) {
                 if (force_step_G > 0 && G != force_step_G) continue;
                 if (G > max_workgroups()) continue;
                 size_t lds = 0; bool tr = false;
-                std::string src = jit_sstep_source(plan, cp, backward, N, G, &lds, &tr);
+                std::string src = N <= 8 ? jit_sstep_source(plan, cp, backward, N, G, &lds, &tr) : jit_smstep_source(plan, cp, backward, N, G, &lds, &tr);
                 if (src.empty()) continue;
                 c.source = src; c.stream = true; c.needs_t = tr;
                 c.lp.ok = true; c.lp.G = G; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
@@ -578,7 +578,8 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
                 float* wt = reinterpret_cast<float*>(g->ws + g->layout.wt_off);
                 a.weights_t = wt;
                 StepLayout lay;
-                compute_step_layout(g->plan.words.data(), desc_off, jc->lp.G, 1, N, lay);
+                compute_step_layout(g->plan.words.data(), desc_off, jc->lp.G, 1, 1, lay);      // (one stream: only the task list is needed)
+                if (!lay.ok) return step_error(hipErrorInvalidValue, "step layout of a streaming kernel");
                 for (int t = 0; t < lay.ph[0].n_tasks; ++t)
                     for (int e2 = 0; e2 < lay.ph[0].task[t].n_edges; ++e2) {
                         const StepEdge& ed = lay.ph[0].task[t].e[e2];

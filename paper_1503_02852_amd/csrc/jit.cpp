@@ -662,6 +662,86 @@ std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, i
     return o.str();
 }
 
+// Streaming matrix-core variant for N >= 9 streams and layers whose weights do not fit on chip.
+std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed) {
+    const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
+    if (phases.size() != 1 || N < 9 || G < 1 || G > 256) return "";
+    if (P.n_params * 4 >= (int64_t(1) << 31)) return "";      // 32-bit byte offsets into the weight buffers
+    const int32_t* pg = P.words.data() + phases[0].prog_off;
+    const int ic = (pg[PG_MAXDIM] + G - 1) / G;
+    if (ic < 1 || ic > STEP_THREADS) return "";
+    const int SPP = std::min(N, STEP_THREADS / ic), IPT = (N + SPP - 1) / SPP;
+    if (IPT > 8) return "";
+    StepLayout lay;
+    compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, SPP, lay);
+    if (!lay.ok || lay.n_sources < 1) return "";
+    const StepPhase& ph = lay.ph[0];
+    if (ph.n_tasks < 1) return "";
+    const int NT = ph.n_tasks, CMAX = ph.cmax;
+    const int MT = (N + 15) / 16, NTU = (NT * CMAX + 15) / 16;
+    if (MT * NTU > 16) return "";
+    int tr = -1;
+    std::vector<std::pair<int, int>> edge_of;      // (s * STEP_MAX_TASKS + task) -> edge
+    for (int t = 0; t < NT; ++t)
+        for (int e = 0; e < ph.task[t].n_edges; ++e) {
+            const StepEdge& ed = ph.task[t].e[e];
+            if (tr >= 0 && tr != ed.transposed) return "";
+            tr = ed.transposed;
+            if (ed.k_len != lay.src[ed.src].k_len || ed.k_len % 4 != 0) return "";
+            for (auto& pr : edge_of) if (pr.first == ed.src * STEP_MAX_TASKS + t) return "";      // two connections of one task from one source
+            edge_of.push_back({ed.src * STEP_MAX_TASKS + t, e});
+        }
+    if (tr < 0) return "";
+    int kmax = 0;
+    for (int sidx = 0; sidx < lay.n_sources; ++sidx) kmax = std::max(kmax, lay.src[sidx].k_len);
+    // D register sets, D - 1 chunks of (MT + NTU) 128-bit loads per lane in flight: about 40
+    const int dmax = std::max(2, std::min({8, 40 / (MT + NTU) + 1, (kmax + 63) / 64 + 1}));
+    int D = dmax, best_slots = 1 << 30;
+    for (int d = dmax; d >= std::max(2, dmax - 2); --d) {
+        int slots = 0;
+        for (int sidx = 0; sidx < lay.n_sources; ++sidx) slots += ((lay.src[sidx].k_len + 63) / 64 + d - 1) / d * d;
+        if (slots < best_slots) { best_slots = slots; D = d; }
+    }
+    const int ACCS = NTU * 16 + 4;
+    const size_t lds = (size_t)4 * MT * 16 * ACCS * 4;
+    if (lds > STEP_LDS_LIMIT) return "";
+    std::ostringstream o;
+    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+    emit_phase_descriptor(o, P, phases[0], 0, 0);
+    auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases, int dflt) {
+        o << "    static __device__ __forceinline__ constexpr int " << name << "(int " << arg << ") {\n        switch (" << arg << ") {\n";
+        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << ";\n";
+        o << "            default: return " << dflt << ";\n        }\n    }\n";
+    };
+    o << "struct SM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << lay.n_sources << ", NTU = " << NTU << ", D = " << D
+      << ", CMAX = " << CMAX << ", ACCS = " << ACCS << ", TR = " << tr << ", IPT = " << IPT << ", SPP = " << SPP << ";\n";
+    std::vector<std::pair<int, int>> ks, used, ngr;
+    for (int sidx = 0; sidx < lay.n_sources; ++sidx) {
+        ks.push_back({sidx, lay.src[sidx].k_len});
+        for (int nt = 0; nt < NTU; ++nt) {
+            bool any = false;
+            for (int col = nt * 16; col < nt * 16 + 16; ++col) {
+                const int t = col / CMAX;
+                for (auto& pr : edge_of) if (t < NT && pr.first == sidx * STEP_MAX_TASKS + t) any = true;
+            }
+            if (any) used.push_back({sidx * 16 + nt, 1});
+        }
+        ngr.push_back({sidx, ((lay.src[sidx].k_len + 63) / 64 + D - 1) / D});
+    }
+    emit_switch("K", "s", ks, 0); emit_switch("edge_", "key", edge_of, -1); emit_switch("used_", "key", used, 0); emit_switch("ngr", "s", ngr, 0);
+    o << "    static __device__ __forceinline__ constexpr int edge(int s, int task) { return edge_(s * " << STEP_MAX_TASKS << " + task); }\n";
+    o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
+    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+         "void rnng_step_jit(StepArgs a) {\n"
+         "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
+         "    __shared__ SShared ms;\n"
+         "    smstep_kernel_body<PH0, SM>(a, ms, lds, (int)blockIdx.x);\n"
+         "}\n";
+    if (lds_bytes) *lds_bytes = lds;
+    if (transposed) *transposed = tr != 0;
+    return o.str();
+}
+
 bool jit_compile(const std::string& source, std::string* log_out) {
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_cache.find(source);

@@ -2196,4 +2196,291 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
     }
 }
 
+
+// =============================================================================================
+// Streaming matrix-core variant (run-time specialised, single-phase components, many streams, wide
+// layers): the matrix-core variant above with the weights read from memory every step instead of
+// kept in LDS.  Lane (c, q) of a wavefront loads, per 64-column chunk and 16-row tile, the four
+// weights W[row c][k0 + 16 wave + 4 q ...] with one 128-bit load (B operands) next to the polling
+// load of the four source values of stream c (A operands); D register sets hold the operands of D
+// chunks, so that (MT + NTU) * (D - 1) loads per lane are in flight.  The weight loads of a step's
+// first chunks are issued before the hold-off of the polling loads: they do not depend on the
+// exchange.  With more (stream, unit) items than threads the element-wise program runs in IPT
+// passes of SPP streams each (the accumulator tiles hold all streams).
+//
+// SM is a generated descriptor:
+//   static constexpr int NJ (streams), MT, NSRC, NTU, D, CMAX, ACCS, TR (1: the matrices are read
+//   from the transposed copy), IPT, SPP; constexpr K(s), ngr(s), edge(s, task) (edge of the task
+//   that reads source s, -1: none), used(s, nt).
+// =============================================================================================
+template <class PH, class SM>
+__device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& ms, float* lds, int w) {
+    if (w < 0 || w >= a.G) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int T = a.T, N = a.N;
+    StepShared& sh = ms.sh;
+    constexpr int IPT = SM::IPT, SPP = SM::SPP;
+    if (tid == 0) compute_step_layout(a.words, a.desc_off, a.G, 1, SPP < SM::NJ ? SPP : SM::NJ, sh.lay);
+    __syncthreads();
+    const StepPhase& ph = sh.lay.ph[0];
+    {
+        const int ic = ph.item_chunk;
+        const int il = tid % ic, n = tid / ic;
+        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N && n < SPP ? n : 0xFFFF) << 16);
+    }
+    constexpr int CMAX = SM::CMAX, D = SM::D, NPAD = SM::MT * 16, ACCS = SM::ACCS;
+    for (int i = tid; i < 4 * NPAD * ACCS; i += STEP_THREADS) lds[i] = 0.0f;
+    __syncthreads();
+    PhaseRegs<PH> r;
+    phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
+    const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    const int item_n = tid / suni(ph.item_chunk);
+    // floats between the same item of consecutive passes, per gather / store (SPP streams further on)
+    int gpass[PH::NG > 0 ? PH::NG : 1], spass[PH::NST > 0 ? PH::NST : 1];
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g) gpass[g] = SPP * (r.gstride[g] / N);
+#pragma unroll
+    for (int q = 0; q < PH::NST; ++q) spass[q] = SPP * (r.sstride[q] / N);
+
+    const __amdgpu_buffer_rsrc_t rwb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(SM::TR ? a.weights_t : a.weights), 0, (int)a.weight_bytes, STEP_RSRC_FLAGS);
+    const int wcol = wave * 16 + 4 * (lane >> 4);
+    // byte offset of this lane's B operand in chunk 0, per source and row tile (no row behind the
+    // lane's tile column, or the task does not read the source: outside the descriptor)
+    unsigned boff[SM::NSRC][SM::NTU];
+#pragma unroll
+    for (int sidx = 0; sidx < SM::NSRC; ++sidx)
+#pragma unroll
+        for (int nt = 0; nt < SM::NTU; ++nt) {
+            const int col = nt * 16 + (lane & 15);
+            const int task = col / CMAX, ul = col - task * CMAX;
+            unsigned off = 0xC0000000u;
+#pragma unroll
+            for (int t2 = 0; t2 < STEP_MAX_TASKS; ++t2)
+                if (task == t2 && SM::edge(sidx, t2) >= 0) {
+                    const StepTask& tk = ph.task[t2];
+                    const int u = w * tk.chunk + ul;
+                    if (ul < tk.chunk && u < tk.n_out)
+                        off = (unsigned)(((long long)tk.e[SM::edge(sidx, t2) >= 0 ? SM::edge(sidx, t2) : 0].w_off + (long long)u * SM::K(sidx) + wcol) * 4);
+                }
+            boff[sidx][nt] = off;
+        }
+    int aoff[SM::NSRC][SM::MT];
+#pragma unroll
+    for (int sidx = 0; sidx < SM::NSRC; ++sidx)
+#pragma unroll
+        for (int mt = 0; mt < SM::MT; ++mt) {
+            const int n = mt * 16 + (lane & 15);
+            aoff[sidx][mt] = n < N ? (n * SM::K(sidx) + wcol) * 4 : 0x7FFFFFF0;
+        }
+
+    bool dead = false;
+    int pdelay = 0;
+    float sn[IPT][PH::NG > 0 ? PH::NG : 1];
+    float carry[IPT][PH::NC > 0 ? PH::NC : 1];
+#pragma unroll
+    for (int p = 0; p < IPT; ++p)
+#pragma unroll
+        for (int c = 0; c < (PH::NC > 0 ? PH::NC : 1); ++c) carry[p][c] = 0.0f;
+    const int nsteps = step_count(a);
+    for (int step = 0; step < nsteps; ++step) {
+        const int t = step_frame(a, step);
+        RNNG_STAMP(0);
+        __amdgpu_buffer_rsrc_t rs[SM::NSRC];
+#pragma unroll
+        for (int sidx = 0; sidx < SM::NSRC; ++sidx) {
+            const StepSource& sc = sh.lay.src[sidx];
+            const int frame = t + suni(sc.frame_off);
+            const bool in_window = frame >= 0 && frame < T;
+            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)(in_window ? frame : 0) * N * SM::K(sidx);
+            rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * SM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
+        }
+        muintx4 v[D][SM::MT];
+        mfloatx4 wb[D][SM::NTU];
+        auto load_a = [&](muintx4 (&dst)[SM::MT], const __amdgpu_buffer_rsrc_t& rsrc, const int (&base)[SM::MT], int K, bool k_ragged, int k0, bool on) {
+#pragma unroll
+            for (int mt = 0; mt < SM::MT; ++mt) {
+                int off = base[mt] + k0 * 4;
+                if (k_ragged) off = k0 + wcol < K ? off : 0x7FFFFFF0;
+                off = on ? off : 0x7FFFFFF0;
+                dst[mt] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
+            }
+        };
+        auto load_b = [&](mfloatx4 (&dst)[SM::NTU], const unsigned (&base)[SM::NTU], int K, bool k_ragged, int k0, bool on) {
+#pragma unroll
+            for (int nt = 0; nt < SM::NTU; ++nt) {
+                unsigned off = base[nt] + (unsigned)(k0 * 4);
+                if (k_ragged) off = k0 + wcol < K ? off : 0xC0000000u;
+                off = on ? off : 0xC0000000u;
+                const muintx4 x = __builtin_amdgcn_raw_buffer_load_b128(rwb, (int)off, 0, 0);
+                dst[nt] = mfloatx4{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
+            }
+        };
+        auto incomplete = [&](const muintx4 (&x)[SM::MT]) {
+            unsigned m = 0;
+#pragma unroll
+            for (int mt = 0; mt < SM::MT; ++mt) {
+                const unsigned m1 = x[mt].x > x[mt].y ? x[mt].x : x[mt].y, m2 = x[mt].z > x[mt].w ? x[mt].z : x[mt].w;
+                const unsigned m3 = m1 > m2 ? m1 : m2;
+                m = m > m3 ? m : m3;
+            }
+            return __builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) != 0;
+        };
+        // the weights of the first chunks do not wait for the exchange
+        step_static_for<0, D - 1>([&](auto ii) {
+            constexpr int i = decltype(ii)::value;
+            load_b(wb[i], boff[0], SM::K(0), SM::K(0) % 64 != 0, i * 64, i * 64 < (SM::K(0) + 63) / 64 * 64);
+        });
+        for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
+        bool retried = false;
+        step_static_for<0, D - 1>([&](auto ii) {
+            constexpr int i = decltype(ii)::value;
+            load_a(v[i], rs[0], aoff[0], SM::K(0), SM::K(0) % 64 != 0, i * 64, i * 64 < (SM::K(0) + 63) / 64 * 64);
+        });
+        mfloatx4 acc[SM::MT][SM::NTU];
+#pragma unroll
+        for (int mt = 0; mt < SM::MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < SM::NTU; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+        bool bad = incomplete(v[0]);
+
+        step_static_for<0, SM::NSRC>([&](auto ss) {
+            constexpr int sidx = decltype(ss)::value;
+            constexpr int NGR = SM::ngr(sidx);
+            constexpr int KP = (SM::K(sidx) + 63) / 64 * 64;
+            constexpr int snext = sidx + 1 < SM::NSRC ? sidx + 1 : sidx;
+            constexpr int KPN = (SM::K(snext) + 63) / 64 * 64;
+#pragma unroll 1
+            for (int g = 0; g < NGR; ++g) {
+                step_static_for<0, D>([&](auto ii) {
+                    constexpr int i = decltype(ii)::value;
+                    constexpr int j = (i + D - 1) % D;
+                    constexpr int i1 = (i + 1) % D;
+                    const int k0 = (g * D + i) * 64;
+                    const int gj = i == 0 ? g : g + 1;
+                    const bool same = gj < NGR;
+                    const int kj = same ? (gj * D + j) * 64 : j * 64;
+                    const bool on = same ? kj < KP : (sidx + 1 < SM::NSRC && kj < KPN);
+                    auto ahead = [&]() {
+                        if (same) {
+                            load_b(wb[j], boff[sidx], SM::K(sidx), SM::K(sidx) % 64 != 0, kj, on);
+                            load_a(v[j], rs[sidx], aoff[sidx], SM::K(sidx), SM::K(sidx) % 64 != 0, kj, on);
+                        } else {
+                            load_b(wb[j], boff[snext], SM::K(snext), SM::K(snext) % 64 != 0, kj, on);
+                            load_a(v[j], rs[snext], aoff[snext], SM::K(snext), SM::K(snext) % 64 != 0, kj, on);
+                        }
+                    };
+                    if (k0 < KP) {
+                        if (bad && !dead) {
+                            retried = true;
+                            muintx4 again[SM::MT];
+                            int spins = 0;
+                            for (;;) {
+                                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                                __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
+                                step_compiler_barrier();
+                                load_a(again, rs[sidx], aoff[sidx], SM::K(sidx), SM::K(sidx) % 64 != 0, k0, true);
+                                if (!incomplete(again)) break;
+                            }
+#pragma unroll
+                            for (int mt = 0; mt < SM::MT; ++mt) v[i][mt] = again[mt];
+                        }
+                        if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
+                        // the operands of this chunk, before the set of the chunk before it is loaded again
+                        mfloatx4 opb[SM::NTU];
+#pragma unroll
+                        for (int nt = 0; nt < SM::NTU; ++nt) opb[nt] = wb[i][nt];
+                        ahead();
+                        bad = incomplete(v[i1]);
+#pragma unroll
+                        for (int mt = 0; mt < SM::MT; ++mt)
+#pragma unroll
+                            for (int nt = 0; nt < SM::NTU; ++nt)
+                                if (SM::used(sidx, nt)) {
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].x), opb[nt][0], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].y), opb[nt][1], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].z), opb[nt][2], acc[mt][nt], 0, 0, 0);
+                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
+                                }
+                    } else {
+                        ahead();
+                        bad = incomplete(v[i1]);
+                    }
+                });
+            }
+        });
+        // ---- hand the accumulators to the element-wise threads: one partial tile per wavefront ----
+        {
+            const int tb = wave * (NPAD * ACCS);
+#pragma unroll
+            for (int mt = 0; mt < SM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < SM::NTU; ++nt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        lds[tb + (mt * 16 + 4 * (lane >> 4) + i) * ACCS + nt * 16 + (lane & 15)] = acc[mt][nt][i];
+        }
+        RNNG_STAMP(3);
+        if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
+        else if ((step & 63) == 63 && pdelay > 0) --pdelay;
+        RNNG_STAMP(4);
+        // ---- element-wise program: IPT passes, one thread per (stream, unit) in each ----
+#pragma unroll
+        for (int p = 0; p < IPT; ++p) {
+            const int pn = item_n + p * SPP;      // the pass's stream
+            if (r.n < 0 || pn >= N) continue;
+            float s[MAX_SLOTS];
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g) {
+                if (PH::gkind(g) == GA_KIND_ACC) {
+                    float x = 0.0f;
+                    if (r.gptr[g] != nullptr) {
+                        const int tb = pn * ACCS + PH::gaux(g) * CMAX + item_il;
+                        x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
+                    }
+                    s[g] = x;
+                } else if (PH::gkind(g) == GA_KIND_CARRY && step > 0) {
+                    s[g] = carry[p][PH::cidx(g)];
+                } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
+                    s[g] = sn[p][g];
+                } else {
+                    const int frame = t + r.goff[g];
+                    float x = 0.0f;
+                    if (r.gptr[g] != nullptr && frame >= 0 && frame < T) {
+                        const float* src = r.gptr[g] + (long long)frame * r.gstride[g] + (long long)p * gpass[g];
+                        x = PH::gkind(g) == GA_KIND_FRAMES ? load_coherent(src) : *src;
+                    }
+                    s[g] = x;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < PH::NI; ++q) s[PH::NG + q] = r.inv[q];
+            PH::ops(s);
+#pragma unroll
+            for (int q = 0; q < PH::NST; ++q) {
+                if (r.sptr[q] == nullptr) continue;
+                float* dst = r.sptr[q] + (long long)t * r.sstride[q] + (long long)p * spass[q];
+                if (PH::stshared(q)) store_shared(dst, s[PH::stslot(q)]);
+                else store_plain(dst, s[PH::stslot(q)]);
+            }
+#pragma unroll
+            for (int g = 0; g < PH::NG; ++g)
+                if (PH::gkind(g) == GA_KIND_CARRY) carry[p][PH::cidx(g)] = s[PH::gaux(g)];
+            // STATIC inputs of the next step
+            if (step + 1 < nsteps) {
+                const int t2 = a.backward ? t - 1 : t + 1;
+#pragma unroll
+                for (int g = 0; g < PH::NG; ++g)
+                    if (PH::gkind(g) == GA_KIND_STATIC) {
+                        const int frame = t2 + r.goff[g];
+                        float x = 0.0f;
+                        if (r.gptr[g] != nullptr && frame >= 0 && frame < T) x = r.gptr[g][(long long)frame * r.gstride[g] + (long long)p * gpass[g]];
+                        sn[p][g] = x;
+                    }
+            }
+        }
+        RNNG_STAMP(5);
+        step_lds_barrier();   // the tiles are written again in the next step
+    }
+}
+
 }  // namespace rnng

@@ -410,12 +410,14 @@ def test_fig4_shapes_short_window(H, N, T):
 
 # ---- the streaming step kernel (weights read from memory every step) on small and ragged shapes ----
 
-@pytest.mark.parametrize("case", ["lstm_n1", "lstm_n3_ragged", "elman_n8", "generalized_n2", "stack_n1", "gates_n5"])
+@pytest.mark.parametrize("case", ["lstm_n1", "lstm_n3_ragged", "elman_n8", "generalized_n2", "stack_n1", "gates_n5",
+                                  "lstm_n12", "lstm_n40_ragged", "elman_n33", "generalized_n20", "stack_n16", "wide_units_n70"])
 def test_streaming_step_kernel_on_small_shapes(monkeypatch, case):
     """RNNG_STEP_BUILD=stream makes the streaming variant take shapes the register / LDS variants
-    would serve: widths that are no multiples of 256 (ragged last chunk), of the 4 wavefronts'
-    share or of the workgroup count, several sources per task, 1 to 8 streams, both directions
-    (the backward one reads transposed copies), a window computed in two pieces."""
+    would serve: widths that are no multiples of 256 or 64 (ragged last chunk), of the 4 wavefronts'
+    share or of the workgroup count, several sources per task, 1 to 8 streams (vector arithmetic)
+    and more (matrix cores), both directions (the backward one reads transposed copies), a window
+    computed in two pieces."""
     from paper_1503_02852_amd.runner import window_for
     monkeypatch.setenv("RNNG_STEP_BUILD", "stream")
     spec, T, N = {
@@ -425,6 +427,13 @@ def test_streaming_step_kernel_on_small_shapes(monkeypatch, case):
         "generalized_n2": (wl.generalized_net(8, 260, 2, 4), 8, 2),
         "stack_n1": (wl.lstm_net(10, [768, 520], 6), 7, 1),
         "gates_n5": (wl.lstm_net(6, [64], 4), 11, 5),
+        # more than 8 streams: the matrix-core form of the streaming variant
+        "lstm_n12": (wl.lstm_net(12, [512], 6), 6, 12),
+        "lstm_n40_ragged": (wl.lstm_net(9, [300], 5), 5, 40),
+        "elman_n33": (wl.elman_net(7, 1100, 4), 5, 33),
+        "generalized_n20": (wl.generalized_net(8, 260, 2, 4), 6, 20),
+        "stack_n16": (wl.lstm_net(10, [768, 520], 6), 5, 16),
+        "wide_units_n70": (wl.lstm_net(6, [1536], 4), 4, 70),      # 6 units per workgroup x 70 streams: two element-wise passes
     }[case]
     w = wl.make_workload(case, spec, T=T, N=N, seed=90, scale=0.05 if max(n["dim"] for n in spec.nodes) > 400 else 0.2, bias_scale=0.2, masked_fraction=0.2)
     win, ref = run_both(w, label=f"streaming {case}")
