@@ -176,3 +176,21 @@ def test_step_kernel_variants_compile(monkeypatch, early, window):
     spec2 = wl.elman_net(7, 33, 4)
     g2 = binding.Graph(spec2.node_array(), spec2.edge_array())
     assert g2.specialise(3) == 2
+
+
+@pytest.mark.parametrize("H,N", [(2048, 1), (4096, 1), (2048, 16), (4096, 64)])
+def test_wide_layers_get_a_streaming_step_kernel(H, N):
+    """Section 4's second experiment (all layers 2,048 or 4,096 wide): the recurrent weights fit
+    neither registers nor LDS, so both directions must be served by the streaming build (one
+    kernel per direction compiles for gfx950) and the backward one needs the transposed copy of
+    the parameter buffer in the workspace."""
+    import workloads as wl
+    from paper_1503_02852_amd import binding
+    spec = wl.lstm_net(H, [H], H)
+    g = binding.Graph(spec.node_array(), spec.edge_array())
+    n = g.specialise(N)
+    if n == 0:
+        pytest.skip("run-time compiler not available")
+    assert n == 2
+    # room for the transposed copy of the parameter buffer
+    assert g.workspace_bytes(8, N) > 4 * g.param_count()
