@@ -195,6 +195,12 @@ int rnn_state_grad(const rnn_graph* g, int32_t node, const float** d_ds);
  *            reports the window's error flags like rnn_check. */
 int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream);
 
+/* on != 0: every gradient element has one writer and a fixed order of additions, so rnn_grads
+ * returns the same bits from run to run (the weight-gradient and column sums are then not split
+ * over workgroups that add atomically: slower where a sum is long and its matrix small).  Off by
+ * default.  E_total is a double sum of per-workgroup parts whose order is not fixed either way. */
+int rnn_set_deterministic(rnn_graph* g, int32_t on);
+
 /* Waits for hip_stream and reports what the kernels of the current window have flagged since its
  * rnn_forward (or rnn_forward_range(.., 0, ..)): RNN_ERR_DEVICE if a recurrent step kernel gave up
  * a bounded wait or found itself on another XCD than observed (the window's activations and

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "librnngraph.so")
 EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_param_count",
            "rnn_edge_param_offset", "rnn_bias_param_offset", "rnn_workspace_bytes", "rnn_forward",
            "rnn_forward_range", "rnn_shift_window", "rnn_set_onehot_input",
-           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_check", "rnn_specialise",
+           "rnn_output", "rnn_bptt", "rnn_state_grad", "rnn_grads", "rnn_check", "rnn_set_deterministic", "rnn_specialise",
            "rnn_forward_static", "rnn_last_error"]
 # measurement and inspection aids (include/rnngraph_aux.h)
 AUX_EXPORTS = ["rnn_step_build", "rnn_debug_read_control", "rnn_profile_enable", "rnn_profile_read", "rnn_plan_work"]
@@ -74,6 +74,8 @@ def load_library(build_if_missing=True):
     lib.rnn_state_grad.restype = C.c_int
     lib.rnn_grads.argtypes = [vp, vp, C.POINTER(C.c_double), vp]
     lib.rnn_grads.restype = C.c_int
+    lib.rnn_set_deterministic.argtypes = [vp, C.c_int32]
+    lib.rnn_set_deterministic.restype = C.c_int
     lib.rnn_check.argtypes = [vp, vp]
     lib.rnn_check.restype = C.c_int
     lib.rnn_step_build.argtypes = [vp, C.c_int32, C.c_int32, i32p]
@@ -221,6 +223,9 @@ class Graph:
 
     def specialise(self, N):
         return _check(self.lib.rnn_specialise(self.handle, N))
+
+    def set_deterministic(self, on=True):
+        _check(self.lib.rnn_set_deterministic(self.handle, 1 if on else 0))
 
     def check(self, stream=0):
         _check(self.lib.rnn_check(self.handle, stream))

@@ -138,6 +138,7 @@ struct rnn_graph {
     bool fwd_done = false, bptt_done = false;
     int fwd_upto = 0;                     // frames [0, fwd_upto) of the current window hold forward results
     bool framewise = false;               // benchmark mode: every frame on its own, no batching over frames
+    bool deterministic = false;           // rnn_set_deterministic: one writer per gradient element, fixed summation order
     bool no_alloc = false;                // inside rnn_forward_static: load no code, create no events, stage no host copies
     PlanView view() const {
         PlanView pv;
@@ -374,7 +375,7 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
                 for (int q = 0; q < grp.p[i].n_pairs; ++q) kmax = std::max(kmax, grp.p[i].pairs[q].K);
             }
             int split = 1;
-            if (tiles < 256) split = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, kmax / 512), (512 + tiles - 1) / tiles));
+            if (tiles < 256 && !g->deterministic) split = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(16, kmax / 512), (512 + tiles - 1) / tiles));
             grp.split_k = split;
             if (split > 1 && !grp.accumulate)
                 for (int i = 0; i < grp.n_problems; ++i) {
@@ -1119,7 +1120,7 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
         int split = (int)((1024 + tiles - 1) / tiles);
         const int max_split = (int)((F + 127) / 128);
         if (split > max_split) split = max_split;
-        if (split < 1) split = 1;
+        if (split < 1 || g->deterministic) split = 1;
         // split_k > 1 adds atomically into the zeroed buffer; split_k == 1 must add too (accumulate)
         grp.split_k = split; grp.accumulate = 1;
         hipError_t r = launch_gemm_group(GEMM_TN, grp, s);
@@ -1129,7 +1130,8 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
     for (const GradGemmPlan& gg : P.grad_gemms) {
         if (g->is_onehot(gg.src_buf)) {      // scatter-add instead of a GEMM over a one-hot matrix (indices have no history: frames before the window are zero vectors)
             if (F - (int64_t)gg.delay * N <= 0) continue;
-            e = launch_onehot_scatter(d_grads + gg.w_off, g->frame0(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F, s);
+            e = launch_onehot_scatter(d_grads + gg.w_off, g->frame0(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F,
+                                      g->deterministic, s);
             if (e != hipSuccess) return fail_hip(e, "one-hot weight gradient");
             ++n_launch;
             continue;
@@ -1147,9 +1149,15 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
     e = flush();
     if (e != hipSuccess) return fail_hip(e, "gradient GEMM");
     g->prof.end(prof, n_launch, s);
-    e = launch_colsum(g->view(), P.colsum_off, P.n_colsum, P.colsum_max_dim, g->weights, d_grads, H + T, N, H, s);
+    e = launch_colsum(g->view(), P.colsum_off, P.n_colsum, P.colsum_max_dim, g->weights, d_grads, H + T, N, H, g->deterministic, s);
     if (e != hipSuccess) return fail_hip(e, "diagonal / bias gradient");
     if (loss) return read_control(g, loss, s);
+    return RNN_OK;
+}
+
+int rnn_set_deterministic(rnn_graph* g, int32_t on) {
+    if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
+    g->deterministic = on != 0;
     return RNN_OK;
 }
 

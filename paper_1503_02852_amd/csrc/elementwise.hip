@@ -207,12 +207,12 @@ hipError_t launch_squared_error_delta(const float* y, const float* d, float* ds,
 }
 
 hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
-                         int T, int N, int t0, hipStream_t stream) {
+                         int T, int N, int t0, bool one_writer, hipStream_t stream) {
     if (n_tasks <= 0 || max_dim <= 0) return hipSuccess;
     const long long rows = (long long)(T - t0) * N;
     int splits = (int)((rows + 63) / 64);
     if (splits > 128) splits = 128;
-    if (splits < 1) splits = 1;
+    if (splits < 1 || one_writer) splits = 1;      // one workgroup per (task, 64 units): a fixed order of additions
     hipLaunchKernelGGL(colsum_kernel, dim3((max_dim + 63) / 64, n_tasks, splits), dim3(64, 4), 0, stream, pv, tasks_off,
                        weights, grads, T, N, t0);
     return hipGetLastError();
@@ -332,9 +332,27 @@ hipError_t launch_onehot_gather(float* C, const float* W, const int* idx, int n_
     return hipGetLastError();
 }
 
+namespace {
+// The same sum with one writer per element: thread j walks the rows in order.
+__global__ __launch_bounds__(256) void onehot_scatter_ordered_kernel(float* __restrict__ G, const float* __restrict__ ds, const int* __restrict__ idx,
+                                                                     int n_dst, int n_src, long long shift_rows, long long total_rows) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n_dst) return;
+    for (long long f = shift_rows; f < total_rows; ++f) {
+        const int c = idx[f - shift_rows];
+        if (c >= 0 && c < n_src) G[(size_t)j * n_src + c] += ds[f * n_dst + j];
+    }
+}
+}  // namespace
+
 hipError_t launch_onehot_scatter(float* G, const float* ds, const int* idx, int n_dst, int n_src, int64_t shift_rows, int64_t total_rows,
-                                 hipStream_t stream) {
+                                 bool ordered, hipStream_t stream) {
     if (total_rows - shift_rows <= 0) return hipSuccess;
+    if (ordered) {
+        hipLaunchKernelGGL(onehot_scatter_ordered_kernel, dim3((n_dst + 255) / 256), dim3(256), 0, stream, G, ds, idx, n_dst, n_src,
+                           (long long)shift_rows, (long long)total_rows);
+        return hipGetLastError();
+    }
     const int grid = (int)std::min<int64_t>(total_rows - shift_rows, 8192);
     hipLaunchKernelGGL(onehot_scatter_kernel, dim3(grid), dim3(256), 0, stream, G, ds, idx, n_dst, n_src, (long long)shift_rows, (long long)total_rows);
     return hipGetLastError();

@@ -59,7 +59,7 @@ hipError_t launch_squared_error_delta(const float* y, const float* d, float* ds,
 // Column-sum tasks (diagonal-weight and bias gradients), atomically added into grads.
 // The sums run over frames [t0, T); factors may reach back to frames before t0.
 hipError_t launch_colsum(const PlanView& pv, int tasks_off, int n_tasks, int max_dim, const float* weights, float* grads,
-                         int T, int N, int t0, hipStream_t stream);
+                         int T, int N, int t0, bool one_writer, hipStream_t stream);
 // Zeroes the first `rows` rows of every buffer whose flag is 1 (the history frames in front of a fresh window).
 hipError_t launch_zero_history(float* const* buf_ptr, const int32_t* buf_dim, const int32_t* buf_flags, int n_bufs, int64_t rows,
                                hipStream_t stream);
@@ -76,8 +76,10 @@ hipError_t launch_xcc_probe(unsigned* out, int n_blocks, hipStream_t stream);
 // [row0, row0 + rows), and the matching weight gradient G[j][idx[f - shift_rows]] += ds[f][j].
 hipError_t launch_onehot_gather(float* C, const float* W, const int* idx, int n_dst, int n_src, int64_t row0, int64_t rows,
                                 int64_t shift_rows, int64_t total_rows, bool accumulate, hipStream_t stream);
+// ordered: the rows are added one after another in increasing order (one writer per element: the
+// sums are the same bits from run to run), else with float atomics from many workgroups.
 hipError_t launch_onehot_scatter(float* G, const float* ds, const int* idx, int n_dst, int n_src, int64_t shift_rows, int64_t total_rows,
-                                 hipStream_t stream);
+                                 bool ordered, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------
 // Persistent recurrent-step kernel (all T steps of one recurrent node and direction)

@@ -444,3 +444,39 @@ def test_streaming_step_kernel_on_small_shapes(monkeypatch, case):
     win2.bptt(); win2.compute_grads(); win2.check()
     for k in spec.output_nodes():
         assert nerr(win2.node_output(k), ref["y"][k]) < OUT_TOL
+
+
+def test_deterministic_gradient_sums():
+    """rnn_set_deterministic: the gradients of two runs agree to the last bit (one writer per element,
+    no atomic splits of the sums over frames) and still match the oracle; with class-index inputs
+    the scatter-add runs in frame order."""
+    from paper_1503_02852_amd.runner import window_for
+    w = wl.make_workload("det", wl.lstm_net(30, [96, 64], 30), T=300, N=3, seed=95, scale=0.3, bias_scale=0.2)
+    runs = []
+    for _ in range(2):
+        win = window_for(w)
+        win.g.set_deterministic(True)
+        win.forward(); win.bptt(); win.compute_grads(); win.check()
+        runs.append(win.grads.cpu().numpy().copy())
+    assert np.array_equal(runs[0], runs[1])
+    ref = go.forward_bptt(w.spec.nodes, w.spec.edges, w.weights, w.biases, w.inputs, w.targets, w.T, w.N)
+    gw, gb = win.grads_unpacked()
+    for m, g in enumerate(ref["grad_w"]):
+        if g is not None:
+            assert nerr(gw[m], g) < GRAD_TOL
+    # one-hot input given as indices: ordered scatter-add
+    c = wl.make_config("charlm_n1", T=200)
+    idx = {k: x.argmax(axis=2) for k, x in c.inputs.items()}
+    runs = []
+    for _ in range(2):
+        win = window_for(c)
+        win.set_onehot_inputs(idx)
+        win.g.set_deterministic(True)
+        win.forward(); win.bptt(); win.compute_grads(); win.check()
+        runs.append(win.grads.cpu().numpy().copy())
+    assert np.array_equal(runs[0], runs[1])
+    ref = go.forward_bptt(c.spec.nodes, c.spec.edges, c.weights, c.biases, c.inputs, c.targets, c.T, c.N)
+    gw, gb = win.grads_unpacked()
+    for m, g in enumerate(ref["grad_w"]):
+        if g is not None:
+            assert nerr(gw[m], g) < GRAD_TOL
