@@ -10,7 +10,7 @@ under "also" short runs of the many-stream workloads (the N = 32 half of the met
 batched-GEMM figures against the fp32 matrix peak).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload speech_n1] [--no-cpu-baseline]
-                    [--no-framewise] [--no-also] [--index-input]
+                    [--no-framewise] [--no-also] [--no-paper-schedule] [--index-input]
 
 Workloads: speech_n1 (default: 2 x 256 peephole LSTM, T = 1024, N = 1), charlm_n1, charlm_n32,
 generalized_n64, tiny; the paper's Section 4 shapes lm_elman_n1, lm_lstm_n1 (38,000-512-20,000,
@@ -214,6 +214,8 @@ def main():
     ap.add_argument("--no-framewise", action="store_true",
                     help="skip the frame-by-frame schedule (the paper's baseline: no batching over frames)")
     ap.add_argument("--no-also", action="store_true", help="skip the short runs of the many-stream workloads")
+    ap.add_argument("--no-paper-schedule", action="store_true",
+                    help="skip the extra run on Section 3.1's schedule verbatim (its step launches carry the same kernel name: profiles)")
     ap.add_argument("--index-input", action="store_true",
                     help="give one-hot input layers as class indices (column gather / scatter-add instead of GEMMs "
                          "over one-hot matrices); for the word-input workloads lm_*")
@@ -241,7 +243,7 @@ def main():
                paper_rule_gflops=paper_rule_flops_per_frame(w.spec) * frames / (m["ms_per_step"] * 1e-3) / 1e9,
                breakdown=m["breakdown"], batched_gemms=m["gemms"], roofline=m["roofline"])
     del m
-    if out["config"]["schedule"] == "chain":
+    if out["config"]["schedule"] == "chain" and not args.no_paper_schedule:
         # the same workload on the paper's schedule verbatim (one step launch per recurrent node)
         os.environ["RNNG_CHAIN"] = "0"
         try:

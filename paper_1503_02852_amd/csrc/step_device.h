@@ -864,60 +864,17 @@ __device__ __forceinline__ void group_poll_issue(PollRegs<MV>& pr, const WaveReg
     step_compiler_barrier();
 }
 
-// Completes the polling of frame t, whose first attempt is already under way: the step's work
-// that does not need the polled vectors (mid) runs under it, then the loads are checked and
-// repeated until none holds a sentinel, and the vectors go to LDS.
-template <class MV, int NB, class Mid>
-__device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, Mid&& mid) {
+// Hands polled values to LDS: out-of-window frames and lanes beyond the vector arrive as zeros; a
+// bundle's interleaved elements [unit][B] go to the blocks of the sources that read its members.
+template <class MV, int NB>
+__device__ __forceinline__ void group_poll_deliver(const PollRegs<MV>& pr, float* xs, int tid) {
     typedef GroupX<MV, NB> GX;
-    auto& v64 = pr.v64;
-    auto& v32 = pr.v32;
-    // The range of the thread index lets the bounds tests of whole regions fold.  That pays in
-    // kernels that poll bundles (two stores per pair: 1.30 -> 1.24 ms in charlm_n1's backward
-    // loop); the single stores of plain regions are faster behind their tests (each store then
-    // waits for its own load only: 0.83 against 0.89 ms in the forward loop), so kernels without
-    // bundles are not told.
+    const auto& v64 = pr.v64;
+    const auto& v32 = pr.v32;
     bool bundles = false;
 #pragma unroll
     for (int r = 0; r < MV::NREG; ++r) bundles = bundles || MV::RB(r) > 1;
     if (bundles) __builtin_assume(tid >= 0 && tid < STEP_THREADS);
-    auto all_ok = [&]() {
-        bool ok = true;
-#pragma unroll
-        for (int s = 0; s < MV::NREG; ++s) {
-            if ((MV::RK(s) & 1) == 0) {
-#pragma unroll
-                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
-                    if (j < GX::pairs_per_thread(s)) ok = ok && v64[s][j].x != STEP_SENTINEL && v64[s][j].y != STEP_SENTINEL;
-            } else {
-#pragma unroll
-                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
-                    if (j < GX::words_per_thread(s)) ok = ok && v32[s][j] != STEP_SENTINEL;
-            }
-        }
-        return ok;
-    };
-    mid();
-    int spins = 0;
-    for (;;) {
-        const bool ok = all_ok();
-        // one decision per wavefront (a scalar branch; per-lane loop exits cost ~25 scalar
-        // instructions of mask handling per step, and a wavefront issues one instruction every
-        // four clocks): a wavefront repeats all its loads while any lane holds a sentinel
-        if (__builtin_amdgcn_ballot_w64(!ok) == 0 || dead) break;
-        if (++spins > a.spin_limit) { dead = true; if ((tid & 63) == 0) atomicExch(a.ctrl, 1u); break; }
-        __builtin_amdgcn_s_sleep(WAVE_RETRY_SLEEP);
-        group_poll_issue<MV, NB>(pr, wv, a, t, tid);
-    }
-#if defined(RNNG_STEP_TRACE)
-    const int trace_step = a.backward ? a.t_end - 1 - t : t - a.t_begin;
-    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= RNNG_STEP_TRACE_AT && trace_step < RNNG_STEP_TRACE_AT + 8) {
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (trace_step - RNNG_STEP_TRACE_AT)] = spins;
-        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (trace_step - RNNG_STEP_TRACE_AT)] = clock64();
-    }
-#endif
-    // out-of-window frames and lanes beyond the vector arrive as zeros; a bundle's interleaved
-    // elements [unit][B] go to the blocks of the sources that read its members
 #pragma unroll
     for (int r = 0; r < MV::NREG; ++r) {
             const int RK = MV::RK(r), B = MV::RB(r), K = RK / B, total = MV::N * RK;      // (MV::N: the stream count the kernel is built for)
@@ -971,6 +928,59 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
             }
         }
     }
+}
+
+// Completes the polling of frame t, whose first attempt is already under way: the step's work
+// that does not need the polled vectors (mid) runs under it, then the loads are checked and
+// repeated until none holds a sentinel, and the vectors go to LDS.
+template <class MV, int NB, class Mid>
+__device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, Mid&& mid) {
+    typedef GroupX<MV, NB> GX;
+    // The range of the thread index lets the bounds tests of whole regions fold.  That pays in
+    // kernels that poll bundles (two stores per pair: 1.30 -> 1.24 ms in charlm_n1's backward
+    // loop); the single stores of plain regions are faster behind their tests (each store then
+    // waits for its own load only: 0.83 against 0.89 ms in the forward loop), so kernels without
+    // bundles are not told.
+    bool bundles = false;
+#pragma unroll
+    for (int r = 0; r < MV::NREG; ++r) bundles = bundles || MV::RB(r) > 1;
+    if (bundles) __builtin_assume(tid >= 0 && tid < STEP_THREADS);
+    auto all_ok = [&](const PollRegs<MV>& q) {
+        bool ok = true;
+#pragma unroll
+        for (int s = 0; s < MV::NREG; ++s) {
+            if ((MV::RK(s) & 1) == 0) {
+#pragma unroll
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                    if (j < GX::pairs_per_thread(s)) ok = ok && q.v64[s][j].x != STEP_SENTINEL && q.v64[s][j].y != STEP_SENTINEL;
+            } else {
+#pragma unroll
+                for (int j = 0; j < GROUP_MAX_LOADS; ++j)
+                    if (j < GX::words_per_thread(s)) ok = ok && q.v32[s][j] != STEP_SENTINEL;
+            }
+        }
+        return ok;
+    };
+    mid();
+    int spins = 0;
+    for (;;) {
+        const bool ok = all_ok(pr);
+        // one decision per wavefront (a scalar branch; per-lane loop exits cost ~25 scalar
+        // instructions of mask handling per step, and a wavefront issues one instruction every
+        // four clocks): a wavefront repeats all its loads while any lane holds a sentinel
+        if (__builtin_amdgcn_ballot_w64(!ok) == 0 || dead) break;
+        if (++spins > a.spin_limit) { dead = true; if ((tid & 63) == 0) atomicExch(a.ctrl, 1u); break; }
+        __builtin_amdgcn_s_sleep(WAVE_RETRY_SLEEP);
+        group_poll_issue<MV, NB>(pr, wv, a, t, tid);
+    }
+#if defined(RNNG_STEP_TRACE)
+    const int trace_step = a.backward ? a.t_end - 1 - t : t - a.t_begin;
+    if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && trace_step >= RNNG_STEP_TRACE_AT && trace_step < RNNG_STEP_TRACE_AT + 8) {
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[64 + (trace_step - RNNG_STEP_TRACE_AT)] = spins;
+        reinterpret_cast<unsigned long long*>(a.ctrl + 16)[72 + (trace_step - RNNG_STEP_TRACE_AT)] = clock64();
+    }
+#endif
+    group_poll_deliver<MV, NB>(pr, xs, tid);
 }
 
 // Sums every p[v] over the 64 lanes.  Pairs of values are folded with the lane-swap
