@@ -166,8 +166,8 @@ int rnn_set_onehot_input(rnn_graph* g, int32_t input, const int32_t* d_indices);
  * the backward pass the connection outputs z_n(t) of multiplicative layers and the weight-gradient
  * terms eps_m(t) y_k(t - d_m)^T of the window's first frames use them, as the last two equations
  * of Section 2.2 say (only the back-propagation of delta and epsilon stops at the window start).
- * One-hot inputs given as class indices keep no history: their delayed connections see zero
- * vectors before the window start. */
+ * For a one-hot input given as class indices the library likewise keeps the indices of the history
+ * frames. */
 int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream);
 
 /* DEVICE view of node's activations y [T][N][dim] inside the workspace of the last rnn_forward

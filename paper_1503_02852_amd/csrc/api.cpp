@@ -37,6 +37,7 @@ struct Layout {
     int64_t sync_off = 0;                 // 1 KiB of zero-initialised control words; the loss (double) sits at its start
     std::vector<int64_t> buf_off;         // per buffer id, bytes; -1 = not in the workspace
     int64_t partial_off = -1;             // partial sums of the two-dimensional matrix-core kernels (one launch at a time)
+    std::vector<int64_t> idx_off;         // per exec node id: int32 [(hist + T)][N] copy of a one-hot input's class indices, or -1
     int64_t wt_off = -1;                  // transposed copies of the matrices the streaming kernels read transposed (parameter layout)
     int64_t flags_off = 0;                // per buffer id: 1 = frame tensor of the workspace (has history frames)
     int64_t total = 0;
@@ -74,6 +75,10 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool tra
     }
     if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)(T + P.hist) * partial_floats * 4, 256); }
     if (transposed_copy) { L.wt_off = cur; cur = align_up(cur + P.n_params * 4, 256); }
+    // an input whose connections are delayed may be given as class indices: room for its indices with history frames
+    L.idx_off.assign(P.xnodes.size(), -1);
+    for (size_t k = 0; k < P.xnodes.size(); ++k)
+        if (P.xnodes[k].kind == NODE_INPUT && P.input_delayed[k]) { L.idx_off[k] = cur; cur = align_up(cur + F * 4, 256); }
     L.total = cur;
     return L;
 }
@@ -158,6 +163,10 @@ struct rnn_graph {
     // the caller's frame 0 of a workspace tensor
     float* frame0(int id) const { return buf(id) + (caller_input(id) ? 0 : (int64_t)hist() * N * plan.buf_dim[id]); }
     bool is_onehot(int buf) const { return buf >= 0 && buf < (int)onehot.size() && onehot[buf] != nullptr; }
+    // class indices of a one-hot input with history frames in front (internal frame 0), or nullptr if the node keeps none
+    int32_t* onehot_history(int buf) const {
+        return buf >= 0 && buf < (int)layout.idx_off.size() && layout.idx_off[buf] >= 0 ? reinterpret_cast<int32_t*>(ws + layout.idx_off[buf]) : nullptr;
+    }
     double* loss_ptr() const { return reinterpret_cast<double*>(ws + layout.sync_off); }
     unsigned* ctrl_ptr() const { return reinterpret_cast<unsigned*>(ws + layout.sync_off + 16); }
     int force_step_G = 0;
@@ -414,9 +423,13 @@ hipError_t run_gemms(rnn_graph* g, const std::vector<GemmProblemPlan>& probs, bo
             for (const GemmPairPlan& pr : pp.pairs) if (!g->is_onehot(pr.a_buf)) first = false;      // the GEMMs have written C
             for (const GemmPairPlan& pr : pp.pairs) {
                 if (!g->is_onehot(pr.a_buf)) continue;
-                // the class indices are the caller's [T][N]: no history, frames before the window read as zero vectors
-                hipError_t e = launch_onehot_gather(g->buf(pp.c_buf), g->weights + pr.b_w_off, g->onehot[pr.a_buf], pp.n, pr.k_len, r0, rows,
-                                                    HN + (int64_t)pr.delay * g->N, F - HN, !first, s);
+                // the caller's indices [T][N] (row 0 = internal row HN), or, for an input with delayed
+                // connections, the library's copy with history frames in front
+                const int32_t* hist_idx = g->onehot_history(pr.a_buf);
+                hipError_t e = hist_idx ? launch_onehot_gather(g->buf(pp.c_buf), g->weights + pr.b_w_off, hist_idx, pp.n, pr.k_len, r0, rows,
+                                                               (int64_t)pr.delay * g->N, F, !first, s)
+                                        : launch_onehot_gather(g->buf(pp.c_buf), g->weights + pr.b_w_off, g->onehot[pr.a_buf], pp.n, pr.k_len, r0, rows,
+                                                               HN + (int64_t)pr.delay * g->N, F - HN, !first, s);
                 if (e != hipSuccess) return e;
                 first = false; ++n_launch;
             }
@@ -884,6 +897,19 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
             if (e != hipSuccess) return fail_hip(e, "history reset");
         }
     }
+    // one-hot inputs with delayed connections: their class indices likewise (-1, the zero vector, in a fresh window's history)
+    for (size_t i = 0; i < P.input_nodes.size(); ++i) {
+        const int k = P.input_nodes[i];
+        int32_t* hist_idx = g->is_onehot(k) ? g->onehot_history(k) : nullptr;
+        if (!hist_idx) continue;
+        if (t_begin == 0 && H > 0) {
+            e = launch_fill_sentinel(reinterpret_cast<float*>(hist_idx), (int64_t)H * N, s);      // all bits set = -1
+            if (e != hipSuccess) return fail_hip(e, "index history reset");
+        }
+        e = hipMemcpyAsync(hist_idx + (int64_t)(H + t_begin) * N, g->onehot[k] + (int64_t)t_begin * N, (size_t)(t_end - t_begin) * N * sizeof(int32_t),
+                           hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail_hip(e, "index copy");
+    }
     // inputs that are not read in place: the new frames go behind the history frames of their copy
     for (size_t i = 0; i < P.input_nodes.size(); ++i) {
         const int k = P.input_nodes[i];
@@ -1007,6 +1033,16 @@ int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream) {
         hipError_t e = shift(b);
         if (e != hipSuccess) return fail_hip(e, "window shift");
     }
+    for (size_t k = 0; k < P.xnodes.size(); ++k) {
+        int32_t* hist_idx = g->is_onehot((int)k) ? g->onehot_history((int)k) : nullptr;
+        if (!hist_idx) continue;
+        const int64_t fr = g->N;
+        for (int t = 0; t + frames < Ti; t += frames) {
+            const int n = std::min(frames, Ti - frames - t);
+            hipError_t e = hipMemcpyAsync(hist_idx + t * fr, hist_idx + (t + frames) * fr, (size_t)n * fr * sizeof(int32_t), hipMemcpyDeviceToDevice, s);
+            if (e != hipSuccess) return fail_hip(e, "window shift");
+        }
+    }
     // interleaved exchange tensors of forward activations move along with their members
     for (const BundlePlan& bp : P.bundles) {
         if (bp.members[0] >= (int)P.xnodes.size() || g->layout.buf_off[bp.ebuf] < 0) continue;
@@ -1128,10 +1164,16 @@ int rnn_grads(rnn_graph* g, float* d_grads, double* loss, void* hip_stream) {
         return r;
     };
     for (const GradGemmPlan& gg : P.grad_gemms) {
-        if (g->is_onehot(gg.src_buf)) {      // scatter-add instead of a GEMM over a one-hot matrix (indices have no history: frames before the window are zero vectors)
-            if (F - (int64_t)gg.delay * N <= 0) continue;
-            e = launch_onehot_scatter(d_grads + gg.w_off, g->frame0(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F,
-                                      g->deterministic, s);
+        if (g->is_onehot(gg.src_buf)) {      // scatter-add instead of a GEMM over a one-hot matrix
+            if (const int32_t* hist_idx = g->onehot_history(gg.src_buf)) {
+                // every frame of the window against the class of frame t - d, which may lie in the history
+                e = launch_onehot_scatter(d_grads + gg.w_off, g->frame0(gg.dst_buf), hist_idx + (int64_t)(H - gg.delay) * N, gg.n_dst, gg.n_src, 0, F,
+                                          g->deterministic, s);
+            } else {
+                if (F - (int64_t)gg.delay * N <= 0) continue;
+                e = launch_onehot_scatter(d_grads + gg.w_off, g->frame0(gg.dst_buf), g->onehot[gg.src_buf], gg.n_dst, gg.n_src, (int64_t)gg.delay * N, F,
+                                          g->deterministic, s);
+            }
             if (e != hipSuccess) return fail_hip(e, "one-hot weight gradient");
             ++n_launch;
             continue;

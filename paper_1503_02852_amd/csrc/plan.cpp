@@ -295,8 +295,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     P.buf_alloc.assign(P.n_bufs, 0);
     P.hist = 0;
     P.input_staged.assign(K, 0);
+    P.input_delayed.assign(K, 0);
     for (int m = 0; m < M; ++m) {
         P.hist = std::max(P.hist, xe[m].delay);
+        if (xn[xe[m].src].kind == NODE_INPUT && xe[m].delay > 0) P.input_delayed[xe[m].src] = 1;
         if (xn[xe[m].src].kind == NODE_INPUT && (xe[m].delay > 0 || xe[m].wkind != W_FULL)) P.input_staged[xe[m].src] = 1;
     }
     for (int k = 0; k < K; ++k) {

@@ -107,6 +107,7 @@ struct Plan {
     // workspace tensor of its own (with history) instead; the others are read by GEMMs only, which
     // take the caller's rows directly.
     std::vector<char> input_staged;               // per exec node id
+    std::vector<char> input_delayed;              // per exec node id: an input node with a delayed out-connection
 
     int ybuf(int k) const { return k; }
     int dbuf(int k) const { return (int)xnodes.size() + k; }

@@ -194,3 +194,15 @@ def test_wide_layers_get_a_streaming_step_kernel(H, N):
     assert n == 2
     # room for the transposed copy of the parameter buffer
     assert g.workspace_bytes(8, N) > 4 * g.param_count()
+
+
+def test_headers_are_plain_c(tmp_path):
+    """The boundary is a C ABI: both headers must compile as C (no C++ in the signatures)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "t.c"
+    src.write_text('#include "rnngraph.h"\n#include "rnngraph_aux.h"\nint main(void) { return rnn_last_error() == 0; }\n')
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"), str(src)], check=True)

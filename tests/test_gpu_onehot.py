@@ -122,3 +122,43 @@ def test_dense_input_can_be_restored_and_non_full_connections_are_refused():
     win2 = window_for(w2)
     with pytest.raises(RnnError):
         win2.g.set_onehot_input(0, torch.zeros(4, dtype=torch.int32, device="cuda:0").data_ptr())
+
+
+def test_index_input_with_delayed_connections_in_a_carried_window():
+    """A one-hot layer with delayed connections (delays 1 and 2), given as class indices, in a
+    window that is moved ahead twice: the library keeps the indices of the history frames, so the
+    forward pass and the truncated gradient see the real word of frame t - d before the window start."""
+    import torch
+    from paper_1503_02852_amd.runner import window_for
+    from tests.test_gpu_window import mask_older_frames
+    T, hp = 12, 6
+    L = T + 2 * hp
+    long, x, idx = with_word_input("two_inputs_n4", T=L, seed=11, empty_fraction=0.1)
+    spec, N = long.spec, long.N
+    y_long, z_long = go.forward(spec.nodes, spec.edges, long.weights, long.biases, long.inputs, L, N)
+    first = wl.Workload(name="carry", spec=spec, T=T, N=N, weights=long.weights, biases=long.biases,
+                        inputs={k: v[:T].copy() for k, v in long.inputs.items()}, targets={k: v[:T].copy() for k, v in long.targets.items()})
+    win = window_for(first)
+    win.set_onehot_inputs({x: idx[:T]})
+    win.forward()
+    for step in (1, 2):
+        a, b = step * hp, step * hp + T
+        win.g.shift_window(hp, win._stream())
+        # the caller shifts its own tensors: the dense input, the class indices, the targets
+        for k, ten in list(win.inputs.items()):
+            ten[:T - hp] = ten[hp:].clone()
+            ten[T - hp:] = torch.from_numpy(long.inputs[k][b - hp:b]).to(win.dev)
+        win.onehot[x][:T - hp] = win.onehot[x][hp:].clone()
+        win.onehot[x][T - hp:] = torch.from_numpy(idx[b - hp:b]).to(win.dev)
+        for k, ten in win.targets.items():
+            ten[:T - hp] = ten[hp:].clone()
+            ten[T - hp:] = torch.from_numpy(long.targets[k][b - hp:b]).to(win.dev)
+        win.forward_range(T - hp, T)
+        masked = mask_older_frames({k: v[a:b].copy() for k, v in long.targets.items()}, T - hp)
+        mask_older_frames(win.targets, T - hp)
+        win.bptt()
+        loss = win.compute_grads(want_loss=True)
+        tl = {k: np.concatenate([v[:a], masked[k], v[b:]]) for k, v in long.targets.items()}
+        ref = go.bptt_window(spec.nodes, spec.edges, long.weights, long.biases, y_long, z_long, tl, a, T, N)
+        check_against(win, first, ref, f"index input, advance {step}")
+        assert abs(loss - ref["loss"]) <= 1e-4 * max(1.0, abs(ref["loss"]))
