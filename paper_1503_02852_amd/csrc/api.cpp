@@ -66,7 +66,8 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool tra
     (void)K;
     for (int b = 0; b < P.n_bufs; ++b) {
         if (!P.buf_alloc[b]) continue;
-        const int64_t rows = P.buf_alloc[b] == 1 ? F : N;
+        if (P.buf_alloc[b] == 3 && !(N >= 16 && N % 16 == 0)) continue;      // tile-blocked twins: whole 16-stream tiles only
+        const int64_t rows = P.buf_alloc[b] == 2 ? N : F;
         L.buf_off[b] = cur; cur = align_up(cur + rows * P.buf_dim[b] * 4, 256);
         // Tensors of the same shape would lie a power of two apart, so the lines that a step polls
         // in several tensors at the same frame would all fall on the same memory channel: skew them.
@@ -177,7 +178,7 @@ struct rnn_graph {
     bool use_jit = true;
     bool use_store_window = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false, mstep = false, stream = false, needs_t = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
+    struct JitChoice { bool wave = false, mstep = false, stream = false, needs_t = false, blocked = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
     bool prefer_streaming = false;        // RNNG_STEP_BUILD=stream
     // the workgroups of a step launch wait for each other, so all of them must be resident at once:
@@ -255,11 +256,12 @@ struct rnn_graph {
                 for (int G : {256, 128, 64, 32, 16}) {
                     if (force_step_G > 0 && G != force_step_G) continue;
                     if (G * J > max_workgroups()) continue;
-                    size_t lds = 0; int rows = 0;
-                    std::string src = jit_mstep_source(plan, cp, backward, N, G, J, &lds, &rows);
+                    size_t lds = 0; int rows = 0, threads = 256; bool blocked = false;
+                    std::string src = jit_mstep_source(plan, cp, backward, N, G, J, &lds, &rows, &threads, &blocked);
                     if (src.empty()) continue;
                     if (best_rows < 0 || (best_rows < 16 && rows > best_rows)) {      // first hit = most workgroups; move to fewer only to fill a tile
                         best.source = src; best.mstep = true; best.lp.ok = true; best.lp.G = G; best.lp.NB = 1; best.lp.lds_bytes = lds; best.J = J;
+                        best.lp.threads = threads; best.blocked = blocked;
                         best.lp.xcd_stride = G * J <= 32 ? 8 : 1;
                         best_rows = rows;
                     }
@@ -308,7 +310,7 @@ struct rnn_graph {
     // Chains of recurrent components run side by side in one launch: all members in the
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
     // workgroups shared among the members).
-    struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false; size_t lds_bytes = 0; };
+    struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false, blocked = false; size_t lds_bytes = 0; int threads = 256; };
     std::map<std::tuple<int, bool, int>, ChainChoice> chain_choices;
     bool use_chains = true;
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
@@ -348,7 +350,7 @@ struct rnn_graph {
                     c.G.push_back(pg); c.J.push_back(pj);
                 }
                 if (c.G.size() == ch.members.size()) {
-                    c.source = jit_mstep_chain_source(plan, ch, backward, N, c.G, c.J, &c.lds_bytes);
+                    c.source = jit_mstep_chain_source(plan, ch, backward, N, c.G, c.J, &c.lds_bytes, &c.threads, &c.blocked);
                     c.mstep = !c.source.empty();
                 }
             }
@@ -467,8 +469,9 @@ hipError_t ensure_xcd_map(unsigned* scratch, hipStream_t s, const XcdMap** out) 
     return hipSuccess;
 }
 
-// The wave-autonomous kernels address a stored tensor through one buffer descriptor with 32-bit
-// offsets and park idle lanes 1 GiB beyond: every tensor of the window must stay below 1 GiB.
+// The wave-autonomous kernels and the matrix-core kernels with weights in LDS address a stored
+// tensor through one buffer descriptor with 32-bit offsets and park idle lanes 1 GiB beyond:
+// every tensor of the window must stay below 1 GiB.
 bool wave_tensor_sizes_ok(const rnn_graph* g) {
     int64_t maxdim = 1;
     for (int b = 0; b < g->plan.n_bufs; ++b) {
@@ -501,8 +504,10 @@ const std::string& windowed(const std::string& source, std::string& cache) {
 // Sentinel prefill of the tensors that workgroups poll during frames [t0, t1).  The wave-autonomous
 // kernel polls the interleaved bundle tensors instead of bundled members; the members are filled as
 // well, so that a fall-back to another kernel build finds them prepared.
-hipError_t fill_shared(rnn_graph* g, const std::vector<int>& bufs, bool with_bundles, int t0, int t1, hipStream_t s) {
+// A kernel with tile-blocked exchange polls the twins and nothing else.
+hipError_t fill_shared(rnn_graph* g, const std::vector<int>& bufs, bool with_bundles, int t0, int t1, hipStream_t s, bool twins = false) {
     std::vector<int> list(bufs);
+    if (twins) for (int& b : list) b += g->plan.twin_base;
     if (with_bundles)
         for (int b : bufs) {
             const int bi = g->plan.bundle_of[b];
@@ -563,20 +568,23 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
     StepLaunchPlan lp;
     const int desc_off = backward ? cp.bwd_desc_off : cp.fwd_desc_off;
     rnn_graph::JitChoice* jc = (g->use_jit && jit_available()) ? const_cast<rnn_graph::JitChoice*>(&g->jit_choice(comp, backward, N)) : nullptr;
-    const bool have_jit = jc && !jc->source.empty() && !g->framewise && (!jc->wave || wave_tensor_sizes_ok(g));
+    const bool have_jit = jc && !jc->source.empty() && !g->framewise &&
+                          (!(jc->wave || (jc->mstep && !jc->two_d)) || wave_tensor_sizes_ok(g));
     const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
     const int spin_limit = g->spin_limit;
     if (have_jit) {
-        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, jc->wave, t0, t1, s);
+        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, jc->wave, t0, t1, s, jc->blocked);
         if (fe != hipSuccess) return step_error(fe, "sentinel fill");
         const bool window = jc->wave && wave_store_window_ok(g);
         std::string why;
-        hipFunction_t fn = jit_step_function(window ? windowed(jc->source, jc->source_window) : jc->source, &why, !g->no_alloc);
+        hipFunction_t fn = jit_step_function(window ? windowed(jc->source, jc->source_window) : jc->source, &why, !g->no_alloc,
+                                             jc->mstep && !jc->two_d ? MSTEP_LDS_LIMIT : STEP_LDS_LIMIT);
         if (!fn) return step_error(hipSuccess, "specialised step kernel unavailable: " + why, g->no_alloc ? RNN_ERR_SEQUENCE : RNN_ERR_DEVICE);
         StepArgs a;
         fill_step_args(a, pv, jc->lp, desc_off, g->weights, g->ctrl_ptr(), T, N, backward, spin_limit, t0, t1);
         if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
         a.J = jc->J;
+        a.twin_base = g->plan.twin_base;
         if (jc->two_d) {
             if (g->layout.partial_off < 0) return step_error(hipErrorInvalidValue, "partial-sum tensor missing from the workspace");
             a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
@@ -650,21 +658,22 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     StepRun none; none.e = hipErrorNotSupported;
     if (!g->use_jit || !jit_available()) return none;
     rnn_graph::ChainChoice& cc = const_cast<rnn_graph::ChainChoice&>(g->chain_choice(chain, backward, g->N));
-    if (cc.source.empty() || (!cc.mstep && !wave_tensor_sizes_ok(g))) return none;
+    if (cc.source.empty() || !wave_tensor_sizes_ok(g)) return none;
     const bool window = !cc.mstep && wave_store_window_ok(g);
     std::string why;
-    hipFunction_t fn = jit_step_function(window ? windowed(cc.source, cc.source_window) : cc.source, &why, !g->no_alloc);
+    hipFunction_t fn = jit_step_function(window ? windowed(cc.source, cc.source_window) : cc.source, &why, !g->no_alloc,
+                                         cc.mstep ? MSTEP_LDS_LIMIT : STEP_LDS_LIMIT);
     if (!fn) return step_error(hipSuccess, "specialised chain step kernel unavailable: " + why, g->no_alloc ? RNN_ERR_SEQUENCE : RNN_ERR_DEVICE);
     const PlanView pv = g->view();
     const int T = g->Ti(), N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     for (const CompPlan& m : ch.members) {
-        hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s);
+        hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s, cc.blocked);
         if (e != hipSuccess) return step_error(e, "sentinel fill");
     }
     StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;
     if (cc.mstep) {
-        lp.G = 0; lp.NB = 1; lp.lds_bytes = cc.lds_bytes; lp.xcd_stride = 1;
+        lp.G = 0; lp.NB = 1; lp.lds_bytes = cc.lds_bytes; lp.xcd_stride = 1; lp.threads = cc.threads;
         for (size_t i = 0; i < cc.G.size(); ++i) lp.G += cc.G[i] * cc.J[i];      // launch size
     }
     StepArgs a;
@@ -672,6 +681,7 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
                    T, N, backward, g->spin_limit, t0, t1);
     if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
     a.n_groups = (int)ch.members.size();
+    a.twin_base = g->plan.twin_base;
     for (int i = 0; i < a.n_groups; ++i) {
         a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
         a.grp_G[i] = cc.G[i];
@@ -873,7 +883,7 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
     }
     std::memcpy(&g->blob[L.dims_off], P.buf_dim.data(), (size_t)P.n_bufs * 4);
     for (int b = 0; b < P.n_bufs; ++b) {
-        const int32_t flag = (P.buf_alloc[b] == 1 && L.buf_off[b] >= 0) ? 1 : 0;
+        const int32_t flag = ((P.buf_alloc[b] == 1 || P.buf_alloc[b] == 3) && L.buf_off[b] >= 0) ? 1 : 0;
         std::memcpy(&g->blob[L.flags_off + 4 * (int64_t)b], &flag, 4);
     }
     if (!P.words.empty()) std::memcpy(&g->blob[L.words_off], P.words.data(), P.words.size() * 4);
@@ -1032,6 +1042,10 @@ int rnn_shift_window(rnn_graph* g, int32_t frames, void* hip_stream) {
         if (g->layout.buf_off[b] < 0) continue;      // an input read in place: the caller shifts it
         hipError_t e = shift(b);
         if (e != hipSuccess) return fail_hip(e, "window shift");
+        if (P.twin_base >= 0 && g->layout.buf_off[P.twin_base + b] >= 0) {      // its tile-blocked twin has the same frame size
+            e = shift(P.twin_base + b);
+            if (e != hipSuccess) return fail_hip(e, "window shift");
+        }
     }
     for (size_t k = 0; k < P.xnodes.size(); ++k) {
         int32_t* hist_idx = g->is_onehot((int)k) ? g->onehot_history((int)k) : nullptr;

@@ -410,7 +410,9 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
 // otherwise *lds_bytes receives the dynamic LDS size.
 namespace {
 // One component of a matrix-core kernel: descriptors PH0 and MM inside namespace ns.
-bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J,
+// blocked: exchange through the tile-blocked twins (only if every exchanged tensor has one and the
+// streams come in whole 16-stream tiles).
+bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J, int NW, bool blocked,
                       const std::string& ns, size_t* lds_bytes, int* rows) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     if (phases.size() != 1 || N_all < 1 || J < 1 || G * J > 256) return false;
@@ -420,8 +422,15 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
     if (!lay.ok) return false;
     MLayout ml;
-    compute_mstep_layout(lay, N, (int)(STEP_LDS_LIMIT / 4), ml);
-    if (!ml.ok || (size_t)ml.total_floats * 4 > STEP_LDS_LIMIT) return false;
+    compute_mstep_layout(lay, N, NW, (int)(MSTEP_LDS_LIMIT / 4), ml);
+    if (!ml.ok || (size_t)ml.total_floats * 4 > MSTEP_LDS_LIMIT) return false;
+    const int CW = 16 * NW;      // columns of a chunk
+    if (blocked) {
+        if (N_all < 16 || N_all % 16 != 0 || N % 16 != 0 || P.twin_base < 0) return false;
+        auto has_twin = [&](int b) { return b >= 0 && b < P.twin_base && P.buf_alloc[P.twin_base + b] == 3; };
+        for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) if (!has_twin(b)) return false;
+        for (int s = 0; s < ml.n_src; ++s) if (!has_twin(lay.src[s].buf) || lay.src[s].k_len != P.buf_dim[lay.src[s].buf]) return false;
+    }
     const StepPhase& ph = lay.ph[0];
     const int MT = (N + 15) / 16, NTU = (ph.n_tasks * ph.cmax + 15) / 16;
     if (MT * NTU > 16) return false;     // accumulator registers
@@ -430,13 +439,18 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     // sources' chunk sequences least
     int kmax = 0;
     for (int s = 0; s < ml.n_src; ++s) kmax = std::max(kmax, lay.src[s].k_len);
-    const int dmax = std::max(2, std::min(12 / MT + 1, (kmax + 63) / 64 + 1));
+    // short chunk sequences are unrolled whole: the chunks in flight may then span several sources
+    int nch = 0;
+    for (int s = 0; s < ml.n_src; ++s) nch += (lay.src[s].k_len + CW - 1) / CW;
+    const bool flat = nch <= 40;
+    const int dmax = flat ? std::max(2, std::min(12 / MT + 1, nch + 1)) : std::max(2, std::min(12 / MT + 1, (kmax + CW - 1) / CW + 1));
     int D = dmax, best_slots = 1 << 30;
-    for (int d = dmax; d >= std::max(2, dmax / 2); --d) {
+    for (int d = dmax; !flat && d >= std::max(2, dmax / 2); --d) {
         int slots = 0;
-        for (int s = 0; s < ml.n_src; ++s) slots += ((lay.src[s].k_len + 63) / 64 + d - 1) / d * d;
+        for (int s = 0; s < ml.n_src; ++s) slots += ((lay.src[s].k_len + CW - 1) / CW + d - 1) / d * d;
         if (slots < best_slots) { best_slots = slots; D = d; }
     }
+    if (const char* env = std::getenv("RNNG_MSTEP_DEPTH")) D = std::max(2, std::min(flat ? std::min(16 / MT + 1, nch + 1) : dmax, std::atoi(env)));      // (measurement)
     o << "namespace " << ns << " {\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
     auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases, int dflt) {
@@ -445,8 +459,11 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
         o << "            default: return " << dflt << ";\n        }\n    }\n";
     };
     o << "struct MM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
-      << ", D = " << D << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ";\n";
-    std::vector<std::pair<int, int>> ks, blk, used, ngr;
+      << ", D = " << D << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ", NW = " << NW << ", NCH = " << nch << ";\n"
+      << "    static constexpr bool FLAT = " << (flat ? "true" : "false") << ", XB = " << (blocked ? "true" : "false") << ";\n";
+    std::vector<std::pair<int, int>> ks, blk, used, ngr, csrc, ck0;
+    for (int s = 0, c = 0; s < ml.n_src && flat; ++s)
+        for (int k = 0; k < lay.src[s].k_len; k += CW, ++c) { csrc.push_back({c, s}); ck0.push_back({c, k}); }
     for (int s = 0; s < ml.n_src; ++s) {
         ks.push_back({s, lay.src[s].k_len});
         for (int t = 0; t < ph.n_tasks; ++t) if (ml.blk[s][t] >= 0) blk.push_back({s * STEP_MAX_TASKS + t, ml.blk[s][t]});
@@ -458,10 +475,10 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
             }
             if (any) used.push_back({s * 16 + nt, 1});
         }
-        ngr.push_back({s, ((lay.src[s].k_len + 63) / 64 + D - 1) / D});
+        ngr.push_back({s, ((lay.src[s].k_len + CW - 1) / CW + D - 1) / D});
     }
     emit_switch("K", "s", ks, 0); emit_switch("blk_", "key", blk, -1); emit_switch("used_", "key", used, 0);
-    emit_switch("ngr", "s", ngr, 0);
+    emit_switch("ngr", "s", ngr, 0); emit_switch("csrc", "c", csrc, 0); emit_switch("ck0", "c", ck0, 0);
     o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n";
     o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
     o << "}  // namespace " << ns << "\n";
@@ -471,11 +488,39 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
 }
 }  // namespace
 
-std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J, size_t* lds_bytes, int* rows) {
+// Wavefronts per workgroup of the matrix-core variant: eight where that fits (twice the loads in
+// flight per compute unit), else four.  RNNG_MSTEP_WAVES = 4 / 8 allows only that count.
+static std::vector<int> mstep_wave_counts() {
+    if (const char* env = std::getenv("RNNG_MSTEP_WAVES")) { const int v = std::atoi(env); if (v == 4 || v == 8) return {v}; }
+    return {8, 4};
+}
+static const char* mstep_kernel_attributes(int NW) {
+    return NW == 8 ? "extern \"C\" __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))\n"
+                   : "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n";
+}
+
+// RNNG_MSTEP_BLOCKED = 0: no exchange through tile-blocked twins (the row-major path, as for ragged stream counts).
+static std::vector<int> mstep_blocked_choices() {
+    if (const char* env = std::getenv("RNNG_MSTEP_BLOCKED")) if (std::atoi(env) == 0) return {0};
+    return {1, 0};
+}
+
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N_all, int G, int J, size_t* lds_bytes, int* rows, int* threads,
+                             bool* blocked) {
     std::ostringstream o;
-    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
-    if (!emit_mstep_group(o, P, cp, backward, N_all, G, J, "grp0", lds_bytes, rows)) return "";
-    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+    int NW = 0; bool xb = false;
+    for (int nw : mstep_wave_counts()) {
+        for (int b : mstep_blocked_choices()) {
+            o.str("");
+            o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+            if (emit_mstep_group(o, P, cp, backward, N_all, G, J, nw, b != 0, "grp0", lds_bytes, rows)) { NW = nw; xb = b != 0; break; }
+        }
+        if (NW) break;
+    }
+    if (!NW) return "";
+    if (threads) *threads = 64 * NW;
+    if (blocked) *blocked = xb;
+    o << mstep_kernel_attributes(NW) <<
          "void rnng_step_jit(StepArgs a) {\n"
          "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
          "    __shared__ MShared ms;\n"
@@ -551,21 +596,33 @@ std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, 
 
 // Several components side by side (a chain): group g takes the blocks [grp_first[g], ...).
 std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
-                                   const std::vector<int>& J, size_t* lds_bytes) {
+                                   const std::vector<int>& J, size_t* lds_bytes, int* threads, bool* blocked) {
     std::ostringstream o;
-    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     const int n = (int)ch.members.size();
     if (n < 2 || n > STEP_MAX_GROUPS || (int)G.size() != n || (int)J.size() != n) return "";
     size_t lds_max = 0;
-    int total = 0;
-    for (int g = 0; g < n; ++g) {
-        size_t lds = 0;
-        if (!emit_mstep_group(o, P, ch.members[g], backward, N, G[g], J[g], "grp" + std::to_string(g), &lds, nullptr)) return "";
-        lds_max = std::max(lds_max, lds);
-        total += G[g] * J[g];
+    int total = 0, NW = 0; bool xb = false;
+    for (int nw : mstep_wave_counts()) {      // one launch: the same number of wavefronts and the same exchange for all members
+        for (int b : mstep_blocked_choices()) {
+            o.str("");
+            o << "#include \"step_device.h\"\nusing namespace rnng;\n";
+            lds_max = 0; total = 0;
+            bool all = true;
+            for (int g = 0; g < n && all; ++g) {
+                size_t lds = 0;
+                all = emit_mstep_group(o, P, ch.members[g], backward, N, G[g], J[g], nw, b != 0, "grp" + std::to_string(g), &lds, nullptr);
+                lds_max = std::max(lds_max, lds);
+                total += G[g] * J[g];
+            }
+            if (all) { NW = nw; xb = b != 0; break; }
+        }
+        if (NW) break;
     }
+    if (!NW) return "";
+    if (blocked) *blocked = xb;
     if (total > 256) return "";      // every workgroup must be resident: they wait for each other
-    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+    if (threads) *threads = 64 * NW;
+    o << mstep_kernel_attributes(NW) <<
          "void rnng_step_jit(StepArgs a) {\n"
          "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
          "    __shared__ MShared ms;\n"
@@ -804,7 +861,7 @@ bool jit_available() {
     return g_rtc.ok;
 }
 
-hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load) {
+hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load, unsigned max_dynamic_lds) {
     if (!allow_load) {
         std::lock_guard<std::mutex> lock(g_mutex);
         auto it = g_cache.find(source);
@@ -822,14 +879,14 @@ hipFunction_t jit_step_function(const std::string& source, std::string* err, boo
     e = hipModuleGetFunction(&ce.fn, ce.module, "rnng_step_jit");
     if (e != hipSuccess) { (void)hipGetLastError(); ce.fn = nullptr; if (err) *err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e); return nullptr; }
     // more than 64 KiB of dynamic LDS needs an opt-in; an error here surfaces at launch
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ce.fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)STEP_LDS_LIMIT);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(ce.fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
     (void)hipGetLastError();   // a refusal must not linger as the thread's last error
     return ce.fn;
 }
 
 hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream) {
     void* params[1] = {&a};
-    return hipModuleLaunchKernel(fn, (unsigned)(lp.G * lp.xcd_stride), 1, 1, STEP_THREADS, 1, 1, (unsigned)lp.lds_bytes, stream,
+    return hipModuleLaunchKernel(fn, (unsigned)(lp.G * lp.xcd_stride), 1, 1, (unsigned)lp.threads, 1, 1, (unsigned)lp.lds_bytes, stream,
                                  params, nullptr);
 }
 

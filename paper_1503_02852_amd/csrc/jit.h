@@ -21,7 +21,10 @@ std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, 
 // Matrix-core variant for many streams; *lds_bytes receives the dynamic LDS size.
 // G unit chunks x J stream groups (N / J streams each).
 // *rows receives the accumulator rows per workgroup (tasks x units per chunk).
-std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int J, size_t* lds_bytes, int* rows = nullptr);
+// *threads: threads per workgroup of the launch (512 where eight wavefronts fit, else 256);
+// *blocked: the kernel exchanges through the tile-blocked twins of the shared tensors.
+std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int J, size_t* lds_bytes, int* rows = nullptr,
+                             int* threads = nullptr, bool* blocked = nullptr);
 // Matrix-core variant with the two-dimensional split (row groups of GJ workgroups that share
 // the columns of every source; partial sums travel through a tensor of *partial_floats floats per frame).
 std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int GJ, size_t* lds_bytes,
@@ -29,7 +32,7 @@ std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, 
 // Chain of matrix-core components in one launch: member g on G[g] unit chunks x J[g] stream groups
 // (at most 256 workgroups in all).  Empty if some member is not eligible.
 std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
-                                   const std::vector<int>& J, size_t* lds_bytes);
+                                   const std::vector<int>& J, size_t* lds_bytes, int* threads = nullptr, bool* blocked = nullptr);
 // Streaming variant (N <= 8 streams; weights read from memory every step, for layers too wide to
 // keep on chip): G unit chunks.  *transposed: the kernel reads transposed copies of some matrices.
 std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed);
@@ -43,7 +46,8 @@ bool jit_available();
 // Loaded kernel for the source on the current device, or nullptr with the reason (compiler log,
 // loader error) in *err.  allow_load = false: only a kernel that is already loaded is returned
 // (nothing is compiled or loaded, so no memory is allocated).
-hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load = true);
+// max_dynamic_lds: the most dynamic LDS a launch of the kernel may ask for.
+hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load = true, unsigned max_dynamic_lds = STEP_LDS_LIMIT);
 hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream);
 
 void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, int desc_off, const float* weights,

@@ -86,6 +86,7 @@ hipError_t launch_onehot_scatter(float* G, const float* ds, const int* idx, int 
 // ---------------------------------------------------------------------------------------
 struct StepLaunchPlan {
     bool ok; int G, NB, xcd_stride; size_t lds_bytes;
+    int threads = 256;      // per workgroup (run-time specialised variants only)
 };
 // Chooses the number of workgroups for a component's step descriptor; ok = false if the
 // component does not fit the kernel's limits (then the caller steps with per-frame launches).

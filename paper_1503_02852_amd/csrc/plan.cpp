@@ -533,6 +533,17 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             make_bundles(cp.fwd_shared_bufs);
             make_bundles(cp.bwd_shared_bufs);
         }
+        // ---- tile-blocked twins of the exchanged tensors ----
+        P.twin_base = (int)P.buf_dim.size();
+        for (int b = 0; b < P.twin_base; ++b) { P.buf_dim.push_back(P.buf_dim[b]); P.buf_alloc.push_back(0); }
+        auto make_twins = [&](const CompPlan& cp) {
+            if (!cp.recurrent || cp.fwd_phases.size() != 1 || cp.bwd_phases.size() != 1) return;
+            for (const std::vector<int>* list : {&cp.fwd_shared_bufs, &cp.bwd_shared_bufs})
+                for (int b : *list)
+                    if (b < P.twin_base && P.buf_alloc[b] == 1 && P.buf_dim[b] % 16 == 0) P.buf_alloc[P.twin_base + b] = 3;
+        };
+        for (const CompPlan& cp : P.comps) make_twins(cp);
+        for (const ChainPlan& ch : P.chains) for (const CompPlan& cp : ch.members) make_twins(cp);
         P.n_bufs = (int)P.buf_dim.size();
         P.bundle_of.assign(P.n_bufs, -1);
         for (size_t i = 0; i < P.bundles.size(); ++i)

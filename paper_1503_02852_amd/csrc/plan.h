@@ -87,7 +87,16 @@ struct Plan {
     // (used when y_k / ds_k is read by other workgroups during the step loop)
     int n_bufs = 0;
     std::vector<int> buf_dim;
-    std::vector<char> buf_alloc;            // 0 not in the workspace, 1 [T][N][dim], 2 [N][dim]
+    std::vector<char> buf_alloc;            // 0 not in the workspace, 1 [T][N][dim], 2 [N][dim], 3 a tile-blocked twin (below)
+    // Tile-blocked twins.  A many-stream step kernel polls an exchanged tensor in tiles of 16
+    // streams x 16 units, and a wavefront's load is served at full rate only if its 1 KiB lies at
+    // consecutive addresses (measured: 77 GB/s per workgroup against 35 GB/s for 16 rows of 64
+    // bytes).  Every tensor b that workgroups of a single-phase recurrent component exchange, and
+    // whose width is a multiple of 16, therefore has a twin with the id twin_base + b:
+    // [frame][stream / 16][unit / 16][(unit % 16) / 4][stream % 16][unit % 4], allocated for
+    // windows whose stream count is a multiple of 16.  The producing kernel stores each value
+    // twice (row-major for everyone else, blocked for the pollers).
+    int twin_base = -1;
     std::vector<CompPlan> comps;
     std::vector<ChainPlan> chains;
     std::vector<BundlePlan> bundles;

@@ -137,7 +137,7 @@ void fill_step_args(StepArgs& a, const PlanView& pv, const StepLaunchPlan& lp, i
     a.t_begin = t_begin; a.t_end = t_end; a.J = 1;
     a.buf_ptr = pv.buf_ptr; a.words = pv.words; a.weights = weights; a.ctrl = ctrl; a.desc_off = desc_off;
     a.T = T; a.N = N; a.backward = backward ? 1 : 0; a.G = lp.G; a.xcd_stride = lp.xcd_stride; a.spin_limit = spin_limit;
-    a.n_groups = 0; a.partial = nullptr; a.store_base = nullptr; a.store_bytes = 0; a.weights_t = nullptr; a.weight_bytes = 0;
+    a.n_groups = 0; a.partial = nullptr; a.store_base = nullptr; a.store_bytes = 0; a.weights_t = nullptr; a.weight_bytes = 0; a.twin_base = 0;
     for (int g = 0; g < STEP_MAX_GROUPS; ++g) { a.grp_desc_off[g] = 0; a.grp_G[g] = 0; a.grp_J[g] = 1; a.grp_first[g] = 0; a.xcc_expect[g] = -1; }
 }
 

@@ -334,6 +334,10 @@ struct PhaseRegs {
     // store).  Needs tensors below 1 GiB, which the host checks.
     unsigned svrun[PH::NST > 0 ? PH::NST : 1];
     int sdelta[PH::NST > 0 ? PH::NST : 1];
+    // the same for gathers from tensors (matrix-core variant): frame-0 address of the tensor
+    // (uniform) and the byte offset of the thread's element in frame 0 (idle lane: far outside)
+    const float* gbase[PH::NG > 0 ? PH::NG : 1];
+    unsigned gvoff[PH::NG > 0 ? PH::NG : 1];
     float inv[PH::NI > 0 ? PH::NI : 1];
     float carry[PH::NC > 0 ? PH::NC : 1];
     // loader side of the static-gather ring: this thread's (static gather, item) pairs
@@ -370,11 +374,13 @@ __device__ __forceinline__ void ring_fill(const PhaseRegs<PH>& r, const StepArgs
 
 // MODE 0: LDS variant (static gathers through the workgroup ring); 1: wave-autonomous variant
 // (per-wavefront ring, own matrix-vector set-up); 2: static gathers are loaded directly.
-template <class PH, int NB, int MODE = 0>
-__device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a, const StepShared& sh, float* lds, int w, int tid) {
+// SH: StepShared, or a leaner table set with the members lay and iteminfo (threads beyond
+// STEP_THREADS, which some variants have, own no item).
+template <class PH, int NB, int MODE = 0, class SH = StepShared>
+__device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a, const SH& sh, float* lds, int w, int tid) {
     const StepPhase& ph = sh.lay.ph[PH::P];
     cwords_t pw = (cwords_t)a.words + suni(ph.prog_off);
-    const unsigned item = sh.iteminfo[PH::P][tid];
+    const unsigned item = tid < STEP_THREADS ? sh.iteminfo[PH::P][tid] : 0xFFFF0000u;
     const int il = (int)(item & 0xFFFF);
     r.n = (item >> 16) == 0xFFFF ? -1 : (int)(item >> 16);
     const int G = a.G, N = a.N;
@@ -399,6 +405,10 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
         } else {
             r.gptr[g] = active ? ((cbufs_t)a.buf_ptr)[e[GA_BUF]] + (size_t)r.n * dim + i : nullptr;
             r.goff[g] = e[GA_FRAME_OFF];
+            if (MODE == 2) {
+                r.gbase[g] = suni_ptr(((cbufs_t)a.buf_ptr)[e[GA_BUF]]);
+                r.gvoff[g] = active ? (unsigned)((r.n * dim + i) * 4) : 0xC0000000u;
+            }
         }
     }
     cwords_t iv = pw + PG_HEADER_WORDS + PH::NG * GA_WORDS;
@@ -437,9 +447,10 @@ __device__ __forceinline__ void phase_setup(PhaseRegs<PH>& r, const StepArgs& a,
             }
         }
     }
-    if (MODE != 0) return;   // the other variants have their own matrix-vector and ring set-up
-    if (PH::HAS_TASKS) { matvec_setup<NB>(r.mv, sh, PH::P, tid); sources_setup(r.src, a, sh, PH::P); }
-    if (PH::NS > 0 && r.pf_steps > 0) ring_fill<PH>(r, a, lds, 0, 0, tid);
+    if constexpr (MODE == 0) {   // the other variants have their own matrix-vector and ring set-up
+        if (PH::HAS_TASKS) { matvec_setup<NB>(r.mv, sh, PH::P, tid); sources_setup(r.src, a, sh, PH::P); }
+        if (PH::NS > 0 && r.pf_steps > 0) ring_fill<PH>(r, a, lds, 0, 0, tid);
+    }
 }
 
 // Optional cycle stamps of one workgroup's steps 64..71 (8 stamps per step, written behind the
@@ -1253,14 +1264,16 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 // and feeds word j of it to the j-th of four multiply steps, whose B operand is word j of the
 // 128-bit LDS read W[row][c + 4 q ..] (the order in which a dot product's columns are summed is
 // free).  Nothing of x passes through LDS and the wavefronts do not wait for each other inside a
-// step's contraction: D chunks of 64 columns (16 per wavefront) are in flight in registers, and a
+// step's contraction: D chunks of 16 * NW columns (16 per wavefront; NW = 4 or 8 wavefronts: what a
+// workgroup can poll per microsecond grows with the wavefronts that have loads in flight, measured
+// 43 / 79 / 94 GB/s with 4 / 8 / 16) are in flight in registers, and a
 // chunk that comes back with a sentinel is loaded again by the wavefront that needs it.  One
 // accumulator set serves all sources; the four partial tiles meet in LDS, where the element-wise
 // program runs with one thread per (stream, unit).
 //
 // MM is a generated descriptor:
 //   static constexpr int NJ (streams per workgroup), MT (16-stream tiles), NSRC, NTU (16-row
-//   tiles), D (chunks in flight), CMAX, ACCS (row stride of an accumulator tile);
+//   tiles), D (chunks in flight), CMAX, ACCS (row stride of an accumulator tile), NW (wavefronts);
 //   constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task) (row block of the task
 //   in source s, -1: none), used(s, nt).
 // =============================================================================================
@@ -1284,8 +1297,10 @@ struct MLayout {
 };
 
 // Same on host and device.  lay is the generic step layout (tasks, sources) for G workgroups.
-RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int lds_limit_floats, MLayout& m) {
+// nw: wavefronts per workgroup (4 or 8); a chunk of a source is 16 * nw columns, 16 per wavefront.
+RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int nw, int lds_limit_floats, MLayout& m) {
     m.ok = 0;
+    const int cw = 16 * nw;
     if (!lay.ok || lay.n_phases != 1 || lay.n_sources < 1) return;
     const StepPhase& ph = lay.ph[0];
     if (ph.item_chunk * N > STEP_THREADS) return;
@@ -1303,20 +1318,22 @@ RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int lds_l
                 if (ph.task[t].e[e].src == s && m.blk[s][t] < 0) m.blk[s][t] = (short)nb++;
         }
         m.rows[s] = nb * ph.cmax;
-        m.wstride[s] = (lay.src[s].k_len + 63) / 64 * 64 + 4;      // zero-padded to whole chunks; = 4 (mod 32): conflict-free 128-bit reads
+        m.wstride[s] = (lay.src[s].k_len + cw - 1) / cw * cw + 4;      // zero-padded to whole chunks; = 4 (mod 32): conflict-free 128-bit reads
         wsmax = m.wstride[s] > wsmax ? m.wstride[s] : wsmax;
         m.wbase[s] = cur; cur += m.rows[s] * m.wstride[s];
     }
     m.zrow = cur; cur += wsmax;
     const int ntu = (ph.n_tasks * ph.cmax + 15) / 16;
     m.accstride = ntu * 16 + 4;                         // = 4 (mod 16): conflict-free tile rows
-    m.accbase = cur; cur += 4 * npad * m.accstride;     // one partial tile per wavefront
+    m.accbase = cur; cur += nw * npad * m.accstride;    // one partial tile per wavefront
     if (cur > lds_limit_floats) return;
     m.total_floats = cur;
     m.ok = 1;
 }
 
-struct MShared { StepShared sh; MLayout ml; };
+struct MStore { static constexpr bool SW = false; };      // stores through one descriptor per stored tensor
+// (leaner than StepShared: one phase, so that more of the 160 KiB is left for weight rows)
+struct MShared { StepLayout lay; unsigned iteminfo[1][STEP_THREADS]; MLayout ml; unsigned retried[2]; };
 
 template <class PH, class MM>
 // w: index of this workgroup among the a.G * a.J workgroups of the component.
@@ -1328,17 +1345,19 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     const int T = a.T;
     const int n0 = wj * MM::NJ;                                            // first stream of this workgroup
     const int N = a.N - n0 < MM::NJ ? a.N - n0 : MM::NJ;                   // its streams
-    StepShared& sh = ms.sh;
-    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, MM::NJ, sh.lay); compute_mstep_layout(sh.lay, MM::NJ, (int)(STEP_LDS_LIMIT / 4), ms.ml); }
+    MShared& sh = ms;
+    constexpr int NW = MM::NW, NTHR = 64 * NW, CW = 16 * NW;      // wavefronts, threads, columns of a chunk
+    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, MM::NJ, sh.lay); compute_mstep_layout(sh.lay, MM::NJ, NW, (int)(MSTEP_LDS_LIMIT / 4), ms.ml); }
     __syncthreads();
     const StepPhase& ph = sh.lay.ph[0];
     const MLayout& ml = ms.ml;
-    {
+    if (tid < STEP_THREADS) {      // the element-wise items sit on the first STEP_THREADS threads
         const int ic = ph.item_chunk;
         const int il = tid % ic, n = tid / ic;
         sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N ? n0 + n : 0xFFFF) << 16);      // global stream index
     }
-    for (int i = tid; i < ml.total_floats; i += STEP_THREADS) lds[i] = 0.0f;
+    for (int i = tid; i < ml.total_floats; i += NTHR) lds[i] = 0.0f;
+    if (tid < 2) ms.retried[tid] = 0u;
     __syncthreads();
     // resident weights: W_lds[s][blk(s, task) * cmax + ul][k]; edges of one task that share a
     // source add up in one row
@@ -1351,7 +1370,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 const StepEdge ed = task.e[e];
                 if (ed.src != s) continue;
                 const float* W = a.weights + ed.w_off;
-                for (int i = tid; i < CMAX * K; i += STEP_THREADS) {
+                for (int i = tid; i < CMAX * K; i += NTHR) {
                     const int ul = i / K, k = i - ul * K;
                     const int u = w * task.chunk + ul;
                     float v = 0.0f;
@@ -1368,7 +1387,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 
     constexpr int D = MM::D, NPAD = MM::MT * 16, ACCS = MM::ACCS;
     const int accbase = suni(ml.accbase);
-    const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    const int item_il = tid < STEP_THREADS ? (int)(sh.iteminfo[0][tid] & 0xFFFF) : 0;
     const int item_n = tid / suni(ph.item_chunk);                          // local stream of this thread's item
     // LDS address of the weight row behind each of this lane's tile columns, per source
     int brow[MM::NSRC][MM::NTU];
@@ -1385,6 +1404,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         }
     // this lane's A-operand element inside a chunk: stream 16 mt + (lane & 15), columns wcol ... wcol + 3;
     // its byte offset in chunk 0 of each source (a stream beyond N: outside the descriptor)
+    // With tile-blocked exchange (MM::XB) the source is the tensor's twin, whose 16 x 16 tiles
+    // [(unit % 16) / 4][stream % 16][unit % 4] are 1 KiB of consecutive addresses each: the
+    // wavefront's load of a tile is lane l -> bytes 16 l, and the tiles of a stream tile's
+    // column blocks follow each other.
     const int wcol = wave * 16 + 4 * (lane >> 4);
     int aoff[MM::NSRC][MM::MT];
 #pragma unroll
@@ -1392,41 +1415,67 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 #pragma unroll
         for (int mt = 0; mt < MM::MT; ++mt) {
             const int n = mt * 16 + (lane & 15);
-            aoff[sidx][mt] = n < N ? (n * MM::K(sidx) + wcol) * 4 : 0x7FFFFFF0;
+            if (MM::XB) aoff[sidx][mt] = ((mt * (MM::K(sidx) / 16) + wave) * 256 + lane * 4) * 4;
+            else aoff[sidx][mt] = n < N ? (n * MM::K(sidx) + wcol) * 4 : 0x7FFFFFF0;
         }
+
+    // Stores go through one buffer descriptor per stored tensor with a running per-lane offset
+    // (a lane without an element is parked outside the tensor), gathers read a harmless address
+    // where a lane has nothing to load: the time loop has no load or store behind a per-lane
+    // branch, so the compiler can count what is in flight instead of waiting for all of it.
+    wave_store_setup<PH, MStore>(r, a);
+    wave_carry_init<PH>(r, a);
+    // tile-blocked exchange: the exchanged values are stored a second time, written through, into
+    // the twins (the row-major copies, which nobody polls, are then stored plainly)
+    const float* xbase[PH::NST > 0 ? PH::NST : 1];
+    unsigned xvrun[PH::NST > 0 ? PH::NST : 1];
+    if constexpr (MM::XB) {
+        cwords_t pw = (cwords_t)a.words + suni(ph.prog_off);
+        cwords_t st = pw + PG_HEADER_WORDS + PH::NG * GA_WORDS + PH::NI * IV_WORDS + pw[PG_NOPS] * MO_WORDS;
+#pragma unroll
+        for (int q = 0; q < PH::NST; ++q) {
+            xbase[q] = nullptr; xvrun[q] = WAVE_NO_STORE;
+            if (!PH::stshared(q)) continue;
+            const int dim = suni(st[q * ST_WORDS + ST_DIM]);
+            xbase[q] = suni_ptr(((cbufs_t)a.buf_ptr)[a.twin_base + suni(st[q * ST_WORDS + ST_BUF])]);
+            if (r.sptr[q] != nullptr) {
+                const int i = (int)(r.sptr[q] - r.sbase[q]) - r.n * dim;      // this thread's unit
+                const int off = ((r.n >> 4) * (dim >> 4) + (i >> 4)) * 256 + ((((i & 15) >> 2) << 4) + (r.n & 15)) * 4 + (i & 3);
+                xvrun[q] = (unsigned)((off + step_frame(a, 0) * r.sstride[q]) * 4);
+            }
+        }
+    }
+    const bool wave_items = __builtin_amdgcn_ballot_w64(r.n >= 0) != 0;      // wavefronts without items skip the element-wise part
+    const int item_n_safe = r.n >= 0 ? item_n : 0;
+    // value of gather g (STATIC or FRAMES kind) at `frame`; zero outside the window or for an idle
+    // lane (a buffer load outside the descriptor's range)
+    auto gather_at = [&](auto gg, int frame) -> float {
+        constexpr int g = decltype(gg)::value;
+        const bool in_window = frame >= 0 && frame < T;
+        const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(r.gbase[g]), 0, T * r.gstride[g] * 4, STEP_RSRC_FLAGS);
+        const int off = in_window ? (int)(r.gvoff[g] + (unsigned)(frame * r.gstride[g] * 4)) : (int)WAVE_NO_STORE;
+        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rg, off, 0, PH::gkind(g) == GA_KIND_STATIC ? 0 : STEP_COHERENT_AUX));
+    };
 
     bool dead = false;
     int pdelay = 0;
     float sn[PH::NG > 0 ? PH::NG : 1];      // STATIC inputs of the next step, loaded one step ahead
     const int nsteps = step_count(a);
+    if (wave_items && nsteps > 0)
+        step_static_for<0, PH::NG>([&](auto gg) {
+            constexpr int g = decltype(gg)::value;
+            if (PH::gkind(g) == GA_KIND_STATIC) sn[g] = gather_at(gg, step_frame(a, 0) + r.goff[g]);
+        });
     for (int step = 0; step < nsteps; ++step) {
         const int t = step_frame(a, step);
         float s[MAX_SLOTS];
         RNNG_STAMP(0);
-        // element-wise inputs: registers (carry), early loads (static), coherent loads (dynamic)
-#pragma unroll
-        for (int g = 0; g < PH::NG; ++g) {
-            if (PH::gkind(g) == GA_KIND_CARRY) {
-                if (step > 0) {
-                    s[g] = r.carry[PH::cidx(g)];
-                } else {      // first step of this call: the previous frame's value, if the window has one
-                    const int frame = t + r.goff[g];
-                    s[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
-                }
-            } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
-                s[g] = sn[g];
-            } else if (PH::gkind(g) != GA_KIND_ACC) {
-                const int frame = t + r.goff[g];
-                float v = 0.0f;
-                if (r.gptr[g] != nullptr && frame >= 0 && frame < T) {
-                    if (PH::gkind(g) == GA_KIND_STATIC) v = r.gptr[g][(long long)frame * r.gstride[g]];
-                    else v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
-                }
-                s[g] = v;
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+        // element-wise inputs from the thread's own earlier frames: coherent loads, issued first
+        if (wave_items)
+            step_static_for<0, PH::NG>([&](auto gg) {
+                constexpr int g = decltype(gg)::value;
+                if (PH::gkind(g) == GA_KIND_FRAMES) s[g] = gather_at(gg, t + r.goff[g]);
+            });
         RNNG_STAMP(1);
 
         // one buffer descriptor per source tensor; a frame outside the window gets an empty one
@@ -1437,39 +1486,29 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             const StepSource& sc = sh.lay.src[sidx];
             const int frame = t + suni(sc.frame_off);
             const bool in_window = frame >= 0 && frame < T;
-            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + ((size_t)(in_window ? frame : 0) * a.N + n0) * MM::K(sidx);
+            // (a twin's frame has the same size, and its stream tiles are as large as 16 rows)
+            const float* g = ((cbufs_t)a.buf_ptr)[(MM::XB ? a.twin_base : 0) + suni(sc.buf)] + ((size_t)(in_window ? frame : 0) * a.N + n0) * MM::K(sidx);
             rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * MM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
         }
-        auto prefetch_statics = [&]() {
-            if (step + 1 < nsteps) {
-                const int t2 = a.backward ? t - 1 : t + 1;
-#pragma unroll
-                for (int g = 0; g < PH::NG; ++g)
-                    if (PH::gkind(g) == GA_KIND_STATIC) {
-                        const int frame = t2 + r.goff[g];
-                        float x = 0.0f;
-                        if (r.gptr[g] != nullptr && frame >= 0 && frame < T) x = r.gptr[g][(long long)frame * r.gstride[g]];
-                        sn[g] = x;
-                    }
-            }
-        };
         // ---- chunk pipeline ----
-        // A source's columns are cut into groups of D chunks of 64 columns (the last group padded
-        // with empty chunks that are skipped).  Chunk i of a group lives in register set i, so
-        // every register index is static although the loop over a source's groups is not
-        // unrolled.  D - 1 chunks are in flight: while chunk i is multiplied, the set of chunk
-        // i - 1 takes the loads of chunk i + D - 1 and chunk i + 1 is tested for sentinels.  These
-        // three run in one basic block (loads that have nothing to fetch get an offset outside
-        // the descriptor instead of a branch), so that the compiler can place the loads and the
-        // test between the matrix instructions, where the wavefront would otherwise idle.
+        // The sources' columns form one sequence of chunks of CW columns (a source's last chunk
+        // zero-padded).  D register sets hold D - 1 chunks in flight: while chunk c is multiplied,
+        // the set of chunk c - 1 takes the loads of chunk c + D - 1 and chunk c + 1 is tested for
+        // sentinels.  These three run in one basic block, so that the compiler can place the loads
+        // and the test between the matrix instructions, where the wavefront would otherwise idle.
+        // Short sequences (MM::FLAT) are unrolled whole, so that the chunks in flight may span any
+        // number of sources; long ones run source by source in groups of D chunks (the last group
+        // of a source padded with empty chunks that are skipped; loads that have nothing to fetch
+        // get an offset outside the descriptor instead of a branch), which looks ahead into the
+        // next source's first group only.
         muintx4 v[D][MM::MT];
         // This lane's operands of the chunk with first column k0 of source S (on: else nothing is
-        // fetched).  Columns beyond K read as zeros; they exist only if K is no multiple of 64.
+        // fetched).  Columns beyond K read as zeros; they exist only if K is no multiple of CW.
         auto load_chunk = [&](muintx4 (&dst)[MM::MT], const __amdgpu_buffer_rsrc_t& rsrc, const int (&base)[MM::MT], int K, bool k_ragged, int k0, bool on) {
 #pragma unroll
             for (int mt = 0; mt < MM::MT; ++mt) {
-                int off = base[mt] + k0 * 4;
-                if (k_ragged) off = k0 + wcol < K ? off : 0x7FFFFFF0;
+                int off = base[mt] + (MM::XB ? k0 * 64 : k0 * 4);      // (blocked: k0 / 16 tiles of 1 KiB further)
+                if (k_ragged) off = k0 + (MM::XB ? wave * 16 : wcol) < K ? off : 0x7FFFFFF0;
                 off = on ? off : 0x7FFFFFF0;
                 dst[mt] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
             }
@@ -1485,14 +1524,75 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             }
             return __builtin_amdgcn_ballot_w64(m == STEP_SENTINEL) != 0;
         };
+        bool retried = false;
+        // the retry loads into registers of its own (a reload of the pipelined set would make
+        // every later use of it wait for all loads in flight)
+        auto reload = [&](muintx4 (&dst)[MM::MT], auto ss, int k0) {
+            constexpr int sidx = decltype(ss)::value;
+            retried = true;
+            muintx4 again[MM::MT];
+            int spins = 0;
+            for (;;) {
+                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
+                step_compiler_barrier();
+                load_chunk(again, rs[sidx], aoff[sidx], MM::K(sidx), MM::K(sidx) % CW != 0, k0, true);
+                if (!incomplete(again)) break;
+            }
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt) dst[mt] = again[mt];
+        };
+        mfloatx4 acc[MM::MT][MM::NTU];
+        // chunk in register set `set` (first column k0 of source sidx) times the resident weights
+        auto multiply = [&](auto ss, const muintx4 (&x)[MM::MT], const mfloatx4 (&opb)[MM::NTU]) {
+            constexpr int sidx = decltype(ss)::value;
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MM::NTU; ++nt)
+                    if (MM::used(sidx, nt)) {
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(x[mt].x), opb[nt][0], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(x[mt].y), opb[nt][1], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(x[mt].z), opb[nt][2], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(x[mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
+                    }
+        };
         // hold the first loads back until the producers' stores are usually visible
         for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
-        bool retried = false;
+        if constexpr (MM::FLAT) {
+            constexpr int NCH = MM::NCH;
+            step_static_for<0, D - 1>([&](auto ii) {
+                constexpr int i = decltype(ii)::value;
+                constexpr int sx = MM::csrc(i < NCH ? i : 0);
+                load_chunk(v[i], rs[sx], aoff[sx], MM::K(sx), MM::K(sx) % CW != 0, MM::ck0(i < NCH ? i : 0), i < NCH);
+            });
+#pragma unroll
+            for (int mt = 0; mt < MM::MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MM::NTU; ++nt) acc[mt][nt] = mfloatx4{0.0f, 0.0f, 0.0f, 0.0f};
+            bool bad = incomplete(v[0]);      // of the chunk that comes next
+            step_static_for<0, NCH>([&](auto cc) {
+                constexpr int c = decltype(cc)::value;
+                constexpr int i = c % D, j = (c + D - 1) % D, i1 = (c + 1) % D;
+                constexpr int sidx = MM::csrc(c), k0 = MM::ck0(c);
+                constexpr int ca = c + D - 1 < NCH ? c + D - 1 : 0;      // the chunk D - 1 positions ahead, if any
+                constexpr int sa = MM::csrc(ca);
+                mfloatx4 opb[MM::NTU];
+#pragma unroll
+                for (int nt = 0; nt < MM::NTU; ++nt)
+                    if (MM::used(sidx, nt)) opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * 16]);
+                if (bad && !dead) reload(v[i], StepIntC<sidx>{}, k0);
+                if (c == 0) { RNNG_STAMP(2); }
+                if (c == 1) { RNNG_STAMP(6); RNNG_STAMP(7); }
+                if (c + D - 1 < NCH) load_chunk(v[j], rs[sa], aoff[sa], MM::K(sa), MM::K(sa) % CW != 0, MM::ck0(ca), true);
+                bad = c + 1 < NCH ? incomplete(v[i1]) : false;
+                multiply(StepIntC<sidx>{}, v[i], opb);
+            });
+        } else {
         step_static_for<0, D - 1>([&](auto ii) {
             constexpr int i = decltype(ii)::value;
-            load_chunk(v[i], rs[0], aoff[0], MM::K(0), MM::K(0) % 64 != 0, i * 64, i * 64 < (MM::K(0) + 63) / 64 * 64);
+            load_chunk(v[i], rs[0], aoff[0], MM::K(0), MM::K(0) % CW != 0, i * CW, i * CW < (MM::K(0) + CW - 1) / CW * CW);
         });
-        mfloatx4 acc[MM::MT][MM::NTU];
 #pragma unroll
         for (int mt = 0; mt < MM::MT; ++mt)
 #pragma unroll
@@ -1502,25 +1602,25 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         step_static_for<0, MM::NSRC>([&](auto ss) {
             constexpr int sidx = decltype(ss)::value;
             constexpr int NGR = MM::ngr(sidx);
-            constexpr int KP = (MM::K(sidx) + 63) / 64 * 64;              // weight rows are zero-padded up to here
+            constexpr int KP = (MM::K(sidx) + CW - 1) / CW * CW;              // weight rows are zero-padded up to here
             constexpr int snext = sidx + 1 < MM::NSRC ? sidx + 1 : sidx;
-            constexpr int KPN = (MM::K(snext) + 63) / 64 * 64;
+            constexpr int KPN = (MM::K(snext) + CW - 1) / CW * CW;
 #pragma unroll 1
             for (int g = 0; g < NGR; ++g) {
                 step_static_for<0, D>([&](auto ii) {
                     constexpr int i = decltype(ii)::value;
                     constexpr int j = (i + D - 1) % D;                   // register set of the chunk D - 1 positions ahead
                     constexpr int i1 = (i + 1) % D;                      // register set of the next chunk
-                    const int k0 = (g * D + i) * 64;
+                    const int k0 = (g * D + i) * CW;
                     // the chunk D - 1 positions ahead: in this source, or in the next one's first group
                     const int gj = i == 0 ? g : g + 1;
                     const bool same = gj < NGR;
-                    const int kj = same ? (gj * D + j) * 64 : j * 64;
+                    const int kj = same ? (gj * D + j) * CW : j * CW;
                     const bool on = same ? kj < KP : (sidx + 1 < MM::NSRC && kj < KPN);
                     const __amdgpu_buffer_rsrc_t rn = same ? rs[sidx] : rs[snext];
                     auto ahead = [&]() {
-                        if (same) load_chunk(v[j], rn, aoff[sidx], MM::K(sidx), MM::K(sidx) % 64 != 0, kj, on);
-                        else load_chunk(v[j], rn, aoff[snext], MM::K(snext), MM::K(snext) % 64 != 0, kj, on);
+                        if (same) load_chunk(v[j], rn, aoff[sidx], MM::K(sidx), MM::K(sidx) % CW != 0, kj, on);
+                        else load_chunk(v[j], rn, aoff[snext], MM::K(snext), MM::K(snext) % CW != 0, kj, on);
                     };
                     if (k0 < KP) {
                         // the weights of this chunk (tiles the source does not feed read the zero row)
@@ -1528,36 +1628,12 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 #pragma unroll
                         for (int nt = 0; nt < MM::NTU; ++nt)
                             if (MM::used(sidx, nt)) opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * 16]);
-                        if (bad && !dead) {
-                            // the retry loads into registers of its own (a reload of the pipelined
-                            // set would make every later use of it wait for all loads in flight)
-                            retried = true;
-                            muintx4 again[MM::MT];
-                            int spins = 0;
-                            for (;;) {
-                                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
-                                __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
-                                step_compiler_barrier();
-                                load_chunk(again, rs[sidx], aoff[sidx], MM::K(sidx), MM::K(sidx) % 64 != 0, k0, true);
-                                if (!incomplete(again)) break;
-                            }
-#pragma unroll
-                            for (int mt = 0; mt < MM::MT; ++mt) v[i][mt] = again[mt];
-                        }
+                        if (bad && !dead) reload(v[i], ss, k0);
                         if (sidx == 0 && i == 0 && g == 0) { RNNG_STAMP(2); }
                         if (sidx == 0 && i == 1 && g == 0) { RNNG_STAMP(6); RNNG_STAMP(7); }
                         ahead();
                         bad = incomplete(v[i1]);
-#pragma unroll
-                        for (int mt = 0; mt < MM::MT; ++mt)
-#pragma unroll
-                            for (int nt = 0; nt < MM::NTU; ++nt)
-                                if (MM::used(sidx, nt)) {
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].x), opb[nt][0], acc[mt][nt], 0, 0, 0);
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].y), opb[nt][1], acc[mt][nt], 0, 0, 0);
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].z), opb[nt][2], acc[mt][nt], 0, 0, 0);
-                                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(v[i][mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
-                                }
+                        multiply(ss, v[i], opb);
                     } else {
                         ahead();
                         bad = incomplete(v[i1]);
@@ -1565,7 +1641,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 });
             }
         });
-        prefetch_statics();
+        }
         // ---- hand the accumulators to the element-wise threads: one partial tile per wavefront ----
         // (the previous step's readers of the tiles are behind the barrier that ends a step)
         {
@@ -1579,31 +1655,56 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                         lds[tb + (mt * 16 + 4 * (lane >> 4) + i) * ACCS + nt * 16 + (lane & 15)] = acc[mt][nt][i];
         }
         RNNG_STAMP(3);
-        if (__syncthreads_or(retried ? 1 : 0)) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
-        else if ((step & 63) == 63 && pdelay > 0) --pdelay;
+        // did any wavefront have to load a chunk again?  (word `step & 1`; the other one is cleared for the next step)
+        if (retried && lane == 0) atomicOr(&ms.retried[step & 1], 1u);
+        step_lds_barrier();
+        if (MSTEP_POLL_INC > 0) {
+            if (ms.retried[step & 1]) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
+            else if ((step & 63) == 63 && pdelay > 0) --pdelay;
+            if (tid == 0) ms.retried[(step + 1) & 1] = 0u;
+        }
         RNNG_STAMP(4);
         // ---- element-wise program: one thread per (stream, unit) ----
-        if (r.n >= 0) {
+        if (wave_items) {
 #pragma unroll
-            for (int g = 0; g < PH::NG; ++g)
+            for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
+            step_static_for<0, PH::NG>([&](auto gg) {
+                constexpr int g = decltype(gg)::value;
+                if (PH::gkind(g) == GA_KIND_CARRY) s[g] = r.carry[PH::cidx(g)];
+                else if (PH::gkind(g) == GA_KIND_STATIC) s[g] = sn[g];
                 if (PH::gkind(g) == GA_KIND_ACC) {
-                    float x = 0.0f;
-                    if (r.gptr[g] != nullptr) {
-                        const int tb = accbase + item_n * ACCS + PH::gaux(g) * CMAX + item_il;
-                        x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
-                    }
-                    s[g] = x;
+                    const int tb = accbase + item_n_safe * ACCS + PH::gaux(g) * CMAX + item_il;
+                    float x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
+                    if constexpr (NW == 8)
+                        x += (lds[tb + 4 * NPAD * ACCS] + lds[tb + 5 * NPAD * ACCS]) + (lds[tb + 6 * NPAD * ACCS] + lds[tb + 7 * NPAD * ACCS]);
+                    s[g] = r.gptr[g] != nullptr ? x : 0.0f;
                 }
+            });
             PH::ops(s);
 #pragma unroll
             for (int q = 0; q < PH::NST; ++q) {
-                if (r.sptr[q] == nullptr) continue;
-                if (PH::stshared(q)) store_shared(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
-                else store_plain(r.sptr[q] + (long long)t * r.sstride[q], s[PH::stslot(q)]);
+                wave_store<PH, MStore>(r, q, s[PH::stslot(q)], PH::stshared(q) && !MM::XB ? 2 : 0, a);
+                if (MM::XB && PH::stshared(q)) {
+                    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xbase[q]), 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
+                    __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(s[PH::stslot(q)]), rx, (int)xvrun[q], 0, STEP_COHERENT_AUX);
+                }
             }
 #pragma unroll
             for (int g = 0; g < PH::NG; ++g)
                 if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
+            // the next step's STATIC inputs, behind this step's stores: they arrive during that
+            // step's contraction (behind the last step: outside the window, nothing is loaded)
+            const int t2 = a.backward ? t - 1 : t + 1;
+            const bool more = step + 1 < nsteps;
+            step_static_for<0, PH::NG>([&](auto gg) {
+                constexpr int g = decltype(gg)::value;
+                if (PH::gkind(g) == GA_KIND_STATIC) sn[g] = gather_at(gg, more ? t2 + r.goff[g] : -1);
+            });
+        }
+        wave_store_advance<PH>(r);
+        if constexpr (MM::XB) {
+#pragma unroll
+            for (int q = 0; q < PH::NST; ++q) xvrun[q] += (unsigned)(r.sdelta[q] * 4);
         }
         RNNG_STAMP(5);
         step_lds_barrier();   // the tiles are written again in the next step

@@ -23,6 +23,7 @@ namespace rnng {
 
 constexpr int STEP_THREADS = 256;
 constexpr unsigned STEP_LDS_LIMIT = 148 * 1024;   // dynamic LDS per workgroup (the static tables take 11.3 KiB of the 160 KiB)
+constexpr unsigned MSTEP_LDS_LIMIT = 152 * 1024;  // the same for the matrix-core variant with weights in LDS (tables of 6.4 KiB)
 constexpr int STEP_MAX_PHASES = 4;
 constexpr int STEP_MAX_TASKS = 8;      // per phase
 constexpr int STEP_MAX_EDGES = 8;      // per task
@@ -93,6 +94,9 @@ struct StepArgs {
     // transposed are stored transposed (same offsets), and the size of both buffers in bytes.
     const float* weights_t;
     unsigned weight_bytes;
+    // Matrix-core build with tile-blocked exchange: buffer twin_base + b is the blocked twin of
+    // the exchanged tensor b (see the kernel).
+    int twin_base;
 };
 
 RNNG_HD inline int step_count(const StepArgs& a) { return a.t_end - a.t_begin; }
