@@ -217,39 +217,14 @@ struct rnn_graph {
             }
             if (force_step_G > 0) break;
         }
-        // 2. matrix-core variant for many streams: weights in LDS, MFMA, the smallest workgroup count that fits
-        // 2a. many streams and wide sources: the two-dimensional split, where a workgroup polls a
-        //     sixteenth of every source (worth its second exchange once the one-dimensional split
-        //     would poll a quarter of a megabyte per workgroup and step, and while a workgroup has
-        //     few rows: then the one-dimensional split wastes most of its 16-row tiles, whereas
-        //     here several workgroups' rows share a tile and the partial sums stay small; measured
-        //     on generalized_n64: backward (4 rows) faster, forward (16 rows) slower)
-        if (c.source.empty() && N > 8 && force_step_G <= 0 && force_step_J <= 0 && max_workgroups() >= 256 &&
-            !(std::getenv("RNNG_MSTEP_2D") && std::atoi(std::getenv("RNNG_MSTEP_2D")) == 0)) {
-            StepLayout lay;
-            compute_step_layout(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, 256, 1, N, lay);
-            int64_t polled = 0;
-            if (lay.ok) for (int sidx = 0; sidx < lay.n_sources; ++sidx) polled += (int64_t)N * lay.src[sidx].k_len * 4;
-            const bool forced = std::getenv("RNNG_MSTEP_2D") != nullptr;      // = 1: wherever the kernel can run (tests)
-            if (polled >= 256 * 1024 || forced) {
-                // row groups of 16 while a workgroup has at most 8 rows; of 4 with more rows, so that
-                // the partial sums a workgroup writes and polls per step stay at N * 64 values
-                const int rows = lay.ph[0].n_tasks * lay.ph[0].cmax;
-                int gj = rows <= 8 ? 16 : 4;
-                if (const char* env = std::getenv("RNNG_MSTEP_2D_GROUP")) gj = std::atoi(env);
-                size_t lds = 0; int64_t pf = 0;
-                std::string src = jit_mstep2_source(plan, cp, backward, N, 256, gj, &lds, &pf);
-                if (src.empty() && gj != 16) src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
-                if (!src.empty()) {
-                    c.source = src; c.lp.ok = true; c.lp.G = 256; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
-                    c.two_d = true; c.mstep = true; c.partial_floats = pf;
-                }
-            }
-        }
+        // 2. matrix-core variants for many streams (weights in LDS or registers, MFMA)
+        // 2a. one-dimensional split: stream groups, as many as possible (every group halves the
+        //     bytes a workgroup polls per step); unit chunks: as many as the compute units allow
+        //     while a workgroup still fills a 16-row tile, else the smallest count whose weight
+        //     rows fit on chip
+        JitChoice one_d;
+        int one_d_rows = -1;
         if (c.source.empty() && N > 8) {
-            // stream groups: as many as possible (every group halves the bytes a workgroup polls per
-            // step); unit chunks: as many as the 256 CUs allow while a workgroup still fills a
-            // 16-row tile, else the smallest count whose weight rows fit LDS
             for (int J : {4, 2, 1}) {
                 if (force_step_J > 0 && J != force_step_J) continue;
                 JitChoice best; int best_rows = -1;
@@ -267,9 +242,37 @@ struct rnn_graph {
                     }
                     if (best_rows >= 16) break;
                 }
-                if (!best.source.empty()) { c = best; break; }
+                if (!best.source.empty()) { one_d = best; one_d_rows = best_rows; break; }
             }
         }
+        // 2b. the two-dimensional split, where a workgroup polls a sixteenth (or a quarter) of every
+        //     source and the row groups' members share 16-row tiles, at the price of a second
+        //     exchange per step: only where the one-dimensional split cannot fill its tiles
+        //     (RNNG_MSTEP_2D = 1: wherever the kernel can run; = 0: never)
+        const char* env2d = std::getenv("RNNG_MSTEP_2D");
+        const bool forced_2d = env2d && std::atoi(env2d) != 0, no_2d = env2d && std::atoi(env2d) == 0;
+        if (c.source.empty() && N > 8 && force_step_G <= 0 && force_step_J <= 0 && max_workgroups() >= 256 && !no_2d &&
+            (forced_2d || one_d_rows < 16)) {
+            StepLayout lay;
+            compute_step_layout(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, 256, 1, N, lay);
+            int64_t polled = 0;
+            if (lay.ok) for (int sidx = 0; sidx < lay.n_sources; ++sidx) polled += (int64_t)N * lay.src[sidx].k_len * 4;
+            if (polled >= 256 * 1024 || forced_2d) {
+                // row groups of 16 while a workgroup has at most 8 rows; of 4 with more rows, so that
+                // the partial sums a workgroup writes and polls per step stay at N * 64 values
+                const int rows = lay.ph[0].n_tasks * lay.ph[0].cmax;
+                int gj = rows <= 8 ? 16 : 4;
+                if (const char* env = std::getenv("RNNG_MSTEP_2D_GROUP")) gj = std::atoi(env);
+                size_t lds = 0; int64_t pf = 0;
+                std::string src = jit_mstep2_source(plan, cp, backward, N, 256, gj, &lds, &pf);
+                if (src.empty() && gj != 16) src = jit_mstep2_source(plan, cp, backward, N, 256, 16, &lds, &pf);
+                if (!src.empty()) {
+                    c.source = src; c.lp.ok = true; c.lp.G = 256; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
+                    c.two_d = true; c.mstep = true; c.partial_floats = pf;
+                }
+            }
+        }
+        if (c.source.empty() && !one_d.source.empty()) c = one_d;
         // 3. LDS-resident variant
         if (c.source.empty() && plan_step_launch(plan.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, N, force_step_G, c.lp))
             c.source = jit_step_source(plan, cp, backward, c.lp.NB);

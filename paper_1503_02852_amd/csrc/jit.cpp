@@ -421,10 +421,44 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     StepLayout lay;
     compute_step_layout(P.words.data(), backward ? cp.bwd_desc_off : cp.fwd_desc_off, G, 1, N, lay);
     if (!lay.ok) return false;
-    MLayout ml;
-    compute_mstep_layout(lay, N, NW, (int)(MSTEP_LDS_LIMIT / 4), ml);
-    if (!ml.ok || (size_t)ml.total_floats * 4 > MSTEP_LDS_LIMIT) return false;
     const int CW = 16 * NW;      // columns of a chunk
+    MLayout ml;
+    compute_mstep_layout(lay, N, NW, 0u, (int)(MSTEP_LDS_LIMIT / 4), ml);
+    // Weight rows that do not fit LDS go to vector registers, whole sources at a time and the
+    // largest first (eight wavefronts only: 256 registers per lane, of which the weights may
+    // take 144; the chunk sequence must be short enough to be unrolled, so that every register
+    // index is static).  A lane keeps 4 words per (chunk, row tile the source feeds).
+    unsigned reg_mask = 0;
+    int reg_words = 0;
+    if (!ml.ok && lay.ok && lay.n_phases == 1 && NW == 8 && !(std::getenv("RNNG_MSTEP_REGS") && std::atoi(std::getenv("RNNG_MSTEP_REGS")) == 0)) {
+        const StepPhase& ph0 = lay.ph[0];
+        const int ntu0 = (ph0.n_tasks * ph0.cmax + 15) / 16;
+        int nch0 = 0;
+        for (int s = 0; s < lay.n_sources; ++s) nch0 += (lay.src[s].k_len + CW - 1) / CW;
+        auto words_of = [&](int s) {      // registers per lane if source s lives there
+            int tiles = 0;
+            for (int nt = 0; nt < ntu0; ++nt) {
+                bool any = false;
+                for (int col = nt * 16; col < nt * 16 + 16 && !any; ++col) {
+                    const int t = col / ph0.cmax;
+                    if (t >= ph0.n_tasks) continue;
+                    for (int e = 0; e < ph0.task[t].n_edges; ++e) if (ph0.task[t].e[e].src == s) any = true;
+                }
+                tiles += any;
+            }
+            return (lay.src[s].k_len + CW - 1) / CW * tiles * 4;
+        };
+        while (nch0 <= 40) {
+            int pick = -1;
+            for (int s = 0; s < lay.n_sources; ++s)
+                if (!((reg_mask >> s) & 1) && (pick < 0 || words_of(s) > words_of(pick))) pick = s;
+            if (pick < 0 || reg_words + words_of(pick) > 144) break;
+            reg_mask |= 1u << pick; reg_words += words_of(pick);
+            compute_mstep_layout(lay, N, NW, reg_mask, (int)(MSTEP_LDS_LIMIT / 4), ml);
+            if (ml.ok) break;
+        }
+    }
+    if (!ml.ok || (size_t)ml.total_floats * 4 > MSTEP_LDS_LIMIT) return false;
     if (blocked) {
         if (N_all < 16 || N_all % 16 != 0 || N % 16 != 0 || P.twin_base < 0) return false;
         auto has_twin = [&](int b) { return b >= 0 && b < P.twin_base && P.buf_alloc[P.twin_base + b] == 3; };
@@ -443,7 +477,10 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     int nch = 0;
     for (int s = 0; s < ml.n_src; ++s) nch += (lay.src[s].k_len + CW - 1) / CW;
     const bool flat = nch <= 40;
-    const int dmax = flat ? std::max(2, std::min(12 / MT + 1, nch + 1)) : std::max(2, std::min(12 / MT + 1, (kmax + CW - 1) / CW + 1));
+    // loads in flight per lane: about four with eight wavefronts (measured on two workloads: 4 / 8 / 12
+    // in flight give 1.81 / 1.88 / 1.91 ms and 3.56 / 3.59 / 3.70 ms), a dozen with four
+    const int inflight = NW == 8 ? 4 : 12;
+    const int dmax = flat ? std::max(2, std::min(inflight / MT + 1, nch + 1)) : std::max(2, std::min(inflight / MT + 1, (kmax + CW - 1) / CW + 1));
     int D = dmax, best_slots = 1 << 30;
     for (int d = dmax; !flat && d >= std::max(2, dmax / 2); --d) {
         int slots = 0;
@@ -479,6 +516,15 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     }
     emit_switch("K", "s", ks, 0); emit_switch("blk_", "key", blk, -1); emit_switch("used_", "key", used, 0);
     emit_switch("ngr", "s", ngr, 0); emit_switch("csrc", "c", csrc, 0); emit_switch("ck0", "c", ck0, 0);
+    // register-resident weights: index of (chunk, row tile) in the lane's register array
+    std::vector<std::pair<int, int>> widx;
+    if (reg_mask && !flat) return false;
+    for (auto& cs : csrc)
+        if ((reg_mask >> cs.second) & 1)
+            for (int nt = 0; nt < NTU; ++nt)
+                if (std::find(used.begin(), used.end(), std::make_pair(cs.second * 16 + nt, 1)) != used.end()) { const int i = (int)widx.size(); widx.push_back({cs.first * 16 + nt, i}); }
+    emit_switch("widx", "key", widx, 0);
+    o << "    static constexpr unsigned REGMASK = " << reg_mask << "u;\n    static constexpr int NRW = " << widx.size() << ";\n";
     o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n";
     o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
     o << "}  // namespace " << ns << "\n";

@@ -1298,7 +1298,8 @@ struct MLayout {
 
 // Same on host and device.  lay is the generic step layout (tasks, sources) for G workgroups.
 // nw: wavefronts per workgroup (4 or 8); a chunk of a source is 16 * nw columns, 16 per wavefront.
-RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int nw, int lds_limit_floats, MLayout& m) {
+// reg_mask: bit s set = the weight rows of source s live in vector registers, not in LDS.
+RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int nw, unsigned reg_mask, int lds_limit_floats, MLayout& m) {
     m.ok = 0;
     const int cw = 16 * nw;
     if (!lay.ok || lay.n_phases != 1 || lay.n_sources < 1) return;
@@ -1319,8 +1320,10 @@ RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int nw, i
         }
         m.rows[s] = nb * ph.cmax;
         m.wstride[s] = (lay.src[s].k_len + cw - 1) / cw * cw + 4;      // zero-padded to whole chunks; = 4 (mod 32): conflict-free 128-bit reads
+        m.wbase[s] = cur;
+        if ((reg_mask >> s) & 1) continue;
         wsmax = m.wstride[s] > wsmax ? m.wstride[s] : wsmax;
-        m.wbase[s] = cur; cur += m.rows[s] * m.wstride[s];
+        cur += m.rows[s] * m.wstride[s];
     }
     m.zrow = cur; cur += wsmax;
     const int ntu = (ph.n_tasks * ph.cmax + 15) / 16;
@@ -1347,7 +1350,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     const int N = a.N - n0 < MM::NJ ? a.N - n0 : MM::NJ;                   // its streams
     MShared& sh = ms;
     constexpr int NW = MM::NW, NTHR = 64 * NW, CW = 16 * NW;      // wavefronts, threads, columns of a chunk
-    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, MM::NJ, sh.lay); compute_mstep_layout(sh.lay, MM::NJ, NW, (int)(MSTEP_LDS_LIMIT / 4), ms.ml); }
+    if (tid == 0) { compute_step_layout(a.words, a.desc_off, a.G, 1, MM::NJ, sh.lay); compute_mstep_layout(sh.lay, MM::NJ, NW, MM::REGMASK, (int)(MSTEP_LDS_LIMIT / 4), ms.ml); }
     __syncthreads();
     const StepPhase& ph = sh.lay.ph[0];
     const MLayout& ml = ms.ml;
@@ -1363,6 +1366,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     // source add up in one row
     constexpr int CMAX = MM::CMAX;
     for (int s = 0; s < ml.n_src; ++s) {
+        if ((MM::REGMASK >> s) & 1) continue;      // (in registers, below)
         const int K = sh.lay.src[s].k_len;
         for (int t = 0; t < ph.n_tasks; ++t) {
             const StepTask& task = ph.task[t];
@@ -1402,6 +1406,41 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             for (int t2 = 0; t2 < STEP_MAX_TASKS; ++t2) if (task == t2) b = MM::blk(sidx, t2);
             brow[sidx][nt] = (b >= 0 ? suni(ml.wbase[sidx]) + (b * CMAX + ul) * suni(ml.wstride[sidx]) : suni(ml.zrow)) + 4 * (lane >> 4);
         }
+    // Weight rows that do not fit LDS stay in vector registers for the whole launch (sources in
+    // MM::REGMASK; only with the unrolled chunk sequence, where every register index is static):
+    // for chunk c and row tile nt this lane keeps the four words it would read from LDS, i.e. the
+    // B operands of the chunk's four multiply steps, W[row of (nt, lane & 15)][k0 + 16 wave +
+    // 4 (lane >> 4) ...].  Edges of one task that share the source add up.
+    mfloatx4 wr[MM::NRW > 0 ? MM::NRW : 1];
+    if constexpr (MM::NRW > 0) {
+        step_static_for<0, MM::NCH>([&](auto cc) {
+            constexpr int c = decltype(cc)::value, sidx = MM::csrc(c), k0 = MM::ck0(c);
+            if constexpr (((MM::REGMASK >> sidx) & 1) != 0) {
+                step_static_for<0, MM::NTU>([&](auto tt) {
+                    constexpr int nt = decltype(tt)::value;
+                    if constexpr (MM::used(sidx, nt)) {
+                        const int col = nt * 16 + (lane & 15);
+                        const int task = col / CMAX, ul = col - task * CMAX;
+                        const int kk = k0 + wave * 16 + 4 * (lane >> 4);
+                        mfloatx4 wv = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (task < ph.n_tasks) {
+                            const StepTask& tk = ph.task[task];
+                            const int u = w * tk.chunk + ul;
+                            for (int e = 0; e < tk.n_edges; ++e) {
+                                const StepEdge ed = tk.e[e];
+                                if (ed.src != sidx || ul >= tk.chunk || u >= tk.n_out) continue;
+                                const float* W = a.weights + ed.w_off;
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (kk + j < MM::K(sidx)) wv[j] += ed.transposed ? W[(size_t)(kk + j) * tk.n_out + u] : W[(size_t)u * MM::K(sidx) + kk + j];
+                            }
+                        }
+                        wr[MM::widx(c * 16 + nt)] = wv;
+                    }
+                });
+            }
+        });
+    }
     // this lane's A-operand element inside a chunk: stream 16 mt + (lane & 15), columns wcol ... wcol + 3;
     // its byte offset in chunk 0 of each source (a stream beyond N: outside the descriptor)
     // With tile-blocked exchange (MM::XB) the source is the tensor's twin, whose 16 x 16 tiles
@@ -1578,9 +1617,13 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 constexpr int ca = c + D - 1 < NCH ? c + D - 1 : 0;      // the chunk D - 1 positions ahead, if any
                 constexpr int sa = MM::csrc(ca);
                 mfloatx4 opb[MM::NTU];
-#pragma unroll
-                for (int nt = 0; nt < MM::NTU; ++nt)
-                    if (MM::used(sidx, nt)) opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * 16]);
+                step_static_for<0, MM::NTU>([&](auto tt) {
+                    constexpr int nt = decltype(tt)::value;
+                    if constexpr (MM::used(sidx, nt)) {
+                        if constexpr (((MM::REGMASK >> sidx) & 1) != 0) opb[nt] = wr[MM::widx(c * 16 + nt)];
+                        else opb[nt] = *reinterpret_cast<const mfloatx4*>(&lds[brow[sidx][nt] + k0 + wave * 16]);
+                    }
+                });
                 if (bad && !dead) reload(v[i], StepIntC<sidx>{}, k0);
                 if (c == 0) { RNNG_STAMP(2); }
                 if (c == 1) { RNNG_STAMP(6); RNNG_STAMP(7); }

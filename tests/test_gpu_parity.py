@@ -309,11 +309,47 @@ def test_wide_layers_with_the_two_dimensional_split(monkeypatch, kind, N):
     spec = wl.elman_net(12, 1024, 6) if kind == "elman" else wl.lstm_net(12, [1024], 6)
     w = wl.make_workload(f"wide_{kind}", spec, T=5, N=N, seed=41, scale=0.05, bias_scale=0.1, masked_fraction=0.2)
     win, ref = run_both(w, label=f"2-D split, {kind}, N={N}")
+    rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, b) == ("matrix_2d", False) for k in rec for b in (False, True))
     win2 = window_for(w)
     win2.forward_range(0, 2); win2.forward_range(2, 5)
     win2.bptt(); win2.compute_grads()
     for k in w.spec.output_nodes():
         assert nerr(win2.node_output(k), ref["y"][k]) < OUT_TOL
+
+
+@pytest.mark.parametrize("kind,N", [("elman", 16), ("lstm", 16), ("lstm", 24), ("lstm", 64), ("elman", 48)])
+def test_wide_layers_with_weight_rows_in_registers(kind, N):
+    """1024-wide recurrent layers at many streams with the one-dimensional split: the weight rows
+    of a workgroup exceed LDS, so whole sources stay in vector registers.  Stream counts that are
+    multiples of 16 exchange through the tile-blocked twins (one and several stream groups), the
+    others through the row-major tensors; a window computed in two pieces."""
+    from paper_1503_02852_amd.runner import window_for
+    spec = wl.elman_net(12, 1024, 6) if kind == "elman" else wl.lstm_net(12, [1024], 6)
+    w = wl.make_workload(f"wide_{kind}", spec, T=5, N=N, seed=43, scale=0.05, bias_scale=0.1, masked_fraction=0.2)
+    win, ref = run_both(w, label=f"weights in registers, {kind}, N={N}")
+    rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    # (a backward loop that cannot fill a 16-row tile per workgroup may take the two-dimensional split)
+    assert rec and all(win.g.step_build(k, False) == ("matrix", False) for k in rec)
+    assert N % 16 or all(win.g.step_build(k, True) == ("matrix", False) for k in rec)
+    win2 = window_for(w)
+    win2.forward_range(0, 2); win2.forward_range(2, 5)
+    win2.bptt(); win2.compute_grads()
+    for k in w.spec.output_nodes():
+        assert nerr(win2.node_output(k), ref["y"][k]) < OUT_TOL
+
+
+@pytest.mark.parametrize("env", [{"RNNG_MSTEP_BLOCKED": "0"}, {"RNNG_MSTEP_WAVES": "4"}, {"RNNG_MSTEP_WAVES": "4", "RNNG_MSTEP_BLOCKED": "0"},
+                                 {"RNNG_MSTEP_REGS": "0"}])
+def test_matrix_core_kernel_switches(monkeypatch, env):
+    """The matrix-core step kernel with four wavefronts, with the exchange through the row-major
+    tensors at a stream count that would allow the tile-blocked twins, and without weight rows in
+    registers: a stack (one launch for both layers) and a single layer with a delay-2 connection."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    run_both(wl.make_workload("stack", wl.lstm_net(12, [64, 48], 5), T=9, N=32, seed=51, scale=0.3, bias_scale=0.2, masked_fraction=0.2),
+             label=f"stack, {env}")
+    run_both(wl.make_workload("gen", wl.generalized_net(8, 64, 2, 4), T=7, N=16, seed=52, scale=0.3, bias_scale=0.2), label=f"generalized, {env}")
 
 
 @pytest.mark.parametrize("local", ["0", "1"])
