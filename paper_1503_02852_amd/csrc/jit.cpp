@@ -13,6 +13,7 @@
 #include <hip/hiprtc.h>
 
 #include <cstdio>
+#include <algorithm>
 #include <cstdlib>
 #include <map>
 #include <mutex>
@@ -497,10 +498,29 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     };
     o << "struct MM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
       << ", D = " << D << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ", NW = " << NW << ", NCH = " << nch << ";\n"
-      << "    static constexpr bool FLAT = " << (flat ? "true" : "false") << ", XB = " << (blocked ? "true" : "false") << ";\n";
+      << "    static constexpr bool FLAT = " << (flat ? "true" : "false") << ", XB = " << (blocked ? "true" : "false") << ";\n"
+      ;
     std::vector<std::pair<int, int>> ks, blk, used, ngr, csrc, ck0;
-    for (int s = 0, c = 0; s < ml.n_src && flat; ++s)
-        for (int k = 0; k < lay.src[s].k_len; k += CW, ++c) { csrc.push_back({c, s}); ck0.push_back({c, k}); }
+    // The unrolled chunk sequence takes the sources in the order in which their values arrive: what
+    // another component of the launch produces (it runs ahead) and the component's own values of
+    // older frames first, the values that the other workgroups have produced in the step before
+    // (frame offset +- 1) last, so that the first multiplications run while those are on their way.
+    // CLATE: the first chunk of the latter.
+    int clate = 0;
+    if (flat) {
+        const std::vector<int>& own = backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs;
+        auto late = [&](int s) { return std::find(own.begin(), own.end(), lay.src[s].buf) != own.end() && std::abs(lay.src[s].frame_off) <= 1; };
+        std::vector<int> ord;
+        for (int s = 0; s < ml.n_src; ++s) if (!late(s)) ord.push_back(s);
+        for (int s = 0; s < ml.n_src; ++s) if (late(s)) ord.push_back(s);
+        int c = 0;
+        bool seen_late = false;
+        for (int s : ord) {
+            if (late(s) && !seen_late) { clate = c; seen_late = true; }
+            for (int k = 0; k < lay.src[s].k_len; k += CW, ++c) { csrc.push_back({c, s}); ck0.push_back({c, k}); }
+        }
+        if (!seen_late) clate = c;
+    }
     for (int s = 0; s < ml.n_src; ++s) {
         ks.push_back({s, lay.src[s].k_len});
         for (int t = 0; t < ph.n_tasks; ++t) if (ml.blk[s][t] >= 0) blk.push_back({s * STEP_MAX_TASKS + t, ml.blk[s][t]});
@@ -524,7 +544,7 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
             for (int nt = 0; nt < NTU; ++nt)
                 if (std::find(used.begin(), used.end(), std::make_pair(cs.second * 16 + nt, 1)) != used.end()) { const int i = (int)widx.size(); widx.push_back({cs.first * 16 + nt, i}); }
     emit_switch("widx", "key", widx, 0);
-    o << "    static constexpr unsigned REGMASK = " << reg_mask << "u;\n    static constexpr int NRW = " << widx.size() << ";\n";
+    o << "    static constexpr unsigned REGMASK = " << reg_mask << "u;\n    static constexpr int NRW = " << widx.size() << ", CLATE = " << clate << ";\n";
     o << "    static __device__ __forceinline__ constexpr int blk(int s, int task) { return blk_(s * " << STEP_MAX_TASKS << " + task); }\n";
     o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
     o << "}  // namespace " << ns << "\n";

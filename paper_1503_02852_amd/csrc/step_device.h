@@ -1596,13 +1596,19 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(x[mt].w), opb[nt][3], acc[mt][nt], 0, 0, 0);
                     }
         };
-        // hold the first loads back until the producers' stores are usually visible
-        for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
+        // The loads of what the other workgroups produced in the step before are held back until
+        // those stores are usually visible (a first attempt that comes back with a sentinel costs a
+        // whole extra round trip); chunks in front of them (MM::CLATE) are not.
+        // (With the unrolled sequence, where the multiplications of the early chunks fill that time,
+        // holding back measured slower than retrying: charlm_n32 forward 1.26 against 0.89 ms.)
+        constexpr int POLL_INC = MM::FLAT ? 0 : MSTEP_POLL_INC;
+        auto hold_off = [&]() { for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1); };
         if constexpr (MM::FLAT) {
             constexpr int NCH = MM::NCH;
             step_static_for<0, D - 1>([&](auto ii) {
                 constexpr int i = decltype(ii)::value;
                 constexpr int sx = MM::csrc(i < NCH ? i : 0);
+                if (i == MM::CLATE) hold_off();
                 load_chunk(v[i], rs[sx], aoff[sx], MM::K(sx), MM::K(sx) % CW != 0, MM::ck0(i < NCH ? i : 0), i < NCH);
             });
 #pragma unroll
@@ -1627,11 +1633,13 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 if (bad && !dead) reload(v[i], StepIntC<sidx>{}, k0);
                 if (c == 0) { RNNG_STAMP(2); }
                 if (c == 1) { RNNG_STAMP(6); RNNG_STAMP(7); }
+                if (c + D - 1 == MM::CLATE) hold_off();
                 if (c + D - 1 < NCH) load_chunk(v[j], rs[sa], aoff[sa], MM::K(sa), MM::K(sa) % CW != 0, MM::ck0(ca), true);
                 bad = c + 1 < NCH ? incomplete(v[i1]) : false;
                 multiply(StepIntC<sidx>{}, v[i], opb);
             });
         } else {
+        hold_off();
         step_static_for<0, D - 1>([&](auto ii) {
             constexpr int i = decltype(ii)::value;
             load_chunk(v[i], rs[0], aoff[0], MM::K(0), MM::K(0) % CW != 0, i * CW, i * CW < (MM::K(0) + CW - 1) / CW * CW);
@@ -1699,10 +1707,10 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         }
         RNNG_STAMP(3);
         // did any wavefront have to load a chunk again?  (word `step & 1`; the other one is cleared for the next step)
-        if (retried && lane == 0) atomicOr(&ms.retried[step & 1], 1u);
+        if (POLL_INC > 0 && retried && lane == 0) atomicOr(&ms.retried[step & 1], 1u);
         step_lds_barrier();
-        if (MSTEP_POLL_INC > 0) {
-            if (ms.retried[step & 1]) pdelay = pdelay + MSTEP_POLL_INC < 96 ? pdelay + MSTEP_POLL_INC : 96;
+        if (POLL_INC > 0) {
+            if (ms.retried[step & 1]) pdelay = pdelay + POLL_INC < 96 ? pdelay + POLL_INC : 96;
             else if ((step & 63) == 63 && pdelay > 0) --pdelay;
             if (tid == 0) ms.retried[(step + 1) & 1] = 0u;
         }
