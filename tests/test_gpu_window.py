@@ -63,6 +63,10 @@ WINDOW_NETS = {
     "generalized": lambda: (wl.generalized_net(8, 16, 2, 4), 2),
     "lstm_many_streams": lambda: (wl.lstm_net(8, [32], 4), 20),
     "lstm2_many_streams": lambda: (wl.lstm_net(8, [32, 24], 4), 18),
+    # 128-wide layers at a multiple of 16 streams: tile-blocked exchange forward, products sent backward
+    # (a stack in one launch; delay-2 connections and gated layer inputs)
+    "lstm2_16_streams": lambda: (wl.lstm_net(8, [128, 128], 4), 16),
+    "generalized_32_streams": lambda: (wl.generalized_net(8, 128, 2, 4), 32),
     # random graphs: delays up to 3, multiplicative nodes fed through delayed connections, inputs
     # with delayed and element-wise out-connections (the library keeps its own history of those)
     "random_a": lambda: (wl.random_graph(np.random.default_rng(501), n_inner=7, max_delay=3, n_inputs=2), 2),
