@@ -26,8 +26,6 @@ enum {
     RNN_BUILD_PER_FRAME = 6,    /* no persistent kernel: launches per frame */
     RNN_BUILD_STREAMING = 7,    /* run-time specialised, weights streamed from memory every step
                                    (layers too wide to keep on chip) */
-    RNN_BUILD_MATRIX_SCATTER = 8, /* run-time specialised, matrix cores, backward loop of many streams: every
-                                   workgroup multiplies its own rows and sends the products to their owners */
     RNN_BUILD_CHAIN = 16
 };
 int rnn_step_build(const rnn_graph* g, int32_t node, int32_t backward, int32_t* build);

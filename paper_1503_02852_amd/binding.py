@@ -19,7 +19,7 @@ EXPORTS = ["rnn_graph_create", "rnn_graph_destroy", "rnn_graph_schedule", "rnn_p
            "rnn_forward_static", "rnn_last_error"]
 # measurement and inspection aids (include/rnngraph_aux.h)
 AUX_EXPORTS = ["rnn_step_build", "rnn_debug_read_control", "rnn_profile_enable", "rnn_profile_read", "rnn_plan_work"]
-BUILD_NAMES = {0: "none", 1: "wave", 2: "matrix", 3: "matrix_2d", 4: "lds", 5: "interpreted", 6: "per_frame", 7: "streaming", 8: "matrix_scatter"}
+BUILD_NAMES = {0: "none", 1: "wave", 2: "matrix", 3: "matrix_2d", 4: "lds", 5: "interpreted", 6: "per_frame", 7: "streaming"}
 
 _lib = None
 

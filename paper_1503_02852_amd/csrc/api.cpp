@@ -48,8 +48,7 @@ int64_t g_layout_skew = 4352;      // bytes, a multiple of 256 (RNNG_LAYOUT_SKEW
 
 // partial_floats: floats per frame of the largest partial-sum tensor any launch of the window needs
 // transposed_copy: a streaming kernel of the window reads matrices transposed
-// ring_floats: floats of the ring of partial sums of the backward kernels that send products
-Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool transposed_copy, int64_t ring_floats) {
+Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool transposed_copy) {
     Layout L;
     int n_alloc = 0;
     const int K = (int)P.xnodes.size();
@@ -75,9 +74,7 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool tra
         cur += g_layout_skew * (1 + n_alloc % 13);
         ++n_alloc;
     }
-    if (partial_floats > 0 || ring_floats > 0) {      // (one launch at a time uses the region)
-        L.partial_off = cur; cur = align_up(cur + std::max((int64_t)(T + P.hist) * partial_floats, ring_floats) * 4, 256);
-    }
+    if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)(T + P.hist) * partial_floats * 4, 256); }
     if (transposed_copy) { L.wt_off = cur; cur = align_up(cur + P.n_params * 4, 256); }
     // an input whose connections are delayed may be given as class indices: room for its indices with history frames
     L.idx_off.assign(P.xnodes.size(), -1);
@@ -181,7 +178,7 @@ struct rnn_graph {
     bool use_jit = true;
     bool use_store_window = true;
     // Run-time specialised step kernels, chosen once per (component, direction, stream count).
-    struct JitChoice { bool wave = false, mstep = false, stream = false, needs_t = false, blocked = false, scatter = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0, slot_floats = 0; };
+    struct JitChoice { bool wave = false, mstep = false, stream = false, needs_t = false, blocked = false; int J = 1; StepLaunchPlan lp; std::string source, source_window; bool two_d = false; int64_t partial_floats = 0; };
     int force_step_J = 0;
     bool prefer_streaming = false;        // RNNG_STEP_BUILD=stream
     // the workgroups of a step launch wait for each other, so all of them must be resident at once:
@@ -225,21 +222,6 @@ struct rnn_graph {
         //     bytes a workgroup polls per step); unit chunks: as many as the compute units allow
         //     while a workgroup still fills a 16-row tile, else the smallest count whose weight
         //     rows fit on chip
-        // 2-. backward loops of many-stream windows: the variant that sends the products of a
-        //     workgroup's own rows (most unit chunks first)
-        const char* env2d = std::getenv("RNNG_MSTEP_2D");
-        const bool forced_2d = env2d && std::atoi(env2d) != 0, no_2d = env2d && std::atoi(env2d) == 0;
-        if (c.source.empty() && backward && N >= 16 && force_step_J <= 0 && !forced_2d)
-            for (int G : {256, 128, 64, 32, 16}) {
-                if (force_step_G > 0 && G != force_step_G) continue;
-                if (G * (N / 16) > max_workgroups()) continue;
-                size_t lds = 0; int64_t slot = 0;
-                std::string src = jit_ostep_source(plan, {&cp}, N, {G}, &lds, &slot);
-                if (src.empty()) continue;
-                c.source = src; c.mstep = true; c.scatter = true; c.slot_floats = slot; c.J = N / 16;
-                c.lp.ok = true; c.lp.G = G; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1; c.lp.threads = 512;
-                break;
-            }
         JitChoice one_d;
         int one_d_rows = -1;
         if (c.source.empty() && N > 8) {
@@ -267,6 +249,8 @@ struct rnn_graph {
         //     source and the row groups' members share 16-row tiles, at the price of a second
         //     exchange per step: only where the one-dimensional split cannot fill its tiles
         //     (RNNG_MSTEP_2D = 1: wherever the kernel can run; = 0: never)
+        const char* env2d = std::getenv("RNNG_MSTEP_2D");
+        const bool forced_2d = env2d && std::atoi(env2d) != 0, no_2d = env2d && std::atoi(env2d) == 0;
         if (c.source.empty() && N > 8 && force_step_G <= 0 && force_step_J <= 0 && max_workgroups() >= 256 && !no_2d &&
             (forced_2d || one_d_rows < 16)) {
             StepLayout lay;
@@ -312,18 +296,6 @@ struct rnn_graph {
         }
         return m;
     }
-    // floats of the largest ring of partial sums that a backward launch of a window with N streams needs
-    int64_t ring_floats(int N) {
-        int64_t m = 0;
-        if (!use_jit) return 0;
-        for (size_t c = 0; c < plan.comps.size(); ++c) {
-            const CompPlan& cp = plan.comps[c];
-            if (!cp.recurrent || !cp.has_bwd_program) continue;
-            if (cp.chain >= 0 && !chain_choice(cp.chain, true, N).source.empty()) { m = std::max(m, 8 * chain_choice(cp.chain, true, N).slot_floats); continue; }
-            m = std::max(m, 8 * jit_choice((int)c, true, N).slot_floats);
-        }
-        return m;
-    }
     // true if a step launch of a window with N streams reads transposed copies of weight matrices
     bool transposed_copy(int N) {
         if (!use_jit) return false;
@@ -341,7 +313,7 @@ struct rnn_graph {
     // Chains of recurrent components run side by side in one launch: all members in the
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
     // workgroups shared among the members).
-    struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false, blocked = false, scatter = false; size_t lds_bytes = 0; int threads = 256; int64_t slot_floats = 0; };
+    struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false, blocked = false; size_t lds_bytes = 0; int threads = 256; };
     std::map<std::tuple<int, bool, int>, ChainChoice> chain_choices;
     bool use_chains = true;
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
@@ -359,21 +331,6 @@ struct rnn_graph {
                 c.G.push_back(pick);
             }
             if (c.G.size() == ch.members.size()) c.source = jit_chain_source(plan, ch, backward, N, c.G);
-            if (c.source.empty() && backward && N >= 16 && force_step_J <= 0) {
-                // backward loops of many-stream windows: the variant that sends the products of a
-                // workgroup's own rows; every member the most unit chunks that fit its share
-                const int share = std::min(256, max_workgroups()) / (int)ch.members.size();
-                std::vector<const CompPlan*> mem;
-                for (const CompPlan& m : ch.members) mem.push_back(&m);
-                for (int G : {128, 64, 32, 16}) {
-                    if (G * (N / 16) > share) continue;
-                    std::vector<int> gs(ch.members.size(), G);
-                    c.source = jit_ostep_source(plan, mem, N, gs, &c.lds_bytes, &c.slot_floats);
-                    if (c.source.empty()) continue;
-                    c.G = gs; c.J.assign(ch.members.size(), N / 16); c.mstep = true; c.scatter = true; c.threads = 512;
-                    break;
-                }
-            }
             if (c.source.empty() && N > 8 && force_step_J <= 0) {
                 // matrix-core members: each gets an equal share of the 256 workgroups; per member the
                 // most stream groups, then the most unit chunks that fit the share (as for a single
@@ -619,8 +576,7 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
     const bool have_interp = !g->framewise && plan_step_launch(g->plan.words.data(), desc_off, N, g->force_step_G, lp);
     const int spin_limit = g->spin_limit;
     if (have_jit) {
-        // (the variant that sends products polls its ring and none of the exchanged tensors)
-        hipError_t fe = jc->scatter ? hipSuccess : fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, jc->wave, t0, t1, s, jc->blocked);
+        hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, jc->wave, t0, t1, s, jc->blocked);
         if (fe != hipSuccess) return step_error(fe, "sentinel fill");
         const bool window = jc->wave && wave_store_window_ok(g);
         std::string why;
@@ -632,13 +588,6 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
         if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
         a.J = jc->J;
         a.twin_base = g->plan.twin_base;
-        if (jc->scatter) {
-            if (g->layout.partial_off < 0) return step_error(hipErrorInvalidValue, "ring of partial sums missing from the workspace");
-            a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
-            a.grp_desc_off[0] = desc_off;
-            hipError_t e = launch_fill_sentinel(a.partial, 8 * jc->slot_floats, s);
-            if (e != hipSuccess) return step_error(e, "sentinel fill");
-        }
         if (jc->two_d) {
             if (g->layout.partial_off < 0) return step_error(hipErrorInvalidValue, "partial-sum tensor missing from the workspace");
             a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
@@ -672,7 +621,7 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
         if (!launch_fits_device(g, lp_all.G, why)) return step_error(hipSuccess, why);
         hipError_t e = jit_launch(fn, a, lp_all, s);
         if (e != hipSuccess) { (void)hipGetLastError(); return step_error(e, "specialised step kernel launch"); }
-        served = jc->wave ? RNN_BUILD_WAVE : jc->scatter ? RNN_BUILD_MATRIX_SCATTER : jc->two_d ? RNN_BUILD_MATRIX_2D : jc->stream ? RNN_BUILD_STREAMING : jc->mstep ? RNN_BUILD_MATRIX : RNN_BUILD_LDS;
+        served = jc->wave ? RNN_BUILD_WAVE : jc->two_d ? RNN_BUILD_MATRIX_2D : jc->stream ? RNN_BUILD_STREAMING : jc->mstep ? RNN_BUILD_MATRIX : RNN_BUILD_LDS;
         g->prof.end(prof, 1, s);
         return ok;
     }
@@ -722,7 +671,6 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     const int T = g->Ti(), N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     for (const CompPlan& m : ch.members) {
-        if (cc.scatter) break;      // (polls its ring and none of the exchanged tensors)
         hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s, cc.blocked);
         if (e != hipSuccess) return step_error(e, "sentinel fill");
     }
@@ -737,12 +685,6 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
     a.n_groups = (int)ch.members.size();
     a.twin_base = g->plan.twin_base;
-    if (cc.scatter) {
-        if (g->layout.partial_off < 0) return step_error(hipErrorInvalidValue, "ring of partial sums missing from the workspace");
-        a.partial = reinterpret_cast<float*>(g->ws + g->layout.partial_off);
-        hipError_t fe = launch_fill_sentinel(a.partial, 8 * cc.slot_floats, s);
-        if (fe != hipSuccess) return step_error(fe, "sentinel fill");
-    }
     for (int i = 0; i < a.n_groups; ++i) {
         a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
         a.grp_G[i] = cc.G[i];
@@ -758,7 +700,7 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     if (!launch_fits_device(g, participants, why)) return step_error(hipSuccess, why);
     hipError_t e = jit_launch(fn, a, lp, s);
     if (e != hipSuccess) { (void)hipGetLastError(); return step_error(e, "specialised chain step kernel launch"); }
-    for (int c = ch.first; c <= ch.last; ++c) g->served[c][backward ? 1 : 0] = (cc.scatter ? RNN_BUILD_MATRIX_SCATTER : cc.mstep ? RNN_BUILD_MATRIX : RNN_BUILD_WAVE) | RNN_BUILD_CHAIN;
+    for (int c = ch.first; c <= ch.last; ++c) g->served[c][backward ? 1 : 0] = (cc.mstep ? RNN_BUILD_MATRIX : RNN_BUILD_WAVE) | RNN_BUILD_CHAIN;
     g->prof.end(prof, 1, s);
     StepRun ok;
     return ok;
@@ -844,7 +786,7 @@ int64_t rnn_workspace_bytes(const rnn_graph* g, int32_t T, int32_t N) {
     if (!g) return fail(RNN_ERR_INVALID_ARGUMENT, "graph is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
     if ((int64_t)(T + g->plan.hist) * N >= (int64_t(1) << 31)) return fail(RNN_ERR_INVALID_ARGUMENT, "T * N exceeds 2^31 - 1");
-    return make_layout(g->plan, T, N, const_cast<rnn_graph*>(g)->partial_frame_floats(N), const_cast<rnn_graph*>(g)->transposed_copy(N), const_cast<rnn_graph*>(g)->ring_floats(N)).total;
+    return make_layout(g->plan, T, N, const_cast<rnn_graph*>(g)->partial_frame_floats(N), const_cast<rnn_graph*>(g)->transposed_copy(N)).total;
 }
 
 namespace {
@@ -911,8 +853,8 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
         if (!d_inputs[i] && !g->is_onehot(P.input_nodes[i])) return fail(RNN_ERR_INVALID_ARGUMENT, "an input tensor pointer is NULL");
     if (!d_workspace) return fail(RNN_ERR_WORKSPACE, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(RNN_ERR_WORKSPACE, "workspace is not 256-byte aligned");
-    if (ws_bytes < make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N), g->ring_floats(N)).total)
-        return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N), g->ring_floats(N)).total) + " bytes");
+    if (ws_bytes < make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N)).total)
+        return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N)).total) + " bytes");
     if (g->cu_count == 0) {
         // The step kernels' launch shapes depend on how many workgroups the device keeps resident.
         int dev = 0, cus = 0;
@@ -922,7 +864,7 @@ int rnn_forward_range(rnn_graph* g, const float* d_weights, const float* const* 
         if (cus != g->max_workgroups()) { g->jit_choices.clear(); g->chain_choices.clear(); }      // chosen for a whole device
         g->cu_count = cus;
     }
-    Layout L = make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N), g->ring_floats(N));
+    Layout L = make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N));
     if (ws_bytes < L.total) return fail(RNN_ERR_WORKSPACE, "workspace too small: need " + std::to_string(L.total) + " bytes");
     if (t_begin > 0) {
         // the earlier frames must be there: same window shape and workspace, computed up to t_begin
@@ -1030,7 +972,7 @@ int rnn_forward_static(rnn_graph* g, const float* d_weights, const float* const*
         if (!d_outputs[i]) return fail(RNN_ERR_INVALID_ARGUMENT, "an output tensor pointer is NULL");
     if (T <= 0 || N <= 0) return fail(RNN_ERR_INVALID_ARGUMENT, "T and N must be positive");
     if (g->prof.mask != 0) return fail(RNN_ERR_SEQUENCE, "kernel-class timing creates events: switch it off for rnn_forward_static");
-    const int64_t need = make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N), g->ring_floats(N)).total;
+    const int64_t need = make_layout(P, T, N, g->partial_frame_floats(N), g->transposed_copy(N)).total;
     if (need > (int64_t)RNN_STATIC_WORKSPACE_BYTES)
         return fail(RNN_ERR_WORKSPACE, "the window needs " + std::to_string(need) + " bytes of workspace, the static workspace holds " +
                                            std::to_string((int64_t)RNN_STATIC_WORKSPACE_BYTES));

@@ -449,7 +449,7 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
             }
             return (lay.src[s].k_len + CW - 1) / CW * tiles * 4;
         };
-        while (nch0 <= 64) {
+        while (nch0 <= 40) {
             int pick = -1;
             for (int s = 0; s < lay.n_sources; ++s)
                 if (!((reg_mask >> s) & 1) && (pick < 0 || words_of(s) > words_of(pick))) pick = s;
@@ -477,7 +477,7 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     // short chunk sequences are unrolled whole: the chunks in flight may then span several sources
     int nch = 0;
     for (int s = 0; s < ml.n_src; ++s) nch += (lay.src[s].k_len + CW - 1) / CW;
-    const bool flat = nch <= 64;
+    const bool flat = nch <= 40;
     // loads in flight per lane: about four with eight wavefronts (measured on two workloads: 4 / 8 / 12
     // in flight give 1.81 / 1.88 / 1.91 ms and 3.56 / 3.59 / 3.70 ms), a dozen with four
     const int inflight = NW == 8 ? 4 : 12;
@@ -782,182 +782,6 @@ std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, i
          "}\n";
     if (lds_bytes) *lds_bytes = lds;
     if (transposed) *transposed = any_t;
-    return o.str();
-}
-
-// Matrix-core variant of the backward loop that sends products instead of sources (see the kernel).
-// members: one component, or the members of a chain; G[i] unit chunks for member i; N streams.
-// Empty if not eligible; otherwise *lds_bytes receives the dynamic LDS size, *slot_floats the floats
-// of one slot of the ring of partial sums.
-std::string jit_ostep_source(const Plan& P, const std::vector<const CompPlan*>& members, int N, const std::vector<int>& G,
-                             size_t* lds_bytes, int64_t* slot_floats) {
-    const int NM = (int)members.size();
-    if (NM < 1 || NM > STEP_MAX_GROUPS || (int)G.size() != NM) return "";
-    if (N < 16 || N % 16 != 0 || N / 16 > 4) return "";
-    if (const char* env = std::getenv("RNNG_MSTEP_SCATTER")) if (std::atoi(env) == 0) return "";
-    const int J = N / 16, NW = 8;
-    int total = 0;
-    for (int g : G) total += g * J;
-    if (total > 256) return "";
-    struct Term { int aidx; int64_t w_off; };
-    struct PG { int src, dst, task, delay, n_out, c_dst, CB = 0, kmask = 0; std::vector<Term> terms; bool in_regs = true; int64_t RB = 0; int C = 0; int wl0 = 0; };
-    struct Member { StepLayout lay; const int32_t* pw; const int32_t* st; int nst, c; std::vector<int> aidx; int n_a = 0; std::vector<int64_t> RB; std::vector<int> C, BLK; };
-    std::vector<Member> mem(NM);
-    for (int m = 0; m < NM; ++m) {
-        const CompPlan& cp = *members[m];
-        if (cp.bwd_phases.size() != 1 || cp.bwd_phases[0].mv_off < 0) return "";
-        Member& M = mem[m];
-        compute_step_layout(P.words.data(), cp.bwd_desc_off, G[m], 1, 16, M.lay);
-        if (!M.lay.ok || M.lay.n_phases != 1) return "";
-        M.pw = &P.words[cp.bwd_phases[0].prog_off];
-        M.nst = M.pw[PG_NSTORES];
-        M.st = M.pw + PG_HEADER_WORDS + M.pw[PG_NGATHER] * GA_WORDS + M.pw[PG_NINV] * IV_WORDS + M.pw[PG_NOPS] * MO_WORDS;
-        // one chunk size for every node of the member: 4, 8 or 16 units per workgroup
-        M.c = M.lay.ph[0].item_chunk;
-        if (M.c != 4 && M.c != 8 && M.c != 16) return "";
-        for (int q = 0; q < M.nst; ++q) if (M.st[q * ST_WORDS + ST_DIM] != M.c * G[m]) return "";
-        M.aidx.assign(M.nst, -1);
-    }
-    // product groups: the edges of every task, by the member that produces their source and by delay
-    std::vector<PG> pgs;
-    for (int m = 0; m < NM; ++m) {
-        const StepPhase& ph = mem[m].lay.ph[0];
-        for (int tk = 0; tk < ph.n_tasks; ++tk) {
-            const StepTask& task = ph.task[tk];
-            if (task.n_out != mem[m].c * G[m] || task.n_out % 128 != 0) return "";
-            for (int e = 0; e < task.n_edges; ++e) {
-                const StepEdge& ed = task.e[e];
-                if (!ed.transposed) return "";
-                const StepSource& sc = mem[m].lay.src[ed.src];
-                int pm = -1, pq = -1;
-                for (int m2 = 0; m2 < NM && pm < 0; ++m2)
-                    for (int q = 0; q < mem[m2].nst; ++q)
-                        if (mem[m2].st[q * ST_WORDS + ST_BUF] == sc.buf && (mem[m2].st[q * ST_WORDS + ST_FLAGS] & 1)) { pm = m2; pq = q; break; }
-                if (pm < 0 || sc.frame_off < 0 || sc.k_len != mem[pm].c * G[pm]) return "";
-                if (pm == m && sc.frame_off < 1) return "";
-                if (mem[pm].aidx[pq] < 0) mem[pm].aidx[pq] = mem[pm].n_a++;
-                PG* pg = nullptr;
-                for (PG& x : pgs) if (x.src == pm && x.dst == m && x.task == tk && x.delay == sc.frame_off) pg = &x;
-                if (!pg) { PG x; x.src = pm; x.dst = m; x.task = tk; x.delay = sc.frame_off; x.n_out = task.n_out; x.c_dst = mem[m].c; pgs.push_back(x); pg = &pgs.back(); }
-                pg->terms.push_back(Term{mem[pm].aidx[pq], ed.w_off});
-            }
-        }
-    }
-    if (pgs.empty()) return "";
-    int max_delay = 0;
-    for (PG& x : pgs) max_delay = std::max(max_delay, x.delay);
-    if (max_delay > 3) return "";      // the ring has 8 slots: d_max + d_min + 1 <= 8 with two steps to spare
-    // regions of the ring slot: per (member, task) G * J * C blocks of c * 16 floats
-    int64_t slot = 0;
-    for (int m = 0; m < NM; ++m) {
-        const int nt = mem[m].lay.ph[0].n_tasks;
-        mem[m].RB.assign(nt, 0); mem[m].C.assign(nt, 0); mem[m].BLK.assign(nt, mem[m].c * 16);
-        for (int tk = 0; tk < nt; ++tk) {
-            int C = 0;
-            for (PG& x : pgs) if (x.dst == m && x.task == tk) { x.CB = C; C += G[x.src]; }
-            // every group's blocks fill whole 1 KiB loads
-            for (PG& x : pgs) if (x.dst == m && x.task == tk && (G[x.src] * mem[m].c * 16 * 4) % 1024 != 0) return "";
-            mem[m].C[tk] = C; mem[m].RB[tk] = slot;
-            slot += (int64_t)G[m] * J * C * mem[m].c * 16;
-        }
-    }
-    if (slot * 4 * 8 >= (int64_t(1) << 31)) return "";      // 32-bit byte offsets inside the ring
-    for (PG& x : pgs) { x.RB = mem[x.dst].RB[x.task]; x.C = mem[x.dst].C[x.task]; }
-    // per member: LDS layout and register budget
-    std::ostringstream o;
-    o << "#include \"step_device.h\"\nusing namespace rnng;\n";
-    size_t lds_max = 0;
-    auto emit_switch = [&](const char* name, const std::vector<std::pair<int, int64_t>>& cases) {
-        o << "    static __device__ __forceinline__ constexpr long long " << name << "(int key) {\n        switch (key) {\n";
-        for (auto& c : cases) o << "            case " << c.first << ": return " << c.second << "LL;\n";
-        o << "            default: return 0;\n        }\n    }\n";
-    };
-    for (int m = 0; m < NM; ++m) {
-        Member& M = mem[m];
-        const int KA = M.n_a * M.c, NA = (KA + 15) / 16;
-        if (NA > 4) return "";
-        std::vector<int> mine;      // product groups this member computes
-        for (size_t i = 0; i < pgs.size(); ++i) if (pgs[i].src == m) mine.push_back((int)i);
-        // k chunks (16 own rows) a group uses; weights: 4 words per lane and (tile of the wavefront, chunk)
-        int reg_words = 0, lds_floats = 0;
-        const int nt_tasks = M.lay.ph[0].n_tasks;
-        const int RED0 = 0, AM0 = RED0 + std::max(1, nt_tasks) * NW * 64 * 4, AS = NA * 16 + 4;
-        lds_floats = AM0 + 16 * AS;
-        // the largest groups first into registers (at most 144 words per lane), the rest into LDS
-        std::vector<int> order(mine);
-        auto words_of = [&](int pi) { int kc = 0; for (int b = 0; b < 4; ++b) kc += (pgs[pi].kmask >> b) & 1; return pgs[pi].n_out / 16 / NW * kc * 4; };
-        for (int pi : mine) {
-            PG& x = pgs[pi];
-            x.kmask = 0;
-            for (const Term& t : x.terms) for (int k = t.aidx * M.c; k < (t.aidx + 1) * M.c; ++k) x.kmask |= 1 << (k / 16);
-        }
-        std::sort(order.begin(), order.end(), [&](int a2, int b2) { return words_of(a2) > words_of(b2); });
-        for (int pi : order) {
-            PG& x = pgs[pi];
-            if (reg_words + words_of(pi) <= 144) { x.in_regs = true; reg_words += words_of(pi); }
-            else { x.in_regs = false; x.wl0 = lds_floats; lds_floats += words_of(pi) * NW * 64; }
-        }
-        if ((size_t)lds_floats * 4 > MSTEP_LDS_LIMIT) return "";
-        lds_max = std::max(lds_max, (size_t)lds_floats * 4);
-        o << "namespace grp" << m << " {\n";
-        emit_phase_descriptor(o, P, members[m]->bwd_phases[0], 0, 0);
-        o << "struct OM {\n    static constexpr int G = " << G[m] << ", J = " << J << ", CU = " << M.c << ", NTK = " << nt_tasks << ", NPG = " << mine.size()
-          << ", NA = " << NA << ", AS = " << AS << ", RED0 = " << RED0 << ", AM0 = " << AM0 << ", LDS_FLOATS = " << lds_floats << ";\n"
-          << "    static constexpr long long SLOT = " << slot << "LL;\n";
-        // consumer side: per task the region and its segments (one per product group that feeds it)
-        std::vector<std::pair<int, int64_t>> t_rb, t_c, t_nseg, seg_first, seg_delay, st_aidx;
-        for (int tk = 0; tk < nt_tasks; ++tk) {
-            t_rb.push_back({tk, M.RB[tk]}); t_c.push_back({tk, M.C[tk]});
-            int ns = 0;
-            for (PG& x : pgs) if (x.dst == m && x.task == tk) {
-                // (segments in the order of their first block)
-                seg_first.push_back({tk * 8 + ns, (int64_t)x.CB * M.c * 16 * 4 / 1024});      // first 1 KiB load of the segment
-                seg_delay.push_back({tk * 8 + ns, x.delay});
-                ++ns;
-            }
-            if (ns > 8) return "";
-            t_nseg.push_back({tk, ns});
-        }
-        for (int q = 0; q < M.nst; ++q) st_aidx.push_back({q, M.aidx[q]});
-        emit_switch("t_rb", t_rb); emit_switch("t_c", t_c); emit_switch("t_nseg", t_nseg);
-        emit_switch("seg_first", seg_first); emit_switch("seg_delay", seg_delay); emit_switch("st_aidx", st_aidx);
-        // producer side
-        std::vector<std::pair<int, int64_t>> p_rb, p_c, p_cb, p_cdst, p_delay, p_nout, p_kmask, p_regs, p_w0, p_nterms, pt_aidx, pt_woff, p_gdst, p_foreign;
-        int w0 = 0;
-        for (size_t i = 0; i < mine.size(); ++i) {
-            const PG& x = pgs[mine[i]];
-            p_rb.push_back({(int)i, x.RB}); p_c.push_back({(int)i, x.C}); p_cb.push_back({(int)i, x.CB}); p_cdst.push_back({(int)i, x.c_dst});
-            p_delay.push_back({(int)i, x.delay}); p_nout.push_back({(int)i, x.n_out}); p_kmask.push_back({(int)i, x.kmask});
-            p_regs.push_back({(int)i, x.in_regs ? 1 : 0}); p_gdst.push_back({(int)i, G[x.dst]}); p_foreign.push_back({(int)i, x.dst != m ? 1 : 0});
-            p_w0.push_back({(int)i, x.in_regs ? w0 : x.wl0});
-            if (x.in_regs) w0 += words_of(mine[i]) / 4;
-            if (x.terms.size() > 16) return "";
-            p_nterms.push_back({(int)i, (int64_t)x.terms.size()});
-            for (size_t t = 0; t < x.terms.size(); ++t) { pt_aidx.push_back({(int)(i * 16 + t), x.terms[t].aidx}); pt_woff.push_back({(int)(i * 16 + t), x.terms[t].w_off}); }
-        }
-        emit_switch("p_rb", p_rb); emit_switch("p_c", p_c); emit_switch("p_cb", p_cb); emit_switch("p_cdst", p_cdst); emit_switch("p_gdst", p_gdst);
-        emit_switch("p_delay", p_delay); emit_switch("p_nout", p_nout); emit_switch("p_kmask", p_kmask); emit_switch("p_regs", p_regs);
-        emit_switch("p_foreign", p_foreign); emit_switch("p_w0", p_w0); emit_switch("p_nterms", p_nterms); emit_switch("pt_aidx", pt_aidx); emit_switch("pt_woff", pt_woff);
-        o << "    static constexpr int NRW = " << std::max(1, w0) << ";\n};\n}  // namespace grp" << m << "\n";
-    }
-    o << "extern \"C\" __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))\n"
-         "void rnng_step_jit(StepArgs a) {\n"
-         "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
-         "    __shared__ MShared ms;\n"
-         "    const int b = blockIdx.x;\n"
-         "    StepArgs c = a;\n";
-    int first = 0;
-    for (int m = 0; m < NM; ++m) {
-        o << "    if (b >= " << first << " && b < " << first + G[m] * J << ") {\n"
-             "        c.desc_off = a.grp_desc_off[" << m << "]; c.G = " << G[m] << "; c.J = " << J << ";\n"
-             "        ostep_kernel_body<grp" << m << "::PH0, grp" << m << "::OM>(c, ms, lds, b - " << first << ");\n"
-             "        return;\n"
-             "    }\n";
-        first += G[m] * J;
-    }
-    o << "}\n";
-    if (lds_bytes) *lds_bytes = lds_max;
-    if (slot_floats) *slot_floats = slot;
     return o.str();
 }
 

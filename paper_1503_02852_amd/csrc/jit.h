@@ -46,11 +46,6 @@ bool jit_available();
 // Loaded kernel for the source on the current device, or nullptr with the reason (compiler log,
 // loader error) in *err.  allow_load = false: only a kernel that is already loaded is returned
 // (nothing is compiled or loaded, so no memory is allocated).
-// Matrix-core variant of the backward loop that sends products of a workgroup's own rows to the
-// owners of the result instead of polling all sources (members: one component or a chain's);
-// *slot_floats: floats of one of the 8 slots of the ring of partial sums.
-std::string jit_ostep_source(const Plan& P, const std::vector<const CompPlan*>& members, int N, const std::vector<int>& G,
-                             size_t* lds_bytes, int64_t* slot_floats);
 // max_dynamic_lds: the most dynamic LDS a launch of the kernel may ask for.
 hipFunction_t jit_step_function(const std::string& source, std::string* err, bool allow_load = true, unsigned max_dynamic_lds = STEP_LDS_LIMIT);
 hipError_t jit_launch(hipFunction_t fn, StepArgs& a, const StepLaunchPlan& lp, hipStream_t stream);

@@ -2110,276 +2110,6 @@ __device__ __forceinline__ void mstep2_kernel_body(const StepArgs& a, M2Shared& 
 }
 
 // =============================================================================================
-// Matrix-core variant of the BACKWARD loop that sends products instead of sources.
-//
-// The backward loop of an LSTM-like layer contracts over four times as many values as it produces
-// (the state gradients of all gates of frame t + 1 against the transposed matrices), so the
-// variants above, in which every workgroup polls every source, move and multiply far more than
-// needed, and a workgroup's few output rows leave its 16-row tiles half empty.  Here a workgroup
-// multiplies what it has itself: right after the element-wise program it holds ds(t) of its own
-// units (KA values per stream, all nodes of its chunk), and the rows of those units in every
-// matrix that leads back from them.  For every product group (destination task, delay d) it
-// computes P[n][u] = sum_k ds_own[n][k] W[k][u] for ALL units u of the destination (a 16 x KA by
-// KA x n_out product with full tiles; W rows from registers or LDS) and stores, written through,
-// the piece of every destination workgroup into that workgroup's region of slot (t - d) mod 8 of
-// a ring of partial sums: [slot][task region][destination workgroup][contribution][unit][stream].
-// A step begins with polling the contributions to the workgroup's own frame (consecutive
-// addresses, 1 KiB per wavefront load), adding them in a fixed order and handing the memory back
-// as sentinels; contributions from frames outside the computed range do not exist and are not
-// waited for.  Per step a workgroup of a layer of H units with G chunks polls G blocks per
-// product group instead of four H-wide sources, at the price of storing n_out x 16 partial sums.
-// The ring is safe because a slot is written again 8 - d_max - 1 >= 2 steps after its owner has
-// read it and handed it back, and every workgroup of a step has waited for all of the step before.
-//
-// OM is a generated descriptor (see jit_ostep_source): G, J, CU (units per workgroup), NTK tasks
-// with their regions (t_rb, t_c, segments), NPG product groups with destination region, weights'
-// place and terms, NA chunks of 16 own rows, LDS offsets.
-// =============================================================================================
-constexpr int OSTEP_RING = 8;
-
-template <class PH, class OM>
-// w: index of this workgroup among the OM::G * OM::J workgroups of the component.
-__device__ __forceinline__ void ostep_kernel_body(const StepArgs& a, MShared& ms, float* lds, int w) {
-    if (w < 0 || w >= OM::G * OM::J) return;
-    constexpr int NW = 8, NTHR = 64 * NW, CU = OM::CU, BLK = CU * 16, LPB = 256 / BLK;      // LPB blocks per 1 KiB load
-    const int wj = w / OM::G, wc = w - wj * OM::G;      // stream group, unit chunk
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int T = a.T;
-    const int n0 = wj * 16;
-    MShared& sh = ms;
-    if (tid == 0) compute_step_layout(a.words, a.desc_off, OM::G, 1, 16, sh.lay);
-    __syncthreads();
-    const StepPhase& ph = sh.lay.ph[0];
-    if (tid < STEP_THREADS) {
-        const int ic = ph.item_chunk;
-        const int il = tid % ic, n = tid / ic;
-        sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < 16 ? n0 + n : 0xFFFF) << 16);
-    }
-    for (int i = tid; i < OM::LDS_FLOATS; i += NTHR) lds[i] = 0.0f;
-    __syncthreads();
-    PhaseRegs<PH> r;
-    phase_setup<PH, 1, 2>(r, a, sh, lds, wc, tid);
-    wave_store_setup<PH, MStore>(r, a);
-    wave_carry_init<PH>(r, a);
-    // ---- the rows of the workgroup's own units in every matrix that leads back from them ----
-    // For product group p, tile i of this wavefront (destination units 16 (wave + 8 i) ...) and own
-    // rows 16 kc ..., lane (n, q) keeps W[row 16 kc + 4 q + j][unit n of the tile], j = 0 .. 3: the B
-    // operands of four multiply steps.  Own row k is unit k % CU of the k / CU-th exchanged node.
-    mfloatx4 wr[OM::NRW];
-    step_static_for<0, OM::NPG>([&](auto pp) {
-        constexpr int p = decltype(pp)::value;
-        constexpr int NT = (int)OM::p_nout(p) / 16 / NW, KM = (int)OM::p_kmask(p);
-        step_static_for<0, NT>([&](auto ii) {
-            constexpr int i = decltype(ii)::value;
-            step_static_for<0, OM::NA>([&](auto kk) {
-                constexpr int kc = decltype(kk)::value;
-                if constexpr (((KM >> kc) & 1) != 0) {
-                    mfloatx4 wv = {0.0f, 0.0f, 0.0f, 0.0f};
-                    const int col = (wave + NW * i) * 16 + (lane & 15);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int k = kc * 16 + 4 * (lane >> 4) + j, ai = k / CU, ul = k - ai * CU;
-                        for (int t = 0; t < (int)OM::p_nterms(p); ++t)
-                            if ((int)OM::pt_aidx(p * 16 + t) == ai)
-                                wv[j] += a.weights[OM::pt_woff(p * 16 + t) + (long long)(wc * CU + ul) * OM::p_nout(p) + col];
-                    }
-                    constexpr int NKC = ((KM >> 0) & 1) + ((KM >> 1) & 1) + ((KM >> 2) & 1) + ((KM >> 3) & 1);
-                    constexpr int kpos = (kc > 0 ? ((KM >> 0) & 1) : 0) + (kc > 1 ? ((KM >> 1) & 1) : 0) + (kc > 2 ? ((KM >> 2) & 1) : 0);
-                    if constexpr (OM::p_regs(p) != 0) wr[(int)OM::p_w0(p) + i * NKC + kpos] = wv;
-                    else *reinterpret_cast<mfloatx4*>(&lds[(int)OM::p_w0(p) + ((i * NKC + kpos) * NTHR + tid) * 4]) = wv;
-                }
-            });
-        });
-    });
-    __syncthreads();
-
-    const bool wave_items = __builtin_amdgcn_ballot_w64(r.n >= 0) != 0;
-    const int item_il = tid < STEP_THREADS ? (int)(sh.iteminfo[0][tid] & 0xFFFF) : 0;
-    const int item_n = r.n >= 0 ? tid / suni(ph.item_chunk) : 0;      // local stream of this thread's item
-    auto gather_at = [&](auto gg, int frame) -> float {
-        constexpr int g = decltype(gg)::value;
-        const bool in_window = frame >= 0 && frame < T;
-        const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(r.gbase[g]), 0, T * r.gstride[g] * 4, STEP_RSRC_FLAGS);
-        const int off = in_window ? (int)(r.gvoff[g] + (unsigned)(frame * r.gstride[g] * 4)) : (int)WAVE_NO_STORE;
-        return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rg, off, 0, PH::gkind(g) == GA_KIND_STATIC ? 0 : STEP_COHERENT_AUX));
-    };
-    bool dead = false;
-    float sn[PH::NG > 0 ? PH::NG : 1];
-    const int nsteps = step_count(a);
-    if (wave_items && nsteps > 0)
-        step_static_for<0, PH::NG>([&](auto gg) {
-            constexpr int g = decltype(gg)::value;
-            if (PH::gkind(g) == GA_KIND_STATIC) sn[g] = gather_at(gg, step_frame(a, 0) + r.goff[g]);
-        });
-    const muintx4 sentinels = {STEP_SENTINEL, STEP_SENTINEL, STEP_SENTINEL, STEP_SENTINEL};
-    for (int step = 0; step < nsteps; ++step) {
-        const int t = step_frame(a, step);
-        float s[MAX_SLOTS];
-        RNNG_STAMP(0);
-        if (wave_items)
-            step_static_for<0, PH::NG>([&](auto gg) {
-                constexpr int g = decltype(gg)::value;
-                if (PH::gkind(g) == GA_KIND_FRAMES) s[g] = gather_at(gg, t + r.goff[g]);
-            });
-        // ---- 1. the contributions to this frame: poll, add in a fixed order, hand the memory back ----
-        step_static_for<0, OM::NTK>([&](auto tt) {
-            constexpr int tk = decltype(tt)::value;
-            constexpr int NL = (int)OM::t_c(tk) * BLK / 256, NLW = (NL + NW - 1) / NW;      // loads of 1 KiB in all / per wavefront
-            const float* region = a.partial + (long long)(t & (OSTEP_RING - 1)) * OM::SLOT + OM::t_rb(tk) + (long long)(wc * OM::J + wj) * (OM::t_c(tk) * BLK);
-            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(region), 0, (int)OM::t_c(tk) * BLK * 4, STEP_RSRC_FLAGS);
-            mfloatx4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-            constexpr int NB8 = (NLW + 7) / 8;      // batches of at most 8 loads in flight per lane
-            step_static_for<0, NB8>([&](auto bb) {
-            constexpr int j0 = decltype(bb)::value * 8, NLB = NLW - j0 < 8 ? NLW - j0 : 8;
-            muintx4 v[NLB];
-            int off[NLB];
-#pragma unroll
-            for (int j = 0; j < NLB; ++j) {
-                const int i = (j0 + j) * NW + wave;
-                // the delay of the product group the load belongs to: its producers ran at frame t + delay
-                int delay = (int)OM::seg_delay(tk * 8);
-#pragma unroll
-                for (int sg = 1; sg < (int)OM::t_nseg(tk); ++sg) delay = i >= (int)OM::seg_first(tk * 8 + sg) ? (int)OM::seg_delay(tk * 8 + sg) : delay;
-                const bool on = i < NL && t + delay < a.t_end;
-                off[j] = on ? (i * 256 + lane * 4) * 4 : 0x7FFFFFF0;
-                v[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[j], 0, STEP_COHERENT_AUX);
-            }
-#pragma unroll
-            for (int j = 0; j < NLB; ++j) {
-                auto incomplete = [&](const muintx4& x) {
-                    const unsigned m1 = x.x > x.y ? x.x : x.y, m2 = x.z > x.w ? x.z : x.w;
-                    return __builtin_amdgcn_ballot_w64((m1 > m2 ? m1 : m2) == STEP_SENTINEL) != 0;
-                };
-                if (j0 + j == 0) { RNNG_STAMP(1); }
-                if (incomplete(v[j]) && !dead) {
-                    muintx4 again;
-                    int spins = 0;
-                    for (;;) {
-                        if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
-                        __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
-                        step_compiler_barrier();
-                        again = __builtin_amdgcn_raw_buffer_load_b128(rs, off[j], 0, STEP_COHERENT_AUX);
-                        if (!incomplete(again)) break;
-                    }
-                    v[j] = again;
-                }
-                if (j0 + j == 0) { RNNG_STAMP(2); }
-                sum[0] += __uint_as_float(v[j].x); sum[1] += __uint_as_float(v[j].y);
-                sum[2] += __uint_as_float(v[j].z); sum[3] += __uint_as_float(v[j].w);
-                __builtin_amdgcn_raw_buffer_store_b128(sentinels, rs, off[j], 0, STEP_COHERENT_AUX);
-            }
-            });
-            *reinterpret_cast<mfloatx4*>(&lds[OM::RED0 + ((tk * NW + wave) * 64 + lane) * 4]) = sum;
-        });
-        RNNG_STAMP(3);
-        step_lds_barrier();
-        RNNG_STAMP(4);
-        // ---- 2. element-wise program: one thread per (stream, unit) ----
-        if (wave_items) {
-#pragma unroll
-            for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
-            step_static_for<0, PH::NG>([&](auto gg) {
-                constexpr int g = decltype(gg)::value;
-                if (PH::gkind(g) == GA_KIND_CARRY) s[g] = r.carry[PH::cidx(g)];
-                else if (PH::gkind(g) == GA_KIND_STATIC) s[g] = sn[g];
-                if (PH::gkind(g) == GA_KIND_ACC) {
-                    // the value sits in lane (block b of the load, unit, stream / 4) of every wavefront's sum
-                    float x = 0.0f;
-#pragma unroll
-                    for (int wv = 0; wv < NW; ++wv)
-#pragma unroll
-                        for (int b = 0; b < LPB; ++b)
-                            x += lds[OM::RED0 + ((PH::gaux(g) * NW + wv) * 64 + b * (BLK / 4) + item_il * 4 + (item_n >> 2)) * 4 + (item_n & 3)];
-                    s[g] = r.gptr[g] != nullptr ? x : 0.0f;
-                }
-            });
-            PH::ops(s);
-#pragma unroll
-            for (int q = 0; q < PH::NST; ++q) {
-                wave_store<PH, MStore>(r, q, s[PH::stslot(q)], 0, a);
-                // ds of the workgroup's own units: the A operand of the products below
-                if ((int)OM::st_aidx(q) >= 0 && r.n >= 0) lds[OM::AM0 + item_n * OM::AS + (int)OM::st_aidx(q) * CU + item_il] = r.sptr[q] != nullptr ? s[PH::stslot(q)] : 0.0f;
-            }
-#pragma unroll
-            for (int g = 0; g < PH::NG; ++g)
-                if (PH::gkind(g) == GA_KIND_CARRY) r.carry[PH::cidx(g)] = s[PH::gaux(g)];
-            const int t2 = t - 1;
-            const bool more = step + 1 < nsteps;
-            step_static_for<0, PH::NG>([&](auto gg) {
-                constexpr int g = decltype(gg)::value;
-                if (PH::gkind(g) == GA_KIND_STATIC) sn[g] = gather_at(gg, more ? t2 + r.goff[g] : -1);
-            });
-        }
-        wave_store_advance<PH>(r);
-        RNNG_STAMP(5);
-        step_lds_barrier();
-        // ---- 3. products of the own rows, sent to the owners of the results ----
-        mfloatx4 aq[OM::NA];
-#pragma unroll
-        for (int kc = 0; kc < OM::NA; ++kc) aq[kc] = *reinterpret_cast<const mfloatx4*>(&lds[OM::AM0 + (lane & 15) * OM::AS + kc * 16 + 4 * (lane >> 4)]);
-        step_static_for<0, OM::NPG>([&](auto pp) {
-            constexpr int p = decltype(pp)::value;
-            constexpr int NT = (int)OM::p_nout(p) / 16 / NW, KM = (int)OM::p_kmask(p), CD = (int)OM::p_cdst(p), BD = CD * 16;
-            constexpr int NKC = ((KM >> 0) & 1) + ((KM >> 1) & 1) + ((KM >> 2) & 1) + ((KM >> 3) & 1);
-            const int tau = t - (int)OM::p_delay(p);
-            const bool send = tau >= a.t_begin;
-            const float* dest = a.partial + (long long)(tau & (OSTEP_RING - 1)) * OM::SLOT + OM::p_rb(p);
-            const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(dest), 0, (int)(OM::p_gdst(p) * OM::J * OM::p_c(p) * BD * 4), STEP_RSRC_FLAGS);
-            auto dest_off = [&](int i) {
-                // destination unit u of tile i: block (workgroup d, this contribution), [unit][stream]
-                const int u = (wave + NW * i) * 16 + (lane & 15), d = u / CD, ul = u - d * CD;
-                return (((d * OM::J + wj) * (int)OM::p_c(p) + (int)OM::p_cb(p) + wc) * BD + ul * 16 + 4 * (lane >> 4)) * 4;
-            };
-            constexpr int TG = 8, NTG = (NT + TG - 1) / TG;      // tiles in groups of at most 8
-            step_static_for<0, NTG>([&](auto gg) {
-                constexpr int i0 = decltype(gg)::value * TG, NI = NT - i0 < TG ? NT - i0 : TG;
-                // Another component of the launch may lag any number of frames behind this one: a
-                // block must have been read and handed back (all sentinels) before it is written
-                // again.  (Workgroups of one component are never more than d_min frames apart.)
-                muintx4 chk[NI];
-                if constexpr (OM::p_foreign(p) != 0) {
-#pragma unroll
-                    for (int i = 0; i < NI; ++i) chk[i] = __builtin_amdgcn_raw_buffer_load_b128(rd, send ? dest_off(i0 + i) : 0x7FFFFFF0, 0, STEP_COHERENT_AUX);
-                }
-                step_static_for<0, NI>([&](auto ii) {
-                    constexpr int i = i0 + decltype(ii)::value;
-                    mfloatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-                    step_static_for<0, OM::NA>([&](auto kk) {
-                        constexpr int kc = decltype(kk)::value;
-                        if constexpr (((KM >> kc) & 1) != 0) {
-                            constexpr int kpos = (kc > 0 ? ((KM >> 0) & 1) : 0) + (kc > 1 ? ((KM >> 1) & 1) : 0) + (kc > 2 ? ((KM >> 2) & 1) : 0);
-                            mfloatx4 b;
-                            if constexpr (OM::p_regs(p) != 0) b = wr[(int)OM::p_w0(p) + i * NKC + kpos];
-                            else b = *reinterpret_cast<const mfloatx4*>(&lds[(int)OM::p_w0(p) + ((i * NKC + kpos) * NTHR + tid) * 4]);
-                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aq[kc][0], b[0], acc, 0, 0, 0);
-                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aq[kc][1], b[1], acc, 0, 0, 0);
-                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aq[kc][2], b[2], acc, 0, 0, 0);
-                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aq[kc][3], b[3], acc, 0, 0, 0);
-                        }
-                    });
-                    const int off = dest_off(i);
-                    if constexpr (OM::p_foreign(p) != 0) {
-                        muintx4 x = chk[i - i0];
-                        int spins = 0;
-                        while (send && !dead) {
-                            const unsigned m1 = x.x < x.y ? x.x : x.y, m2 = x.z < x.w ? x.z : x.w;
-                            if (__builtin_amdgcn_ballot_w64((m1 < m2 ? m1 : m2) != STEP_SENTINEL) == 0) break;
-                            if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
-                            __builtin_amdgcn_s_sleep(2);
-                            step_compiler_barrier();
-                            x = __builtin_amdgcn_raw_buffer_load_b128(rd, off, 0, STEP_COHERENT_AUX);
-                        }
-                    }
-                    // acc[e]: stream 4 (lane >> 4) + e
-                    const muintx4 o = {step_shared_bits(acc[0]), step_shared_bits(acc[1]), step_shared_bits(acc[2]), step_shared_bits(acc[3])};
-                    __builtin_amdgcn_raw_buffer_store_b128(o, rd, send ? off : 0x7FFFFFF0, 0, STEP_COHERENT_AUX);
-                });
-            });
-        });
-    }
-}
-
-// =============================================================================================
 // Streaming variant (run-time specialised, single-phase components, few streams, wide layers).
 //
 // From about 2,000 units on, the full weight matrices inside a recurrent node no longer fit the

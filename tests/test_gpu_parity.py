@@ -319,14 +319,12 @@ def test_wide_layers_with_the_two_dimensional_split(monkeypatch, kind, N):
 
 
 @pytest.mark.parametrize("kind,N", [("elman", 16), ("lstm", 16), ("lstm", 24), ("lstm", 64), ("elman", 48)])
-def test_wide_layers_with_weight_rows_in_registers(monkeypatch, kind, N):
+def test_wide_layers_with_weight_rows_in_registers(kind, N):
     """1024-wide recurrent layers at many streams with the one-dimensional split: the weight rows
     of a workgroup exceed LDS, so whole sources stay in vector registers.  Stream counts that are
     multiples of 16 exchange through the tile-blocked twins (one and several stream groups), the
-    others through the row-major tensors; a window computed in two pieces.  (The backward variant
-    that sends products is switched off here: it has a test of its own.)"""
+    others through the row-major tensors; a window computed in two pieces."""
     from paper_1503_02852_amd.runner import window_for
-    monkeypatch.setenv("RNNG_MSTEP_SCATTER", "0")
     spec = wl.elman_net(12, 1024, 6) if kind == "elman" else wl.lstm_net(12, [1024], 6)
     w = wl.make_workload(f"wide_{kind}", spec, T=5, N=N, seed=43, scale=0.05, bias_scale=0.1, masked_fraction=0.2)
     win, ref = run_both(w, label=f"weights in registers, {kind}, N={N}")
@@ -341,7 +339,7 @@ def test_wide_layers_with_weight_rows_in_registers(monkeypatch, kind, N):
         assert nerr(win2.node_output(k), ref["y"][k]) < OUT_TOL
 
 
-SCATTER_NETS = {
+MANY_STREAM_NETS = {
     "elman_1024_n16": lambda: (wl.elman_net(12, 1024, 6), 16, 0.05),
     "lstm_1024_n64": lambda: (wl.lstm_net(12, [1024], 6), 64, 0.05),
     "lstm_stack_n32": lambda: (wl.lstm_net(12, [256, 128, 256], 6), 32, 0.15),
@@ -350,21 +348,20 @@ SCATTER_NETS = {
 }
 
 
-@pytest.mark.parametrize("name", sorted(SCATTER_NETS))
-def test_backward_loop_that_sends_products(name):
-    """The backward variant of the matrix-core kernel in which a workgroup multiplies the state
-    gradients of its own units and sends the products to the owners of the results: single layers
-    (4, 8 and 16 units per workgroup; weights in registers and in LDS), a stack in one launch
-    (layers that run ahead wait until their blocks of the ring are free), delay-2 connections."""
-    spec, N, scale = SCATTER_NETS[name]()
+@pytest.mark.parametrize("name", sorted(MANY_STREAM_NETS))
+def test_many_stream_layers_of_several_widths(name):
+    """Matrix-core step kernels at stream counts that are multiples of 16 (exchange through the
+    tile-blocked twins): single wide layers with weight rows in registers, a stack of three layers
+    of different widths in one launch, delay-2 connections, three to four stream groups."""
+    spec, N, scale = MANY_STREAM_NETS[name]()
     w = wl.make_workload(name, spec, T=13, N=N, seed=61, scale=scale, bias_scale=0.1, masked_fraction=0.2)
-    win, ref = run_both(w, label=f"products sent backward, {name}")
+    win, ref = run_both(w, label=f"many streams, {name}")
     rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
-    assert rec and all(win.g.step_build(k, True)[0] == "matrix_scatter" for k in rec)
+    assert rec and all(win.g.step_build(k, b)[0] in ("matrix", "matrix_2d") for k in rec for b in (False, True))
 
 
 @pytest.mark.parametrize("env", [{"RNNG_MSTEP_BLOCKED": "0"}, {"RNNG_MSTEP_WAVES": "4"}, {"RNNG_MSTEP_WAVES": "4", "RNNG_MSTEP_BLOCKED": "0"},
-                                 {"RNNG_MSTEP_REGS": "0"}, {"RNNG_MSTEP_SCATTER": "0"}])
+                                 {"RNNG_MSTEP_REGS": "0"}])
 def test_matrix_core_kernel_switches(monkeypatch, env):
     """The matrix-core step kernel with four wavefronts, with the exchange through the row-major
     tensors at a stream count that would allow the tile-blocked twins, and without weight rows in
