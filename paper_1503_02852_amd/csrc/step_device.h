@@ -1411,10 +1411,33 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     // for chunk c and row tile nt this lane keeps the four words it would read from LDS, i.e. the
     // B operands of the chunk's four multiply steps, W[row of (nt, lane & 15)][k0 + 16 wave +
     // 4 (lane >> 4) ...].  Edges of one task that share the source add up.
+    // The workgroups of an XCD poll the same lines of its L2 at about the same time.  With the
+    // unrolled chunk sequence every workgroup therefore walks a source's chunks from a place of its
+    // own (rank inside the XCD; chunk c of the sequence stands for columns rot(sidx, k0) ...), which
+    // spreads the requests over the L2's channels (stand-alone probe: 10 to 28 % more polled bytes
+    // per microsecond).  The order of the sources stays.  Kept for components with several sources
+    // (measured: charlm_n32 3.68 -> 3.54 ms per window, generalized_n64 14.22 -> 14.15); a layer
+    // with one source ran 3 % slower with it (fig4_h2048_n16).
+#if !defined(MSTEP_ROTATE)
+#define MSTEP_ROTATE 1
+#endif
+    int krot[MM::NSRC];
+#pragma unroll
+    for (int sidx = 0; sidx < MM::NSRC; ++sidx) {
+        const int nch = (MM::K(sidx) + CW - 1) / CW;
+        krot[sidx] = MM::FLAT && MSTEP_ROTATE && MM::NSRC > 1 ? suni((int)((blockIdx.x >> 3) & 31) * nch / 32 * CW) : 0;
+    }
+    auto rot = [&](auto ss, int k0) {
+        constexpr int sidx = decltype(ss)::value;
+        constexpr int KP = (MM::K(sidx) + CW - 1) / CW * CW;
+        const int kk = k0 + krot[sidx];
+        return kk >= KP ? kk - KP : kk;
+    };
     mfloatx4 wr[MM::NRW > 0 ? MM::NRW : 1];
     if constexpr (MM::NRW > 0) {
         step_static_for<0, MM::NCH>([&](auto cc) {
-            constexpr int c = decltype(cc)::value, sidx = MM::csrc(c), k0 = MM::ck0(c);
+            constexpr int c = decltype(cc)::value, sidx = MM::csrc(c);
+            const int k0 = rot(StepIntC<sidx>{}, MM::ck0(c));
             if constexpr (((MM::REGMASK >> sidx) & 1) != 0) {
                 step_static_for<0, MM::NTU>([&](auto tt) {
                     constexpr int nt = decltype(tt)::value;
@@ -1609,7 +1632,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 constexpr int i = decltype(ii)::value;
                 constexpr int sx = MM::csrc(i < NCH ? i : 0);
                 if (i == MM::CLATE) hold_off();
-                load_chunk(v[i], rs[sx], aoff[sx], MM::K(sx), MM::K(sx) % CW != 0, MM::ck0(i < NCH ? i : 0), i < NCH);
+                load_chunk(v[i], rs[sx], aoff[sx], MM::K(sx), MM::K(sx) % CW != 0, rot(StepIntC<sx>{}, MM::ck0(i < NCH ? i : 0)), i < NCH);
             });
 #pragma unroll
             for (int mt = 0; mt < MM::MT; ++mt)
@@ -1619,7 +1642,8 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             step_static_for<0, NCH>([&](auto cc) {
                 constexpr int c = decltype(cc)::value;
                 constexpr int i = c % D, j = (c + D - 1) % D, i1 = (c + 1) % D;
-                constexpr int sidx = MM::csrc(c), k0 = MM::ck0(c);
+                constexpr int sidx = MM::csrc(c);
+                const int k0 = rot(StepIntC<sidx>{}, MM::ck0(c));
                 constexpr int ca = c + D - 1 < NCH ? c + D - 1 : 0;      // the chunk D - 1 positions ahead, if any
                 constexpr int sa = MM::csrc(ca);
                 mfloatx4 opb[MM::NTU];
@@ -1634,7 +1658,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 if (c == 0) { RNNG_STAMP(2); }
                 if (c == 1) { RNNG_STAMP(6); RNNG_STAMP(7); }
                 if (c + D - 1 == MM::CLATE) hold_off();
-                if (c + D - 1 < NCH) load_chunk(v[j], rs[sa], aoff[sa], MM::K(sa), MM::K(sa) % CW != 0, MM::ck0(ca), true);
+                if (c + D - 1 < NCH) load_chunk(v[j], rs[sa], aoff[sa], MM::K(sa), MM::K(sa) % CW != 0, rot(StepIntC<sa>{}, MM::ck0(ca)), true);
                 bad = c + 1 < NCH ? incomplete(v[i1]) : false;
                 multiply(StepIntC<sidx>{}, v[i], opb);
             });
