@@ -449,7 +449,9 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
             }
             return (lay.src[s].k_len + CW - 1) / CW * tiles * 4;
         };
-        while (nch0 <= 64) {
+        int flat_max0 = 64;
+        if (const char* env = std::getenv("RNNG_MSTEP_FLAT_MAX")) flat_max0 = std::max(0, std::min(64, std::atoi(env)));
+        while (nch0 <= flat_max0) {
             int pick = -1;
             for (int s = 0; s < lay.n_sources; ++s)
                 if (!((reg_mask >> s) & 1) && (pick < 0 || words_of(s) > words_of(pick))) pick = s;
@@ -477,7 +479,9 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     // short chunk sequences are unrolled whole: the chunks in flight may then span several sources
     int nch = 0;
     for (int s = 0; s < ml.n_src; ++s) nch += (lay.src[s].k_len + CW - 1) / CW;
-    const bool flat = nch <= 64;
+    int flat_max = 64;
+    if (const char* env = std::getenv("RNNG_MSTEP_FLAT_MAX")) flat_max = std::max(0, std::min(64, std::atoi(env)));      // (tests: the grouped sequence on small shapes)
+    const bool flat = nch <= flat_max;
     // loads in flight per lane: about four with eight wavefronts (measured on two workloads: 4 / 8 / 12
     // in flight give 1.81 / 1.88 / 1.91 ms and 3.56 / 3.59 / 3.70 ms), a dozen with four
     const int inflight = NW == 8 ? 4 : 12;
