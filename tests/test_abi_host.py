@@ -178,7 +178,7 @@ def test_step_kernel_variants_compile(monkeypatch, early, window):
     assert g2.specialise(3) == 2
 
 
-@pytest.mark.parametrize("H,N", [(2048, 1), (4096, 1), (2048, 16), (4096, 64)])
+@pytest.mark.parametrize("H,N", [(2048, 1), (4096, 1), (2048, 64), (4096, 16), (4096, 64)])
 def test_wide_layers_get_a_streaming_step_kernel(H, N):
     """Section 4's second experiment (all layers 2,048 or 4,096 wide): the recurrent weights fit
     neither registers nor LDS, so both directions must be served by the streaming build (one
@@ -194,6 +194,18 @@ def test_wide_layers_get_a_streaming_step_kernel(H, N):
     assert n == 2
     # room for the transposed copy of the parameter buffer
     assert g.workspace_bytes(8, N) > 4 * g.param_count()
+
+
+def test_a_2048_wide_layer_at_16_streams_keeps_its_weights_on_chip():
+    """All layers 2,048 wide at 16 streams: 256 workgroups hold the 64 MiB of recurrent weights in
+    registers and LDS (256 KiB each), so no transposed copy of the parameters is needed."""
+    import workloads as wl
+    from paper_1503_02852_amd import binding
+    spec = wl.lstm_net(2048, [2048], 2048)
+    g = binding.Graph(spec.node_array(), spec.edge_array())
+    if g.specialise(16) == 0:
+        pytest.skip("run-time compiler not available")
+    assert g.workspace_bytes(8, 16) < 4 * g.param_count()
 
 
 def test_headers_are_plain_c(tmp_path):
