@@ -39,11 +39,20 @@ __device__ __forceinline__ void load_kc(float (&r)[8], const float* __restrict__
         }
     }
 }
+// A thread holds four consecutive k of one row; k rows lie 132 floats apart, so the four threads
+// that share a row index group would hit two banks twice if all stored their element e at once.
+// Instruction i stores element (e0 + i) % 4 with e0 = 0, 2, 2, 0 for tid % 4 = 0 .. 3: the 32 lanes
+// of a half-wavefront then fall into four disjoint windows of eight banks.
 __device__ __forceinline__ void store_kc(float* __restrict__ lds, const float (&r)[8], int tid) {
+    const int a = tid & 3, e0 = (a == 1 || a == 2) ? 2 : 0;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) lds[(4 * (tid & 3) + e) * STRIDE + (tid >> 2) + 64 * j] = r[4 * j + e];
+        for (int i = 0; i < 4; ++i) {
+            const int e = (e0 + i) & 3;
+            const float v = e == 0 ? r[4 * j] : e == 1 ? r[4 * j + 1] : e == 2 ? r[4 * j + 2] : r[4 * j + 3];
+            lds[(4 * a + e) * STRIDE + (tid >> 2) + 64 * j] = v;
+        }
 }
 
 // ---- M/N-contiguous source: element (k, c) at base[k * ld + c] ------------------------------
