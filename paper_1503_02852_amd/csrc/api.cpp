@@ -64,22 +64,26 @@ Layout make_layout(const Plan& P, int T, int N, int64_t partial_floats, bool tra
     L.buf_off.assign(P.n_bufs, -1);
     const int64_t F = (int64_t)(T + P.hist) * N;      // every frame tensor has P.hist history frames in front
     (void)K;
-    for (int b = 0; b < P.n_bufs; ++b) {
-        if (!P.buf_alloc[b]) continue;
-        if (P.buf_alloc[b] == 3 && !(N >= 16 && N % 16 == 0)) continue;      // tile-blocked twins: whole 16-stream tiles only
+    auto place = [&](int b) {
         const int64_t rows = P.buf_alloc[b] == 2 ? N : F;
         L.buf_off[b] = cur; cur = align_up(cur + rows * P.buf_dim[b] * 4, 256);
         // Tensors of the same shape would lie a power of two apart, so the lines that a step polls
         // in several tensors at the same frame would all fall on the same memory channel: skew them.
         cur += g_layout_skew * (1 + n_alloc % 13);
         ++n_alloc;
-    }
+    };
+    for (int b = 0; b < P.n_bufs; ++b)
+        if (P.buf_alloc[b] == 1 || P.buf_alloc[b] == 2) place(b);
     if (partial_floats > 0) { L.partial_off = cur; cur = align_up(cur + (int64_t)(T + P.hist) * partial_floats * 4, 256); }
     if (transposed_copy) { L.wt_off = cur; cur = align_up(cur + P.n_params * 4, 256); }
     // an input whose connections are delayed may be given as class indices: room for its indices with history frames
     L.idx_off.assign(P.xnodes.size(), -1);
     for (size_t k = 0; k < P.xnodes.size(); ++k)
         if (P.xnodes[k].kind == NODE_INPUT && P.input_delayed[k]) { L.idx_off[k] = cur; cur = align_up(cur + F * 4, 256); }
+    // tile-blocked twins (whole 16-stream tiles only), behind everything else
+    if (N >= 16 && N % 16 == 0)
+        for (int b = 0; b < P.n_bufs; ++b)
+            if (P.buf_alloc[b] == 3) place(b);
     L.total = cur;
     return L;
 }
