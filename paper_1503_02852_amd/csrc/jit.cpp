@@ -790,7 +790,7 @@ std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, i
 }
 
 // Streaming matrix-core variant for N >= 9 streams and layers whose weights do not fit on chip.
-std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed) {
+std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed, bool* blocked) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     if (phases.size() != 1 || N < 9 || G < 1 || G > 256) return "";
     if (P.n_params * 4 >= (int64_t(1) << 31)) return "";      // 32-bit byte offsets into the weight buffers
@@ -832,6 +832,12 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
     const int ACCS = NTU * 16 + 4;
     const size_t lds = (size_t)4 * MT * 16 * ACCS * 4;
     if (lds > STEP_LDS_LIMIT) return "";
+    // exchange through the tile-blocked twins: whole 16-stream tiles in the window and in every
+    // pass of the element-wise part, every exchanged tensor with a twin
+    bool xb = N % 16 == 0 && (IPT == 1 || SPP % 16 == 0) && P.twin_base >= 0 && !mstep_blocked_choices().empty() && mstep_blocked_choices()[0] != 0;
+    auto has_twin = [&](int b) { return b >= 0 && b < P.twin_base && P.buf_alloc[P.twin_base + b] == 3; };
+    for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) xb = xb && has_twin(b);
+    for (int sidx = 0; sidx < lay.n_sources; ++sidx) xb = xb && has_twin(lay.src[sidx].buf) && lay.src[sidx].k_len == P.buf_dim[lay.src[sidx].buf];
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
@@ -841,7 +847,8 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
         o << "            default: return " << dflt << ";\n        }\n    }\n";
     };
     o << "struct SM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << lay.n_sources << ", NTU = " << NTU << ", D = " << D
-      << ", CMAX = " << CMAX << ", ACCS = " << ACCS << ", TR = " << tr << ", IPT = " << IPT << ", SPP = " << SPP << ";\n";
+      << ", CMAX = " << CMAX << ", ACCS = " << ACCS << ", TR = " << tr << ", IPT = " << IPT << ", SPP = " << SPP << ";\n"
+      << "    static constexpr bool XB = " << (xb ? "true" : "false") << ";\n";
     std::vector<std::pair<int, int>> ks, used, ngr;
     for (int sidx = 0; sidx < lay.n_sources; ++sidx) {
         ks.push_back({sidx, lay.src[sidx].k_len});
@@ -866,6 +873,7 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
          "}\n";
     if (lds_bytes) *lds_bytes = lds;
     if (transposed) *transposed = tr != 0;
+    if (blocked) *blocked = xb;
     return o.str();
 }
 

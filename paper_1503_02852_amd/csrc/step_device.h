@@ -2450,14 +2450,32 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
                 }
             boff[sidx][nt] = off;
         }
+    // (SM::XB: the sources are the tile-blocked twins of the exchanged tensors, as in the variant with
+    // on-chip weights: a wavefront's load of a 16 x 16 tile is 1 KiB of consecutive addresses)
     int aoff[SM::NSRC][SM::MT];
 #pragma unroll
     for (int sidx = 0; sidx < SM::NSRC; ++sidx)
 #pragma unroll
         for (int mt = 0; mt < SM::MT; ++mt) {
             const int n = mt * 16 + (lane & 15);
-            aoff[sidx][mt] = n < N ? (n * SM::K(sidx) + wcol) * 4 : 0x7FFFFFF0;
+            if (SM::XB) aoff[sidx][mt] = ((mt * (SM::K(sidx) / 16) + wave) * 256 + lane * 4) * 4;
+            else aoff[sidx][mt] = n < N ? (n * SM::K(sidx) + wcol) * 4 : 0x7FFFFFF0;
         }
+    // the twin's element of this thread's item (pass 0) per exchanged store, frame 0
+    float* xptr[PH::NST > 0 ? PH::NST : 1];
+    if constexpr (SM::XB) {
+        cwords_t pw = (cwords_t)a.words + suni(ph.prog_off);
+        cwords_t st = pw + PG_HEADER_WORDS + PH::NG * GA_WORDS + PH::NI * IV_WORDS + pw[PG_NOPS] * MO_WORDS;
+#pragma unroll
+        for (int q = 0; q < PH::NST; ++q) {
+            xptr[q] = nullptr;
+            if (!PH::stshared(q) || r.sptr[q] == nullptr) continue;
+            const int dim = suni(st[q * ST_WORDS + ST_DIM]);
+            const int i = (int)(r.sptr[q] - r.sbase[q]) - r.n * dim;      // this thread's unit
+            xptr[q] = ((cbufs_t)a.buf_ptr)[a.twin_base + suni(st[q * ST_WORDS + ST_BUF])] +
+                      ((r.n >> 4) * (dim >> 4) + (i >> 4)) * 256 + ((((i & 15) >> 2) << 4) + (r.n & 15)) * 4 + (i & 3);
+        }
+    }
 
     bool dead = false;
     int pdelay = 0;
@@ -2477,7 +2495,7 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
             const StepSource& sc = sh.lay.src[sidx];
             const int frame = t + suni(sc.frame_off);
             const bool in_window = frame >= 0 && frame < T;
-            const float* g = ((cbufs_t)a.buf_ptr)[suni(sc.buf)] + (size_t)(in_window ? frame : 0) * N * SM::K(sidx);
+            const float* g = ((cbufs_t)a.buf_ptr)[(SM::XB ? a.twin_base : 0) + suni(sc.buf)] + (size_t)(in_window ? frame : 0) * N * SM::K(sidx);
             rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * SM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
         }
         muintx4 v[D][SM::MT];
@@ -2485,8 +2503,8 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
         auto load_a = [&](muintx4 (&dst)[SM::MT], const __amdgpu_buffer_rsrc_t& rsrc, const int (&base)[SM::MT], int K, bool k_ragged, int k0, bool on) {
 #pragma unroll
             for (int mt = 0; mt < SM::MT; ++mt) {
-                int off = base[mt] + k0 * 4;
-                if (k_ragged) off = k0 + wcol < K ? off : 0x7FFFFFF0;
+                int off = base[mt] + (SM::XB ? k0 * 64 : k0 * 4);
+                if (k_ragged) off = k0 + (SM::XB ? wave * 16 : wcol) < K ? off : 0x7FFFFFF0;
                 off = on ? off : 0x7FFFFFF0;
                 dst[mt] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, STEP_COHERENT_AUX);
             }
@@ -2645,7 +2663,11 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
             for (int q = 0; q < PH::NST; ++q) {
                 if (r.sptr[q] == nullptr) continue;
                 float* dst = r.sptr[q] + (long long)t * r.sstride[q] + (long long)p * spass[q];
-                if (PH::stshared(q)) store_shared(dst, s[PH::stslot(q)]);
+                if (PH::stshared(q) && SM::XB) {
+                    // (SPP streams further on = SPP / 16 stream tiles = the same distance as in the row-major tensor)
+                    store_plain(dst, s[PH::stslot(q)]);
+                    store_shared(xptr[q] + (long long)t * r.sstride[q] + (long long)p * spass[q], s[PH::stslot(q)]);
+                } else if (PH::stshared(q)) store_shared(dst, s[PH::stslot(q)]);
                 else store_plain(dst, s[PH::stslot(q)]);
             }
 #pragma unroll
