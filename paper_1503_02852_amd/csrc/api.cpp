@@ -200,10 +200,10 @@ struct rnn_graph {
             for (int G : {256, 128, 64, 32}) {
                 if (force_step_G > 0 && G != force_step_G) continue;
                 if (G > max_workgroups()) continue;
-                size_t lds = 0; bool tr = false, xb = false;
-                std::string src = N <= 8 ? jit_sstep_source(plan, cp, backward, N, G, &lds, &tr) : jit_smstep_source(plan, cp, backward, N, G, &lds, &tr, &xb);
+                size_t lds = 0; bool tr = false, xb = false; int threads = 256;
+                std::string src = N <= 8 ? jit_sstep_source(plan, cp, backward, N, G, &lds, &tr) : jit_smstep_source(plan, cp, backward, N, G, &lds, &tr, &xb, &threads);
                 if (src.empty()) continue;
-                c.source = src; c.stream = true; c.needs_t = tr; c.blocked = xb;
+                c.source = src; c.stream = true; c.needs_t = tr; c.blocked = xb; c.lp.threads = threads;
                 c.lp.ok = true; c.lp.G = G; c.lp.NB = 1; c.lp.lds_bytes = lds; c.lp.xcd_stride = 1;
                 break;
             }

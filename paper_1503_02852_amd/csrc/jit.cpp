@@ -790,7 +790,8 @@ std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, i
 }
 
 // Streaming matrix-core variant for N >= 9 streams and layers whose weights do not fit on chip.
-std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed, bool* blocked) {
+std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed, bool* blocked,
+                              int* threads) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     if (phases.size() != 1 || N < 9 || G < 1 || G > 256) return "";
     if (P.n_params * 4 >= (int64_t(1) << 31)) return "";      // 32-bit byte offsets into the weight buffers
@@ -821,16 +822,24 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
     if (tr < 0) return "";
     int kmax = 0;
     for (int sidx = 0; sidx < lay.n_sources; ++sidx) kmax = std::max(kmax, lay.src[sidx].k_len);
-    // D register sets, D - 1 chunks of (MT + NTU) 128-bit loads per lane in flight: about 40
-    const int dmax = std::max(2, std::min({8, 40 / (MT + NTU) + 1, (kmax + 63) / 64 + 1}));
+    // Eight wavefronts (256 registers per lane) where the operand sets and accumulators fit, else
+    // four; RNNG_SMSTEP_WAVES = 4 / 8 allows only that count.  D register sets, D - 1 chunks of
+    // (MT + NTU) 128-bit loads per lane in flight: about 40 with four wavefronts, 20 with eight.
+    int NW = 8;
+    if (const char* env = std::getenv("RNNG_SMSTEP_WAVES")) NW = std::atoi(env) == 4 ? 4 : 8;
+    // (several element-wise passes keep their carried values and early-loaded inputs per pass in
+    // registers: with them, eight wavefronts spill)
+    if (NW == 8 && (IPT > 1 || 4 * (MT * NTU + 2 * (MT + NTU)) > 160)) NW = 4;
+    const int CW = 16 * NW, inflight = NW == 8 ? 20 : 40;
+    const int dmax = std::max(2, std::min({8, inflight / (MT + NTU) + 1, (kmax + CW - 1) / CW + 1}));
     int D = dmax, best_slots = 1 << 30;
     for (int d = dmax; d >= std::max(2, dmax - 2); --d) {
         int slots = 0;
-        for (int sidx = 0; sidx < lay.n_sources; ++sidx) slots += ((lay.src[sidx].k_len + 63) / 64 + d - 1) / d * d;
+        for (int sidx = 0; sidx < lay.n_sources; ++sidx) slots += ((lay.src[sidx].k_len + CW - 1) / CW + d - 1) / d * d;
         if (slots < best_slots) { best_slots = slots; D = d; }
     }
     const int ACCS = NTU * 16 + 4;
-    const size_t lds = (size_t)4 * MT * 16 * ACCS * 4;
+    const size_t lds = (size_t)NW * MT * 16 * ACCS * 4;
     if (lds > STEP_LDS_LIMIT) return "";
     // exchange through the tile-blocked twins: whole 16-stream tiles in the window and in every
     // pass of the element-wise part, every exchanged tensor with a twin
@@ -847,7 +856,7 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
         o << "            default: return " << dflt << ";\n        }\n    }\n";
     };
     o << "struct SM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << lay.n_sources << ", NTU = " << NTU << ", D = " << D
-      << ", CMAX = " << CMAX << ", ACCS = " << ACCS << ", TR = " << tr << ", IPT = " << IPT << ", SPP = " << SPP << ";\n"
+      << ", CMAX = " << CMAX << ", ACCS = " << ACCS << ", TR = " << tr << ", IPT = " << IPT << ", SPP = " << SPP << ", NW = " << NW << ";\n"
       << "    static constexpr bool XB = " << (xb ? "true" : "false") << ";\n";
     std::vector<std::pair<int, int>> ks, used, ngr;
     for (int sidx = 0; sidx < lay.n_sources; ++sidx) {
@@ -860,12 +869,12 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
             }
             if (any) used.push_back({sidx * 16 + nt, 1});
         }
-        ngr.push_back({sidx, ((lay.src[sidx].k_len + 63) / 64 + D - 1) / D});
+        ngr.push_back({sidx, ((lay.src[sidx].k_len + CW - 1) / CW + D - 1) / D});
     }
     emit_switch("K", "s", ks, 0); emit_switch("edge_", "key", edge_of, -1); emit_switch("used_", "key", used, 0); emit_switch("ngr", "s", ngr, 0);
     o << "    static __device__ __forceinline__ constexpr int edge(int s, int task) { return edge_(s * " << STEP_MAX_TASKS << " + task); }\n";
     o << "    static __device__ __forceinline__ constexpr bool used(int s, int nt) { return used_(s * 16 + nt) != 0; }\n};\n";
-    o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
+    o << mstep_kernel_attributes(NW) <<
          "void rnng_step_jit(StepArgs a) {\n"
          "    extern __shared__ __attribute__((aligned(16))) float lds[];\n"
          "    __shared__ SShared ms;\n"
@@ -874,6 +883,7 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
     if (lds_bytes) *lds_bytes = lds;
     if (transposed) *transposed = tr != 0;
     if (blocked) *blocked = xb;
+    if (threads) *threads = 64 * NW;
     return o.str();
 }
 

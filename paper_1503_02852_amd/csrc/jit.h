@@ -37,7 +37,8 @@ std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool back
 // keep on chip): G unit chunks.  *transposed: the kernel reads transposed copies of some matrices.
 std::string jit_sstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed);
 // The same for N >= 9 streams on the matrix cores.
-std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed, bool* blocked = nullptr);
+std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, size_t* lds_bytes, bool* transposed, bool* blocked = nullptr,
+                              int* threads = nullptr);
 // Compiles (or finds in the process-wide cache) the source; false if hiprtc is missing or the
 // compile fails (the log, if any, goes to *log).  Needs no GPU.
 bool jit_compile(const std::string& source, std::string* log);

@@ -2386,7 +2386,7 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
 // =============================================================================================
 // Streaming matrix-core variant (run-time specialised, single-phase components, many streams, wide
 // layers): the matrix-core variant above with the weights read from memory every step instead of
-// kept in LDS.  Lane (c, q) of a wavefront loads, per 64-column chunk and 16-row tile, the four
+// kept in LDS.  Lane (c, q) of a wavefront loads, per chunk (16 columns per wavefront) and 16-row tile, the four
 // weights W[row c][k0 + 16 wave + 4 q ...] with one 128-bit load (B operands) next to the polling
 // load of the four source values of stream c (A operands); D register sets hold the operands of D
 // chunks, so that (MT + NTU) * (D - 1) loads per lane are in flight.  The weight loads of a step's
@@ -2395,8 +2395,9 @@ __device__ __forceinline__ void sstep_kernel_body(const StepArgs& a, SShared& ms
 // passes of SPP streams each (the accumulator tiles hold all streams).
 //
 // SM is a generated descriptor:
-//   static constexpr int NJ (streams), MT, NSRC, NTU, D, CMAX, ACCS, TR (1: the matrices are read
-//   from the transposed copy), IPT, SPP; constexpr K(s), ngr(s), edge(s, task) (edge of the task
+//   static constexpr int NJ (streams), MT, NSRC, NTU, D, CMAX, ACCS, NW (wavefronts: 8, or 4 where the
+//   operand registers of 8 do not fit), TR (1: the matrices are read from the transposed copy), IPT,
+//   SPP, XB (exchange through the tile-blocked twins); constexpr K(s), ngr(s), edge(s, task) (edge of the task
 //   that reads source s, -1: none), used(s, nt).
 // =============================================================================================
 template <class PH, class SM>
@@ -2405,21 +2406,21 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = a.T, N = a.N;
     StepShared& sh = ms.sh;
-    constexpr int IPT = SM::IPT, SPP = SM::SPP;
+    constexpr int IPT = SM::IPT, SPP = SM::SPP, NW = SM::NW, NTHR = 64 * NW, CW = 16 * NW;      // wavefronts, threads, columns of a chunk
     if (tid == 0) compute_step_layout(a.words, a.desc_off, a.G, 1, SPP < SM::NJ ? SPP : SM::NJ, sh.lay);
     __syncthreads();
     const StepPhase& ph = sh.lay.ph[0];
-    {
+    if (tid < STEP_THREADS) {      // the element-wise items sit on the first STEP_THREADS threads
         const int ic = ph.item_chunk;
         const int il = tid % ic, n = tid / ic;
         sh.iteminfo[0][tid] = (unsigned)il | ((unsigned)(n < N && n < SPP ? n : 0xFFFF) << 16);
     }
     constexpr int CMAX = SM::CMAX, D = SM::D, NPAD = SM::MT * 16, ACCS = SM::ACCS;
-    for (int i = tid; i < 4 * NPAD * ACCS; i += STEP_THREADS) lds[i] = 0.0f;
+    for (int i = tid; i < NW * NPAD * ACCS; i += NTHR) lds[i] = 0.0f;
     __syncthreads();
     PhaseRegs<PH> r;
     phase_setup<PH, 1, 2>(r, a, sh, lds, w, tid);
-    const int item_il = (int)(sh.iteminfo[0][tid] & 0xFFFF);
+    const int item_il = tid < STEP_THREADS ? (int)(sh.iteminfo[0][tid] & 0xFFFF) : 0;
     const int item_n = tid / suni(ph.item_chunk);
     // floats between the same item of consecutive passes, per gather / store (SPP streams further on)
     int gpass[PH::NG > 0 ? PH::NG : 1], spass[PH::NST > 0 ? PH::NST : 1];
@@ -2532,13 +2533,13 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
         // the weights of the first chunks do not wait for the exchange
         step_static_for<0, D - 1>([&](auto ii) {
             constexpr int i = decltype(ii)::value;
-            load_b(wb[i], boff[0], SM::K(0), SM::K(0) % 64 != 0, i * 64, i * 64 < (SM::K(0) + 63) / 64 * 64);
+            load_b(wb[i], boff[0], SM::K(0), SM::K(0) % CW != 0, i * CW, i * CW < (SM::K(0) + CW - 1) / CW * CW);
         });
         for (int i = 0; i < pdelay; ++i) __builtin_amdgcn_s_sleep(1);
         bool retried = false;
         step_static_for<0, D - 1>([&](auto ii) {
             constexpr int i = decltype(ii)::value;
-            load_a(v[i], rs[0], aoff[0], SM::K(0), SM::K(0) % 64 != 0, i * 64, i * 64 < (SM::K(0) + 63) / 64 * 64);
+            load_a(v[i], rs[0], aoff[0], SM::K(0), SM::K(0) % CW != 0, i * CW, i * CW < (SM::K(0) + CW - 1) / CW * CW);
         });
         mfloatx4 acc[SM::MT][SM::NTU];
 #pragma unroll
@@ -2550,27 +2551,27 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
         step_static_for<0, SM::NSRC>([&](auto ss) {
             constexpr int sidx = decltype(ss)::value;
             constexpr int NGR = SM::ngr(sidx);
-            constexpr int KP = (SM::K(sidx) + 63) / 64 * 64;
+            constexpr int KP = (SM::K(sidx) + CW - 1) / CW * CW;
             constexpr int snext = sidx + 1 < SM::NSRC ? sidx + 1 : sidx;
-            constexpr int KPN = (SM::K(snext) + 63) / 64 * 64;
+            constexpr int KPN = (SM::K(snext) + CW - 1) / CW * CW;
 #pragma unroll 1
             for (int g = 0; g < NGR; ++g) {
                 step_static_for<0, D>([&](auto ii) {
                     constexpr int i = decltype(ii)::value;
                     constexpr int j = (i + D - 1) % D;
                     constexpr int i1 = (i + 1) % D;
-                    const int k0 = (g * D + i) * 64;
+                    const int k0 = (g * D + i) * CW;
                     const int gj = i == 0 ? g : g + 1;
                     const bool same = gj < NGR;
-                    const int kj = same ? (gj * D + j) * 64 : j * 64;
+                    const int kj = same ? (gj * D + j) * CW : j * CW;
                     const bool on = same ? kj < KP : (sidx + 1 < SM::NSRC && kj < KPN);
                     auto ahead = [&]() {
                         if (same) {
-                            load_b(wb[j], boff[sidx], SM::K(sidx), SM::K(sidx) % 64 != 0, kj, on);
-                            load_a(v[j], rs[sidx], aoff[sidx], SM::K(sidx), SM::K(sidx) % 64 != 0, kj, on);
+                            load_b(wb[j], boff[sidx], SM::K(sidx), SM::K(sidx) % CW != 0, kj, on);
+                            load_a(v[j], rs[sidx], aoff[sidx], SM::K(sidx), SM::K(sidx) % CW != 0, kj, on);
                         } else {
-                            load_b(wb[j], boff[snext], SM::K(snext), SM::K(snext) % 64 != 0, kj, on);
-                            load_a(v[j], rs[snext], aoff[snext], SM::K(snext), SM::K(snext) % 64 != 0, kj, on);
+                            load_b(wb[j], boff[snext], SM::K(snext), SM::K(snext) % CW != 0, kj, on);
+                            load_a(v[j], rs[snext], aoff[snext], SM::K(snext), SM::K(snext) % CW != 0, kj, on);
                         }
                     };
                     if (k0 < KP) {
@@ -2582,7 +2583,7 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
                                 if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
                                 __builtin_amdgcn_s_sleep(MSTEP_RETRY_SLEEP);
                                 step_compiler_barrier();
-                                load_a(again, rs[sidx], aoff[sidx], SM::K(sidx), SM::K(sidx) % 64 != 0, k0, true);
+                                load_a(again, rs[sidx], aoff[sidx], SM::K(sidx), SM::K(sidx) % CW != 0, k0, true);
                                 if (!incomplete(again)) break;
                             }
 #pragma unroll
@@ -2640,6 +2641,8 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
                     if (r.gptr[g] != nullptr) {
                         const int tb = pn * ACCS + PH::gaux(g) * CMAX + item_il;
                         x = (lds[tb] + lds[tb + NPAD * ACCS]) + (lds[tb + 2 * NPAD * ACCS] + lds[tb + 3 * NPAD * ACCS]);
+                        if constexpr (NW == 8)
+                            x += (lds[tb + 4 * NPAD * ACCS] + lds[tb + 5 * NPAD * ACCS]) + (lds[tb + 6 * NPAD * ACCS] + lds[tb + 7 * NPAD * ACCS]);
                     }
                     s[g] = x;
                 } else if (PH::gkind(g) == GA_KIND_CARRY && step > 0) {
