@@ -827,9 +827,7 @@ std::string jit_smstep_source(const Plan& P, const CompPlan& cp, bool backward, 
     // (MT + NTU) 128-bit loads per lane in flight: about 40 with four wavefronts, 20 with eight.
     int NW = 8;
     if (const char* env = std::getenv("RNNG_SMSTEP_WAVES")) NW = std::atoi(env) == 4 ? 4 : 8;
-    // (several element-wise passes keep their carried values and early-loaded inputs per pass in
-    // registers: with them, eight wavefronts spill)
-    if (NW == 8 && (IPT > 1 || 4 * (MT * NTU + 2 * (MT + NTU)) > 160)) NW = 4;
+    if (NW == 8 && 4 * (MT * NTU + 2 * (MT + NTU)) > 160) NW = 4;
     const int CW = 16 * NW, inflight = NW == 8 ? 20 : 40;
     const int dmax = std::max(2, std::min({8, inflight / (MT + NTU) + 1, (kmax + CW - 1) / CW + 1}));
     int D = dmax, best_slots = 1 << 30;

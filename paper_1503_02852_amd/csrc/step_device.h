@@ -2629,7 +2629,8 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
         else if ((step & 63) == 63 && pdelay > 0) --pdelay;
         RNNG_STAMP(4);
         // ---- element-wise program: IPT passes, one thread per (stream, unit) in each ----
-#pragma unroll
+        // (not unrolled: interleaved passes would keep several slot files in registers)
+#pragma unroll 1
         for (int p = 0; p < IPT; ++p) {
             const int pn = item_n + p * SPP;      // the pass's stream
             if (r.n < 0 || pn >= N) continue;
@@ -2645,16 +2646,19 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
                             x += (lds[tb + 4 * NPAD * ACCS] + lds[tb + 5 * NPAD * ACCS]) + (lds[tb + 6 * NPAD * ACCS] + lds[tb + 7 * NPAD * ACCS]);
                     }
                     s[g] = x;
-                } else if (PH::gkind(g) == GA_KIND_CARRY && step > 0) {
+                } else if (PH::gkind(g) == GA_KIND_CARRY && step > 0 && IPT == 1) {
                     s[g] = carry[p][PH::cidx(g)];
-                } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0) {
+                } else if (PH::gkind(g) == GA_KIND_STATIC && step > 0 && IPT == 1) {
                     s[g] = sn[p][g];
                 } else {
+                    // (with several passes a step is long, and values kept per pass would cost the
+                    // registers that eight wavefronts need: everything is loaded where it is used,
+                    // also what the thread itself stored in the step before)
                     const int frame = t + r.goff[g];
                     float x = 0.0f;
                     if (r.gptr[g] != nullptr && frame >= 0 && frame < T) {
                         const float* src = r.gptr[g] + (long long)frame * r.gstride[g] + (long long)p * gpass[g];
-                        x = PH::gkind(g) == GA_KIND_FRAMES ? load_coherent(src) : *src;
+                        x = PH::gkind(g) == GA_KIND_STATIC ? *src : load_coherent(src);
                     }
                     s[g] = x;
                 }
@@ -2675,9 +2679,9 @@ __device__ __forceinline__ void smstep_kernel_body(const StepArgs& a, SShared& m
             }
 #pragma unroll
             for (int g = 0; g < PH::NG; ++g)
-                if (PH::gkind(g) == GA_KIND_CARRY) carry[p][PH::cidx(g)] = s[PH::gaux(g)];
+                if (PH::gkind(g) == GA_KIND_CARRY && IPT == 1) carry[p][PH::cidx(g)] = s[PH::gaux(g)];
             // STATIC inputs of the next step
-            if (step + 1 < nsteps) {
+            if (step + 1 < nsteps && IPT == 1) {
                 const int t2 = a.backward ? t - 1 : t + 1;
 #pragma unroll
                 for (int g = 0; g < PH::NG; ++g)
