@@ -1256,26 +1256,32 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 //
 // With N >= 9 streams a step's full connections are skinny GEMMs: acc[n][row] = sum_s sum_k
 // x_s[n][k] * W_s[row][k] over the shared source tensors x_s [N][K_s], row = task * cmax + local
-// unit.  Each workgroup owns a chunk of every layer's units and keeps its weight rows resident in
+// unit.  Each workgroup owns a chunk of every layer's units and keeps its weight rows on chip: in
 // LDS (per source one block of cmax rows for every task the source feeds; a task the source does
-// not feed reads a shared row of zeros).  Per step every wavefront polls its own quarter of each
-// source's columns (sentinel protocol) with 128-bit coherent loads that ARE the A operands of
+// not feed reads a shared row of zeros), and whole sources that do not fit there in vector
+// registers (MM::REGMASK).  Per step every wavefront polls its own share of each source's columns
+// (sentinel protocol) with 128-bit coherent loads that ARE the A operands of
 // v_mfma_f32_16x16x4_f32: lane (m, q) of a wavefront loads x[16 mt + m][c + 4 q .. c + 4 q + 3]
 // and feeds word j of it to the j-th of four multiply steps, whose B operand is word j of the
-// 128-bit LDS read W[row][c + 4 q ..] (the order in which a dot product's columns are summed is
+// 128-bit read W[row][c + 4 q ..] (the order in which a dot product's columns are summed is
 // free).  Nothing of x passes through LDS and the wavefronts do not wait for each other inside a
-// step's contraction: D chunks of 16 * NW columns (16 per wavefront; NW = 4 or 8 wavefronts: what a
+// step's contraction: chunks of 16 * NW columns (16 per wavefront; NW = 4 or 8 wavefronts: what a
 // workgroup can poll per microsecond grows with the wavefronts that have loads in flight, measured
-// 43 / 79 / 94 GB/s with 4 / 8 / 16) are in flight in registers, and a
-// chunk that comes back with a sentinel is loaded again by the wavefront that needs it.  One
-// accumulator set serves all sources; the four partial tiles meet in LDS, where the element-wise
-// program runs with one thread per (stream, unit).
+// 43 / 79 / 94 GB/s with 4 / 8 / 16) are in flight in D register sets, and a chunk that comes back
+// with a sentinel is loaded again by the wavefront that needs it.  With MM::XB the sources are
+// the tile-blocked twins of the exchanged tensors (a wavefront's load is 1 KiB of consecutive
+// addresses: 77 instead of 35 GB/s per workgroup).  One accumulator set serves all sources; the
+// NW partial tiles meet in LDS, where the element-wise program runs with one thread per
+// (stream, unit) on the first STEP_THREADS threads.
 //
 // MM is a generated descriptor:
 //   static constexpr int NJ (streams per workgroup), MT (16-stream tiles), NSRC, NTU (16-row
-//   tiles), D (chunks in flight), CMAX, ACCS (row stride of an accumulator tile), NW (wavefronts);
-//   constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task) (row block of the task
-//   in source s, -1: none), used(s, nt).
+//   tiles), D (register sets of chunks), CMAX, ACCS (row stride of an accumulator tile), NW
+//   (wavefronts), NCH (chunks of all sources), CLATE (first chunk that holds the previous step's
+//   own values), NRW (weight quads in registers); bool FLAT (the chunk sequence is unrolled whole),
+//   XB; unsigned REGMASK; constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task)
+//   (row block of the task in source s, -1: none), used(s, nt), csrc(c) / ck0(c) (source and first
+//   column of chunk c), widx(c * 16 + nt) (register index of a weight quad).
 // =============================================================================================
 
 #if !defined(MSTEP_POLL_INC)
