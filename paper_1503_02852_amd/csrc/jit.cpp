@@ -184,8 +184,8 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     std::vector<int> F(lay.n_sources), xoff(lay.n_sources);
     int XF = 0;
     for (int s = 0; s < lay.n_sources; ++s) { F[s] = (lay.src[s].k_len + 63) / 64; xoff[s] = XF; XF += F[s]; }
-    if (XF * NB > 96) return false;
-    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 16) return false;
+    if (XF * NB > 128) return false;
+    for (int s = 0; s < lay.n_sources; ++s) if (F[s] > 32) return false;
     int per_unit = 0;
     for (int t = 0; t < ph.n_tasks; ++t) for (int e = 0; e < ph.task[t].n_edges; ++e) per_unit += F[ph.task[t].e[e].src];
     const int RW = UW * per_unit;
@@ -219,7 +219,7 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
         }
         sreg[s] = r; sb[s] = B; sj[s] = j;
     }
-    for (const Region& rg : regs) if (NB * rg.rk > ((rg.rk & 1) ? 2048 : 4096)) return false;
+    for (const Region& rg : regs) if (NB * rg.rk > ((rg.rk & 1) ? 4096 : 8192)) return false;
     // bundle stores: stores of this program into bundle members
     const int32_t* pw0 = P.words.data() + phases[0].prog_off;
     const int32_t* st0 = pw0 + PG_HEADER_WORDS + pw0[PG_NGATHER] * GA_WORDS + pw0[PG_NINV] * IV_WORDS + pw0[PG_NOPS] * MO_WORDS;

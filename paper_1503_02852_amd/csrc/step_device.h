@@ -562,7 +562,7 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
 }
 
 constexpr int WAVE_RING_STEPS = 16;
-constexpr int WAVE_FMAX = 16;   // elements of one contraction per lane (K <= 1024)
+constexpr int WAVE_FMAX = 32;   // elements of one contraction per lane (K <= 2048)
 
 template <class MV>
 struct WaveRegs {
@@ -828,7 +828,7 @@ struct GroupX {
 #if !defined(WAVE_RETRY_SLEEP)
 #define WAVE_RETRY_SLEEP 0      // units of 64 clocks between polling attempts
 #endif
-constexpr int GROUP_MAX_LOADS = 8;   // per thread and region (N * K <= 2048 elements when K is odd, 4096 when even)
+constexpr int GROUP_MAX_LOADS = 16;  // per thread and region (N * K <= 4096 elements when K is odd, 8192 when even)
 
 constexpr unsigned WAVE_POLL_OUTSIDE = 0x40000000u;
 

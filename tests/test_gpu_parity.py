@@ -468,12 +468,32 @@ def test_squared_error_many_streams_full_width_frame():
                                    (4096, 1, 5), (4096, 16, 3), (4096, 64, 3)])
 def test_fig4_shapes_short_window(H, N, T):
     """Full widths and stream counts over a short window (the full windows have 2,048 / N frames).
-    From 2,048 units on a layer's recurrent weights no longer fit on chip: the step kernel streams
-    them from memory every step."""
+    At 2,048 units and one stream (or 16) a layer's recurrent weights still fit on chip, 256 KiB
+    per workgroup; at 64 streams, and from 4,096 units on, the step kernel streams them from memory
+    every step."""
     w = wl.make_config(f"fig4_h{H}_n{N}", T=T)
     win, _ = run_both(w, check_all_nodes=True, label=f"fig4_h{H}_n{N}_T{T}")
     print(f"[parity] fig4_h{H}_n{N}: forward build {win.g.step_build(w.spec.node_by_name('L1.h'))}, "
           f"backward build {win.g.step_build(w.spec.node_by_name('L1.h'), True)}", flush=True)
+
+
+LONG_ROW_NETS = {
+    "lstm_1280_n1": (lambda: wl.lstm_net(20, [1280], 8), 7, 1),       # 20 elements per lane, bundled gate deltas of 5,120 words
+    "lstm_2048_n2": (lambda: wl.lstm_net(12, [2048], 8), 5, 2),       # forward in registers at 2 streams, backward streamed
+    "elman_1800_n3": (lambda: wl.elman_net(9, 1800, 6), 8, 3),        # 29 elements per lane (ragged: 1,800 = 62 * 29 + 2)
+    "elman_1999_n1": (lambda: wl.elman_net(9, 1999, 6), 8, 1),        # odd width: polled word by word
+}
+
+
+@pytest.mark.parametrize("name", sorted(LONG_ROW_NETS))
+def test_register_build_with_long_weight_rows(name):
+    """The weights-in-registers build with rows of 1,025 to 2,048 elements (17 to 32 per lane),
+    at widths that are no multiple of 64, odd, and at more than one stream."""
+    make, T, N = LONG_ROW_NETS[name]
+    w = wl.make_workload(name, make(), T=T, N=N, seed=77, scale=0.04, bias_scale=0.3, masked_fraction=0.1)
+    win, ref = run_both(w, label=f"long rows, {name}")
+    rec = [k for k in range(len(w.spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, False)[0] == "wave" for k in rec)
 
 
 # ---- the streaming step kernel (weights read from memory every step) on small and ragged shapes ----
