@@ -15,6 +15,8 @@ Readings where the paper is silent (all listed in the design notes of the reposi
   * a third weight kind "diagonal" besides "full" and "identity" (needed for peepholes);
   * y_k = f_k(s_k) is applied to multiplicative nodes too (Section 2.2's delta equation
     uses f_k' for any layer);
+  * the activation functions f_k (Section 2.1 leaves them open): linear, logistic sigmoid, tanh,
+    and the rectifier max(0, s), whose derivative at s = 0 is taken as 0;
   * a fresh window starts from zero activations (frame index <= 0); a window that carries
     state (BPTT(h; h') of Section 3.2) starts from the activations the earlier frames left,
     and its backward pass follows the last two equations of Section 2.2 literally: delta and
@@ -31,7 +33,7 @@ Readings where the paper is silent (all listed in the design notes of the reposi
     eps = -dE/dz is exactly that).
 
 Parity pins (tests/, `-m "not gpu"`): a separately written textbook peephole LSTM and
-Elman net with hand-derived full BPTT, central finite differences of E_total,
+Elman net (tanh and rectifier) with hand-derived full BPTT, central finite differences of E_total,
 stream-independence, delay-line, unreachable-node and relabelling invariants; forward with a
 carried history against one forward pass over the whole sequence; bptt_window against bptt itself
 (whole sequence), against central finite differences of the window's error with the pre-window
@@ -45,7 +47,7 @@ import numpy as np
 
 INPUT, ADD, MUL = 0, 1, 2
 CROSS_ENTROPY, SQUARED_ERROR = 1, 2          # values of a node's is_output
-LINEAR, SIGMOID, TANH, SOFTMAX = 0, 1, 2, 3
+LINEAR, SIGMOID, TANH, SOFTMAX, RELU = 0, 1, 2, 3, 4
 FULL, DIAG, IDENTITY = 0, 1, 2
 
 
@@ -100,6 +102,8 @@ def _activation(act, s):
         return 1.0 / (1.0 + np.exp(-s))
     if act == TANH:
         return np.tanh(s)
+    if act == RELU:
+        return np.maximum(s, 0.0)
     if act == SOFTMAX:
         m = s.max(axis=-1, keepdims=True)
         ex = np.exp(s - m)
@@ -114,6 +118,8 @@ def _activation_derivative(act, y):
         return y * (1.0 - y)
     if act == TANH:
         return 1.0 - y * y
+    if act == RELU:
+        return (y > 0.0).astype(y.dtype)
     raise ValueError(act)
 
 

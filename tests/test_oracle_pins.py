@@ -598,3 +598,69 @@ def test_squared_error_lstm_finite_differences_and_truncated_window():
     w = wl.make_workload("lstm_sq", spec, T=8, N=2, seed=44, scale=0.8, bias_scale=0.5, masked_fraction=0.2)
     check_finite_differences(w, n_probe=3)
     check_truncated_gradient_by_finite_differences(w, t_first=3, n_probe=3)
+
+
+# ---- the rectifier as an activation function f_k (Section 2.1 leaves f_k open; Section 2.2 needs f_k') ----
+
+def test_rectifier_layer_closed_form():
+    """One hidden layer y = max(0, W x + b) under a linear squared-error read-out with fixed
+    numbers: values, the zero derivative of the units that are off (and of a unit exactly at 0),
+    and the weight gradient, all written out by hand."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 2, name="x")
+    h = g.add_node(wl.ADD, wl.RELU, 3, has_bias=True, name="h")
+    out = g.add_node(wl.ADD, wl.LINEAR, 1, is_output=wl.SQUARED_ERROR, name="out")
+    e_xh = g.add_edge(x, h, wl.FULL, 0)
+    e_ho = g.add_edge(h, out, wl.FULL, 0)
+    W = np.array([[1.0, -1.0], [0.5, 0.5], [2.0, 1.0]])
+    b = np.array([0.0, -2.0, -5.0])
+    V = np.array([[1.0, 2.0, 3.0]])
+    weights = [None, None]; weights[e_xh] = W; weights[e_ho] = V
+    biases = [None, b, None]
+    X = np.array([[[3.0, 1.0]], [[1.0, 3.0]]])          # T = 2, N = 1
+    D = np.array([[[1.0]], [[0.5]]])
+    # frame 0: s = (2, 0, 2): unit 1 sits exactly at 0; frame 1: s = (-2, 0, 0)
+    r = go.forward_bptt(g.nodes, g.edges, weights, biases, {x: X}, {out: D}, 2, 1)
+    np.testing.assert_array_equal(r["y"][h], np.array([[[2.0, 0.0, 2.0]], [[0.0, 0.0, 0.0]]]))
+    np.testing.assert_array_equal(r["y"][out], np.array([[[8.0]], [[0.0]]]))
+    assert r["loss"] == pytest.approx(0.5 * (7.0 ** 2 + 0.5 ** 2))
+    # dE/ds_h = (y - d) V f'(s): frame 0 -> 7 * (1, 0, 3), frame 1 -> all units off
+    np.testing.assert_allclose(r["grad_b"][h], np.array([7.0, 0.0, 21.0]))
+    np.testing.assert_allclose(r["grad_w"][e_xh], np.outer([7.0, 0.0, 21.0], [3.0, 1.0]))
+    np.testing.assert_allclose(r["grad_w"][e_ho], np.array([[7.0 * 2.0, 0.0, 7.0 * 2.0]]))
+
+
+def test_textbook_rectifier_elman_equivalence():
+    """A singleton with a delay-1 full self-loop and the rectifier == a textbook Elman net with
+    rectified hidden units, values and full BPTT gradients."""
+    T, N = 12, 2
+    spec = wl.elman_net(5, 7, 4, act=wl.RELU)
+    w = wl.make_workload("elman_relu", spec, T, N, seed=6, scale=0.5, bias_scale=0.4, masked_fraction=0.15)
+    r = run_oracle(w)
+    x, h, out = 0, 1, 2
+    assert (r["y"][h] == 0).any() and (r["y"][h] > 0).any()
+    tot = 0.0; G = None
+    for n in range(N):
+        loss, probs, g, hh = tb.elman_loss_and_grads(w.weights[0], w.weights[1], w.biases[h], w.weights[2],
+                                                     w.biases[out], w.inputs[x][:, n], w.targets[out][:, n], rectifier=True)
+        tot += loss
+        assert relerr(r["y"][out][:, n], probs) < 1e-12
+        assert relerr(r["y"][h][:, n], hh) < 1e-12
+        G = g if G is None else {k: G[k] + g[k] for k in g}
+    assert abs(r["loss"] - tot) < 1e-11 * max(1.0, abs(tot))
+    for m, name in ((0, "Wx"), (1, "Wh"), (2, "Wy")):
+        assert relerr(r["grad_w"][m], G[name]) < 1e-11
+    assert relerr(r["grad_b"][h], G["bh"]) < 1e-11
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_finite_differences_random_graphs_with_rectifiers(seed):
+    """Random recurrent graphs whose inner nodes (additive and multiplicative) draw from linear /
+    sigmoid / tanh / rectifier: every gradient against central differences (the probes' steps of
+    1e-5 stay clear of the kinks for these seeds), forward + BPTT and a carried window."""
+    rng = np.random.default_rng(900 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, acts=(wl.LINEAR, wl.SIGMOID, wl.TANH, wl.RELU, wl.RELU))
+    assert any(n["act"] == wl.RELU for n in spec.nodes)
+    w = wl.make_workload("rand_relu", spec, T=6, N=2, seed=seed, scale=0.8, bias_scale=0.5, masked_fraction=0.2 if seed % 2 else 0.0)
+    check_finite_differences(w, n_probe=4, seed=seed)
+    check_truncated_gradient_by_finite_differences(w, t_first=2, n_probe=3)

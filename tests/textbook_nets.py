@@ -118,9 +118,9 @@ def lstm_stack_loss_and_grads(layer_params, Wy, by, xs, targets, use_h=True, sta
     return loss, probs, grads, dWy, dby, hs
 
 
-def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets, h0=None):
-    """h(t) = tanh(Wx x(t) + Wh h(t-1) + bh); p(t) = softmax(Wy h(t) + by); one stream; h(-1) = h0
-    (a constant of the window; default zero)."""
+def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets, h0=None, rectifier=False):
+    """h(t) = tanh(Wx x(t) + Wh h(t-1) + bh), or max(0, .) with rectifier=True; p(t) =
+    softmax(Wy h(t) + by); one stream; h(-1) = h0 (a constant of the window; default zero)."""
     Wx, Wh, bh, Wy, by = (np.asarray(a, dtype=np.float64) for a in (Wx, Wh, bh, Wy, by))
     xs = np.asarray(xs, dtype=np.float64)
     T = xs.shape[0]
@@ -130,7 +130,8 @@ def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets, h0=None):
     loss = 0.0
     for t in range(T):
         hp = h[t - 1] if t > 0 else h0
-        h[t] = np.tanh(Wx @ xs[t] + Wh @ hp + bh)
+        a = Wx @ xs[t] + Wh @ hp + bh
+        h[t] = np.where(a > 0, a, 0.0) if rectifier else np.tanh(a)
         probs[t] = _softmax(Wy @ h[t] + by)
         if targets[t] >= 0:
             loss -= np.log(probs[t, targets[t]])
@@ -142,7 +143,7 @@ def elman_loss_and_grads(Wx, Wh, bh, Wy, by, xs, targets, h0=None):
         if targets[t] >= 0:
             dl = probs[t].copy(); dl[targets[t]] -= 1.0
         G["Wy"] += np.outer(dl, h[t]); G["by"] += dl
-        da = (Wy.T @ dl + dh_next) * (1 - h[t] ** 2)
+        da = (Wy.T @ dl + dh_next) * (np.where(h[t] > 0, 1.0, 0.0) if rectifier else 1 - h[t] ** 2)
         hp = h[t - 1] if t > 0 else h0
         G["Wx"] += np.outer(da, xs[t]); G["Wh"] += np.outer(da, hp); G["bh"] += da
         dh_next = Wh.T @ da
