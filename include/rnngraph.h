@@ -54,14 +54,15 @@ enum rnn_status {
 /* Node (layer) kinds: Section 2.1 defines additive layers (sum of the incoming connection
  * outputs, then an activation function) and multiplicative layers (element-wise product). */
 enum { RNN_NODE_INPUT = 0, RNN_NODE_ADD = 1, RNN_NODE_MUL = 2 };
-/* Activation functions f_k; softmax is allowed on output nodes only and is paired with the
- * cross-entropy criterion, the case for which Section 2.2 writes the output delta out. */
-enum { RNN_ACT_LINEAR = 0, RNN_ACT_SIGMOID = 1, RNN_ACT_TANH = 2, RNN_ACT_SOFTMAX = 3 };
-/* Values of rnn_node_desc.is_output.  Section 2.2 initialises the delta of an output layer
- * "according to the error criterion defined by E(t) and the activation function of the output
- * layer":  RNN_OUT_CROSS_ENTROPY: additive softmax layer, class-index targets,
+/* Activation functions f_k (Section 2.1 leaves them open); softmax is allowed on output nodes
+ * only and is paired with the cross-entropy criterion, the case for which Section 2.2 writes the
+ * output delta out.  RNN_ACT_RELU is the rectifier max(0, s); its derivative at s = 0 counts as 0. */
+enum { RNN_ACT_LINEAR = 0, RNN_ACT_SIGMOID = 1, RNN_ACT_TANH = 2, RNN_ACT_SOFTMAX = 3, RNN_ACT_RELU = 4 };
+/* Values of rnn_node_desc.is_output.  In Section 2.2 the initial delta of an output layer
+ * depends on the error criterion E(t) and on the layer's activation function.
+ * RNN_OUT_CROSS_ENTROPY: additive softmax layer, class-index targets,
  * E(t) = -ln y_target, delta = d - y;  RNN_OUT_SQUARED_ERROR (the MSE criterion that Section 4
- * names): additive layer with linear, sigmoid or tanh activation, dense targets,
+ * names): additive layer with linear, sigmoid, tanh or rectifier activation, dense targets,
  * E(t) = 1/2 sum_j (d_j - y_j)^2, delta_j = (d_j - y_j) f'(s_j). */
 enum { RNN_OUT_NONE = 0, RNN_OUT_CROSS_ENTROPY = 1, RNN_OUT_SQUARED_ERROR = 2 };
 /* Weight kinds: full matrix [n_dst x n_src] (row-major, z = W y), diagonal (a vector, used for

@@ -24,11 +24,11 @@ Readings where the paper is silent (all listed in the design notes of the reposi
     weight-gradient terms eps_m(t) y_k(t - d_m)^T of the frames t > t0' use the real
     y_k(t - d_m), also where t - d_m <= t0'; error terms from frames after the window are zero;
   * E_total = sum over frames, streams and output nodes of E(t) (no averaging).  Two error
-    criteria (Section 2.2: delta of an output layer follows "the error criterion defined by E(t)
-    and the activation function of the output layer"): is_output = 1, softmax with minimum
+    criteria (Section 2.2: the initial delta of an output layer depends on the criterion E(t) and
+    on the layer's activation function): is_output = 1, softmax with minimum
     cross-entropy, E = -ln y_target (natural log), class targets, -1 masks the frame; is_output = 2,
     squared error E = 1/2 sum_j (d_j - y_j)^2 (the MSE criterion Section 4 names) on a linear,
-    sigmoid or tanh output layer, dense targets, a NaN target element has no error;
+    sigmoid, tanh or rectifier output layer, dense targets, a NaN target element has no error;
   * the functions return dE_total/dW (the paper's nabla W = -sum eps y^T with
     eps = -dE/dz is exactly that).
 

@@ -22,7 +22,7 @@ std::string validate_graph(const std::vector<GNode>& nodes, const std::vector<GE
     for (int k = 0; k < K; ++k) {
         const GNode& n = nodes[k];
         if (n.kind < NODE_INPUT || n.kind > NODE_MUL) { e << "node " << k << ": unknown kind " << n.kind; return e.str(); }
-        if (n.act < ACT_LINEAR || n.act > ACT_SOFTMAX) { e << "node " << k << ": unknown activation " << n.act; return e.str(); }
+        if (n.act < ACT_LINEAR || n.act > ACT_RELU) { e << "node " << k << ": unknown activation " << n.act; return e.str(); }
         if (n.dim <= 0) { e << "node " << k << ": dim must be positive"; return e.str(); }
         if (n.kind == NODE_INPUT && (n.has_bias || n.is_output || n.act != ACT_LINEAR)) {
             e << "node " << k << ": an input node has no bias, no activation and is not an output"; return e.str();
@@ -37,7 +37,7 @@ std::string validate_graph(const std::vector<GNode>& nodes, const std::vector<GE
         } else if (n.is_output == OUT_SQUARED_ERROR) {
             ++n_outputs;
             if (n.kind != NODE_ADD || n.act == ACT_SOFTMAX) {
-                e << "node " << k << ": a squared-error output node must be additive with linear, sigmoid or tanh activation"; return e.str();
+                e << "node " << k << ": a squared-error output node must be additive with linear, sigmoid, tanh or rectifier activation"; return e.str();
             }
         } else if (n.act == ACT_SOFTMAX) {
             e << "node " << k << ": softmax is allowed on output nodes only"; return e.str();

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void squared_error_delta_kernel(const float* _
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += 256LL * gridDim.x) {
         const float yi = y[i], di = d[i];
         const float err = di != di ? 0.0f : yi - di;      // a NaN target element carries no error
-        const float fp = act == 1 ? yi * (1.0f - yi) : act == 2 ? 1.0f - yi * yi : 1.0f;
+        const float fp = act == 1 ? yi * (1.0f - yi) : act == 2 ? 1.0f - yi * yi : act == 4 ? (yi > 0.0f ? 1.0f : 0.0f) : 1.0f;
         ds[i] = err * fp;
         l += 0.5f * err * err;
     }

@@ -103,6 +103,8 @@ __device__ __forceinline__ void run_ops(float (&s)[MAX_SLOTS], const ProgramView
             case MOP_TANH: r = tanh_f(va); break;
             case MOP_DSIG: { const float y = s[b]; r = va * y * (1.0f - y); break; }
             case MOP_DTANH: { const float y = s[b]; r = va * (1.0f - y * y); break; }
+            case MOP_RELU: r = fmaxf(va, 0.0f); break;
+            case MOP_DRELU: r = s[b] > 0.0f ? va : 0.0f; break;
             default: r = 0.0f; break;
         }
         s[d] = r;

@@ -72,6 +72,8 @@ void emit_ops(std::ostringstream& o, const int32_t* pw) {
             case MOP_TANH: o << "step_tanh(s[" << a << "])"; break;
             case MOP_DSIG: o << "s[" << a << "] * s[" << b << "] * (1.0f - s[" << b << "])"; break;
             case MOP_DTANH: o << "s[" << a << "] * (1.0f - s[" << b << "] * s[" << b << "])"; break;
+            case MOP_RELU: o << "fmaxf(s[" << a << "], 0.0f)"; break;
+            case MOP_DRELU: o << "(s[" << b << "] > 0.0f ? s[" << a << "] : 0.0f)"; break;
             default: o << "0.0f"; break;
         }
         o << ";\n";

@@ -53,7 +53,7 @@ hipError_t launch_softmax_rows(float* y, int64_t rows, int dim, hipStream_t stre
 hipError_t launch_softmax_ce_delta(const float* y, const int32_t* targets, float* ds, double* loss, unsigned* flag,
                                    int64_t rows, int dim, hipStream_t stream);
 // Squared-error output layer: ds = (y - d) f'(s) element by element (0 where d is NaN), f' from y
-// for act = linear / sigmoid / tanh; *loss += 1/2 sum (d - y)^2.
+// for act = linear / sigmoid / tanh / rectifier; *loss += 1/2 sum (d - y)^2.
 hipError_t launch_squared_error_delta(const float* y, const float* d, float* ds, double* loss, int64_t n, int act,
                                       hipStream_t stream);
 // Column-sum tasks (diagonal-weight and bias gradients), atomically added into grads.

@@ -21,7 +21,7 @@ int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 struct FactorH { int buf, frame_off, w_off, slot; };
 struct TermH { std::vector<FactorH> f; };
-enum { POST_NONE = 0, POST_SIGMOID = 1, POST_TANH = 2, POST_DSIGMOID = 3, POST_DTANH = 4 };
+enum { POST_NONE = 0, POST_SIGMOID = 1, POST_TANH = 2, POST_DSIGMOID = 3, POST_DTANH = 4, POST_RELU = 5, POST_DRELU = 6 };
 struct OpH {
     int post = POST_NONE, dim = 0, out_buf = -1, pre_buf = -1, bias_off = -1, acc_buf = -1, acc_task = 0,
         deriv_buf = -1, out_slot = -1;
@@ -119,6 +119,8 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
         else if (o.post == POST_TANH) mop(MOP_TANH, R, R, 0, 0);
         else if (o.post == POST_DSIGMOID) mop(MOP_DSIG, R, R, L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES), 0);
         else if (o.post == POST_DTANH) mop(MOP_DTANH, R, R, L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES), 0);
+        else if (o.post == POST_RELU) mop(MOP_RELU, R, R, 0, 0);
+        else if (o.post == POST_DRELU) mop(MOP_DRELU, R, R, L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES), 0);
         stores.push_back({o.out_buf, R, o.dim, 0});
     }
     const int off = (int)w.size();
@@ -360,7 +362,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             std::vector<MvTaskH> tasks; std::vector<OpH> ops;
             for (int k : np) {
                 OpH o; o.dim = xn[k].dim; o.out_buf = P.ybuf(k); o.out_slot = slot[k];
-                o.post = xn[k].act == ACT_SIGMOID ? POST_SIGMOID : xn[k].act == ACT_TANH ? POST_TANH : POST_NONE;
+                o.post = xn[k].act == ACT_SIGMOID ? POST_SIGMOID : xn[k].act == ACT_TANH ? POST_TANH : xn[k].act == ACT_RELU ? POST_RELU : POST_NONE;
                 if (xn[k].has_bias) o.bias_off = (int)P.bias_off[k];
                 MvTaskH task; task.n_out = xn[k].dim; task.acc_buf = P.abuf(k);
                 TermH product;
@@ -420,6 +422,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                 OpH o; o.dim = xn[j].dim; o.out_buf = P.dbuf(j); o.out_slot = slot[j];
                 if (xn[j].act == ACT_SIGMOID) { o.post = POST_DSIGMOID; o.deriv_buf = P.ybuf(j); }
                 else if (xn[j].act == ACT_TANH) { o.post = POST_DTANH; o.deriv_buf = P.ybuf(j); }
+                else if (xn[j].act == ACT_RELU) { o.post = POST_DRELU; o.deriv_buf = P.ybuf(j); }
                 MvTaskH task; task.n_out = xn[j].dim; task.acc_buf = P.abuf(j);
                 for (int m : out_e[j]) {
                     const GEdge& e = xe[m];

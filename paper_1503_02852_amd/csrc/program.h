@@ -34,7 +34,9 @@ enum {
     MOP_TANH = 5,   // d = tanh(a)
     MOP_DSIG = 6,   // d = a * b * (1 - b)
     MOP_DTANH = 7,  // d = a * (1 - b * b)
-    MOP_ZERO = 8    // d = 0
+    MOP_ZERO = 8,   // d = 0
+    MOP_RELU = 9,   // d = max(a, 0)
+    MOP_DRELU = 10  // d = b > 0 ? a : 0
 };
 
 // Program header, then gather entries, inv entries, ops, stores.

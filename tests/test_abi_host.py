@@ -107,6 +107,9 @@ def test_invalid_graphs_are_rejected():
     bad([X, H, [wl.MUL, wl.LINEAR, 3, 0, 2]], [[0, 1, 0, 0], [1, 2, 0, 2]])     # squared-error output that is multiplicative
     bad([X, H, [wl.ADD, wl.TANH, 2, 1, 3]], ok_edges)                           # unknown output kind
     Graph(np.array([X, H, [wl.ADD, wl.TANH, 2, 1, 2]], np.int32), np.array(ok_edges, np.int32))      # a valid squared-error output
+    assert "activation" in bad([X, [wl.ADD, 5, 3, 1, 0], O], ok_edges)          # unknown activation
+    bad([X, H, [wl.ADD, wl.RELU, 2, 1, 1]], ok_edges)                           # cross-entropy output with a rectifier
+    Graph(np.array([X, [wl.ADD, wl.RELU, 3, 1, 0], [wl.ADD, wl.RELU, 2, 1, 2]], np.int32), np.array(ok_edges, np.int32))   # rectified hidden and squared-error layers
 
 
 def test_runtime_argument_errors_without_gpu_work():

@@ -92,6 +92,33 @@ def test_elman():
     run_both(wl.make_workload("elman", wl.elman_net(20, 150, 11), T=33, N=5, seed=2, scale=0.15))
 
 
+RELU_ACTS = (wl.LINEAR, wl.SIGMOID, wl.TANH, wl.RELU, wl.RELU)
+
+
+@pytest.mark.parametrize("N", [1, 5, 33])
+def test_rectifier_elman(N):
+    """A rectified Elman layer (Section 2.1 leaves the activation function open): weights in
+    registers at few streams, matrix cores at many."""
+    w = wl.make_workload("elman_relu", wl.elman_net(20, 150, 11, act=wl.RELU), T=21, N=N, seed=5, scale=0.1, bias_scale=0.2)
+    win, ref = run_both(w, label=f"rectifier Elman, N={N}")
+    h = ref["y"][1]
+    assert (h == 0).any() and (h > 0).any()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_graphs_with_rectifiers(seed):
+    """Random recurrent graphs whose additive and multiplicative nodes draw the rectifier too."""
+    rng = np.random.default_rng(900 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, n_inputs=1 + seed % 2, acts=RELU_ACTS)
+    run_both(wl.make_workload(f"rand_relu{seed}", spec, T=8 + seed, N=1 + 4 * (seed % 3), seed=seed, scale=0.8, bias_scale=0.5,
+                              masked_fraction=0.2 if seed % 2 else 0.0))
+
+
+def test_rectifier_with_the_interpreting_step_kernel(monkeypatch):
+    monkeypatch.setenv("RNNG_JIT", "0")
+    run_both(wl.make_workload("elman_relu", wl.elman_net(9, 40, 5, act=wl.RELU), T=13, N=3, seed=6, scale=0.2, bias_scale=0.2), label="rectifier Elman, RNNG_JIT=0")
+
+
 def test_lstm_without_output_recurrence():
     run_both(wl.make_workload("lm_lstm", wl.lstm_net(12, [70], 9, output_recurrence=False), T=40, N=3, seed=3, scale=0.3))
 
@@ -443,7 +470,7 @@ def test_language_model_shapes_short_window(name):
 
 # ---- output layers with dense targets under the squared error (Section 2.2: the output delta follows the error criterion) ----
 
-@pytest.mark.parametrize("act", [wl.LINEAR, wl.SIGMOID, wl.TANH])
+@pytest.mark.parametrize("act", [wl.LINEAR, wl.SIGMOID, wl.TANH, wl.RELU])
 def test_squared_error_output_layer(act):
     spec = wl.lstm_net(12, [40, 24], 7, squared_error_act=act)
     run_both(wl.make_workload("lstm_sq", spec, T=21, N=3, seed=80 + act, scale=0.4, bias_scale=0.3, masked_fraction=0.25), label=f"squared error, act {act}")

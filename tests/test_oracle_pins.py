@@ -558,7 +558,7 @@ def test_windowed_bptt_keeps_pre_window_connection_outputs():
 
 # ---- the squared-error criterion (Section 2.2: delta of an output layer follows the error criterion; Section 4 names the MSE) ----
 
-@pytest.mark.parametrize("act", [wl.LINEAR, wl.SIGMOID, wl.TANH])
+@pytest.mark.parametrize("act", [wl.LINEAR, wl.SIGMOID, wl.TANH, wl.RELU])
 def test_squared_error_output_layer_closed_form(act):
     """One layer y = f(W x + b) under E = 1/2 sum (d - y)^2: dE/dW = sum_t ((y - d) f'(s)) x^T in
     closed form, NaN targets left out, and delta = (d - y) f'(s)."""
@@ -571,8 +571,8 @@ def test_squared_error_output_layer_closed_form(act):
     r = run_oracle(w)
     X = w.inputs[x].astype(np.float64)
     S = X @ w.weights[e].astype(np.float64).T + w.biases[out]
-    Y = S if act == wl.LINEAR else 1 / (1 + np.exp(-S)) if act == wl.SIGMOID else np.tanh(S)
-    dY = np.ones_like(Y) if act == wl.LINEAR else Y * (1 - Y) if act == wl.SIGMOID else 1 - Y * Y
+    Y = S if act == wl.LINEAR else 1 / (1 + np.exp(-S)) if act == wl.SIGMOID else np.tanh(S) if act == wl.TANH else np.where(S > 0, S, 0.0)
+    dY = np.ones_like(Y) if act == wl.LINEAR else Y * (1 - Y) if act == wl.SIGMOID else 1 - Y * Y if act == wl.TANH else np.where(S > 0, 1.0, 0.0)
     D = w.targets[out].astype(np.float64)
     err = np.where(np.isnan(D), 0.0, Y - D)
     assert r["loss"] == pytest.approx(0.5 * (err ** 2).sum(), rel=1e-13)

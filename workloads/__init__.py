@@ -11,7 +11,7 @@ Enumerations are the interface's integer codes (they appear in the C header too)
   activation: 0 linear, 1 logistic sigmoid, 2 tanh, 3 softmax (output nodes only), 4 rectifier max(0, s)
   weight kind: 0 full matrix [n_dst x n_src], 1 diagonal (vector), 2 identity
   is_output : 0 no, 1 softmax output with class targets (cross-entropy), 2 output with dense
-              targets under the squared error (linear, sigmoid or tanh activation)
+              targets under the squared error (linear, sigmoid, tanh or rectifier activation)
 """
 from __future__ import annotations
 
