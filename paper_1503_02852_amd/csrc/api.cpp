@@ -317,7 +317,11 @@ struct rnn_graph {
     // Chains of recurrent components run side by side in one launch: all members in the
     // wave-autonomous build (N <= 8, member g on XCD g), or all in the matrix-core build (the 256
     // workgroups shared among the members).
-    struct ChainChoice { std::string source, source_window; std::vector<int> G, J; bool mstep = false, blocked = false; size_t lds_bytes = 0; int threads = 256; };
+    struct ChainChoice {
+        std::string source, source_window; std::vector<int> G, J; bool mstep = false, blocked = false; size_t lds_bytes = 0; int threads = 256;
+        bool split = false;      // the backward launch with helper members (ChainPlan::bwd_split)
+    };
+    static const std::vector<CompPlan>& chain_members(const ChainPlan& ch, const ChainChoice& cc) { return cc.split ? ch.bwd_split : ch.members; }
     std::map<std::tuple<int, bool, int>, ChainChoice> chain_choices;
     bool use_chains = true;
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
@@ -339,27 +343,38 @@ struct rnn_graph {
                 // matrix-core members: each gets an equal share of the 256 workgroups; per member the
                 // most stream groups, then the most unit chunks that fit the share (as for a single
                 // component: fewer only while a workgroup does not fill a 16-row tile)
-                const int share = std::min(256, max_workgroups()) / (int)ch.members.size();
-                c.G.clear(); c.J.clear();
-                for (const CompPlan& m : ch.members) {
-                    int pg = 0, pj = 0, best_rows = -1;
-                    for (int J : {4, 2, 1}) {
-                        for (int G : {128, 64, 32, 16}) {
-                            if (G * J > share) continue;
-                            size_t lds = 0; int rows = 0;
-                            if (jit_mstep_source(plan, m, backward, N, G, J, &lds, &rows).empty()) continue;
-                            if (best_rows < 0 || (best_rows < 16 && rows > best_rows)) { pg = G; pj = J; best_rows = rows; }
-                            if (best_rows >= 16) break;
+                // Backward launches of a stack are bound by the matrix instructions of the members that
+                // also contract the later member's error terms, while compute units idle: helper members
+                // take those products (RNNG_CHAIN_HELPERS = 0: never).
+                const char* envh = std::getenv("RNNG_CHAIN_HELPERS");
+                c.split = backward && !ch.bwd_split.empty() && !(envh && std::atoi(envh) == 0);
+                for (int attempt = 0; attempt < 2 && c.source.empty(); ++attempt) {
+                    if (attempt == 1) { if (!c.split) break; c.split = false; }
+                    const std::vector<CompPlan>& members = chain_members(ch, c);
+                    const int share = std::min(256, max_workgroups()) / (int)members.size();
+                    c.G.clear(); c.J.clear();
+                    for (const CompPlan& m : members) {
+                        int pg = 0, pj = 0, best_rows = -1;
+                        for (int J : {4, 2, 1}) {
+                            for (int G : {128, 64, 32, 16}) {
+                                if (G * J > share) continue;
+                                size_t lds = 0; int rows = 0;
+                                if (jit_mstep_source(plan, m, backward, N, G, J, &lds, &rows).empty()) continue;
+                                if (best_rows < 0 || (best_rows < 16 && rows > best_rows)) { pg = G; pj = J; best_rows = rows; }
+                                if (best_rows >= 16) break;
+                            }
+                            if (pg) break;
                         }
-                        if (pg) break;
+                        if (!pg) break;
+                        c.G.push_back(pg); c.J.push_back(pj);
                     }
-                    if (!pg) break;
-                    c.G.push_back(pg); c.J.push_back(pj);
+                    if (c.G.size() == members.size()) {
+                        c.source = jit_mstep_chain_source(plan, members, backward, N, c.G, c.J, &c.lds_bytes, &c.threads, &c.blocked);
+                        c.mstep = !c.source.empty();
+                        if (c.split && !c.blocked) { c.source.clear(); c.mstep = false; }      // (helpers pay only with the tile-blocked exchange's full tiles)
+                    }
                 }
-                if (c.G.size() == ch.members.size()) {
-                    c.source = jit_mstep_chain_source(plan, ch, backward, N, c.G, c.J, &c.lds_bytes, &c.threads, &c.blocked);
-                    c.mstep = !c.source.empty();
-                }
+                if (c.source.empty()) c.split = false;
             }
         }
         return chain_choices.emplace(key, c).first->second;
@@ -514,7 +529,7 @@ const std::string& windowed(const std::string& source, std::string& cache) {
 // A kernel with tile-blocked exchange polls the twins and nothing else.
 hipError_t fill_shared(rnn_graph* g, const std::vector<int>& bufs, bool with_bundles, int t0, int t1, hipStream_t s, bool twins = false) {
     std::vector<int> list(bufs);
-    if (twins) for (int& b : list) b += g->plan.twin_base;
+    if (twins) for (int& b : list) if (g->plan.buf_alloc[g->plan.twin_base + b] == 3) b += g->plan.twin_base;      // (tensors without a twin are polled as they are)
     if (with_bundles)
         for (int b : bufs) {
             const int bi = g->plan.bundle_of[b];
@@ -674,7 +689,8 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     const PlanView pv = g->view();
     const int T = g->Ti(), N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
-    for (const CompPlan& m : ch.members) {
+    const std::vector<CompPlan>& members = rnn_graph::chain_members(ch, cc);
+    for (const CompPlan& m : members) {
         hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s, cc.blocked);
         if (e != hipSuccess) return step_error(e, "sentinel fill");
     }
@@ -684,13 +700,13 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
         for (size_t i = 0; i < cc.G.size(); ++i) lp.G += cc.G[i] * cc.J[i];      // launch size
     }
     StepArgs a;
-    fill_step_args(a, pv, lp, backward ? ch.members[0].bwd_desc_off : ch.members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
+    fill_step_args(a, pv, lp, backward ? members[0].bwd_desc_off : members[0].fwd_desc_off, g->weights, g->ctrl_ptr(),
                    T, N, backward, g->spin_limit, t0, t1);
     if (window) { a.store_base = reinterpret_cast<float*>(g->ws); a.store_bytes = (unsigned)g->layout.total; }
-    a.n_groups = (int)ch.members.size();
+    a.n_groups = (int)members.size();
     a.twin_base = g->plan.twin_base;
     for (int i = 0; i < a.n_groups; ++i) {
-        a.grp_desc_off[i] = backward ? ch.members[i].bwd_desc_off : ch.members[i].fwd_desc_off;
+        a.grp_desc_off[i] = backward ? members[i].bwd_desc_off : members[i].fwd_desc_off;
         a.grp_G[i] = cc.G[i];
         if (cc.mstep) {
             a.grp_J[i] = cc.J[i];

@@ -109,12 +109,15 @@ void emit_phase_descriptor(std::ostringstream& o, const Plan& P, const PhasePlan
     emit_switch("gkind", "g", kinds); emit_switch("gaux", "g", auxs); emit_switch("sidx", "g", sidx);
     emit_switch("cidx", "g", cidx); emit_switch("sgather", "si", sgather);
     const int32_t* st = pw + PG_HEADER_WORDS + ng * GA_WORDS + ni * IV_WORDS + nops * MO_WORDS;
-    std::vector<std::pair<int, int>> slots, shareds;
+    std::vector<std::pair<int, int>> slots, shareds, twins;
     for (int q = 0; q < nst; ++q) {
         slots.push_back({q, st[q * ST_WORDS + ST_SLOT]});
         if (st[q * ST_WORDS + ST_FLAGS] & 1) shareds.push_back({q, 1});
+        const int b = st[q * ST_WORDS + ST_BUF];
+        if (P.twin_base >= 0 && b < P.twin_base && P.buf_alloc[P.twin_base + b] == 3) twins.push_back({q, 1});
     }
-    emit_switch("stslot", "q", slots); emit_switch("stshared", "q", shareds);
+    // (sttwin: the stored tensor has a tile-blocked twin, which many-stream kernels poll instead of it)
+    emit_switch("stslot", "q", slots); emit_switch("stshared", "q", shareds); emit_switch("sttwin", "q", twins);
     o << "    static __device__ __forceinline__ void ops(float* s) {\n";
     emit_ops(o, pw);
     o << "    }\n};\n";
@@ -467,7 +470,8 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     if (blocked) {
         if (N_all < 16 || N_all % 16 != 0 || N % 16 != 0 || P.twin_base < 0) return false;
         auto has_twin = [&](int b) { return b >= 0 && b < P.twin_base && P.buf_alloc[P.twin_base + b] == 3; };
-        for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) if (!has_twin(b)) return false;
+        // (a helper member's sums are read element by element from the row-major tensor)
+        if (!cp.helper) for (int b : backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs) if (!has_twin(b)) return false;
         for (int s = 0; s < ml.n_src; ++s) if (!has_twin(lay.src[s].buf) || lay.src[s].k_len != P.buf_dim[lay.src[s].buf]) return false;
     }
     const StepPhase& ph = lay.ph[0];
@@ -504,7 +508,8 @@ bool emit_mstep_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, 
     };
     o << "struct MM {\n    static constexpr int NJ = " << N << ", MT = " << MT << ", NSRC = " << ml.n_src << ", NTU = " << NTU
       << ", D = " << D << ", CMAX = " << ml.cmax << ", ACCS = " << ml.accstride << ", NW = " << NW << ", NCH = " << nch << ";\n"
-      << "    static constexpr bool FLAT = " << (flat ? "true" : "false") << ", XB = " << (blocked ? "true" : "false") << ";\n"
+      << "    static constexpr bool FLAT = " << (flat ? "true" : "false") << ", XB = " << (blocked ? "true" : "false")
+      << ", HELPER = " << (cp.helper ? "true" : "false") << ";\n"
       ;
     std::vector<std::pair<int, int>> ks, blk, used, ngr, csrc, ck0;
     // The unrolled chunk sequence takes the sources in the order in which their values arrive: what
@@ -667,10 +672,10 @@ std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, 
 }
 
 // Several components side by side (a chain): group g takes the blocks [grp_first[g], ...).
-std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
+std::string jit_mstep_chain_source(const Plan& P, const std::vector<CompPlan>& members, bool backward, int N, const std::vector<int>& G,
                                    const std::vector<int>& J, size_t* lds_bytes, int* threads, bool* blocked) {
     std::ostringstream o;
-    const int n = (int)ch.members.size();
+    const int n = (int)members.size();
     if (n < 2 || n > STEP_MAX_GROUPS || (int)G.size() != n || (int)J.size() != n) return "";
     size_t lds_max = 0;
     int total = 0, NW = 0; bool xb = false;
@@ -682,7 +687,7 @@ std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool back
             bool all = true;
             for (int g = 0; g < n && all; ++g) {
                 size_t lds = 0;
-                all = emit_mstep_group(o, P, ch.members[g], backward, N, G[g], J[g], nw, b != 0, "grp" + std::to_string(g), &lds, nullptr);
+                all = emit_mstep_group(o, P, members[g], backward, N, G[g], J[g], nw, b != 0, "grp" + std::to_string(g), &lds, nullptr);
                 lds_max = std::max(lds_max, lds);
                 total += G[g] * J[g];
             }

@@ -30,8 +30,9 @@ std::string jit_mstep_source(const Plan& P, const CompPlan& cp, bool backward, i
 std::string jit_mstep2_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G, int GJ, size_t* lds_bytes,
                               int64_t* partial_floats);
 // Chain of matrix-core components in one launch: member g on G[g] unit chunks x J[g] stream groups
-// (at most 256 workgroups in all).  Empty if some member is not eligible.
-std::string jit_mstep_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G,
+// (at most 256 workgroups in all); members: a chain's members, or its backward launch with helper
+// members (ChainPlan::bwd_split).  Empty if some member is not eligible.
+std::string jit_mstep_chain_source(const Plan& P, const std::vector<CompPlan>& members, bool backward, int N, const std::vector<int>& G,
                                    const std::vector<int>& J, size_t* lds_bytes, int* threads = nullptr, bool* blocked = nullptr);
 // Streaming variant (N <= 8 streams; weights read from memory every step, for layers too wide to
 // keep on chip): G unit chunks.  *transposed: the kernel reads transposed copies of some matrices.

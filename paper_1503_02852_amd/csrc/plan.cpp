@@ -24,7 +24,7 @@ struct TermH { std::vector<FactorH> f; };
 enum { POST_NONE = 0, POST_SIGMOID = 1, POST_TANH = 2, POST_DSIGMOID = 3, POST_DTANH = 4, POST_RELU = 5, POST_DRELU = 6 };
 struct OpH {
     int post = POST_NONE, dim = 0, out_buf = -1, pre_buf = -1, bias_off = -1, acc_buf = -1, acc_task = 0,
-        deriv_buf = -1, out_slot = -1;
+        deriv_buf = -1, out_slot = -1, polled_buf = -1;
     bool new_program = false;   // must not share a program with the operation before it
     bool pre_static = false;    // pre_buf was written before the step loop (batched GEMM), not by an earlier part
     bool partial_out = false;   // out_buf holds a partial sum, not the layer's value
@@ -72,6 +72,7 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
         if (o.pre_buf >= 0) L.gather_slot(o.pre_buf, 0, o.dim, GA_KIND_FRAMES);
         if (o.bias_off >= 0) L.inv_index(o.bias_off, o.dim);
         if (o.acc_buf >= 0) L.gather_slot(o.acc_buf, o.acc_task, o.dim, GA_KIND_ACC);
+        if (o.polled_buf >= 0) L.gather_slot(o.polled_buf, 0, o.dim, GA_KIND_POLLED);
         for (const TermH& t : o.terms)
             for (const FactorH& f : t.f) {
                 if (f.slot < 0) L.gather_slot(f.buf, f.frame_off, buf_dim[f.buf], GA_KIND_FRAMES);
@@ -95,6 +96,7 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
         if (o.pre_buf >= 0) summands.push_back({L.gather_slot(o.pre_buf, 0, o.dim, GA_KIND_FRAMES)});
         if (o.bias_off >= 0) summands.push_back({ng + L.inv_index(o.bias_off, o.dim)});
         if (o.acc_buf >= 0) summands.push_back({L.gather_slot(o.acc_buf, o.acc_task, o.dim, GA_KIND_ACC)});
+        if (o.polled_buf >= 0) summands.push_back({L.gather_slot(o.polled_buf, 0, o.dim, GA_KIND_POLLED)});
         for (const TermH& t : o.terms) {
             std::vector<int> atoms;
             for (const FactorH& f : t.f) {
@@ -292,7 +294,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     const std::vector<GNode>& xn = P.xnodes;
     const std::vector<GEdge>& xe = P.xedges;
     const Schedule& S = P.xsched;
-    P.n_bufs = 5 * K;
+    P.n_bufs = 6 * K;
     P.buf_dim.assign(P.n_bufs, 0);
     P.buf_alloc.assign(P.n_bufs, 0);
     P.hist = 0;
@@ -304,7 +306,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         if (xn[xe[m].src].kind == NODE_INPUT && (xe[m].delay > 0 || xe[m].wkind != W_FULL)) P.input_staged[xe[m].src] = 1;
     }
     for (int k = 0; k < K; ++k) {
-        for (int b : {P.ybuf(k), P.dbuf(k), P.abuf(k), P.pbuf(k), P.qbuf(k)}) P.buf_dim[b] = xn[k].dim;
+        for (int b : {P.ybuf(k), P.dbuf(k), P.abuf(k), P.pbuf(k), P.qbuf(k), P.hbuf(k)}) P.buf_dim[b] = xn[k].dim;
         if (xn[k].kind != NODE_INPUT) P.buf_alloc[P.ybuf(k)] = P.buf_alloc[P.dbuf(k)] = 1;
         else if (P.input_staged[k]) P.buf_alloc[P.ybuf(k)] = 1;
     }
@@ -322,7 +324,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     // Lowers component c into cp.  fused[m] marks full connections between different recurrent
     // components that the step kernel evaluates itself (as if they were delayed connections of
     // the component) instead of taking them from a GEMM over all frames.
-    auto lower_component = [&](int c, const std::vector<char>& fused, CompPlan& cp) -> bool {
+    // helper (optional): the backward products of the fused connections go to a helper member
+    // instead (ChainPlan::bwd_split), which *helper receives; it stays without a backward program if
+    // the component has no such connection.
+    auto lower_component = [&](int c, const std::vector<char>& fused, CompPlan& cp, CompPlan* helper = nullptr) -> bool {
         auto batched = [&](int m) { return S.edge_class[m] == EDGE_BATCHED && !fused[m]; };
         cp.recurrent = S.comp_recurrent[c] != 0;
         std::vector<int> members;
@@ -418,8 +423,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             std::map<int, int> slot;
             for (size_t i = 0; i < np.size(); ++i) slot[np[i]] = (int)i;
             std::vector<MvTaskH> tasks; std::vector<OpH> ops;
+            std::vector<MvTaskH> htasks; std::vector<OpH> hops; std::vector<int> hparts;
             for (int j : np) {
                 OpH o; o.dim = xn[j].dim; o.out_buf = P.dbuf(j); o.out_slot = slot[j];
+                MvTaskH htask; htask.n_out = xn[j].dim; htask.acc_buf = P.abuf(j);
                 if (xn[j].act == ACT_SIGMOID) { o.post = POST_DSIGMOID; o.deriv_buf = P.ybuf(j); }
                 else if (xn[j].act == ACT_TANH) { o.post = POST_DTANH; o.deriv_buf = P.ybuf(j); }
                 else if (xn[j].act == ACT_RELU) { o.post = POST_DRELU; o.deriv_buf = P.ybuf(j); }
@@ -429,6 +436,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     const int k = e.dst;
                     if (e.wkind == W_FULL) {
                         if (batched(m)) { o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); o.pre_static = true; }
+                        else if (helper && fused[m]) htask.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
                         else task.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
                         continue;
                     }
@@ -442,7 +450,22 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     o.terms.push_back(t);
                 }
                 if (!task.edges.empty()) { o.acc_buf = task.acc_buf; o.acc_task = (int)tasks.size(); tasks.push_back(task); P.buf_alloc[task.acc_buf] = 2; }
+                if (!htask.edges.empty()) {
+                    // the helper's program: sum of its products, stored where this program polls it
+                    o.polled_buf = P.hbuf(j);
+                    OpH ho; ho.dim = xn[j].dim; ho.out_buf = P.hbuf(j); ho.out_slot = (int)hops.size();
+                    ho.acc_buf = htask.acc_buf; ho.acc_task = (int)htasks.size();
+                    htasks.push_back(htask); hops.push_back(ho); hparts.push_back(P.qbuf(j));
+                    P.buf_alloc[htask.acc_buf] = 2; P.buf_alloc[P.hbuf(j)] = 1;
+                    helper->bwd_shared_bufs.push_back(P.hbuf(j));
+                }
                 ops.push_back(o);
+            }
+            if (helper && !hops.empty()) {
+                std::vector<char> hwritten(P.n_bufs, 0), hshared(P.n_bufs, 0);
+                for (const OpH& ho : hops) hwritten[ho.out_buf] = hshared[ho.out_buf] = 1;
+                if (!emit_phase(P, helper->bwd_phases, htasks, hops, hparts, hwritten, hshared, 1, err)) return false;
+                helper->recurrent = true; helper->helper = true; helper->has_bwd_program = true;
             }
             std::vector<int> part_bufs;
             for (int j : np) part_bufs.push_back(P.qbuf(j));
@@ -454,6 +477,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         }
         cp.has_bwd_program = true;
         cp.bwd_desc_off = emit_desc(cp.bwd_phases);
+        if (helper && helper->has_bwd_program) helper->bwd_desc_off = emit_desc(helper->bwd_phases);
         return true;
     };
     P.comps.assign(S.n_comps, CompPlan());
@@ -505,6 +529,16 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     ch.members.push_back(fc);
                 }
                 if (!ch.members.empty()) {
+                    // the backward launch with helper members (many streams)
+                    ch.bwd_split.push_back(ch.members.back());
+                    for (int k = last - 1; k >= c; --k) {
+                        CompPlan fc, hc;
+                        if (!lower_component(k, fused, fc, &hc)) return false;
+                        if (fc.bwd_phases.size() != 1 || !hc.has_bwd_program || hc.bwd_phases.size() != 1) { ch.bwd_split.clear(); break; }
+                        ch.bwd_split.push_back(hc);
+                        ch.bwd_split.push_back(fc);
+                    }
+                    if ((int)ch.bwd_split.size() > STEP_MAX_GROUPS) ch.bwd_split.clear();
                     for (int k = c; k <= last; ++k) P.comps[k].chain = (int)P.chains.size();
                     P.chains.push_back(ch);
                 }

@@ -51,7 +51,10 @@ enum { GA_BUF = 0, GA_FRAME_OFF, GA_DIM, GA_KIND, GA_AUX, GA_WORDS };
 //           be loaded early and cached
 //   CARRY   the value this same program computed in the previous step (aux = its result slot):
 //           may be kept in a register instead of being re-loaded
-enum { GA_KIND_FRAMES = 0, GA_KIND_ACC = 1, GA_KIND_STATIC = 2, GA_KIND_CARRY = 3 };
+//   POLLED  written by another component of the same launch, element by element for this frame
+//           (a sum that a helper member of a chain computes ahead of time): load it coherently
+//           and repeat while it shows the sentinel
+enum { GA_KIND_FRAMES = 0, GA_KIND_ACC = 1, GA_KIND_STATIC = 2, GA_KIND_CARRY = 3, GA_KIND_POLLED = 4 };
 enum { IV_W_OFF = 0, IV_DIM, IV_WORDS };
 enum { MO_PACKED = 0, MO_C, MO_WORDS };                         // packed = opcode | dst << 8 | a << 16 | b << 24
 enum { ST_BUF = 0, ST_SLOT, ST_DIM, ST_FLAGS, ST_WORDS };         // flags bit 0: other workgroups poll this buffer

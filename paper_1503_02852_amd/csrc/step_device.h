@@ -1279,7 +1279,8 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 //   tiles), D (register sets of chunks), CMAX, ACCS (row stride of an accumulator tile), NW
 //   (wavefronts), NCH (chunks of all sources), CLATE (first chunk that holds the previous step's
 //   own values), NRW (weight quads in registers); bool FLAT (the chunk sequence is unrolled whole),
-//   XB; unsigned REGMASK; constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task)
+//   XB, HELPER (a chain's helper member: its program only stores the sums of its products, which
+//   another member's program polls element by element); unsigned REGMASK; constexpr K(s), ngr(s) (groups of D chunks of source s), blk(s, task)
 //   (row block of the task in source s, -1: none), used(s, nt), csrc(c) / ck0(c) (source and first
 //   column of chunk c), widx(c * 16 + nt) (register index of a weight quad).
 // =============================================================================================
@@ -1503,7 +1504,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
 #pragma unroll
         for (int q = 0; q < PH::NST; ++q) {
             xbase[q] = nullptr; xvrun[q] = WAVE_NO_STORE;
-            if (!PH::stshared(q)) continue;
+            if (!PH::stshared(q) || !PH::sttwin(q)) continue;
             const int dim = suni(st[q * ST_WORDS + ST_DIM]);
             xbase[q] = suni_ptr(((cbufs_t)a.buf_ptr)[a.twin_base + suni(st[q * ST_WORDS + ST_BUF])]);
             if (r.sptr[q] != nullptr) {
@@ -1542,7 +1543,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
         if (wave_items)
             step_static_for<0, PH::NG>([&](auto gg) {
                 constexpr int g = decltype(gg)::value;
-                if (PH::gkind(g) == GA_KIND_FRAMES) s[g] = gather_at(gg, t + r.goff[g]);
+                if (PH::gkind(g) == GA_KIND_FRAMES || PH::gkind(g) == GA_KIND_POLLED) s[g] = gather_at(gg, t + r.goff[g]);
             });
         RNNG_STAMP(1);
 
@@ -1557,6 +1558,25 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
             // (a twin's frame has the same size, and its stream tiles are as large as 16 rows)
             const float* g = ((cbufs_t)a.buf_ptr)[(MM::XB ? a.twin_base : 0) + suni(sc.buf)] + ((size_t)(in_window ? frame : 0) * a.N + n0) * MM::K(sidx);
             rs[sidx] = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(g), 0, in_window ? N * MM::K(sidx) * 4 : 0, STEP_RSRC_FLAGS);
+        }
+        // A helper member has no values of its own to wait for and would otherwise poll each frame
+        // of its sources while the producing member's stores are still under way, which slows that
+        // member's own exchange.  It therefore starts a step only when the frame of the NEXT step
+        // shows its first value: the producers have then consumed, hence seen, all of this step's
+        // frame, and every load below succeeds at once.  (The last step has no next frame.)
+        if constexpr (MM::HELPER) {
+            if (step + 1 < nsteps) {
+                const StepSource& sc = sh.lay.src[0];
+                const int frame = step_frame(a, step + 1) + suni(sc.frame_off);
+                if (frame >= 0 && frame < T) {
+                    const float* p = ((cbufs_t)a.buf_ptr)[(MM::XB ? a.twin_base : 0) + suni(sc.buf)] + ((size_t)frame * a.N + n0) * MM::K(0);
+                    int spins = 0;
+                    while (__float_as_uint(load_coherent(p)) == STEP_SENTINEL && !dead) {
+                        if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                        __builtin_amdgcn_s_sleep(8);
+                    }
+                }
+            }
         }
         // ---- chunk pipeline ----
         // The sources' columns form one sequence of chunks of CW columns (a source's last chunk
@@ -1761,11 +1781,24 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                     s[g] = r.gptr[g] != nullptr ? x : 0.0f;
                 }
             });
+            // sums that a helper member of the launch computes ahead of this member: loaded at the
+            // step's start, here they have normally arrived (the wavefront repeats while one is missing)
+            step_static_for<0, PH::NG>([&](auto gg) {
+                constexpr int g = decltype(gg)::value;
+                if constexpr (PH::gkind(g) == GA_KIND_POLLED) {
+                    int spins = 0;
+                    while (__builtin_amdgcn_ballot_w64(__float_as_uint(s[g]) == STEP_SENTINEL) != 0 && !dead) {
+                        if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                        s[g] = gather_at(gg, t + r.goff[g]);
+                    }
+                }
+            });
             PH::ops(s);
 #pragma unroll
             for (int q = 0; q < PH::NST; ++q) {
-                wave_store<PH, MStore>(r, q, s[PH::stslot(q)], PH::stshared(q) && !MM::XB ? 2 : 0, a);
-                if (MM::XB && PH::stshared(q)) {
+                const bool twin = MM::XB && PH::stshared(q) && PH::sttwin(q);
+                wave_store<PH, MStore>(r, q, s[PH::stslot(q)], PH::stshared(q) && !twin ? 2 : 0, a);
+                if (twin) {
                     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xbase[q]), 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
                     __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(s[PH::stslot(q)]), rx, (int)xvrun[q], 0, STEP_COHERENT_AUX);
                 }

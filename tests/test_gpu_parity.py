@@ -231,6 +231,19 @@ def test_lstm_stack_with_many_streams_runs_side_by_side(layers, N):
     run_both(wl.make_workload("lstm_stack_streams", spec, T=15, N=N, seed=31, scale=0.4, bias_scale=0.3, masked_fraction=0.2))
 
 
+@pytest.mark.parametrize("helpers", ["1", "0"])
+@pytest.mark.parametrize("layers,N", [([64, 32], 32), ([128, 128], 16), ([32, 64], 48)])
+def test_two_layer_stack_backward_with_and_without_helper_members(monkeypatch, layers, N, helpers):
+    """A two-layer stack at a multiple of 16 streams: in the backward launch the products of the
+    connections between the layers are computed by a helper member on otherwise idle compute units
+    and polled element by element by the lower layer's program (RNNG_CHAIN_HELPERS = 0: contracted
+    by the lower layer itself)."""
+    monkeypatch.setenv("RNNG_CHAIN_HELPERS", helpers)
+    spec = wl.lstm_net(12, layers, 5)
+    run_both(wl.make_workload("lstm_stack_helpers", spec, T=17, N=N, seed=35, scale=0.3, bias_scale=0.3, masked_fraction=0.2),
+             label=f"stack {layers}, N={N}, RNNG_CHAIN_HELPERS={helpers}")
+
+
 @pytest.mark.parametrize("chain", ["1", "0"])
 @pytest.mark.parametrize("N", [2, 24])
 def test_stack_in_one_launch_and_layers_one_after_another(monkeypatch, chain, N):
