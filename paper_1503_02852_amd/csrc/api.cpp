@@ -518,6 +518,20 @@ bool wave_store_window_ok(const rnn_graph* g) {
     }
     return true;
 }
+// The matrix-core build also loads its element-wise inputs through the window: every tensor that
+// the phases' programs gather from must lie in the workspace too (not in a tensor of the caller).
+bool gathers_in_workspace(const rnn_graph* g, const std::vector<PhasePlan>& phases) {
+    for (const PhasePlan& ph : phases) {
+        const int32_t* pw = g->plan.words.data() + ph.prog_off;
+        for (int i = 0; i < pw[PG_NGATHER]; ++i) {
+            const int32_t* ga = pw + PG_HEADER_WORDS + i * GA_WORDS;
+            if (ga[GA_KIND] == GA_KIND_ACC) continue;
+            const char* p = reinterpret_cast<const char*>(g->buf(ga[GA_BUF]));
+            if (g->caller_input(ga[GA_BUF]) || p == nullptr || p < g->ws || p >= g->ws + g->layout.total) return false;
+        }
+    }
+    return true;
+}
 const std::string& windowed(const std::string& source, std::string& cache) {
     if (cache.empty()) cache = "#define RNNG_STORE_WINDOW 1\n" + source;
     return cache;
@@ -597,7 +611,9 @@ StepRun run_phases(rnn_graph* g, int comp, bool backward, hipStream_t s, int t0,
     if (have_jit) {
         hipError_t fe = fill_shared(g, backward ? cp.bwd_shared_bufs : cp.fwd_shared_bufs, jc->wave, t0, t1, s, jc->blocked);
         if (fe != hipSuccess) return step_error(fe, "sentinel fill");
-        const bool window = jc->wave && wave_store_window_ok(g);
+        // (matrix-core build: measured per direction; backward loops, with more stores and loads per
+        // step, gain 3 %, forward loops lose 4 to 6 %)
+        const bool window = (jc->wave || (jc->mstep && !jc->two_d && backward && gathers_in_workspace(g, cp.bwd_phases))) && wave_store_window_ok(g);
         std::string why;
         hipFunction_t fn = jit_step_function(window ? windowed(jc->source, jc->source_window) : jc->source, &why, !g->no_alloc,
                                              jc->mstep && !jc->two_d ? MSTEP_LDS_LIMIT : STEP_LDS_LIMIT);
@@ -681,7 +697,8 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     if (!g->use_jit || !jit_available()) return none;
     rnn_graph::ChainChoice& cc = const_cast<rnn_graph::ChainChoice&>(g->chain_choice(chain, backward, g->N));
     if (cc.source.empty() || !wave_tensor_sizes_ok(g)) return none;
-    const bool window = !cc.mstep && wave_store_window_ok(g);
+    bool window = wave_store_window_ok(g) && (!cc.mstep || backward);      // (matrix-core build: backward launches only, as for single components)
+    if (cc.mstep && window) for (const CompPlan& m : rnn_graph::chain_members(ch, cc)) window = window && gathers_in_workspace(g, m.bwd_phases);
     std::string why;
     hipFunction_t fn = jit_step_function(window ? windowed(cc.source, cc.source_window) : cc.source, &why, !g->no_alloc,
                                          cc.mstep ? MSTEP_LDS_LIMIT : STEP_LDS_LIMIT);

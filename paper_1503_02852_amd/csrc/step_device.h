@@ -1341,7 +1341,11 @@ RNNG_HD inline void compute_mstep_layout(const StepLayout& lay, int N, int nw, u
     m.ok = 1;
 }
 
-struct MStore { static constexpr bool SW = false; };      // stores through one descriptor per stored tensor
+// With RNNG_STORE_WINDOW (the workspace fits 2 GiB) the element-wise loads and stores of the
+// matrix-core build all go through ONE descriptor over the workspace, else through one per tensor:
+// with 13 stores and 8 loads per step the descriptors' scalar work was a third of the
+// element-wise part's instructions and spilled scalar registers.
+struct MStore { static constexpr bool SW = RNNG_STORE_WINDOW != 0; };
 // (leaner than StepShared: one phase, so that more of the 160 KiB is left for weight rows)
 struct MShared { StepLayout lay; unsigned iteminfo[1][STEP_THREADS]; MLayout ml; unsigned retried[2]; };
 
@@ -1494,6 +1498,11 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     // branch, so the compiler can count what is in flight instead of waiting for all of it.
     wave_store_setup<PH, MStore>(r, a);
     wave_carry_init<PH>(r, a);
+    if constexpr (MStore::SW) {      // gather offsets relative to the window (parked lanes stay outside)
+#pragma unroll
+        for (int g = 0; g < PH::NG; ++g)
+            if (PH::gkind(g) != GA_KIND_ACC && r.gvoff[g] != 0xC0000000u) r.gvoff[g] += (unsigned)((r.gbase[g] - a.store_base) * 4);
+    }
     // tile-blocked exchange: the exchanged values are stored a second time, written through, into
     // the twins (the row-major copies, which nobody polls, are then stored plainly)
     const float* xbase[PH::NST > 0 ? PH::NST : 1];
@@ -1511,6 +1520,7 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 const int i = (int)(r.sptr[q] - r.sbase[q]) - r.n * dim;      // this thread's unit
                 const int off = ((r.n >> 4) * (dim >> 4) + (i >> 4)) * 256 + ((((i & 15) >> 2) << 4) + (r.n & 15)) * 4 + (i & 3);
                 xvrun[q] = (unsigned)((off + step_frame(a, 0) * r.sstride[q]) * 4);
+                if (MStore::SW) xvrun[q] += (unsigned)((xbase[q] - a.store_base) * 4);
             }
         }
     }
@@ -1521,7 +1531,8 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
     auto gather_at = [&](auto gg, int frame) -> float {
         constexpr int g = decltype(gg)::value;
         const bool in_window = frame >= 0 && frame < T;
-        const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(r.gbase[g]), 0, T * r.gstride[g] * 4, STEP_RSRC_FLAGS);
+        const __amdgpu_buffer_rsrc_t rg = MStore::SW ? __builtin_amdgcn_make_buffer_rsrc(a.store_base, 0, (int)a.store_bytes, STEP_RSRC_FLAGS)
+                                                     : __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(r.gbase[g]), 0, T * r.gstride[g] * 4, STEP_RSRC_FLAGS);
         const int off = in_window ? (int)(r.gvoff[g] + (unsigned)(frame * r.gstride[g] * 4)) : (int)WAVE_NO_STORE;
         return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rg, off, 0, PH::gkind(g) == GA_KIND_STATIC ? 0 : STEP_COHERENT_AUX));
     };
@@ -1799,7 +1810,8 @@ __device__ __forceinline__ void mstep_kernel_body(const StepArgs& a, MShared& ms
                 const bool twin = MM::XB && PH::stshared(q) && PH::sttwin(q);
                 wave_store<PH, MStore>(r, q, s[PH::stslot(q)], PH::stshared(q) && !twin ? 2 : 0, a);
                 if (twin) {
-                    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xbase[q]), 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
+                    const __amdgpu_buffer_rsrc_t rx = MStore::SW ? __builtin_amdgcn_make_buffer_rsrc(a.store_base, 0, (int)a.store_bytes, STEP_RSRC_FLAGS)
+                                                                 : __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xbase[q]), 0, a.T * r.sstride[q] * 4, STEP_RSRC_FLAGS);
                     __builtin_amdgcn_raw_buffer_store_b32(step_shared_bits(s[PH::stslot(q)]), rx, (int)xvrun[q], 0, STEP_COHERENT_AUX);
                 }
             }
