@@ -9,6 +9,8 @@
 // staged through LDS in k-major order ([k][m], row stride 132 floats) so that the MFMA operand
 // fetch of a wavefront is a conflict-free ds_read_b32 for both operand orientations; global
 // loads for chunk c+1 are in flight while chunk c is multiplied.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace rnng {
@@ -92,8 +94,28 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(const GemmGroup g) {
     const int split = blockIdx.z - pi * g.split_k;
     const GemmProblem& P = g.p[pi];
     const int tiles_m = (P.M + BM - 1) / BM, tiles_n = (P.N + BN - 1) / BN;
-    if ((int)blockIdx.x >= tiles_m * tiles_n) return;
-    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x - tm * tiles_n;
+    const int n_tiles = tiles_m * tiles_n;
+    if ((int)blockIdx.x >= n_tiles) return;
+    // Which tile a workgroup takes.  Workgroups go to the eight XCDs in turn and each XCD has an
+    // L2 of its own, so workgroup b takes tile start(b % 8) + b / 8: every XCD works on one
+    // consecutive range of tiles.  Inside the range the tiles run down groups of g.group_m row
+    // blocks before they move to the next column block, so that the workgroups that are resident
+    // together on an XCD share both A panels and B panels in its L2.
+    int tile = blockIdx.x;
+    const int GM = g.group_m;
+    if (GM > 0) {
+        const int q = n_tiles / 8, r = n_tiles - 8 * q, x = tile & 7;
+        tile = x * q + (x < r ? x : r) + (tile >> 3);
+    }
+    int tm, tn;
+    if (GM > 1) {
+        const int per_group = GM * tiles_n, group = tile / per_group, first_m = group * GM;
+        const int gsz = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+        const int in_group = tile - group * per_group;
+        tn = in_group / gsz; tm = first_m + in_group - tn * gsz;
+    } else {
+        tm = tile / tiles_n; tn = tile - tm * tiles_n;
+    }
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -172,10 +194,13 @@ hipError_t launch_gemm_group(GemmMode mode, const GemmGroup& g, hipStream_t stre
     }
     if (max_tiles == 0) return hipSuccess;
     dim3 grid(max_tiles, 1, g.n_problems * g.split_k), block(NTHREADS);
+    static const int group_m = [] { const char* env = std::getenv("RNNG_GEMM_GROUP_M"); return env ? std::atoi(env) : 8; }();
+    GemmGroup gg = g;
+    gg.group_m = group_m < 0 ? 0 : group_m;
     switch (mode) {
-        case GEMM_NT: hipLaunchKernelGGL((gemm_kernel<true, true>), grid, block, 0, stream, g); break;
-        case GEMM_NN: hipLaunchKernelGGL((gemm_kernel<true, false>), grid, block, 0, stream, g); break;
-        case GEMM_TN: hipLaunchKernelGGL((gemm_kernel<false, false>), grid, block, 0, stream, g); break;
+        case GEMM_NT: hipLaunchKernelGGL((gemm_kernel<true, true>), grid, block, 0, stream, gg); break;
+        case GEMM_NN: hipLaunchKernelGGL((gemm_kernel<true, false>), grid, block, 0, stream, gg); break;
+        case GEMM_TN: hipLaunchKernelGGL((gemm_kernel<false, false>), grid, block, 0, stream, gg); break;
     }
     return hipGetLastError();
 }

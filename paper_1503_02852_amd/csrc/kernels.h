@@ -29,6 +29,7 @@ struct GemmGroup {
     int n_problems;
     int split_k;      // >1: K is split over blockIdx.z and results are added atomically (C must be pre-zeroed)
     int accumulate;   // 1: C += result instead of C = result (ignored when split_k > 1)
+    int group_m;      // set by launch_gemm_group: tile order (see the kernel); 0: row by row, no XCD ranges
 };
 enum GemmMode {
     GEMM_NT = 0,   // A K-contiguous, B K-contiguous      (forward:  Y_dst = Y_src W^T)
