@@ -15,7 +15,8 @@ extern "C" {
 /* Which build of the persistent recurrent-step kernel (Section 3.1, sequential part) ran the step
  * loop of the recurrent node that contains `node` at its last launch in the given direction
  * (backward = 0 / 1); RNN_BUILD_NONE if the node is in no recurrent node or nothing ran yet.
- * RNN_BUILD_CHAIN is or-ed in when stacked recurrent nodes shared one launch. */
+ * RNN_BUILD_CHAIN is or-ed in when stacked recurrent nodes shared one launch (RNN_BUILD_HELPERS too if
+ * that launch had helper members). */
 enum {
     RNN_BUILD_NONE = 0,
     RNN_BUILD_WAVE = 1,         /* run-time specialised, weights in registers (few streams) */
@@ -26,7 +27,9 @@ enum {
     RNN_BUILD_PER_FRAME = 6,    /* no persistent kernel: launches per frame */
     RNN_BUILD_STREAMING = 7,    /* run-time specialised, weights streamed from memory every step
                                    (layers too wide to keep on chip) */
-    RNN_BUILD_CHAIN = 16
+    RNN_BUILD_CHAIN = 16,
+    RNN_BUILD_HELPERS = 32      /* or-ed in with RNN_BUILD_CHAIN: the launch had helper members, which took the
+                                   products of the connections between the stacked nodes (backward, many streams) */
 };
 int rnn_step_build(const rnn_graph* g, int32_t node, int32_t backward, int32_t* build);
 

@@ -236,6 +236,12 @@ class Graph:
         _check(self.lib.rnn_step_build(self.handle, node, 1 if backward else 0, C.byref(b)))
         return BUILD_NAMES[b.value & 15], bool(b.value & 16)
 
+    def step_build_has_helpers(self, node, backward=True):
+        """True if the chain launch that last ran the recurrent node of `node` had helper members."""
+        b = C.c_int32()
+        _check(self.lib.rnn_step_build(self.handle, node, 1 if backward else 0, C.byref(b)))
+        return bool(b.value & 32)
+
     def plan_work(self, T, N):
         fl, by = (C.c_int64 * 5)(), (C.c_int64 * 2)()
         _check(self.lib.rnn_plan_work(self.handle, T, N, fl, by))

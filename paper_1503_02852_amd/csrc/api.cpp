@@ -737,7 +737,7 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     if (!launch_fits_device(g, participants, why)) return step_error(hipSuccess, why);
     hipError_t e = jit_launch(fn, a, lp, s);
     if (e != hipSuccess) { (void)hipGetLastError(); return step_error(e, "specialised chain step kernel launch"); }
-    for (int c = ch.first; c <= ch.last; ++c) g->served[c][backward ? 1 : 0] = (cc.mstep ? RNN_BUILD_MATRIX : RNN_BUILD_WAVE) | RNN_BUILD_CHAIN;
+    for (int c = ch.first; c <= ch.last; ++c) g->served[c][backward ? 1 : 0] = (cc.mstep ? RNN_BUILD_MATRIX : RNN_BUILD_WAVE) | RNN_BUILD_CHAIN | (cc.split ? RNN_BUILD_HELPERS : 0);
     g->prof.end(prof, 1, s);
     StepRun ok;
     return ok;

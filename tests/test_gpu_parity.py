@@ -240,8 +240,12 @@ def test_two_layer_stack_backward_with_and_without_helper_members(monkeypatch, l
     by the lower layer itself)."""
     monkeypatch.setenv("RNNG_CHAIN_HELPERS", helpers)
     spec = wl.lstm_net(12, layers, 5)
-    run_both(wl.make_workload("lstm_stack_helpers", spec, T=17, N=N, seed=35, scale=0.3, bias_scale=0.3, masked_fraction=0.2),
-             label=f"stack {layers}, N={N}, RNNG_CHAIN_HELPERS={helpers}")
+    win, _ = run_both(wl.make_workload("lstm_stack_helpers", spec, T=17, N=N, seed=35, scale=0.3, bias_scale=0.3, masked_fraction=0.2),
+                      label=f"stack {layers}, N={N}, RNNG_CHAIN_HELPERS={helpers}")
+    rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, True) == ("matrix", True) for k in rec)
+    assert all(win.g.step_build_has_helpers(k, True) == (helpers == "1") for k in rec)
+    assert not any(win.g.step_build_has_helpers(k, False) for k in rec)
 
 
 @pytest.mark.parametrize("chain", ["1", "0"])
