@@ -549,12 +549,17 @@ hipError_t fill_shared(rnn_graph* g, const std::vector<int>& bufs, bool with_bun
             const int bi = g->plan.bundle_of[b];
             if (bi >= 0 && std::find(list.begin(), list.end(), g->plan.bundles[bi].ebuf) == list.end()) list.push_back(g->plan.bundles[bi].ebuf);
         }
+    FillRanges fr; fr.count = 0;
     for (int b : list) {
-        const int64_t fr = (int64_t)g->N * g->plan.buf_dim[b];
-        hipError_t e = launch_fill_sentinel(g->buf(b) + t0 * fr, (t1 - t0) * fr, s);
-        if (e != hipSuccess) return e;
+        const int64_t frame = (int64_t)g->N * g->plan.buf_dim[b];
+        fr.p[fr.count] = g->buf(b) + t0 * frame; fr.n[fr.count] = (t1 - t0) * frame;
+        if (++fr.count == FILL_MAX_RANGES) {
+            hipError_t e = launch_fill_sentinel_ranges(fr, s);
+            if (e != hipSuccess) return e;
+            fr.count = 0;
+        }
     }
-    return hipSuccess;
+    return launch_fill_sentinel_ranges(fr, s);
 }
 
 // The workgroups of a persistent step launch wait for each other's results, so every one that takes
@@ -707,8 +712,11 @@ StepRun run_chain(rnn_graph* g, int chain, bool backward, hipStream_t s, int t0,
     const int T = g->Ti(), N = g->N;
     const int prof = g->prof.begin(backward ? RNN_PROF_STEP_BWD : RNN_PROF_STEP_FWD, s);
     const std::vector<CompPlan>& members = rnn_graph::chain_members(ch, cc);
-    for (const CompPlan& m : members) {
-        hipError_t e = fill_shared(g, backward ? m.bwd_shared_bufs : m.fwd_shared_bufs, !cc.mstep, t0, t1, s, cc.blocked);
+    {
+        std::vector<int> exchanged;      // of all members: one fill launch
+        for (const CompPlan& m : members)
+            for (int b : backward ? m.bwd_shared_bufs : m.fwd_shared_bufs) exchanged.push_back(b);
+        hipError_t e = fill_shared(g, exchanged, !cc.mstep, t0, t1, s, cc.blocked);
         if (e != hipSuccess) return step_error(e, "sentinel fill");
     }
     StepLaunchPlan lp; lp.ok = true; lp.G = 32; lp.NB = step_nb_for(N); lp.lds_bytes = 0; lp.xcd_stride = 8;

@@ -98,5 +98,9 @@ hipError_t launch_recurrent_steps(const PlanView& pv, const StepLaunchPlan& lp, 
                                   hipStream_t stream);
 // Fills n floats with the "not yet written" bit pattern the step kernel's consumers wait on.
 hipError_t launch_fill_sentinel(float* p, int64_t n, hipStream_t stream);
+// The same for up to FILL_MAX_RANGES ranges with one launch (a step launch's exchanged tensors).
+constexpr int FILL_MAX_RANGES = 16;
+struct FillRanges { float* p[FILL_MAX_RANGES]; long long n[FILL_MAX_RANGES]; int count; };
+hipError_t launch_fill_sentinel_ranges(const FillRanges& r, hipStream_t stream);
 
 }  // namespace rnng

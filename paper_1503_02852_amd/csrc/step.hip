@@ -97,6 +97,13 @@ __global__ __launch_bounds__(256) void fill_bits_kernel(unsigned* __restrict__ p
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += 256LL * gridDim.x) p[i] = v;
 }
 
+// blockIdx.y: the range
+__global__ __launch_bounds__(256) void fill_ranges_kernel(const FillRanges r, unsigned v) {
+    unsigned* __restrict__ p = reinterpret_cast<unsigned*>(r.p[blockIdx.y]);
+    const long long n = r.n[blockIdx.y];
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += 256LL * gridDim.x) p[i] = v;
+}
+
 }  // namespace
 
 int step_nb_for(int N) { return N <= 1 ? 1 : N <= 2 ? 2 : N <= 4 ? 4 : N <= 8 ? 8 : 0; }
@@ -172,6 +179,18 @@ hipError_t launch_fill_sentinel(float* p, int64_t n, hipStream_t stream) {
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(fill_bits_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, reinterpret_cast<unsigned*>(p),
                        (long long)n, STEP_SENTINEL);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_sentinel_ranges(const FillRanges& r, hipStream_t stream) {
+    if (r.count <= 0) return hipSuccess;
+    if (r.count > FILL_MAX_RANGES) return hipErrorInvalidValue;
+    long long most = 0;
+    for (int i = 0; i < r.count; ++i) most = r.n[i] > most ? r.n[i] : most;
+    if (most <= 0) return hipSuccess;
+    long long blocks = (most + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_ranges_kernel, dim3((unsigned)blocks, (unsigned)r.count), dim3(256), 0, stream, r, STEP_SENTINEL);
     return hipGetLastError();
 }
 
