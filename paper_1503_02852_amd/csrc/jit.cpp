@@ -195,6 +195,17 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     for (int t = 0; t < ph.n_tasks; ++t) for (int e = 0; e < ph.task[t].n_edges; ++e) per_unit += F[ph.task[t].e[e].src];
     const int RW = UW * per_unit;
     if (RW > 384) return false;
+    // Rows of more than 1,024 elements (or very wide source sets): the weights, the source values,
+    // the partial sums and the polling registers of a lane together must fit the 512 registers of a
+    // wavefront that has a SIMD to itself with room to spare, else the kernel spills (a 2,048-wide
+    // LSTM layer forward: fine at 1 and 2 streams, 257 registers spilled at 4).
+    bool long_rows = XF * NB > 96;
+    for (int s = 0; s < lay.n_sources; ++s) long_rows = long_rows || F[s] > 16;
+    if (long_rows) {
+        int polled_words = 0;
+        for (int s = 0; s < lay.n_sources; ++s) polled_words += NB * lay.src[s].k_len;
+        if (RW + XF * NB + 2 * UW * ph.n_tasks * NB + (polled_words + 255) / 256 > 440) return false;
+    }
     o << "namespace " << ns << " {\n";
     emit_phase_descriptor(o, P, phases[0], 0, 0);
     auto emit_switch = [&](const char* name, const char* arg, const std::vector<std::pair<int, int>>& cases) {

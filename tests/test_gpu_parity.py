@@ -540,6 +540,15 @@ def test_register_build_with_long_weight_rows(name):
     assert rec and all(win.g.step_build(k, False)[0] == "wave" for k in rec)
 
 
+def test_a_2048_wide_layer_at_four_streams_streams_its_weights():
+    """At four streams the weights, source values and partial sums of a 2,048-wide LSTM layer no
+    longer fit a lane's registers: both directions take the streaming build."""
+    w = wl.make_workload("lstm_2048_n4", wl.lstm_net(12, [2048], 8), T=5, N=4, seed=78, scale=0.04, bias_scale=0.3)
+    win, ref = run_both(w, label="2,048-wide layer, N=4")
+    rec = [k for k in range(len(w.spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, b)[0] == "streaming" for k in rec for b in (False, True))
+
+
 # ---- the streaming step kernel (weights read from memory every step) on small and ragged shapes ----
 
 @pytest.mark.parametrize("case", ["lstm_n1", "lstm_n3_ragged", "elman_n8", "generalized_n2", "stack_n1", "gates_n5",
