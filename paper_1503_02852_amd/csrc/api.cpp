@@ -319,26 +319,56 @@ struct rnn_graph {
     // workgroups shared among the members).
     struct ChainChoice {
         std::string source, source_window; std::vector<int> G, J; bool mstep = false, blocked = false; size_t lds_bytes = 0; int threads = 256;
-        bool split = false;      // the backward launch with helper members (ChainPlan::bwd_split)
+        bool split = false, backward = false;      // split: the launch with helper members (ChainPlan::fwd_split / bwd_split)
     };
-    static const std::vector<CompPlan>& chain_members(const ChainPlan& ch, const ChainChoice& cc) { return cc.split ? ch.bwd_split : ch.members; }
+    static const std::vector<CompPlan>& chain_members(const ChainPlan& ch, const ChainChoice& cc) {
+        return !cc.split ? ch.members : cc.backward ? ch.bwd_split : ch.fwd_split;
+    }
     std::map<std::tuple<int, bool, int>, ChainChoice> chain_choices;
     bool use_chains = true;
+    // Weights-in-registers launches: a helper group pays in the backward launch, where it takes
+    // half of the lower layer's polled sources and multiply-adds, if those are a noticeable part of
+    // a step that is otherwise mostly exchange latency.  Measured, backward / forward step kernels
+    // with against without helper groups: charlm_n1 (128 multiply-adds per lane and step moved)
+    // 0.81 / 0.88 against 1.21 / 0.81 ms; speech_n1 (32 per lane) 1.13 / 1.37 against 1.04 / 0.92.
+    bool wave_helpers_pay(const std::vector<CompPlan>& members, bool backward, int N) const {
+        int min_fma = 100;
+        if (const char* env = std::getenv("RNNG_CHAIN_HELPER_MIN")) min_fma = std::atoi(env);
+        if (!backward) return false;
+        for (const CompPlan& m : members)
+            if (m.helper && m.step_weight_floats * step_nb_for(N) / (32 * 256) >= min_fma) return true;
+        return false;
+    }
     const ChainChoice& chain_choice(int chain, bool backward, int N) {
         const std::tuple<int, bool, int> key(chain, backward, N);
         auto it = chain_choices.find(key);
         if (it != chain_choices.end()) return it->second;
         ChainChoice c;
+        c.backward = backward;
         const ChainPlan& ch = plan.chains[chain];
+        // Helper members take the products of the connections between the stacked nodes
+        // (RNNG_CHAIN_HELPERS = 0: never; 1: in every launch that can have them; default: in the
+        // matrix-core backward launch and in weights-in-registers backward launches from
+        // RNNG_CHAIN_HELPER_MIN multiply-adds per lane and step on)
+        const char* envh = std::getenv("RNNG_CHAIN_HELPERS");
+        const bool helpers_off = envh && std::atoi(envh) == 0, helpers_all = envh && std::atoi(envh) == 1;
         if (use_jit && use_chains && force_step_G <= 0 && !prefer_streaming) {
-            for (const CompPlan& m : ch.members) {
-                int pick = 0;
-                for (int G : {32, 16, 8})
-                    if (!jit_wave_source(plan, m, backward, N, G).empty()) { pick = G; break; }
-                if (!pick) break;
-                c.G.push_back(pick);
+            for (int attempt = 0; attempt < 2 && c.source.empty(); ++attempt) {
+                c.split = attempt == 0 && !helpers_off && !(backward ? ch.bwd_split : ch.fwd_split).empty();
+                if (attempt == 0 && !c.split) continue;
+                const std::vector<CompPlan>& members = chain_members(ch, c);
+                c.G.clear();
+                for (const CompPlan& m : members) {
+                    int pick = 0;
+                    for (int G : {32, 16, 8})
+                        if (!jit_wave_source(plan, m, backward, N, G).empty()) { pick = G; break; }
+                    if (!pick) break;
+                    c.G.push_back(pick);
+                }
+                if (c.G.size() == members.size() && (!c.split || helpers_all || wave_helpers_pay(members, backward, N)))
+                    c.source = jit_chain_source(plan, members, backward, N, c.G);
             }
-            if (c.G.size() == ch.members.size()) c.source = jit_chain_source(plan, ch, backward, N, c.G);
+            if (c.source.empty()) c.split = false;
             if (c.source.empty() && N > 8 && force_step_J <= 0) {
                 // matrix-core members: each gets an equal share of the 256 workgroups; per member the
                 // most stream groups, then the most unit chunks that fit the share (as for a single
@@ -346,8 +376,7 @@ struct rnn_graph {
                 // Backward launches of a stack are bound by the matrix instructions of the members that
                 // also contract the later member's error terms, while compute units idle: helper members
                 // take those products (RNNG_CHAIN_HELPERS = 0: never).
-                const char* envh = std::getenv("RNNG_CHAIN_HELPERS");
-                c.split = backward && !ch.bwd_split.empty() && !(envh && std::atoi(envh) == 0);
+                c.split = backward && !ch.bwd_split.empty() && !helpers_off;
                 for (int attempt = 0; attempt < 2 && c.source.empty(); ++attempt) {
                     if (attempt == 1) { if (!c.split) break; c.split = false; }
                     const std::vector<CompPlan>& members = chain_members(ch, c);

@@ -170,13 +170,21 @@ std::vector<int> polled_buffers(const Plan& P, const CompPlan& cp, bool backward
         const int bi = P.bundle_of[lay.src[s].buf];
         out.push_back(bi >= 0 ? P.bundles[bi].ebuf : lay.src[s].buf);
     }
+    // and the sums of a helper member that the element-wise program polls
+    for (const PhasePlan& ph : backward ? cp.bwd_phases : cp.fwd_phases) {
+        const int32_t* pw = &P.words[ph.prog_off];
+        for (int g = 0; g < pw[PG_NGATHER]; ++g)
+            if (pw[PG_HEADER_WORDS + g * GA_WORDS + GA_KIND] == GA_KIND_POLLED) out.push_back(pw[PG_HEADER_WORDS + g * GA_WORDS + GA_BUF]);
+    }
     return out;
 }
 
 // group: index of this component in a chain launch (0 for a launch of its own); foreign: tensors
 // that the other groups of the chain poll.
+// *lds_bytes (optional): the static LDS of the group's body (the bodies of a chain launch are
+// inlined into one kernel, whose LDS is the sum over its groups).
 bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N, int G, const std::string& ns,
-                     int group, const std::vector<int>& foreign) {
+                     int group, const std::vector<int>& foreign, size_t* lds_bytes = nullptr) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
     const int NB = step_nb_for(N);
     if (phases.size() != 1 || NB == 0) return false;
@@ -195,6 +203,14 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     for (int t = 0; t < ph.n_tasks; ++t) for (int e = 0; e < ph.task[t].n_edges; ++e) per_unit += F[ph.task[t].e[e].src];
     const int RW = UW * per_unit;
     if (RW > 384) return false;
+    if (lds_bytes) {
+        const int32_t* pw = P.words.data() + phases[0].prog_off;
+        int n_static = 0, xs = 0;
+        for (int g = 0; g < pw[PG_NGATHER]; ++g) n_static += pw[PG_HEADER_WORDS + g * GA_WORDS + GA_KIND] == GA_KIND_STATIC;
+        for (int s = 0; s < lay.n_sources; ++s) xs += NB * 64 * ((F[s] + 3) / 4 * 4);
+        const size_t ring = (size_t)4 * 16 * std::max(1, n_static * UW * NB), tables = (size_t)STEP_MAX_PHASES * STEP_THREADS * 6;
+        *lds_bytes = 4 * (ring + 2 * (size_t)std::max(1, xs)) + sizeof(StepLayout) + tables;
+    }
     // Rows of more than 1,024 elements (or very wide source sets): the weights, the source values,
     // the partial sums and the polling registers of a lane together must fit the 512 registers of a
     // wavefront that has a SIMD to itself with room to spare, else the kernel spills (a 2,048-wide
@@ -399,18 +415,22 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
 // Chain of recurrent components side by side in one launch: group g (component members[g], with
 // G[g] workgroups on XCD g) runs its own wave-autonomous body; a member's full connections from
 // earlier members are ordinary polled sources, so the groups trail each other by about one step.
-std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G) {
+std::string jit_chain_source(const Plan& P, const std::vector<CompPlan>& members, bool backward, int N, const std::vector<int>& G) {
     std::ostringstream o;
     o << "#include \"step_device.h\"\nusing namespace rnng;\n";
-    const int n = (int)ch.members.size();
+    const int n = (int)members.size();
     if (n < 2 || n > STEP_MAX_GROUPS || (int)G.size() != n) return "";
+    size_t lds_total = 0;
     for (int g = 0; g < n; ++g) {
         std::vector<int> foreign;
         for (int h = 0; h < n; ++h)
             if (h != g)
-                for (int b : polled_buffers(P, ch.members[h], backward, N, G[h])) foreign.push_back(b);
-        if (G[g] > 32 || !emit_wave_group(o, P, ch.members[g], backward, N, G[g], "grp" + std::to_string(g), g, foreign)) return "";
+                for (int b : polled_buffers(P, members[h], backward, N, G[h])) foreign.push_back(b);
+        size_t lds = 0;
+        if (G[g] > 32 || !emit_wave_group(o, P, members[g], backward, N, G[g], "grp" + std::to_string(g), g, foreign, &lds)) return "";
+        lds_total += lds;
     }
+    if (lds_total > 158 * 1024) return "";      // of 160 KiB (three groups at 8 streams can exceed it)
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
          "    const int grp = blockIdx.x & 7, w = blockIdx.x >> 3;\n"

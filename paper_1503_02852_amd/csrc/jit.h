@@ -15,9 +15,10 @@ namespace rnng {
 std::string jit_step_source(const Plan& P, const CompPlan& cp, bool backward, int NB);
 // Same for the wave-autonomous variant with G workgroups; empty if the component is not eligible.
 std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, int N, int G);
-// Chain of recurrent components side by side in one launch, member g with G[g] <= 32 workgroups;
+// Chain of recurrent components side by side in one launch, member g with G[g] <= 32 workgroups
+// (members: a chain's members, or its launch with helper members: ChainPlan::fwd_split / bwd_split);
 // empty if a member is not eligible for the wave-autonomous variant.
-std::string jit_chain_source(const Plan& P, const ChainPlan& ch, bool backward, int N, const std::vector<int>& G);
+std::string jit_chain_source(const Plan& P, const std::vector<CompPlan>& members, bool backward, int N, const std::vector<int>& G);
 // Matrix-core variant for many streams; *lds_bytes receives the dynamic LDS size.
 // G unit chunks x J stream groups (N / J streams each).
 // *rows receives the accumulator rows per workgroup (tasks x units per chunk).

@@ -294,7 +294,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     const std::vector<GNode>& xn = P.xnodes;
     const std::vector<GEdge>& xe = P.xedges;
     const Schedule& S = P.xsched;
-    P.n_bufs = 6 * K;
+    P.n_bufs = 7 * K;
     P.buf_dim.assign(P.n_bufs, 0);
     P.buf_alloc.assign(P.n_bufs, 0);
     P.hist = 0;
@@ -306,7 +306,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         if (xn[xe[m].src].kind == NODE_INPUT && (xe[m].delay > 0 || xe[m].wkind != W_FULL)) P.input_staged[xe[m].src] = 1;
     }
     for (int k = 0; k < K; ++k) {
-        for (int b : {P.ybuf(k), P.dbuf(k), P.abuf(k), P.pbuf(k), P.qbuf(k), P.hbuf(k)}) P.buf_dim[b] = xn[k].dim;
+        for (int b : {P.ybuf(k), P.dbuf(k), P.abuf(k), P.pbuf(k), P.qbuf(k), P.hbuf(k), P.fbuf(k)}) P.buf_dim[b] = xn[k].dim;
         if (xn[k].kind != NODE_INPUT) P.buf_alloc[P.ybuf(k)] = P.buf_alloc[P.dbuf(k)] = 1;
         else if (P.input_staged[k]) P.buf_alloc[P.ybuf(k)] = 1;
     }
@@ -324,10 +324,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     // Lowers component c into cp.  fused[m] marks full connections between different recurrent
     // components that the step kernel evaluates itself (as if they were delayed connections of
     // the component) instead of taking them from a GEMM over all frames.
-    // helper (optional): the backward products of the fused connections go to a helper member
-    // instead (ChainPlan::bwd_split), which *helper receives; it stays without a backward program if
-    // the component has no such connection.
-    auto lower_component = [&](int c, const std::vector<char>& fused, CompPlan& cp, CompPlan* helper = nullptr) -> bool {
+    // fhelper / helper (optional): the forward / backward products of the fused connections go to
+    // helper members instead (ChainPlan::fwd_split / bwd_split), which *fhelper / *helper receive;
+    // one stays without a program if the component has no such connection in that direction.
+    auto lower_component = [&](int c, const std::vector<char>& fused, CompPlan& cp, CompPlan* helper = nullptr, CompPlan* fhelper = nullptr) -> bool {
         auto batched = [&](int m) { return S.edge_class[m] == EDGE_BATCHED && !fused[m]; };
         cp.recurrent = S.comp_recurrent[c] != 0;
         std::vector<int> members;
@@ -365,8 +365,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             std::map<int, int> slot;
             for (size_t i = 0; i < np.size(); ++i) slot[np[i]] = (int)i;
             std::vector<MvTaskH> tasks; std::vector<OpH> ops;
+            std::vector<MvTaskH> htasks; std::vector<OpH> hops; std::vector<int> hparts;
             for (int k : np) {
                 OpH o; o.dim = xn[k].dim; o.out_buf = P.ybuf(k); o.out_slot = slot[k];
+                MvTaskH htask; htask.n_out = xn[k].dim; htask.acc_buf = P.abuf(k);
                 o.post = xn[k].act == ACT_SIGMOID ? POST_SIGMOID : xn[k].act == ACT_TANH ? POST_TANH : xn[k].act == ACT_RELU ? POST_RELU : POST_NONE;
                 if (xn[k].has_bias) o.bias_off = (int)P.bias_off[k];
                 MvTaskH task; task.n_out = xn[k].dim; task.acc_buf = P.abuf(k);
@@ -375,7 +377,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     const GEdge& e = xe[m];
                     if (e.wkind == W_FULL) {
                         if (batched(m)) { o.pre_buf = shared_y[k] ? P.pbuf(k) : P.ybuf(k); o.pre_static = true; }
-                        else {
+                        else if (fhelper && fused[m]) {
+                            htask.edges.push_back(MvEdgeH{(int)full_off(m), xn[e.src].dim, 0, P.ybuf(e.src), -e.delay});
+                            fhelper->step_weight_floats += (int64_t)xn[k].dim * xn[e.src].dim;
+                        } else {
                             task.edges.push_back(MvEdgeH{(int)full_off(m), xn[e.src].dim, 0, P.ybuf(e.src), -e.delay});
                             cp.step_weight_floats += (int64_t)xn[k].dim * xn[e.src].dim;
                         }
@@ -388,7 +393,22 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                 }
                 if (xn[k].kind == NODE_MUL) o.terms.push_back(product);
                 if (!task.edges.empty()) { o.acc_buf = task.acc_buf; o.acc_task = (int)tasks.size(); tasks.push_back(task); P.buf_alloc[task.acc_buf] = 2; }
+                if (!htask.edges.empty()) {
+                    // the helper's program: sum of its products, stored where this program polls it
+                    o.polled_buf = P.fbuf(k);
+                    OpH ho; ho.dim = xn[k].dim; ho.out_buf = P.fbuf(k); ho.out_slot = (int)hops.size();
+                    ho.acc_buf = htask.acc_buf; ho.acc_task = (int)htasks.size();
+                    htasks.push_back(htask); hops.push_back(ho); hparts.push_back(P.pbuf(k));
+                    P.buf_alloc[htask.acc_buf] = 2; P.buf_alloc[P.fbuf(k)] = 1;
+                    fhelper->fwd_shared_bufs.push_back(P.fbuf(k));
+                }
                 ops.push_back(o);
+            }
+            if (fhelper && !hops.empty()) {
+                std::vector<char> hwritten(P.n_bufs, 0), hshared(P.n_bufs, 0);
+                for (const OpH& ho : hops) hwritten[ho.out_buf] = hshared[ho.out_buf] = 1;
+                if (!emit_phase(P, fhelper->fwd_phases, htasks, hops, hparts, hwritten, hshared, -1, err)) return false;
+                fhelper->recurrent = true; fhelper->helper = true; fhelper->has_fwd_program = true;
             }
             std::vector<int> part_bufs;
             for (int k : np) part_bufs.push_back(P.pbuf(k));
@@ -406,6 +426,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
             return off;
         };
         cp.fwd_desc_off = emit_desc(cp.fwd_phases);
+        if (fhelper && fhelper->has_fwd_program) fhelper->fwd_desc_off = emit_desc(fhelper->fwd_phases);
 
         // ---- backward ----
         if (cp.softmax_node >= 0 || cp.sqerr_node >= 0) return true;   // the output delta comes from the error-criterion kernel
@@ -436,7 +457,10 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     const int k = e.dst;
                     if (e.wkind == W_FULL) {
                         if (batched(m)) { o.pre_buf = shared_d[j] ? P.qbuf(j) : P.dbuf(j); o.pre_static = true; }
-                        else if (helper && fused[m]) htask.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
+                        else if (helper && fused[m]) {
+                            htask.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
+                            helper->step_weight_floats += (int64_t)xn[j].dim * xn[k].dim;
+                        }
                         else task.edges.push_back(MvEdgeH{(int)full_off(m), xn[k].dim, 1, P.dbuf(k), e.delay});
                         continue;
                     }
@@ -529,16 +553,24 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     ch.members.push_back(fc);
                 }
                 if (!ch.members.empty()) {
-                    // the backward launch with helper members (many streams)
-                    ch.bwd_split.push_back(ch.members.back());
-                    for (int k = last - 1; k >= c; --k) {
-                        CompPlan fc, hc;
-                        if (!lower_component(k, fused, fc, &hc)) return false;
-                        if (fc.bwd_phases.size() != 1 || !hc.has_bwd_program || hc.bwd_phases.size() != 1) { ch.bwd_split.clear(); break; }
-                        ch.bwd_split.push_back(hc);
-                        ch.bwd_split.push_back(fc);
+                    // the launches with helper members
+                    std::vector<CompPlan> split(last - c + 1), bh(last - c + 1), fh(last - c + 1);
+                    bool fok = true, bok = true;
+                    for (int k = c; k <= last; ++k) {
+                        const int i = k - c;
+                        if (!lower_component(k, fused, split[i], &bh[i], &fh[i])) return false;
+                        if (split[i].fwd_phases.size() != 1 || split[i].bwd_phases.size() != 1) fok = bok = false;
+                        if (k > c && (!fh[i].has_fwd_program || fh[i].fwd_phases.size() != 1)) fok = false;
+                        if (k < last && (!bh[i].has_bwd_program || bh[i].bwd_phases.size() != 1)) bok = false;
                     }
-                    if ((int)ch.bwd_split.size() > STEP_MAX_GROUPS) ch.bwd_split.clear();
+                    if (fok && 2 * (last - c) + 1 <= STEP_MAX_GROUPS) {
+                        ch.fwd_split.push_back(ch.members.front());
+                        for (int k = c + 1; k <= last; ++k) { ch.fwd_split.push_back(fh[k - c]); ch.fwd_split.push_back(split[k - c]); }
+                    }
+                    if (bok && 2 * (last - c) + 1 <= STEP_MAX_GROUPS) {
+                        ch.bwd_split.push_back(ch.members.back());
+                        for (int k = last - 1; k >= c; --k) { ch.bwd_split.push_back(bh[k - c]); ch.bwd_split.push_back(split[k - c]); }
+                    }
                     for (int k = c; k <= last; ++k) P.comps[k].chain = (int)P.chains.size();
                     P.chains.push_back(ch);
                 }

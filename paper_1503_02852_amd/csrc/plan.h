@@ -52,7 +52,7 @@ struct CompPlan {
     std::vector<int> fwd_shared_bufs, bwd_shared_bufs;
     int64_t step_weight_floats = 0;         // weights of all full connections inside the component
     int chain = -1;                         // index into Plan::chains if the component is a chain member
-    bool helper = false;                    // a helper member of a chain's backward launch (ChainPlan::bwd_split)
+    bool helper = false;                    // a helper member of a chain launch (ChainPlan::fwd_split / bwd_split)
 };
 
 // Consecutive recurrent components first..last whose step loops can run side by side in one
@@ -60,18 +60,19 @@ struct CompPlan {
 // chain members taken into the step loop (read with the sentinel protocol like a component's own
 // delayed connections) instead of into a GEMM over all frames.
 //
-// bwd_split (empty if not built) is a second lowering of the backward launch for many streams,
-// where a step is bound by its matrix instructions and a stack leaves compute units idle: the
-// products W^T ds of the connections between members are not added to the contraction of the
-// member they lead into; a helper member per such member (helper = true: a step program without
-// recurrence, only the backward direction) computes them from the later member's error terms as
-// soon as those appear and stores the sums into a tensor of its own (Plan::hbuf), which the
-// earlier member's program reads element by element (GA_KIND_POLLED).  Order: the last component,
-// then helper and split lowering of each earlier one.
+// fwd_split / bwd_split (empty if not built) are second lowerings of the two launches, in which
+// the products of the connections between members are not added to the contraction of the member
+// they lead into (a step of that member is bound by its arithmetic, while compute units idle): a
+// helper member per such member (helper = true: a step program without recurrence, one direction
+// only) computes them from the other member's values as soon as those appear and stores the sums
+// into a tensor of its own (Plan::fbuf forward, Plan::hbuf backward), which the member's program
+// reads element by element (GA_KIND_POLLED).  Order forward: the first component, then helper and
+// split lowering of each later one; backward: the last component, then helper and split lowering
+// of each earlier one.
 struct ChainPlan {
     int first = 0, last = 0;
     std::vector<CompPlan> members;
-    std::vector<CompPlan> bwd_split;
+    std::vector<CompPlan> fwd_split, bwd_split;
 };
 
 // Exchange bundle: up to four equally wide tensors that one step program stores and other
@@ -96,7 +97,7 @@ struct Plan {
     // buffers: y of exec node k -> k; ds of k -> K + k; matrix-vector accumulator of k -> 2K + k;
     // batched pre-activation of k kept apart from y_k -> 3K + k, likewise for ds_k -> 4K + k
     // (used when y_k / ds_k is read by other workgroups during the step loop); the sums that a
-    // chain's helper member hands to the backward program of k -> 5K + k
+    // chain's helper member hands to the backward program of k -> 5K + k, to the forward program -> 6K + k
     int n_bufs = 0;
     std::vector<int> buf_dim;
     std::vector<char> buf_alloc;            // 0 not in the workspace, 1 [T][N][dim], 2 [N][dim], 3 a tile-blocked twin (below)
@@ -136,6 +137,7 @@ struct Plan {
     int pbuf(int k) const { return 3 * (int)xnodes.size() + k; }
     int qbuf(int k) const { return 4 * (int)xnodes.size() + k; }
     int hbuf(int k) const { return 5 * (int)xnodes.size() + k; }
+    int fbuf(int k) const { return 6 * (int)xnodes.size() + k; }
 };
 
 // Returns false and a reason on an invalid graph.

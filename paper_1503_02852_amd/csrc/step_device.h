@@ -1128,7 +1128,8 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
                 // idle lanes read a valid (unused) ring entry instead of branching around the load
                 const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
                 s[g] = ring[js * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
-            } else if (PH::gkind(g) == GA_KIND_FRAMES) {
+            } else if (PH::gkind(g) == GA_KIND_FRAMES || PH::gkind(g) == GA_KIND_POLLED) {
+                // (POLLED: a helper group's sum for this frame; it runs ahead, the value is checked below)
                 const int frame = t + r.goff[g];
                 float v = 0.0f;
                 if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
@@ -1213,6 +1214,19 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
         if (PH::gkind(g) == GA_KIND_ACC) s[g] = acc[PH::gaux(g)];
+    // sums of a helper group: normally there since the step's start; the wavefront repeats the
+    // load while one of its lanes still sees the sentinel
+#pragma unroll
+    for (int g = 0; g < PH::NG; ++g) {
+        if (PH::gkind(g) == GA_KIND_POLLED) {
+            int spins = 0;
+            while (__builtin_amdgcn_ballot_w64(__float_as_uint(s[g]) == STEP_SENTINEL) != 0 && !dead) {
+                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+                const int frame = t + r.goff[g];
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) s[g] = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+            }
+        }
+    }
     PH::ops(s);
     RNNG_STAMP(4);
 #pragma unroll

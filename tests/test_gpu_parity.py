@@ -248,6 +248,31 @@ def test_two_layer_stack_backward_with_and_without_helper_members(monkeypatch, l
     assert not any(win.g.step_build_has_helpers(k, False) for k in rec)
 
 
+def test_small_stack_at_eight_streams_whose_groups_exceed_lds_together():
+    """Two 40-wide layers at 8 streams: the source areas of the backward launch's two groups
+    (eight and four short source vectors, a quad per lane each) add up to more than the 160 KiB of
+    LDS, so that direction runs the layers one after another."""
+    spec = wl.lstm_net(12, [40, 40], 5)
+    win, _ = run_both(wl.make_workload("lstm_stack_n8", spec, T=19, N=8, seed=37, scale=0.3, bias_scale=0.3, masked_fraction=0.2), label="stack [40, 40], N=8")
+    rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, False) == ("wave", True) and win.g.step_build(k, True) == ("wave", False) for k in rec)
+
+
+@pytest.mark.parametrize("helpers", ["1", "0"])
+@pytest.mark.parametrize("layers,N", [([24, 20], 1), ([64, 48], 2), ([40, 40], 4), ([512, 512], 1)])
+def test_two_layer_stack_at_few_streams_with_and_without_helper_groups(monkeypatch, layers, N, helpers):
+    """A two-layer stack in the weights-in-registers build: with RNNG_CHAIN_HELPERS = 1 a third
+    group of workgroups (on an XCD of its own) computes the products of the connections between the
+    layers in both directions, and the layers' programs poll its sums element by element."""
+    monkeypatch.setenv("RNNG_CHAIN_HELPERS", helpers)
+    spec = wl.lstm_net(12, layers, 5)
+    win, _ = run_both(wl.make_workload("lstm_stack_wave_helpers", spec, T=19, N=N, seed=36, scale=0.3 if layers[0] < 100 else 0.06, bias_scale=0.3, masked_fraction=0.2),
+                      label=f"stack {layers}, N={N}, RNNG_CHAIN_HELPERS={helpers}")
+    rec = [k for k in range(len(spec.nodes)) if win.g.step_build(k)[0] != "none"]
+    assert rec and all(win.g.step_build(k, b) == ("wave", True) for k in rec for b in (False, True))
+    assert all(win.g.step_build_has_helpers(k, b) == (helpers == "1") for k in rec for b in (False, True))
+
+
 @pytest.mark.parametrize("chain", ["1", "0"])
 @pytest.mark.parametrize("N", [2, 24])
 def test_stack_in_one_launch_and_layers_one_after_another(monkeypatch, chain, N):
