@@ -326,15 +326,16 @@ struct rnn_graph {
     }
     std::map<std::tuple<int, bool, int>, ChainChoice> chain_choices;
     bool use_chains = true;
-    // Weights-in-registers launches: a helper group pays in the backward launch, where it takes
-    // half of the lower layer's polled sources and multiply-adds, if those are a noticeable part of
-    // a step that is otherwise mostly exchange latency.  Measured, backward / forward step kernels
-    // with against without helper groups: charlm_n1 (128 multiply-adds per lane and step moved)
-    // 0.81 / 0.88 against 1.21 / 0.81 ms; speech_n1 (32 per lane) 1.13 / 1.37 against 1.04 / 0.92.
+    // Weights-in-registers launches: a step is mostly exchange latency, and the helper group reads
+    // its sources across XCDs (more than a microsecond per step), so it pays where the multiply-adds
+    // and polled sources it takes over weigh enough.  Measured, step kernels forward / backward with
+    // against without helper groups: charlm_n1 (128 multiply-adds per lane and step moved) 0.76 / 0.79
+    // against 0.81 / 1.21 ms; speech_n1 (32 per lane, 0.9 us per step) 1.11 / 0.91 against 0.93 / 1.04:
+    // backward launches (the helper halves the lower layer's sources) from 24 per lane on, forward
+    // launches from 100.
     bool wave_helpers_pay(const std::vector<CompPlan>& members, bool backward, int N) const {
-        int min_fma = 100;
+        int min_fma = backward ? 24 : 100;
         if (const char* env = std::getenv("RNNG_CHAIN_HELPER_MIN")) min_fma = std::atoi(env);
-        if (!backward) return false;
         for (const CompPlan& m : members)
             if (m.helper && m.step_weight_floats * step_nb_for(N) / (32 * 256) >= min_fma) return true;
         return false;
@@ -348,8 +349,8 @@ struct rnn_graph {
         const ChainPlan& ch = plan.chains[chain];
         // Helper members take the products of the connections between the stacked nodes
         // (RNNG_CHAIN_HELPERS = 0: never; 1: in every launch that can have them; default: in the
-        // matrix-core backward launch and in weights-in-registers backward launches from
-        // RNNG_CHAIN_HELPER_MIN multiply-adds per lane and step on)
+        // matrix-core backward launch and in weights-in-registers launches from RNNG_CHAIN_HELPER_MIN
+        // multiply-adds per lane and step on, else from 24 backward / 100 forward)
         const char* envh = std::getenv("RNNG_CHAIN_HELPERS");
         const bool helpers_off = envh && std::atoi(envh) == 0, helpers_all = envh && std::atoi(envh) == 1;
         if (use_jit && use_chains && force_step_G <= 0 && !prefer_streaming) {

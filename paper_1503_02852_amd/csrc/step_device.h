@@ -944,8 +944,10 @@ __device__ __forceinline__ void group_poll_deliver(const PollRegs<MV>& pr, float
 // Completes the polling of frame t, whose first attempt is already under way: the step's work
 // that does not need the polled vectors (mid) runs under it, then the loads are checked and
 // repeated until none holds a sentinel, and the vectors go to LDS.
-template <class MV, int NB, class Mid>
-__device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, Mid&& mid) {
+// extra(false) tells whether the wavefront's other polled values (a helper group's sums, loaded by
+// mid) have arrived, extra(true) loads them again: they take part in the same attempts.
+template <class MV, int NB, class Mid, class Extra>
+__device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const WaveRegs<MV>& wv, const StepArgs& a, int step, int t, int tid, bool& dead, Mid&& mid, Extra&& extra) {
     typedef GroupX<MV, NB> GX;
     // The range of the thread index lets the bounds tests of whole regions fold.  That pays in
     // kernels that poll bundles (two stores per pair: 1.30 -> 1.24 ms in charlm_n1's backward
@@ -975,7 +977,7 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
     mid();
     int spins = 0;
     for (;;) {
-        const bool ok = all_ok(pr);
+        const bool ok = all_ok(pr) && extra(false);
         // one decision per wavefront (a scalar branch; per-lane loop exits cost ~25 scalar
         // instructions of mask handling per step, and a wavefront issues one instruction every
         // four clocks): a wavefront repeats all its loads while any lane holds a sentinel
@@ -983,6 +985,7 @@ __device__ __forceinline__ void group_poll(PollRegs<MV>& pr, float* xs, const Wa
         if (++spins > a.spin_limit) { dead = true; if ((tid & 63) == 0) atomicExch(a.ctrl, 1u); break; }
         __builtin_amdgcn_s_sleep(WAVE_RETRY_SLEEP);
         group_poll_issue<MV, NB>(pr, wv, a, t, tid);
+        extra(true);
     }
 #if defined(RNNG_STEP_TRACE)
     const int trace_step = a.backward ? a.t_end - 1 - t : t - a.t_begin;
@@ -1139,13 +1142,28 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 #pragma unroll
         for (int v = 0; v < PH::NI; ++v) s[PH::NG + v] = r.inv[v];
     };
+    // a helper group's sums (POLLED gathers, loaded by gathers()): arrived? / load them again
+    auto polled_sums = [&](bool reload) {
+        bool ok = true;
+#pragma unroll
+        for (int g = 0; g < PH::NG; ++g) {
+            if (PH::gkind(g) == GA_KIND_POLLED) {
+                if (reload && has_units) {
+                    const int frame = t + r.goff[g];
+                    if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) s[g] = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                }
+                ok = ok && (!has_units || __float_as_uint(s[g]) != STEP_SENTINEL);
+            }
+        }
+        return ok;
+    };
     float xr[NB][MV::XF > 0 ? MV::XF : 1];
     if (MV::NSRC == 0) gathers();
     RNNG_STAMP(1);
     if (MV::NSRC > 0) {
         float* xs = xs_all + PAR * GX::FLOATS;
         if (!MV::PE) group_poll_issue<MV, NB>(pr, wv, a, t, tid);
-        group_poll<MV, NB>(pr, xs, wv, a, step, t, tid, dead, gathers);
+        group_poll<MV, NB>(pr, xs, wv, a, step, t, tid, dead, gathers, polled_sums);
         step_lds_barrier();
 #if defined(RNNG_STEP_TRACE)
         if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= RNNG_STEP_TRACE_AT && step < RNNG_STEP_TRACE_AT + 8) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - RNNG_STEP_TRACE_AT)] = clock64();
@@ -1214,17 +1232,12 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
 #pragma unroll
     for (int g = 0; g < PH::NG; ++g)
         if (PH::gkind(g) == GA_KIND_ACC) s[g] = acc[PH::gaux(g)];
-    // sums of a helper group: normally there since the step's start; the wavefront repeats the
-    // load while one of its lanes still sees the sentinel
-#pragma unroll
-    for (int g = 0; g < PH::NG; ++g) {
-        if (PH::gkind(g) == GA_KIND_POLLED) {
-            int spins = 0;
-            while (__builtin_amdgcn_ballot_w64(__float_as_uint(s[g]) == STEP_SENTINEL) != 0 && !dead) {
-                if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
-                const int frame = t + r.goff[g];
-                if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) s[g] = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
-            }
+    // (a component without sources of its own checks a helper group's sums here; the others did in their poll)
+    if (MV::NSRC == 0) {
+        int spins = 0;
+        while (__builtin_amdgcn_ballot_w64(!polled_sums(false)) != 0 && !dead) {
+            if (++spins > a.spin_limit) { dead = true; if (lane == 0) atomicExch(a.ctrl, 1u); break; }
+            polled_sums(true);
         }
     }
     PH::ops(s);
