@@ -164,6 +164,16 @@ def test_window_moved_ahead_with_carried_state(name):
         assert differs > 1e-3, "the carried state made no difference: the test does not tell the two apart"
 
 
+@pytest.mark.parametrize("name", ["lstm2", "lstm2_streams", "lstm2_16_streams"])
+def test_windows_with_helper_members_in_every_launch(monkeypatch, name):
+    """The same two checks with helper members forced into both launches of the stacks (forward
+    pieces: the helper's sums cover exactly the frames of a piece; moved windows: nothing of a
+    helper's tensors is carried)."""
+    monkeypatch.setenv("RNNG_CHAIN_HELPERS", "1")
+    test_window_computed_in_pieces_equals_the_window_at_once(name)
+    test_window_moved_ahead_with_carried_state(name)
+
+
 def test_frame_by_frame_schedule_gives_the_same_results(monkeypatch):
     """The baseline schedule of Section 4 (every frame on its own) must reach the oracle as well."""
     from paper_1503_02852_amd.runner import window_for
