@@ -181,8 +181,7 @@ std::vector<int> polled_buffers(const Plan& P, const CompPlan& cp, bool backward
 
 // group: index of this component in a chain launch (0 for a launch of its own); foreign: tensors
 // that the other groups of the chain poll.
-// *lds_bytes (optional): the static LDS of the group's body (the bodies of a chain launch are
-// inlined into one kernel, whose LDS is the sum over its groups).
+// *lds_bytes (optional): the static LDS of the group's body.
 bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, bool backward, int N, int G, const std::string& ns,
                      int group, const std::vector<int>& foreign, size_t* lds_bytes = nullptr) {
     const std::vector<PhasePlan>& phases = backward ? cp.bwd_phases : cp.fwd_phases;
@@ -353,10 +352,17 @@ bool emit_wave_group(std::ostringstream& o, const Plan& P, const CompPlan& cp, b
     o << "    static __device__ __forceinline__ constexpr int esrc(int task, int e) { return esrc_(task * " << STEP_MAX_EDGES << " + e); }\n";
     o << "    static __device__ __forceinline__ constexpr int woff(int ul, int task, int e) { return woff_((ul * "
       << (ph.n_tasks > 0 ? ph.n_tasks : 1) << " + task) * " << STEP_MAX_EDGES << " + e); }\n};\n";
-    o << "__device__ __forceinline__ void body(const StepArgs& a, int w) {\n"
-         "    __shared__ StepShared sh;\n"
-         "    __shared__ float ring_all[4][WaveRing<PH0, MV, " << NB << ">::FLOATS];\n"
-         "    __shared__ __attribute__((aligned(16))) float xs_all[2 * GroupX<MV, " << NB << ">::FLOATS];\n"
+    // (the group's LDS as one struct: a chain launch overlays those of its groups, of which a
+    // workgroup runs exactly one)
+    o << "struct Lds {\n"
+         "    StepShared sh;\n"
+         "    float ring_all[4][WaveRing<PH0, MV, " << NB << ">::FLOATS];\n"
+         "    __attribute__((aligned(16))) float xs_all[2 * GroupX<MV, " << NB << ">::FLOATS];\n"
+         "};\n"
+         "__device__ __forceinline__ void body(const StepArgs& a, int w, Lds& l) {\n"
+         "    StepShared& sh = l.sh;\n"
+         "    auto& ring_all = l.ring_all;\n"
+         "    float* xs_all = l.xs_all;\n"
          "    wave_prologue<MV, " << NB << ">(a, sh);\n"
          "    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;\n"
          "    // same in all lanes; false: the wavefront only helps polling\n"
@@ -405,9 +411,10 @@ std::string jit_wave_source(const Plan& P, const CompPlan& cp, bool backward, in
     if (!emit_wave_group(o, P, cp, backward, N, G, "grp0", 0, std::vector<int>())) return "";
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
+         "    __shared__ grp0::Lds l;\n"
          "    const int w = step_part_index(a);\n"
          "    if (w < 0) return;\n"
-         "    grp0::body(a, w);\n"
+         "    grp0::body(a, w, l);\n"
          "}\n";
     return o.str();
 }
@@ -428,17 +435,20 @@ std::string jit_chain_source(const Plan& P, const std::vector<CompPlan>& members
                 for (int b : polled_buffers(P, members[h], backward, N, G[h])) foreign.push_back(b);
         size_t lds = 0;
         if (G[g] > 32 || !emit_wave_group(o, P, members[g], backward, N, G[g], "grp" + std::to_string(g), g, foreign, &lds)) return "";
-        lds_total += lds;
+        lds_total = std::max(lds_total, lds);
     }
-    if (lds_total > 158 * 1024) return "";      // of 160 KiB (three groups at 8 streams can exceed it)
+    if (lds_total > 158 * 1024) return "";      // of 160 KiB (the groups' areas lie on top of each other)
     o << "extern \"C\" __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))\n"
          "void rnng_step_jit(StepArgs a) {\n"
+         "    __shared__ union Lds {\n";
+    for (int g = 0; g < n; ++g) o << "        grp" << g << "::Lds l" << g << ";\n";
+    o << "    } lds;\n"
          "    const int grp = blockIdx.x & 7, w = blockIdx.x >> 3;\n"
          "    if (grp >= a.n_groups || w >= a.grp_G[grp]) return;\n"
          "    StepArgs b = a;\n"
          "    b.desc_off = a.grp_desc_off[grp]; b.G = a.grp_G[grp];\n"
          "    switch (grp) {\n";
-    for (int g = 0; g < n; ++g) o << "        case " << g << ": grp" << g << "::body(b, w); break;\n";
+    for (int g = 0; g < n; ++g) o << "        case " << g << ": grp" << g << "::body(b, w, lds.l" << g << "); break;\n";
     o << "        default: break;\n    }\n}\n";
     return o.str();
 }
