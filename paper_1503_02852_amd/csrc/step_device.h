@@ -340,6 +340,9 @@ struct PhaseRegs {
     unsigned gvoff[PH::NG > 0 ? PH::NG : 1];
     float inv[PH::NI > 0 ? PH::NI : 1];
     float carry[PH::NC > 0 ? PH::NC : 1];
+    // wave-autonomous variant: a helper group's sums (POLLED gathers) for the NEXT step, loaded one
+    // step ahead (they come from another XCD, which takes longer than a step's own exchange)
+    float polled_next[PH::NG > 0 ? PH::NG : 1];
     // loader side of the static-gather ring: this thread's (static gather, item) pairs
     const float* pbase[STEP_PF_PAIRS_PER_THREAD];
     long long pstride[STEP_PF_PAIRS_PER_THREAD];
@@ -1104,6 +1107,10 @@ __device__ __forceinline__ void wave_carry_init(PhaseRegs<PH>& r, const StepArgs
             const int frame = t + r.goff[g];
             r.carry[PH::cidx(g)] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? r.gptr[g][(long long)frame * r.gstride[g]] : 0.0f;
         }
+        if (PH::gkind(g) == GA_KIND_POLLED) {      // the first step's: checked (and loaded again if need be) like every step's
+            const int frame = t + r.goff[g];
+            r.polled_next[g] = (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) ? load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]) : 0.0f;
+        }
     }
 }
 
@@ -1131,12 +1138,20 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
                 // idle lanes read a valid (unused) ring entry instead of branching around the load
                 const int item = (n_l * MV::UW + ul_l) < RG::ITEMS ? (n_l * MV::UW + ul_l) : 0;
                 s[g] = ring[js * RG::PAIRS + PH::sidx(g) * RG::ITEMS + item];
-            } else if (PH::gkind(g) == GA_KIND_FRAMES || PH::gkind(g) == GA_KIND_POLLED) {
-                // (POLLED: a helper group's sum for this frame; it runs ahead, the value is checked below)
+            } else if (PH::gkind(g) == GA_KIND_FRAMES) {
                 const int frame = t + r.goff[g];
                 float v = 0.0f;
                 if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
                 s[g] = v;
+            } else if (PH::gkind(g) == GA_KIND_POLLED) {
+                // a helper group's sum for this frame, loaded one step ahead (the helper runs ahead; the
+                // value is checked with the poll's attempts); now the next step's goes out (behind the
+                // last step: a frame that nothing reads)
+                s[g] = r.polled_next[g];
+                const int frame = step_frame(a, step + 1) + r.goff[g];
+                float v = 0.0f;
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                r.polled_next[g] = v;
             }
         }
 #pragma unroll
