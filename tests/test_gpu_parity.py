@@ -347,15 +347,19 @@ def test_target_index_out_of_range_is_reported():
             assert nerr(gw[m], g) < GRAD_TOL
 
 
-def test_a_wait_that_runs_into_its_limit_is_reported_on_every_path(monkeypatch):
+@pytest.mark.parametrize("helpers,N", [(None, 1), ("1", 1), ("1", 32)])
+def test_a_wait_that_runs_into_its_limit_is_reported_on_every_path(monkeypatch, helpers, N):
     """RNNG_SPIN_LIMIT=1 makes every bounded wait of the step kernels give up after one repeat: the
     kernels then stop waiting, run to their end and raise the error word.  rnn_check must report
     it after a forward pass alone and after rnn_grads without a loss pointer; a window in which no
-    wait happened to expire must be correct."""
+    wait happened to expire must be correct.  Also with helper members in the launches (their sums
+    are waited for like every exchanged value), weights in registers and matrix cores."""
     from paper_1503_02852_amd.binding import RnnError
     from paper_1503_02852_amd.runner import window_for
     monkeypatch.setenv("RNNG_SPIN_LIMIT", "1")
-    w = wl.make_workload("spin", wl.lstm_net(8, [64, 64], 4), T=200, N=1, seed=66, scale=0.3)
+    if helpers is not None:
+        monkeypatch.setenv("RNNG_CHAIN_HELPERS", helpers)
+    w = wl.make_workload("spin", wl.lstm_net(8, [64, 64], 4), T=200 if N == 1 else 60, N=N, seed=66, scale=0.3)
     win = window_for(w)
     win.forward()
     flagged = False
