@@ -15,6 +15,10 @@ Readings where the paper is silent (all listed in the design notes of the reposi
   * a third weight kind "diagonal" besides "full" and "identity" (needed for peepholes);
   * y_k = f_k(s_k) is applied to multiplicative nodes too (Section 2.2's delta equation
     uses f_k' for any layer);
+  * a third aggregation function g_k besides sum and product (Section 2.1 allows "other"
+    functions there): the element-wise maximum of the incoming connection outputs, node kind 3;
+    its error terms go to the connection that holds the maximum, to the first one (lowest edge
+    index) if several do;
   * the activation functions f_k (Section 2.1 leaves them open): linear, logistic sigmoid, tanh,
     and the rectifier max(0, s), whose derivative at s = 0 is taken as 0;
   * a fresh window starts from zero activations (frame index <= 0); a window that carries
@@ -45,7 +49,7 @@ from __future__ import annotations
 
 import numpy as np
 
-INPUT, ADD, MUL = 0, 1, 2
+INPUT, ADD, MUL, MAX = 0, 1, 2, 3
 CROSS_ENTROPY, SQUARED_ERROR = 1, 2          # values of a node's is_output
 LINEAR, SIGMOID, TANH, SOFTMAX, RELU = 0, 1, 2, 3, 4
 FULL, DIAG, IDENTITY = 0, 1, 2
@@ -170,6 +174,10 @@ def forward(nodes, edges, weights, biases, inputs, T, N, history=None):
                     s = s + z[m][t]
                 if B[k] is not None:
                     s = s + B[k]
+            elif n["kind"] == MAX:
+                s = z[anterior[k][0]][t]
+                for m in anterior[k][1:]:
+                    s = np.maximum(s, z[m][t])
             else:
                 s = np.ones((N, n["dim"]))
                 for m in anterior[k]:
@@ -248,6 +256,14 @@ def bptt(nodes, edges, weights, biases, y, z, targets, T, N, t_first=0):
                 e = edges[m]
                 if n["kind"] == ADD:
                     eps = delta[k][t]
+                elif n["kind"] == MAX:
+                    # ds/dz_m is 1 where connection m holds the maximum (the first one, if several do), else 0
+                    eps = delta[k][t].copy()
+                    for other in anterior[k]:
+                        if other < m:
+                            eps = eps * (z[m][t] > z[other][t])
+                        elif other > m:
+                            eps = eps * (z[m][t] >= z[other][t])
                 else:
                     eps = delta[k][t].copy()
                     for other in anterior[k]:

@@ -664,3 +664,65 @@ def test_finite_differences_random_graphs_with_rectifiers(seed):
     w = wl.make_workload("rand_relu", spec, T=6, N=2, seed=seed, scale=0.8, bias_scale=0.5, masked_fraction=0.2 if seed % 2 else 0.0)
     check_finite_differences(w, n_probe=4, seed=seed)
     check_truncated_gradient_by_finite_differences(w, t_first=2, n_probe=3)
+
+
+# ---- a third aggregation function: the element-wise maximum (Section 2.1: g_k may be another function) ----
+
+def test_maximum_layer_closed_form():
+    """A node that takes the element-wise maximum of a diagonal, an identity and a delayed
+    identity connection, with fixed numbers: values, the routing of the error to the connection
+    that holds the maximum (the first one on a tie) and the diagonal weight gradient by hand."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 2, name="x")
+    u = g.add_node(wl.INPUT, wl.LINEAR, 2, name="u")
+    mx = g.add_node(wl.MAX, wl.LINEAR, 2, name="mx")
+    out = g.add_node(wl.ADD, wl.LINEAR, 2, is_output=wl.SQUARED_ERROR, name="out")
+    e_d = g.add_edge(x, mx, wl.DIAG, 0)          # z0 = w * x(t)
+    e_i = g.add_edge(u, mx, wl.IDENTITY, 0)      # z1 = u(t)
+    e_p = g.add_edge(u, mx, wl.IDENTITY, 1)      # z2 = u(t - 1)
+    e_o = g.add_edge(mx, out, wl.IDENTITY, 0)
+    weights = [None] * 4; weights[e_d] = np.array([2.0, -1.0])
+    X = np.array([[[1.0, 1.0]], [[0.5, -4.0]]])          # T = 2, N = 1
+    U = np.array([[[2.0, 3.0]], [[0.0, 3.5]]])
+    D = np.array([[[0.0, 0.0]], [[0.0, 0.0]]])
+    # frame 0: z0 = (2, -1), z1 = (2, 3), z2 = (0, 0)   -> max (2, 3): unit 0 is a tie of z0 and z1 -> z0 takes it; unit 1 -> z1
+    # frame 1: z0 = (1, 4),  z1 = (0, 3.5), z2 = (2, 3) -> max (2, 4): unit 0 -> z2; unit 1 -> z0
+    r = go.forward_bptt(g.nodes, g.edges, weights, [None] * 4, {x: X, u: U}, {out: D}, 2, 1)
+    np.testing.assert_array_equal(r["y"][mx], np.array([[[2.0, 3.0]], [[2.0, 4.0]]]))
+    assert r["loss"] == pytest.approx(0.5 * (4 + 9 + 4 + 16))
+    # dE/ds_mx = y - d = (2, 3), (2, 4); the diagonal weight sees it where z0 holds the maximum:
+    # unit 0 at frame 0 (x = 1) and unit 1 at frame 1 (x = -4)
+    np.testing.assert_allclose(r["grad_w"][e_d], np.array([2.0 * 1.0, 4.0 * -4.0]))
+
+
+def test_maximum_of_one_connection_is_the_connection_itself():
+    """With a single incoming connection the maximum node is an additive node without bias."""
+    def net(kind):
+        g = wl.GraphSpec()
+        x = g.add_node(wl.INPUT, wl.LINEAR, 4, name="x")
+        h = g.add_node(wl.ADD, wl.TANH, 4, has_bias=True, name="h")
+        m = g.add_node(kind, wl.SIGMOID, 4, name="m")
+        out = g.add_node(wl.ADD, wl.SOFTMAX, 3, has_bias=True, is_output=True, name="out")
+        g.add_edge(x, h, wl.FULL, 0); g.add_edge(h, h, wl.FULL, 1); g.add_edge(h, m, wl.DIAG, 0); g.add_edge(m, out, wl.FULL, 0)
+        g.add_edge(m, h, wl.IDENTITY, 2)
+        return g
+    wa = wl.make_workload("one_add", net(wl.ADD), T=7, N=2, seed=51, scale=0.6, bias_scale=0.3)
+    wm = wl.make_workload("one_max", net(wl.MAX), T=7, N=2, seed=51, scale=0.6, bias_scale=0.3)
+    ra, rm = run_oracle(wa), run_oracle(wm)
+    assert ra["loss"] == rm["loss"]
+    for a, b in zip(ra["grad_w"], rm["grad_w"]):
+        if a is not None:
+            np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 4, 5, 7, 9, 10])
+def test_finite_differences_random_graphs_with_maximum_nodes(seed):
+    """Random recurrent graphs in which about half of the inner nodes take the maximum of one to
+    seven connections: every gradient against central differences (the probes' steps of 1e-5 do not
+    change which connection holds a maximum for these seeds), forward + BPTT and a carried window."""
+    rng = np.random.default_rng(950 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, max_fraction=0.5)
+    assert any(n["kind"] == wl.MAX for n in spec.nodes)
+    w = wl.make_workload("rand_max", spec, T=6, N=2, seed=seed, scale=0.8, bias_scale=0.5, masked_fraction=0.2 if seed % 2 else 0.0)
+    check_finite_differences(w, n_probe=4, seed=seed)
+    check_truncated_gradient_by_finite_differences(w, t_first=2, n_probe=3)

@@ -7,7 +7,7 @@ layer, an edge is a connection with a weight matrix and a delay) and (b) seeded
 random weights, inputs and targets.
 
 Enumerations are the interface's integer codes (they appear in the C header too):
-  node kind : 0 input, 1 additive, 2 multiplicative
+  node kind : 0 input, 1 additive, 2 multiplicative, 3 element-wise maximum
   activation: 0 linear, 1 logistic sigmoid, 2 tanh, 3 softmax (output nodes only), 4 rectifier max(0, s)
   weight kind: 0 full matrix [n_dst x n_src], 1 diagonal (vector), 2 identity
   is_output : 0 no, 1 softmax output with class targets (cross-entropy), 2 output with dense
@@ -17,7 +17,7 @@ from __future__ import annotations
 
 import numpy as np
 
-INPUT, ADD, MUL = 0, 1, 2
+INPUT, ADD, MUL, MAX = 0, 1, 2, 3
 LINEAR, SIGMOID, TANH, SOFTMAX, RELU = 0, 1, 2, 3, 4
 FULL, DIAG, IDENTITY = 0, 1, 2
 CROSS_ENTROPY, SQUARED_ERROR = 1, 2
@@ -175,17 +175,20 @@ def generalized_net(n_in=128, n_cells=1024, n_layers=3, n_out=256):
 
 
 def random_graph(rng, n_inner=6, max_dim=5, p_edge=0.35, max_delay=3, n_inputs=1, force_mul=True, squared_error_outputs=0,
-                 acts=(LINEAR, SIGMOID, TANH)):
+                 acts=(LINEAR, SIGMOID, TANH), max_fraction=0.0):
     """A small random valid graph for brute-force / finite-difference tests: additive and
     multiplicative nodes, full / diagonal / identity edges, delays 0..max_delay, multiple
     edges between a node pair, self-loops; delay-0 edges only run from lower to higher node
-    id, so the delay-0 subgraph is acyclic.  acts: the activations the inner nodes draw from."""
+    id, so the delay-0 subgraph is acyclic.  acts: the activations the inner nodes draw from;
+    max_fraction: share of the inner nodes that take the element-wise maximum of their inputs."""
     g = GraphSpec()
     dims = [int(rng.integers(2, max_dim + 1)) for _ in range(2)]   # two dim classes
     ins = [g.add_node(INPUT, LINEAR, dims[int(rng.integers(0, 2))], name=f"x{j}") for j in range(n_inputs)]
     inner = []
     for j in range(n_inner):
         kind = MUL if (rng.random() < 0.35 or (force_mul and j == n_inner // 2)) else ADD
+        if max_fraction > 0 and not (force_mul and j == n_inner // 2) and rng.random() < max_fraction:
+            kind = MAX
         act = int(acts[int(rng.integers(0, len(acts)))])
         dim = dims[int(rng.integers(0, 2))]
         inner.append(g.add_node(kind, act, dim, has_bias=(kind == ADD and rng.random() < 0.5), name=f"v{j}"))
