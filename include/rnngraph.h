@@ -52,8 +52,11 @@ enum rnn_status {
 };
 
 /* Node (layer) kinds: Section 2.1 defines additive layers (sum of the incoming connection
- * outputs, then an activation function) and multiplicative layers (element-wise product). */
-enum { RNN_NODE_INPUT = 0, RNN_NODE_ADD = 1, RNN_NODE_MUL = 2 };
+ * outputs, then an activation function) and multiplicative layers (element-wise product), and
+ * allows other aggregation functions; RNN_NODE_MAX takes the element-wise maximum of the incoming
+ * connection outputs (its error terms go to the connection that holds the maximum, to the one
+ * with the lowest edge index if several do). */
+enum { RNN_NODE_INPUT = 0, RNN_NODE_ADD = 1, RNN_NODE_MUL = 2, RNN_NODE_MAX = 3 };
 /* Activation functions f_k (Section 2.1 leaves them open); softmax is allowed on output nodes
  * only and is paired with the cross-entropy criterion, the case for which Section 2.2 writes the
  * output delta out.  RNN_ACT_RELU is the rectifier max(0, s); its derivative at s = 0 counts as 0. */
@@ -81,7 +84,7 @@ typedef struct { int32_t src, dst, delay, wkind; } rnn_edge_desc;
  * input node; a non-input node has no incoming edge; an input node has a bias, an activation or
  * is an output; softmax on a node that is not a cross-entropy output, a cross-entropy output
  * that is not additive-softmax, a squared-error output that is not additive or has softmax;
- * an output node with outgoing edges; has_bias on a multiplicative node; there is no output
+ * an output node with outgoing edges; has_bias on a multiplicative or maximum node; there is no output
  * node; or the delay-0 edges contain a cycle (Section 3.1 needs the per-step remainder to be a
  * DAG). */
 int rnn_graph_create(const rnn_node_desc* nodes, int32_t n_nodes,

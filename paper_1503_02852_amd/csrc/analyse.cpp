@@ -21,13 +21,13 @@ std::string validate_graph(const std::vector<GNode>& nodes, const std::vector<GE
     int n_outputs = 0;
     for (int k = 0; k < K; ++k) {
         const GNode& n = nodes[k];
-        if (n.kind < NODE_INPUT || n.kind > NODE_MUL) { e << "node " << k << ": unknown kind " << n.kind; return e.str(); }
+        if (n.kind < NODE_INPUT || n.kind > NODE_MAX) { e << "node " << k << ": unknown kind " << n.kind; return e.str(); }
         if (n.act < ACT_LINEAR || n.act > ACT_RELU) { e << "node " << k << ": unknown activation " << n.act; return e.str(); }
         if (n.dim <= 0) { e << "node " << k << ": dim must be positive"; return e.str(); }
         if (n.kind == NODE_INPUT && (n.has_bias || n.is_output || n.act != ACT_LINEAR)) {
             e << "node " << k << ": an input node has no bias, no activation and is not an output"; return e.str();
         }
-        if (n.kind == NODE_MUL && n.has_bias) { e << "node " << k << ": a multiplicative node has no bias"; return e.str(); }
+        if ((n.kind == NODE_MUL || n.kind == NODE_MAX) && n.has_bias) { e << "node " << k << ": a multiplicative or maximum node has no bias"; return e.str(); }
         if (n.is_output < OUT_NONE || n.is_output > OUT_SQUARED_ERROR) { e << "node " << k << ": unknown output kind " << n.is_output; return e.str(); }
         if (n.is_output == OUT_CROSS_ENTROPY) {
             ++n_outputs;

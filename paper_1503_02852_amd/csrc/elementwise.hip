@@ -142,13 +142,23 @@ __global__ __launch_bounds__(256) void colsum_kernel(PlanView pv, int tasks_off,
         for (long long r = (long long)t0 * N + (long long)blockIdx.z * 4 + threadIdx.y; r < rows; r += 4LL * gridDim.z) {
             const int t = (int)(r / N), n = (int)(r % N);
             float prod = 1.0f;
-            for (int j = 0; j < nf; ++j) {
+            auto value = [&](int j) {
                 const int32_t* f = w + CS_HEADER_WORDS + j * CF_WORDS;
                 const int frame = t + f[CF_FRAME_OFF];
                 float v = 0.0f;
                 if (frame >= 0 && frame < T) v = pv.buf_ptr[f[CF_BUF]][((size_t)frame * N + n) * dim + i];
                 if (f[CF_W_OFF] >= 0) v *= weights[f[CF_W_OFF] + i];
-                prod *= v;
+                return v;
+            };
+            for (int j = 0; j < nf; ++j) {
+                const int cmp = w[CS_HEADER_WORDS + j * CF_WORDS + CF_CMP];
+                if (cmp != 0 && j + 1 < nf) {      // [this >= next] or [this > next]: a maximum node's routing
+                    const float a = value(j), b = value(j + 1);
+                    prod *= (cmp == 1 ? a >= b : a > b) ? 1.0f : 0.0f;
+                    ++j;
+                } else {
+                    prod *= value(j);
+                }
             }
             s += prod;
         }

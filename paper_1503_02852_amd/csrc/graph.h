@@ -9,7 +9,7 @@ namespace rnng {
 struct GNode { int kind, act, dim, has_bias, is_output; };
 struct GEdge { int src, dst, delay, wkind; };
 
-enum { NODE_INPUT = 0, NODE_ADD = 1, NODE_MUL = 2 };
+enum { NODE_INPUT = 0, NODE_ADD = 1, NODE_MUL = 2, NODE_MAX = 3 };
 enum { ACT_LINEAR = 0, ACT_SIGMOID = 1, ACT_TANH = 2, ACT_SOFTMAX = 3, ACT_RELU = 4 };
 enum { OUT_NONE = 0, OUT_CROSS_ENTROPY = 1, OUT_SQUARED_ERROR = 2 };      // GNode::is_output
 enum { W_FULL = 0, W_DIAG = 1, W_IDENTITY = 2 };

@@ -105,6 +105,9 @@ __device__ __forceinline__ void run_ops(float (&s)[MAX_SLOTS], const ProgramView
             case MOP_DTANH: { const float y = s[b]; r = va * (1.0f - y * y); break; }
             case MOP_RELU: r = fmaxf(va, 0.0f); break;
             case MOP_DRELU: r = s[b] > 0.0f ? va : 0.0f; break;
+            case MOP_MAX: r = fmaxf(va, s[b]); break;
+            case MOP_GE: r = va >= s[b] ? 1.0f : 0.0f; break;
+            case MOP_GT: r = va > s[b] ? 1.0f : 0.0f; break;
             default: r = 0.0f; break;
         }
         s[d] = r;

@@ -74,6 +74,9 @@ void emit_ops(std::ostringstream& o, const int32_t* pw) {
             case MOP_DTANH: o << "s[" << a << "] * (1.0f - s[" << b << "] * s[" << b << "])"; break;
             case MOP_RELU: o << "fmaxf(s[" << a << "], 0.0f)"; break;
             case MOP_DRELU: o << "(s[" << b << "] > 0.0f ? s[" << a << "] : 0.0f)"; break;
+            case MOP_MAX: o << "fmaxf(s[" << a << "], s[" << b << "])"; break;
+            case MOP_GE: o << "(s[" << a << "] >= s[" << b << "] ? 1.0f : 0.0f)"; break;
+            case MOP_GT: o << "(s[" << a << "] > s[" << b << "] ? 1.0f : 0.0f)"; break;
             default: o << "0.0f"; break;
         }
         o << ";\n";

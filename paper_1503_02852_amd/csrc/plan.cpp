@@ -19,7 +19,9 @@ constexpr int64_t PARAM_ALIGN = 64;   // floats; keeps every weight block 256-by
 
 int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
-struct FactorH { int buf, frame_off, w_off, slot; };
+// cmp 1 / 2: this factor and the next one of the term stand for [this >= next] / [this > next]
+// (1 or 0), the routing of a maximum node's error terms
+struct FactorH { int buf, frame_off, w_off, slot; int cmp = 0; };
 struct TermH { std::vector<FactorH> f; };
 enum { POST_NONE = 0, POST_SIGMOID = 1, POST_TANH = 2, POST_DSIGMOID = 3, POST_DTANH = 4, POST_RELU = 5, POST_DRELU = 6 };
 struct OpH {
@@ -28,6 +30,7 @@ struct OpH {
     bool new_program = false;   // must not share a program with the operation before it
     bool pre_static = false;    // pre_buf was written before the step loop (batched GEMM), not by an earlier part
     bool partial_out = false;   // out_buf holds a partial sum, not the layer's value
+    bool agg_max = false;       // the terms are aggregated by their maximum, not their sum (maximum node, forward)
     std::vector<TermH> terms;
 };
 struct MvEdgeH { int w_off, k_len, transposed, src_buf, frame_off; };
@@ -80,8 +83,12 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
             }
         if (o.deriv_buf >= 0) L.gather_slot(o.deriv_buf, 0, o.dim, GA_KIND_FRAMES);
     }
+    bool has_cmp = false;
+    for (const OpH& o : ops) for (const TermH& t : o.terms) for (const FactorH& f : t.f) has_cmp = has_cmp || f.cmp != 0;
     const int ng = (int)L.gathers.size(), ni = (int)L.invs.size();
-    const int res0 = ng + ni, tmp = res0 + (int)ops.size(), n_slots = tmp + 1;
+    // temporaries: the running product; with comparisons also their running product and two operands
+    const int res0 = ng + ni, tmp = res0 + (int)ops.size(), tmp_mask = tmp + 1, tmp_a = tmp + 2, tmp_b = tmp + 3;
+    const int n_slots = tmp + (has_cmp ? 4 : 1);
     if (n_slots > MAX_SLOTS || ng > STEP_MAX_GATHERS) return -1;
     if (dry_run) return 0;
     std::vector<std::array<int, 2>> mops;      // packed, c
@@ -92,22 +99,17 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
         const OpH& o = ops[r];
         max_dim = std::max(max_dim, o.dim);
         const int R = res0 + (int)r;
-        std::vector<std::vector<int>> summands;
-        if (o.pre_buf >= 0) summands.push_back({L.gather_slot(o.pre_buf, 0, o.dim, GA_KIND_FRAMES)});
-        if (o.bias_off >= 0) summands.push_back({ng + L.inv_index(o.bias_off, o.dim)});
-        if (o.acc_buf >= 0) summands.push_back({L.gather_slot(o.acc_buf, o.acc_task, o.dim, GA_KIND_ACC)});
-        if (o.polled_buf >= 0) summands.push_back({L.gather_slot(o.polled_buf, 0, o.dim, GA_KIND_POLLED)});
-        for (const TermH& t : o.terms) {
-            std::vector<int> atoms;
-            for (const FactorH& f : t.f) {
-                atoms.push_back(f.slot >= 0 ? res0 + f.slot : L.gather_slot(f.buf, f.frame_off, buf_dim[f.buf], GA_KIND_FRAMES));
-                if (f.w_off >= 0 || f.w_off <= -1000) atoms.push_back(ng + L.inv_index(f.w_off, buf_dim[f.buf]));
-            }
-            summands.push_back(atoms);
-        }
         bool have = false;
-        for (const std::vector<int>& a : summands) {
-            if (a.size() == 1) {
+        // adds (or, for a maximum node, merges) the product of the slots in `a` into R
+        auto accumulate = [&](const std::vector<int>& a) {
+            if (o.agg_max) {
+                int v = a[0];
+                if (a.size() > 1) {
+                    for (size_t j = 1; j < a.size(); ++j) { mop(MOP_MUL, have ? tmp : R, v, a[j], 0); v = have ? tmp : R; }
+                    if (have) mop(MOP_MAX, R, R, tmp, 0);
+                } else if (!have) mop(MOP_MOV, R, v, 0, 0);
+                else mop(MOP_MAX, R, R, v, 0);
+            } else if (a.size() == 1) {
                 if (!have) mop(MOP_MOV, R, a[0], 0, 0); else mop(MOP_ADD, R, R, a[0], 0);
             } else {
                 int p = a[0];
@@ -115,6 +117,36 @@ int emit_program(std::vector<int32_t>& w, const std::vector<OpH>& all_ops, int f
                 if (!have) mop(MOP_MUL, R, p, a.back(), 0); else mop(MOP_FMA, R, p, a.back(), R);
             }
             have = true;
+        };
+        if (o.pre_buf >= 0) accumulate({L.gather_slot(o.pre_buf, 0, o.dim, GA_KIND_FRAMES)});
+        if (o.bias_off >= 0) accumulate({ng + L.inv_index(o.bias_off, o.dim)});
+        if (o.acc_buf >= 0) accumulate({L.gather_slot(o.acc_buf, o.acc_task, o.dim, GA_KIND_ACC)});
+        if (o.polled_buf >= 0) accumulate({L.gather_slot(o.polled_buf, 0, o.dim, GA_KIND_POLLED)});
+        for (const TermH& t : o.terms) {
+            std::vector<int> atoms;
+            // value of a factor: its slot, or (times its weight) in `scratch`
+            auto value_of = [&](const FactorH& f, int scratch) {
+                const int sl = f.slot >= 0 ? res0 + f.slot : L.gather_slot(f.buf, f.frame_off, buf_dim[f.buf], GA_KIND_FRAMES);
+                if (!(f.w_off >= 0 || f.w_off <= -1000)) return sl;
+                mop(MOP_MUL, scratch, sl, ng + L.inv_index(f.w_off, buf_dim[f.buf]), 0);
+                return scratch;
+            };
+            bool mask = false;
+            for (size_t i = 0; i < t.f.size(); ++i) {
+                const FactorH& f = t.f[i];
+                if (f.cmp != 0 && i + 1 < t.f.size()) {
+                    const int va = value_of(f, tmp_a), vb = value_of(t.f[i + 1], tmp_b);
+                    ++i;
+                    if (!mask) mop(f.cmp == 1 ? MOP_GE : MOP_GT, tmp_mask, va, vb, 0);
+                    else { mop(f.cmp == 1 ? MOP_GE : MOP_GT, tmp_a, va, vb, 0); mop(MOP_MUL, tmp_mask, tmp_mask, tmp_a, 0); }
+                    mask = true;
+                    continue;
+                }
+                atoms.push_back(f.slot >= 0 ? res0 + f.slot : L.gather_slot(f.buf, f.frame_off, buf_dim[f.buf], GA_KIND_FRAMES));
+                if (f.w_off >= 0 || f.w_off <= -1000) atoms.push_back(ng + L.inv_index(f.w_off, buf_dim[f.buf]));
+            }
+            if (mask) atoms.push_back(tmp_mask);
+            accumulate(atoms);
         }
         if (!have) mop(MOP_ZERO, R, 0, 0, 0);
         if (o.post == POST_SIGMOID) mop(MOP_SIG, R, R, 0, 0);
@@ -201,7 +233,7 @@ bool split_wide_ops(std::vector<OpH>& ops, const std::vector<int>& part_bufs, co
                 return false;
             }
             out.push_back(cur);
-            cur = OpH(); cur.dim = o.dim; cur.pre_buf = pb; cur.out_buf = pb; cur.new_program = true; cur.partial_out = true; cur.terms.push_back(t);
+            cur = OpH(); cur.dim = o.dim; cur.pre_buf = pb; cur.out_buf = pb; cur.new_program = true; cur.partial_out = true; cur.agg_max = o.agg_max; cur.terms.push_back(t);
             if (!op_fits(cur, buf_dim, 2)) {
                 err = "a connection into a multiplicative layer has too many sibling connections for one step program";
                 return false;
@@ -280,7 +312,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     P.xnodes = nodes;
     for (int m = 0; m < M0; ++m) {
         const GEdge& e = edges[m];
-        if (e.wkind == W_FULL && nodes[e.dst].kind == NODE_MUL) {
+        if (e.wkind == W_FULL && (nodes[e.dst].kind == NODE_MUL || nodes[e.dst].kind == NODE_MAX)) {
             int s = (int)P.xnodes.size();
             P.xnodes.push_back(GNode{NODE_ADD, ACT_LINEAR, nodes[e.dst].dim, 0, 0});
             P.xedges.push_back(GEdge{e.src, s, e.delay, W_FULL}); P.xedge_param.push_back(m);
@@ -371,6 +403,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                 MvTaskH htask; htask.n_out = xn[k].dim; htask.acc_buf = P.abuf(k);
                 o.post = xn[k].act == ACT_SIGMOID ? POST_SIGMOID : xn[k].act == ACT_TANH ? POST_TANH : xn[k].act == ACT_RELU ? POST_RELU : POST_NONE;
                 if (xn[k].has_bias) o.bias_off = (int)P.bias_off[k];
+                o.agg_max = xn[k].kind == NODE_MAX;
                 MvTaskH task; task.n_out = xn[k].dim; task.acc_buf = P.abuf(k);
                 TermH product;
                 for (int m : in_e[k]) {
@@ -471,6 +504,12 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
                     if (xn[k].kind == NODE_MUL)
                         for (int m2 : in_e[k])
                             if (m2 != m) t.f.push_back(FactorH{P.ybuf(xe[m2].src), e.delay - xe[m2].delay, w_off_of(m2), -1});
+                    if (xn[k].kind == NODE_MAX)      // the error goes to the connection that holds the maximum (the first one of several)
+                        for (int m2 : in_e[k])
+                            if (m2 != m) {
+                                t.f.push_back(FactorH{P.ybuf(j), 0, w_off_of(m), -1, m2 < m ? 2 : 1});
+                                t.f.push_back(FactorH{P.ybuf(xe[m2].src), e.delay - xe[m2].delay, w_off_of(m2), -1});
+                            }
                     o.terms.push_back(t);
                 }
                 if (!task.edges.empty()) { o.acc_buf = task.acc_buf; o.acc_task = (int)tasks.size(); tasks.push_back(task); P.buf_alloc[task.acc_buf] = 2; }
@@ -628,7 +667,7 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
     P.n_colsum = 0;
     auto emit_colsum = [&](int dim, int out_off, const std::vector<FactorH>& fs) {
         P.words.push_back(dim); P.words.push_back(out_off); P.words.push_back((int)fs.size());
-        for (const FactorH& f : fs) { P.words.push_back(f.buf); P.words.push_back(f.frame_off); P.words.push_back(f.w_off); }
+        for (const FactorH& f : fs) { P.words.push_back(f.buf); P.words.push_back(f.frame_off); P.words.push_back(f.w_off); P.words.push_back(f.cmp); }
         ++P.n_colsum; P.colsum_max_dim = std::max(P.colsum_max_dim, dim);
     };
     for (int m = 0; m < M; ++m) {
@@ -640,6 +679,12 @@ bool build_plan(const std::vector<GNode>& nodes, const std::vector<GEdge>& edges
         if (xn[e.dst].kind == NODE_MUL)
             for (int m2 : in_e[e.dst])
                 if (m2 != m) fs.push_back(FactorH{P.ybuf(xe[m2].src), -xe[m2].delay, w_off_of(m2), -1});
+        if (xn[e.dst].kind == NODE_MAX)
+            for (int m2 : in_e[e.dst])
+                if (m2 != m) {
+                    fs.push_back(FactorH{P.ybuf(e.src), -e.delay, w_off_of(m), -1, m2 < m ? 2 : 1});
+                    fs.push_back(FactorH{P.ybuf(xe[m2].src), -xe[m2].delay, w_off_of(m2), -1});
+                }
         emit_colsum(xn[e.dst].dim, (int)full_off(m), fs);
     }
     for (int k = 0; k < K0; ++k)

@@ -36,7 +36,10 @@ enum {
     MOP_DTANH = 7,  // d = a * (1 - b * b)
     MOP_ZERO = 8,   // d = 0
     MOP_RELU = 9,   // d = max(a, 0)
-    MOP_DRELU = 10  // d = b > 0 ? a : 0
+    MOP_DRELU = 10, // d = b > 0 ? a : 0
+    MOP_MAX = 11,   // d = max(a, b)
+    MOP_GE = 12,    // d = a >= b ? 1 : 0
+    MOP_GT = 13     // d = a > b ? 1 : 0
 };
 
 // Program header, then gather entries, inv entries, ops, stores.
@@ -78,7 +81,7 @@ enum { MVE_W_OFF = 0, MVE_KLEN, MVE_TRANSPOSED, MVE_SRC_BUF, MVE_FRAME_OFF, MVE_
 //   factor = buffer(t + frame_off, n, i) * [weights[w_off + i]].
 //   [dim, out_off, n_factors, factors...], factor = [buf, frame_off, w_off]
 enum { CS_DIM = 0, CS_OUT_OFF, CS_NFACTORS, CS_HEADER_WORDS };
-enum { CF_BUF = 0, CF_FRAME_OFF, CF_W_OFF, CF_WORDS };
+enum { CF_BUF = 0, CF_FRAME_OFF, CF_W_OFF, CF_CMP, CF_WORDS };     // CF_CMP 1 / 2: this factor and the next one stand for [this >= next] / [this > next]
 
 // Plan words and the buffer table never change while a kernel runs: device code reads them
 // through the constant address space, which makes uniform reads scalar loads.

@@ -108,6 +108,8 @@ def test_invalid_graphs_are_rejected():
     bad([X, H, [wl.ADD, wl.TANH, 2, 1, 3]], ok_edges)                           # unknown output kind
     Graph(np.array([X, H, [wl.ADD, wl.TANH, 2, 1, 2]], np.int32), np.array(ok_edges, np.int32))      # a valid squared-error output
     assert "activation" in bad([X, [wl.ADD, 5, 3, 1, 0], O], ok_edges)          # unknown activation
+    bad([X, [wl.MAX, wl.LINEAR, 3, 1, 0], O], [[0, 1, 0, 2], [1, 2, 0, 0]])     # bias on a maximum node
+    Graph(np.array([X, [wl.MAX, wl.TANH, 3, 0, 0], O], np.int32), np.array([[0, 1, 0, 2], [0, 1, 1, 1], [1, 2, 0, 0]], np.int32))   # a maximum node
     bad([X, H, [wl.ADD, wl.RELU, 2, 1, 1]], ok_edges)                           # cross-entropy output with a rectifier
     Graph(np.array([X, [wl.ADD, wl.RELU, 3, 1, 0], [wl.ADD, wl.RELU, 2, 1, 2]], np.int32), np.array(ok_edges, np.int32))   # rectified hidden and squared-error layers
 

@@ -114,6 +114,58 @@ def test_random_graphs_with_rectifiers(seed):
                               masked_fraction=0.2 if seed % 2 else 0.0))
 
 
+def maxout_net(n_in, H, n_out, pieces=3):
+    """An Elman-like layer of maximum units (Section 2.1: another aggregation function): `pieces`
+    tanh layers fed by the input and the delayed output, whose element-wise maximum (taken through
+    diagonal and identity connections, one of them delayed) is the layer's output."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, n_in, name="x")
+    ps = [g.add_node(wl.ADD, wl.TANH, H, has_bias=True, name=f"p{j}") for j in range(pieces)]
+    m = g.add_node(wl.MAX, wl.LINEAR, H, name="m")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, n_out, has_bias=True, is_output=True, name="out")
+    for j, p in enumerate(ps):
+        g.add_edge(x, p, wl.FULL, 0)
+        g.add_edge(m, p, wl.FULL, 1)
+        g.add_edge(p, m, wl.DIAG if j % 2 == 0 else wl.IDENTITY, 0)
+    g.add_edge(m, m, wl.DIAG, 2)
+    g.add_edge(m, out, wl.FULL, 0)
+    return g
+
+
+@pytest.mark.parametrize("H,N", [(24, 1), (150, 3), (64, 20), (256, 32)])
+def test_maximum_units(H, N):
+    """Layers of maximum units inside a recurrent node, at few streams and many."""
+    w = wl.make_workload("maxout", maxout_net(10, H, 6), T=14, N=N, seed=9, scale=0.5 if H < 100 else 0.12, bias_scale=0.3, masked_fraction=0.2)
+    run_both(w, label=f"maximum units, H={H}, N={N}")
+
+
+def test_full_connection_into_a_maximum_node():
+    """Full connections into a maximum node go through a linear node of their own, as into a
+    multiplicative node; here outside any recurrent node (batched)."""
+    g = wl.GraphSpec()
+    x = g.add_node(wl.INPUT, wl.LINEAR, 7, name="x")
+    h = g.add_node(wl.ADD, wl.TANH, 9, has_bias=True, name="h")
+    m = g.add_node(wl.MAX, wl.SIGMOID, 9, name="m")
+    out = g.add_node(wl.ADD, wl.SOFTMAX, 4, has_bias=True, is_output=True, name="out")
+    g.add_edge(x, h, wl.FULL, 0); g.add_edge(h, h, wl.FULL, 1)
+    g.add_edge(x, m, wl.FULL, 0); g.add_edge(h, m, wl.IDENTITY, 0); g.add_edge(h, m, wl.DIAG, 1); g.add_edge(x, m, wl.FULL, 2)
+    g.add_edge(m, out, wl.FULL, 0)
+    run_both(wl.make_workload("max_full", g, T=11, N=3, seed=10, scale=0.6, bias_scale=0.3), label="full connections into a maximum node")
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 4, 5, 7, 9, 10])
+def test_random_graphs_with_maximum_nodes(seed):
+    rng = np.random.default_rng(950 + seed)
+    spec = wl.random_graph(rng, n_inner=6 + seed % 3, max_delay=3, n_inputs=1 + seed % 2, max_fraction=0.5, acts=RELU_ACTS)
+    run_both(wl.make_workload(f"rand_max{seed}", spec, T=8 + seed, N=1 + 4 * (seed % 3), seed=seed, scale=0.8, bias_scale=0.5,
+                              masked_fraction=0.2 if seed % 2 else 0.0))
+
+
+def test_maximum_units_with_the_interpreting_step_kernel(monkeypatch):
+    monkeypatch.setenv("RNNG_JIT", "0")
+    run_both(wl.make_workload("maxout", maxout_net(10, 24, 6), T=14, N=2, seed=11, scale=0.5, bias_scale=0.3), label="maximum units, RNNG_JIT=0")
+
+
 def test_rectifier_with_the_interpreting_step_kernel(monkeypatch):
     monkeypatch.setenv("RNNG_JIT", "0")
     run_both(wl.make_workload("elman_relu", wl.elman_net(9, 40, 5, act=wl.RELU), T=13, N=3, seed=6, scale=0.2, bias_scale=0.2), label="rectifier Elman, RNNG_JIT=0")

@@ -74,6 +74,8 @@ WINDOW_NETS = {
     "random_many_streams": lambda: (wl.random_graph(np.random.default_rng(503), n_inner=6, max_delay=2, n_inputs=2), 11),
     # dense targets under the squared error (masked by NaN)
     "lstm_squared_error": lambda: (wl.lstm_net(10, [24], 5, squared_error_act=wl.TANH), 2),
+    # maximum units (another aggregation function)
+    "random_maximum": lambda: (wl.random_graph(np.random.default_rng(955), n_inner=7, max_delay=3, max_fraction=0.5), 2),
     # rectified units
     "elman_rectifier": lambda: (wl.elman_net(8, 30, 5, act=wl.RELU), 2),
     "random_rectifier": lambda: (wl.random_graph(np.random.default_rng(505), n_inner=7, max_delay=3, acts=(wl.LINEAR, wl.SIGMOID, wl.TANH, wl.RELU, wl.RELU)), 3),
