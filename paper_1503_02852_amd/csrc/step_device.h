@@ -1145,13 +1145,8 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
                 s[g] = v;
             } else if (PH::gkind(g) == GA_KIND_POLLED) {
                 // a helper group's sum for this frame, loaded one step ahead (the helper runs ahead; the
-                // value is checked with the poll's attempts); now the next step's goes out (behind the
-                // last step: a frame that nothing reads)
+                // value is checked with the poll's attempts)
                 s[g] = r.polled_next[g];
-                const int frame = step_frame(a, step + 1) + r.goff[g];
-                float v = 0.0f;
-                if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
-                r.polled_next[g] = v;
             }
         }
 #pragma unroll
@@ -1172,13 +1167,28 @@ __device__ __forceinline__ void wave_step(PhaseRegs<PH>& r, const WaveRegs<MV>& 
         }
         return ok;
     };
+    // the next step's sums go out behind this step's poll (behind the last step: a frame that nothing
+    // reads).  In front of the poll they cost more than they gain: the poll's check waits for every
+    // load in flight, also for these, which come from another XCD (charlm_n1 1.77 against 1.68 ms).
+    auto polled_ahead = [&]() {
+        if (!has_units) return;
+#pragma unroll
+        for (int g = 0; g < PH::NG; ++g)
+            if (PH::gkind(g) == GA_KIND_POLLED) {
+                const int frame = step_frame(a, step + 1) + r.goff[g];
+                float v = 0.0f;
+                if (r.gptr[g] != nullptr && frame >= 0 && frame < a.T) v = load_coherent(r.gptr[g] + (long long)frame * r.gstride[g]);
+                r.polled_next[g] = v;
+            }
+    };
     float xr[NB][MV::XF > 0 ? MV::XF : 1];
-    if (MV::NSRC == 0) gathers();
+    if (MV::NSRC == 0) { gathers(); polled_ahead(); }
     RNNG_STAMP(1);
     if (MV::NSRC > 0) {
         float* xs = xs_all + PAR * GX::FLOATS;
         if (!MV::PE) group_poll_issue<MV, NB>(pr, wv, a, t, tid);
         group_poll<MV, NB>(pr, xs, wv, a, step, t, tid, dead, gathers, polled_sums);
+        polled_ahead();
         step_lds_barrier();
 #if defined(RNNG_STEP_TRACE)
         if (blockIdx.x == RNNG_STEP_TRACE - 1 && tid == 0 && step >= RNNG_STEP_TRACE_AT && step < RNNG_STEP_TRACE_AT + 8) reinterpret_cast<unsigned long long*>(a.ctrl + 16)[80 + (step - RNNG_STEP_TRACE_AT)] = clock64();
